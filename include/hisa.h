@@ -1,0 +1,267 @@
+/*
+ * hisa.h -- C ABI of libhisa: the HISA instruction set of the CHET paper
+ * (Sec. "HISA", Fig. "Instructions of the HISA") over RNS-CKKS, executed by
+ * hand-written HIP kernels on one AMD gfx950 GPU, plus the HW-tiled tensor
+ * kernels of the paper's runtime (Sec. "Runtime", Algorithm 1).
+ *
+ * Conventions
+ *  - Every function returns an int: HISA_OK (0) or a negative HISA_ERR_* code;
+ *    hisa_last_error(ctx) gives a message owned by the context.  Nothing
+ *    throws across this boundary.
+ *  - hisa_ct / hisa_pt are opaque handles that own DEVICE memory.  The caller
+ *    owns every handle it receives through an out-pointer and releases it
+ *    with hisa_free (the table's `free`).  `*_assign` forms mutate their first
+ *    argument in place (the table's `...Assign` instructions).
+ *  - Pointers named host_* / plain `const double*`, `const int32_t*`,
+ *    `uint64_t* host` are HOST pointers; `dev_*` are DEVICE pointers.
+ *  - All work is enqueued on the HIP stream given to hisa_create (NULL = the
+ *    default stream); functions that return data to the host synchronise that
+ *    stream before returning.  A context is not thread-safe.
+ *  - Ciphertexts are (c0, c1[, c2]) with c0 + c1*s (+ c2*s^2) ~ scale * message,
+ *    kept in NTT form on the device, layout [poly][limb][N] of uint64 residues
+ *    in [0, q_i); export/import use COEFFICIENT form with canonical residues,
+ *    which is the representation the bit-exact parity tests compare.
+ *  - Keys never cross the boundary in normal use (Sec. "HISA": key handling is
+ *    the library's business); hisa_key_export exists for parity tests only.
+ *  - No function falls back to the CPU: without a usable GPU hisa_create fails.
+ */
+#ifndef HISA_H
+#define HISA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HISA_OK 0
+#define HISA_ERR_ARG (-1)             /* null pointer, bad size, bad parameter          */
+#define HISA_ERR_LEVEL_MISMATCH (-2)  /* operands carry different numbers of limbs      */
+#define HISA_ERR_SCALE_MISMATCH (-3)  /* add/sub operands differ in scale (rel. 2^-30)   */
+#define HISA_ERR_NO_KEY (-4)          /* rotation amount / relin without a generated key */
+#define HISA_ERR_BAD_DIVISOR (-5)     /* divScalar with x != maxScalarDiv(c, ub)         */
+#define HISA_ERR_DEPTH_EXHAUSTED (-6) /* rescale of a one-limb ciphertext                */
+#define HISA_ERR_OOM (-7)             /* device allocation failed                        */
+#define HISA_ERR_HIP (-8)             /* a HIP runtime call or kernel launch failed      */
+#define HISA_ERR_SIZE (-9)            /* wrong number of polynomials for this operation  */
+
+#define HISA_MAX_Q 48       /* most ciphertext primes                */
+#define HISA_MAX_PRIMES 64  /* most ciphertext + special primes       */
+
+typedef struct hisa_ctx hisa_ctx;
+typedef struct hisa_ct hisa_ct;
+typedef struct hisa_pt hisa_pt;
+
+/*
+ * Initialisation lies outside the HISA (Sec. "HISA", last paragraphs): ring
+ * degree N = 2^log_n (N/2 complex slots), the ciphertext primes q_0..q_{L-1}
+ * (q_bits[i] bits each, = 1 mod 2N, the largest unused such prime below
+ * 2^bits), dnum key-switching digits of alpha = ceil(L/dnum) primes, alpha
+ * special primes of special_bits bits, and the seed of all randomness.
+ * noise = 1: discrete Gaussian errors, sigma 3.2; noise = 0: all error
+ * polynomials zero (for exactness tests only).  Bits must lie in [log_n+2, 60].
+ */
+typedef struct {
+    uint32_t log_n;               /* 10 .. 16 */
+    uint32_t num_q;               /* L, 1 .. HISA_MAX_Q */
+    uint32_t q_bits[HISA_MAX_Q];
+    uint32_t dnum;                /* 1 .. L */
+    uint32_t special_bits;
+    uint32_t noise;
+    uint64_t seed;
+} hisa_params;
+
+/* hip_stream: a hipStream_t (may be NULL).  The context allocates its tables,
+ * the ternary secret and a device memory pool; hisa_destroy releases all of it
+ * (handles still alive become dangling). */
+int hisa_create(const hisa_params* params, void* hip_stream, hisa_ctx** out);
+int hisa_destroy(hisa_ctx* ctx);
+const char* hisa_last_error(const hisa_ctx* ctx);
+int hisa_sync(hisa_ctx* ctx);
+
+/* Evaluation keys (Sec. "HEAAN": re-linearisation and rotation need keys).
+ * hisa_keygen makes the re-linearisation key.  hisa_gen_rot_keys makes one key
+ * per distinct left-rotation amount in host array left_steps[n] -- the paper's
+ * rotation-key selection (Sec. "Rotation Keys Selection"); amounts are taken
+ * modulo N/2, zero and repeats are skipped. */
+int hisa_keygen(hisa_ctx* ctx);
+int hisa_gen_rot_keys(hisa_ctx* ctx, const int32_t* left_steps, size_t n);
+
+/* ---- Integers profile: encode / decode (Fig. "Instructions of the HISA") ----
+ * The HEAAN family packs N/2 complex numbers (Sec. "HEAAN"); host arrays
+ * re[count], im[count] (im may be NULL = real input), count <= N/2, missing
+ * slots are zero.  The plaintext gets `limbs` limbs (1..L) and the given scale.
+ * Slot j is the value at the root exp(i*pi*5^j/N), which makes rotLeft a cyclic
+ * left shift.  Arithmetic is fp64, so encode is approximate (rounding error
+ * O(sqrt N) per Sec. "HEAAN"), not bit-reproducible across implementations. */
+int hisa_encode(hisa_ctx* ctx, const double* re, const double* im, size_t count, double scale, uint32_t limbs,
+                hisa_pt** out);
+int hisa_decode(hisa_ctx* ctx, const hisa_pt* pt, double* re, double* im, size_t count);
+/* Exact route for parity tests: signed integer coefficients host_coeffs[N]. */
+int hisa_pt_from_coeffs(hisa_ctx* ctx, const int64_t* host_coeffs, double scale, uint32_t limbs, hisa_pt** out);
+/* host[limbs][N], coefficient form, canonical residues. */
+int hisa_pt_export(hisa_ctx* ctx, const hisa_pt* pt, uint64_t* host);
+int hisa_pt_info(const hisa_pt* pt, uint32_t* limbs, double* scale);
+
+/* ---- Encryption profile ----
+ * encrypt: symmetric, c1 = a uniform, c0 = -a*s + e + m, at the plaintext's
+ * level; the context's encryption counter selects the random streams and is
+ * advanced by one per ciphertext.  decrypt: c0 + c1*s (+ c2*s^2). */
+int hisa_encrypt(hisa_ctx* ctx, const hisa_pt* pt, hisa_ct** out);
+int hisa_decrypt(hisa_ctx* ctx, const hisa_ct* ct, hisa_pt** out);
+int hisa_copy(hisa_ctx* ctx, const hisa_ct* ct, hisa_ct** out);
+int hisa_free(hisa_ctx* ctx, void* handle); /* hisa_ct* or hisa_pt*; NULL is a no-op */
+int hisa_set_enc_counter(hisa_ctx* ctx, uint64_t counter);
+
+/* ---- add / sub: ciphertext, plaintext or scalar (limb-wise mod q_i) ----
+ * Operands need equal limb counts and (for add/sub) equal scales.  The scalar
+ * forms add round(x * scale) to the constant coefficient of c0, which shifts
+ * every slot by x. */
+int hisa_add(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b, hisa_ct** out);
+int hisa_sub(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b, hisa_ct** out);
+int hisa_add_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_ct* b);
+int hisa_sub_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_ct* b);
+int hisa_add_plain(hisa_ctx* ctx, const hisa_ct* a, const hisa_pt* p, hisa_ct** out);
+int hisa_sub_plain(hisa_ctx* ctx, const hisa_ct* a, const hisa_pt* p, hisa_ct** out);
+int hisa_add_plain_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_pt* p);
+int hisa_sub_plain_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_pt* p);
+int hisa_add_scalar(hisa_ctx* ctx, const hisa_ct* a, double x, hisa_ct** out);
+int hisa_sub_scalar(hisa_ctx* ctx, const hisa_ct* a, double x, hisa_ct** out);
+int hisa_add_scalar_assign(hisa_ctx* ctx, hisa_ct* a, double x);
+int hisa_sub_scalar_assign(hisa_ctx* ctx, hisa_ct* a, double x);
+
+/* ---- mul: ciphertext, plaintext or scalar; Relin profile ----
+ * mul = mul_no_relin + relinearize.  mul_no_relin gives the three-polynomial
+ * ciphertext (a0 b0, a0 b1 + a1 b0, a1 b1); relinearize (in place) brings it
+ * back to two with the s^2 key.  mul_scalar multiplies every residue by the
+ * integer round(x * x_scale) (the "FixedPrecision(weight, plainLogP)" of
+ * Algorithm 1); scales multiply. */
+int hisa_mul(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b, hisa_ct** out);
+int hisa_mul_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_ct* b);
+int hisa_mul_no_relin(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b, hisa_ct** out);
+int hisa_relinearize(hisa_ctx* ctx, hisa_ct* ct);
+int hisa_mul_plain(hisa_ctx* ctx, const hisa_ct* a, const hisa_pt* p, hisa_ct** out);
+int hisa_mul_plain_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_pt* p);
+int hisa_mul_scalar(hisa_ctx* ctx, const hisa_ct* a, double x, double x_scale, hisa_ct** out);
+int hisa_mul_scalar_assign(hisa_ctx* ctx, hisa_ct* a, double x, double x_scale);
+
+/* ---- rotations ("Rotate ciphertext c left/right x slots") ----
+ * rotLeft(r): (sigma_g(c0), 0) + KeySwitch_g(sigma_g(c1)), g = 5^r mod 2N;
+ * rotRight(r) = rotLeft(N/2 - r); r = 0 (mod N/2) is a copy and needs no key;
+ * any other amount needs its key from hisa_gen_rot_keys, else HISA_ERR_NO_KEY. */
+int hisa_rot_left(hisa_ctx* ctx, const hisa_ct* a, int32_t steps, hisa_ct** out);
+int hisa_rot_right(hisa_ctx* ctx, const hisa_ct* a, int32_t steps, hisa_ct** out);
+int hisa_rot_left_assign(hisa_ctx* ctx, hisa_ct* a, int32_t steps);
+int hisa_rot_right_assign(hisa_ctx* ctx, hisa_ct* a, int32_t steps);
+
+/* ---- Division profile, RNS reading (Sec. "HISA": the divisor is a coprime
+ * modulus of the ciphertext) ----
+ * max_scalar_div: the last modulus q_{l-1} of the ciphertext if l > 1 and it is
+ * below ub, else 1.  div_scalar(d): d = 1 is a no-op; d must equal
+ * max_scalar_div for some ub (else HISA_ERR_BAD_DIVISOR); rounds to nearest,
+ * drops the last limb, divides the scale by d.  rescale = div_scalar by
+ * max_scalar_div(ct, +inf). */
+int hisa_max_scalar_div(hisa_ctx* ctx, const hisa_ct* ct, double ub, uint64_t* d);
+int hisa_div_scalar(hisa_ctx* ctx, hisa_ct* ct, uint64_t d);
+int hisa_rescale(hisa_ctx* ctx, hisa_ct* ct);
+
+/* ---- batched forms: n ciphertexts of equal shape, one launch set ----
+ * in[n] / out[n] are host arrays of handles; out receives n new handles that
+ * are views of one device allocation.  rot_left_batch shares one rotation
+ * amount (one key, read once per batch).  The *_assign_batch forms mutate. */
+int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n, int32_t steps, hisa_ct** out);
+int hisa_relinearize_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n);
+int hisa_rescale_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n);
+int hisa_add_batch(hisa_ctx* ctx, const hisa_ct* const* a, const hisa_ct* const* b, size_t n, hisa_ct** out);
+int hisa_mul_plain_batch(hisa_ctx* ctx, const hisa_ct* const* a, const hisa_pt* p, size_t n, hisa_ct** out);
+int hisa_mul_no_relin_batch(hisa_ctx* ctx, const hisa_ct* const* a, const hisa_ct* const* b, size_t n,
+                            hisa_ct** out);
+int hisa_encrypt_batch(hisa_ctx* ctx, const hisa_pt* const* pts, size_t n, hisa_ct** out);
+/* n ciphertexts (2 polynomials, `limbs` limbs) whose residues are uniform
+ * random words of stream `counter`: synthetic benchmark inputs that are
+ * indistinguishable from encryptions. */
+int hisa_ct_random_batch(hisa_ctx* ctx, size_t n, uint32_t limbs, double scale, uint64_t counter, hisa_ct** out);
+
+/* ---- tensor layer (Sec. "Runtime": CipherTensor, HW-tiling, Algorithm 1) ----
+ * A CipherTensor is a vector of ciphertexts plus plain-integer metadata: the
+ * outer (batch, channel) dimensions index ciphertexts cts[b*channels + c]; one
+ * ciphertext holds the height x width plane of one channel, element (y, x) in
+ * slot offset + y*h_stride + x*w_stride (strides allow padding between rows).
+ * `clean` is the runtime's flag that every slot outside the plane's elements
+ * is zero.  The struct is host memory owned by the caller; the handles in cts
+ * are owned like any other handle. */
+typedef struct {
+    uint32_t batch, channels;    /* outer (vector) dimensions                 */
+    uint32_t height, width;      /* logical inner dimensions                  */
+    uint32_t h_stride, w_stride; /* physical strides in slots                 */
+    uint32_t offset;             /* slot of element (0,0)                     */
+    uint32_t clean;              /* 1: slots outside the elements hold zeros  */
+    hisa_ct** cts;               /* batch*channels handles                    */
+} hisa_tensor;
+
+#define HISA_CONV_SCALAR 0 /* literal Algorithm 1: mulScalar by round(w * q_last), add, one divScalar       */
+#define HISA_CONV_MASKED 1 /* as SCALAR with weight scale q_last/2^25, then one mulPlain by the 0/1 mask of   */
+                           /* valid output positions (scale 2^25) before the divScalar: leaves a clean tensor */
+#define HISA_CONV_PLAIN 2  /* one mulPlain per tap: plaintext = w * mask encoded at scale q_last            */
+
+typedef struct {
+    uint32_t fh, fw;      /* filter height, width                                                   */
+    uint32_t stride;      /* output stride (>= 1)                                                   */
+    uint32_t pad_same;    /* 0: VALID.  1: SAME, the input must carry a zero border of fh/2, fw/2   */
+    uint32_t mode;        /* HISA_CONV_*                                                           */
+} hisa_conv_geom;
+
+/* HW-tiled conv2d (Algorithm 1; cross-correlation, no kernel flip): for every
+ * output channel oc: sum over ic, (fh, fw) of weight * rotLeft(in[ic],
+ * fh*h_stride + fw*w_stride), then one divScalar.  Rotations are computed once
+ * per (ic, tap) and shared by all oc.  host weights w[FH][FW][IC][OC]; bias[OC]
+ * may be NULL.  out->cts must point to room for batch*OC handles; the other
+ * fields of *out are filled in (strides multiplied by the conv stride). */
+int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w, const double* bias, uint32_t out_channels,
+                const hisa_conv_geom* geom, hisa_tensor* out);
+/* Fully connected layer over all elements of all channels (Sec. "Homomorphic
+ * matmul", version without replicas): host w[OUT][C][H][W]; per output o:
+ * sum_c mulPlain(in[c], encode(w[o][c] placed on the element slots, scale
+ * q_last)), one divScalar, then rotate-and-add over the power-of-two window
+ * covering the plane; output o is a 1x1 plane in slot `offset`. */
+int hisa_fc(hisa_ctx* ctx, const hisa_tensor* in, const double* w, const double* bias, uint32_t out_features,
+            hisa_tensor* out);
+/* 2x2 sum pool with stride 2 (the 1/4 of the average is left to the next
+ * layer's weights): x + rot(w_stride) + rot(h_stride) + rot(h_stride+w_stride). */
+int hisa_sum_pool2x2(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out);
+/* Degree-2 activation a*x^2 + b*x evaluated as x^2 + (b/a)*x (one mul +
+ * relinearize, one mulScalar at scale = ct scale, one add, one divScalar); the
+ * factor a is left to the next layer's weights. */
+int hisa_poly2_act(hisa_ctx* ctx, const hisa_tensor* in, double a, double b, hisa_tensor* out);
+/* The rotation amounts a layer will use on this input layout, for
+ * hisa_gen_rot_keys: writes up to cap amounts to host steps[], count to *n. */
+int hisa_conv2d_rot_steps(const hisa_tensor* in, const hisa_conv_geom* geom, int32_t* steps, size_t cap, size_t* n);
+int hisa_fc_rot_steps(const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n);
+int hisa_pool_rot_steps(const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n);
+
+/* ---- parity / debug surface ----
+ * get_primes: host q[L], p[alpha].  ct_export: host[polys][limbs][N],
+ * COEFFICIENT form, canonical residues.  ct_import: the inverse (new handle).
+ * ntt_raw: in-place forward (inverse != 0: inverse) negacyclic NTT of n_polys
+ * consecutive device polynomials dev_buf[n_polys][N] modulo prime prime_index
+ * (0..L-1: q_i, L..L+alpha-1: special); forward output index i holds
+ * a(psi^(2*bitrev(i)+1)).  key_export: host[dnum][2][L+alpha][N], NTT form,
+ * (b, a) per digit; key_id 0 = relinearisation key, else a Galois element. */
+int hisa_get_primes(hisa_ctx* ctx, uint64_t* q, uint64_t* p);
+int hisa_get_alpha(hisa_ctx* ctx, uint32_t* alpha);
+int hisa_ct_info(const hisa_ct* ct, uint32_t* limbs, uint32_t* polys, double* scale);
+int hisa_ct_export(hisa_ctx* ctx, const hisa_ct* ct, uint64_t* host);
+int hisa_ct_import(hisa_ctx* ctx, const uint64_t* host, uint32_t polys, uint32_t limbs, double scale, hisa_ct** out);
+int hisa_ct_import_batch(hisa_ctx* ctx, const uint64_t* host, size_t n, uint32_t polys, uint32_t limbs, double scale,
+                         hisa_ct** out);
+int hisa_ct_device_ptr(const hisa_ct* ct, uint64_t** dev);
+int hisa_ntt_raw(hisa_ctx* ctx, uint64_t* dev_buf, uint32_t prime_index, size_t n_polys, int inverse);
+int hisa_key_export(hisa_ctx* ctx, uint64_t key_id, uint64_t* host);
+int hisa_galois_elt(hisa_ctx* ctx, int32_t left_steps, uint64_t* g);
+int hisa_secret_export(hisa_ctx* ctx, int64_t* host_coeffs);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HISA_H */

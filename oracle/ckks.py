@@ -316,7 +316,12 @@ class Oracle:
     def add(self, a: Ct, b: Ct, subtract=False) -> Ct:
         self._check_pair(a, b)
         if a.polys != b.polys:
-            raise OracleError("size mismatch")
+            # a two-polynomial ciphertext is a three-polynomial one with c2 = 0
+            if a.polys < b.polys and subtract:
+                raise OracleError("size mismatch")
+            polys = max(a.polys, b.polys)
+            pad = lambda c: Ct(np.concatenate([c.data, np.zeros((polys - c.polys,) + c.data.shape[1:], np.uint64)]), c.scale)
+            a, b = pad(a), pad(b)
         out = np.zeros_like(a.data)
         lib().orc_add(self._h, _p(a.data), _p(b.data), a.polys, a.limbs, int(subtract), _p(out))
         return Ct(out, a.scale)

@@ -1,0 +1,329 @@
+// Sampling and limb-wise kernels: the counter-based generator with its
+// uniform / ternary / discrete-Gaussian samplers, add / sub / mulPlain /
+// mulScalar / mulNoRelin, the combine steps of encryption, decryption and key
+// generation, and the NTT-form automorphism gather.  All of them stream
+// [..][limb][N] arrays once: they are bound by HBM bandwidth.
+#include "hisa_internal.hpp"
+#include "modarith.cuh"
+
+#define NT 256
+
+// ---- counter-based generator: rnd(seed, kind, ctr, idx) -------------------
+__device__ __forceinline__ u64 mix64(u64 x) {
+    x ^= x >> 32; x *= 0x6a09e667f3bcc909ULL;
+    x ^= x >> 29; x *= 0xbb67ae8584caa73bULL;
+    x ^= x >> 32;
+    return x;
+}
+__device__ __forceinline__ u64 stream_key(u64 seed, u64 kind, u64 ctr) {
+    return mix64(seed + 0x3c6ef372fe94f82bULL * (((kind << 56) | ctr) + 1));
+}
+__device__ __forceinline__ u64 rnd_at(u64 key, u64 idx) { return mix64(key + 0x3c6ef372fe94f82bULL * (idx + 1)); }
+
+// floor(2^63 * P(|X| <= k)) for the discrete Gaussian with sigma = 3.2 cut at |x| <= 19
+__constant__ u64 c_gauss_cdt[19] = {
+    1149872836518706973ULL, 3340023669317320718ULL, 5231742859181312982ULL, 6713673040852152709ULL,
+    7766573333558595572ULL, 8445050410543775182ULL, 8841576294031517592ULL, 9051758687454227207ULL,
+    9152802460441190481ULL, 9196859083481262423ULL, 9214281214904026344ULL, 9220529772758650828ULL,
+    9222562348483741346ULL, 9223162004373033245ULL, 9223322456656299389ULL, 9223361395058736926ULL,
+    9223369965413244325ULL, 9223371676247247624ULL, 9223371985993021523ULL};
+
+__global__ __launch_bounds__(NT) void sample_uniform_kernel(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr,
+                                                            PolyMap map, u64 batch_stride, u64 ctr_step, u64* out,
+                                                            int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const int p = blockIdx.y, entry = p % map.period, b = p / map.period;
+    const int prime = map.prime_of[entry];
+    if (prime < 0) return;
+    const PrimeConst pc = primes[prime];
+    const u64 key = stream_key(seed, kind, ctr + (u64)b * ctr_step);
+    u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    u64 w = rnd_at(key, (u64)prime * n + j);
+    out[(u64)b * batch_stride + (u64)entry * n + j] = barrett128(0, w, pc.q, pc.r1, pc.r0);
+}
+
+hipError_t launch_sample_uniform(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, const PolyMap& map, int n_polys,
+                                 u64 batch_stride, u64 ctr_step, u64* out, int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, n_polys);
+    hipLaunchKernelGGL(sample_uniform_kernel, grid, dim3(NT), 0, st, primes, seed, kind, ctr, map, batch_stride, ctr_step,
+                       out, log_n);
+    return hipGetLastError();
+}
+
+// One small signed polynomial per batch entry (ternary secret, or Gaussian
+// error, or zero), reduced into every mapped limb.  raw (may be null) receives
+// the signed coefficients of batch entry 0.
+__global__ __launch_bounds__(NT) void sample_small_kernel(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr,
+                                                          int noise_on, int ternary, PolyMap map, u64 batch_stride,
+                                                          u64 ctr_step, u64* out, i64* raw, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const int b = blockIdx.y;
+    const u64 key = stream_key(seed, kind, ctr + (u64)b * ctr_step);
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    const u64 w = rnd_at(key, j);
+    i64 v;
+    if (ternary) {
+        u64 t = w % 3;
+        v = t == 0 ? 0 : (t == 1 ? 1 : -1);
+    } else if (noise_on) {
+        u64 mag_src = w >> 1;
+        i64 mag = 0;
+        for (int k = 0; k < 19; k++) mag += (mag_src >= c_gauss_cdt[k]);
+        v = (w & 1) ? -mag : mag;
+    } else {
+        v = 0;
+    }
+    if (raw && b == 0) raw[j] = v;
+    for (int e = 0; e < map.period; e++) {
+        int prime = map.prime_of[e];
+        if (prime < 0) continue;
+        u64 q = primes[prime].q;
+        out[(u64)b * batch_stride + (u64)e * n + j] = v >= 0 ? (u64)v : q - (u64)(-v);
+    }
+}
+
+hipError_t launch_sample_small(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, int noise_on, int ternary,
+                               const PolyMap& map, int n_polys, u64 batch_stride, u64 ctr_step, u64* out, i64* raw,
+                               int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, n_polys);  // n_polys = batch entries here
+    hipLaunchKernelGGL(sample_small_kernel, grid, dim3(NT), 0, st, primes, seed, kind, ctr, noise_on, ternary, map,
+                       batch_stride, ctr_step, out, raw, log_n);
+    return hipGetLastError();
+}
+
+// ---- add / sub --------------------------------------------------------------
+// out[b][p][i] = a[b][p][i] (+|-) b[b][p][i] for p < polys_b, copy of a for the rest.
+__global__ __launch_bounds__(NT) void addsub_kernel(const PrimeConst* primes, const u64* a, const u64* b, u64* out, int op,
+                                                    int limbs, int polys_a, int polys_b, u64 a_bs, u64 b_bs, u64 o_bs,
+                                                    int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const int limb = blockIdx.y % limbs, poly = blockIdx.y / limbs;
+    const u64 bi = blockIdx.z;
+    const u64 q = primes[limb].q;
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    const u64 off = ((u64)poly * limbs + limb) * n + j;
+    u64 x = a[bi * a_bs + off];
+    if (poly < polys_b) {
+        u64 y = b[bi * b_bs + off];
+        x = op == OP_ADD ? addmod(x, y, q) : submod(x, y, q);
+    }
+    out[bi * o_bs + off] = x;
+}
+
+hipError_t launch_addsub(const PrimeConst* primes, const u64* a, const u64* b, u64* out, int op, int limbs, int polys_a,
+                         int polys_b, u64 n_batch, u64 a_bs, u64 b_bs, u64 o_bs, int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, limbs * polys_a, (unsigned)n_batch);
+    hipLaunchKernelGGL(addsub_kernel, grid, dim3(NT), 0, st, primes, a, b, out, op, limbs, polys_a, polys_b, a_bs, b_bs,
+                       o_bs, log_n);
+    return hipGetLastError();
+}
+
+struct LimbConsts {
+    u64 v[HISA_MAX_PRIMES];
+    u64 v_sh[HISA_MAX_PRIMES];
+};
+
+// first polynomial +- per-limb constant (a constant polynomial is that constant at every evaluation point)
+__global__ __launch_bounds__(NT) void add_const_kernel(const PrimeConst* primes, const u64* a, u64* out, LimbConsts c,
+                                                       int op, int limbs, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const int limb = blockIdx.y % limbs, poly = blockIdx.y / limbs;
+    const u64 q = primes[limb].q;
+    const u64 off = ((u64)poly * limbs + limb) * n + (u64)blockIdx.x * NT + threadIdx.x;
+    u64 x = a[off];
+    if (poly == 0) x = op == OP_ADD ? addmod(x, c.v[limb], q) : submod(x, c.v[limb], q);
+    out[off] = x;
+}
+
+hipError_t launch_add_const(const PrimeConst* primes, const u64* a, u64* out, const u64* consts, int op, int limbs,
+                            int polys, int log_n, hipStream_t st) {
+    LimbConsts c = {};
+    for (int i = 0; i < limbs; i++) c.v[i] = consts[i];
+    dim3 grid((1u << log_n) / NT, limbs * polys);
+    hipLaunchKernelGGL(add_const_kernel, grid, dim3(NT), 0, st, primes, a, out, c, op, limbs, log_n);
+    return hipGetLastError();
+}
+
+// ---- multiply ---------------------------------------------------------------
+__global__ __launch_bounds__(NT) void mul_plain_kernel(const PrimeConst* primes, const u64* a, const u64* pt, u64* out,
+                                                       int limbs, u64 a_bs, u64 o_bs, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const int limb = blockIdx.y % limbs, poly = blockIdx.y / limbs;
+    const u64 bi = blockIdx.z;
+    const PrimeConst pc = primes[limb];
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    const u64 off = ((u64)poly * limbs + limb) * n + j;
+    out[bi * o_bs + off] = mulmod_barrett(a[bi * a_bs + off], pt[(u64)limb * n + j], pc.q, pc.r1, pc.r0);
+}
+
+hipError_t launch_mul_plain(const PrimeConst* primes, const u64* a, const u64* pt, u64* out, int limbs, int polys,
+                            u64 n_batch, u64 a_bs, u64 o_bs, int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, limbs * polys, (unsigned)n_batch);
+    hipLaunchKernelGGL(mul_plain_kernel, grid, dim3(NT), 0, st, primes, a, pt, out, limbs, a_bs, o_bs, log_n);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(NT) void mul_const_kernel(const PrimeConst* primes, const u64* a, u64* out, LimbConsts c,
+                                                       int limbs, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const int limb = blockIdx.y % limbs;
+    const u64 q = primes[limb].q;
+    const u64 off = (u64)blockIdx.y * n + (u64)blockIdx.x * NT + threadIdx.x;
+    out[off] = shoup_mul(a[off], c.v[limb], c.v_sh[limb], q);
+}
+
+hipError_t launch_mul_const(const PrimeConst* primes, const u64* a, u64* out, const u64* consts, int limbs, int polys,
+                            int log_n, hipStream_t st) {
+    // consts: [limbs] values followed by [limbs] Shoup companions
+    LimbConsts c = {};
+    for (int i = 0; i < limbs; i++) { c.v[i] = consts[i]; c.v_sh[i] = consts[limbs + i]; }
+    dim3 grid((1u << log_n) / NT, limbs * polys);
+    hipLaunchKernelGGL(mul_const_kernel, grid, dim3(NT), 0, st, primes, a, out, c, limbs, log_n);
+    return hipGetLastError();
+}
+
+// (a0, a1) x (b0, b1) -> (a0 b0, a0 b1 + a1 b0, a1 b1)
+__global__ __launch_bounds__(NT) void mul_no_relin_kernel(const PrimeConst* primes, const u64* a, const u64* b, u64* out,
+                                                          int limbs, u64 a_bs, u64 b_bs, u64 o_bs, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const int limb = blockIdx.y;
+    const u64 bi = blockIdx.z;
+    const PrimeConst pc = primes[limb];
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    const u64 o0 = (u64)limb * n + j, o1 = ((u64)limbs + limb) * n + j, o2 = ((u64)2 * limbs + limb) * n + j;
+    const u64 a0 = a[bi * a_bs + o0], a1 = a[bi * a_bs + o1];
+    const u64 b0 = b[bi * b_bs + o0], b1 = b[bi * b_bs + o1];
+    out[bi * o_bs + o0] = mulmod_barrett(a0, b0, pc.q, pc.r1, pc.r0);
+    Acc128 acc = {0, 0};
+    acc_mad(acc, a0, b1);
+    acc_mad(acc, a1, b0);
+    out[bi * o_bs + o1] = acc_reduce(acc, pc.q, pc.r1, pc.r0);
+    out[bi * o_bs + o2] = mulmod_barrett(a1, b1, pc.q, pc.r1, pc.r0);
+}
+
+hipError_t launch_mul_no_relin(const PrimeConst* primes, const u64* a, const u64* b, u64* out, int limbs, u64 n_batch,
+                               u64 a_bs, u64 b_bs, u64 o_bs, int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, limbs, (unsigned)n_batch);
+    hipLaunchKernelGGL(mul_no_relin_kernel, grid, dim3(NT), 0, st, primes, a, b, out, limbs, a_bs, b_bs, o_bs, log_n);
+    return hipGetLastError();
+}
+
+// ---- encryption profile -----------------------------------------------------
+// ct[b] = (-a*s + e + m, a): a already sits in ct[b][1] (NTT form), e[b][limbs][N] in NTT form
+__global__ __launch_bounds__(NT) void encrypt_combine_kernel(const PrimeConst* primes, const u64* secret, const u64* pt,
+                                                             const u64* e, u64* ct, int limbs, u64 pt_bs, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const int limb = blockIdx.y;
+    const u64 bi = blockIdx.z;
+    const PrimeConst pc = primes[limb];
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    const u64 off = (u64)limb * n + j;
+    u64* c = ct + bi * 2 * limbs * n;
+    u64 as = mulmod_barrett(c[(u64)limbs * n + off], secret[off], pc.q, pc.r1, pc.r0);
+    u64 v = addmod(negmod(as, pc.q), e[bi * limbs * n + off], pc.q);
+    c[off] = addmod(v, pt[bi * pt_bs + off], pc.q);
+}
+
+hipError_t launch_encrypt_combine(const PrimeConst* primes, const u64* secret, const u64* pt, const u64* e, u64* ct,
+                                  int limbs, u64 n_batch, u64 pt_bs, int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, limbs, (unsigned)n_batch);
+    hipLaunchKernelGGL(encrypt_combine_kernel, grid, dim3(NT), 0, st, primes, secret, pt, e, ct, limbs, pt_bs, log_n);
+    return hipGetLastError();
+}
+
+// pt = c0 + c1*s (+ c2*s^2)
+__global__ __launch_bounds__(NT) void decrypt_kernel(const PrimeConst* primes, const u64* secret, const u64* ct, u64* pt,
+                                                     int limbs, int polys, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const int limb = blockIdx.y;
+    const PrimeConst pc = primes[limb];
+    const u64 off = (u64)limb * n + (u64)blockIdx.x * NT + threadIdx.x;
+    const u64 s = secret[off];
+    u64 acc = ct[off], sp = s;
+    for (int p = 1; p < polys; p++) {
+        acc = addmod(acc, mulmod_barrett(ct[(u64)p * limbs * n + off], sp, pc.q, pc.r1, pc.r0), pc.q);
+        sp = mulmod_barrett(sp, s, pc.q, pc.r1, pc.r0);
+    }
+    pt[off] = acc;
+}
+
+hipError_t launch_decrypt(const PrimeConst* primes, const u64* secret, const u64* ct, u64* pt, int limbs, int polys,
+                          int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, limbs);
+    hipLaunchKernelGGL(decrypt_kernel, grid, dim3(NT), 0, st, primes, secret, ct, pt, limbs, polys, log_n);
+    return hipGetLastError();
+}
+
+// key digit: b = -a*s + e + [prime in digit] * (P mod q) * target ; a already in key_digit[1]
+__global__ __launch_bounds__(NT) void key_combine_kernel(const PrimeConst* primes, const u64* secret, const u64* target,
+                                                         const u64* e, const u64* pmod_all, u64* key_digit, int total,
+                                                         int L, int alpha, int digit, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const int prime = blockIdx.y;
+    const PrimeConst pc = primes[prime];
+    const u64 off = (u64)prime * n + (u64)blockIdx.x * NT + threadIdx.x;
+    u64 a = key_digit[(u64)total * n + off];
+    u64 v = addmod(negmod(mulmod_barrett(a, secret[off], pc.q, pc.r1, pc.r0), pc.q), e[off], pc.q);
+    if (prime < L && prime / alpha == digit)
+        v = addmod(v, mulmod_barrett(pmod_all[prime], target[off], pc.q, pc.r1, pc.r0), pc.q);
+    key_digit[off] = v;
+}
+
+hipError_t launch_key_combine(const PrimeConst* primes, const u64* secret, const u64* target, const u64* e,
+                              const u64* pmod_all, u64* key_digit, int total, int L, int alpha, int digit, int log_n,
+                              hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, total);
+    hipLaunchKernelGGL(key_combine_kernel, grid, dim3(NT), 0, st, primes, secret, target, e, pmod_all, key_digit, total, L,
+                       alpha, digit, log_n);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(NT) void square_kernel(const PrimeConst* primes, const u64* s, u64* out, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const PrimeConst pc = primes[blockIdx.y];
+    const u64 off = (u64)blockIdx.y * n + (u64)blockIdx.x * NT + threadIdx.x;
+    out[off] = mulmod_barrett(s[off], s[off], pc.q, pc.r1, pc.r0);
+}
+
+hipError_t launch_pointwise_square(const PrimeConst* primes, const u64* s, u64* out, int total, int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, total);
+    hipLaunchKernelGGL(square_kernel, grid, dim3(NT), 0, st, primes, s, out, log_n);
+    return hipGetLastError();
+}
+
+// sigma_g in NTT form is a pure gather: out[i] = in[src(i)] with
+// 2*bitrev(src)+1 = (2*bitrev(i)+1)*g mod 2N.  Aligned blocks map to aligned blocks.
+__global__ __launch_bounds__(NT) void automorph_ntt_kernel(const u64* in, u64 in_bs, u64* out, u64 out_bs, u64 g,
+                                                           int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const uint32_t i = blockIdx.x * NT + threadIdx.x;
+    const uint32_t mask = (2u << log_n) - 1;
+    uint32_t e = 2 * (__brev(i) >> (32 - log_n)) + 1;
+    uint32_t e2 = (uint32_t)((u64)e * g) & mask;
+    uint32_t src = __brev((e2 - 1) >> 1) >> (32 - log_n);
+    out[(u64)blockIdx.z * out_bs + (u64)blockIdx.y * n + i] = in[(u64)blockIdx.z * in_bs + (u64)blockIdx.y * n + src];
+}
+
+hipError_t launch_automorph_ntt(const u64* in, u64 in_bs, u64* out, u64 out_bs, u64 galois, int n_polys, u64 n_batch,
+                                int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, n_polys, (unsigned)n_batch);
+    hipLaunchKernelGGL(automorph_ntt_kernel, grid, dim3(NT), 0, st, in, in_bs, out, out_bs, galois, log_n);
+    return hipGetLastError();
+}
+
+// signed integer coefficients -> residues modulo q_0..q_{limbs-1}
+__global__ __launch_bounds__(NT) void reduce_i64_kernel(const PrimeConst* primes, const i64* coeffs, u64* out, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const PrimeConst pc = primes[blockIdx.y];
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    i64 v = coeffs[j];
+    u64 mag = v < 0 ? (u64)0 - (u64)v : (u64)v;
+    u64 r = barrett128(0, mag, pc.q, pc.r1, pc.r0);
+    out[(u64)blockIdx.y * n + j] = v < 0 ? negmod(r, pc.q) : r;
+}
+
+hipError_t launch_reduce_i64(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs, int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, limbs);
+    hipLaunchKernelGGL(reduce_i64_kernel, grid, dim3(NT), 0, st, primes, coeffs, out, log_n);
+    return hipGetLastError();
+}

@@ -1,0 +1,98 @@
+// encode / decode in fp64 (the HEAAN-style packing of N/2 complex slots, slot
+// j at the root exp(i*pi*5^j/N)), and the centred CRT lift that turns RNS
+// coefficients into doubles.  Direct sums with exact integer angle reduction
+// into a table of the 2N-th roots of unity.
+#include "hisa_internal.hpp"
+#include "modarith.cuh"
+
+#define NT 256
+
+// coeffs[k] = round( factor * sum_j ( re_j cos(pi e/N) + im_j sin(pi e/N) ) ),  e = 5^j k mod 2N
+__global__ __launch_bounds__(NT) void encode_kernel(const double* cs, const double* sn, const double* re, const double* im,
+                                                    int count, double factor, i64* coeffs, int log_n) {
+    const uint32_t k = blockIdx.x * NT + threadIdx.x;
+    const uint32_t mask = (2u << log_n) - 1;
+    uint32_t g = 1;
+    double acc = 0.0;
+    for (int j = 0; j < count; j++) {
+        uint32_t e = (g * k) & mask;
+        acc += re[j] * cs[e];
+        if (im) acc += im[j] * sn[e];
+        g = (g * 5u) & mask;
+    }
+    coeffs[k] = (i64)round(acc * factor);
+}
+
+hipError_t launch_encode(const double* cs, const double* sn, const double* re, const double* im, int count, double factor,
+                         i64* coeffs, int log_n, hipStream_t st) {
+    hipLaunchKernelGGL(encode_kernel, dim3((1u << log_n) / NT), dim3(NT), 0, st, cs, sn, re, im, count, factor, coeffs,
+                       log_n);
+    return hipGetLastError();
+}
+
+// Centred mixed-radix digits v_i in (-q_i/2, q_i/2] with x = v_0 + q_0 (v_1 + q_1 (v_2 + ...)), then Horner in fp64.
+// Small centred values have zero top digits, so the float result is accurate for them.
+__global__ __launch_bounds__(NT) void crt_to_double_kernel(const PrimeConst* primes, const u64* x, int limbs,
+                                                           const u64* ginv, const u64* ginv_sh, int L, double inv_scale,
+                                                           double* out, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    double val = 0.0, weight = 1.0;
+    // digits are produced low to high; accumulate v_i * (q_0...q_{i-1}) in fp64 from the low end would lose the
+    // small terms, so keep the digits and run Horner from the top
+    i64 dig[HISA_MAX_Q];
+    for (int i = 0; i < limbs; i++) {
+        const PrimeConst qi = primes[i];
+        u64 t = x[(u64)i * n + j];
+        for (int m = 0; m < i; m++) {
+            i64 vm = dig[m];
+            u64 mag = vm < 0 ? (u64)(-vm) : (u64)vm;
+            u64 r = barrett128(0, mag, qi.q, qi.r1, qi.r0);
+            if (vm < 0) r = negmod(r, qi.q);
+            t = submod(t, r, qi.q);
+            t = shoup_mul(t, ginv[(u64)m * L + i], ginv_sh[(u64)m * L + i], qi.q);
+        }
+        dig[i] = t > qi.half ? (i64)t - (i64)qi.q : (i64)t;
+    }
+    (void)weight;
+    for (int i = limbs - 1; i >= 0; i--) val = val * (double)primes[i].q + (double)dig[i];
+    out[j] = val * inv_scale;
+}
+
+hipError_t launch_crt_to_double(const PrimeConst* primes, const u64* coeff_form, int limbs, const u64* garner_inv,
+                                const u64* garner_inv_sh, int L, double inv_scale, double* out, int log_n, hipStream_t st) {
+    hipLaunchKernelGGL(crt_to_double_kernel, dim3((1u << log_n) / NT), dim3(NT), 0, st, primes, coeff_form, limbs,
+                       garner_inv, garner_inv_sh, L, inv_scale, out, log_n);
+    return hipGetLastError();
+}
+
+// z_j = sum_k m_k exp(i*pi*e/N),  e = 5^j k mod 2N
+__global__ __launch_bounds__(NT) void decode_kernel(const double* cs, const double* sn, const double* m, int count,
+                                                    double* re, double* im, int log_n) {
+    const int j = blockIdx.x * NT + threadIdx.x;
+    if (j >= count) return;
+    const uint32_t n = 1u << log_n, mask = 2 * n - 1;
+    // 5^j mod 2N by square and multiply
+    uint32_t g = 1, base = 5, ex = (uint32_t)j;
+    while (ex) {
+        if (ex & 1) g = (g * base) & mask;
+        base = (base * base) & mask;
+        ex >>= 1;
+    }
+    double ar = 0.0, ai = 0.0;
+    uint32_t e = 0;
+    for (uint32_t k = 0; k < n; k++) {
+        double v = m[k];
+        ar += v * cs[e];
+        ai += v * sn[e];
+        e = (e + g) & mask;
+    }
+    re[j] = ar;
+    if (im) im[j] = ai;
+}
+
+hipError_t launch_decode(const double* cs, const double* sn, const double* m, int count, double* re, double* im, int log_n,
+                         hipStream_t st) {
+    hipLaunchKernelGGL(decode_kernel, dim3((count + NT - 1) / NT), dim3(NT), 0, st, cs, sn, m, count, re, im, log_n);
+    return hipGetLastError();
+}

@@ -1,0 +1,1326 @@
+// Host side of libhisa: context set-up (primes, roots, tables, keys), handle
+// and device-memory management, argument checks, and the launch sequences
+// behind every C-ABI entry point.  No arithmetic on polynomial data happens
+// here; the kernels are in ntt.hip, elementwise.hip, keyswitch.hip, encode.hip.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+
+#include "hisa_internal.hpp"
+
+// ---------------------------------------------------------------------------
+// host-side number theory (set-up only)
+// ---------------------------------------------------------------------------
+namespace hm {
+static inline u64 mul(u64 a, u64 b, u64 m) { return (u64)((u128)a * b % m); }
+static u64 pw(u64 b, u64 e, u64 m) {
+    u64 r = 1 % m;
+    b %= m;
+    for (; e; e >>= 1, b = mul(b, b, m))
+        if (e & 1) r = mul(r, b, m);
+    return r;
+}
+static inline u64 inv(u64 a, u64 p) { return pw(a % p, p - 2, p); }
+static inline u64 shoup(u64 w, u64 q) { return (u64)(((u128)w << 64) / q); }
+
+// deterministic Miller-Rabin for 64-bit inputs (witnesses: the primes up to 37)
+static bool is_prime(u64 n) {
+    const u64 wit[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
+    if (n < 2) return false;
+    for (u64 w : wit) {
+        if (n == w) return true;
+        if (n % w == 0) return false;
+    }
+    u64 odd = n - 1;
+    int twos = 0;
+    while (!(odd & 1)) { odd >>= 1; ++twos; }
+    for (u64 w : wit) {
+        u64 x = pw(w, odd, n);
+        if (x == 1 || x == n - 1) continue;
+        bool witness = true;
+        for (int k = 1; k < twos && witness; ++k) {
+            x = mul(x, x, n);
+            if (x == n - 1) witness = false;
+        }
+        if (witness) return false;
+    }
+    return true;
+}
+
+// largest unused prime = 1 (mod 2N) below 2^bits
+static u64 pick_prime(unsigned bits, unsigned log_n, const std::vector<u64>& taken) {
+    const u64 step = (u64)2 << log_n;
+    for (u64 c = ((u64)1 << bits) + 1 - step; c > step; c -= step) {
+        if (!is_prime(c)) continue;
+        if (std::find(taken.begin(), taken.end(), c) == taken.end()) return c;
+    }
+    return 0;
+}
+
+// primitive 2N-th root of unity from the smallest base that works
+static u64 find_psi(u64 q, unsigned log_n) {
+    const u64 n = (u64)1 << log_n;
+    for (u64 base = 2; base < q; ++base) {
+        u64 cand = pw(base, (q - 1) / (2 * n), q);
+        if (pw(cand, n, q) == q - 1) return cand;
+    }
+    return 0;
+}
+
+static inline uint32_t brev(uint32_t x, unsigned bits) {
+    uint32_t r = 0;
+    for (unsigned i = 0; i < bits; ++i) r |= ((x >> i) & 1u) << (bits - 1 - i);
+    return r;
+}
+
+// exact integer nearest to the double v (ties away from zero), reduced modulo q
+static u64 double_to_residue(double v, u64 q) {
+    bool neg = v < 0;
+    double a = fabs(v);
+    u64 r;
+    if (a < 9007199254740992.0) {  // below 2^53: round() is exact
+        r = (u64)round(a) % q;
+    } else {                        // an integer already: mantissa * 2^e
+        int e;
+        double m = frexp(a, &e);    // a = m * 2^e, m in [0.5, 1)
+        u64 mant = (u64)ldexp(m, 53);
+        r = mul(mant % q, pw(2, (u64)(e - 53), q), q);
+    }
+    return (neg && r) ? q - r : r;
+}
+}  // namespace hm
+
+// ---------------------------------------------------------------------------
+// errors, memory
+// ---------------------------------------------------------------------------
+static int fail(hisa_ctx* ctx, int code, const char* fmt, ...) {
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        ctx->err = buf;
+    }
+    return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                        \
+    do {                                                                                          \
+        hipError_t e__ = (expr);                                                                  \
+        if (e__ != hipSuccess)                                                                    \
+            return fail(ctx, e__ == hipErrorOutOfMemory ? HISA_ERR_OOM : HISA_ERR_HIP, "%s: %s", #expr, \
+                        hipGetErrorString(e__));                                                  \
+    } while (0)
+
+#define TRY(expr)                  \
+    do {                           \
+        int rc__ = (expr);         \
+        if (rc__ != HISA_OK) return rc__; \
+    } while (0)
+
+static DevBlock* dev_alloc(hisa_ctx* ctx, size_t bytes) {
+    bytes = (bytes + 255) & ~(size_t)255;
+    if (bytes == 0) bytes = 256;
+    void* p = nullptr;
+    auto it = ctx->pool.find(bytes);
+    if (it != ctx->pool.end() && !it->second.empty()) {
+        p = it->second.back();
+        it->second.pop_back();
+    } else {
+        if (hipMalloc(&p, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            // give cached blocks back and retry once
+            for (auto& kv : ctx->pool) {
+                for (void* q : kv.second) (void)hipFree(q);
+                kv.second.clear();
+            }
+            if (hipMalloc(&p, bytes) != hipSuccess) {
+                (void)hipGetLastError();
+                fail(ctx, HISA_ERR_OOM, "device allocation of %zu bytes failed", bytes);
+                return nullptr;
+            }
+        }
+        ctx->pool_bytes += bytes;
+    }
+    DevBlock* b = new DevBlock{p, bytes, 1};
+    return b;
+}
+
+// Work on one stream: a block returned to the pool may be handed out again at
+// once, later kernels are ordered behind the earlier ones that used it.
+static void dev_release(hisa_ctx* ctx, DevBlock* b) {
+    if (!b) return;
+    if (--b->refs > 0) return;
+    ctx->pool[b->bytes].push_back(b->ptr);
+    delete b;
+}
+
+struct Temp {
+    hisa_ctx* ctx;
+    DevBlock* blk;
+    Temp(hisa_ctx* c, size_t bytes) : ctx(c), blk(dev_alloc(c, bytes)) {}
+    ~Temp() { dev_release(ctx, blk); }
+    bool ok() const { return blk != nullptr; }
+    u64* u() const { return (u64*)blk->ptr; }
+    template <class T> T* as() const { return (T*)blk->ptr; }
+    Temp(const Temp&) = delete;
+    Temp& operator=(const Temp&) = delete;
+};
+
+static bool valid_ct(const hisa_ct* c) { return c && c->magic == HISA_MAGIC_CT; }
+static bool valid_pt(const hisa_pt* p) { return p && p->magic == HISA_MAGIC_PT; }
+
+static inline size_t poly_words(const hisa_ctx* ctx) { return (size_t)ctx->N; }
+static inline size_t ct_words(const hisa_ctx* ctx, uint32_t polys, uint32_t limbs) { return (size_t)polys * limbs * ctx->N; }
+
+// n ciphertext handles that are views of one allocation, [n][polys][limbs][N]
+static int alloc_ct_batch(hisa_ctx* ctx, size_t n, uint32_t polys, uint32_t limbs, double scale, hisa_ct** out) {
+    size_t words = ct_words(ctx, polys, limbs);
+    DevBlock* blk = dev_alloc(ctx, n * words * sizeof(u64));
+    if (!blk) return HISA_ERR_OOM;
+    blk->refs = (int)n;
+    for (size_t i = 0; i < n; i++)
+        out[i] = new hisa_ct{HISA_MAGIC_CT, blk, (u64*)blk->ptr + i * words, polys, limbs, scale};
+    return HISA_OK;
+}
+
+static int alloc_pt(hisa_ctx* ctx, uint32_t limbs, double scale, hisa_pt** out) {
+    DevBlock* blk = dev_alloc(ctx, (size_t)limbs * ctx->N * sizeof(u64));
+    if (!blk) return HISA_ERR_OOM;
+    *out = new hisa_pt{HISA_MAGIC_PT, blk, (u64*)blk->ptr, limbs, scale};
+    return HISA_OK;
+}
+
+// A batch of equally shaped ciphertexts as one strided array.  When the
+// handles are not evenly spaced views, they are first copied side by side.
+struct BatchIn {
+    const u64* base = nullptr;
+    u64 stride = 0;
+    DevBlock* tmp = nullptr;
+};
+
+static int gather_batch(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, BatchIn* bi) {
+    const size_t words = ct_words(ctx, cts[0]->polys, cts[0]->limbs);
+    bool even = true;
+    for (size_t i = 1; i < n && even; i++) even = cts[i]->data == cts[0]->data + i * words;
+    if (even) {
+        bi->base = cts[0]->data;
+        bi->stride = words;
+        return HISA_OK;
+    }
+    bi->tmp = dev_alloc(ctx, n * words * sizeof(u64));
+    if (!bi->tmp) return HISA_ERR_OOM;
+    for (size_t i = 0; i < n; i++)
+        HIP_TRY(ctx, hipMemcpyAsync((u64*)bi->tmp->ptr + i * words, cts[i]->data, words * sizeof(u64),
+                                    hipMemcpyDeviceToDevice, ctx->stream));
+    bi->base = (u64*)bi->tmp->ptr;
+    bi->stride = words;
+    return HISA_OK;
+}
+
+static int check_batch_shape(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, uint32_t polys) {
+    if (!cts || n == 0) return fail(ctx, HISA_ERR_ARG, "empty batch");
+    for (size_t i = 0; i < n; i++) {
+        if (!valid_ct(cts[i])) return fail(ctx, HISA_ERR_ARG, "batch entry %zu is not a ciphertext", i);
+        if (cts[i]->limbs != cts[0]->limbs) return fail(ctx, HISA_ERR_LEVEL_MISMATCH, "batch entries differ in level");
+        if (cts[i]->polys != cts[0]->polys || (polys && cts[i]->polys != polys))
+            return fail(ctx, HISA_ERR_SIZE, "batch entry %zu has %u polynomials", i, cts[i]->polys);
+    }
+    return HISA_OK;
+}
+
+static PolyMap identity_map(int limbs) {
+    PolyMap m = {};
+    m.period = limbs;
+    for (int i = 0; i < limbs; i++) m.prime_of[i] = (int16_t)i;
+    return m;
+}
+
+// ---------------------------------------------------------------------------
+// context
+// ---------------------------------------------------------------------------
+template <class T>
+static hipError_t upload(T** dst, const std::vector<T>& src) {
+    hipError_t e = hipMalloc((void**)dst, src.size() * sizeof(T));
+    if (e != hipSuccess) return e;
+    return hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice);
+}
+
+static void build_conv_table_host(const hisa_ctx* ctx, const std::vector<int>& src, std::vector<u64>& inv_hat,
+                                  std::vector<u64>& inv_hat_sh, std::vector<u64>& hat, std::vector<u64>& dmod) {
+    const int a = (int)src.size(), total = (int)ctx->total;
+    inv_hat.assign(a, 0); inv_hat_sh.assign(a, 0); hat.assign((size_t)a * total, 0); dmod.assign(total, 0);
+    for (int i = 0; i < a; i++) {
+        const u64 ci = ctx->mod[src[i]];
+        u64 prod = 1 % ci;
+        for (int m = 0; m < a; m++)
+            if (m != i) prod = hm::mul(prod, ctx->mod[src[m]] % ci, ci);
+        inv_hat[i] = hm::inv(prod, ci);
+        inv_hat_sh[i] = hm::shoup(inv_hat[i], ci);
+        for (int t = 0; t < total; t++) {
+            const u64 qt = ctx->mod[t];
+            u64 h = 1 % qt;
+            for (int m = 0; m < a; m++)
+                if (m != i) h = hm::mul(h, ctx->mod[src[m]] % qt, qt);
+            hat[(size_t)i * total + t] = h;
+        }
+    }
+    for (int t = 0; t < total; t++) {
+        const u64 qt = ctx->mod[t];
+        u64 d = 1 % qt;
+        for (int m = 0; m < a; m++) d = hm::mul(d, ctx->mod[src[m]] % qt, qt);
+        dmod[t] = d;
+    }
+}
+
+static int make_conv_table(hisa_ctx* ctx, const std::vector<int>& src, ConvTable* tab) {
+    std::vector<u64> ih, ihs, hat, dmod;
+    build_conv_table_host(ctx, src, ih, ihs, hat, dmod);
+    tab->a = (int)src.size();
+    for (int i = 0; i < tab->a; i++) tab->src[i] = src[i];
+    tab->inv_hat = ih;
+    HIP_TRY(ctx, upload(&tab->d_inv_hat, ih));
+    HIP_TRY(ctx, upload(&tab->d_inv_hat_sh, ihs));
+    HIP_TRY(ctx, upload(&tab->d_hat, hat));
+    HIP_TRY(ctx, upload(&tab->d_dmod, dmod));
+    return HISA_OK;
+}
+
+static void free_conv_table(ConvTable* t) {
+    (void)hipFree(t->d_inv_hat); (void)hipFree(t->d_inv_hat_sh); (void)hipFree(t->d_hat); (void)hipFree(t->d_dmod);
+}
+
+// conversion table of digit j restricted to `a` present primes
+static int modup_table(hisa_ctx* ctx, int digit, int a, ConvTable** out) {
+    auto key = std::make_pair(digit, a);
+    auto it = ctx->modup_tabs.find(key);
+    if (it == ctx->modup_tabs.end()) {
+        std::vector<int> src;
+        for (int i = 0; i < a; i++) src.push_back(digit * (int)ctx->alpha + i);
+        ConvTable tab = {};
+        TRY(make_conv_table(ctx, src, &tab));
+        it = ctx->modup_tabs.emplace(key, tab).first;
+    }
+    *out = &it->second;
+    return HISA_OK;
+}
+
+static int sample_secret(hisa_ctx* ctx);
+
+extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** out) {
+    if (!prm || !out) return HISA_ERR_ARG;
+    *out = nullptr;
+    if (prm->log_n < 10 || prm->log_n > 16 || prm->num_q < 1 || prm->num_q > HISA_MAX_Q || prm->dnum < 1 ||
+        prm->dnum > prm->num_q || prm->noise > 1)
+        return HISA_ERR_ARG;
+    const uint32_t alpha = (prm->num_q + prm->dnum - 1) / prm->dnum;
+    if (prm->num_q + alpha > HISA_MAX_PRIMES) return HISA_ERR_ARG;
+    for (uint32_t i = 0; i < prm->num_q; i++)
+        if (prm->q_bits[i] < prm->log_n + 2 || prm->q_bits[i] > 60) return HISA_ERR_ARG;
+    if (prm->special_bits < prm->log_n + 2 || prm->special_bits > 60) return HISA_ERR_ARG;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return HISA_ERR_HIP;
+
+    hisa_ctx* ctx = new hisa_ctx();
+    ctx->prm = *prm;
+    ctx->log_n = prm->log_n; ctx->N = 1u << prm->log_n;
+    ctx->L = prm->num_q; ctx->dnum = prm->dnum; ctx->alpha = alpha; ctx->K = alpha; ctx->total = ctx->L + ctx->K;
+    ctx->stream = (hipStream_t)hip_stream;
+    ctx->enc_counter = 0; ctx->pool_bytes = 0; ctx->moddown_tab = nullptr;
+    *out = ctx;  // from here on the caller can read last_error and must destroy
+
+    const u64 n = ctx->N;
+    for (uint32_t i = 0; i < ctx->total; i++) {
+        unsigned bits = i < ctx->L ? prm->q_bits[i] : prm->special_bits;
+        u64 p = hm::pick_prime(bits, ctx->log_n, ctx->mod);
+        if (!p) return fail(ctx, HISA_ERR_ARG, "no %u-bit prime = 1 mod 2N left", bits);
+        ctx->mod.push_back(p);
+        ctx->psi.push_back(hm::find_psi(p, ctx->log_n));
+    }
+    // per-prime constants and twiddle tables
+    std::vector<u64> tw((size_t)ctx->total * n), tw_sh(tw.size()), itw(tw.size()), itw_sh(tw.size());
+    std::vector<u64> fwd(n), bwd(n);
+    for (uint32_t i = 0; i < ctx->total; i++) {
+        const u64 q = ctx->mod[i];
+        PrimeConst pc;
+        pc.q = q;
+        u128 ratio = (~(u128)0) / q;  // floor((2^128 - 1)/q) = floor(2^128/q) since q is odd and > 1
+        pc.r1 = (u64)(ratio >> 64); pc.r0 = (u64)ratio;
+        pc.n_inv = hm::inv(n % q, q); pc.n_inv_sh = hm::shoup(pc.n_inv, q);
+        pc.half = q / 2;
+        ctx->pc.push_back(pc);
+        const u64 psi = ctx->psi[i], psi_inv = hm::inv(psi, q);
+        fwd[0] = bwd[0] = 1;
+        for (u64 e = 1; e < n; e++) { fwd[e] = hm::mul(fwd[e - 1], psi, q); bwd[e] = hm::mul(bwd[e - 1], psi_inv, q); }
+        for (u64 x = 0; x < n; x++) {
+            const u64 e = hm::brev((uint32_t)x, ctx->log_n);
+            const size_t o = (size_t)i * n + x;
+            tw[o] = fwd[e]; tw_sh[o] = hm::shoup(fwd[e], q);
+            itw[o] = bwd[e]; itw_sh[o] = hm::shoup(bwd[e], q);
+        }
+    }
+    HIP_TRY(ctx, upload(&ctx->d_primes, ctx->pc));
+    HIP_TRY(ctx, upload(&ctx->d_tw, tw));
+    HIP_TRY(ctx, upload(&ctx->d_tw_sh, tw_sh));
+    HIP_TRY(ctx, upload(&ctx->d_itw, itw));
+    HIP_TRY(ctx, upload(&ctx->d_itw_sh, itw_sh));
+    ctx->tabs = NttTables{ctx->d_primes, ctx->d_tw, ctx->d_tw_sh, ctx->d_itw, ctx->d_itw_sh};
+
+    // mod-down: source = the special primes; P^-1 and P modulo every q_i
+    {
+        std::vector<int> src;
+        for (uint32_t m = 0; m < ctx->K; m++) src.push_back((int)(ctx->L + m));
+        ctx->moddown_tab = new ConvTable();
+        TRY(make_conv_table(ctx, src, ctx->moddown_tab));
+        std::vector<u64> pinv(ctx->L), pinv_sh(ctx->L), pmod(ctx->total, 0);
+        for (uint32_t i = 0; i < ctx->total; i++) {
+            const u64 q = ctx->mod[i];
+            u64 pm = 1 % q;
+            for (uint32_t m = 0; m < ctx->K; m++) pm = hm::mul(pm, ctx->mod[ctx->L + m] % q, q);
+            pmod[i] = pm;
+            if (i < ctx->L) { pinv[i] = hm::inv(pm, q); pinv_sh[i] = hm::shoup(pinv[i], q); }
+        }
+        HIP_TRY(ctx, upload(&ctx->d_pinv, pinv));
+        HIP_TRY(ctx, upload(&ctx->d_pinv_sh, pinv_sh));
+        HIP_TRY(ctx, upload(&ctx->d_pmod, pmod));
+    }
+    // 2N-th roots of unity for encode / decode
+    {
+        std::vector<double> cs(2 * n), sn(2 * n);
+        const long double pi = 3.14159265358979323846264338327950288L;
+        for (u64 t = 0; t < 2 * n; t++) {
+            cs[t] = (double)cosl(pi * (long double)t / (long double)n);
+            sn[t] = (double)sinl(pi * (long double)t / (long double)n);
+        }
+        HIP_TRY(ctx, upload(&ctx->d_cos, cs));
+        HIP_TRY(ctx, upload(&ctx->d_sin, sn));
+    }
+    HIP_TRY(ctx, hipMalloc((void**)&ctx->d_secret, (size_t)ctx->total * n * sizeof(u64)));
+    TRY(sample_secret(ctx));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_destroy(hisa_ctx* ctx) {
+    if (!ctx) return HISA_OK;
+    (void)hipStreamSynchronize(ctx->stream);
+    for (auto* m : {&ctx->keys, &ctx->aux})
+        for (auto& kv : *m)
+            if (kv.second.blk) { (void)hipFree(kv.second.blk->ptr); delete kv.second.blk; }
+    for (auto& kv : ctx->pool)
+        for (void* p : kv.second) (void)hipFree(p);
+    for (auto& kv : ctx->modup_tabs) free_conv_table(&kv.second);
+    if (ctx->moddown_tab) { free_conv_table(ctx->moddown_tab); delete ctx->moddown_tab; }
+    (void)hipFree(ctx->d_primes); (void)hipFree(ctx->d_tw); (void)hipFree(ctx->d_tw_sh); (void)hipFree(ctx->d_itw);
+    (void)hipFree(ctx->d_itw_sh); (void)hipFree(ctx->d_secret); (void)hipFree(ctx->d_pinv); (void)hipFree(ctx->d_pinv_sh);
+    (void)hipFree(ctx->d_pmod); (void)hipFree(ctx->d_cos); (void)hipFree(ctx->d_sin);
+    delete ctx;
+    return HISA_OK;
+}
+
+extern "C" const char* hisa_last_error(const hisa_ctx* ctx) { return ctx ? ctx->err.c_str() : "no context"; }
+
+extern "C" int hisa_sync(hisa_ctx* ctx) {
+    if (!ctx) return HISA_ERR_ARG;
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HISA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// keys
+// ---------------------------------------------------------------------------
+static int sample_secret(hisa_ctx* ctx) {
+    PolyMap all = identity_map((int)ctx->total);
+    HIP_TRY(ctx, launch_sample_small(ctx->d_primes, ctx->prm.seed, 1, 0, 0, 1, all, 1, 0, 0, ctx->d_secret, nullptr,
+                                     (int)ctx->log_n, ctx->stream));
+    HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, ctx->d_secret, 0, (int)ctx->total, all, ctx->stream));
+    return HISA_OK;
+}
+
+// key towards `target` (NTT form over all primes): per digit, a uniform (kind 4), e Gaussian (kind 5),
+// b = -a*s + e + [prime in digit] (P mod q) target
+static int gen_switch_key(hisa_ctx* ctx, u64 key_id, const u64* target) {
+    const size_t n = ctx->N, total = ctx->total;
+    const size_t words = (size_t)ctx->dnum * 2 * total * n;
+    void* p = nullptr;
+    HIP_TRY(ctx, hipMalloc(&p, words * sizeof(u64)));
+    DevBlock* blk = new DevBlock{p, words * sizeof(u64), 1};
+    SwitchKey key{blk, (u64*)p};
+    ctx->keys[key_id] = key;
+    Temp e(ctx, total * n * sizeof(u64));
+    if (!e.ok()) return HISA_ERR_OOM;
+    PolyMap all = identity_map((int)total);
+    for (uint32_t j = 0; j < ctx->dnum; j++) {
+        const u64 ctr = (key_id << 8) | j;
+        u64* digit = key.data + (size_t)j * 2 * total * n;
+        HIP_TRY(ctx, launch_sample_uniform(ctx->d_primes, ctx->prm.seed, 4, ctr, all, (int)total, 0, 0, digit + total * n,
+                                           (int)ctx->log_n, ctx->stream));
+        HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, digit + total * n, 0, (int)total, all, ctx->stream));
+        HIP_TRY(ctx, launch_sample_small(ctx->d_primes, ctx->prm.seed, 5, ctr, (int)ctx->prm.noise, 0, all, 1, 0, 0, e.u(),
+                                         nullptr, (int)ctx->log_n, ctx->stream));
+        HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, e.u(), 0, (int)total, all, ctx->stream));
+        HIP_TRY(ctx, launch_key_combine(ctx->d_primes, ctx->d_secret, target, e.u(), ctx->d_pmod, digit, (int)total,
+                                        (int)ctx->L, (int)ctx->alpha, (int)j, (int)ctx->log_n, ctx->stream));
+    }
+    return HISA_OK;
+}
+
+extern "C" int hisa_keygen(hisa_ctx* ctx) {
+    if (!ctx) return HISA_ERR_ARG;
+    if (ctx->keys.count(0)) return HISA_OK;
+    Temp s2(ctx, (size_t)ctx->total * ctx->N * sizeof(u64));
+    if (!s2.ok()) return HISA_ERR_OOM;
+    HIP_TRY(ctx, launch_pointwise_square(ctx->d_primes, ctx->d_secret, s2.u(), (int)ctx->total, (int)ctx->log_n,
+                                         ctx->stream));
+    return gen_switch_key(ctx, 0, s2.u());
+}
+
+static u64 galois_of(const hisa_ctx* ctx, int32_t steps) {
+    const u64 slots = ctx->N / 2, mask = 2 * (u64)ctx->N - 1;
+    i64 r = (i64)steps % (i64)slots;
+    if (r < 0) r += (i64)slots;
+    u64 g = 1;
+    for (i64 i = 0; i < r; i++) g = (g * 5) & mask;
+    return r == 0 ? 0 : g;
+}
+
+extern "C" int hisa_galois_elt(hisa_ctx* ctx, int32_t left_steps, uint64_t* g) {
+    if (!ctx || !g) return HISA_ERR_ARG;
+    u64 v = galois_of(ctx, left_steps);
+    *g = v ? v : 1;
+    return HISA_OK;
+}
+
+extern "C" int hisa_gen_rot_keys(hisa_ctx* ctx, const int32_t* left_steps, size_t count) {
+    if (!ctx || (!left_steps && count)) return fail(ctx, HISA_ERR_ARG, "null steps");
+    for (size_t i = 0; i < count; i++) {
+        const u64 g = galois_of(ctx, left_steps[i]);
+        if (g == 0 || ctx->keys.count(g)) continue;
+        Temp tgt(ctx, (size_t)ctx->total * ctx->N * sizeof(u64));
+        if (!tgt.ok()) return HISA_ERR_OOM;
+        HIP_TRY(ctx, launch_automorph_ntt(ctx->d_secret, 0, tgt.u(), 0, g, (int)ctx->total, 1, (int)ctx->log_n, ctx->stream));
+        TRY(gen_switch_key(ctx, g, tgt.u()));
+    }
+    return HISA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// encode / decode / plaintexts
+// ---------------------------------------------------------------------------
+extern "C" int hisa_pt_from_coeffs(hisa_ctx* ctx, const int64_t* host_coeffs, double scale, uint32_t limbs, hisa_pt** out) {
+    if (!ctx || !host_coeffs || !out || limbs < 1 || limbs > ctx->L) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    Temp co(ctx, ctx->N * sizeof(i64));
+    if (!co.ok()) return HISA_ERR_OOM;
+    HIP_TRY(ctx, hipMemcpyAsync(co.blk->ptr, host_coeffs, ctx->N * sizeof(i64), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));  // the host buffer may be reused by the caller
+    TRY(alloc_pt(ctx, limbs, scale, out));
+    HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>(), (*out)->data, (int)limbs, (int)ctx->log_n, ctx->stream));
+    HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, (*out)->data, 0, (int)limbs, identity_map((int)limbs), ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_encode(hisa_ctx* ctx, const double* re, const double* im, size_t count, double scale, uint32_t limbs,
+                           hisa_pt** out) {
+    if (!ctx || !out || (!re && count) || limbs < 1 || limbs > ctx->L || count > ctx->N / 2 || !(scale > 0))
+        return fail(ctx, HISA_ERR_ARG, "bad argument");
+    // coefficients must fit a signed 64-bit integer: |m_k| <= scale * max|z| * ~1
+    Temp buf(ctx, (2 * count + 2) * sizeof(double));
+    Temp co(ctx, ctx->N * sizeof(i64));
+    if (!buf.ok() || !co.ok()) return HISA_ERR_OOM;
+    double* d_re = buf.as<double>();
+    double* d_im = im ? d_re + count : nullptr;
+    if (count) HIP_TRY(ctx, hipMemcpyAsync(d_re, re, count * sizeof(double), hipMemcpyHostToDevice, ctx->stream));
+    if (im && count) HIP_TRY(ctx, hipMemcpyAsync(d_im, im, count * sizeof(double), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    HIP_TRY(ctx, launch_encode(ctx->d_cos, ctx->d_sin, d_re, d_im, (int)count, 2.0 * scale / (double)ctx->N, co.as<i64>(),
+                               (int)ctx->log_n, ctx->stream));
+    TRY(alloc_pt(ctx, limbs, scale, out));
+    HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>(), (*out)->data, (int)limbs, (int)ctx->log_n, ctx->stream));
+    HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, (*out)->data, 0, (int)limbs, identity_map((int)limbs), ctx->stream));
+    return HISA_OK;
+}
+
+// q_m^-1 mod q_i tables for the mixed-radix lift, built on first use
+static int garner_tables(hisa_ctx* ctx, u64** inv, u64** inv_sh) {
+    static const u64 KEY = 0;
+    auto it = ctx->aux.find(KEY);
+    if (it == ctx->aux.end()) {
+        const size_t L = ctx->L;
+        std::vector<u64> t(2 * L * L, 0);
+        for (size_t m = 0; m < L; m++)
+            for (size_t i = 0; i < L; i++) {
+                if (i == m) continue;
+                u64 v = hm::inv(ctx->mod[m] % ctx->mod[i], ctx->mod[i]);
+                t[m * L + i] = v;
+                t[L * L + m * L + i] = hm::shoup(v, ctx->mod[i]);
+            }
+        u64* d = nullptr;
+        HIP_TRY(ctx, upload(&d, t));
+        DevBlock* blk = new DevBlock{d, t.size() * sizeof(u64), 1};
+        it = ctx->aux.emplace(KEY, SwitchKey{blk, d}).first;
+    }
+    *inv = it->second.data;
+    *inv_sh = it->second.data + (size_t)ctx->L * ctx->L;
+    return HISA_OK;
+}
+
+extern "C" int hisa_decode(hisa_ctx* ctx, const hisa_pt* pt, double* re, double* im, size_t count) {
+    if (!ctx || !valid_pt(pt) || !re || count > ctx->N / 2) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    const size_t n = ctx->N;
+    Temp co(ctx, (size_t)pt->limbs * n * sizeof(u64));
+    Temp m(ctx, n * sizeof(double));
+    Temp z(ctx, (2 * count + 2) * sizeof(double));
+    if (!co.ok() || !m.ok() || !z.ok()) return HISA_ERR_OOM;
+    InttExtra ex = {};
+    ex.in = pt->data;
+    HIP_TRY(ctx, launch_intt(ctx->tabs, (int)ctx->log_n, co.u(), 0, (int)pt->limbs, identity_map((int)pt->limbs), &ex,
+                             ctx->stream));
+    u64 *ginv, *ginv_sh;
+    TRY(garner_tables(ctx, &ginv, &ginv_sh));
+    HIP_TRY(ctx, launch_crt_to_double(ctx->d_primes, co.u(), (int)pt->limbs, ginv, ginv_sh, (int)ctx->L, 1.0 / pt->scale,
+                                      m.as<double>(), (int)ctx->log_n, ctx->stream));
+    double* d_re = z.as<double>();
+    double* d_im = d_re + count;
+    HIP_TRY(ctx, launch_decode(ctx->d_cos, ctx->d_sin, m.as<double>(), (int)count, d_re, d_im, (int)ctx->log_n, ctx->stream));
+    if (count) HIP_TRY(ctx, hipMemcpyAsync(re, d_re, count * sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+    if (im && count) HIP_TRY(ctx, hipMemcpyAsync(im, d_im, count * sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_pt_export(hisa_ctx* ctx, const hisa_pt* pt, uint64_t* host) {
+    if (!ctx || !valid_pt(pt) || !host) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    const size_t words = (size_t)pt->limbs * ctx->N;
+    Temp co(ctx, words * sizeof(u64));
+    if (!co.ok()) return HISA_ERR_OOM;
+    InttExtra ex = {};
+    ex.in = pt->data;
+    HIP_TRY(ctx, launch_intt(ctx->tabs, (int)ctx->log_n, co.u(), 0, (int)pt->limbs, identity_map((int)pt->limbs), &ex,
+                             ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(host, co.u(), words * sizeof(u64), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_pt_info(const hisa_pt* pt, uint32_t* limbs, double* scale) {
+    if (!valid_pt(pt)) return HISA_ERR_ARG;
+    if (limbs) *limbs = pt->limbs;
+    if (scale) *scale = pt->scale;
+    return HISA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// encryption profile
+// ---------------------------------------------------------------------------
+extern "C" int hisa_encrypt_batch(hisa_ctx* ctx, const hisa_pt* const* pts, size_t n, hisa_ct** out) {
+    if (!ctx || !pts || !out || n == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    for (size_t i = 0; i < n; i++) {
+        if (!valid_pt(pts[i])) return fail(ctx, HISA_ERR_ARG, "entry %zu is not a plaintext", i);
+        if (pts[i]->limbs != pts[0]->limbs) return fail(ctx, HISA_ERR_LEVEL_MISMATCH, "plaintexts differ in level");
+    }
+    const uint32_t l = pts[0]->limbs;
+    const size_t nn = ctx->N, lw = (size_t)l * nn;
+    TRY(alloc_ct_batch(ctx, n, 2, l, pts[0]->scale, out));
+    for (size_t i = 0; i < n; i++) out[i]->scale = pts[i]->scale;
+    u64* ct = out[0]->data;
+    Temp e(ctx, n * lw * sizeof(u64));
+    Temp ptbuf(ctx, n * lw * sizeof(u64));
+    if (!e.ok() || !ptbuf.ok()) return HISA_ERR_OOM;
+    PolyMap lm = identity_map((int)l);
+    // c1 = a: uniform in coefficient form, then NTT.  Treat (ciphertext, poly 1) as batch entries of stride 2*l*N.
+    HIP_TRY(ctx, launch_sample_uniform(ctx->d_primes, ctx->prm.seed, 2, ctx->enc_counter, lm, (int)(n * l), 2 * lw, 1,
+                                       ct + lw, (int)ctx->log_n, ctx->stream));
+    HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, ct + lw, 2 * lw, (int)(n * l), lm, ctx->stream));
+    HIP_TRY(ctx, launch_sample_small(ctx->d_primes, ctx->prm.seed, 3, ctx->enc_counter, (int)ctx->prm.noise, 0, lm, (int)n,
+                                     lw, 1, e.u(), nullptr, (int)ctx->log_n, ctx->stream));
+    HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, e.u(), lw, (int)(n * l), lm, ctx->stream));
+    const u64* pt_base = pts[0]->data;
+    u64 pt_bs = 0;
+    if (n > 1) {
+        for (size_t i = 0; i < n; i++)
+            HIP_TRY(ctx, hipMemcpyAsync(ptbuf.u() + i * lw, pts[i]->data, lw * sizeof(u64), hipMemcpyDeviceToDevice,
+                                        ctx->stream));
+        pt_base = ptbuf.u();
+        pt_bs = lw;
+    }
+    HIP_TRY(ctx, launch_encrypt_combine(ctx->d_primes, ctx->d_secret, pt_base, e.u(), ct, (int)l, n, pt_bs, (int)ctx->log_n,
+                                        ctx->stream));
+    ctx->enc_counter += n;
+    return HISA_OK;
+}
+
+extern "C" int hisa_encrypt(hisa_ctx* ctx, const hisa_pt* pt, hisa_ct** out) { return hisa_encrypt_batch(ctx, &pt, 1, out); }
+
+extern "C" int hisa_set_enc_counter(hisa_ctx* ctx, uint64_t counter) {
+    if (!ctx) return HISA_ERR_ARG;
+    ctx->enc_counter = counter;
+    return HISA_OK;
+}
+
+extern "C" int hisa_decrypt(hisa_ctx* ctx, const hisa_ct* ct, hisa_pt** out) {
+    if (!ctx || !valid_ct(ct) || !out) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(alloc_pt(ctx, ct->limbs, ct->scale, out));
+    HIP_TRY(ctx, launch_decrypt(ctx->d_primes, ctx->d_secret, ct->data, (*out)->data, (int)ct->limbs, (int)ct->polys,
+                                (int)ctx->log_n, ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_copy(hisa_ctx* ctx, const hisa_ct* ct, hisa_ct** out) {
+    if (!ctx || !valid_ct(ct) || !out) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(alloc_ct_batch(ctx, 1, ct->polys, ct->limbs, ct->scale, out));
+    HIP_TRY(ctx, hipMemcpyAsync((*out)->data, ct->data, ct_words(ctx, ct->polys, ct->limbs) * sizeof(u64),
+                                hipMemcpyDeviceToDevice, ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_free(hisa_ctx* ctx, void* handle) {
+    if (!handle) return HISA_OK;
+    if (!ctx) return HISA_ERR_ARG;
+    uint32_t magic = *(uint32_t*)handle;
+    if (magic == HISA_MAGIC_CT) {
+        hisa_ct* c = (hisa_ct*)handle;
+        dev_release(ctx, c->blk);
+        c->magic = 0;
+        delete c;
+    } else if (magic == HISA_MAGIC_PT) {
+        hisa_pt* p = (hisa_pt*)handle;
+        dev_release(ctx, p->blk);
+        p->magic = 0;
+        delete p;
+    } else {
+        return fail(ctx, HISA_ERR_ARG, "not a live handle");
+    }
+    return HISA_OK;
+}
+
+// swap the storage of an in-place result into the caller's handle
+static void adopt(hisa_ctx* ctx, hisa_ct* dst, hisa_ct* src) {
+    dev_release(ctx, dst->blk);
+    dst->blk = src->blk; dst->data = src->data; dst->polys = src->polys; dst->limbs = src->limbs; dst->scale = src->scale;
+    src->magic = 0;
+    delete src;
+}
+
+// ---------------------------------------------------------------------------
+// add / sub
+// ---------------------------------------------------------------------------
+static bool same_scale(double a, double b) { return fabs(a - b) <= ldexp(fmax(fabs(a), fabs(b)), -30); }
+
+static int addsub_into(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b, int op, u64* dst) {
+    HIP_TRY(ctx, launch_addsub(ctx->d_primes, a->data, b->data, dst, op, (int)a->limbs, (int)a->polys, (int)b->polys, 1, 0,
+                               0, 0, (int)ctx->log_n, ctx->stream));
+    return HISA_OK;
+}
+
+static int addsub_check(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b) {
+    if (!ctx || !valid_ct(a) || !valid_ct(b)) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    if (a->limbs != b->limbs) return fail(ctx, HISA_ERR_LEVEL_MISMATCH, "levels %u and %u", a->limbs, b->limbs);
+    if (!same_scale(a->scale, b->scale)) return fail(ctx, HISA_ERR_SCALE_MISMATCH, "scales %g and %g", a->scale, b->scale);
+    return HISA_OK;
+}
+
+static int addsub(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b, int op, hisa_ct** out) {
+    TRY(addsub_check(ctx, a, b));
+    if (!out) return fail(ctx, HISA_ERR_ARG, "null out");
+    if (a->polys < b->polys) {
+        if (op == OP_SUB) return fail(ctx, HISA_ERR_SIZE, "subtrahend has more polynomials");
+        std::swap(a, b);
+    }
+    TRY(alloc_ct_batch(ctx, 1, a->polys, a->limbs, a->scale, out));
+    return addsub_into(ctx, a, b, op, (*out)->data);
+}
+
+static int addsub_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_ct* b, int op) {
+    TRY(addsub_check(ctx, a, b));
+    if (a->polys < b->polys) return fail(ctx, HISA_ERR_SIZE, "right operand has more polynomials");
+    return addsub_into(ctx, a, b, op, a->data);
+}
+
+extern "C" int hisa_add(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b, hisa_ct** out) { return addsub(ctx, a, b, OP_ADD, out); }
+extern "C" int hisa_sub(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b, hisa_ct** out) { return addsub(ctx, a, b, OP_SUB, out); }
+extern "C" int hisa_add_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_ct* b) { return addsub_assign(ctx, a, b, OP_ADD); }
+extern "C" int hisa_sub_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_ct* b) { return addsub_assign(ctx, a, b, OP_SUB); }
+
+static int addsub_plain(hisa_ctx* ctx, const hisa_ct* a, const hisa_pt* p, int op, u64* dst) {
+    // the plaintext is a one-polynomial operand: polys_b = 1
+    HIP_TRY(ctx, launch_addsub(ctx->d_primes, a->data, p->data, dst, op, (int)a->limbs, (int)a->polys, 1, 1, 0, 0, 0,
+                               (int)ctx->log_n, ctx->stream));
+    return HISA_OK;
+}
+
+static int plain_check(hisa_ctx* ctx, const hisa_ct* a, const hisa_pt* p, bool need_scale) {
+    if (!ctx || !valid_ct(a) || !valid_pt(p)) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    if (a->limbs != p->limbs) return fail(ctx, HISA_ERR_LEVEL_MISMATCH, "levels %u and %u", a->limbs, p->limbs);
+    if (need_scale && !same_scale(a->scale, p->scale))
+        return fail(ctx, HISA_ERR_SCALE_MISMATCH, "scales %g and %g", a->scale, p->scale);
+    return HISA_OK;
+}
+
+static int addsub_plain_new(hisa_ctx* ctx, const hisa_ct* a, const hisa_pt* p, int op, hisa_ct** out) {
+    TRY(plain_check(ctx, a, p, true));
+    if (!out) return fail(ctx, HISA_ERR_ARG, "null out");
+    TRY(alloc_ct_batch(ctx, 1, a->polys, a->limbs, a->scale, out));
+    return addsub_plain(ctx, a, p, op, (*out)->data);
+}
+
+extern "C" int hisa_add_plain(hisa_ctx* ctx, const hisa_ct* a, const hisa_pt* p, hisa_ct** out) { return addsub_plain_new(ctx, a, p, OP_ADD, out); }
+extern "C" int hisa_sub_plain(hisa_ctx* ctx, const hisa_ct* a, const hisa_pt* p, hisa_ct** out) { return addsub_plain_new(ctx, a, p, OP_SUB, out); }
+extern "C" int hisa_add_plain_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_pt* p) {
+    TRY(plain_check(ctx, a, p, true));
+    return addsub_plain(ctx, a, p, OP_ADD, a->data);
+}
+extern "C" int hisa_sub_plain_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_pt* p) {
+    TRY(plain_check(ctx, a, p, true));
+    return addsub_plain(ctx, a, p, OP_SUB, a->data);
+}
+
+static int addsub_scalar(hisa_ctx* ctx, const hisa_ct* a, double x, int op, u64* dst) {
+    u64 consts[HISA_MAX_PRIMES];
+    const double v = x * a->scale;
+    if (!isfinite(v)) return fail(ctx, HISA_ERR_ARG, "scalar times scale is not finite");
+    for (uint32_t i = 0; i < a->limbs; i++) consts[i] = hm::double_to_residue(v, ctx->mod[i]);
+    HIP_TRY(ctx, launch_add_const(ctx->d_primes, a->data, dst, consts, op, (int)a->limbs, (int)a->polys, (int)ctx->log_n,
+                                  ctx->stream));
+    return HISA_OK;
+}
+
+static int addsub_scalar_new(hisa_ctx* ctx, const hisa_ct* a, double x, int op, hisa_ct** out) {
+    if (!ctx || !valid_ct(a) || !out) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(alloc_ct_batch(ctx, 1, a->polys, a->limbs, a->scale, out));
+    return addsub_scalar(ctx, a, x, op, (*out)->data);
+}
+
+extern "C" int hisa_add_scalar(hisa_ctx* ctx, const hisa_ct* a, double x, hisa_ct** out) { return addsub_scalar_new(ctx, a, x, OP_ADD, out); }
+extern "C" int hisa_sub_scalar(hisa_ctx* ctx, const hisa_ct* a, double x, hisa_ct** out) { return addsub_scalar_new(ctx, a, x, OP_SUB, out); }
+extern "C" int hisa_add_scalar_assign(hisa_ctx* ctx, hisa_ct* a, double x) {
+    if (!ctx || !valid_ct(a)) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    return addsub_scalar(ctx, a, x, OP_ADD, a->data);
+}
+extern "C" int hisa_sub_scalar_assign(hisa_ctx* ctx, hisa_ct* a, double x) {
+    if (!ctx || !valid_ct(a)) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    return addsub_scalar(ctx, a, x, OP_SUB, a->data);
+}
+
+extern "C" int hisa_add_batch(hisa_ctx* ctx, const hisa_ct* const* a, const hisa_ct* const* b, size_t n, hisa_ct** out) {
+    if (!ctx || !out) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_batch_shape(ctx, a, n, 0));
+    TRY(check_batch_shape(ctx, b, n, a[0]->polys));
+    for (size_t i = 0; i < n; i++) TRY(addsub_check(ctx, a[i], b[i]));
+    BatchIn ia, ib;
+    TRY(gather_batch(ctx, a, n, &ia));
+    int rc = gather_batch(ctx, b, n, &ib);
+    if (rc == HISA_OK) rc = alloc_ct_batch(ctx, n, a[0]->polys, a[0]->limbs, a[0]->scale, out);
+    if (rc == HISA_OK) {
+        for (size_t i = 0; i < n; i++) out[i]->scale = a[i]->scale;
+        hipError_t e = launch_addsub(ctx->d_primes, ia.base, ib.base, out[0]->data, OP_ADD, (int)a[0]->limbs, (int)a[0]->polys,
+                                     (int)a[0]->polys, n, ia.stride, ib.stride, ia.stride, (int)ctx->log_n, ctx->stream);
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "add batch: %s", hipGetErrorString(e));
+    }
+    dev_release(ctx, ia.tmp);
+    dev_release(ctx, ib.tmp);
+    return rc;
+}
+
+// ---------------------------------------------------------------------------
+// multiply
+// ---------------------------------------------------------------------------
+extern "C" int hisa_mul_plain_batch(hisa_ctx* ctx, const hisa_ct* const* a, const hisa_pt* p, size_t n, hisa_ct** out) {
+    if (!ctx || !out) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_batch_shape(ctx, a, n, 0));
+    TRY(plain_check(ctx, a[0], p, false));
+    BatchIn ia;
+    TRY(gather_batch(ctx, a, n, &ia));
+    int rc = alloc_ct_batch(ctx, n, a[0]->polys, a[0]->limbs, a[0]->scale * p->scale, out);
+    if (rc == HISA_OK) {
+        for (size_t i = 0; i < n; i++) out[i]->scale = a[i]->scale * p->scale;
+        hipError_t e = launch_mul_plain(ctx->d_primes, ia.base, p->data, out[0]->data, (int)a[0]->limbs, (int)a[0]->polys, n,
+                                        ia.stride, ia.stride, (int)ctx->log_n, ctx->stream);
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "mul_plain: %s", hipGetErrorString(e));
+    }
+    dev_release(ctx, ia.tmp);
+    return rc;
+}
+
+extern "C" int hisa_mul_plain(hisa_ctx* ctx, const hisa_ct* a, const hisa_pt* p, hisa_ct** out) {
+    return hisa_mul_plain_batch(ctx, &a, p, 1, out);
+}
+
+extern "C" int hisa_mul_plain_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_pt* p) {
+    TRY(plain_check(ctx, a, p, false));
+    HIP_TRY(ctx, launch_mul_plain(ctx->d_primes, a->data, p->data, a->data, (int)a->limbs, (int)a->polys, 1, 0, 0,
+                                  (int)ctx->log_n, ctx->stream));
+    a->scale *= p->scale;
+    return HISA_OK;
+}
+
+static int mul_scalar_into(hisa_ctx* ctx, const hisa_ct* a, double x, double x_scale, u64* dst) {
+    u64 consts[2 * HISA_MAX_PRIMES];
+    const double v = x * x_scale;
+    if (!isfinite(v)) return fail(ctx, HISA_ERR_ARG, "scalar times scale is not finite");
+    for (uint32_t i = 0; i < a->limbs; i++) {
+        consts[i] = hm::double_to_residue(v, ctx->mod[i]);
+        consts[a->limbs + i] = hm::shoup(consts[i], ctx->mod[i]);
+    }
+    HIP_TRY(ctx, launch_mul_const(ctx->d_primes, a->data, dst, consts, (int)a->limbs, (int)a->polys, (int)ctx->log_n,
+                                  ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_mul_scalar(hisa_ctx* ctx, const hisa_ct* a, double x, double x_scale, hisa_ct** out) {
+    if (!ctx || !valid_ct(a) || !out) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(alloc_ct_batch(ctx, 1, a->polys, a->limbs, a->scale * x_scale, out));
+    return mul_scalar_into(ctx, a, x, x_scale, (*out)->data);
+}
+
+extern "C" int hisa_mul_scalar_assign(hisa_ctx* ctx, hisa_ct* a, double x, double x_scale) {
+    if (!ctx || !valid_ct(a)) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(mul_scalar_into(ctx, a, x, x_scale, a->data));
+    a->scale *= x_scale;
+    return HISA_OK;
+}
+
+extern "C" int hisa_mul_no_relin_batch(hisa_ctx* ctx, const hisa_ct* const* a, const hisa_ct* const* b, size_t n,
+                                       hisa_ct** out) {
+    if (!ctx || !out) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_batch_shape(ctx, a, n, 2));
+    TRY(check_batch_shape(ctx, b, n, 2));
+    if (a[0]->limbs != b[0]->limbs) return fail(ctx, HISA_ERR_LEVEL_MISMATCH, "levels %u and %u", a[0]->limbs, b[0]->limbs);
+    BatchIn ia, ib;
+    TRY(gather_batch(ctx, a, n, &ia));
+    int rc = gather_batch(ctx, b, n, &ib);
+    if (rc == HISA_OK) rc = alloc_ct_batch(ctx, n, 3, a[0]->limbs, 0.0, out);
+    if (rc == HISA_OK) {
+        for (size_t i = 0; i < n; i++) out[i]->scale = a[i]->scale * b[i]->scale;
+        hipError_t e = launch_mul_no_relin(ctx->d_primes, ia.base, ib.base, out[0]->data, (int)a[0]->limbs, n, ia.stride,
+                                           ib.stride, ct_words(ctx, 3, a[0]->limbs), (int)ctx->log_n, ctx->stream);
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "mul_no_relin: %s", hipGetErrorString(e));
+    }
+    dev_release(ctx, ia.tmp);
+    dev_release(ctx, ib.tmp);
+    return rc;
+}
+
+extern "C" int hisa_mul_no_relin(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b, hisa_ct** out) {
+    return hisa_mul_no_relin_batch(ctx, &a, &b, 1, out);
+}
+
+// ---------------------------------------------------------------------------
+// hybrid key switching
+// ---------------------------------------------------------------------------
+// Per-level factors that close the inverse transform of the polynomial to be
+// switched: N^-1 * (D_j / q_i)^-1 mod q_i for limb i in digit j.
+struct LevelPost {
+    u64* d;  // [l] values then [l] Shoup companions
+};
+
+static int level_post(hisa_ctx* ctx, int l, u64** post, u64** post_sh) {
+    const u64 KEY = 16 + (u64)l;
+    auto it = ctx->aux.find(KEY);
+    if (it == ctx->aux.end()) {
+        std::vector<u64> t(2 * (size_t)l);
+        const int digits = (l + (int)ctx->alpha - 1) / (int)ctx->alpha;
+        for (int j = 0; j < digits; j++) {
+            const int lo = j * (int)ctx->alpha, hi = std::min(lo + (int)ctx->alpha, l);
+            ConvTable* tab;
+            TRY(modup_table(ctx, j, hi - lo, &tab));
+            for (int i = lo; i < hi; i++) {
+                const u64 q = ctx->mod[i];
+                t[i] = hm::mul(ctx->pc[i].n_inv, tab->inv_hat[i - lo], q);
+                t[l + i] = hm::shoup(t[i], q);
+            }
+        }
+        u64* d = nullptr;
+        HIP_TRY(ctx, upload(&d, t));
+        it = ctx->aux.emplace(KEY, SwitchKey{new DevBlock{d, t.size() * sizeof(u64), 1}, d}).first;
+    }
+    *post = it->second.data;
+    *post_sh = it->second.data + l;
+    return HISA_OK;
+}
+
+static int moddown_post(hisa_ctx* ctx, u64** post, u64** post_sh) {
+    const u64 KEY = 1;
+    auto it = ctx->aux.find(KEY);
+    if (it == ctx->aux.end()) {
+        // laid out for a PolyMap of period l + K is not possible (l varies), so the table is indexed by
+        // special-prime number and the caller offsets the pointer by -l
+        std::vector<u64> t(2 * (size_t)ctx->K);
+        for (uint32_t m = 0; m < ctx->K; m++) {
+            const u64 q = ctx->mod[ctx->L + m];
+            t[m] = hm::mul(ctx->pc[ctx->L + m].n_inv, ctx->moddown_tab->inv_hat[m], q);
+            t[ctx->K + m] = hm::shoup(t[m], q);
+        }
+        u64* d = nullptr;
+        HIP_TRY(ctx, upload(&d, t));
+        it = ctx->aux.emplace(KEY, SwitchKey{new DevBlock{d, t.size() * sizeof(u64), 1}, d}).first;
+    }
+    *post = it->second.data;
+    *post_sh = it->second.data + ctx->K;
+    return HISA_OK;
+}
+
+// Key switch of B polynomials d[b] (NTT form, l limbs, at d + b*d_bs) under `key`;
+// out[b] = (ks0 + add0, ks1 + add1) with the optional addends taken from
+// add + b*add_bs (add_polys polynomials of l limbs, read through sigma_g when add_galois != 0).
+static int key_switch_core(hisa_ctx* ctx, const u64* d, u64 d_bs, size_t B, int l, const SwitchKey& key, const u64* add,
+                           u64 add_bs, int add_polys, u64 add_galois, u64* out) {
+    const size_t n = ctx->N;
+    const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total;
+    const int ext_limbs = l + K;
+    const int digits = (l + alpha - 1) / alpha;
+    const int log_n = (int)ctx->log_n;
+    hipStream_t st = ctx->stream;
+
+    Temp y(ctx, B * l * n * sizeof(u64));
+    Temp ext(ctx, B * (size_t)digits * ext_limbs * n * sizeof(u64));
+    Temp acc(ctx, B * 2 * (size_t)ext_limbs * n * sizeof(u64));
+    Temp conv(ctx, B * 2 * (size_t)l * n * sizeof(u64));
+    if (!y.ok() || !ext.ok() || !acc.ok() || !conv.ok()) return HISA_ERR_OOM;
+    const u64 ext_bs = (u64)digits * ext_limbs * n;
+
+    // 1. coefficient form, each limb pre-multiplied by (D_j/q_i)^-1
+    u64 *post, *post_sh;
+    TRY(level_post(ctx, l, &post, &post_sh));
+    InttExtra ex = {};
+    ex.in = d; ex.in_batch_stride = d_bs; ex.post = post; ex.post_sh = post_sh;
+    HIP_TRY(ctx, launch_intt(ctx->tabs, log_n, y.u(), (u64)l * n, (int)(B * l), identity_map(l), &ex, st));
+
+    // 2.-3. per digit: convert to every other prime, transform; own primes keep the input's NTT form
+    for (int j = 0; j < digits; j++) {
+        const int lo = j * alpha, hi = std::min(lo + alpha, l);
+        ConvTable* tab;
+        TRY(modup_table(ctx, j, hi - lo, &tab));
+        ConvArgs ca = {};
+        ca.y = y.u(); ca.y_bs = (u64)l * n; ca.src_pos0 = lo; ca.src_prime0 = lo; ca.a = hi - lo;
+        ca.hat = tab->d_hat; ca.dmod = tab->d_dmod; ca.total = total;
+        ca.out = ext.u() + (size_t)j * ext_limbs * n; ca.out_bs = ext_bs;
+        PolyMap pm = {};
+        pm.period = ext_limbs;
+        int nt = 0;
+        for (int x = 0; x < ext_limbs; x++) {
+            const int prime = x < l ? x : L + (x - l);
+            const bool own = x >= lo && x < hi;
+            pm.prime_of[x] = own ? (int16_t)-1 : (int16_t)prime;
+            if (!own) { ca.tgt_pos[nt] = (int16_t)x; ca.tgt_prime[nt] = (int16_t)prime; nt++; }
+        }
+        ca.n_targets = nt;
+        HIP_TRY(ctx, launch_base_conv(ctx->d_primes, ca, B, log_n, st));
+        HIP_TRY(ctx, launch_copy_limbs(d + (size_t)lo * n, d_bs, ext.u() + ((size_t)j * ext_limbs + lo) * n, ext_bs, hi - lo, B,
+                                       log_n, st));
+        // batch entries of this digit are ext_bs apart
+        HIP_TRY(ctx, launch_ntt(ctx->tabs, log_n, ext.u() + (size_t)j * ext_limbs * n, ext_bs, (int)(B * ext_limbs), pm, st));
+    }
+
+    // 4. inner product with the key
+    HIP_TRY(ctx, launch_inner_product(ctx->d_primes, ext.u(), ext_bs, digits, l, K, L, key.data, total, acc.u(),
+                                      (u64)2 * ext_limbs * n, B, log_n, st));
+
+    // 5. mod-down: special limbs to coefficient form (pre-multiplied by (P/p_m)^-1), convert, transform, combine
+    u64 *mpost, *mpost_sh;
+    TRY(moddown_post(ctx, &mpost, &mpost_sh));
+    {
+        PolyMap pm = {};
+        pm.period = ext_limbs;
+        for (int x = 0; x < ext_limbs; x++) pm.prime_of[x] = x < l ? (int16_t)-1 : (int16_t)(L + x - l);
+        InttExtra ex2 = {};
+        ex2.post = mpost - l; ex2.post_sh = mpost_sh - l;  // entry x >= l reads post[x - l]
+        HIP_TRY(ctx, launch_intt(ctx->tabs, log_n, acc.u(), (u64)ext_limbs * n, (int)(B * 2 * ext_limbs), pm, &ex2, st));
+        ConvArgs ca = {};
+        ca.y = acc.u(); ca.y_bs = (u64)ext_limbs * n; ca.src_pos0 = l; ca.src_prime0 = L; ca.a = K;
+        ca.hat = ctx->moddown_tab->d_hat; ca.dmod = ctx->moddown_tab->d_dmod; ca.total = total;
+        ca.out = conv.u(); ca.out_bs = (u64)l * n; ca.n_targets = l;
+        for (int i = 0; i < l; i++) { ca.tgt_pos[i] = (int16_t)i; ca.tgt_prime[i] = (int16_t)i; }
+        HIP_TRY(ctx, launch_base_conv(ctx->d_primes, ca, B * 2, log_n, st));
+        HIP_TRY(ctx, launch_ntt(ctx->tabs, log_n, conv.u(), (u64)l * n, (int)(B * 2 * l), identity_map(l), st));
+    }
+    HIP_TRY(ctx, launch_moddown_final(ctx->d_primes, acc.u(), (u64)2 * ext_limbs * n, conv.u(), (u64)2 * l * n, ctx->d_pinv,
+                                      ctx->d_pinv_sh, add, add_bs, add_polys, add_galois, out, (u64)2 * l * n, l, K, B, log_n,
+                                      st));
+    return HISA_OK;
+}
+
+extern "C" int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n, int32_t steps, hisa_ct** out) {
+    if (!ctx || !out) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_batch_shape(ctx, in, n, 2));
+    const u64 g = galois_of(ctx, steps);
+    const int l = (int)in[0]->limbs;
+    if (g == 0) {  // rotation by a multiple of N/2: a copy, no key needed
+        TRY(alloc_ct_batch(ctx, n, 2, (uint32_t)l, 0.0, out));
+        for (size_t i = 0; i < n; i++) {
+            out[i]->scale = in[i]->scale;
+            HIP_TRY(ctx, hipMemcpyAsync(out[i]->data, in[i]->data, ct_words(ctx, 2, l) * sizeof(u64), hipMemcpyDeviceToDevice,
+                                        ctx->stream));
+        }
+        return HISA_OK;
+    }
+    auto it = ctx->keys.find(g);
+    if (it == ctx->keys.end()) return fail(ctx, HISA_ERR_NO_KEY, "no rotation key for %d slots (galois element %llu)", steps,
+                                           (unsigned long long)g);
+    BatchIn bi;
+    TRY(gather_batch(ctx, in, n, &bi));
+    const size_t nn = ctx->N, lw = (size_t)l * nn;
+    int rc = HISA_OK;
+    {
+        // sigma_g(c1) in NTT form (a gather); sigma_g(c0) is gathered inside the last kernel
+        Temp r1(ctx, n * lw * sizeof(u64));
+        if (!r1.ok()) rc = HISA_ERR_OOM;
+        if (rc == HISA_OK) {
+            hipError_t e = launch_automorph_ntt(bi.base + lw, bi.stride, r1.u(), lw, g, l, n, (int)ctx->log_n, ctx->stream);
+            if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "automorph: %s", hipGetErrorString(e));
+        }
+        if (rc == HISA_OK) rc = alloc_ct_batch(ctx, n, 2, (uint32_t)l, 0.0, out);
+        if (rc == HISA_OK) {
+            for (size_t i = 0; i < n; i++) out[i]->scale = in[i]->scale;
+            rc = key_switch_core(ctx, r1.u(), lw, n, l, it->second, bi.base, bi.stride, 1, g, out[0]->data);
+        }
+    }
+    dev_release(ctx, bi.tmp);
+    return rc;
+}
+
+extern "C" int hisa_rot_left(hisa_ctx* ctx, const hisa_ct* a, int32_t steps, hisa_ct** out) {
+    return hisa_rot_left_batch(ctx, &a, 1, steps, out);
+}
+
+extern "C" int hisa_rot_right(hisa_ctx* ctx, const hisa_ct* a, int32_t steps, hisa_ct** out) {
+    if (!ctx) return HISA_ERR_ARG;
+    const i64 slots = ctx->N / 2;
+    i64 r = (i64)steps % slots;
+    if (r < 0) r += slots;
+    return hisa_rot_left_batch(ctx, &a, 1, (int32_t)((slots - r) % slots), out);
+}
+
+extern "C" int hisa_rot_left_assign(hisa_ctx* ctx, hisa_ct* a, int32_t steps) {
+    hisa_ct* tmp = nullptr;
+    const hisa_ct* ca = a;
+    TRY(hisa_rot_left_batch(ctx, &ca, 1, steps, &tmp));
+    adopt(ctx, a, tmp);
+    return HISA_OK;
+}
+
+extern "C" int hisa_rot_right_assign(hisa_ctx* ctx, hisa_ct* a, int32_t steps) {
+    hisa_ct* tmp = nullptr;
+    TRY(hisa_rot_right(ctx, a, steps, &tmp));
+    adopt(ctx, a, tmp);
+    return HISA_OK;
+}
+
+extern "C" int hisa_relinearize_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n) {
+    if (!ctx) return HISA_ERR_ARG;
+    TRY(check_batch_shape(ctx, (const hisa_ct* const*)cts, n, 0));
+    if (cts[0]->polys == 2) return HISA_OK;
+    if (cts[0]->polys != 3) return fail(ctx, HISA_ERR_SIZE, "relinearize needs 2 or 3 polynomials");
+    auto it = ctx->keys.find(0);
+    if (it == ctx->keys.end()) return fail(ctx, HISA_ERR_NO_KEY, "no relinearisation key: call hisa_keygen");
+    const int l = (int)cts[0]->limbs;
+    const size_t lw = (size_t)l * ctx->N;
+    BatchIn bi;
+    TRY(gather_batch(ctx, (const hisa_ct* const*)cts, n, &bi));
+    std::vector<hisa_ct*> fresh(n);
+    int rc = alloc_ct_batch(ctx, n, 2, (uint32_t)l, 0.0, fresh.data());
+    if (rc == HISA_OK) {
+        rc = key_switch_core(ctx, bi.base + 2 * lw, bi.stride, n, l, it->second, bi.base, bi.stride, 2, 0, fresh[0]->data);
+        for (size_t i = 0; i < n; i++) {
+            fresh[i]->scale = cts[i]->scale;
+            if (rc == HISA_OK) adopt(ctx, cts[i], fresh[i]);
+            else hisa_free(ctx, fresh[i]);
+        }
+    }
+    dev_release(ctx, bi.tmp);
+    return rc;
+}
+
+extern "C" int hisa_relinearize(hisa_ctx* ctx, hisa_ct* ct) { return hisa_relinearize_batch(ctx, &ct, 1); }
+
+extern "C" int hisa_mul(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b, hisa_ct** out) {
+    if (!out) return fail(ctx, HISA_ERR_ARG, "null out");
+    TRY(hisa_mul_no_relin(ctx, a, b, out));
+    int rc = hisa_relinearize(ctx, *out);
+    if (rc != HISA_OK) { hisa_free(ctx, *out); *out = nullptr; }
+    return rc;
+}
+
+extern "C" int hisa_mul_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_ct* b) {
+    hisa_ct* tmp = nullptr;
+    TRY(hisa_mul(ctx, a, b, &tmp));
+    adopt(ctx, a, tmp);
+    return HISA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// division profile
+// ---------------------------------------------------------------------------
+extern "C" int hisa_max_scalar_div(hisa_ctx* ctx, const hisa_ct* ct, double ub, uint64_t* d) {
+    if (!ctx || !valid_ct(ct) || !d) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    *d = 1;
+    if (ct->limbs > 1 && (double)ctx->mod[ct->limbs - 1] < ub) *d = ctx->mod[ct->limbs - 1];
+    return HISA_OK;
+}
+
+extern "C" int hisa_rescale_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n) {
+    if (!ctx) return HISA_ERR_ARG;
+    TRY(check_batch_shape(ctx, (const hisa_ct* const*)cts, n, 0));
+    const int l = (int)cts[0]->limbs, polys = (int)cts[0]->polys;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "rescale of a one-limb ciphertext");
+    const size_t nn = ctx->N, n_bp = n * polys;
+    BatchIn bi;
+    TRY(gather_batch(ctx, (const hisa_ct* const*)cts, n, &bi));
+    int rc = HISA_OK;
+    std::vector<hisa_ct*> fresh(n);
+    {
+        Temp last(ctx, n_bp * nn * sizeof(u64));
+        Temp r(ctx, n_bp * (size_t)(l - 1) * nn * sizeof(u64));
+        if (!last.ok() || !r.ok()) rc = HISA_ERR_OOM;
+        if (rc == HISA_OK) rc = alloc_ct_batch(ctx, n, (uint32_t)polys, (uint32_t)(l - 1), 0.0, fresh.data());
+        if (rc == HISA_OK) {
+            hipError_t e;
+            PolyMap pm = {};
+            pm.period = l;
+            for (int i = 0; i < l; i++) pm.prime_of[i] = i == l - 1 ? (int16_t)(l - 1) : (int16_t)-1;
+            InttExtra ex = {};
+            ex.in = bi.base; ex.in_batch_stride = (u64)l * nn; ex.out_entry0 = l - 1;
+            e = launch_intt(ctx->tabs, (int)ctx->log_n, last.u(), nn, (int)(n_bp * l), pm, &ex, ctx->stream);
+            if (e == hipSuccess) e = launch_rescale_spread(ctx->d_primes, last.u(), r.u(), l, n_bp, (int)ctx->log_n, ctx->stream);
+            if (e == hipSuccess)
+                e = launch_ntt(ctx->tabs, (int)ctx->log_n, r.u(), (u64)(l - 1) * nn, (int)(n_bp * (l - 1)), identity_map(l - 1),
+                               ctx->stream);
+            u64 qlinv[HISA_MAX_Q], qlinv_sh[HISA_MAX_Q];
+            for (int i = 0; i < l - 1; i++) {
+                qlinv[i] = hm::inv(ctx->mod[l - 1] % ctx->mod[i], ctx->mod[i]);
+                qlinv_sh[i] = hm::shoup(qlinv[i], ctx->mod[i]);
+            }
+            if (e == hipSuccess)
+                e = launch_rescale_final(ctx->d_primes, bi.base, r.u(), qlinv, qlinv_sh, fresh[0]->data, l, n_bp, (int)ctx->log_n,
+                                         ctx->stream);
+            if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "rescale: %s", hipGetErrorString(e));
+            for (size_t i = 0; i < n; i++) {
+                fresh[i]->scale = cts[i]->scale / (double)ctx->mod[l - 1];
+                if (rc == HISA_OK) adopt(ctx, cts[i], fresh[i]);
+                else hisa_free(ctx, fresh[i]);
+            }
+        }
+    }
+    dev_release(ctx, bi.tmp);
+    return rc;
+}
+
+extern "C" int hisa_rescale(hisa_ctx* ctx, hisa_ct* ct) { return hisa_rescale_batch(ctx, &ct, 1); }
+
+extern "C" int hisa_div_scalar(hisa_ctx* ctx, hisa_ct* ct, uint64_t d) {
+    if (!ctx || !valid_ct(ct)) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    if (d == 1) return HISA_OK;
+    if (ct->limbs < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "no modulus left to divide by");
+    if (d != ctx->mod[ct->limbs - 1])
+        return fail(ctx, HISA_ERR_BAD_DIVISOR, "divisor %llu is not the last modulus %llu", (unsigned long long)d,
+                    (unsigned long long)ctx->mod[ct->limbs - 1]);
+    return hisa_rescale(ctx, ct);
+}
+
+// ---------------------------------------------------------------------------
+// parity / debug surface
+// ---------------------------------------------------------------------------
+extern "C" int hisa_get_primes(hisa_ctx* ctx, uint64_t* q, uint64_t* p) {
+    if (!ctx) return HISA_ERR_ARG;
+    if (q) for (uint32_t i = 0; i < ctx->L; i++) q[i] = ctx->mod[i];
+    if (p) for (uint32_t i = 0; i < ctx->K; i++) p[i] = ctx->mod[ctx->L + i];
+    return HISA_OK;
+}
+
+extern "C" int hisa_get_alpha(hisa_ctx* ctx, uint32_t* alpha) {
+    if (!ctx || !alpha) return HISA_ERR_ARG;
+    *alpha = ctx->alpha;
+    return HISA_OK;
+}
+
+extern "C" int hisa_ct_info(const hisa_ct* ct, uint32_t* limbs, uint32_t* polys, double* scale) {
+    if (!valid_ct(ct)) return HISA_ERR_ARG;
+    if (limbs) *limbs = ct->limbs;
+    if (polys) *polys = ct->polys;
+    if (scale) *scale = ct->scale;
+    return HISA_OK;
+}
+
+extern "C" int hisa_ct_device_ptr(const hisa_ct* ct, uint64_t** dev) {
+    if (!valid_ct(ct) || !dev) return HISA_ERR_ARG;
+    *dev = ct->data;
+    return HISA_OK;
+}
+
+extern "C" int hisa_ct_export(hisa_ctx* ctx, const hisa_ct* ct, uint64_t* host) {
+    if (!ctx || !valid_ct(ct) || !host) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    const size_t words = ct_words(ctx, ct->polys, ct->limbs);
+    Temp co(ctx, words * sizeof(u64));
+    if (!co.ok()) return HISA_ERR_OOM;
+    InttExtra ex = {};
+    ex.in = ct->data; ex.in_batch_stride = (u64)ct->limbs * ctx->N;
+    HIP_TRY(ctx, launch_intt(ctx->tabs, (int)ctx->log_n, co.u(), (u64)ct->limbs * ctx->N, (int)(ct->polys * ct->limbs),
+                             identity_map((int)ct->limbs), &ex, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(host, co.u(), words * sizeof(u64), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_ct_import_batch(hisa_ctx* ctx, const uint64_t* host, size_t n, uint32_t polys, uint32_t limbs,
+                                    double scale, hisa_ct** out) {
+    if (!ctx || !host || !out || n == 0 || polys < 1 || polys > 3 || limbs < 1 || limbs > ctx->L)
+        return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(alloc_ct_batch(ctx, n, polys, limbs, scale, out));
+    const size_t words = n * ct_words(ctx, polys, limbs);
+    HIP_TRY(ctx, hipMemcpyAsync(out[0]->data, host, words * sizeof(u64), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, out[0]->data, (u64)limbs * ctx->N, (int)(n * polys * limbs),
+                            identity_map((int)limbs), ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_ct_import(hisa_ctx* ctx, const uint64_t* host, uint32_t polys, uint32_t limbs, double scale,
+                              hisa_ct** out) {
+    return hisa_ct_import_batch(ctx, host, 1, polys, limbs, scale, out);
+}
+
+extern "C" int hisa_ct_random_batch(hisa_ctx* ctx, size_t n, uint32_t limbs, double scale, uint64_t counter, hisa_ct** out) {
+    if (!ctx || !out || n == 0 || limbs < 1 || limbs > ctx->L) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(alloc_ct_batch(ctx, n, 2, limbs, scale, out));
+    // every (ciphertext, polynomial) pair is one batch entry with its own stream counter
+    HIP_TRY(ctx, launch_sample_uniform(ctx->d_primes, ctx->prm.seed, 2, counter, identity_map((int)limbs), (int)(n * 2 * limbs),
+                                       (u64)limbs * ctx->N, 1, out[0]->data, (int)ctx->log_n, ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_ntt_raw(hisa_ctx* ctx, uint64_t* dev_buf, uint32_t prime_index, size_t n_polys, int inverse) {
+    if (!ctx || !dev_buf || prime_index >= ctx->total || n_polys == 0 || n_polys > (1u << 20))
+        return fail(ctx, HISA_ERR_ARG, "bad argument");
+    PolyMap pm = {};
+    pm.period = 1;
+    pm.prime_of[0] = (int16_t)prime_index;
+    if (inverse) HIP_TRY(ctx, launch_intt(ctx->tabs, (int)ctx->log_n, dev_buf, ctx->N, (int)n_polys, pm, nullptr, ctx->stream));
+    else HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, dev_buf, ctx->N, (int)n_polys, pm, ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_key_export(hisa_ctx* ctx, uint64_t key_id, uint64_t* host) {
+    if (!ctx || !host) return HISA_ERR_ARG;
+    auto it = ctx->keys.find(key_id);
+    if (it == ctx->keys.end()) return fail(ctx, HISA_ERR_NO_KEY, "no key %llu", (unsigned long long)key_id);
+    const size_t words = (size_t)ctx->dnum * 2 * ctx->total * ctx->N;
+    HIP_TRY(ctx, hipMemcpyAsync(host, it->second.data, words * sizeof(u64), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_secret_export(hisa_ctx* ctx, int64_t* host_coeffs) {
+    if (!ctx || !host_coeffs) return HISA_ERR_ARG;
+    Temp raw(ctx, ctx->N * sizeof(i64));
+    Temp scratch(ctx, ctx->N * sizeof(u64));
+    if (!raw.ok() || !scratch.ok()) return HISA_ERR_OOM;
+    PolyMap one = identity_map(1);
+    HIP_TRY(ctx, launch_sample_small(ctx->d_primes, ctx->prm.seed, 1, 0, 0, 1, one, 1, 0, 0, scratch.u(), raw.as<i64>(),
+                                     (int)ctx->log_n, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(host_coeffs, raw.blk->ptr, ctx->N * sizeof(i64), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HISA_OK;
+}

@@ -1,0 +1,199 @@
+// Internal declarations shared by the translation units of libhisa.
+// Host orchestration lives in hisa_api.hip; every arithmetic step runs in the
+// kernels declared here (launch wrappers take plain pointers and sizes).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <map>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/hisa.h"
+
+typedef uint64_t u64;
+typedef int64_t i64;
+typedef unsigned __int128 u128;
+
+// Per-prime constants, one entry per prime q_0..q_{L-1}, p_0..p_{K-1}, device resident.
+struct PrimeConst {
+    u64 q;
+    u64 r1, r0;        // floor(2^128 / q)
+    u64 n_inv, n_inv_sh; // N^-1 mod q and its Shoup companion
+    u64 half;          // floor(q / 2)
+};
+
+// Device pointers to the per-prime tables, [prime][N] each.
+struct NttTables {
+    const PrimeConst* primes;
+    const u64* tw;     // psi^bitrev(i)
+    const u64* tw_sh;  // Shoup companions
+    const u64* itw;    // psi^-bitrev(i)
+    const u64* itw_sh;
+};
+
+// Which polynomials a batched NTT launch touches: polynomial p (0 <= p <
+// n_polys) sits at base + (p / period) * batch_stride + (p % period) * N and
+// is transformed modulo prime prime_of[p % period]; a negative entry skips it.
+#define HISA_MAX_PERIOD 256
+struct PolyMap {
+    int32_t period;
+    int16_t prime_of[HISA_MAX_PERIOD];
+};
+
+// Optional extras of an inverse transform.
+struct InttExtra {
+    const u64* in;          // read from here instead of data (same PolyMap addressing with in_batch_stride); may be null
+    u64 in_batch_stride;
+    u64 galois;             // != 0: input index i reads the element that sigma_g moves to i (NTT-form automorphism)
+    const u64* post;        // per period entry: final factor replacing N^-1 (already multiplied by N^-1), may be null
+    const u64* post_sh;
+    int out_entry0;         // output polynomial of entry e sits at (e - out_entry0) * N within its batch slot
+};
+
+// One fast base conversion: source primes src[0..a), all primes as targets.
+struct ConvTable {
+    int a;
+    int src[HISA_MAX_Q];
+    u64* d_inv_hat;     // [a]   (D/c_i)^-1 mod c_i
+    u64* d_inv_hat_sh;  // [a]
+    u64* d_hat;         // [a][total]  (D/c_i) mod t
+    u64* d_dmod;        // [total]     D mod t
+    std::vector<u64> inv_hat; // host copy
+};
+
+struct DevBlock {
+    void* ptr;
+    size_t bytes;
+    int refs;
+};
+
+#define HISA_MAGIC_CT 0x43544631u
+#define HISA_MAGIC_PT 0x50544631u
+
+struct hisa_ct {
+    uint32_t magic;
+    DevBlock* blk;
+    u64* data;  // [polys][limbs][N], NTT form
+    uint32_t polys, limbs;
+    double scale;
+};
+
+struct hisa_pt {
+    uint32_t magic;
+    DevBlock* blk;
+    u64* data;  // [limbs][N], NTT form
+    uint32_t limbs;
+    double scale;
+};
+
+struct SwitchKey {
+    DevBlock* blk;
+    u64* data;  // [dnum][2][total][N]: b then a, NTT form
+};
+
+struct hisa_ctx {
+    hisa_params prm;
+    uint32_t log_n, N, L, K, alpha, dnum, total;
+    hipStream_t stream;
+    std::vector<u64> mod, psi;  // q_0..q_{L-1}, p_0..p_{K-1}
+    std::vector<PrimeConst> pc;
+    PrimeConst* d_primes;
+    u64 *d_tw, *d_tw_sh, *d_itw, *d_itw_sh;
+    NttTables tabs;
+    u64* d_secret;  // [total][N], NTT form
+    std::map<u64, SwitchKey> keys;  // 0: relinearisation, else Galois element
+    std::map<u64, SwitchKey> aux;   // small derived device tables, built on first use
+    std::map<std::pair<int, int>, ConvTable> modup_tabs;  // (digit, size)
+    ConvTable* moddown_tab;
+    u64* d_pinv;      // [L] P^-1 mod q_i
+    u64* d_pinv_sh;
+    u64* d_pmod;      // [L] P mod q_i
+    double *d_cos, *d_sin;  // [2N] roots of unity exp(i*pi*t/N)
+    std::unordered_map<size_t, std::vector<void*>> pool;
+    size_t pool_bytes;
+    u64 enc_counter;
+    std::string err;
+};
+
+// ---- launch wrappers (every one enqueues on `st` and returns hipGetLastError) ----
+hipError_t launch_ntt(const NttTables& t, int log_n, u64* data, u64 batch_stride, int n_polys, const PolyMap& map,
+                      hipStream_t st);
+hipError_t launch_intt(const NttTables& t, int log_n, u64* data, u64 batch_stride, int n_polys, const PolyMap& map,
+                       const InttExtra* extra, hipStream_t st);
+
+// sampling (counter-based generator, both sides of the parity tests implement it)
+hipError_t launch_sample_uniform(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, const PolyMap& map, int n_polys,
+                                 u64 batch_stride, u64 ctr_step, u64* out, int log_n, hipStream_t st);
+hipError_t launch_sample_small(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, int noise_on, int ternary,
+                               const PolyMap& map, int n_polys, u64 batch_stride, u64 ctr_step, u64* out, i64* raw,
+                               int log_n, hipStream_t st);
+
+// element-wise kernels over [batch][polys][limbs][N]
+enum ElemOp { OP_ADD = 0, OP_SUB = 1 };
+hipError_t launch_addsub(const PrimeConst* primes, const u64* a, const u64* b, u64* out, int op, int limbs, int polys_a,
+                         int polys_b, u64 n_batch, u64 a_bs, u64 b_bs, u64 o_bs, int log_n, hipStream_t st);
+hipError_t launch_add_const(const PrimeConst* primes, const u64* a, u64* out, const u64* consts, int op, int limbs,
+                            int polys, int log_n, hipStream_t st);
+hipError_t launch_mul_plain(const PrimeConst* primes, const u64* a, const u64* pt, u64* out, int limbs, int polys,
+                            u64 n_batch, u64 a_bs, u64 o_bs, int log_n, hipStream_t st);
+hipError_t launch_mul_const(const PrimeConst* primes, const u64* a, u64* out, const u64* consts, int limbs, int polys,
+                            int log_n, hipStream_t st);
+hipError_t launch_mul_no_relin(const PrimeConst* primes, const u64* a, const u64* b, u64* out, int limbs, u64 n_batch,
+                               u64 a_bs, u64 b_bs, u64 o_bs, int log_n, hipStream_t st);
+hipError_t launch_encrypt_combine(const PrimeConst* primes, const u64* secret, const u64* pt, const u64* e, u64* ct,
+                                  int limbs, u64 n_batch, u64 pt_bs, int log_n, hipStream_t st);
+hipError_t launch_decrypt(const PrimeConst* primes, const u64* secret, const u64* ct, u64* pt, int limbs, int polys,
+                          int log_n, hipStream_t st);
+hipError_t launch_key_combine(const PrimeConst* primes, const u64* secret, const u64* target, const u64* e,
+                              const u64* pmod_all, u64* key_digit, int total, int L, int alpha, int digit, int log_n,
+                              hipStream_t st);
+hipError_t launch_pointwise_square(const PrimeConst* primes, const u64* s, u64* out, int total, int log_n, hipStream_t st);
+hipError_t launch_automorph_ntt(const u64* in, u64 in_bs, u64* out, u64 out_bs, u64 galois, int n_polys, u64 n_batch,
+                                int log_n, hipStream_t st);
+hipError_t launch_reduce_i64(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs, int log_n, hipStream_t st);
+
+// Fast base conversion (centred): for every batch entry and target,
+//   out[target] = ( sum_i y[src_pos0+i] * hat[i][prime(target)]  -  #{i : y_i > c_i/2} * D ) mod t
+// with y_i the source residues already multiplied by (D/c_i)^-1 mod c_i.
+struct ConvArgs {
+    const u64* y;      // [batch][..][N], coefficient form
+    u64 y_bs;
+    int src_pos0;      // first source limb position inside a batch entry of y
+    int src_prime0;    // its prime index
+    int a;             // number of source limbs
+    const u64* hat;    // [a][total]
+    const u64* dmod;   // [total]
+    int total;
+    u64* out;          // [batch][..][N]
+    u64 out_bs;
+    int n_targets;
+    int16_t tgt_pos[HISA_MAX_PRIMES];   // limb position inside a batch entry of out
+    int16_t tgt_prime[HISA_MAX_PRIMES];
+};
+hipError_t launch_base_conv(const PrimeConst* primes, const ConvArgs& args, u64 n_batch, int log_n, hipStream_t st);
+
+// acc[b][p][x] = sum_j ext[b][j][x] * key[j][p][prime(x)], x over l + K limbs (prime(x) = x for x < l, L + x - l above)
+hipError_t launch_inner_product(const PrimeConst* primes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
+                                const u64* key, int total, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st);
+// out[b][p][i] = (acc[b][p][i] - conv[b][p][i]) * P^-1 + add[b][p][i]   (p < add_polys; through sigma_g if galois != 0)
+hipError_t launch_moddown_final(const PrimeConst* primes, const u64* acc, u64 acc_bs, const u64* conv, u64 conv_bs,
+                                const u64* pinv, const u64* pinv_sh, const u64* add, u64 add_bs, int add_polys, u64 galois,
+                                u64* out, u64 out_bs, int l, int K, u64 n_batch, int log_n, hipStream_t st);
+hipError_t launch_copy_limbs(const u64* src, u64 src_bs, u64* dst, u64 dst_bs, int limbs, u64 n_batch, int log_n,
+                             hipStream_t st);
+
+// rescale pieces: r[bp][i] = centred remainder of the last limb modulo q_i; out = (ct - NTT(r)) * q_last^-1
+hipError_t launch_rescale_spread(const PrimeConst* primes, const u64* last, u64* r, int l, u64 n_bp, int log_n,
+                                 hipStream_t st);
+hipError_t launch_rescale_final(const PrimeConst* primes, const u64* ct, const u64* r, const u64* qlinv, const u64* qlinv_sh,
+                                u64* out, int l, u64 n_bp, int log_n, hipStream_t st);
+
+// encode / decode
+hipError_t launch_encode(const double* cs, const double* sn, const double* re, const double* im, int count, double factor,
+                         i64* coeffs, int log_n, hipStream_t st);
+hipError_t launch_crt_to_double(const PrimeConst* primes, const u64* coeff_form, int limbs, const u64* garner_inv,
+                                const u64* garner_inv_sh, int L, double inv_scale, double* out, int log_n, hipStream_t st);
+hipError_t launch_decode(const double* cs, const double* sn, const double* m, int count, double* re, double* im, int log_n,
+                         hipStream_t st);

@@ -1,0 +1,370 @@
+"""Thin Python binding of libhisa (argument marshalling only).
+
+Every method forwards to the C-ABI entry point of the same name in
+``include/hisa.h``; all arithmetic runs in the HIP kernels of the library.
+PyTorch is used for what it is good at here: the HIP stream the work is
+enqueued on and raw device buffers for ``ntt_raw``.  There is no CPU fallback:
+loading fails loudly when the library has not been built, and creating a
+context fails when there is no GPU.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhisa.so")
+
+MAX_Q = 48
+CONV_SCALAR, CONV_MASKED, CONV_PLAIN = 0, 1, 2
+
+ERRORS = {0: "OK", -1: "ARG", -2: "LEVEL_MISMATCH", -3: "SCALE_MISMATCH", -4: "NO_KEY", -5: "BAD_DIVISOR",
+          -6: "DEPTH_EXHAUSTED", -7: "OOM", -8: "HIP", -9: "SIZE"}
+
+
+class HisaError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("HISA_ERR_%s (%d): %s" % (ERRORS.get(code, "?"), code, msg))
+        self.code = code
+
+
+class Params(C.Structure):
+    _fields_ = [("log_n", C.c_uint32), ("num_q", C.c_uint32), ("q_bits", C.c_uint32 * MAX_Q), ("dnum", C.c_uint32),
+                ("special_bits", C.c_uint32), ("noise", C.c_uint32), ("seed", C.c_uint64)]
+
+
+class TensorStruct(C.Structure):
+    _fields_ = [("batch", C.c_uint32), ("channels", C.c_uint32), ("height", C.c_uint32), ("width", C.c_uint32),
+                ("h_stride", C.c_uint32), ("w_stride", C.c_uint32), ("offset", C.c_uint32), ("clean", C.c_uint32),
+                ("cts", C.POINTER(C.c_void_p))]
+
+
+class ConvGeom(C.Structure):
+    _fields_ = [("fh", C.c_uint32), ("fw", C.c_uint32), ("stride", C.c_uint32), ("pad_same", C.c_uint32),
+                ("mode", C.c_uint32)]
+
+
+_lib = None
+
+
+def load():
+    """dlopen libhisa.so; raises if it was not built (python -m paper_1810_00845_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libhisa.so is missing: build it with `python -m paper_1810_00845_amd.build`; "
+                              "there is no CPU fallback")
+        # PyTorch ships its own HIP runtime; import it first so that libhisa binds to that same
+        # runtime (streams and device pointers are only valid within one runtime instance).
+        import torch  # noqa: F401
+        _lib = C.CDLL(LIB_PATH)
+        _lib.hisa_last_error.restype = C.c_char_p
+        _lib.hisa_last_error.argtypes = [C.c_void_p]
+    return _lib
+
+
+def _dp(a):
+    return a.ctypes.data_as(C.POINTER(C.c_double)) if a is not None else None
+
+
+class _Handle:
+    __slots__ = ("ctx", "h")
+
+    def __init__(self, ctx, h):
+        self.ctx, self.h = ctx, h
+
+    def free(self):
+        if self.h and self.ctx._h:
+            load().hisa_free(C.c_void_p(self.ctx._h), C.c_void_p(self.h))
+        self.h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+class Plaintext(_Handle):
+    @property
+    def limbs(self):
+        l = C.c_uint32()
+        self.ctx._ck(load().hisa_pt_info(C.c_void_p(self.h), C.byref(l), None))
+        return l.value
+
+    @property
+    def scale(self):
+        s = C.c_double()
+        self.ctx._ck(load().hisa_pt_info(C.c_void_p(self.h), None, C.byref(s)))
+        return s.value
+
+
+class Ciphertext(_Handle):
+    def info(self):
+        l, p, s = C.c_uint32(), C.c_uint32(), C.c_double()
+        self.ctx._ck(load().hisa_ct_info(C.c_void_p(self.h), C.byref(l), C.byref(p), C.byref(s)))
+        return l.value, p.value, s.value
+
+    @property
+    def limbs(self):
+        return self.info()[0]
+
+    @property
+    def polys(self):
+        return self.info()[1]
+
+    @property
+    def scale(self):
+        return self.info()[2]
+
+
+class Context:
+    """One parameter set on one GPU (see hisa_create)."""
+
+    def __init__(self, log_n, q_bits, dnum, special_bits, seed, noise=True, stream=None):
+        lib = load()
+        prm = Params()
+        prm.log_n, prm.num_q, prm.dnum = log_n, len(q_bits), dnum
+        for i, b in enumerate(q_bits):
+            prm.q_bits[i] = b
+        prm.special_bits, prm.noise, prm.seed = special_bits, 1 if noise else 0, seed
+        if stream is None:
+            import torch
+            if not torch.cuda.is_available():
+                raise HisaError(-8, "no GPU visible to PyTorch; libhisa has no CPU fallback")
+            stream = torch.cuda.current_stream().cuda_stream
+        self._h = None
+        h = C.c_void_p()
+        rc = lib.hisa_create(C.byref(prm), C.c_void_p(stream), C.byref(h))
+        if rc != 0:
+            msg = lib.hisa_last_error(h).decode() if h.value else "hisa_create failed"
+            if h.value:
+                lib.hisa_destroy(h)
+            raise HisaError(rc, msg)
+        self._h = h.value
+        self.log_n, self.N, self.slots = log_n, 1 << log_n, 1 << (log_n - 1)
+        self.L, self.dnum = len(q_bits), dnum
+        a = C.c_uint32()
+        self._ck(lib.hisa_get_alpha(self._vp, C.byref(a)))
+        self.alpha = self.K = a.value
+        q = (C.c_uint64 * self.L)()
+        p = (C.c_uint64 * self.K)()
+        self._ck(lib.hisa_get_primes(self._vp, q, p))
+        self.primes = [int(x) for x in q] + [int(x) for x in p]
+
+    @property
+    def _vp(self):
+        return C.c_void_p(self._h)
+
+    def _ck(self, rc):
+        if rc != 0:
+            raise HisaError(rc, load().hisa_last_error(self._vp).decode())
+
+    def close(self):
+        if self._h:
+            load().hisa_destroy(self._vp)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def sync(self):
+        self._ck(load().hisa_sync(self._vp))
+
+    # ---- keys ----
+    def keygen(self):
+        self._ck(load().hisa_keygen(self._vp))
+
+    def gen_rot_keys(self, left_steps):
+        arr = (C.c_int32 * len(left_steps))(*[int(s) for s in left_steps])
+        self._ck(load().hisa_gen_rot_keys(self._vp, arr, C.c_size_t(len(left_steps))))
+
+    def galois_elt(self, steps):
+        g = C.c_uint64()
+        self._ck(load().hisa_galois_elt(self._vp, C.c_int32(steps), C.byref(g)))
+        return g.value
+
+    # ---- plaintexts ----
+    def _new_pt(self, h):
+        return Plaintext(self, h.value)
+
+    def _new_ct(self, h):
+        return Ciphertext(self, h if isinstance(h, int) else h.value)
+
+    def encode(self, values, scale, limbs):
+        v = np.asarray(values)
+        re = np.ascontiguousarray(v.real, dtype=np.float64)
+        im = np.ascontiguousarray(v.imag, dtype=np.float64) if np.iscomplexobj(v) else None
+        h = C.c_void_p()
+        self._ck(load().hisa_encode(self._vp, _dp(re), _dp(im), C.c_size_t(len(re)), C.c_double(scale),
+                                    C.c_uint32(limbs), C.byref(h)))
+        return self._new_pt(h)
+
+    def decode(self, pt, count=None):
+        count = self.slots if count is None else count
+        re, im = np.zeros(count), np.zeros(count)
+        self._ck(load().hisa_decode(self._vp, C.c_void_p(pt.h), _dp(re), _dp(im), C.c_size_t(count)))
+        return re + 1j * im
+
+    def pt_from_coeffs(self, coeffs, scale, limbs):
+        a = np.ascontiguousarray(coeffs, dtype=np.int64)
+        assert a.shape == (self.N,)
+        h = C.c_void_p()
+        self._ck(load().hisa_pt_from_coeffs(self._vp, a.ctypes.data_as(C.POINTER(C.c_int64)), C.c_double(scale),
+                                            C.c_uint32(limbs), C.byref(h)))
+        return self._new_pt(h)
+
+    def pt_export(self, pt):
+        out = np.zeros((pt.limbs, self.N), dtype=np.uint64)
+        self._ck(load().hisa_pt_export(self._vp, C.c_void_p(pt.h), out.ctypes.data_as(C.POINTER(C.c_uint64))))
+        return out
+
+    # ---- encryption profile ----
+    def encrypt(self, pt):
+        h = C.c_void_p()
+        self._ck(load().hisa_encrypt(self._vp, C.c_void_p(pt.h), C.byref(h)))
+        return self._new_ct(h)
+
+    def encrypt_batch(self, pts):
+        n = len(pts)
+        arr = (C.c_void_p * n)(*[p.h for p in pts])
+        out = (C.c_void_p * n)()
+        self._ck(load().hisa_encrypt_batch(self._vp, arr, C.c_size_t(n), out))
+        return [self._new_ct(int(out[i])) for i in range(n)]
+
+    def set_enc_counter(self, c):
+        self._ck(load().hisa_set_enc_counter(self._vp, C.c_uint64(c)))
+
+    def decrypt(self, ct):
+        h = C.c_void_p()
+        self._ck(load().hisa_decrypt(self._vp, C.c_void_p(ct.h), C.byref(h)))
+        return self._new_pt(h)
+
+    def copy(self, ct):
+        h = C.c_void_p()
+        self._ck(load().hisa_copy(self._vp, C.c_void_p(ct.h), C.byref(h)))
+        return self._new_ct(h)
+
+    # ---- generic call helpers ----
+    def _out(self, fn, *args):
+        h = C.c_void_p()
+        self._ck(getattr(load(), fn)(self._vp, *args, C.byref(h)))
+        return self._new_ct(h)
+
+    def _inplace(self, fn, *args):
+        self._ck(getattr(load(), fn)(self._vp, *args))
+
+    def add(self, a, b): return self._out("hisa_add", C.c_void_p(a.h), C.c_void_p(b.h))
+    def sub(self, a, b): return self._out("hisa_sub", C.c_void_p(a.h), C.c_void_p(b.h))
+    def add_assign(self, a, b): self._inplace("hisa_add_assign", C.c_void_p(a.h), C.c_void_p(b.h))
+    def sub_assign(self, a, b): self._inplace("hisa_sub_assign", C.c_void_p(a.h), C.c_void_p(b.h))
+    def add_plain(self, a, p): return self._out("hisa_add_plain", C.c_void_p(a.h), C.c_void_p(p.h))
+    def sub_plain(self, a, p): return self._out("hisa_sub_plain", C.c_void_p(a.h), C.c_void_p(p.h))
+    def add_plain_assign(self, a, p): self._inplace("hisa_add_plain_assign", C.c_void_p(a.h), C.c_void_p(p.h))
+    def sub_plain_assign(self, a, p): self._inplace("hisa_sub_plain_assign", C.c_void_p(a.h), C.c_void_p(p.h))
+    def add_scalar(self, a, x): return self._out("hisa_add_scalar", C.c_void_p(a.h), C.c_double(x))
+    def sub_scalar(self, a, x): return self._out("hisa_sub_scalar", C.c_void_p(a.h), C.c_double(x))
+    def add_scalar_assign(self, a, x): self._inplace("hisa_add_scalar_assign", C.c_void_p(a.h), C.c_double(x))
+    def sub_scalar_assign(self, a, x): self._inplace("hisa_sub_scalar_assign", C.c_void_p(a.h), C.c_double(x))
+    def mul(self, a, b): return self._out("hisa_mul", C.c_void_p(a.h), C.c_void_p(b.h))
+    def mul_assign(self, a, b): self._inplace("hisa_mul_assign", C.c_void_p(a.h), C.c_void_p(b.h))
+    def mul_no_relin(self, a, b): return self._out("hisa_mul_no_relin", C.c_void_p(a.h), C.c_void_p(b.h))
+    def relinearize(self, a): self._inplace("hisa_relinearize", C.c_void_p(a.h))
+    def mul_plain(self, a, p): return self._out("hisa_mul_plain", C.c_void_p(a.h), C.c_void_p(p.h))
+    def mul_plain_assign(self, a, p): self._inplace("hisa_mul_plain_assign", C.c_void_p(a.h), C.c_void_p(p.h))
+
+    def mul_scalar(self, a, x, x_scale):
+        return self._out("hisa_mul_scalar", C.c_void_p(a.h), C.c_double(x), C.c_double(x_scale))
+
+    def mul_scalar_assign(self, a, x, x_scale):
+        self._inplace("hisa_mul_scalar_assign", C.c_void_p(a.h), C.c_double(x), C.c_double(x_scale))
+
+    def rot_left(self, a, steps): return self._out("hisa_rot_left", C.c_void_p(a.h), C.c_int32(steps))
+    def rot_right(self, a, steps): return self._out("hisa_rot_right", C.c_void_p(a.h), C.c_int32(steps))
+    def rot_left_assign(self, a, steps): self._inplace("hisa_rot_left_assign", C.c_void_p(a.h), C.c_int32(steps))
+    def rot_right_assign(self, a, steps): self._inplace("hisa_rot_right_assign", C.c_void_p(a.h), C.c_int32(steps))
+
+    def max_scalar_div(self, a, ub):
+        d = C.c_uint64()
+        self._ck(load().hisa_max_scalar_div(self._vp, C.c_void_p(a.h), C.c_double(ub), C.byref(d)))
+        return d.value
+
+    def div_scalar(self, a, d): self._inplace("hisa_div_scalar", C.c_void_p(a.h), C.c_uint64(d))
+    def rescale(self, a): self._inplace("hisa_rescale", C.c_void_p(a.h))
+
+    # ---- batched forms ----
+    @staticmethod
+    def _harr(cts):
+        return (C.c_void_p * len(cts))(*[c.h for c in cts])
+
+    def _batch_out(self, fn, n, *args):
+        out = (C.c_void_p * n)()
+        self._ck(getattr(load(), fn)(self._vp, *args, out))
+        return [self._new_ct(int(out[i])) for i in range(n)]
+
+    def rot_left_batch(self, cts, steps):
+        return self._batch_out("hisa_rot_left_batch", len(cts), self._harr(cts), C.c_size_t(len(cts)), C.c_int32(steps))
+
+    def add_batch(self, a, b):
+        return self._batch_out("hisa_add_batch", len(a), self._harr(a), self._harr(b), C.c_size_t(len(a)))
+
+    def mul_plain_batch(self, a, p):
+        return self._batch_out("hisa_mul_plain_batch", len(a), self._harr(a), C.c_void_p(p.h), C.c_size_t(len(a)))
+
+    def mul_no_relin_batch(self, a, b):
+        return self._batch_out("hisa_mul_no_relin_batch", len(a), self._harr(a), self._harr(b), C.c_size_t(len(a)))
+
+    def relinearize_batch(self, cts):
+        self._ck(load().hisa_relinearize_batch(self._vp, self._harr(cts), C.c_size_t(len(cts))))
+
+    def rescale_batch(self, cts):
+        self._ck(load().hisa_rescale_batch(self._vp, self._harr(cts), C.c_size_t(len(cts))))
+
+    def ct_random_batch(self, n, limbs, scale, counter):
+        return self._batch_out("hisa_ct_random_batch", n, C.c_size_t(n), C.c_uint32(limbs), C.c_double(scale),
+                               C.c_uint64(counter))
+
+    # ---- parity / debug surface ----
+    def ct_export(self, ct):
+        l, p, _ = ct.info()
+        out = np.zeros((p, l, self.N), dtype=np.uint64)
+        self._ck(load().hisa_ct_export(self._vp, C.c_void_p(ct.h), out.ctypes.data_as(C.POINTER(C.c_uint64))))
+        return out
+
+    def ct_import(self, coeff, scale):
+        a = np.ascontiguousarray(coeff, dtype=np.uint64)
+        h = C.c_void_p()
+        self._ck(load().hisa_ct_import(self._vp, a.ctypes.data_as(C.POINTER(C.c_uint64)), C.c_uint32(a.shape[0]),
+                                       C.c_uint32(a.shape[1]), C.c_double(scale), C.byref(h)))
+        return self._new_ct(h)
+
+    def ct_import_batch(self, coeff, scale):
+        a = np.ascontiguousarray(coeff, dtype=np.uint64)
+        n = a.shape[0]
+        out = (C.c_void_p * n)()
+        self._ck(load().hisa_ct_import_batch(self._vp, a.ctypes.data_as(C.POINTER(C.c_uint64)), C.c_size_t(n),
+                                             C.c_uint32(a.shape[1]), C.c_uint32(a.shape[2]), C.c_double(scale), out))
+        return [self._new_ct(int(out[i])) for i in range(n)]
+
+    def ntt_raw(self, dev_tensor, prime_index, inverse=False):
+        """In-place transform of a contiguous int64 CUDA tensor [n_polys, N] (bit pattern = uint64)."""
+        assert dev_tensor.is_cuda and dev_tensor.is_contiguous() and dev_tensor.element_size() == 8
+        assert dev_tensor.shape[-1] == self.N
+        n_polys = dev_tensor.numel() // self.N
+        self._ck(load().hisa_ntt_raw(self._vp, C.c_void_p(dev_tensor.data_ptr()), C.c_uint32(prime_index),
+                                     C.c_size_t(n_polys), C.c_int(1 if inverse else 0)))
+
+    def key_export(self, key_id):
+        out = np.zeros((self.dnum, 2, self.L + self.K, self.N), dtype=np.uint64)
+        self._ck(load().hisa_key_export(self._vp, C.c_uint64(key_id), out.ctypes.data_as(C.POINTER(C.c_uint64))))
+        return out
+
+    def secret_export(self):
+        out = np.zeros(self.N, dtype=np.int64)
+        self._ck(load().hisa_secret_export(self._vp, out.ctypes.data_as(C.POINTER(C.c_int64))))
+        return out

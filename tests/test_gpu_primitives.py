@@ -1,0 +1,271 @@
+"""GPU parity: every HISA primitive through the C ABI against the CPU oracle.
+
+Integer work is compared bit for bit in coefficient form on identical seeded
+inputs; encode/decode (fp64) within the tolerances derived in the design doc.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+PARAMS = {
+    # name: (log_n, q_bits, dnum, special_bits, seed)
+    "n10_a1": (10, [30, 30, 30], 3, 60, 11),          # single-launch NTT, alpha = 1, mixed prime sizes
+    "n12_a2": (12, [50, 40, 45, 50, 36], 3, 55, 12),  # two-launch NTT, alpha = 2, ragged last digit
+    "n13_d1": (13, [55, 50, 50, 50], 1, 58, 13),      # dnum = 1: alpha = 4 special primes
+}
+
+
+@pytest.fixture(scope="module", params=list(PARAMS))
+def pair(request):
+    from oracle import Oracle
+    from paper_1810_00845_amd import hisa
+    log_n, q_bits, dnum, sb, seed = PARAMS[request.param]
+    print("[case]", request.param, flush=True)
+    g = hisa.Context(log_n, q_bits, dnum, sb, seed)
+    o = Oracle(log_n, q_bits, dnum, sb, seed)
+    g.keygen(); o.keygen()
+    steps = [1, 7, g.slots - 3, 64]
+    g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+    yield g, o
+    g.close()
+
+
+def fresh_pair(g, o, seed, limbs, bits=40, scale=2.0 ** 40):
+    from paper_1810_00845_amd import synth
+    co = synth.plaintext_coeffs(seed, g.N, bits)
+    gp, op = g.pt_from_coeffs(co, scale, limbs), o.pt_from_coeffs(co, scale, limbs)
+    ctr = 1000 + seed
+    g.set_enc_counter(ctr); o.enc_counter = ctr
+    return g.encrypt(gp), o.encrypt(op), gp, op
+
+
+def same(g, o, gct, oct_):
+    got = g.ct_export(gct)
+    want = o.export(oct_)
+    assert got.shape == want.shape
+    assert np.array_equal(got, want), "mismatch at %s" % (np.argwhere(got != want)[:4],)
+    assert abs(gct.scale - oct_.scale) <= 1e-12 * abs(oct_.scale)
+
+
+def test_primes_match(pair):
+    g, o = pair
+    assert g.primes == o.primes and g.alpha == o.alpha
+
+
+def test_ntt_raw_forward_inverse(pair):
+    import torch
+    from paper_1810_00845_amd import synth
+    g, o = pair
+    for prime in range(g.L + g.K):
+        q = g.primes[prime]
+        a = synth.uniform_residues(prime, (3, 1, g.N), [q])[:, 0, :]
+        a[0, :4] = [0, q - 1, 1, q // 2]
+        t = torch.from_numpy(a.view(np.int64)).cuda()
+        g.ntt_raw(t, prime)
+        got = t.cpu().numpy().view(np.uint64)
+        for r in range(3):
+            assert np.array_equal(got[r], o.ntt(a[r], prime))
+        g.ntt_raw(t, prime, inverse=True)
+        assert np.array_equal(t.cpu().numpy().view(np.uint64), a)
+
+
+def test_secret_and_keys_match(pair):
+    g, o = pair
+    assert np.array_equal(g.secret_export(), o.secret_coeffs())
+    assert np.array_equal(g.key_export(0), o.keys[0])
+    for r in (1, 64):
+        ge = g.galois_elt(r)
+        assert ge == o.galois_elt(r)
+        assert np.array_equal(g.key_export(ge), o.keys[ge])
+
+
+def test_plaintext_and_encrypt_decrypt(pair):
+    g, o = pair
+    for limbs in (g.L, 1):
+        gct, oct_, gp, op = fresh_pair(g, o, 3 + limbs, limbs)
+        assert np.array_equal(g.pt_export(gp), o.pt_export(op))
+        same(g, o, gct, oct_)
+        assert np.array_equal(g.pt_export(g.decrypt(gct)), o.pt_export(o.decrypt(oct_)))
+    # batch encryption uses consecutive counters
+    from paper_1810_00845_amd import synth
+    cos = [synth.plaintext_coeffs(50 + i, g.N, 30) for i in range(3)]
+    g.set_enc_counter(77); o.enc_counter = 77
+    gcts = g.encrypt_batch([g.pt_from_coeffs(c, 2.0 ** 30, g.L) for c in cos])
+    for c, gc in zip(cos, gcts):
+        same(g, o, gc, o.encrypt(o.pt_from_coeffs(c, 2.0 ** 30, g.L)))
+
+
+def test_add_sub_mul_family(pair):
+    g, o = pair
+    ga, oa, gp, op = fresh_pair(g, o, 1, g.L)
+    gb, ob, _, _ = fresh_pair(g, o, 2, g.L)
+    same(g, o, g.add(ga, gb), o.add(oa, ob))
+    same(g, o, g.sub(ga, gb), o.sub(oa, ob))
+    same(g, o, g.add_plain(ga, gp), o.add_plain(oa, op))
+    same(g, o, g.sub_plain(ga, gp), o.sub_plain(oa, op))
+    same(g, o, g.mul_plain(ga, gp), o.mul_plain(oa, op))
+    for x in (0.625, -1.75, 3.0e-7):
+        same(g, o, g.add_scalar(ga, x), o.add_scalar(oa, x))
+        same(g, o, g.sub_scalar(ga, x), o.sub_scalar(oa, x))
+        same(g, o, g.mul_scalar(ga, x, 2.0 ** 33), o.mul_scalar(oa, x, 2.0 ** 33))
+    same(g, o, g.mul_scalar(ga, -0.37, float(g.primes[g.L - 1])), o.mul_scalar(oa, -0.37, float(o.primes[o.L - 1])))
+    g3, o3 = g.mul_no_relin(ga, gb), o.mul_no_relin(oa, ob)
+    same(g, o, g3, o3)
+    same(g, o, g.add_scalar(g3, 0.3), o.add_scalar(o3, 0.3))      # scale 2^80: beyond 64-bit integers
+    same(g, o, g.add(g3, g.mul_plain(ga, gp)), o.add(o3, o.mul_plain(oa, op)))  # 3 + 2 polynomials
+    # assign forms
+    gc = g.copy(ga); g.add_assign(gc, gb); same(g, o, gc, o.add(oa, ob))
+    gc = g.copy(ga); g.sub_assign(gc, gb); same(g, o, gc, o.sub(oa, ob))
+    gc = g.copy(ga); g.mul_plain_assign(gc, gp); same(g, o, gc, o.mul_plain(oa, op))
+    gc = g.copy(ga); g.mul_scalar_assign(gc, 0.5, 1024.0); same(g, o, gc, o.mul_scalar(oa, 0.5, 1024.0))
+    gc = g.copy(ga); g.add_plain_assign(gc, gp); same(g, o, gc, o.add_plain(oa, op))
+    gc = g.copy(ga); g.sub_scalar_assign(gc, 0.25); same(g, o, gc, o.sub_scalar(oa, 0.25))
+
+
+def test_rescale_every_level(pair):
+    g, o = pair
+    gct, oct_, _, _ = fresh_pair(g, o, 4, g.L)
+    g3, o3 = g.mul_no_relin(gct, gct), o.mul_no_relin(oct_, oct_)
+    g.rescale(g3); o3 = o.rescale(o3)
+    same(g, o, g3, o3)
+    while gct.limbs > 1:
+        d = g.max_scalar_div(gct, float("inf"))
+        assert d == o.max_scalar_div(oct_, float("inf")) == g.primes[gct.limbs - 1]
+        g.div_scalar(gct, d); oct_ = o.div_scalar(oct_, d)
+        same(g, o, gct, oct_)
+    assert g.max_scalar_div(gct, float("inf")) == 1
+
+
+def test_rotations_every_level(pair):
+    g, o = pair
+    gct, oct_, _, _ = fresh_pair(g, o, 5, g.L)
+    while True:
+        for r in (1, 7, 64):
+            same(g, o, g.rot_left(gct, r), o.rot_left(oct_, r))
+        same(g, o, g.rot_right(gct, 3), o.rot_right(oct_, 3))
+        same(g, o, g.rot_left(gct, 0), oct_)
+        same(g, o, g.rot_left(gct, g.slots), oct_)
+        if gct.limbs == 1:
+            break
+        g.rescale(gct); oct_ = o.rescale(oct_)
+    gc = g.copy(gct); g.rot_left_assign(gc, 7); same(g, o, gc, o.rot_left(oct_, 7))
+    gc = g.copy(gct); g.rot_right_assign(gc, 3); same(g, o, gc, o.rot_right(oct_, 3))
+
+
+def test_relinearize_and_mul_every_level(pair):
+    g, o = pair
+    ga, oa, _, _ = fresh_pair(g, o, 6, g.L)
+    gb, ob, _, _ = fresh_pair(g, o, 7, g.L)
+    while True:
+        g3, o3 = g.mul_no_relin(ga, gb), o.mul_no_relin(oa, ob)
+        g.relinearize(g3)
+        same(g, o, g3, o.relinearize(o3))
+        same(g, o, g.mul(ga, gb), o.mul(oa, ob))
+        if ga.limbs == 1:
+            break
+        g.rescale(ga); oa = o.rescale(oa)
+        g.rescale(gb); ob = o.rescale(ob)
+    gc = g.copy(ga); g.mul_assign(gc, gb); same(g, o, gc, o.mul(oa, ob))
+
+
+def test_batched_forms_match_single_calls(pair):
+    g, o = pair
+    cts = [fresh_pair(g, o, 20 + i, g.L) for i in range(5)]
+    gs, os_ = [c[0] for c in cts], [c[1] for c in cts]
+    gp, op = cts[0][2], cts[0][3]
+    for gr, oc in zip(g.rot_left_batch(gs, 7), os_):
+        same(g, o, gr, o.rot_left(oc, 7))
+    # handles that are not views of one allocation (gathered internally), ragged batch of 3
+    mixed = [gs[4], gs[0], gs[2]]
+    for gr, oc in zip(g.rot_left_batch(mixed, 1), [os_[4], os_[0], os_[2]]):
+        same(g, o, gr, o.rot_left(oc, 1))
+    for gr, oa, ob in zip(g.add_batch(gs[:4], gs[1:]), os_[:4], os_[1:]):
+        same(g, o, gr, o.add(oa, ob))
+    for gr, oc in zip(g.mul_plain_batch(gs, gp), os_):
+        same(g, o, gr, o.mul_plain(oc, op))
+    g3 = g.mul_no_relin_batch(gs[:4], gs[1:])
+    o3 = [o.mul_no_relin(a, b) for a, b in zip(os_[:4], os_[1:])]
+    for a, b in zip(g3, o3):
+        same(g, o, a, b)
+    g.relinearize_batch(g3)
+    o2 = [o.relinearize(x) for x in o3]
+    for a, b in zip(g3, o2):
+        same(g, o, a, b)
+    g.rescale_batch(g3)
+    for a, b in zip(g3, o2):
+        same(g, o, a, o.rescale(b))
+
+
+def test_import_export_roundtrip(pair):
+    from paper_1810_00845_amd import synth
+    g, o = pair
+    co = synth.uniform_residues(9, (2, 2, g.L, g.N), g.primes[:g.L])
+    for gc, c in zip(g.ct_import_batch(co, 4.0), co):
+        assert np.array_equal(g.ct_export(gc), c)
+        same(g, o, gc, o.import_ct(c, 4.0))
+
+
+def centred_coeffs(o, coeff_form, limbs):
+    """Centred integers from coefficient-form residues (CRT with Python integers)."""
+    import math
+    qs = o.primes[:limbs]
+    Q = math.prod(qs)
+    out = []
+    for k in range(coeff_form.shape[1]):
+        x = 0
+        for i, q in enumerate(qs):
+            hat = Q // q
+            x += int(coeff_form[i, k]) * pow(hat, -1, q) * hat
+        x %= Q
+        out.append(x - Q if x > Q // 2 else x)
+    return out
+
+
+def test_encode_decode_within_tolerance(pair):
+    """fp64 on the GPU against long double in the oracle: coefficients agree to the fp64 rounding of a
+    sum of N/2 terms, |delta| <= max(1, 2^-45 * scale * sqrt(N)); decoded slots to 2^-20 and to the
+    encoding error bound N/(2*scale)."""
+    from paper_1810_00845_amd import synth
+    g, o = pair
+    z = synth.slot_vector(1, g.slots, complex_values=True)
+    for scale, count in ((2.0 ** 25, g.slots), (2.0 ** 45, g.slots), (2.0 ** 30, 37)):
+        gp = g.encode(z[:count], scale, g.L)
+        assert gp.limbs == g.L and gp.scale == scale
+        got = centred_coeffs(o, g.pt_export(gp), g.L)
+        want = o.encode_coeffs(z[:count], scale)
+        tol = max(1.0, 2.0 ** -45 * scale * g.N ** 0.5)
+        assert max(abs(a - int(b)) for a, b in zip(got, want)) <= tol
+        dec = g.decode(gp)
+        ref = np.zeros(g.slots, dtype=complex); ref[:count] = z[:count]
+        assert np.abs(dec - ref).max() <= g.N / (2 * scale) + 2.0 ** -20
+        # GPU decode of the oracle's plaintext against the oracle's decode
+        op = o.encode(z[:count], scale, g.L)
+        gp2 = g.pt_from_coeffs(want, scale, g.L)
+        assert np.abs(g.decode(gp2) - o.decode(op)).max() <= 2.0 ** -20
+    # end to end through encryption
+    gct = g.encrypt(g.encode(z.real, 2.0 ** 40, g.L))
+    assert np.abs(g.decode(g.decrypt(gct)) - z.real).max() < 1e-6
+
+
+def test_error_codes(pair):
+    from paper_1810_00845_amd import hisa
+    g, o = pair
+    gct, oct_, gp, _ = fresh_pair(g, o, 30, g.L)
+    def code(fn, *a):
+        with pytest.raises(hisa.HisaError) as e:
+            fn(*a)
+        return e.value.code
+    assert code(g.rot_left, gct, 5) == -4                      # no key for this amount
+    assert code(g.add, gct, g.mul_scalar(gct, 1.0, 2.0)) == -3  # scale mismatch
+    if g.L > 1:
+        low = g.copy(gct); g.rescale(low)
+        assert code(g.add, gct, low) == -2                     # level mismatch
+        assert code(g.mul_plain, low, gp) == -2
+        assert code(g.div_scalar, gct, g.primes[0]) == -5      # not the last modulus
+        g.div_scalar(gct, 1)                                   # d = 1: no-op
+        same(g, o, gct, oct_)
+        while low.limbs > 1:
+            g.rescale(low)
+        assert code(g.rescale, low) == -6                      # depth exhausted
+    assert code(g.mul_no_relin, g.mul_no_relin(gct, gct), gct) == -9
