@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the HISA hot path on one MI355X.
+
+Headline metric (the benchmark spec): key-switched rotLeft per second at N = 2^15,
+batch 64 -- the primitive micro-benchmark configuration (16 limbs of 50-bit
+primes, dnum 3, rotation steps {1, 7, 64}).  One "step" rotates a batch of 64
+synthetic ciphertexts, resident in HBM, by one of the three amounts (cycling).
+
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline      dominant kernel of the step, algorithmic bytes / HIP-event time
+  rot_left      whole-operation figures against the staged and strict HBM models
+  ops           per-primitive timings of the same configuration
+  cpu_baseline  the CPU oracle on a bounded sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes_rot_left(N, l, K, alpha, B):
+    """HBM bytes each kernel of one batched rotLeft must move (reads + writes), per kernel name."""
+    LP = 8 * N
+    ext = l + K
+    digits = (l + alpha - 1) // alpha
+    sizes = [min(alpha, l - j * alpha) for j in range(digits)]
+    out = {}
+    out["automorph_ntt_kernel"] = 2 * l * LP * B
+    out["ntt_pass_kernel<true>"] = 2 * LP * B * (l + 2 * K)
+    out["ntt_pass_kernel<false>"] = 2 * LP * B * (sum(ext - a for a in sizes) + 2 * l)
+    out["base_conv_kernel"] = LP * B * (sum(a + (ext - a) for a in sizes) + 2 * (K + l))
+    out["copy_limbs_kernel"] = 2 * l * LP * B
+    out["inner_product_kernel"] = LP * (B * (digits * ext + 2 * ext) + digits * 2 * ext)
+    out["moddown_final_kernel"] = 7 * l * LP * B
+    return out
+
+
+def staged_bytes_rot_left(N, l, K, alpha, dnum_key, L, B):
+    """(11 l + 6 K) LP + key/B: one HBM round trip per change of access pattern, everything else fused."""
+    LP = 8 * N
+    key = dnum_key * 2 * (L + K) * LP
+    return (11 * l + 6 * K) * LP + key / B, 4 * l * LP + key / B
+
+
+def time_op(ctx, fn, iters, warm=2):
+    import torch
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        fn()
+    ctx.sync()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / iters
+
+
+def cpu_baseline(log_n, q_bits, dnum, special_bits, seed, sample, steps):
+    """The oracle's rotLeft on `sample` ciphertexts of the same shape, spread over the host cores."""
+    from concurrent.futures import ThreadPoolExecutor
+    import numpy as np
+    from oracle import Oracle
+    from paper_1810_00845_amd import synth
+    o = Oracle(log_n, q_bits, dnum, special_bits, seed)
+    o.gen_rot_keys(steps[:1])
+    cores = min(sample, os.cpu_count() or 1, 16)
+    coeff = synth.uniform_residues(seed, (sample, 2, len(q_bits), o.N), o.primes[:len(q_bits)])
+    cts = [o.import_ct(coeff[i], 2.0 ** 50) for i in range(sample)]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as ex:
+        list(ex.map(lambda c: o.rot_left(c, steps[0]), cts))
+    dt = time.perf_counter() - t0
+    return {"value": sample / dt, "unit": "rotLeft/s", "cores": cores, "kind": "oracle",
+            "sample": "%d ciphertexts of the same N, limbs, dnum, one rotLeft(%d) each, %.1f s" % (sample, steps[0], dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--log-n", type=int, default=15)
+    ap.add_argument("--limbs", type=int, default=16)
+    ap.add_argument("--dnum", type=int, default=3)
+    ap.add_argument("--bits", type=int, default=50)
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--cpu-sample", type=int, default=8, help="ciphertexts for the oracle baseline (0 = skip)")
+    ap.add_argument("--no-ops", action="store_true", help="skip the per-primitive timings")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    from paper_1810_00845_amd import hisa
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU; libhisa has no CPU fallback")
+
+    log_n, L, dnum, B = args.log_n, args.limbs, args.dnum, args.batch
+    q_bits = [args.bits] * L
+    rot_steps = [1, 7, 64]
+    ctx = hisa.Context(log_n, q_bits, dnum, args.bits, seed=1)
+    ctx.keygen()
+    ctx.gen_rot_keys(rot_steps)
+    N, K, alpha = ctx.N, ctx.K, ctx.alpha
+    cts = ctx.ct_random_batch(B, L, 2.0 ** 50, counter=0)
+    ctx.sync()
+
+    def step(i):
+        out = ctx.rot_left_batch(cts, rot_steps[i % 3])
+        for c in out:
+            c.free()
+
+    for i in range(args.warmup):
+        step(i)
+    ctx.sync(); torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    ctx.sync(); torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    value = B * args.steps / dt
+
+    # per-kernel durations with HIP events on the launch stream (separate pass over the same steps)
+    prof_steps = 3
+    ctx.profile_enable(True)
+    for i in range(prof_steps):
+        step(i)
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    alg = algorithmic_bytes_rot_left(N, L, K, alpha, B)
+    kernels = {}
+    for name, (cnt, ms) in prof.items():
+        per_step_ms = ms / prof_steps
+        gbs = alg.get(name, 0) / (per_step_ms * 1e-3) / 1e9 if per_step_ms > 0 else 0.0
+        kernels[name] = {"launches_per_step": cnt / prof_steps, "ms_per_step": round(per_step_ms, 4),
+                         "avg_launch_us": round(1e3 * ms / cnt, 2), "algorithmic_GBs": round(gbs, 1)}
+    dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["algorithmic_GBs"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(kernels[dom]["algorithmic_GBs"] / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_launch_us": kernels[dom]["avg_launch_us"],
+                "share_of_step": round(kernels[dom]["ms_per_step"] / sum(k["ms_per_step"] for k in kernels.values()), 3)}
+    staged, strict = staged_bytes_rot_left(N, L, K, alpha, dnum, L, B)
+    per_ct_s = dt / (B * args.steps)
+    rot = {"us_per_ct": round(per_ct_s * 1e6, 2),
+           "staged_bytes_per_ct": int(staged), "strict_bytes_per_ct": int(strict),
+           "staged_GBs": round(staged / per_ct_s / 1e9, 1), "frac_of_hbm_staged": round(staged / per_ct_s / 1e9 / HBM_PEAK_GBS, 4),
+           "frac_of_hbm_strict": round(strict / per_ct_s / 1e9 / HBM_PEAK_GBS, 4)}
+
+    ops = {}
+    if not args.no_ops:
+        LP = 8 * N
+        buf = torch.zeros((B * 2 * L, N), dtype=torch.int64, device="cuda")
+        t = time_op(ctx, lambda: ctx.ntt_raw(buf, 0), 10)
+        ops["ntt"] = {"ms": round(t * 1e3, 4), "polys": B * 2 * L, "GBs": round(2 * LP * B * 2 * L / t / 1e9, 1)}
+        t = time_op(ctx, lambda: ctx.ntt_raw(buf, 0, inverse=True), 10)
+        ops["intt"] = {"ms": round(t * 1e3, 4), "polys": B * 2 * L, "GBs": round(2 * LP * B * 2 * L / t / 1e9, 1)}
+        del buf
+        pt = ctx.encode([0.5] * 8, 2.0 ** 50, L)
+
+        def free_all(xs):
+            for x in xs:
+                x.free()
+        t = time_op(ctx, lambda: free_all(ctx.add_batch(cts, cts)), 10)
+        ops["add"] = {"ms": round(t * 1e3, 4), "GBs": round(3 * 2 * L * LP * B / t / 1e9, 1)}
+        t = time_op(ctx, lambda: free_all(ctx.mul_plain_batch(cts, pt)), 10)
+        ops["mul_plain"] = {"ms": round(t * 1e3, 4), "GBs": round((4 * L * B + L) * LP / t / 1e9, 1)}
+
+        def resc():
+            tmp = ctx.add_batch(cts, cts)
+            ctx.rescale_batch(tmp)
+            free_all(tmp)
+        t_add = ops["add"]["ms"] * 1e-3
+        t = time_op(ctx, resc, 5) - t_add
+        ops["rescale"] = {"ms": round(t * 1e3, 4), "GBs": round((2 * L + 2 * (L - 1)) * LP * B / t / 1e9, 1)}
+
+        def relin():
+            tmp = ctx.mul_no_relin_batch(cts, cts)
+            ctx.relinearize_batch(tmp)
+            free_all(tmp)
+        t_mul = time_op(ctx, lambda: free_all(ctx.mul_no_relin_batch(cts, cts)), 5)
+        ops["mul_no_relin"] = {"ms": round(t_mul * 1e3, 4), "GBs": round(7 * L * LP * B / t_mul / 1e9, 1)}
+        t = time_op(ctx, relin, 5) - t_mul
+        ops["relinearize"] = {"ms": round(t * 1e3, 4), "per_s": round(B / t, 1)}
+
+    base = None
+    if args.cpu_sample > 0:
+        base = cpu_baseline(log_n, q_bits, dnum, args.bits, 1, args.cpu_sample, rot_steps)
+
+    print(json.dumps({
+        "metric": "key-switched rotLeft/s at N=2^15 (batch 64)" if (log_n, B) == (15, 64) else
+                  "key-switched rotLeft/s at N=2^%d (batch %d)" % (log_n, B),
+        "value": round(value, 1), "unit": "rotLeft/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "primitive micro-benchmark: rotLeft over a batch of %d random ciphertexts, N=2^%d, "
+                               "%d limbs of %d-bit primes, dnum %d, steps {1,7,64}" % (B, log_n, L, args.bits, dnum),
+                   "log_n": log_n, "limbs": L, "dnum": dnum, "special_primes": K, "batch": B},
+        "roofline": roofline, "rot_left": rot, "kernels": kernels, "ops": ops, "cpu_baseline": base}))
+
+
+if __name__ == "__main__":
+    main()

@@ -186,11 +186,12 @@ int hisa_ct_random_batch(hisa_ctx* ctx, size_t n, uint32_t limbs, double scale, 
 /* ---- tensor layer (Sec. "Runtime": CipherTensor, HW-tiling, Algorithm 1) ----
  * A CipherTensor is a vector of ciphertexts plus plain-integer metadata: the
  * outer (batch, channel) dimensions index ciphertexts cts[b*channels + c]; one
- * ciphertext holds the height x width plane of one channel, element (y, x) in
- * slot offset + y*h_stride + x*w_stride (strides allow padding between rows).
- * `clean` is the runtime's flag that every slot outside the plane's elements
- * is zero.  The struct is host memory owned by the caller; the handles in cts
- * are owned like any other handle. */
+ * ciphertext holds the height x width plane of one channel (HW-tiling), element
+ * (y, x) in slot offset + y*h_stride + x*w_stride (strides leave room for
+ * padding between rows).  `clean` is the runtime's flag that every slot that
+ * holds no element is zero.  The struct is host memory owned by the caller; the
+ * handles in cts are owned like any other handle.  Layer calls fill *out:
+ * out->cts must point to room for the output handles (batch * out channels). */
 typedef struct {
     uint32_t batch, channels;    /* outer (vector) dimensions                 */
     uint32_t height, width;      /* logical inner dimensions                  */
@@ -200,45 +201,72 @@ typedef struct {
     hisa_ct** cts;               /* batch*channels handles                    */
 } hisa_tensor;
 
-#define HISA_CONV_SCALAR 0 /* literal Algorithm 1: mulScalar by round(w * q_last), add, one divScalar       */
-#define HISA_CONV_MASKED 1 /* as SCALAR with weight scale q_last/2^25, then one mulPlain by the 0/1 mask of   */
-                           /* valid output positions (scale 2^25) before the divScalar: leaves a clean tensor */
-#define HISA_CONV_PLAIN 2  /* one mulPlain per tap: plaintext = w * mask encoded at scale q_last            */
+#define HISA_CONV_SCALAR 0 /* literal Algorithm 1: mulScalar by round(w * q_last), add, one divScalar          */
+#define HISA_CONV_MASKED 1 /* weights at scale q_last / 2^25, then ONE mulPlain by the 0/1 mask of the valid    */
+                           /* output positions (scale 2^25) before the divScalar: the output is clean          */
+#define HISA_CONV_PLAIN 2  /* one mulPlain per tap: plaintext = w * mask encoded at scale q_last                 */
+#define HISA_MASK_SCALE 33554432.0 /* 2^25 */
 
 typedef struct {
-    uint32_t fh, fw;      /* filter height, width                                                   */
-    uint32_t stride;      /* output stride (>= 1)                                                   */
-    uint32_t pad_same;    /* 0: VALID.  1: SAME, the input must carry a zero border of fh/2, fw/2   */
-    uint32_t mode;        /* HISA_CONV_*                                                           */
+    uint32_t fh, fw;      /* filter height, width                                                      */
+    uint32_t stride;      /* output stride (>= 1)                                                      */
+    uint32_t pad_same;    /* 0: VALID.  1: SAME -- the input tensor must be clean and its layout must   */
+                          /* leave fh/2 rows and fw/2 columns of zero slots around the plane           */
+    uint32_t mode;        /* HISA_CONV_*                                                              */
 } hisa_conv_geom;
 
 /* HW-tiled conv2d (Algorithm 1; cross-correlation, no kernel flip): for every
- * output channel oc: sum over ic, (fh, fw) of weight * rotLeft(in[ic],
- * fh*h_stride + fw*w_stride), then one divScalar.  Rotations are computed once
- * per (ic, tap) and shared by all oc.  host weights w[FH][FW][IC][OC]; bias[OC]
- * may be NULL.  out->cts must point to room for batch*OC handles; the other
- * fields of *out are filled in (strides multiplied by the conv stride). */
-int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w, const double* bias, uint32_t out_channels,
+ * output channel oc: sum over ic and filter taps (fy, fx) of weight *
+ * rotLeft(in[ic], fy*h_stride + fx*w_stride) (SAME: taps are centred, negative
+ * amounts rotate right), then one divScalar by the last modulus.  Rotations are
+ * computed once per (ic, tap), batched over ic, and shared by all oc.  host
+ * weights w[FH][FW][IC][OC].  Output strides are the input strides times the
+ * conv stride.  Needs the rotation keys listed by hisa_conv2d_rot_steps.
+ * hisa_conv2d_fixed takes the fixed-point integers directly (what
+ * FixedPrecision(weight, plainLogP) and the plaintext encodings produce), so
+ * that two implementations can be fed identical integers:
+ *   SCALAR / MASKED: w_int[FH][FW][IC][OC] (scale w_scale); MASKED also
+ *   pt_coeffs[N], the mask plaintext's signed coefficients (scale pt_scale);
+ *   PLAIN: pt_coeffs[FH][FW][IC][OC][N] (scale pt_scale), w_int unused.
+ * w_scale * pt_scale (or pt_scale alone for PLAIN, w_scale for SCALAR) should
+ * equal the last modulus for the ciphertext scale to be preserved. */
+int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t out_channels,
                 const hisa_conv_geom* geom, hisa_tensor* out);
+int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* w_int, double w_scale,
+                      const int64_t* pt_coeffs, double pt_scale, uint32_t out_channels, const hisa_conv_geom* geom,
+                      hisa_tensor* out);
 /* Fully connected layer over all elements of all channels (Sec. "Homomorphic
- * matmul", version without replicas): host w[OUT][C][H][W]; per output o:
- * sum_c mulPlain(in[c], encode(w[o][c] placed on the element slots, scale
- * q_last)), one divScalar, then rotate-and-add over the power-of-two window
- * covering the plane; output o is a 1x1 plane in slot `offset`. */
-int hisa_fc(hisa_ctx* ctx, const hisa_tensor* in, const double* w, const double* bias, uint32_t out_features,
-            hisa_tensor* out);
-/* 2x2 sum pool with stride 2 (the 1/4 of the average is left to the next
- * layer's weights): x + rot(w_stride) + rot(h_stride) + rot(h_stride+w_stride). */
+ * matmul", the version without replicas): host w[OUT][C][H][W]; per output o:
+ * sum_c mulPlain(in[c], encode(w[o][c] placed on the element slots, zero
+ * elsewhere, scale q_last)), one divScalar, then log2 rotate-and-add steps over
+ * the power-of-two window that covers the plane; output o is a 1x1 plane in
+ * slot `offset` (other slots hold partial sums: clean = 0).  On a 1x1 input it
+ * is Algorithm 1 with a 1x1 filter (mulScalar, no rotations).
+ * hisa_fc_fixed: pt_coeffs[OUT][C][N] signed plaintext coefficients at pt_scale. */
+int hisa_fc(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t out_features, hisa_tensor* out);
+int hisa_fc_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* pt_coeffs, double pt_scale,
+                  uint32_t out_features, hisa_tensor* out);
+/* 2x2 sum pool, stride 2 (the 1/4 of the average belongs in the next layer's
+ * weights): x + rot(w_stride) + rot(h_stride) + rot(h_stride + w_stride);
+ * strides double, no level is used. */
 int hisa_sum_pool2x2(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out);
-/* Degree-2 activation a*x^2 + b*x evaluated as x^2 + (b/a)*x (one mul +
- * relinearize, one mulScalar at scale = ct scale, one add, one divScalar); the
- * factor a is left to the next layer's weights. */
+/* Degree-2 activation a*x^2 + b*x computed as x^2 + (b/a)*x: one mul with
+ * relinearisation, one mulScalar by b/a at scale = ciphertext scale, one add,
+ * one divScalar.  The factor a belongs in the next layer's weights. */
 int hisa_poly2_act(hisa_ctx* ctx, const hisa_tensor* in, double a, double b, hisa_tensor* out);
-/* The rotation amounts a layer will use on this input layout, for
- * hisa_gen_rot_keys: writes up to cap amounts to host steps[], count to *n. */
-int hisa_conv2d_rot_steps(const hisa_tensor* in, const hisa_conv_geom* geom, int32_t* steps, size_t cap, size_t* n);
-int hisa_fc_rot_steps(const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n);
-int hisa_pool_rot_steps(const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n);
+/* The left-rotation amounts a layer will use on this input layout, for
+ * hisa_gen_rot_keys (the rotation-key selection of Sec. "Rotation Keys
+ * Selection"): writes at most cap amounts to host steps[], the count to *n. */
+int hisa_conv2d_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* geom, int32_t* steps, size_t cap,
+                          size_t* n);
+int hisa_fc_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n);
+int hisa_pool_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n);
+/* Encrypts a plain tensor host x[batch][channels][height][width] into a clean
+ * HW-tiled CipherTensor with the given strides and offset, at `limbs` limbs. */
+int hisa_tensor_encrypt(hisa_ctx* ctx, const double* x, double scale, uint32_t limbs, hisa_tensor* inout);
+/* Decrypts and decodes the elements back: host x[batch][channels][height][width]. */
+int hisa_tensor_decrypt(hisa_ctx* ctx, const hisa_tensor* t, double* x);
+int hisa_tensor_free(hisa_ctx* ctx, hisa_tensor* t);
 
 /* ---- parity / debug surface ----
  * get_primes: host q[L], p[alpha].  ct_export: host[polys][limbs][N],
@@ -260,6 +288,16 @@ int hisa_ntt_raw(hisa_ctx* ctx, uint64_t* dev_buf, uint32_t prime_index, size_t 
 int hisa_key_export(hisa_ctx* ctx, uint64_t key_id, uint64_t* host);
 int hisa_galois_elt(hisa_ctx* ctx, int32_t left_steps, uint64_t* g);
 int hisa_secret_export(hisa_ctx* ctx, int64_t* host_coeffs);
+
+
+/* ---- measurement ----
+ * profile_enable(1) brackets every kernel launch of the process with HIP events
+ * recorded on the context's stream; profile_read synchronises, writes one line
+ * per kernel name ("name<TAB>launches<TAB>total milliseconds") into host_buf
+ * (cap bytes, NUL-terminated) and clears the records.  Off by default; meant for
+ * a separate measuring pass, not for timed runs. */
+int hisa_profile_enable(hisa_ctx* ctx, int on);
+int hisa_profile_read(hisa_ctx* ctx, char* host_buf, size_t cap);
 
 #ifdef __cplusplus
 }

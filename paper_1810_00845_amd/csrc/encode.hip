@@ -7,26 +7,31 @@
 
 #define NT 256
 
-// coeffs[k] = round( factor * sum_j ( re_j cos(pi e/N) + im_j sin(pi e/N) ) ),  e = 5^j k mod 2N
-__global__ __launch_bounds__(NT) void encode_kernel(const double* cs, const double* sn, const double* re, const double* im,
-                                                    int count, double factor, i64* coeffs, int log_n) {
+// coeffs[p][k] = round( factor * sum_j ( re[p][j] cos(pi e/N) + im[p][j] sin(pi e/N) ) ),  e = g[j] k mod 2N,
+// g[j] = 5^(slot of entry j) mod 2N.  One launch encodes n_pts vectors that share the slot list g[count]
+// (dense input: g[j] = 5^j; sparse input: only the non-zero slots are listed).
+__global__ __launch_bounds__(NT) void encode_kernel(const double* cs, const double* sn, const uint32_t* g, const double* re,
+                                                    const double* im, int count, double factor, i64* coeffs, int log_n) {
     const uint32_t k = blockIdx.x * NT + threadIdx.x;
     const uint32_t mask = (2u << log_n) - 1;
-    uint32_t g = 1;
+    const size_t p = blockIdx.y;
+    const double* r = re + p * count;
+    const double* m = im ? im + p * count : nullptr;
     double acc = 0.0;
     for (int j = 0; j < count; j++) {
-        uint32_t e = (g * k) & mask;
-        acc += re[j] * cs[e];
-        if (im) acc += im[j] * sn[e];
-        g = (g * 5u) & mask;
+        uint32_t e = (g[j] * k) & mask;
+        acc += r[j] * cs[e];
+        if (m) acc += m[j] * sn[e];
     }
-    coeffs[k] = (i64)round(acc * factor);
+    coeffs[(p << log_n) + k] = (i64)round(acc * factor);
 }
 
-hipError_t launch_encode(const double* cs, const double* sn, const double* re, const double* im, int count, double factor,
-                         i64* coeffs, int log_n, hipStream_t st) {
-    hipLaunchKernelGGL(encode_kernel, dim3((1u << log_n) / NT), dim3(NT), 0, st, cs, sn, re, im, count, factor, coeffs,
-                       log_n);
+hipError_t launch_encode(const double* cs, const double* sn, const uint32_t* g, const double* re, const double* im,
+                         int count, int n_pts, double factor, i64* coeffs, int log_n, hipStream_t st) {
+    if (n_pts <= 0) return hipSuccess;
+    ProfScope prof__("encode_kernel", st);
+    hipLaunchKernelGGL(encode_kernel, dim3((1u << log_n) / NT, n_pts), dim3(NT), 0, st, cs, sn, g, re, im, count, factor,
+                       coeffs, log_n);
     return hipGetLastError();
 }
 
@@ -61,6 +66,7 @@ __global__ __launch_bounds__(NT) void crt_to_double_kernel(const PrimeConst* pri
 
 hipError_t launch_crt_to_double(const PrimeConst* primes, const u64* coeff_form, int limbs, const u64* garner_inv,
                                 const u64* garner_inv_sh, int L, double inv_scale, double* out, int log_n, hipStream_t st) {
+    ProfScope prof__("crt_to_double_kernel", st);
     hipLaunchKernelGGL(crt_to_double_kernel, dim3((1u << log_n) / NT), dim3(NT), 0, st, primes, coeff_form, limbs,
                        garner_inv, garner_inv_sh, L, inv_scale, out, log_n);
     return hipGetLastError();
@@ -93,6 +99,7 @@ __global__ __launch_bounds__(NT) void decode_kernel(const double* cs, const doub
 
 hipError_t launch_decode(const double* cs, const double* sn, const double* m, int count, double* re, double* im, int log_n,
                          hipStream_t st) {
+    ProfScope prof__("decode_kernel", st);
     hipLaunchKernelGGL(decode_kernel, dim3((count + NT - 1) / NT), dim3(NT), 0, st, cs, sn, m, count, re, im, log_n);
     return hipGetLastError();
 }

@@ -93,10 +93,62 @@ static u64 double_to_residue(double v, u64 q) {
 }
 }  // namespace hm
 
+u64 double_to_residue(double v, u64 q) { return hm::double_to_residue(v, q); }
+
+// ---------------------------------------------------------------------------
+// per-kernel timing (HIP events on the launch stream)
+// ---------------------------------------------------------------------------
+bool g_prof_on = false;
+namespace {
+struct ProfRec { std::string kernel; hipEvent_t t0, t1; };
+std::vector<ProfRec> g_prof_recs;
+}
+void prof_begin(const char* kernel, hipStream_t st) {
+    ProfRec r{kernel, nullptr, nullptr};
+    if (hipEventCreate(&r.t0) != hipSuccess || hipEventCreate(&r.t1) != hipSuccess) return;
+    (void)hipEventRecord(r.t0, st);
+    g_prof_recs.push_back(r);
+}
+void prof_end(hipStream_t st) {
+    if (!g_prof_recs.empty()) (void)hipEventRecord(g_prof_recs.back().t1, st);
+}
+
+extern "C" int hisa_profile_enable(hisa_ctx* ctx, int on) {
+    if (!ctx) return HISA_ERR_ARG;
+    g_prof_on = on != 0;
+    return HISA_OK;
+}
+
+// Writes one line per kernel: "<name>\t<launches>\t<total ms>\n" into host_buf and clears the records.
+extern "C" int hisa_profile_read(hisa_ctx* ctx, char* host_buf, size_t cap) {
+    if (!ctx || !host_buf || cap == 0) return HISA_ERR_ARG;
+    (void)hipStreamSynchronize(ctx->stream);
+    std::map<std::string, std::pair<long, double>> agg;
+    for (auto& r : g_prof_recs) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.t0, r.t1) == hipSuccess) {
+            agg[r.kernel].first += 1;
+            agg[r.kernel].second += ms;
+        }
+        (void)hipEventDestroy(r.t0);
+        (void)hipEventDestroy(r.t1);
+    }
+    g_prof_recs.clear();
+    std::string out;
+    char line[256];
+    for (auto& kv : agg) {
+        snprintf(line, sizeof line, "%s\t%ld\t%.6f\n", kv.first.c_str(), kv.second.first, kv.second.second);
+        out += line;
+    }
+    if (out.size() + 1 > cap) return HISA_ERR_ARG;
+    memcpy(host_buf, out.c_str(), out.size() + 1);
+    return HISA_OK;
+}
+
 // ---------------------------------------------------------------------------
 // errors, memory
 // ---------------------------------------------------------------------------
-static int fail(hisa_ctx* ctx, int code, const char* fmt, ...) {
+int fail(hisa_ctx* ctx, int code, const char* fmt, ...) {
     if (ctx) {
         char buf[512];
         va_list ap;
@@ -108,21 +160,7 @@ static int fail(hisa_ctx* ctx, int code, const char* fmt, ...) {
     return code;
 }
 
-#define HIP_TRY(ctx, expr)                                                                        \
-    do {                                                                                          \
-        hipError_t e__ = (expr);                                                                  \
-        if (e__ != hipSuccess)                                                                    \
-            return fail(ctx, e__ == hipErrorOutOfMemory ? HISA_ERR_OOM : HISA_ERR_HIP, "%s: %s", #expr, \
-                        hipGetErrorString(e__));                                                  \
-    } while (0)
-
-#define TRY(expr)                  \
-    do {                           \
-        int rc__ = (expr);         \
-        if (rc__ != HISA_OK) return rc__; \
-    } while (0)
-
-static DevBlock* dev_alloc(hisa_ctx* ctx, size_t bytes) {
+DevBlock* dev_alloc(hisa_ctx* ctx, size_t bytes) {
     bytes = (bytes + 255) & ~(size_t)255;
     if (bytes == 0) bytes = 256;
     void* p = nullptr;
@@ -152,33 +190,17 @@ static DevBlock* dev_alloc(hisa_ctx* ctx, size_t bytes) {
 
 // Work on one stream: a block returned to the pool may be handed out again at
 // once, later kernels are ordered behind the earlier ones that used it.
-static void dev_release(hisa_ctx* ctx, DevBlock* b) {
+void dev_release(hisa_ctx* ctx, DevBlock* b) {
     if (!b) return;
     if (--b->refs > 0) return;
     ctx->pool[b->bytes].push_back(b->ptr);
     delete b;
 }
 
-struct Temp {
-    hisa_ctx* ctx;
-    DevBlock* blk;
-    Temp(hisa_ctx* c, size_t bytes) : ctx(c), blk(dev_alloc(c, bytes)) {}
-    ~Temp() { dev_release(ctx, blk); }
-    bool ok() const { return blk != nullptr; }
-    u64* u() const { return (u64*)blk->ptr; }
-    template <class T> T* as() const { return (T*)blk->ptr; }
-    Temp(const Temp&) = delete;
-    Temp& operator=(const Temp&) = delete;
-};
 
-static bool valid_ct(const hisa_ct* c) { return c && c->magic == HISA_MAGIC_CT; }
-static bool valid_pt(const hisa_pt* p) { return p && p->magic == HISA_MAGIC_PT; }
-
-static inline size_t poly_words(const hisa_ctx* ctx) { return (size_t)ctx->N; }
-static inline size_t ct_words(const hisa_ctx* ctx, uint32_t polys, uint32_t limbs) { return (size_t)polys * limbs * ctx->N; }
 
 // n ciphertext handles that are views of one allocation, [n][polys][limbs][N]
-static int alloc_ct_batch(hisa_ctx* ctx, size_t n, uint32_t polys, uint32_t limbs, double scale, hisa_ct** out) {
+int alloc_ct_batch(hisa_ctx* ctx, size_t n, uint32_t polys, uint32_t limbs, double scale, hisa_ct** out) {
     size_t words = ct_words(ctx, polys, limbs);
     DevBlock* blk = dev_alloc(ctx, n * words * sizeof(u64));
     if (!blk) return HISA_ERR_OOM;
@@ -188,22 +210,14 @@ static int alloc_ct_batch(hisa_ctx* ctx, size_t n, uint32_t polys, uint32_t limb
     return HISA_OK;
 }
 
-static int alloc_pt(hisa_ctx* ctx, uint32_t limbs, double scale, hisa_pt** out) {
+int alloc_pt(hisa_ctx* ctx, uint32_t limbs, double scale, hisa_pt** out) {
     DevBlock* blk = dev_alloc(ctx, (size_t)limbs * ctx->N * sizeof(u64));
     if (!blk) return HISA_ERR_OOM;
     *out = new hisa_pt{HISA_MAGIC_PT, blk, (u64*)blk->ptr, limbs, scale};
     return HISA_OK;
 }
 
-// A batch of equally shaped ciphertexts as one strided array.  When the
-// handles are not evenly spaced views, they are first copied side by side.
-struct BatchIn {
-    const u64* base = nullptr;
-    u64 stride = 0;
-    DevBlock* tmp = nullptr;
-};
-
-static int gather_batch(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, BatchIn* bi) {
+int gather_batch(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, BatchIn* bi) {
     const size_t words = ct_words(ctx, cts[0]->polys, cts[0]->limbs);
     bool even = true;
     for (size_t i = 1; i < n && even; i++) even = cts[i]->data == cts[0]->data + i * words;
@@ -222,7 +236,7 @@ static int gather_batch(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, Batc
     return HISA_OK;
 }
 
-static int check_batch_shape(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, uint32_t polys) {
+int check_batch_shape(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, uint32_t polys) {
     if (!cts || n == 0) return fail(ctx, HISA_ERR_ARG, "empty batch");
     for (size_t i = 0; i < n; i++) {
         if (!valid_ct(cts[i])) return fail(ctx, HISA_ERR_ARG, "batch entry %zu is not a ciphertext", i);
@@ -233,7 +247,7 @@ static int check_batch_shape(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n,
     return HISA_OK;
 }
 
-static PolyMap identity_map(int limbs) {
+PolyMap identity_map(int limbs) {
     PolyMap m = {};
     m.period = limbs;
     for (int i = 0; i < limbs; i++) m.prime_of[i] = (int16_t)i;
@@ -398,6 +412,10 @@ extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** 
         }
         HIP_TRY(ctx, upload(&ctx->d_cos, cs));
         HIP_TRY(ctx, upload(&ctx->d_sin, sn));
+        std::vector<uint32_t> pow5(n / 2);
+        uint32_t g = 1;
+        for (u64 j = 0; j < n / 2; j++) { pow5[j] = g; g = (g * 5u) & (uint32_t)(2 * n - 1); }
+        HIP_TRY(ctx, upload(&ctx->d_pow5, pow5));
     }
     HIP_TRY(ctx, hipMalloc((void**)&ctx->d_secret, (size_t)ctx->total * n * sizeof(u64)));
     TRY(sample_secret(ctx));
@@ -417,7 +435,7 @@ extern "C" int hisa_destroy(hisa_ctx* ctx) {
     if (ctx->moddown_tab) { free_conv_table(ctx->moddown_tab); delete ctx->moddown_tab; }
     (void)hipFree(ctx->d_primes); (void)hipFree(ctx->d_tw); (void)hipFree(ctx->d_tw_sh); (void)hipFree(ctx->d_itw);
     (void)hipFree(ctx->d_itw_sh); (void)hipFree(ctx->d_secret); (void)hipFree(ctx->d_pinv); (void)hipFree(ctx->d_pinv_sh);
-    (void)hipFree(ctx->d_pmod); (void)hipFree(ctx->d_cos); (void)hipFree(ctx->d_sin);
+    (void)hipFree(ctx->d_pmod); (void)hipFree(ctx->d_cos); (void)hipFree(ctx->d_sin); (void)hipFree(ctx->d_pow5);
     delete ctx;
     return HISA_OK;
 }
@@ -518,7 +536,7 @@ extern "C" int hisa_pt_from_coeffs(hisa_ctx* ctx, const int64_t* host_coeffs, do
     HIP_TRY(ctx, hipMemcpyAsync(co.blk->ptr, host_coeffs, ctx->N * sizeof(i64), hipMemcpyHostToDevice, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));  // the host buffer may be reused by the caller
     TRY(alloc_pt(ctx, limbs, scale, out));
-    HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>(), (*out)->data, (int)limbs, (int)ctx->log_n, ctx->stream));
+    HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>(), (*out)->data, (int)limbs, 1, (int)ctx->log_n, ctx->stream));
     HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, (*out)->data, 0, (int)limbs, identity_map((int)limbs), ctx->stream));
     return HISA_OK;
 }
@@ -536,10 +554,10 @@ extern "C" int hisa_encode(hisa_ctx* ctx, const double* re, const double* im, si
     if (count) HIP_TRY(ctx, hipMemcpyAsync(d_re, re, count * sizeof(double), hipMemcpyHostToDevice, ctx->stream));
     if (im && count) HIP_TRY(ctx, hipMemcpyAsync(d_im, im, count * sizeof(double), hipMemcpyHostToDevice, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-    HIP_TRY(ctx, launch_encode(ctx->d_cos, ctx->d_sin, d_re, d_im, (int)count, 2.0 * scale / (double)ctx->N, co.as<i64>(),
-                               (int)ctx->log_n, ctx->stream));
+    HIP_TRY(ctx, launch_encode(ctx->d_cos, ctx->d_sin, ctx->d_pow5, d_re, d_im, (int)count, 1, 2.0 * scale / (double)ctx->N,
+                               co.as<i64>(), (int)ctx->log_n, ctx->stream));
     TRY(alloc_pt(ctx, limbs, scale, out));
-    HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>(), (*out)->data, (int)limbs, (int)ctx->log_n, ctx->stream));
+    HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>(), (*out)->data, (int)limbs, 1, (int)ctx->log_n, ctx->stream));
     HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, (*out)->data, 0, (int)limbs, identity_map((int)limbs), ctx->stream));
     return HISA_OK;
 }

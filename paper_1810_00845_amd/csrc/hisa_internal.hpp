@@ -111,10 +111,76 @@ struct hisa_ctx {
     u64* d_pinv_sh;
     u64* d_pmod;      // [L] P mod q_i
     double *d_cos, *d_sin;  // [2N] roots of unity exp(i*pi*t/N)
+    uint32_t* d_pow5;       // [N/2] 5^j mod 2N
     std::unordered_map<size_t, std::vector<void*>> pool;
     size_t pool_bytes;
     u64 enc_counter;
     std::string err;
+};
+
+// ---- host helpers shared by hisa_api.hip and layers.hip ----
+int fail(hisa_ctx* ctx, int code, const char* fmt, ...);
+
+#define HIP_TRY(ctx, expr)                                                                        \
+    do {                                                                                          \
+        hipError_t e__ = (expr);                                                                  \
+        if (e__ != hipSuccess)                                                                    \
+            return fail(ctx, e__ == hipErrorOutOfMemory ? HISA_ERR_OOM : HISA_ERR_HIP, "%s: %s", #expr, \
+                        hipGetErrorString(e__));                                                  \
+    } while (0)
+
+#define TRY(expr)                  \
+    do {                           \
+        int rc__ = (expr);         \
+        if (rc__ != HISA_OK) return rc__; \
+    } while (0)
+
+DevBlock* dev_alloc(hisa_ctx* ctx, size_t bytes);   // from the context's pool; null (and last_error set) on failure
+void dev_release(hisa_ctx* ctx, DevBlock* b);
+
+struct Temp {  // pooled scratch buffer for the duration of one call
+    hisa_ctx* ctx;
+    DevBlock* blk;
+    Temp(hisa_ctx* c, size_t bytes) : ctx(c), blk(dev_alloc(c, bytes)) {}
+    ~Temp() { dev_release(ctx, blk); }
+    bool ok() const { return blk != nullptr; }
+    u64* u() const { return (u64*)blk->ptr; }
+    template <class T> T* as() const { return (T*)blk->ptr; }
+    Temp(const Temp&) = delete;
+    Temp& operator=(const Temp&) = delete;
+};
+
+static inline bool valid_ct(const hisa_ct* c) { return c && c->magic == HISA_MAGIC_CT; }
+static inline bool valid_pt(const hisa_pt* p) { return p && p->magic == HISA_MAGIC_PT; }
+static inline size_t ct_words(const hisa_ctx* ctx, uint32_t polys, uint32_t limbs) { return (size_t)polys * limbs * ctx->N; }
+
+// n ciphertext handles that are views of one allocation, [n][polys][limbs][N]
+int alloc_ct_batch(hisa_ctx* ctx, size_t n, uint32_t polys, uint32_t limbs, double scale, hisa_ct** out);
+int alloc_pt(hisa_ctx* ctx, uint32_t limbs, double scale, hisa_pt** out);
+
+// A batch of equally shaped ciphertexts as one strided array.  When the handles are not evenly
+// spaced views of one allocation they are first copied side by side (tmp then owns the copy).
+struct BatchIn {
+    const u64* base = nullptr;
+    u64 stride = 0;
+    DevBlock* tmp = nullptr;
+};
+int gather_batch(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, BatchIn* bi);
+int check_batch_shape(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, uint32_t polys);
+PolyMap identity_map(int limbs);
+// exact integer nearest to the double v (ties away from zero), reduced modulo q
+u64 double_to_residue(double v, u64 q);
+
+// Optional per-kernel timing with HIP events on the launch stream (off by default; the benchmark
+// turns it on for a separate pass).  One scope brackets one kernel launch.
+void prof_begin(const char* kernel, hipStream_t st);
+void prof_end(hipStream_t st);
+extern bool g_prof_on;
+struct ProfScope {
+    hipStream_t st;
+    bool on;
+    ProfScope(const char* kernel, hipStream_t s) : st(s), on(g_prof_on) { if (on) prof_begin(kernel, s); }
+    ~ProfScope() { if (on) prof_end(st); }
 };
 
 // ---- launch wrappers (every one enqueues on `st` and returns hipGetLastError) ----
@@ -152,7 +218,8 @@ hipError_t launch_key_combine(const PrimeConst* primes, const u64* secret, const
 hipError_t launch_pointwise_square(const PrimeConst* primes, const u64* s, u64* out, int total, int log_n, hipStream_t st);
 hipError_t launch_automorph_ntt(const u64* in, u64 in_bs, u64* out, u64 out_bs, u64 galois, int n_polys, u64 n_batch,
                                 int log_n, hipStream_t st);
-hipError_t launch_reduce_i64(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs, int log_n, hipStream_t st);
+hipError_t launch_reduce_i64(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs, int n_pts, int log_n,
+                             hipStream_t st);
 
 // Fast base conversion (centred): for every batch entry and target,
 //   out[target] = ( sum_i y[src_pos0+i] * hat[i][prime(target)]  -  #{i : y_i > c_i/2} * D ) mod t
@@ -191,8 +258,8 @@ hipError_t launch_rescale_final(const PrimeConst* primes, const u64* ct, const u
                                 u64* out, int l, u64 n_bp, int log_n, hipStream_t st);
 
 // encode / decode
-hipError_t launch_encode(const double* cs, const double* sn, const double* re, const double* im, int count, double factor,
-                         i64* coeffs, int log_n, hipStream_t st);
+hipError_t launch_encode(const double* cs, const double* sn, const uint32_t* g, const double* re, const double* im,
+                         int count, int n_pts, double factor, i64* coeffs, int log_n, hipStream_t st);
 hipError_t launch_crt_to_double(const PrimeConst* primes, const u64* coeff_form, int limbs, const u64* garner_inv,
                                 const u64* garner_inv_sh, int L, double inv_scale, double* out, int log_n, hipStream_t st);
 hipError_t launch_decode(const double* cs, const double* sn, const double* m, int count, double* re, double* im, int log_n,

@@ -1,0 +1,635 @@
+// HW-tiled homomorphic tensor kernels of the paper's runtime (Sec. "Runtime":
+// CipherTensor metadata, Algorithm 1 and its SAME-padding variant, homomorphic
+// matmul without replicas, pooling, degree-2 activation) on top of the batched
+// HISA primitives.  Host code here only orders launches; the multiply-accumulate
+// over (input channel, tap) pairs runs in the two kernels below.
+#include <math.h>
+
+#include <algorithm>
+#include <set>
+
+#include "hisa_internal.hpp"
+#include "modarith.cuh"
+
+#define NT 256
+#define OCB 4
+#define MAX_TAPS 64
+
+struct MacArgs {
+    const u64* tap_base[MAX_TAPS];  // per tap: [batch*IC][2][l][N]
+    int n_taps, IC, OC, l;
+    u64 ct_words;                   // 2*l*N
+    const u64* w;                   // scalar: residues [T][OC][l]; plain: plaintexts, NTT form
+    u64 w_stride_t, w_stride_oc;    // plain: strides in units of l*N words
+    u64* out;                       // [batch*OC][2][l][N]
+};
+
+// out[b][oc] = sum over T = (tap, ic) of  w[T][oc] * x[tap][b][ic]   (integer weights, one per limb)
+__global__ __launch_bounds__(NT) void scalar_mac_kernel(const PrimeConst* primes, MacArgs g, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    const int pl = blockIdx.y, limb = pl % g.l;
+    const int ocblocks = (g.OC + OCB - 1) / OCB;
+    const int b = blockIdx.z / ocblocks, oc0 = (blockIdx.z % ocblocks) * OCB;
+    const PrimeConst pc = primes[limb];
+    Acc128 acc[OCB];
+    for (int o = 0; o < OCB; o++) acc[o] = {0, 0};
+    int pending = 0;
+    for (int t = 0; t < g.n_taps; t++) {
+        const u64* x = g.tap_base[t] + (u64)b * g.IC * g.ct_words + (u64)pl * n + j;
+        const u64* w = g.w + ((u64)t * g.IC * g.OC + oc0) * g.l + limb;
+        for (int ic = 0; ic < g.IC; ic++) {
+            const u64 xv = x[(u64)ic * g.ct_words];
+            for (int o = 0; o < OCB; o++)
+                if (oc0 + o < g.OC) acc_mad(acc[o], xv, w[((u64)ic * g.OC + o) * g.l]);
+            if (++pending == 8) {  // keep the high words below q
+                for (int o = 0; o < OCB; o++) { acc[o].lo = acc_reduce(acc[o], pc.q, pc.r1, pc.r0); acc[o].hi = 0; }
+                pending = 0;
+            }
+        }
+    }
+    for (int o = 0; o < OCB; o++)
+        if (oc0 + o < g.OC)
+            g.out[((u64)b * g.OC + oc0 + o) * g.ct_words + (u64)pl * n + j] = acc_reduce(acc[o], pc.q, pc.r1, pc.r0);
+}
+
+// out[b][oc] = sum over T = (tap, ic) of  pt[T][oc] (slot-wise) x[tap][b][ic]
+__global__ __launch_bounds__(NT) void plain_mac_kernel(const PrimeConst* primes, MacArgs g, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    const int limb = blockIdx.y;
+    const int b = blockIdx.z / g.OC, oc = blockIdx.z % g.OC;
+    const PrimeConst pc = primes[limb];
+    const u64 ln = (u64)g.l * n;
+    Acc128 a0 = {0, 0}, a1 = {0, 0};
+    int pending = 0;
+    for (int t = 0; t < g.n_taps; t++) {
+        const u64* x = g.tap_base[t] + (u64)b * g.IC * g.ct_words + (u64)limb * n + j;
+        for (int ic = 0; ic < g.IC; ic++) {
+            const u64 T = (u64)t * g.IC + ic;
+            const u64 wv = g.w[(T * g.w_stride_t + (u64)oc * g.w_stride_oc) * ln + (u64)limb * n + j];
+            acc_mad(a0, x[(u64)ic * g.ct_words], wv);
+            acc_mad(a1, x[(u64)ic * g.ct_words + ln], wv);
+            if (++pending == 8) {
+                a0.lo = acc_reduce(a0, pc.q, pc.r1, pc.r0); a0.hi = 0;
+                a1.lo = acc_reduce(a1, pc.q, pc.r1, pc.r0); a1.hi = 0;
+                pending = 0;
+            }
+        }
+    }
+    u64* o = g.out + ((u64)b * g.OC + oc) * g.ct_words + (u64)limb * n + j;
+    o[0] = acc_reduce(a0, pc.q, pc.r1, pc.r0);
+    o[ln] = acc_reduce(a1, pc.q, pc.r1, pc.r0);
+}
+
+static hipError_t launch_scalar_mac(const PrimeConst* primes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, 2 * g.l, batch * ((g.OC + OCB - 1) / OCB));
+    ProfScope prof__("scalar_mac_kernel", st);
+    hipLaunchKernelGGL(scalar_mac_kernel, grid, dim3(NT), 0, st, primes, g, log_n);
+    return hipGetLastError();
+}
+
+static hipError_t launch_plain_mac(const PrimeConst* primes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / NT, g.l, batch * g.OC);
+    ProfScope prof__("plain_mac_kernel", st);
+    hipLaunchKernelGGL(plain_mac_kernel, grid, dim3(NT), 0, st, primes, g, log_n);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// helpers
+// ---------------------------------------------------------------------------
+static int check_tensor(hisa_ctx* ctx, const hisa_tensor* t) {
+    if (!ctx) return HISA_ERR_ARG;
+    if (!t || !t->cts || t->batch == 0 || t->channels == 0 || t->height == 0 || t->width == 0)
+        return fail(ctx, HISA_ERR_ARG, "empty tensor");
+    const u64 last = (u64)t->offset + (u64)(t->height - 1) * t->h_stride + (u64)(t->width - 1) * t->w_stride;
+    if (last >= ctx->N / 2) return fail(ctx, HISA_ERR_ARG, "tensor plane does not fit the %u slots", ctx->N / 2);
+    return check_batch_shape(ctx, (const hisa_ct* const*)t->cts, (size_t)t->batch * t->channels, 2);
+}
+
+static void free_handles(hisa_ctx* ctx, std::vector<hisa_ct*>& v) {
+    for (hisa_ct* c : v) hisa_free(ctx, c);
+    v.clear();
+}
+
+static int32_t norm_step(const hisa_ctx* ctx, i64 r) {
+    const i64 slots = ctx->N / 2;
+    r %= slots;
+    if (r < 0) r += slots;
+    return (int32_t)r;
+}
+
+static std::vector<int32_t> conv_tap_steps(const hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g) {
+    std::vector<int32_t> steps;
+    const i64 ph = g->pad_same ? g->fh / 2 : 0, pw = g->pad_same ? g->fw / 2 : 0;
+    for (uint32_t fy = 0; fy < g->fh; fy++)
+        for (uint32_t fx = 0; fx < g->fw; fx++)
+            steps.push_back(norm_step(ctx, ((i64)fy - ph) * in->h_stride + ((i64)fx - pw) * in->w_stride));
+    return steps;
+}
+
+static int write_steps(const std::vector<int32_t>& all, int32_t* steps, size_t cap, size_t* n) {
+    std::set<int32_t> uniq;
+    for (int32_t s : all)
+        if (s != 0) uniq.insert(s);
+    if (!n) return HISA_ERR_ARG;
+    *n = uniq.size();
+    if (steps) {
+        size_t i = 0;
+        for (int32_t s : uniq) {
+            if (i >= cap) return HISA_ERR_ARG;
+            steps[i++] = s;
+        }
+    }
+    return HISA_OK;
+}
+
+extern "C" int hisa_conv2d_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* geom, int32_t* steps,
+                                     size_t cap, size_t* n) {
+    if (!ctx || !in || !geom) return HISA_ERR_ARG;
+    return write_steps(conv_tap_steps(ctx, in, geom), steps, cap, n);
+}
+
+static int fc_window_log(const hisa_tensor* in) {
+    const u64 span = (u64)(in->height - 1) * in->h_stride + (u64)(in->width - 1) * in->w_stride;
+    int t = 0;
+    while (((u64)1 << t) < span + 1) t++;
+    return t;
+}
+
+extern "C" int hisa_fc_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n) {
+    if (!ctx || !in) return HISA_ERR_ARG;
+    std::vector<int32_t> all;
+    for (int t = 0; t < fc_window_log(in); t++) all.push_back(norm_step(ctx, (i64)1 << t));
+    return write_steps(all, steps, cap, n);
+}
+
+extern "C" int hisa_pool_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n) {
+    if (!ctx || !in) return HISA_ERR_ARG;
+    std::vector<int32_t> all = {norm_step(ctx, in->w_stride), norm_step(ctx, in->h_stride),
+                                norm_step(ctx, (i64)in->h_stride + in->w_stride)};
+    return write_steps(all, steps, cap, n);
+}
+
+// slots of the elements of a plane
+static std::vector<uint32_t> plane_slots(uint32_t h, uint32_t w, uint32_t hs, uint32_t ws, uint32_t off) {
+    std::vector<uint32_t> s;
+    for (uint32_t y = 0; y < h; y++)
+        for (uint32_t x = 0; x < w; x++) s.push_back(off + y * hs + x * ws);
+    return s;
+}
+
+// Encodes n_pts slot vectors that are non-zero only on `slots` (values[n_pts][slots.size()], host) into
+// NTT-form plaintexts out[n_pts][limbs][N] (device).
+static int encode_sparse_batch(hisa_ctx* ctx, const std::vector<uint32_t>& slots, const double* values, size_t n_pts,
+                               double scale, int limbs, u64* out) {
+    const size_t nnz = slots.size(), n = ctx->N;
+    std::vector<uint32_t> g(nnz);
+    const uint32_t mask = 2 * ctx->N - 1;
+    for (size_t i = 0; i < nnz; i++) {
+        uint32_t e = 1, b = 5, k = slots[i];
+        for (; k; k >>= 1, b = (b * b) & mask)
+            if (k & 1) e = (e * b) & mask;
+        g[i] = e;
+    }
+    Temp dg(ctx, nnz * sizeof(uint32_t));
+    Temp dv(ctx, n_pts * nnz * sizeof(double));
+    Temp co(ctx, n_pts * n * sizeof(i64));
+    if (!dg.ok() || !dv.ok() || !co.ok()) return HISA_ERR_OOM;
+    HIP_TRY(ctx, hipMemcpyAsync(dg.blk->ptr, g.data(), nnz * sizeof(uint32_t), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(dv.blk->ptr, values, n_pts * nnz * sizeof(double), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    // grid.y carries the plaintext index: stay below its limit
+    for (size_t p0 = 0; p0 < n_pts; p0 += 32768) {
+        const int cnt = (int)std::min<size_t>(32768, n_pts - p0);
+        HIP_TRY(ctx, launch_encode(ctx->d_cos, ctx->d_sin, dg.as<uint32_t>(), dv.as<double>() + p0 * nnz, nullptr, (int)nnz,
+                                   cnt, 2.0 * scale / (double)n, co.as<i64>() + p0 * n, (int)ctx->log_n, ctx->stream));
+        HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>() + p0 * n, out + p0 * limbs * n, limbs, cnt,
+                                       (int)ctx->log_n, ctx->stream));
+    }
+    for (size_t p0 = 0; p0 < n_pts; p0 += 4096)
+        HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, out + p0 * limbs * n, (u64)limbs * n,
+                                (int)(std::min<size_t>(4096, n_pts - p0) * limbs), identity_map(limbs), ctx->stream));
+    return HISA_OK;
+}
+
+// host signed coefficients [n_pts][N] -> NTT-form plaintexts out[n_pts][limbs][N]
+static int coeffs_to_plain_batch(hisa_ctx* ctx, const int64_t* host, size_t n_pts, int limbs, u64* out) {
+    const size_t n = ctx->N;
+    for (size_t p0 = 0; p0 < n_pts; p0 += 4096) {
+        const size_t cnt = std::min<size_t>(4096, n_pts - p0);
+        Temp co(ctx, cnt * n * sizeof(i64));
+        if (!co.ok()) return HISA_ERR_OOM;
+        HIP_TRY(ctx, hipMemcpyAsync(co.blk->ptr, host + p0 * n, cnt * n * sizeof(i64), hipMemcpyHostToDevice, ctx->stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>(), out + p0 * limbs * n, limbs, (int)cnt, (int)ctx->log_n,
+                                       ctx->stream));
+        HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, out + p0 * limbs * n, (u64)limbs * n, (int)(cnt * limbs),
+                                identity_map(limbs), ctx->stream));
+    }
+    return HISA_OK;
+}
+
+static u64 mod_i64(i64 v, u64 q) {
+    if (v >= 0) return (u64)v % q;
+    u64 m = ((u64)(-(v + 1)) + 1) % q;
+    return m ? q - m : 0;
+}
+
+static void fill_out_meta(hisa_tensor* out, uint32_t batch, uint32_t channels, uint32_t h, uint32_t w, uint32_t hs,
+                          uint32_t ws, uint32_t off, uint32_t clean) {
+    out->batch = batch; out->channels = channels; out->height = h; out->width = w;
+    out->h_stride = hs; out->w_stride = ws; out->offset = off; out->clean = clean;
+}
+
+// ---------------------------------------------------------------------------
+// conv2d
+// ---------------------------------------------------------------------------
+struct ConvPlan {
+    uint32_t out_h, out_w;
+    std::vector<int32_t> steps;
+};
+
+static int conv_plan(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, ConvPlan* p) {
+    if (!g || g->fh == 0 || g->fw == 0 || g->stride == 0 || g->fh * g->fw > MAX_TAPS || g->mode > HISA_CONV_PLAIN)
+        return fail(ctx, HISA_ERR_ARG, "bad conv geometry");
+    if (g->pad_same) {
+        if (!in->clean) return fail(ctx, HISA_ERR_ARG, "SAME padding needs a clean input tensor (zeros around the plane)");
+        p->out_h = (in->height + g->stride - 1) / g->stride;
+        p->out_w = (in->width + g->stride - 1) / g->stride;
+    } else {
+        if (in->height < g->fh || in->width < g->fw) return fail(ctx, HISA_ERR_ARG, "filter larger than the plane");
+        p->out_h = (in->height - g->fh) / g->stride + 1;
+        p->out_w = (in->width - g->fw) / g->stride + 1;
+    }
+    p->steps = conv_tap_steps(ctx, in, g);
+    return HISA_OK;
+}
+
+// d_w: SCALAR/MASKED residues [T][OC][l]; d_pts: MASKED [l][N], PLAIN [T][OC][l][N]
+static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
+                    const u64* d_w, double w_scale, const u64* d_pts, double pt_scale, hisa_tensor* out) {
+    const uint32_t B = in->batch, IC = in->channels, l = in->cts[0]->limbs;
+    const size_t nct = (size_t)B * IC, n = ctx->N;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
+    const int n_taps = (int)plan.steps.size();
+    BatchIn bi;
+    TRY(gather_batch(ctx, (const hisa_ct* const*)in->cts, nct, &bi));
+    std::vector<std::vector<hisa_ct*>> rotated(n_taps);
+    std::vector<hisa_ct*> outs((size_t)B * OC, nullptr);
+    MacArgs ma = {};
+    int rc = HISA_OK;
+    for (int t = 0; t < n_taps && rc == HISA_OK; t++) {
+        if (plan.steps[t] == 0) { ma.tap_base[t] = bi.base; continue; }
+        rotated[t].assign(nct, nullptr);
+        rc = hisa_rot_left_batch(ctx, (const hisa_ct* const*)in->cts, nct, plan.steps[t], rotated[t].data());
+        if (rc != HISA_OK) rotated[t].clear();
+        else ma.tap_base[t] = rotated[t][0]->data;
+    }
+    const double in_scale = in->cts[0]->scale;
+    double mac_scale = in_scale * (g->mode == HISA_CONV_PLAIN ? pt_scale : w_scale);
+    if (rc == HISA_OK) rc = alloc_ct_batch(ctx, (size_t)B * OC, 2, l, mac_scale, outs.data());
+    if (rc == HISA_OK) {
+        ma.n_taps = n_taps; ma.IC = (int)IC; ma.OC = (int)OC; ma.l = (int)l; ma.ct_words = 2 * (u64)l * n;
+        ma.out = outs[0]->data;
+        hipError_t e;
+        if (g->mode == HISA_CONV_PLAIN) {
+            ma.w = d_pts; ma.w_stride_t = OC; ma.w_stride_oc = 1;
+            e = launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+        } else {
+            ma.w = d_w;
+            e = launch_scalar_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+            if (e == hipSuccess && g->mode == HISA_CONV_MASKED) {
+                e = launch_mul_plain(ctx->d_primes, outs[0]->data, d_pts, outs[0]->data, (int)l, 2, (u64)B * OC, ma.ct_words,
+                                     ma.ct_words, (int)ctx->log_n, ctx->stream);
+                for (hisa_ct* c : outs) c->scale = mac_scale * pt_scale;
+            }
+        }
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));
+    }
+    for (auto& v : rotated) free_handles(ctx, v);
+    dev_release(ctx, bi.tmp);
+    if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
+    if (rc != HISA_OK) {
+        for (hisa_ct* c : outs) hisa_free(ctx, c);
+        return rc;
+    }
+    for (size_t i = 0; i < outs.size(); i++) out->cts[i] = outs[i];
+    fill_out_meta(out, B, OC, plan.out_h, plan.out_w, in->h_stride * g->stride, in->w_stride * g->stride, in->offset,
+                  g->mode == HISA_CONV_SCALAR ? 0u : 1u);
+    return HISA_OK;
+}
+
+static int upload_weight_residues(hisa_ctx* ctx, const int64_t* w_int, size_t count, uint32_t l, Temp& dst) {
+    std::vector<u64> res(count * l);
+    for (size_t i = 0; i < count; i++)
+        for (uint32_t k = 0; k < l; k++) res[i * l + k] = mod_i64(w_int[i], ctx->mod[k]);
+    HIP_TRY(ctx, hipMemcpyAsync(dst.blk->ptr, res.data(), res.size() * sizeof(u64), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HISA_OK;
+}
+
+extern "C" int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* w_int, double w_scale,
+                                 const int64_t* pt_coeffs, double pt_scale, uint32_t OC, const hisa_conv_geom* geom,
+                                 hisa_tensor* out) {
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts || OC == 0) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
+    ConvPlan plan;
+    TRY(conv_plan(ctx, in, geom, &plan));
+    const uint32_t l = in->cts[0]->limbs, IC = in->channels;
+    const size_t T = plan.steps.size() * IC, n = ctx->N;
+    if (geom->mode == HISA_CONV_PLAIN) {
+        if (!pt_coeffs) return fail(ctx, HISA_ERR_ARG, "PLAIN mode needs plaintext coefficients");
+        Temp pts(ctx, T * OC * l * n * sizeof(u64));
+        if (!pts.ok()) return HISA_ERR_OOM;
+        TRY(coeffs_to_plain_batch(ctx, pt_coeffs, T * OC, (int)l, pts.u()));
+        return conv_run(ctx, in, geom, plan, OC, nullptr, 1.0, pts.u(), pt_scale, out);
+    }
+    if (!w_int) return fail(ctx, HISA_ERR_ARG, "null weights");
+    Temp dw(ctx, T * OC * l * sizeof(u64));
+    if (!dw.ok()) return HISA_ERR_OOM;
+    TRY(upload_weight_residues(ctx, w_int, T * OC, l, dw));
+    if (geom->mode == HISA_CONV_MASKED) {
+        if (!pt_coeffs) return fail(ctx, HISA_ERR_ARG, "MASKED mode needs the mask plaintext");
+        Temp mask(ctx, (size_t)l * n * sizeof(u64));
+        if (!mask.ok()) return HISA_ERR_OOM;
+        TRY(coeffs_to_plain_batch(ctx, pt_coeffs, 1, (int)l, mask.u()));
+        return conv_run(ctx, in, geom, plan, OC, dw.u(), w_scale, mask.u(), pt_scale, out);
+    }
+    return conv_run(ctx, in, geom, plan, OC, dw.u(), w_scale, nullptr, 1.0, out);
+}
+
+extern "C" int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t OC, const hisa_conv_geom* geom,
+                           hisa_tensor* out) {
+    TRY(check_tensor(ctx, in));
+    if (!w || !out || !out->cts || OC == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    ConvPlan plan;
+    TRY(conv_plan(ctx, in, geom, &plan));
+    const uint32_t l = in->cts[0]->limbs, IC = in->channels;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
+    const size_t taps = plan.steps.size(), T = taps * IC, n = ctx->N;
+    const double q_last = (double)ctx->mod[l - 1];
+    const std::vector<uint32_t> vslots = plane_slots(plan.out_h, plan.out_w, in->h_stride * geom->stride,
+                                                     in->w_stride * geom->stride, in->offset);
+    if (geom->mode == HISA_CONV_PLAIN) {
+        // plaintext (tap, ic, oc) = weight on every valid output position, zero elsewhere, at scale q_last
+        Temp pts(ctx, T * OC * l * n * sizeof(u64));
+        if (!pts.ok()) return HISA_ERR_OOM;
+        std::vector<double> vals(T * OC * vslots.size());
+        for (size_t i = 0; i < T * OC; i++) std::fill_n(vals.begin() + i * vslots.size(), vslots.size(), w[i]);
+        TRY(encode_sparse_batch(ctx, vslots, vals.data(), T * OC, q_last, (int)l, pts.u()));
+        return conv_run(ctx, in, geom, plan, OC, nullptr, 1.0, pts.u(), q_last, out);
+    }
+    const double w_scale = geom->mode == HISA_CONV_MASKED ? q_last / HISA_MASK_SCALE : q_last;
+    std::vector<int64_t> w_int(T * OC);
+    for (size_t i = 0; i < T * OC; i++) {
+        const double v = w[i] * w_scale;
+        if (!(fabs(v) < 9.2e18)) return fail(ctx, HISA_ERR_ARG, "weight %g does not fit the fixed-point range", w[i]);
+        w_int[i] = (int64_t)round(v);
+    }
+    Temp dw(ctx, T * OC * l * sizeof(u64));
+    if (!dw.ok()) return HISA_ERR_OOM;
+    TRY(upload_weight_residues(ctx, w_int.data(), T * OC, l, dw));
+    if (geom->mode == HISA_CONV_MASKED) {
+        Temp mask(ctx, (size_t)l * n * sizeof(u64));
+        if (!mask.ok()) return HISA_ERR_OOM;
+        std::vector<double> ones(vslots.size(), 1.0);
+        TRY(encode_sparse_batch(ctx, vslots, ones.data(), 1, HISA_MASK_SCALE, (int)l, mask.u()));
+        return conv_run(ctx, in, geom, plan, OC, dw.u(), w_scale, mask.u(), HISA_MASK_SCALE, out);
+    }
+    return conv_run(ctx, in, geom, plan, OC, dw.u(), w_scale, nullptr, 1.0, out);
+}
+
+// ---------------------------------------------------------------------------
+// fully connected
+// ---------------------------------------------------------------------------
+// pts: NTT-form plaintexts [OUTC][C][l][N] for outputs o0 .. o0+OUTC-1
+static int fc_chunk(hisa_ctx* ctx, const hisa_tensor* in, const BatchIn& bi, const u64* pts, double pt_scale, uint32_t OUTC,
+                    hisa_ct** outs) {
+    const uint32_t B = in->batch, C = in->channels, l = in->cts[0]->limbs;
+    MacArgs ma = {};
+    ma.tap_base[0] = bi.base; ma.n_taps = 1; ma.IC = (int)C; ma.OC = (int)OUTC; ma.l = (int)l;
+    ma.ct_words = 2 * (u64)l * ctx->N;
+    ma.w = pts; ma.w_stride_t = 1; ma.w_stride_oc = C;
+    ma.out = outs[0]->data;
+    (void)pt_scale;
+    HIP_TRY(ctx, launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream));
+    return HISA_OK;
+}
+
+static int fc_finish(hisa_ctx* ctx, const hisa_tensor* in, std::vector<hisa_ct*>& outs, uint32_t OUT, hisa_tensor* out) {
+    int rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
+    // rotate-and-add over the power-of-two window that covers the plane: slot s ends up with the sum of
+    // slots s .. s + 2^T - 1, so slot `offset` holds the sum over all elements
+    for (int t = 0; t < fc_window_log(in) && rc == HISA_OK; t++) {
+        std::vector<hisa_ct*> rot(outs.size(), nullptr);
+        rc = hisa_rot_left_batch(ctx, (const hisa_ct* const*)outs.data(), outs.size(), norm_step(ctx, (i64)1 << t), rot.data());
+        if (rc != HISA_OK) break;
+        hipError_t e = launch_addsub(ctx->d_primes, outs[0]->data, rot[0]->data, outs[0]->data, OP_ADD, (int)outs[0]->limbs, 2,
+                                     2, outs.size(), ct_words(ctx, 2, outs[0]->limbs), ct_words(ctx, 2, outs[0]->limbs),
+                                     ct_words(ctx, 2, outs[0]->limbs), (int)ctx->log_n, ctx->stream);
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "fc add: %s", hipGetErrorString(e));
+        free_handles(ctx, rot);
+    }
+    if (rc != HISA_OK) {
+        free_handles(ctx, outs);
+        return rc;
+    }
+    for (size_t i = 0; i < outs.size(); i++) out->cts[i] = outs[i];
+    fill_out_meta(out, in->batch, OUT, 1, 1, 1, 1, in->offset, 0);
+    return HISA_OK;
+}
+
+static int fc_common(hisa_ctx* ctx, const hisa_tensor* in, const double* w, const int64_t* pt_coeffs, double pt_scale,
+                     uint32_t OUT, hisa_tensor* out) {
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts || OUT == 0) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
+    const uint32_t B = in->batch, C = in->channels, l = in->cts[0]->limbs;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "fc needs a level to rescale into");
+    const size_t n = ctx->N, hw = (size_t)in->height * in->width;
+    // the B*OUT accumulators must be one evenly spaced batch; the plaintexts are built OUTC outputs at a time
+    const size_t pt_bytes = (size_t)C * l * n * sizeof(u64);
+    const uint32_t OUTC = (uint32_t)std::max<size_t>(1, std::min<size_t>(OUT, ((size_t)2 << 30) / pt_bytes));
+    BatchIn bi;
+    TRY(gather_batch(ctx, (const hisa_ct* const*)in->cts, (size_t)B * C, &bi));
+    std::vector<hisa_ct*> outs((size_t)B * OUT, nullptr);
+    const double in_scale = in->cts[0]->scale;
+    int rc = alloc_ct_batch(ctx, outs.size(), 2, l, in_scale * pt_scale, outs.data());
+    const std::vector<uint32_t> slots = plane_slots(in->height, in->width, in->h_stride, in->w_stride, in->offset);
+    for (uint32_t o0 = 0; o0 < OUT && rc == HISA_OK; o0 += OUTC) {
+        const uint32_t cnt = std::min(OUTC, OUT - o0);
+        Temp pts(ctx, (size_t)cnt * pt_bytes);
+        if (!pts.ok()) { rc = HISA_ERR_OOM; break; }
+        if (w) rc = encode_sparse_batch(ctx, slots, w + (size_t)o0 * C * hw, (size_t)cnt * C, pt_scale, (int)l, pts.u());
+        else rc = coeffs_to_plain_batch(ctx, pt_coeffs + (size_t)o0 * C * n, (size_t)cnt * C, (int)l, pts.u());
+        if (rc != HISA_OK) break;
+        // accumulators of outputs o0.. for every image b: out index b*OUT + o  ->  launch per image
+        for (uint32_t b = 0; b < B && rc == HISA_OK; b++) {
+            BatchIn one = bi;
+            one.base = bi.base + (size_t)b * C * bi.stride;
+            hisa_tensor view = *in;
+            view.batch = 1;
+            rc = fc_chunk(ctx, &view, one, pts.u(), pt_scale, cnt, &outs[(size_t)b * OUT + o0]);
+        }
+    }
+    dev_release(ctx, bi.tmp);
+    if (rc != HISA_OK) {
+        free_handles(ctx, outs);
+        return rc;
+    }
+    return fc_finish(ctx, in, outs, OUT, out);
+}
+
+extern "C" int hisa_fc_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* pt_coeffs, double pt_scale, uint32_t OUT,
+                             hisa_tensor* out) {
+    if (!pt_coeffs) return fail(ctx, HISA_ERR_ARG, "null plaintext coefficients");
+    return fc_common(ctx, in, nullptr, pt_coeffs, pt_scale, OUT, out);
+}
+
+extern "C" int hisa_fc(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t OUT, hisa_tensor* out) {
+    if (!ctx || !in || !w) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    if (in->height == 1 && in->width == 1) {
+        // Algorithm 1 with a 1x1 filter: conv weights [1][1][IC][OC] = transposed fc weights [OUT][C]
+        std::vector<double> wt((size_t)in->channels * OUT);
+        for (uint32_t o = 0; o < OUT; o++)
+            for (uint32_t c = 0; c < in->channels; c++) wt[(size_t)c * OUT + o] = w[(size_t)o * in->channels + c];
+        hisa_conv_geom g = {1, 1, 1, 0, HISA_CONV_SCALAR};
+        return hisa_conv2d(ctx, in, wt.data(), OUT, &g, out);
+    }
+    TRY(check_tensor(ctx, in));
+    return fc_common(ctx, in, w, nullptr, (double)ctx->mod[in->cts[0]->limbs - 1], OUT, out);
+}
+
+// ---------------------------------------------------------------------------
+// pooling, activation
+// ---------------------------------------------------------------------------
+extern "C" int hisa_sum_pool2x2(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out) {
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts || in->height < 2 || in->width < 2) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    const size_t nct = (size_t)in->batch * in->channels;
+    const uint32_t l = in->cts[0]->limbs;
+    const u64 words = ct_words(ctx, 2, l);
+    std::vector<hisa_ct*> acc(nct, nullptr);
+    TRY(alloc_ct_batch(ctx, nct, 2, l, in->cts[0]->scale, acc.data()));
+    BatchIn bi;
+    int rc = gather_batch(ctx, (const hisa_ct* const*)in->cts, nct, &bi);
+    if (rc == HISA_OK) {
+        hipError_t e = hipMemcpyAsync(acc[0]->data, bi.base, nct * words * sizeof(u64), hipMemcpyDeviceToDevice, ctx->stream);
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "copy: %s", hipGetErrorString(e));
+    }
+    dev_release(ctx, bi.tmp);
+    const i64 shifts[3] = {(i64)in->w_stride, (i64)in->h_stride, (i64)in->h_stride + in->w_stride};
+    for (int k = 0; k < 3 && rc == HISA_OK; k++) {
+        std::vector<hisa_ct*> rot(nct, nullptr);
+        rc = hisa_rot_left_batch(ctx, (const hisa_ct* const*)in->cts, nct, norm_step(ctx, shifts[k]), rot.data());
+        if (rc != HISA_OK) break;
+        hipError_t e = launch_addsub(ctx->d_primes, acc[0]->data, rot[0]->data, acc[0]->data, OP_ADD, (int)l, 2, 2, nct, words,
+                                     words, words, (int)ctx->log_n, ctx->stream);
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "pool add: %s", hipGetErrorString(e));
+        free_handles(ctx, rot);
+    }
+    if (rc != HISA_OK) {
+        free_handles(ctx, acc);
+        return rc;
+    }
+    for (size_t i = 0; i < nct; i++) { acc[i]->scale = in->cts[i]->scale; out->cts[i] = acc[i]; }
+    fill_out_meta(out, in->batch, in->channels, in->height / 2, in->width / 2, in->h_stride * 2, in->w_stride * 2, in->offset, 0);
+    return HISA_OK;
+}
+
+extern "C" int hisa_poly2_act(hisa_ctx* ctx, const hisa_tensor* in, double a, double b, hisa_tensor* out) {
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts || a == 0.0 || !isfinite(b / a)) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    const size_t nct = (size_t)in->batch * in->channels;
+    const uint32_t l = in->cts[0]->limbs;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "activation needs a level to rescale into");
+    std::vector<hisa_ct*> sq(nct, nullptr);
+    TRY(hisa_mul_no_relin_batch(ctx, (const hisa_ct* const*)in->cts, (const hisa_ct* const*)in->cts, nct, sq.data()));
+    int rc = hisa_relinearize_batch(ctx, sq.data(), nct);
+    if (rc == HISA_OK && b != 0.0) {
+        // (b/a) * x at scale s * s: multiply every residue by round((b/a) * s)
+        const double s = in->cts[0]->scale, v = (b / a) * s;
+        const u64 words = ct_words(ctx, 2, l);
+        BatchIn bi;
+        rc = gather_batch(ctx, (const hisa_ct* const*)in->cts, nct, &bi);
+        Temp lin(ctx, nct * words * sizeof(u64));
+        if (rc == HISA_OK && !lin.ok()) rc = HISA_ERR_OOM;
+        if (rc == HISA_OK) {
+            u64 consts[2 * HISA_MAX_PRIMES];
+            for (uint32_t i = 0; i < l; i++) {
+                consts[i] = double_to_residue(v, ctx->mod[i]);
+                consts[l + i] = (u64)(((u128)consts[i] << 64) / ctx->mod[i]);
+            }
+            hipError_t e = launch_mul_const(ctx->d_primes, bi.base, lin.u(), consts, (int)l, (int)(nct * 2), (int)ctx->log_n,
+                                            ctx->stream);
+            if (e == hipSuccess)
+                e = launch_addsub(ctx->d_primes, sq[0]->data, lin.u(), sq[0]->data, OP_ADD, (int)l, 2, 2, nct, words, words, words,
+                                  (int)ctx->log_n, ctx->stream);
+            if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "activation: %s", hipGetErrorString(e));
+        }
+        dev_release(ctx, bi.tmp);
+    }
+    if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, sq.data(), nct);
+    if (rc != HISA_OK) {
+        free_handles(ctx, sq);
+        return rc;
+    }
+    for (size_t i = 0; i < nct; i++) out->cts[i] = sq[i];
+    fill_out_meta(out, in->batch, in->channels, in->height, in->width, in->h_stride, in->w_stride, in->offset, in->clean);
+    return HISA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// tensor <-> host
+// ---------------------------------------------------------------------------
+extern "C" int hisa_tensor_encrypt(hisa_ctx* ctx, const double* x, double scale, uint32_t limbs, hisa_tensor* t) {
+    if (!ctx || !x || !t || !t->cts || t->batch == 0 || t->channels == 0 || limbs < 1 || limbs > ctx->L)
+        return fail(ctx, HISA_ERR_ARG, "bad argument");
+    const u64 last = (u64)t->offset + (u64)(t->height - 1) * t->h_stride + (u64)(t->width - 1) * t->w_stride;
+    if (t->height == 0 || t->width == 0 || last >= ctx->N / 2) return fail(ctx, HISA_ERR_ARG, "plane does not fit the slots");
+    const size_t nct = (size_t)t->batch * t->channels, n = ctx->N;
+    const std::vector<uint32_t> slots = plane_slots(t->height, t->width, t->h_stride, t->w_stride, t->offset);
+    DevBlock* blk = dev_alloc(ctx, nct * limbs * n * sizeof(u64));
+    if (!blk) return HISA_ERR_OOM;
+    int rc = encode_sparse_batch(ctx, slots, x, nct, scale, (int)limbs, (u64*)blk->ptr);
+    std::vector<hisa_pt*> pts(nct, nullptr);
+    if (rc == HISA_OK) {
+        blk->refs = (int)nct + 1;
+        for (size_t i = 0; i < nct; i++)
+            pts[i] = new hisa_pt{HISA_MAGIC_PT, blk, (u64*)blk->ptr + i * limbs * n, limbs, scale};
+        rc = hisa_encrypt_batch(ctx, (const hisa_pt* const*)pts.data(), nct, t->cts);
+        for (hisa_pt* p : pts) hisa_free(ctx, p);
+    }
+    dev_release(ctx, blk);
+    if (rc == HISA_OK) t->clean = 1;
+    return rc;
+}
+
+extern "C" int hisa_tensor_decrypt(hisa_ctx* ctx, const hisa_tensor* t, double* x) {
+    TRY(check_tensor(ctx, t));
+    if (!x) return fail(ctx, HISA_ERR_ARG, "null output");
+    const size_t nct = (size_t)t->batch * t->channels, hw = (size_t)t->height * t->width;
+    const std::vector<uint32_t> slots = plane_slots(t->height, t->width, t->h_stride, t->w_stride, t->offset);
+    const size_t count = (size_t)slots.back() + 1;
+    std::vector<double> re(count);
+    for (size_t i = 0; i < nct; i++) {
+        hisa_pt* pt = nullptr;
+        TRY(hisa_decrypt(ctx, t->cts[i], &pt));
+        int rc = hisa_decode(ctx, pt, re.data(), nullptr, count);
+        hisa_free(ctx, pt);
+        if (rc != HISA_OK) return rc;
+        for (size_t k = 0; k < hw; k++) x[i * hw + k] = re[slots[k]];
+    }
+    return HISA_OK;
+}
+
+extern "C" int hisa_tensor_free(hisa_ctx* ctx, hisa_tensor* t) {
+    if (!ctx || !t) return HISA_ERR_ARG;
+    if (t->cts)
+        for (size_t i = 0; i < (size_t)t->batch * t->channels; i++) {
+            hisa_free(ctx, t->cts[i]);
+            t->cts[i] = nullptr;
+        }
+    return HISA_OK;
+}

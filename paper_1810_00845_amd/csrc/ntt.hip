@@ -121,6 +121,7 @@ __global__ __launch_bounds__(NT) void ntt_pass_kernel(PassArgs a, NttTables t, P
 static hipError_t run_pass(bool inv, PassArgs a, const NttTables& t, const PolyMap& map, int n_polys, hipStream_t st) {
     int tile_log = a.log_n < TILE_LOG ? a.log_n : TILE_LOG;
     dim3 grid((unsigned)n_polys << (a.log_n - tile_log));
+    ProfScope prof__(inv ? "ntt_pass_kernel<true>" : "ntt_pass_kernel<false>", st);
     if (inv) hipLaunchKernelGGL(ntt_pass_kernel<true>, grid, dim3(NT), 0, st, a, t, map);
     else hipLaunchKernelGGL(ntt_pass_kernel<false>, grid, dim3(NT), 0, st, a, t, map);
     return hipGetLastError();

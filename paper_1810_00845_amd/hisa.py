@@ -359,6 +359,96 @@ class Context:
         self._ck(load().hisa_ntt_raw(self._vp, C.c_void_p(dev_tensor.data_ptr()), C.c_uint32(prime_index),
                                      C.c_size_t(n_polys), C.c_int(1 if inverse else 0)))
 
+    # ---- tensor layer ----
+    def tensor_encrypt(self, x, scale, limbs, h_stride=None, w_stride=1, offset=0):
+        """x[batch][channels][height][width] -> clean HW-tiled CipherTensor."""
+        x = np.ascontiguousarray(x, dtype=np.float64)
+        b, c, h, w = x.shape
+        t = CipherTensor(self, [None] * (b * c), b, c, h, w, h_stride if h_stride else w * w_stride, w_stride, offset, 1)
+        st, arr = t._struct()
+        self._ck(load().hisa_tensor_encrypt(self._vp, _dp(x), C.c_double(scale), C.c_uint32(limbs), C.byref(st)))
+        t._adopt(st, arr)
+        return t
+
+    def tensor_decrypt(self, t):
+        out = np.zeros((t.batch, t.channels, t.height, t.width))
+        st, _arr = t._struct()
+        self._ck(load().hisa_tensor_decrypt(self._vp, C.byref(st), _dp(out)))
+        return out
+
+    def _layer(self, fn, t, n_out_cts, *args):
+        st, _arr = t._struct()
+        out = CipherTensor(self, [None] * n_out_cts, 0, 0, 0, 0, 0, 0, 0, 0)
+        ost, oarr = out._struct()
+        self._ck(getattr(load(), fn)(self._vp, C.byref(st), *args, C.byref(ost)))
+        out._adopt(ost, oarr)
+        return out
+
+    def conv2d(self, t, w, fh, fw, stride=1, pad_same=False, mode=CONV_SCALAR):
+        w = np.ascontiguousarray(w, dtype=np.float64)
+        assert w.shape[:3] == (fh, fw, t.channels)
+        oc = w.shape[3]
+        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode)
+        return self._layer("hisa_conv2d", t, t.batch * oc, _dp(w), C.c_uint32(oc), C.byref(g))
+
+    def conv2d_fixed(self, t, w_int, w_scale, pt_coeffs, pt_scale, oc, fh, fw, stride=1, pad_same=False, mode=CONV_SCALAR):
+        i64p = C.POINTER(C.c_int64)
+        wi = np.ascontiguousarray(w_int, dtype=np.int64) if w_int is not None else None
+        pc = np.ascontiguousarray(pt_coeffs, dtype=np.int64) if pt_coeffs is not None else None
+        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode)
+        return self._layer("hisa_conv2d_fixed", t, t.batch * oc, wi.ctypes.data_as(i64p) if wi is not None else None,
+                           C.c_double(w_scale), pc.ctypes.data_as(i64p) if pc is not None else None, C.c_double(pt_scale),
+                           C.c_uint32(oc), C.byref(g))
+
+    def fc(self, t, w):
+        w = np.ascontiguousarray(w, dtype=np.float64)
+        out_features = w.shape[0]
+        assert w.size == out_features * t.channels * t.height * t.width
+        return self._layer("hisa_fc", t, t.batch * out_features, _dp(w), C.c_uint32(out_features))
+
+    def fc_fixed(self, t, pt_coeffs, pt_scale):
+        pc = np.ascontiguousarray(pt_coeffs, dtype=np.int64)
+        out_features = pc.shape[0]
+        assert pc.shape == (out_features, t.channels, self.N)
+        return self._layer("hisa_fc_fixed", t, t.batch * out_features, pc.ctypes.data_as(C.POINTER(C.c_int64)),
+                           C.c_double(pt_scale), C.c_uint32(out_features))
+
+    def sum_pool2x2(self, t):
+        return self._layer("hisa_sum_pool2x2", t, t.batch * t.channels)
+
+    def poly2_act(self, t, a, b):
+        return self._layer("hisa_poly2_act", t, t.batch * t.channels, C.c_double(a), C.c_double(b))
+
+    def _steps(self, fn, t, *args):
+        st, _arr = t._struct()
+        buf = (C.c_int32 * 256)()
+        n = C.c_size_t()
+        self._ck(getattr(load(), fn)(self._vp, C.byref(st), *args, buf, C.c_size_t(256), C.byref(n)))
+        return [int(buf[i]) for i in range(n.value)]
+
+    def conv2d_rot_steps(self, t, fh, fw, stride=1, pad_same=False):
+        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, 0)
+        return self._steps("hisa_conv2d_rot_steps", t, C.byref(g))
+
+    def fc_rot_steps(self, t):
+        return self._steps("hisa_fc_rot_steps", t)
+
+    def pool_rot_steps(self, t):
+        return self._steps("hisa_pool_rot_steps", t)
+
+    def profile_enable(self, on=True):
+        self._ck(load().hisa_profile_enable(self._vp, C.c_int(1 if on else 0)))
+
+    def profile_read(self):
+        """{kernel name: (launches, total ms)} since the last read."""
+        buf = C.create_string_buffer(1 << 16)
+        self._ck(load().hisa_profile_read(self._vp, buf, C.c_size_t(len(buf))))
+        out = {}
+        for line in buf.value.decode().splitlines():
+            name, cnt, ms = line.split("\t")
+            out[name] = (int(cnt), float(ms))
+        return out
+
     def key_export(self, key_id):
         out = np.zeros((self.dnum, 2, self.L + self.K, self.N), dtype=np.uint64)
         self._ck(load().hisa_key_export(self._vp, C.c_uint64(key_id), out.ctypes.data_as(C.POINTER(C.c_uint64))))
@@ -368,3 +458,39 @@ class Context:
         out = np.zeros(self.N, dtype=np.int64)
         self._ck(load().hisa_secret_export(self._vp, out.ctypes.data_as(C.POINTER(C.c_int64))))
         return out
+
+
+class CipherTensor:
+    """Vector of ciphertexts + layout metadata (the paper's CipherTensor, HW-tiled)."""
+
+    def __init__(self, ctx, cts, batch, channels, height, width, h_stride, w_stride, offset, clean):
+        self.ctx, self.cts = ctx, cts
+        self.batch, self.channels, self.height, self.width = batch, channels, height, width
+        self.h_stride, self.w_stride, self.offset, self.clean = h_stride, w_stride, offset, clean
+
+    def meta(self):
+        return (self.batch, self.channels, self.height, self.width, self.h_stride, self.w_stride, self.offset, self.clean)
+
+    def shaped_like(self, cts=None, **kw):
+        t = CipherTensor(self.ctx, self.cts if cts is None else cts, *self.meta())
+        for k, v in kw.items():
+            setattr(t, k, v)
+        return t
+
+    def _struct(self):
+        n = len(self.cts)
+        arr = (C.c_void_p * n)(*[(c.h if c is not None else None) for c in self.cts])
+        st = TensorStruct(self.batch, self.channels, self.height, self.width, self.h_stride, self.w_stride, self.offset,
+                          self.clean, C.cast(arr, C.POINTER(C.c_void_p)))
+        return st, arr
+
+    def _adopt(self, st, arr):
+        self.batch, self.channels, self.height, self.width = st.batch, st.channels, st.height, st.width
+        self.h_stride, self.w_stride, self.offset, self.clean = st.h_stride, st.w_stride, st.offset, st.clean
+        self.cts = [Ciphertext(self.ctx, int(arr[i])) for i in range(len(arr))]
+
+    def free(self):
+        for c in self.cts:
+            if c is not None:
+                c.free()
+        self.cts = []

@@ -1,0 +1,113 @@
+"""Pins of the oracle's tensor layers against fp64 plaintext tensor arithmetic (no GPU).
+
+The encrypted layer, decrypted, must agree with the plain layer to 1e-3 on the
+value ranges of the workloads; the instruction counts must be those of
+Algorithm 1.
+"""
+import numpy as np
+import pytest
+
+import plain_net
+from oracle import Oracle, layers
+from paper_1810_00845_amd import synth
+
+
+def config1_oracle(seed=1):
+    o = Oracle(12, [30, 30, 30], 3, 60, seed)
+    return o
+
+
+# (MASKED splits the last modulus into weight scale x mask scale 2^25: it needs ~50-bit primes, not these 30-bit ones)
+@pytest.mark.parametrize("mode", [layers.CONV_PLAIN, layers.CONV_SCALAR])
+def test_config1_conv_matches_plain_conv_and_op_counts(mode):
+    o = config1_oracle()
+    x = synth.image(1, 1, 8, 8)[None]                    # [1][1][8][8], row-major in the slots
+    w = synth.conv_weights(2, 3, 3, 1, 1)
+    t = layers.tensor_encrypt(o, x, 2.0 ** 25, 3)
+    assert (t.h_stride, t.w_stride, t.offset) == (8, 1, 0)
+    o.gen_rot_keys(layers.rot_steps_conv(o, t, 3, 3))
+    assert len(o.keys) == 8                               # nine taps, the (0,0) tap needs no key
+    counts = {"rot": 0, "ks": 0, "mul": 0, "add": 0, "rescale": 0}
+    real = {n: getattr(o, n) for n in ("rot_left", "mul_plain", "mul_int", "add", "div_scalar")}
+    def wrap(name, key, extra=None):
+        def f(*a, **k):
+            counts[key] += 1
+            if extra:
+                extra(*a)
+            return real[name](*a, **k)
+        setattr(o, name, f)
+    wrap("rot_left", "rot", lambda ct, r: counts.__setitem__("ks", counts["ks"] + (r % o.slots != 0)))
+    wrap("mul_plain", "mul"); wrap("mul_int", "mul"); wrap("add", "add"); wrap("div_scalar", "rescale")
+    out, ints = layers.conv2d(o, t, w, mode=mode)
+    assert counts["rot"] == 9 and counts["ks"] == 8 and counts["add"] == 8 and counts["rescale"] == 1
+    assert counts["mul"] == 9
+    assert (out.height, out.width, out.channels, out.h_stride) == (6, 6, 1, 8)
+    assert out.cts[0].limbs == 2 and abs(out.cts[0].scale - 2.0 ** 25) < 1e-6 * 2.0 ** 25
+    got = layers.tensor_decrypt(o, out)
+    want = plain_net.conv2d(x, w)
+    assert np.abs(got - want).max() <= 1e-3
+    if mode != layers.CONV_SCALAR:                        # masked modes leave zeros off the valid positions
+        z = o.decode(o.decrypt(out.cts[0])).real
+        z[layers.plane_slots(6, 6, 8, 1, 0)] = 0
+        assert np.abs(z).max() <= 1e-3
+
+
+def test_strided_same_multichannel_conv():
+    o = Oracle(11, [45, 45, 45], 3, 50, seed=3)
+    x = synth.image(3, 2, 6, 6)[None]                     # 2 channels, 6x6 planes
+    w = synth.conv_weights(4, 3, 3, 2, 3)
+    # SAME padding: the plane sits inside a border of one zero slot (row stride 8, first element at slot 9)
+    t = layers.tensor_encrypt(o, x, 2.0 ** 40, 3, h_stride=8, w_stride=1, offset=9)
+    o.gen_rot_keys(layers.rot_steps_conv(o, t, 3, 3, pad_same=True))
+    out, _ = layers.conv2d(o, t, w, stride=1, pad_same=True, mode=layers.CONV_MASKED)
+    assert (out.height, out.width, out.clean) == (6, 6, 1)
+    assert np.abs(layers.tensor_decrypt(o, out) - plain_net.conv2d(x, w, pad_same=True)).max() <= 1e-3
+    # a second SAME conv on the clean output, stride 2
+    w2 = synth.conv_weights(5, 3, 3, 3, 2)
+    out2, _ = layers.conv2d(o, out, w2, stride=2, pad_same=True, mode=layers.CONV_MASKED)
+    want2 = plain_net.conv2d(plain_net.conv2d(x, w, pad_same=True), w2, stride=2, pad_same=True)
+    assert (out2.height, out2.width, out2.h_stride, out2.w_stride) == (3, 3, 16, 2)
+    assert np.abs(layers.tensor_decrypt(o, out2) - want2).max() <= 1e-3
+    # VALID, stride 2, literal Algorithm 1
+    o.gen_rot_keys(layers.rot_steps_conv(o, t, 3, 3))
+    out3, _ = layers.conv2d(o, t, w, stride=2, mode=layers.CONV_SCALAR)
+    assert (out3.height, out3.width, out3.h_stride, out3.w_stride) == (2, 2, 16, 2)
+    assert np.abs(layers.tensor_decrypt(o, out3) - plain_net.conv2d(x, w, stride=2)).max() <= 1e-3
+
+
+def test_fc_pool_activation_chain():
+    o = Oracle(11, [50, 45, 45, 45, 45], 5, 55, seed=4)
+    o.keygen()
+    x = synth.image(6, 2, 4, 4)[None]
+    t = layers.tensor_encrypt(o, x, 2.0 ** 45, 5)
+    # activation 0.3 x^2 + 0.2 x, without its leading factor
+    act = layers.poly2_act(o, t, 0.3, 0.2)
+    ref = plain_net.poly2_act_without_a(x, 0.3, 0.2)
+    assert act.cts[0].limbs == 4 and np.abs(layers.tensor_decrypt(o, act) - ref).max() <= 1e-3
+    # sum pool
+    o.gen_rot_keys([1, 4, 5])
+    pool = layers.sum_pool2x2(o, act)
+    ref = plain_net.sum_pool2x2(ref)
+    assert (pool.height, pool.h_stride, pool.w_stride) == (2, 8, 2)
+    assert np.abs(layers.tensor_decrypt(o, pool) - ref).max() <= 1e-3
+    # fully connected over 2 channels x 2 x 2 elements -> 3 outputs, then 3 -> 2 on 1x1 planes
+    w1 = synth.fc_weights(7, 3, 2, 2, 2, std=0.3)
+    o.gen_rot_keys([1, 2, 4, 8])
+    f1, _ = layers.fc(o, pool, w1)
+    ref1 = plain_net.fc(ref, w1)
+    assert (f1.channels, f1.height, f1.width) == (3, 1, 1)
+    assert np.abs(layers.tensor_decrypt(o, f1) - ref1).max() <= 1e-3
+    w2 = synth.fc_weights(8, 2, 3, 1, 1, std=0.5)
+    f2, _ = layers.fc(o, f1, w2)
+    assert f2.cts[0].limbs == 2
+    assert np.abs(layers.tensor_decrypt(o, f2) - plain_net.fc(ref1, w2)).max() <= 1e-3
+
+
+def test_plain_reference_conv_is_cross_correlation():
+    x = np.zeros((1, 1, 4, 4)); x[0, 0, 1, 2] = 1.0
+    w = np.arange(9.0).reshape(3, 3, 1, 1)
+    out = plain_net.conv2d(x, w)
+    # output (y, x) = sum_ij w[i][j] x[y+i][x+j]: the impulse at (1,2) meets w[1-y][2-x]
+    assert out[0, 0].tolist() == [[5.0, 4.0], [2.0, 1.0]]
+    same = plain_net.conv2d(x, w, pad_same=True)
+    assert same.shape == (1, 1, 4, 4) and same[0, 0, 1, 2] == 4.0 and same[0, 0, 2, 3] == 0.0 and same[0, 0, 0, 1] == 8.0
