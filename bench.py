@@ -90,7 +90,7 @@ def main():
     ap.add_argument("--dnum", type=int, default=3)
     ap.add_argument("--bits", type=int, default=50)
     ap.add_argument("--batch", type=int, default=64)
-    ap.add_argument("--cpu-sample", type=int, default=8, help="ciphertexts for the oracle baseline (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=32, help="ciphertexts for the oracle baseline (0 = skip)")
     ap.add_argument("--no-ops", action="store_true", help="skip the per-primitive timings")
     args = ap.parse_args()
     if args.gpus != 1:
