@@ -38,6 +38,12 @@ def algorithmic_bytes_rot_left(N, l, K, alpha, B):
     out["copy_limbs_kernel"] = 2 * l * LP * B
     out["inner_product_kernel"] = LP * (B * (digits * ext + 2 * ext) + digits * 2 * ext)
     out["moddown_final_kernel"] = 7 * l * LP * B
+    # fused fp64 pipeline (primes below 2^50): what each launch set must read and write once
+    conv_out = sum(ext - a for a in sizes)
+    out["ntt_fp_kernel<inv_to_y>"] = 2 * LP * B * (l + 2 * K)
+    out["ntt_fp_kernel<conv_fwd>"] = LP * B * (l + conv_out)
+    out["inner_product_fp_kernel"] = LP * (B * (conv_out + l + 2 * ext) + digits * 2 * ext)
+    out["ntt_fp_kernel<conv_fwd_final>"] = LP * B * (2 * K + 2 * l + l + 2 * l)
     return out
 
 

@@ -264,6 +264,8 @@ static hipError_t upload(T** dst, const std::vector<T>& src) {
     return hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice);
 }
 
+static double centred_double(u64 x, u64 q) { return x > q / 2 ? -(double)(q - x) : (double)x; }
+
 static void build_conv_table_host(const hisa_ctx* ctx, const std::vector<int>& src, std::vector<u64>& inv_hat,
                                   std::vector<u64>& inv_hat_sh, std::vector<u64>& hat, std::vector<u64>& dmod) {
     const int a = (int)src.size(), total = (int)ctx->total;
@@ -301,10 +303,18 @@ static int make_conv_table(hisa_ctx* ctx, const std::vector<int>& src, ConvTable
     HIP_TRY(ctx, upload(&tab->d_inv_hat_sh, ihs));
     HIP_TRY(ctx, upload(&tab->d_hat, hat));
     HIP_TRY(ctx, upload(&tab->d_dmod, dmod));
+    tab->d_hat_f = nullptr;
+    if (ctx->tabs.fp_ok) {
+        std::vector<double> hf(hat.size());
+        for (int i = 0; i < tab->a; i++)
+            for (uint32_t t = 0; t < ctx->total; t++) hf[(size_t)i * ctx->total + t] = centred_double(hat[(size_t)i * ctx->total + t], ctx->mod[t]);
+        HIP_TRY(ctx, upload(&tab->d_hat_f, hf));
+    }
     return HISA_OK;
 }
 
 static void free_conv_table(ConvTable* t) {
+    (void)hipFree(t->d_hat_f);
     (void)hipFree(t->d_inv_hat); (void)hipFree(t->d_inv_hat_sh); (void)hipFree(t->d_hat); (void)hipFree(t->d_dmod);
 }
 
@@ -382,7 +392,37 @@ extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** 
     HIP_TRY(ctx, upload(&ctx->d_tw_sh, tw_sh));
     HIP_TRY(ctx, upload(&ctx->d_itw, itw));
     HIP_TRY(ctx, upload(&ctx->d_itw_sh, itw_sh));
-    ctx->tabs = NttTables{ctx->d_primes, ctx->d_tw, ctx->d_tw_sh, ctx->d_itw, ctx->d_itw_sh};
+    ctx->tabs = NttTables{ctx->d_primes, ctx->d_tw, ctx->d_tw_sh, ctx->d_itw, ctx->d_itw_sh, 0, nullptr, nullptr, nullptr, nullptr};
+    // fp64 path: every prime below 2^50 and a ring degree the single-launch transform covers
+    {
+        bool fp_ok = ctx->log_n >= 12 && ctx->log_n <= 15;
+        for (u64 q : ctx->mod) fp_ok = fp_ok && q < ((u64)1 << 50);
+        if (fp_ok) {
+            std::vector<FpPrime> fpr(ctx->total);
+            std::vector<double> ftw(tw.size()), utw(tw.size()), vtw(tw.size()), pinv_f(ctx->total, 0.0);
+            for (uint32_t i = 0; i < ctx->total; i++) {
+                const u64 q = ctx->mod[i];
+                fpr[i].p = (double)q; fpr[i].pinv = 1.0 / (double)q; fpr[i].half = (double)(q / 2);
+                const u64 psi_inv = hm::inv(ctx->psi[i], q);
+                bwd[0] = 1;
+                for (u64 e = 1; e < n; e++) bwd[e] = hm::mul(bwd[e - 1], psi_inv, q);   // psi^-e
+                const size_t o = (size_t)i * n;
+                for (u64 x = 0; x < n; x++) {
+                    ftw[o + x] = centred_double(tw[o + x], q);
+                    vtw[o + x] = centred_double(hm::mul(bwd[x], ctx->pc[i].n_inv, q), q);
+                }
+                utw[o] = 0.0;
+                for (u64 m = 1; m < n; m <<= 1)   // psi^(-k N/m), k < m: exponents stay below N
+                    for (u64 k = 0; k < m; k++) utw[o + m + k] = centred_double(bwd[k * (n / m)], q);
+            }
+            HIP_TRY(ctx, upload(&ctx->d_fprimes, fpr));
+            HIP_TRY(ctx, upload(&ctx->d_ftw, ftw));
+            HIP_TRY(ctx, upload(&ctx->d_utw, utw));
+            HIP_TRY(ctx, upload(&ctx->d_vtw, vtw));
+            ctx->tabs.fp_ok = 1; ctx->tabs.fprimes = ctx->d_fprimes;
+            ctx->tabs.ftw = ctx->d_ftw; ctx->tabs.utw = ctx->d_utw; ctx->tabs.vtw = ctx->d_vtw;
+        }
+    }
 
     // mod-down: source = the special primes; P^-1 and P modulo every q_i
     {
@@ -401,6 +441,11 @@ extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** 
         HIP_TRY(ctx, upload(&ctx->d_pinv, pinv));
         HIP_TRY(ctx, upload(&ctx->d_pinv_sh, pinv_sh));
         HIP_TRY(ctx, upload(&ctx->d_pmod, pmod));
+        if (ctx->tabs.fp_ok) {
+            std::vector<double> pf(ctx->total, 0.0);
+            for (uint32_t i = 0; i < ctx->L; i++) pf[i] = centred_double(pinv[i], ctx->mod[i]);
+            HIP_TRY(ctx, upload(&ctx->d_pinv_f, pf));
+        }
     }
     // 2N-th roots of unity for encode / decode
     {
@@ -435,6 +480,8 @@ extern "C" int hisa_destroy(hisa_ctx* ctx) {
     if (ctx->moddown_tab) { free_conv_table(ctx->moddown_tab); delete ctx->moddown_tab; }
     (void)hipFree(ctx->d_primes); (void)hipFree(ctx->d_tw); (void)hipFree(ctx->d_tw_sh); (void)hipFree(ctx->d_itw);
     (void)hipFree(ctx->d_itw_sh); (void)hipFree(ctx->d_secret); (void)hipFree(ctx->d_pinv); (void)hipFree(ctx->d_pinv_sh);
+    (void)hipFree(ctx->d_fprimes); (void)hipFree(ctx->d_ftw); (void)hipFree(ctx->d_utw); (void)hipFree(ctx->d_vtw);
+    (void)hipFree(ctx->d_pinv_f);
     (void)hipFree(ctx->d_pmod); (void)hipFree(ctx->d_cos); (void)hipFree(ctx->d_sin); (void)hipFree(ctx->d_pow5);
     delete ctx;
     return HISA_OK;
@@ -1061,6 +1108,103 @@ static int key_switch_core(hisa_ctx* ctx, const u64* d, u64 d_bs, size_t B, int 
     return HISA_OK;
 }
 
+// (D_j/q_i)^-1 of every limb at level l (and (P/p_m)^-1 of the special primes) as centred doubles, device resident
+static int fp_post_tables(hisa_ctx* ctx, int l, double** post_q, double** post_p) {
+    const u64 KEY = 4096 + (u64)l;
+    auto it = ctx->aux.find(KEY);
+    if (it == ctx->aux.end()) {
+        std::vector<double> t((size_t)l + ctx->K);
+        const int digits = (l + (int)ctx->alpha - 1) / (int)ctx->alpha;
+        for (int j = 0; j < digits; j++) {
+            const int lo = j * (int)ctx->alpha, hi = std::min(lo + (int)ctx->alpha, l);
+            ConvTable* tab;
+            TRY(modup_table(ctx, j, hi - lo, &tab));
+            for (int i = lo; i < hi; i++) t[i] = centred_double(tab->inv_hat[i - lo], ctx->mod[i]);
+        }
+        for (uint32_t m = 0; m < ctx->K; m++) t[l + m] = centred_double(ctx->moddown_tab->inv_hat[m], ctx->mod[ctx->L + m]);
+        double* d = nullptr;
+        HIP_TRY(ctx, upload(&d, t));
+        it = ctx->aux.emplace(KEY, SwitchKey{new DevBlock{d, t.size() * sizeof(double), 1}, (u64*)d}).first;
+    }
+    *post_q = (double*)it->second.data;
+    *post_p = (double*)it->second.data + l;
+    return HISA_OK;
+}
+
+// Hybrid key switch of B polynomials with the fused fp64 kernels (all primes below 2^50):
+//   A  inverse transform of d (read through sigma_g if galois != 0) times (D_j/q_i)^-1  -> y, centred doubles
+//   B  per digit: base conversion of y to every other prime fused into the forward transform -> ext
+//   IP inner product with the key; a digit's own limbs are read from d itself             -> acc (l + K limbs, b|a)
+//   C  inverse transform of the K special limbs of acc times (P/p_m)^-1                    -> y2
+//   D  base conversion of y2 to q_i fused into the forward transform, then (acc - conv) P^-1 + addend -> out
+static int key_switch_core_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois, size_t B, int l, const SwitchKey& key,
+                              const u64* add, u64 add_bs, int add_polys, u64* out) {
+    const size_t n = ctx->N;
+    const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total;
+    const int ext_limbs = l + K, digits = (l + alpha - 1) / alpha, log_n = (int)ctx->log_n;
+    hipStream_t st = ctx->stream;
+    Temp y(ctx, B * l * n * sizeof(double));
+    Temp ext(ctx, B * (size_t)digits * ext_limbs * n * sizeof(u64));
+    Temp acc(ctx, B * 2 * (size_t)ext_limbs * n * sizeof(u64));
+    Temp y2(ctx, B * 2 * (size_t)K * n * sizeof(double));
+    if (!y.ok() || !ext.ok() || !acc.ok() || !y2.ok()) return HISA_ERR_OOM;
+    double *post_q, *post_p;
+    TRY(fp_post_tables(ctx, l, &post_q, &post_p));
+    FpArgs base = {};
+    base.fprimes = ctx->tabs.fprimes; base.ftw = ctx->tabs.ftw; base.utw = ctx->tabs.utw; base.vtw = ctx->tabs.vtw;
+    {   // A
+        FpArgs a = base;
+        FpTask tk = {};
+        tk.period = l;
+        for (int i = 0; i < l; i++) { tk.pos[i] = (int16_t)i; tk.prime[i] = (int16_t)i; }
+        a.in = d; a.in_bs = d_bs; a.galois = galois; a.post = post_q;
+        a.yout = y.as<double>(); a.yout_bs = (u64)l * n;
+        HIP_TRY(ctx, launch_ntt_fp(FP_INV_TO_Y, log_n, a, tk, B, st));
+    }
+    const u64 ext_bs = (u64)digits * ext_limbs * n;
+    for (int j = 0; j < digits; j++) {  // B
+        const int lo = j * alpha, hi = std::min(lo + alpha, l);
+        ConvTable* tab;
+        TRY(modup_table(ctx, j, hi - lo, &tab));
+        FpArgs a = base;
+        FpTask tk = {};
+        int cnt = 0;
+        for (int x = 0; x < ext_limbs; x++) {
+            if (x >= lo && x < hi) continue;
+            tk.pos[cnt] = (int16_t)(j * ext_limbs + x);
+            tk.prime[cnt] = (int16_t)(x < l ? x : L + (x - l));
+            cnt++;
+        }
+        tk.period = cnt;
+        a.y = y.as<double>(); a.y_bs = (u64)l * n; a.y_pos0 = lo; a.conv_a = hi - lo; a.total = total; a.hat = tab->d_hat_f;
+        a.out = ext.u(); a.out_bs = ext_bs;
+        HIP_TRY(ctx, launch_ntt_fp(FP_FWD_CONV, log_n, a, tk, B, st));
+    }
+    HIP_TRY(ctx, launch_inner_product_fp(ctx->tabs.fprimes, ext.u(), ext_bs, digits, l, K, L, alpha, key.data, total, d, d_bs,
+                                         galois, acc.u(), (u64)2 * ext_limbs * n, B, log_n, st));
+    {   // C: batch entries are (ciphertext, b|a) pairs
+        FpArgs a = base;
+        FpTask tk = {};
+        tk.period = K;
+        for (int m = 0; m < K; m++) { tk.pos[m] = (int16_t)m; tk.prime[m] = (int16_t)(L + m); }
+        a.in = acc.u(); a.in_bs = (u64)ext_limbs * n; a.in_pos_shift = l; a.post = post_p;
+        a.yout = y2.as<double>(); a.yout_bs = (u64)K * n;
+        HIP_TRY(ctx, launch_ntt_fp(FP_INV_TO_Y, log_n, a, tk, B * 2, st));
+    }
+    {   // D
+        FpArgs a = base;
+        FpTask tk = {};
+        tk.period = l;
+        for (int i = 0; i < l; i++) { tk.pos[i] = (int16_t)i; tk.prime[i] = (int16_t)i; }
+        a.y = y2.as<double>(); a.y_bs = (u64)K * n; a.y_pos0 = 0; a.conv_a = K; a.total = total; a.hat = ctx->moddown_tab->d_hat_f;
+        a.acc = acc.u(); a.acc_bs = (u64)ext_limbs * n; a.acc_pos_shift = 0; a.pinv_tab = ctx->d_pinv_f;
+        a.add = add; a.add_bs = add_bs; a.add_ps = (u64)l * n; a.add_div = 2; a.add_polys = add_polys; a.add_galois = galois;
+        a.out = out; a.out_bs = (u64)l * n;
+        HIP_TRY(ctx, launch_ntt_fp(FP_FWD_CONV_FINAL, log_n, a, tk, B * 2, st));
+    }
+    return HISA_OK;
+}
+
 extern "C" int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n, int32_t steps, hisa_ct** out) {
     if (!ctx || !out) return fail(ctx, HISA_ERR_ARG, "bad argument");
     TRY(check_batch_shape(ctx, in, n, 2));
@@ -1082,7 +1226,14 @@ extern "C" int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size
     TRY(gather_batch(ctx, in, n, &bi));
     const size_t nn = ctx->N, lw = (size_t)l * nn;
     int rc = HISA_OK;
-    {
+    if (ctx->tabs.fp_ok) {
+        // fused fp64 pipeline: both automorphisms are gathers inside its first and last kernels
+        rc = alloc_ct_batch(ctx, n, 2, (uint32_t)l, 0.0, out);
+        if (rc == HISA_OK) {
+            for (size_t i = 0; i < n; i++) out[i]->scale = in[i]->scale;
+            rc = key_switch_core_fp(ctx, bi.base + lw, bi.stride, g, n, l, it->second, bi.base, bi.stride, 1, out[0]->data);
+        }
+    } else {
         // sigma_g(c1) in NTT form (a gather); sigma_g(c0) is gathered inside the last kernel
         Temp r1(ctx, n * lw * sizeof(u64));
         if (!r1.ok()) rc = HISA_ERR_OOM;
@@ -1141,7 +1292,10 @@ extern "C" int hisa_relinearize_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t
     std::vector<hisa_ct*> fresh(n);
     int rc = alloc_ct_batch(ctx, n, 2, (uint32_t)l, 0.0, fresh.data());
     if (rc == HISA_OK) {
-        rc = key_switch_core(ctx, bi.base + 2 * lw, bi.stride, n, l, it->second, bi.base, bi.stride, 2, 0, fresh[0]->data);
+        if (ctx->tabs.fp_ok)
+            rc = key_switch_core_fp(ctx, bi.base + 2 * lw, bi.stride, 0, n, l, it->second, bi.base, bi.stride, 2, fresh[0]->data);
+        else
+            rc = key_switch_core(ctx, bi.base + 2 * lw, bi.stride, n, l, it->second, bi.base, bi.stride, 2, 0, fresh[0]->data);
         for (size_t i = 0; i < n; i++) {
             fresh[i]->scale = cts[i]->scale;
             if (rc == HISA_OK) adopt(ctx, cts[i], fresh[i]);

@@ -24,6 +24,11 @@ struct PrimeConst {
     u64 half;          // floor(q / 2)
 };
 
+// fp64 view of a prime below 2^50 (exact modular arithmetic in doubles)
+struct FpPrime {
+    double p, pinv, half;
+};
+
 // Device pointers to the per-prime tables, [prime][N] each.
 struct NttTables {
     const PrimeConst* primes;
@@ -31,6 +36,12 @@ struct NttTables {
     const u64* tw_sh;  // Shoup companions
     const u64* itw;    // psi^-bitrev(i)
     const u64* itw_sh;
+    // fp64 path (all primes below 2^50, 12 <= log2 N <= 15), else fp_ok = 0 and the pointers are null
+    int fp_ok;
+    const FpPrime* fprimes;
+    const double* ftw;  // psi^bitrev(i), centred
+    const double* utw;  // utw[m + k] = psi^(-k N/m), k < m = 2^t: inverse decimation-in-time twiddles
+    const double* vtw;  // psi^-j / N
 };
 
 // Which polynomials a batched NTT launch touches: polynomial p (0 <= p <
@@ -61,6 +72,7 @@ struct ConvTable {
     u64* d_hat;         // [a][total]  (D/c_i) mod t
     u64* d_dmod;        // [total]     D mod t
     std::vector<u64> inv_hat; // host copy
+    double* d_hat_f;    // [a][total]  (D/c_i) mod t as centred doubles (fp64 path), may be null
 };
 
 struct DevBlock {
@@ -111,6 +123,8 @@ struct hisa_ctx {
     u64* d_pinv_sh;
     u64* d_pmod;      // [L] P mod q_i
     double *d_cos, *d_sin;  // [2N] roots of unity exp(i*pi*t/N)
+    FpPrime* d_fprimes;     // fp64 path tables (null when not applicable)
+    double *d_ftw, *d_utw, *d_vtw, *d_pinv_f;
     uint32_t* d_pow5;       // [N/2] 5^j mod 2N
     std::unordered_map<size_t, std::vector<void*>> pool;
     size_t pool_bytes;
@@ -188,6 +202,50 @@ hipError_t launch_ntt(const NttTables& t, int log_n, u64* data, u64 batch_stride
                       hipStream_t st);
 hipError_t launch_intt(const NttTables& t, int log_n, u64* data, u64 batch_stride, int n_polys, const PolyMap& map,
                        const InttExtra* extra, hipStream_t st);
+
+// ---- fp64 single-launch transforms with fused neighbours (ntt_fp.hip) ----
+enum FpMode {
+    FP_FWD_PLAIN = 0,      // u64 coefficients in, u64 NTT form out
+    FP_INV_PLAIN = 1,      // u64 NTT form in (optionally gathered through sigma_g), u64 coefficients out
+    FP_INV_TO_Y = 2,       // as INV_PLAIN, times a per-limb constant, output = centred doubles (input of base conversion)
+    FP_FWD_CONV = 3,       // input = fast base conversion of `a` source limbs (centred doubles), u64 NTT form out
+    FP_FWD_CONV_FINAL = 4  // as FWD_CONV, then out = (acc - ntt) * P^-1 (+ addend, optionally through sigma_g)
+};
+
+struct FpTask {
+    int32_t period;                      // tasks per batch entry
+    int16_t pos[HISA_MAX_PRIMES];        // limb position of the task's polynomial inside a batch entry (output side)
+    int16_t prime[HISA_MAX_PRIMES];      // its prime
+};
+
+struct FpArgs {
+    const FpPrime* fprimes;
+    const double* ftw;
+    const double* utw;
+    const double* vtw;
+    const u64* in; u64 in_bs;          // u64 input [batch][..][N]
+    u64* out; u64 out_bs;              // u64 output
+    double* yout; u64 yout_bs;         // double output (FP_INV_TO_Y)
+    int in_pos_shift;                  // input limb position = pos + in_pos_shift
+    u64 galois;                        // inverse modes: gather through sigma_g (0 = none)
+    const double* post;                // FP_INV_TO_Y: per task entry constant (centred)
+    // base conversion (FP_FWD_CONV*)
+    const double* y; u64 y_bs;         // [batch][..][N] centred doubles, source limbs at y_pos0 ..
+    int y_pos0, conv_a, total;
+    const double* hat;                 // [a][total] (D/c_i) mod t, centred
+    // final combine (FP_FWD_CONV_FINAL): batch entries are (ciphertext, polynomial) pairs
+    const u64* acc; u64 acc_bs; int acc_pos_shift;
+    const double* pinv_tab;            // [prime] P^-1 mod q, centred
+    const u64* add; u64 add_bs, add_ps; int add_div, add_polys;  // addend of entry b: add + (b / add_div) * add_bs +
+    u64 add_galois;                                              // (b % add_div) * add_ps, if b % add_div < add_polys
+};
+hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st);
+
+// acc[b][p][x] = sum_j e_j[x] * key[j][p][prime(x)] in fp64; e_j[x] comes from ext unless x lies in digit j, then
+// from own_src (the NTT-form input itself, read through sigma_g when galois != 0)
+hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
+                                   int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois, u64* acc,
+                                   u64 acc_bs, u64 n_batch, int log_n, hipStream_t st);
 
 // sampling (counter-based generator, both sides of the parity tests implement it)
 hipError_t launch_sample_uniform(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, const PolyMap& map, int n_polys,

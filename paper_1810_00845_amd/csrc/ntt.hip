@@ -127,9 +127,36 @@ static hipError_t run_pass(bool inv, PassArgs a, const NttTables& t, const PolyM
     return hipGetLastError();
 }
 
+// PolyMap -> compact task list of the fp64 single-launch transform; false when it does not fit
+static bool fp_tasks(const NttTables& t, int log_n, const PolyMap& map, int n_polys, int out_entry0, FpTask* tk) {
+    if (!t.fp_ok || log_n < 12 || log_n > 15 || n_polys % map.period != 0) return false;
+    int cnt = 0;
+    for (int e = 0; e < map.period; e++) {
+        if (map.prime_of[e] < 0) continue;
+        if (cnt >= HISA_MAX_PRIMES) return false;
+        tk->pos[cnt] = (int16_t)(e - out_entry0);
+        tk->prime[cnt] = map.prime_of[e];
+        cnt++;
+    }
+    tk->period = cnt;
+    return cnt > 0;
+}
+
+static FpArgs fp_base_args(const NttTables& t) {
+    FpArgs a = {};
+    a.fprimes = t.fprimes; a.ftw = t.ftw; a.utw = t.utw; a.vtw = t.vtw;
+    return a;
+}
+
 hipError_t launch_ntt(const NttTables& t, int log_n, u64* data, u64 batch_stride, int n_polys, const PolyMap& map,
                       hipStream_t st) {
     if (n_polys <= 0) return hipSuccess;
+    FpTask tk;
+    if (fp_tasks(t, log_n, map, n_polys, 0, &tk)) {
+        FpArgs fa = fp_base_args(t);
+        fa.in = data; fa.in_bs = batch_stride; fa.out = data; fa.out_bs = batch_stride;
+        return launch_ntt_fp(FP_FWD_PLAIN, log_n, fa, tk, (u64)(n_polys / map.period), st);
+    }
     PassArgs a = {};
     a.data = data; a.in = nullptr; a.batch_stride = batch_stride; a.log_n = log_n;
     if (log_n <= TILE_LOG) {
@@ -146,6 +173,16 @@ hipError_t launch_ntt(const NttTables& t, int log_n, u64* data, u64 batch_stride
 hipError_t launch_intt(const NttTables& t, int log_n, u64* data, u64 batch_stride, int n_polys, const PolyMap& map,
                        const InttExtra* extra, hipStream_t st) {
     if (n_polys <= 0) return hipSuccess;
+    FpTask tk;
+    if ((!extra || !extra->post) && fp_tasks(t, log_n, map, n_polys, extra ? extra->out_entry0 : 0, &tk)) {
+        FpArgs fa = fp_base_args(t);
+        fa.in = (extra && extra->in) ? extra->in : data;
+        fa.in_bs = (extra && extra->in) ? extra->in_batch_stride : batch_stride;
+        fa.in_pos_shift = extra ? extra->out_entry0 : 0;
+        fa.galois = extra ? extra->galois : 0;
+        fa.out = data; fa.out_bs = batch_stride;
+        return launch_ntt_fp(FP_INV_PLAIN, log_n, fa, tk, (u64)(n_polys / map.period), st);
+    }
     PassArgs a = {};
     a.data = data; a.batch_stride = batch_stride; a.log_n = log_n;
     if (extra) {

@@ -1,0 +1,364 @@
+// Single-launch negacyclic NTT / inverse NTT for N = 2^12 .. 2^15 and primes
+// below 2^50, with exact fp64 modular arithmetic (fparith.cuh) and the
+// neighbouring steps of key switching fused into its load and store stages.
+//
+// One workgroup transforms one limb-polynomial.  N/32 threads hold 32
+// coefficients each in registers (the whole polynomial lives in the register
+// file: 256 KiB at N = 2^15, one 1024-thread workgroup per CU).  The log2 N
+// butterfly levels run as three register-resident radix-32 phases; between
+// phases the polynomial is transposed through LDS as two 32-bit halves, so the
+// staging buffer is N*4 bytes plus padding (132 KiB at N = 2^15) and the transposes
+// need no extra registers.  One pad word per 32 makes every transpose access
+// bank-conflict free.  Global loads and stores always use
+// the mapping "lane <-> consecutive coefficient", i.e. they are coalesced.
+//
+// Index bit fields of a coefficient index: idx = (a:5)(b:5)(c:K3), K3 = log2 N - 10.
+//   mapping P1: thread (b,c), registers a      (coalesced global access)
+//   mapping P2: thread (a,c), registers b
+//   mapping P3: thread (a_low:K3, b), registers (a_high:5-K3, c)
+// Forward (natural in, value at psi^(2 bitrev(i)+1) at index i out): decimation
+// in time, levels 1..5 on a (P1), 6..10 on b (P2), 11.. on c (P3).
+// Inverse: the cyclic inverse transform as decimation in time from bit-reversed
+// input (levels on c in P3, then b in P2, then a in P1) followed by the
+// untwist psi^-j / N (and an optional extra constant per limb).
+#include "hisa_internal.hpp"
+#include "fparith.cuh"
+
+template <int K3>
+struct Geo {
+    static constexpr int LOGN = 10 + K3, TB = 5 + K3, THREADS = 1 << TB, N = 1 << LOGN, CM = (1 << K3) - 1;
+    // Every mapping splits a coefficient index (and its LDS word address) into a term of the thread plus a
+    // compile-time term of the register, so addressing needs one register per mapping, not one per element.
+    // LDS word address = idx + (idx >> 5): one pad word per 32 keeps all three transposes bank-conflict free.
+    static constexpr int LDS_WORDS = N + N / 32;
+    template <int M> static __device__ __forceinline__ int thread_idx(int t) {
+        if (M == 1) return t;
+        if (M == 2) return ((t >> K3) << TB) | (t & CM);
+        return ((t >> 5) << TB) | ((t & 31) << K3);
+    }
+    template <int M> static constexpr int reg_idx(int r) {
+        return M == 1 ? (r << TB) : (M == 2 ? (r << K3) : (((r >> K3) << (K3 + TB)) | (r & CM)));
+    }
+    template <int M> static __device__ __forceinline__ int thread_lds(int t) {
+        if (M == 1) return t + (t >> 5);
+        if (M == 2) return ((t >> K3) << TB) + ((t >> K3) << K3) + (t & CM);
+        return ((t >> 5) << TB) + ((t & 31) << K3) + ((t >> 5) << K3) + ((t & 31) >> (5 - K3));
+    }
+    template <int M> static constexpr int reg_lds(int r) {
+        return M == 1 ? r * ((1 << TB) + (1 << (TB - 5)))
+                      : (M == 2 ? (r << K3) + (r >> (5 - K3))
+                                : ((r >> K3) << (K3 + TB)) + ((r >> K3) << (2 * K3)) + (r & CM));
+    }
+};
+
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+__device__ __forceinline__ uint32_t lo32(double v) { return (uint32_t)__double_as_longlong(v); }
+__device__ __forceinline__ uint32_t hi32(double v) { return (uint32_t)((u64)__double_as_longlong(v) >> 32); }
+__device__ __forceinline__ double mk64(uint32_t lo, uint32_t hi) { return __longlong_as_double((long long)(((u64)hi << 32) | lo)); }
+
+// transpose between two register mappings through LDS, 32-bit halves one after the other
+template <int K3, int FROM, int TO>
+__device__ __forceinline__ void exchange(double (&v)[32], uint32_t* lds, int t) {
+    typedef Geo<K3> G;
+    uint32_t* wr = lds + G::template thread_lds<FROM>(t);
+    const uint32_t* rd = lds + G::template thread_lds<TO>(t);
+    uint32_t tmp[32];
+#pragma unroll
+    for (int r = 0; r < 32; r++) wr[G::template reg_lds<FROM>(r)] = lo32(v[r]);
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 32; r++) tmp[r] = rd[G::template reg_lds<TO>(r)];
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 32; r++) wr[G::template reg_lds<FROM>(r)] = hi32(v[r]);
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 32; r++) v[r] = mk64(tmp[r], rd[G::template reg_lds<TO>(r)]);
+    __syncthreads();
+}
+
+__device__ __forceinline__ void bfly(double& x, double& y, double w, double p, double pinv) {
+    const double t = fp_mulmod(y, w, p, pinv);
+    y = x - t;
+    x = x + t;
+}
+
+// BITS levels over the register-index field [0, BITS) of each group of 2^BITS registers (GROUPS groups), largest
+// distance first; level j uses twiddle tw[(1 << j) * scale_j ...]: the caller gives base index and thread part.
+// Forward phase: twiddle index = (first << j) + (tpart << j) + g, g = group of the pair within the field.
+template <int BITS, int GROUPS, int STRIDE>
+__device__ __forceinline__ void fwd_phase(double (&v)[32], const double* tw, int first, const int (&tpart)[GROUPS], double p,
+                                          double pinv) {
+#pragma unroll
+    for (int j = 0; j < BITS; j++) {
+        const int half = BITS - 1 - j;
+        #pragma unroll
+        for (int grp = 0; grp < GROUPS; grp++) {
+#pragma unroll
+            for (int g = 0; g < (1 << j); g++) {
+                const double w = (tw + (first << j) + g)[tpart[grp] << j];
+#pragma unroll
+                for (int lo = 0; lo < (1 << half); lo++) {
+                    const int r0 = grp * STRIDE + ((g << (half + 1)) | lo);
+                    bfly(v[r0], v[r0 + (1 << half)], w, p, pinv);
+                }
+            }
+        }
+    }
+}
+
+// Inverse phase (decimation in time from bit-reversed input): level j pairs bit j of the field, smallest distance
+// first; twiddle index = (1 << (t0 + j)) + (klow << kshift) + tlow, klow = low j bits of the register field.
+template <int BITS, int GROUPS, int STRIDE>
+__device__ __forceinline__ void inv_phase(double (&v)[32], const double* utw, int t0, int kshift, int tlow, double p,
+                                          double pinv) {
+#pragma unroll
+    for (int j = 0; j < BITS; j++) {
+#pragma unroll
+        for (int klow = 0; klow < (1 << j); klow++) {
+            const bool unit = (t0 + j == 0);  // the very first level multiplies by 1
+            const double w = unit ? 1.0 : (utw + (1 << (t0 + j)) + (klow << kshift))[tlow];
+#pragma unroll
+            for (int grp = 0; grp < GROUPS; grp++) {
+#pragma unroll
+                for (int hi = 0; hi < (1 << (BITS - 1 - j)); hi++) {
+                    const int r0 = grp * STRIDE + ((hi << (j + 1)) | klow);
+                    if (unit) {
+                        const double x = v[r0], y = v[r0 + (1 << j)];
+                        v[r0] = x + y;
+                        v[r0 + (1 << j)] = x - y;
+                    } else {
+                        bfly(v[r0], v[r0 + (1 << j)], w, p, pinv);
+                    }
+                }
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ uint32_t galois_src_fp(uint32_t i, u64 g, int log_n) {
+    const uint32_t mask = (2u << log_n) - 1;
+    const uint32_t e = 2 * (__brev(i) >> (32 - log_n)) + 1;
+    const uint32_t e2 = (uint32_t)((u64)e * g) & mask;
+    return __brev((e2 - 1) >> 1) >> (32 - log_n);
+}
+
+template <int K3, int MODE>
+__global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTask tk) {
+    typedef Geo<K3> G;
+    extern __shared__ uint32_t lds[];
+    const int t = threadIdx.x;
+    const int task = blockIdx.x;
+    const int e = task % tk.period;
+    const u64 b = task / tk.period;
+    const int pos = tk.pos[e], prime = tk.prime[e];
+    const FpPrime fp = a.fprimes[prime];
+    const double p = fp.p, pinv = fp.pinv;
+    constexpr bool INV = (MODE == FP_INV_PLAIN || MODE == FP_INV_TO_Y);
+    double v[32];
+
+    // ---- load (mapping P1: lane <-> consecutive coefficients; register r holds coefficient r*THREADS + t) ----
+    if (MODE == FP_FWD_PLAIN || INV) {
+        const u64* src = a.in + b * a.in_bs + (u64)(pos + a.in_pos_shift) * G::N;
+        if (INV && a.galois) {
+#pragma unroll
+            for (int r = 0; r < 32; r++)
+                v[r] = fp_from_u64(src[galois_src_fp((uint32_t)((r << G::TB) | t), a.galois, G::LOGN)]);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 32; r++) v[r] = fp_from_u64((src + (r << G::TB))[t]);
+        }
+    } else {
+        // fast base conversion: sum_i y_i * hat_i mod p, y_i centred source digits (already times (D/c_i)^-1)
+        const double* y = a.y + b * a.y_bs + (u64)a.y_pos0 * G::N;
+#pragma unroll
+        for (int r = 0; r < 32; r++) v[r] = 0.0;
+        for (int i = 0; i < a.conv_a; i++) {
+            const double h = a.hat[(u64)i * a.total + prime];
+            const double* yi = y + (u64)i * G::N;
+#pragma unroll
+            for (int r = 0; r < 32; r++) v[r] += fp_mulmod((yi + (r << G::TB))[t], h, p, pinv);
+            if ((i & 7) == 7) {
+#pragma unroll
+                for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
+    }
+
+    if (!INV) {
+        const double* tw = a.ftw + (u64)prime * G::N;
+        {   // levels 1..5 on a: twiddles depend on the register index only
+            const int tp[1] = {0};
+            fwd_phase<5, 1, 32>(v, tw, 1, tp, p, pinv);
+        }
+#pragma unroll
+        for (int r = 0; r < 32; r++) {
+            v[r] = fp_norm(v[r], p, pinv);
+        }
+        exchange<K3, 1, 2>(v, lds, t);
+        {   // levels 6..10 on b: index 2^(5+j) + a 2^j + g
+            const int tp[1] = {t >> K3};
+            fwd_phase<5, 1, 32>(v, tw, 32, tp, p, pinv);
+        }
+#pragma unroll
+        for (int r = 0; r < 32; r++) {
+            v[r] = fp_norm(v[r], p, pinv);
+        }
+        exchange<K3, 2, 3>(v, lds, t);
+        {   // levels 11.. on c: index 2^(10+j) + (a 32 + b) 2^j + g, one group per a_high
+            constexpr int GROUPS = 1 << (5 - K3);
+            int tp[GROUPS];
+#pragma unroll
+            for (int grp = 0; grp < GROUPS; grp++) tp[grp] = ((((grp << K3) | (t >> 5)) << 5) | (t & 31));
+            fwd_phase<K3, GROUPS, 1 << K3>(v, tw, 1024, tp, p, pinv);
+        }
+        exchange<K3, 3, 1>(v, lds, t);
+    } else {
+        const double* utw = a.utw + (u64)prime * G::N;
+        exchange<K3, 1, 3>(v, lds, t);
+        // levels t = 0..K3-1 on c
+        inv_phase<K3, 1 << (5 - K3), 1 << K3>(v, utw, 0, 0, 0, p, pinv);
+#pragma unroll
+        for (int r = 0; r < 32; r++) {
+            v[r] = fp_norm(v[r], p, pinv);
+        }
+        exchange<K3, 3, 2>(v, lds, t);
+        // levels t = K3 + j on b: k = (b mod 2^j) 2^K3 + c
+        inv_phase<5, 1, 32>(v, utw, K3, K3, t & G::CM, p, pinv);
+#pragma unroll
+        for (int r = 0; r < 32; r++) {
+            v[r] = fp_norm(v[r], p, pinv);
+        }
+        exchange<K3, 2, 1>(v, lds, t);
+        // levels t = 5 + K3 + j on a: k = (a mod 2^j) 2^(5+K3) + (b, c)
+        inv_phase<5, 1, 32>(v, utw, G::TB, G::TB, t, p, pinv);
+    }
+
+    // ---- store (mapping P1) ----
+    if (MODE == FP_FWD_PLAIN || MODE == FP_FWD_CONV) {
+        u64* dst = a.out + b * a.out_bs + (u64)pos * G::N;
+#pragma unroll
+        for (int r = 0; r < 32; r++) (dst + (r << G::TB))[t] = fp_canonical(v[r], p, pinv);
+    } else if (MODE == FP_FWD_CONV_FINAL) {
+        // out = (acc - conv) * P^-1 (+ addend)
+        const u64* acc = a.acc + b * a.acc_bs + (u64)(pos + a.acc_pos_shift) * G::N;
+        u64* dst = a.out + b * a.out_bs + (u64)pos * G::N;
+        const double pin = a.pinv_tab[prime];
+        const bool with_add = a.add && (int)(b % a.add_div) < a.add_polys;
+        const u64* add = with_add ? a.add + (b / a.add_div) * a.add_bs + (b % a.add_div) * a.add_ps + (u64)pos * G::N : nullptr;
+#pragma unroll
+        for (int r = 0; r < 32; r++) {
+            double x = fp_from_u64((acc + (r << G::TB))[t]) - fp_norm(v[r], p, pinv);
+            x = fp_mulmod(x, pin, p, pinv);
+            if (with_add) {
+                if (a.add_galois) x += fp_from_u64(add[galois_src_fp((uint32_t)((r << G::TB) | t), a.add_galois, G::LOGN)]);
+                else x += fp_from_u64((add + (r << G::TB))[t]);
+            }
+            (dst + (r << G::TB))[t] = fp_canonical(x, p, pinv);
+        }
+    } else {
+        const double* vtw = a.vtw + (u64)prime * G::N;
+        if (MODE == FP_INV_PLAIN) {
+            u64* dst = a.out + b * a.out_bs + (u64)pos * G::N;
+#pragma unroll
+            for (int r = 0; r < 32; r++)
+                (dst + (r << G::TB))[t] = fp_canonical(fp_mulmod(v[r], (vtw + (r << G::TB))[t], p, pinv), p, pinv);
+        } else {
+            double* dst = a.yout + b * a.yout_bs + (u64)pos * G::N;
+            const double post = a.post[e];
+#pragma unroll
+            for (int r = 0; r < 32; r++) {
+                const double x = fp_mulmod(v[r], (vtw + (r << G::TB))[t], p, pinv);
+                (dst + (r << G::TB))[t] = fp_norm(fp_mulmod(x, post, p, pinv), p, pinv);
+            }
+        }
+    }
+}
+
+template <int K3, int MODE>
+static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
+    typedef Geo<K3> G;
+    static bool attr_set = false;
+    const size_t lds_bytes = (size_t)G::LDS_WORDS * 4;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)ntt_fp_kernel<K3, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const char* names[] = {"ntt_fp_kernel<fwd>", "ntt_fp_kernel<inv>", "ntt_fp_kernel<inv_to_y>", "ntt_fp_kernel<conv_fwd>",
+                           "ntt_fp_kernel<conv_fwd_final>"};
+    ProfScope prof__(names[MODE], st);
+    hipLaunchKernelGGL((ntt_fp_kernel<K3, MODE>), dim3((unsigned)(n_batch * tk.period)), dim3(G::THREADS), lds_bytes, st, a, tk);
+    return hipGetLastError();
+}
+
+template <int MODE>
+static hipError_t dispatch_k3(int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
+    switch (log_n) {
+        case 12: return launch_one<2, MODE>(a, tk, n_batch, st);
+        case 13: return launch_one<3, MODE>(a, tk, n_batch, st);
+        case 14: return launch_one<4, MODE>(a, tk, n_batch, st);
+        case 15: return launch_one<5, MODE>(a, tk, n_batch, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
+    if (n_batch == 0 || tk.period <= 0) return hipSuccess;
+    switch (mode) {
+        case FP_FWD_PLAIN: return dispatch_k3<FP_FWD_PLAIN>(log_n, a, tk, n_batch, st);
+        case FP_INV_PLAIN: return dispatch_k3<FP_INV_PLAIN>(log_n, a, tk, n_batch, st);
+        case FP_INV_TO_Y: return dispatch_k3<FP_INV_TO_Y>(log_n, a, tk, n_batch, st);
+        case FP_FWD_CONV: return dispatch_k3<FP_FWD_CONV>(log_n, a, tk, n_batch, st);
+        case FP_FWD_CONV_FINAL: return dispatch_k3<FP_FWD_CONV_FINAL>(log_n, a, tk, n_batch, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// inner product with the switching key, fp64
+// ---------------------------------------------------------------------------
+#define IPF_NT 256
+#define IPF_BCHUNK 8
+__global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits,
+                                                                  int l, int K, int L, int alpha, const u64* key, int total,
+                                                                  const u64* own_src, u64 own_bs, u64 galois, u64* acc, u64 acc_bs,
+                                                                  u64 n_batch, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const uint32_t j = blockIdx.x * IPF_NT + threadIdx.x;
+    const int x = blockIdx.y;
+    const int ext_limbs = l + K;
+    const int prime = x < l ? x : L + (x - l);
+    const int own_digit = x < l ? x / alpha : -1;
+    const FpPrime fp = fprimes[prime];
+    const uint32_t jsrc = galois ? galois_src_fp(j, galois, log_n) : j;
+    const u64 b0 = (u64)blockIdx.z * IPF_BCHUNK;
+    const u64 b1 = b0 + IPF_BCHUNK < n_batch ? b0 + IPF_BCHUNK : n_batch;
+    for (u64 b = b0; b < b1; b++) {
+        double sb = 0.0, sa = 0.0;
+        for (int d = 0; d < digits; d++) {
+            const u64 ev = d == own_digit ? own_src[b * own_bs + (u64)x * n + jsrc]
+                                          : ext[b * ext_bs + ((u64)d * ext_limbs + x) * n + j];
+            const double e = fp_from_u64(ev);
+            sb += fp_mulmod(e, fp_from_u64(key[(((u64)d * 2 + 0) * total + prime) * n + j]), fp.p, fp.pinv);
+            sa += fp_mulmod(e, fp_from_u64(key[(((u64)d * 2 + 1) * total + prime) * n + j]), fp.p, fp.pinv);
+            if ((d & 7) == 7) { sb = fp_norm(sb, fp.p, fp.pinv); sa = fp_norm(sa, fp.p, fp.pinv); }
+        }
+        acc[b * acc_bs + (u64)x * n + j] = fp_canonical(sb, fp.p, fp.pinv);
+        acc[b * acc_bs + ((u64)ext_limbs + x) * n + j] = fp_canonical(sa, fp.p, fp.pinv);
+    }
+}
+
+hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
+                                   int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois, u64* acc,
+                                   u64 acc_bs, u64 n_batch, int log_n, hipStream_t st) {
+    dim3 grid((1u << log_n) / IPF_NT, l + K, (unsigned)((n_batch + IPF_BCHUNK - 1) / IPF_BCHUNK));
+    ProfScope prof__("inner_product_fp_kernel", st);
+    hipLaunchKernelGGL(inner_product_fp_kernel, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha, key,
+                       total, own_src, own_bs, galois, acc, acc_bs, n_batch, log_n);
+    return hipGetLastError();
+}

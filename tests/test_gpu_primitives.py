@@ -13,6 +13,11 @@ PARAMS = {
     "n10_a1": (10, [30, 30, 30], 3, 60, 11),          # single-launch NTT, alpha = 1, mixed prime sizes
     "n12_a2": (12, [50, 40, 45, 50, 36], 3, 55, 12),  # two-launch NTT, alpha = 2, ragged last digit
     "n13_d1": (13, [55, 50, 50, 50], 1, 58, 13),      # dnum = 1: alpha = 4 special primes
+    # all primes below 2^50: the fp64 single-launch transforms and the fused key-switch pipeline
+    "n12_fp": (12, [50, 40, 45, 50, 36], 3, 50, 14),  # alpha = 2, ragged last digit, mixed sizes
+    "n13_fp": (13, [50, 50, 50, 50], 1, 50, 15),      # dnum = 1
+    "n14_fp": (14, [50, 48, 45], 2, 49, 16),
+    "n15_fp": (15, [50, 50, 50], 3, 50, 17),          # the benchmark's ring degree
 }
 
 
