@@ -223,6 +223,7 @@ struct FpArgs {
     const double* ftw;
     const double* utw;
     const double* vtw;
+    int n_tasks;                       // filled in by the launcher
     const u64* in; u64 in_bs;          // u64 input [batch][..][N]
     u64* out; u64 out_bs;              // u64 output
     double* yout; u64 yout_bs;         // double output (FP_INV_TO_Y)

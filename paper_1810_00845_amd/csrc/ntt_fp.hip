@@ -53,6 +53,17 @@ struct Geo {
 
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// Phase timestamps of one workgroup per launch, for tuning builds only (-DNTT_FP_TIMING)
+#ifdef NTT_FP_TIMING
+__device__ long long g_fp_stamps[16 * 4096];
+#define STAMP(k)                                                                                   \
+    do {                                                                                           \
+        if (threadIdx.x == 0 && blockIdx.x < 4096) g_fp_stamps[blockIdx.x * 16 + (k)] = wall_clock64(); \
+    } while (0)
+#else
+#define STAMP(k) do { } while (0)
+#endif
+
 __device__ __forceinline__ uint32_t lo32(double v) { return (uint32_t)__double_as_longlong(v); }
 __device__ __forceinline__ uint32_t hi32(double v) { return (uint32_t)((u64)__double_as_longlong(v) >> 32); }
 __device__ __forceinline__ double mk64(uint32_t lo, uint32_t hi) { return __longlong_as_double((long long)(((u64)hi << 32) | lo)); }
@@ -149,7 +160,12 @@ __global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTa
     typedef Geo<K3> G;
     extern __shared__ uint32_t lds[];
     const int t = threadIdx.x;
-    const int task = blockIdx.x;
+    // Workgroups go to the eight XCDs round-robin by id.  Give each XCD a contiguous range of tasks, so that the
+    // tasks that share inputs (all target limbs of one digit of one ciphertext) run on one XCD, at about the same
+    // time, and find those inputs in its L2.
+    const int per_xcd = gridDim.x >> 3;
+    const int task = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (task >= a.n_tasks) return;
     const int e = task % tk.period;
     const u64 b = task / tk.period;
     const int pos = tk.pos[e], prime = tk.prime[e];
@@ -157,6 +173,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTa
     const double p = fp.p, pinv = fp.pinv;
     constexpr bool INV = (MODE == FP_INV_PLAIN || MODE == FP_INV_TO_Y);
     double v[32];
+    STAMP(0);
 
     // ---- load (mapping P1: lane <-> consecutive coefficients; register r holds coefficient r*THREADS + t) ----
     if (MODE == FP_FWD_PLAIN || INV) {
@@ -188,6 +205,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTa
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
     }
 
+    STAMP(1);
     if (!INV) {
         const double* tw = a.ftw + (u64)prime * G::N;
         {   // levels 1..5 on a: twiddles depend on the register index only
@@ -198,7 +216,9 @@ __global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTa
         for (int r = 0; r < 32; r++) {
             v[r] = fp_norm(v[r], p, pinv);
         }
+        STAMP(2);
         exchange<K3, 1, 2>(v, lds, t);
+        STAMP(3);
         {   // levels 6..10 on b: index 2^(5+j) + a 2^j + g
             const int tp[1] = {t >> K3};
             fwd_phase<5, 1, 32>(v, tw, 32, tp, p, pinv);
@@ -207,7 +227,9 @@ __global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTa
         for (int r = 0; r < 32; r++) {
             v[r] = fp_norm(v[r], p, pinv);
         }
+        STAMP(4);
         exchange<K3, 2, 3>(v, lds, t);
+        STAMP(5);
         {   // levels 11.. on c: index 2^(10+j) + (a 32 + b) 2^j + g, one group per a_high
             constexpr int GROUPS = 1 << (5 - K3);
             int tp[GROUPS];
@@ -215,7 +237,9 @@ __global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTa
             for (int grp = 0; grp < GROUPS; grp++) tp[grp] = ((((grp << K3) | (t >> 5)) << 5) | (t & 31));
             fwd_phase<K3, GROUPS, 1 << K3>(v, tw, 1024, tp, p, pinv);
         }
+        STAMP(6);
         exchange<K3, 3, 1>(v, lds, t);
+        STAMP(7);
     } else {
         const double* utw = a.utw + (u64)prime * G::N;
         exchange<K3, 1, 3>(v, lds, t);
@@ -238,6 +262,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTa
     }
 
     // ---- store (mapping P1) ----
+    STAMP(8);
     if (MODE == FP_FWD_PLAIN || MODE == FP_FWD_CONV) {
         u64* dst = a.out + b * a.out_bs + (u64)pos * G::N;
 #pragma unroll
@@ -276,6 +301,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTa
             }
         }
     }
+    STAMP(9);
 }
 
 template <int K3, int MODE>
@@ -292,7 +318,10 @@ static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hip
     const char* names[] = {"ntt_fp_kernel<fwd>", "ntt_fp_kernel<inv>", "ntt_fp_kernel<inv_to_y>", "ntt_fp_kernel<conv_fwd>",
                            "ntt_fp_kernel<conv_fwd_final>"};
     ProfScope prof__(names[MODE], st);
-    hipLaunchKernelGGL((ntt_fp_kernel<K3, MODE>), dim3((unsigned)(n_batch * tk.period)), dim3(G::THREADS), lds_bytes, st, a, tk);
+    FpArgs args = a;
+    args.n_tasks = (int)(n_batch * tk.period);
+    const unsigned grid = (unsigned)((args.n_tasks + 7) / 8) * 8;
+    hipLaunchKernelGGL((ntt_fp_kernel<K3, MODE>), dim3(grid), dim3(G::THREADS), lds_bytes, st, args, tk);
     return hipGetLastError();
 }
 
