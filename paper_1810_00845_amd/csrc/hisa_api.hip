@@ -407,10 +407,16 @@ extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** 
                 bwd[0] = 1;
                 for (u64 e = 1; e < n; e++) bwd[e] = hm::mul(bwd[e - 1], psi_inv, q);   // psi^-e
                 const size_t o = (size_t)i * n;
-                for (u64 x = 0; x < n; x++) {
-                    ftw[o + x] = centred_double(tw[o + x], q);
-                    vtw[o + x] = centred_double(hm::mul(bwd[x], ctx->pc[i].n_inv, q), q);
-                }
+                for (u64 x = 0; x < n; x++) vtw[o + x] = centred_double(hm::mul(bwd[x], ctx->pc[i].n_inv, q), q);
+                // forward twiddles psi^bitrev(x), permuted inside each level so that the per-thread part of the index
+                // is the fastest one: levels 1..5 (x < 32) as they are; levels 6..10: x = ((32 + a) << j) + g stored at
+                // (32 << j) + g * 32 + a; levels 11..: x = ((1024 + T) << j) + g stored at (1024 << j) + g * 1024 + T
+                for (u64 x = 0; x < n && x < 32; x++) ftw[o + x] = centred_double(tw[o + x], q);
+                for (u64 first : {(u64)32, (u64)1024})
+                    for (u64 j = 0; (first << j) < n && (first == 1024 || j < 5); j++)
+                        for (u64 g = 0; g < ((u64)1 << j); g++)
+                            for (u64 tp = 0; tp < first; tp++)
+                                ftw[o + (first << j) + g * first + tp] = centred_double(tw[o + ((first + tp) << j) + g], q);
                 utw[o] = 0.0;
                 for (u64 m = 1; m < n; m <<= 1)   // psi^(-k N/m), k < m: exponents stay below N
                     for (u64 k = 0; k < m; k++) utw[o + m + k] = centred_double(bwd[k * (n / m)], q);

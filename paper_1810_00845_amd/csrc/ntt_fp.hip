@@ -51,7 +51,17 @@ struct Geo {
     }
 };
 
+// Read-only tables indexed by wave-uniform values go through the constant address space, which makes the
+// compiler use scalar loads (SGPR results, batched, off the vector memory path).  Vector loads of uniform
+// addresses were each followed by a wait and cost the kernel dozens of exposed memory latencies.
+typedef const __attribute__((address_space(4))) double* cdouble_ptr;
+__device__ __forceinline__ cdouble_ptr as_const(const double* p) { return (cdouble_ptr)(unsigned long long)p; }
+
+#ifdef NTT_FP_NO_FENCE
+#define SCHED_FENCE() do { } while (0)
+#else
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#endif
 
 // Phase timestamps of one workgroup per launch, for tuning builds only (-DNTT_FP_TIMING)
 #ifdef NTT_FP_TIMING
@@ -74,41 +84,73 @@ __device__ __forceinline__ void exchange(double (&v)[32], uint32_t* lds, int t) 
     typedef Geo<K3> G;
     uint32_t* wr = lds + G::template thread_lds<FROM>(t);
     const uint32_t* rd = lds + G::template thread_lds<TO>(t);
-    uint32_t tmp[32];
+#ifdef NTT_FP_SKIP_XCHG
+    return;
+#endif
+#ifdef NTT_FP_ONLY_BARRIERS
+    __syncthreads(); __syncthreads(); __syncthreads(); __syncthreads();
+    return;
+#endif
+    // the low words are dead once written, so the incoming low words take their registers: 64 live, not 96
+    uint32_t lo[32], hi[32];
 #pragma unroll
-    for (int r = 0; r < 32; r++) wr[G::template reg_lds<FROM>(r)] = lo32(v[r]);
+    for (int r = 0; r < 32; r++) { lo[r] = lo32(v[r]); hi[r] = hi32(v[r]); }
+#pragma unroll
+    for (int r = 0; r < 32; r++) wr[G::template reg_lds<FROM>(r)] = lo[r];
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < 32; r++) tmp[r] = rd[G::template reg_lds<TO>(r)];
+    for (int r = 0; r < 32; r++) lo[r] = rd[G::template reg_lds<TO>(r)];
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < 32; r++) wr[G::template reg_lds<FROM>(r)] = hi32(v[r]);
+    for (int r = 0; r < 32; r++) wr[G::template reg_lds<FROM>(r)] = hi[r];
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < 32; r++) v[r] = mk64(tmp[r], rd[G::template reg_lds<TO>(r)]);
+    for (int r = 0; r < 32; r++) hi[r] = rd[G::template reg_lds<TO>(r)];
     __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 32; r++) v[r] = mk64(lo[r], hi[r]);
 }
 
 __device__ __forceinline__ void bfly(double& x, double& y, double w, double p, double pinv) {
+#ifdef NTT_FP_SKIP_COMPUTE
+    const double t = y * w + p * pinv;
+#else
     const double t = fp_mulmod(y, w, p, pinv);
+#endif
     y = x - t;
     x = x + t;
 }
 
-// BITS levels over the register-index field [0, BITS) of each group of 2^BITS registers (GROUPS groups), largest
-// distance first; level j uses twiddle tw[(1 << j) * scale_j ...]: the caller gives base index and thread part.
-// Forward phase: twiddle index = (first << j) + (tpart << j) + g, g = group of the pair within the field.
-template <int BITS, int GROUPS, int STRIDE>
-__device__ __forceinline__ void fwd_phase(double (&v)[32], const double* tw, int first, const int (&tpart)[GROUPS], double p,
+// Twiddles.  The forward twiddle of level j of a phase factors as
+//     psi^bitrev(((first + tpart) << j) + g)  =  psi^bitrev((first + tpart) << j)  *  psi^bitrev(g),
+// a per-thread value (one per level: five loads per phase, stored at (first << j) + tpart so that lanes read
+// consecutive addresses) times a value that is the same for every thread (the first entries of the table, read
+// through the scalar cache).  The inverse twiddle psi^(-k N/m), k = (klow << kshift) + tlow, factors the same way.
+// The per-thread values are fetched one phase ahead, before the transpose, so that their latency hides behind
+// the LDS traffic; the products cost 26 modular multiplications per phase.
+template <int BITS, int GROUPS>
+__device__ __forceinline__ void load_fwd_tw(double (&bt)[GROUPS][5], const double* tw, int first, const int (&tpart)[GROUPS]) {
+#pragma unroll
+    for (int grp = 0; grp < GROUPS; grp++)
+#pragma unroll
+        for (int j = 0; j < BITS; j++) bt[grp][j] = (tw + (first << j))[tpart[grp]];
+}
+
+// BITS levels over the register-index field of each group of 2^BITS registers (GROUPS groups), largest distance
+// first.  UNIFORM: the twiddles depend on the register index only (first phase).
+template <int BITS, int GROUPS, int STRIDE, bool UNIFORM>
+__device__ __forceinline__ void fwd_phase(double (&v)[32], const double* tw, const double (&bt)[GROUPS][5], double p,
                                           double pinv) {
 #pragma unroll
     for (int j = 0; j < BITS; j++) {
         const int half = BITS - 1 - j;
-        #pragma unroll
+#pragma unroll
         for (int grp = 0; grp < GROUPS; grp++) {
 #pragma unroll
             for (int g = 0; g < (1 << j); g++) {
-                const double w = (tw + (first << j) + g)[tpart[grp] << j];
+                double w;
+                if (UNIFORM) w = as_const(tw)[(1 << j) + g];
+                else w = g == 0 ? bt[grp][j] : fp_mulmod(bt[grp][j], as_const(tw)[g], p, pinv);
 #pragma unroll
                 for (int lo = 0; lo < (1 << half); lo++) {
                     const int r0 = grp * STRIDE + ((g << (half + 1)) | lo);
@@ -119,17 +161,25 @@ __device__ __forceinline__ void fwd_phase(double (&v)[32], const double* tw, int
     }
 }
 
+template <int BITS>
+__device__ __forceinline__ void load_inv_tw(double (&bt)[5], const double* utw, int t0, int tlow) {
+#pragma unroll
+    for (int j = 0; j < BITS; j++) bt[j] = utw[(1 << (t0 + j)) + tlow];
+}
+
 // Inverse phase (decimation in time from bit-reversed input): level j pairs bit j of the field, smallest distance
-// first; twiddle index = (1 << (t0 + j)) + (klow << kshift) + tlow, klow = low j bits of the register field.
-template <int BITS, int GROUPS, int STRIDE>
-__device__ __forceinline__ void inv_phase(double (&v)[32], const double* utw, int t0, int kshift, int tlow, double p,
-                                          double pinv) {
+// first; twiddle psi^(-k N/2^(t0+j)), k = (klow << t0) + tlow, klow = low j bits of the register field;
+// = utw[2^(t0+j) + tlow] * utw[2^j + klow].  UNIFORM: t0 = 0, tlow = 0.
+template <int BITS, int GROUPS, int STRIDE, bool UNIFORM>
+__device__ __forceinline__ void inv_phase(double (&v)[32], const double* utw, const double (&bt)[5], double p, double pinv) {
 #pragma unroll
     for (int j = 0; j < BITS; j++) {
 #pragma unroll
         for (int klow = 0; klow < (1 << j); klow++) {
-            const bool unit = (t0 + j == 0);  // the very first level multiplies by 1
-            const double w = unit ? 1.0 : (utw + (1 << (t0 + j)) + (klow << kshift))[tlow];
+            const bool unit = UNIFORM && j == 0;  // the very first level multiplies by 1
+            double w = 1.0;
+            if (UNIFORM) { if (!unit) w = as_const(utw)[(1 << j) + klow]; }
+            else w = klow == 0 ? bt[j] : fp_mulmod(bt[j], as_const(utw)[(1 << j) + klow], p, pinv);
 #pragma unroll
             for (int grp = 0; grp < GROUPS; grp++) {
 #pragma unroll
@@ -160,17 +210,18 @@ __global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTa
     typedef Geo<K3> G;
     extern __shared__ uint32_t lds[];
     const int t = threadIdx.x;
-    // Workgroups go to the eight XCDs round-robin by id.  Give each XCD a contiguous range of tasks, so that the
-    // tasks that share inputs (all target limbs of one digit of one ciphertext) run on one XCD, at about the same
-    // time, and find those inputs in its L2.
-    const int per_xcd = gridDim.x >> 3;
-    const int task = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (task >= a.n_tasks) return;
+    // Persistent workgroups: each loops over its share of the tasks, so consecutive tasks on a CU run back to back
+    // (no dispatch gap, the stores of one overlap the loads of the next).  Workgroups go to the eight XCDs
+    // round-robin by id; each XCD gets a contiguous range of tasks, so that tasks sharing inputs (all target
+    // limbs of one digit of one ciphertext) run on one XCD at about the same time and find them in its L2.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
+    const int per_xcd = (a.n_tasks + 7) >> 3;
+    const int task_end = min((xcd + 1) * per_xcd, a.n_tasks);
+    for (int task = xcd * per_xcd + slot; task < task_end; task += slots) {
     const int e = task % tk.period;
     const u64 b = task / tk.period;
     const int pos = tk.pos[e], prime = tk.prime[e];
-    const FpPrime fp = a.fprimes[prime];
-    const double p = fp.p, pinv = fp.pinv;
+    const double p = as_const(&a.fprimes[prime].p)[0], pinv = as_const(&a.fprimes[prime].p)[1];
     constexpr bool INV = (MODE == FP_INV_PLAIN || MODE == FP_INV_TO_Y);
     double v[32];
     STAMP(0);
@@ -179,28 +230,51 @@ __global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTa
     if (MODE == FP_FWD_PLAIN || INV) {
         const u64* src = a.in + b * a.in_bs + (u64)(pos + a.in_pos_shift) * G::N;
         if (INV && a.galois) {
+            // a private copy of the lane id: keeps the 32 gather indices from being kept alive (and spilled) for the
+            // address arithmetic of the store stage
+            int tg = t;
+            asm volatile("" : "+v"(tg));
 #pragma unroll
             for (int r = 0; r < 32; r++)
-                v[r] = fp_from_u64(src[galois_src_fp((uint32_t)((r << G::TB) | t), a.galois, G::LOGN)]);
+                v[r] = fp_from_u64(src[galois_src_fp((uint32_t)((r << G::TB) | tg), a.galois, G::LOGN)]);
         } else {
 #pragma unroll
             for (int r = 0; r < 32; r++) v[r] = fp_from_u64((src + (r << G::TB))[t]);
         }
     } else {
-        // fast base conversion: sum_i y_i * hat_i mod p, y_i centred source digits (already times (D/c_i)^-1)
+        // fast base conversion: sum_i y_i * hat_i mod p, y_i centred source digits (already times (D/c_i)^-1).
+        // Loads are issued eight at a time, one batch ahead of the arithmetic (two explicit buffers; the fences keep
+        // the compiler from sinking each load to its use, which would expose one memory latency per element).
         const double* y = a.y + b * a.y_bs + (u64)a.y_pos0 * G::N;
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = 0.0;
-        for (int i = 0; i < a.conv_a; i++) {
-            const double h = a.hat[(u64)i * a.total + prime];
-            const double* yi = y + (u64)i * G::N;
+        double bufa[8], bufb[8];
 #pragma unroll
-            for (int r = 0; r < 32; r++) v[r] += fp_mulmod((yi + (r << G::TB))[t], h, p, pinv);
+        for (int k = 0; k < 8; k++) bufa[k] = (y + (k << G::TB))[t];
+        for (int i = 0; i < a.conv_a; i++) {
+            const double h = as_const(a.hat)[(u64)i * a.total + prime];
+            const double* yi = y + (u64)i * G::N;
+            const double* yn = (i + 1 < a.conv_a) ? yi + G::N : yi;  // next source limb (dummy reload on the last)
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                SCHED_FENCE();
+                if (c < 3) {
+#pragma unroll
+                    for (int k = 0; k < 8; k++) ((c & 1) ? bufa : bufb)[k] = (yi + (((c + 1) * 8 + k) << G::TB))[t];
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 8; k++) bufa[k] = (yn + (k << G::TB))[t];
+                }
+                SCHED_FENCE();
+#pragma unroll
+                for (int k = 0; k < 8; k++) v[c * 8 + k] += fp_mulmod(((c & 1) ? bufb : bufa)[k], h, p, pinv);
+            }
             if ((i & 7) == 7) {
 #pragma unroll
                 for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
             }
         }
+        SCHED_FENCE();
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
     }
@@ -208,57 +282,60 @@ __global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTa
     STAMP(1);
     if (!INV) {
         const double* tw = a.ftw + (u64)prime * G::N;
+        double bt2[1][5];
         {   // levels 1..5 on a: twiddles depend on the register index only
-            const int tp[1] = {0};
-            fwd_phase<5, 1, 32>(v, tw, 1, tp, p, pinv);
+            const double none[1][5] = {};
+            fwd_phase<5, 1, 32, true>(v, tw, none, p, pinv);
+        }
+        {   // per-thread twiddles of levels 6..10 (index 2^(5+j) + a), fetched before the transpose
+            const int tp[1] = {t >> K3};
+            load_fwd_tw<5, 1>(bt2, tw, 32, tp);
+            SCHED_FENCE();
         }
 #pragma unroll
-        for (int r = 0; r < 32; r++) {
-            v[r] = fp_norm(v[r], p, pinv);
-        }
+        for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
         STAMP(2);
         exchange<K3, 1, 2>(v, lds, t);
         STAMP(3);
-        {   // levels 6..10 on b: index 2^(5+j) + a 2^j + g
-            const int tp[1] = {t >> K3};
-            fwd_phase<5, 1, 32>(v, tw, 32, tp, p, pinv);
-        }
-#pragma unroll
-        for (int r = 0; r < 32; r++) {
-            v[r] = fp_norm(v[r], p, pinv);
-        }
-        STAMP(4);
-        exchange<K3, 2, 3>(v, lds, t);
-        STAMP(5);
-        {   // levels 11.. on c: index 2^(10+j) + (a 32 + b) 2^j + g, one group per a_high
-            constexpr int GROUPS = 1 << (5 - K3);
+        fwd_phase<5, 1, 32, false>(v, tw, bt2, p, pinv);
+        constexpr int GROUPS = 1 << (5 - K3);
+        double bt3[GROUPS][5];
+        {   // levels 11.. on c: index 2^(10+j) + (a 32 + b), one group per a_high
             int tp[GROUPS];
 #pragma unroll
             for (int grp = 0; grp < GROUPS; grp++) tp[grp] = ((((grp << K3) | (t >> 5)) << 5) | (t & 31));
-            fwd_phase<K3, GROUPS, 1 << K3>(v, tw, 1024, tp, p, pinv);
+            load_fwd_tw<K3, GROUPS>(bt3, tw, 1024, tp);
+            SCHED_FENCE();
         }
+#pragma unroll
+        for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
+        STAMP(4);
+        exchange<K3, 2, 3>(v, lds, t);
+        STAMP(5);
+        fwd_phase<K3, GROUPS, 1 << K3, false>(v, tw, bt3, p, pinv);
         STAMP(6);
         exchange<K3, 3, 1>(v, lds, t);
         STAMP(7);
     } else {
         const double* utw = a.utw + (u64)prime * G::N;
+        double bt[5];
         exchange<K3, 1, 3>(v, lds, t);
-        // levels t = 0..K3-1 on c
-        inv_phase<K3, 1 << (5 - K3), 1 << K3>(v, utw, 0, 0, 0, p, pinv);
-#pragma unroll
-        for (int r = 0; r < 32; r++) {
-            v[r] = fp_norm(v[r], p, pinv);
+        {   // levels t = 0..K3-1 on c
+            const double none[5] = {};
+            inv_phase<K3, 1 << (5 - K3), 1 << K3, true>(v, utw, none, p, pinv);
         }
+        load_inv_tw<5>(bt, utw, K3, t & G::CM);   // levels K3 + j on b: k = (b mod 2^j) 2^K3 + c
+        SCHED_FENCE();
+#pragma unroll
+        for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
         exchange<K3, 3, 2>(v, lds, t);
-        // levels t = K3 + j on b: k = (b mod 2^j) 2^K3 + c
-        inv_phase<5, 1, 32>(v, utw, K3, K3, t & G::CM, p, pinv);
+        inv_phase<5, 1, 32, false>(v, utw, bt, p, pinv);
+        load_inv_tw<5>(bt, utw, G::TB, t);        // levels 5 + K3 + j on a: k = (a mod 2^j) 2^(5+K3) + (b, c)
+        SCHED_FENCE();
 #pragma unroll
-        for (int r = 0; r < 32; r++) {
-            v[r] = fp_norm(v[r], p, pinv);
-        }
+        for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
         exchange<K3, 2, 1>(v, lds, t);
-        // levels t = 5 + K3 + j on a: k = (a mod 2^j) 2^(5+K3) + (b, c)
-        inv_phase<5, 1, 32>(v, utw, G::TB, G::TB, t, p, pinv);
+        inv_phase<5, 1, 32, false>(v, utw, bt, p, pinv);
     }
 
     // ---- store (mapping P1) ----
@@ -268,40 +345,58 @@ __global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTa
 #pragma unroll
         for (int r = 0; r < 32; r++) (dst + (r << G::TB))[t] = fp_canonical(v[r], p, pinv);
     } else if (MODE == FP_FWD_CONV_FINAL) {
-        // out = (acc - conv) * P^-1 (+ addend)
+        // out = (acc - conv) * P^-1 (+ addend); operands fetched eight at a time ahead of their use
         const u64* acc = a.acc + b * a.acc_bs + (u64)(pos + a.acc_pos_shift) * G::N;
         u64* dst = a.out + b * a.out_bs + (u64)pos * G::N;
-        const double pin = a.pinv_tab[prime];
+        const double pin = as_const(a.pinv_tab)[prime];
         const bool with_add = a.add && (int)(b % a.add_div) < a.add_polys;
-        const u64* add = with_add ? a.add + (b / a.add_div) * a.add_bs + (b % a.add_div) * a.add_ps + (u64)pos * G::N : nullptr;
+        const u64* add = with_add ? a.add + (b / a.add_div) * a.add_bs + (b % a.add_div) * a.add_ps + (u64)pos * G::N : acc;
+        int tg = t;
+        asm volatile("" : "+v"(tg));
 #pragma unroll
-        for (int r = 0; r < 32; r++) {
-            double x = fp_from_u64((acc + (r << G::TB))[t]) - fp_norm(v[r], p, pinv);
-            x = fp_mulmod(x, pin, p, pinv);
-            if (with_add) {
-                if (a.add_galois) x += fp_from_u64(add[galois_src_fp((uint32_t)((r << G::TB) | t), a.add_galois, G::LOGN)]);
-                else x += fp_from_u64((add + (r << G::TB))[t]);
+        for (int c = 0; c < 4; c++) {
+            u64 va[8], vb[8];
+            SCHED_FENCE();
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                const int r = c * 8 + k;
+                va[k] = (acc + (r << G::TB))[t];
+                if (with_add && a.add_galois) vb[k] = add[galois_src_fp((uint32_t)((r << G::TB) | tg), a.add_galois, G::LOGN)];
+                else vb[k] = (add + (r << G::TB))[t];
             }
-            (dst + (r << G::TB))[t] = fp_canonical(x, p, pinv);
+            SCHED_FENCE();
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                const int r = c * 8 + k;
+                double x = fp_from_u64(va[k]) - fp_norm(v[r], p, pinv);
+                x = fp_mulmod(x, pin, p, pinv);
+                if (with_add) x += fp_from_u64(vb[k]);
+                (dst + (r << G::TB))[t] = fp_canonical(x, p, pinv);
+            }
         }
     } else {
         const double* vtw = a.vtw + (u64)prime * G::N;
-        if (MODE == FP_INV_PLAIN) {
-            u64* dst = a.out + b * a.out_bs + (u64)pos * G::N;
+        const double post = MODE == FP_INV_TO_Y ? as_const(a.post)[e] : 1.0;
+        u64* dst = a.out + b * a.out_bs + (u64)pos * G::N;
+        double* ydst = a.yout + b * a.yout_bs + (u64)pos * G::N;
 #pragma unroll
-            for (int r = 0; r < 32; r++)
-                (dst + (r << G::TB))[t] = fp_canonical(fp_mulmod(v[r], (vtw + (r << G::TB))[t], p, pinv), p, pinv);
-        } else {
-            double* dst = a.yout + b * a.yout_bs + (u64)pos * G::N;
-            const double post = a.post[e];
+        for (int c = 0; c < 4; c++) {
+            double w8[8];
+            SCHED_FENCE();
 #pragma unroll
-            for (int r = 0; r < 32; r++) {
-                const double x = fp_mulmod(v[r], (vtw + (r << G::TB))[t], p, pinv);
-                (dst + (r << G::TB))[t] = fp_norm(fp_mulmod(x, post, p, pinv), p, pinv);
+            for (int k = 0; k < 8; k++) w8[k] = (vtw + ((c * 8 + k) << G::TB))[t];
+            SCHED_FENCE();
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                const int r = c * 8 + k;
+                const double x = fp_mulmod(v[r], w8[k], p, pinv);
+                if (MODE == FP_INV_PLAIN) (dst + (r << G::TB))[t] = fp_canonical(x, p, pinv);
+                else (ydst + (r << G::TB))[t] = fp_norm(fp_mulmod(x, post, p, pinv), p, pinv);
             }
         }
     }
     STAMP(9);
+    }  // task loop
 }
 
 template <int K3, int MODE>
@@ -320,7 +415,28 @@ static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hip
     ProfScope prof__(names[MODE], st);
     FpArgs args = a;
     args.n_tasks = (int)(n_batch * tk.period);
-    const unsigned grid = (unsigned)((args.n_tasks + 7) / 8) * 8;
+    static int n_cu = 0;
+    if (!n_cu) {
+        hipDeviceProp_t prop;
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorInvalidDevice;
+        n_cu = prop.multiProcessorCount > 8 ? prop.multiProcessorCount : 8;
+    }
+    // as many workgroups as are resident on the chip at once
+    static int per_cu = 0;
+    if (!per_cu) {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ntt_fp_kernel<K3, MODE>, G::THREADS, lds_bytes) !=
+                hipSuccess || nb < 1)
+            nb = 1;
+        per_cu = nb;
+    }
+    unsigned grid = (unsigned)(n_cu * per_cu) & ~7u;
+    const unsigned need = (unsigned)((args.n_tasks + 7) / 8) * 8;
+    if (grid > need) grid = need;
+#ifdef NTT_FP_NONPERSISTENT
+    grid = need;
+#endif
     hipLaunchKernelGGL((ntt_fp_kernel<K3, MODE>), dim3(grid), dim3(G::THREADS), lds_bytes, st, args, tk);
     return hipGetLastError();
 }
