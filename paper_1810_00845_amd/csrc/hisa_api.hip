@@ -1232,7 +1232,7 @@ extern "C" int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size
     TRY(gather_batch(ctx, in, n, &bi));
     const size_t nn = ctx->N, lw = (size_t)l * nn;
     int rc = HISA_OK;
-    if (ctx->tabs.fp_ok) {
+    if (ctx->tabs.fp_ok && ctx->dnum <= 8) {
         // fused fp64 pipeline: both automorphisms are gathers inside its first and last kernels
         rc = alloc_ct_batch(ctx, n, 2, (uint32_t)l, 0.0, out);
         if (rc == HISA_OK) {
@@ -1298,7 +1298,7 @@ extern "C" int hisa_relinearize_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t
     std::vector<hisa_ct*> fresh(n);
     int rc = alloc_ct_batch(ctx, n, 2, (uint32_t)l, 0.0, fresh.data());
     if (rc == HISA_OK) {
-        if (ctx->tabs.fp_ok)
+        if (ctx->tabs.fp_ok && ctx->dnum <= 8)
             rc = key_switch_core_fp(ctx, bi.base + 2 * lw, bi.stride, 0, n, l, it->second, bi.base, bi.stride, 2, fresh[0]->data);
         else
             rc = key_switch_core(ctx, bi.base + 2 * lw, bi.stride, n, l, it->second, bi.base, bi.stride, 2, 0, fresh[0]->data);

@@ -468,7 +468,10 @@ hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk,
 // inner product with the switching key, fp64
 // ---------------------------------------------------------------------------
 #define IPF_NT 256
-#define IPF_BCHUNK 8
+#define IPF_ZSPLIT 4
+#define IPF_MAXD 8
+// One thread owns one coefficient of one extended limb: the 2*digits key values stay in registers while the
+// thread walks over its share of the batch, so the key is read IPF_ZSPLIT times per batch, not once per ciphertext.
 __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits,
                                                                   int l, int K, int L, int alpha, const u64* key, int total,
                                                                   const u64* own_src, u64 own_bs, u64 galois, u64* acc, u64 acc_bs,
@@ -479,29 +482,41 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime*
     const int ext_limbs = l + K;
     const int prime = x < l ? x : L + (x - l);
     const int own_digit = x < l ? x / alpha : -1;
-    const FpPrime fp = fprimes[prime];
+    const double p = as_const(&fprimes[prime].p)[0], pinv = as_const(&fprimes[prime].p)[1];
     const uint32_t jsrc = galois ? galois_src_fp(j, galois, log_n) : j;
-    const u64 b0 = (u64)blockIdx.z * IPF_BCHUNK;
-    const u64 b1 = b0 + IPF_BCHUNK < n_batch ? b0 + IPF_BCHUNK : n_batch;
+    const u64 per = (n_batch + IPF_ZSPLIT - 1) / IPF_ZSPLIT;
+    const u64 b0 = (u64)blockIdx.z * per;
+    const u64 b1 = b0 + per < n_batch ? b0 + per : n_batch;
+    double kb[IPF_MAXD], ka[IPF_MAXD];
+#pragma unroll
+    for (int d = 0; d < IPF_MAXD; d++) {
+        if (d < digits) {
+            kb[d] = fp_from_u64(key[(((u64)d * 2 + 0) * total + prime) * n + j]);
+            ka[d] = fp_from_u64(key[(((u64)d * 2 + 1) * total + prime) * n + j]);
+        }
+    }
     for (u64 b = b0; b < b1; b++) {
         double sb = 0.0, sa = 0.0;
-        for (int d = 0; d < digits; d++) {
-            const u64 ev = d == own_digit ? own_src[b * own_bs + (u64)x * n + jsrc]
-                                          : ext[b * ext_bs + ((u64)d * ext_limbs + x) * n + j];
-            const double e = fp_from_u64(ev);
-            sb += fp_mulmod(e, fp_from_u64(key[(((u64)d * 2 + 0) * total + prime) * n + j]), fp.p, fp.pinv);
-            sa += fp_mulmod(e, fp_from_u64(key[(((u64)d * 2 + 1) * total + prime) * n + j]), fp.p, fp.pinv);
-            if ((d & 7) == 7) { sb = fp_norm(sb, fp.p, fp.pinv); sa = fp_norm(sa, fp.p, fp.pinv); }
+#pragma unroll
+        for (int d = 0; d < IPF_MAXD; d++) {
+            if (d < digits) {
+                const u64 ev = d == own_digit ? own_src[b * own_bs + (u64)x * n + jsrc]
+                                              : ext[b * ext_bs + ((u64)d * ext_limbs + x) * n + j];
+                const double e = fp_from_u64(ev);
+                sb += fp_mulmod(e, kb[d], p, pinv);
+                sa += fp_mulmod(e, ka[d], p, pinv);
+            }
         }
-        acc[b * acc_bs + (u64)x * n + j] = fp_canonical(sb, fp.p, fp.pinv);
-        acc[b * acc_bs + ((u64)ext_limbs + x) * n + j] = fp_canonical(sa, fp.p, fp.pinv);
+        acc[b * acc_bs + (u64)x * n + j] = fp_canonical(sb, p, pinv);
+        acc[b * acc_bs + ((u64)ext_limbs + x) * n + j] = fp_canonical(sa, p, pinv);
     }
 }
 
 hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
                                    int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois, u64* acc,
                                    u64 acc_bs, u64 n_batch, int log_n, hipStream_t st) {
-    dim3 grid((1u << log_n) / IPF_NT, l + K, (unsigned)((n_batch + IPF_BCHUNK - 1) / IPF_BCHUNK));
+    if (digits > IPF_MAXD) return hipErrorInvalidValue;  // the caller falls back to the integer path
+    dim3 grid((1u << log_n) / IPF_NT, l + K, IPF_ZSPLIT);
     ProfScope prof__("inner_product_fp_kernel", st);
     hipLaunchKernelGGL(inner_product_fp_kernel, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha, key,
                        total, own_src, own_bs, galois, acc, acc_bs, n_batch, log_n);
