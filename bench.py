@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--cpu-sample", type=int, default=32, help="ciphertexts for the oracle baseline (0 = skip)")
     ap.add_argument("--no-ops", action="store_true", help="skip the per-primitive timings")
+    ap.add_argument("--pmc-calibrate", action="store_true",
+                    help="also run device-to-device copies of 1 GiB (a plain copy of known size, to scale rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -158,6 +161,14 @@ def main():
            "staged_bytes_per_ct": int(staged), "strict_bytes_per_ct": int(strict),
            "staged_GBs": round(staged / per_ct_s / 1e9, 1), "frac_of_hbm_staged": round(staged / per_ct_s / 1e9 / HBM_PEAK_GBS, 4),
            "frac_of_hbm_strict": round(strict / per_ct_s / 1e9 / HBM_PEAK_GBS, 4)}
+
+    if args.pmc_calibrate:
+        src = torch.ones(1 << 27, dtype=torch.int64, device="cuda")   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ops = {}
     if not args.no_ops:
