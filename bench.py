@@ -40,11 +40,25 @@ def algorithmic_bytes_rot_left(N, l, K, alpha, B):
     out["moddown_final_kernel"] = 7 * l * LP * B
     # fused fp64 pipeline (primes below 2^50): what each launch set must read and write once
     conv_out = sum(ext - a for a in sizes)
-    out["ntt_fp_kernel<inv_to_y>"] = 2 * LP * B * (l + 2 * K)
-    out["ntt_fp_kernel<conv_fwd>"] = LP * B * (l + conv_out)
+    # kernel names as rocprofv3 prints them: ntt_fp_kernel<log2 N - 10, mode>; mode 2 = inverse transform to the
+    # conversion input, 3 = base conversion + forward transform, 4 = the same + final combine
+    k3 = "%d" % (N.bit_length() - 1 - 10)
+    out["ntt_fp_kernel<%s, 2>" % k3] = 2 * LP * B * (l + 2 * K)
+    out["ntt_fp_kernel<%s, 3>" % k3] = LP * B * (l + conv_out)
     out["inner_product_fp_kernel"] = LP * (B * (conv_out + l + 2 * ext) + digits * 2 * ext)
-    out["ntt_fp_kernel<conv_fwd_final>"] = LP * B * (2 * K + 2 * l + l + 2 * l)
+    out["ntt_fp_kernel<%s, 4>" % k3] = LP * B * (2 * K + 2 * l + l + 2 * l)
     return out
+
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the headline configuration
+# (profiles/rot_left_n15_l16_dnum3_b64_fused_fp64.md; FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0, the factors a
+# 1 GiB device-to-device copy reads back)
+MEASURED_TRAFFIC = {
+    "ntt_fp_kernel<5, 3>": (2 * 84585.5 + 309248.0) * 1024,
+    "ntt_fp_kernel<5, 4>": (2 * 560048.3 + 585728.0) * 1024,
+    "ntt_fp_kernel<5, 2>": (2 * 182285.8 + 254976.0) * 1024,
+    "inner_product_fp_kernel": (2 * 608301.3 + 720896.0) * 1024,
+}
 
 
 def staged_bytes_rot_left(N, l, K, alpha, dnum_key, L, B):
@@ -151,8 +165,11 @@ def main():
         kernels[name] = {"launches_per_step": cnt / prof_steps, "ms_per_step": round(per_step_ms, 4),
                          "avg_launch_us": round(1e3 * ms / cnt, 2), "algorithmic_GBs": round(gbs, 1)}
     dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    headline = (log_n, L, dnum, B, args.bits) == (15, 16, 3, 64, 50)
     roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["algorithmic_GBs"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(kernels[dom]["algorithmic_GBs"] / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(kernels[dom]["algorithmic_GBs"] / HBM_PEAK_GBS, 4),
+                "traffic": int(MEASURED_TRAFFIC[dom]) if headline and dom in MEASURED_TRAFFIC else None,
+                "algorithmic_bytes_per_launch": int(alg.get(dom, 0) / max(kernels[dom]["launches_per_step"], 1)),
                 "avg_launch_us": kernels[dom]["avg_launch_us"],
                 "share_of_step": round(kernels[dom]["ms_per_step"] / sum(k["ms_per_step"] for k in kernels.values()), 3)}
     staged, strict = staged_bytes_rot_left(N, L, K, alpha, dnum, L, B)

@@ -410,9 +410,13 @@ static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hip
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const char* names[] = {"ntt_fp_kernel<fwd>", "ntt_fp_kernel<inv>", "ntt_fp_kernel<inv_to_y>", "ntt_fp_kernel<conv_fwd>",
-                           "ntt_fp_kernel<conv_fwd_final>"};
-    ProfScope prof__(names[MODE], st);
+    // the name rocprofv3 prints for this instantiation: ntt_fp_kernel<K3, MODE>
+    static const char* const names[4][5] = {
+        {"ntt_fp_kernel<2, 0>", "ntt_fp_kernel<2, 1>", "ntt_fp_kernel<2, 2>", "ntt_fp_kernel<2, 3>", "ntt_fp_kernel<2, 4>"},
+        {"ntt_fp_kernel<3, 0>", "ntt_fp_kernel<3, 1>", "ntt_fp_kernel<3, 2>", "ntt_fp_kernel<3, 3>", "ntt_fp_kernel<3, 4>"},
+        {"ntt_fp_kernel<4, 0>", "ntt_fp_kernel<4, 1>", "ntt_fp_kernel<4, 2>", "ntt_fp_kernel<4, 3>", "ntt_fp_kernel<4, 4>"},
+        {"ntt_fp_kernel<5, 0>", "ntt_fp_kernel<5, 1>", "ntt_fp_kernel<5, 2>", "ntt_fp_kernel<5, 3>", "ntt_fp_kernel<5, 4>"}};
+    ProfScope prof__(names[K3 - 2][MODE], st);
     FpArgs args = a;
     args.n_tasks = (int)(n_batch * tk.period);
     static int n_cu = 0;
