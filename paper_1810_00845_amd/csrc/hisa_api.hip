@@ -1339,6 +1339,57 @@ extern "C" int hisa_max_scalar_div(hisa_ctx* ctx, const hisa_ct* ct, double ub, 
     return HISA_OK;
 }
 
+// Constants of the fp64 rescale at level l, device resident: `total` ones (the base conversion from a one-prime
+// basis has hat = 1), then q_{l-1}^-1 mod q_i as centred doubles for i < l-1.
+static int fp_rescale_tables(hisa_ctx* ctx, int l, double** ones, double** qlinv) {
+    const u64 KEY = 8192 + (u64)l;
+    auto it = ctx->aux.find(KEY);
+    if (it == ctx->aux.end()) {
+        std::vector<double> t((size_t)ctx->total + l, 1.0);
+        for (int i = 0; i < l - 1; i++)
+            t[ctx->total + i] = centred_double(hm::inv(ctx->mod[l - 1] % ctx->mod[i], ctx->mod[i]), ctx->mod[i]);
+        double* d = nullptr;
+        HIP_TRY(ctx, upload(&d, t));
+        it = ctx->aux.emplace(KEY, SwitchKey{new DevBlock{d, t.size() * sizeof(double), 1}, (u64*)d}).first;
+    }
+    *ones = (double*)it->second.data;
+    *qlinv = (double*)it->second.data + ctx->total;
+    return HISA_OK;
+}
+
+// Rescale with the fused fp64 kernels: the last limb goes to centred coefficient form (one inverse transform per
+// polynomial), and one launch reduces it to every remaining prime, transforms it and forms (c_i - r) q_{l-1}^-1.
+// It is the special-prime division of the key switch with a single "special" prime q_{l-1}.
+static int rescale_core_fp(hisa_ctx* ctx, const u64* in, size_t n_bp, int l, u64* out) {
+    const size_t nn = ctx->N;
+    const int log_n = (int)ctx->log_n;
+    Temp y(ctx, n_bp * nn * sizeof(double));
+    if (!y.ok()) return HISA_ERR_OOM;
+    double *ones, *qlinv;
+    TRY(fp_rescale_tables(ctx, l, &ones, &qlinv));
+    FpArgs base = {};
+    base.fprimes = ctx->tabs.fprimes; base.ftw = ctx->tabs.ftw; base.utw = ctx->tabs.utw; base.vtw = ctx->tabs.vtw;
+    {
+        FpArgs a = base;
+        FpTask tk = {};
+        tk.period = 1; tk.pos[0] = 0; tk.prime[0] = (int16_t)(l - 1);
+        a.in = in; a.in_bs = (u64)l * nn; a.in_pos_shift = l - 1; a.post = ones;
+        a.yout = y.as<double>(); a.yout_bs = nn;
+        HIP_TRY(ctx, launch_ntt_fp(FP_INV_TO_Y, log_n, a, tk, n_bp, ctx->stream));
+    }
+    {
+        FpArgs a = base;
+        FpTask tk = {};
+        tk.period = l - 1;
+        for (int i = 0; i < l - 1; i++) { tk.pos[i] = (int16_t)i; tk.prime[i] = (int16_t)i; }
+        a.y = y.as<double>(); a.y_bs = nn; a.y_pos0 = 0; a.conv_a = 1; a.total = (int)ctx->total; a.hat = ones;
+        a.acc = in; a.acc_bs = (u64)l * nn; a.acc_pos_shift = 0; a.pinv_tab = qlinv;
+        a.out = out; a.out_bs = (u64)(l - 1) * nn;
+        HIP_TRY(ctx, launch_ntt_fp(FP_FWD_CONV_FINAL, log_n, a, tk, n_bp, ctx->stream));
+    }
+    return HISA_OK;
+}
+
 extern "C" int hisa_rescale_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n) {
     if (!ctx) return HISA_ERR_ARG;
     TRY(check_batch_shape(ctx, (const hisa_ct* const*)cts, n, 0));
@@ -1349,7 +1400,17 @@ extern "C" int hisa_rescale_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n) 
     TRY(gather_batch(ctx, (const hisa_ct* const*)cts, n, &bi));
     int rc = HISA_OK;
     std::vector<hisa_ct*> fresh(n);
-    {
+    if (ctx->tabs.fp_ok) {
+        rc = alloc_ct_batch(ctx, n, (uint32_t)polys, (uint32_t)(l - 1), 0.0, fresh.data());
+        if (rc == HISA_OK) {
+            rc = rescale_core_fp(ctx, bi.base, n_bp, l, fresh[0]->data);
+            for (size_t i = 0; i < n; i++) {
+                fresh[i]->scale = cts[i]->scale / (double)ctx->mod[l - 1];
+                if (rc == HISA_OK) adopt(ctx, cts[i], fresh[i]);
+                else hisa_free(ctx, fresh[i]);
+            }
+        }
+    } else {
         Temp last(ctx, n_bp * nn * sizeof(u64));
         Temp r(ctx, n_bp * (size_t)(l - 1) * nn * sizeof(u64));
         if (!last.ok() || !r.ok()) rc = HISA_ERR_OOM;

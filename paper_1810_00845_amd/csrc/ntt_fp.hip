@@ -111,6 +111,10 @@ __device__ __forceinline__ void exchange(double (&v)[32], uint32_t* lds, int t) 
     for (int r = 0; r < 32; r++) v[r] = mk64(lo[r], hi[r]);
 }
 
+// Range: with centred twiddles (|w| <= 0.55 p after a factored product) a level takes max|v| = m p to at most
+// (1.21 m + 0.5) p, so five levels from m = 1 (canonical input) stay below 6.2 p and from m = 0.5 (normalised)
+// below 5.1 p, inside the 2^53 = 8 * 2^50 that exact integer arithmetic in doubles allows: one normalisation
+// per phase is enough and none is needed inside a phase.
 __device__ __forceinline__ void bfly(double& x, double& y, double w, double p, double pinv) {
 #ifdef NTT_FP_SKIP_COMPUTE
     const double t = y * w + p * pinv;
@@ -205,8 +209,15 @@ __device__ __forceinline__ uint32_t galois_src_fp(uint32_t i, u64 g, int log_n) 
     return __brev((e2 - 1) >> 1) >> (32 - log_n);
 }
 
+// Second launch bound: waves per SIMD the register allocation must leave room for.  N = 2^15 needs 4 (one
+// workgroup of 16 waves per CU, 128 registers).  At N = 2^14 the same cap lets two workgroups share a CU and
+// overlap one's transposes with the other's arithmetic (measured 16% faster than one workgroup with 256
+// registers); at N <= 2^13 the cap costs spills and the 256-register build is the faster one.
+#ifndef NTT_FP_MIN_WAVES
+#define NTT_FP_MIN_WAVES(K3) ((K3) >= 4 ? 4 : 2)
+#endif
 template <int K3, int MODE>
-__global__ __launch_bounds__(Geo<K3>::THREADS) void ntt_fp_kernel(FpArgs a, FpTask tk) {
+__global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp_kernel(FpArgs a, FpTask tk) {
     typedef Geo<K3> G;
     extern __shared__ uint32_t lds[];
     const int t = threadIdx.x;
@@ -458,6 +469,19 @@ static hipError_t dispatch_k3(int log_n, const FpArgs& a, const FpTask& tk, u64 
 
 hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
     if (n_batch == 0 || tk.period <= 0) return hipSuccess;
+    // every pointer a mode dereferences must be set: a missing one is a host error, not a device fault
+    if (tk.period > HISA_MAX_PRIMES || !a.fprimes) return hipErrorInvalidValue;
+    for (int e = 0; e < tk.period; e++)
+        if (tk.prime[e] < 0) return hipErrorInvalidValue;
+    const bool inv = mode == FP_INV_PLAIN || mode == FP_INV_TO_Y;
+    const bool conv = mode == FP_FWD_CONV || mode == FP_FWD_CONV_FINAL;
+    if (inv && (!a.in || !a.utw || !a.vtw)) return hipErrorInvalidValue;
+    if (!inv && !a.ftw) return hipErrorInvalidValue;
+    if (mode == FP_FWD_PLAIN && !a.in) return hipErrorInvalidValue;
+    if (mode == FP_INV_TO_Y && (!a.yout || !a.post)) return hipErrorInvalidValue;
+    if (mode != FP_INV_TO_Y && !a.out) return hipErrorInvalidValue;
+    if (conv && (!a.y || !a.hat || a.conv_a <= 0 || a.total <= 0)) return hipErrorInvalidValue;
+    if (mode == FP_FWD_CONV_FINAL && (!a.acc || !a.pinv_tab || (a.add && a.add_div <= 0))) return hipErrorInvalidValue;
     switch (mode) {
         case FP_FWD_PLAIN: return dispatch_k3<FP_FWD_PLAIN>(log_n, a, tk, n_batch, st);
         case FP_INV_PLAIN: return dispatch_k3<FP_INV_PLAIN>(log_n, a, tk, n_batch, st);
