@@ -31,23 +31,30 @@ struct Geo {
     // compile-time term of the register, so addressing needs one register per mapping, not one per element.
     // LDS word address = idx + (idx >> 5): one pad word per 32 keeps all three transposes bank-conflict free.
     static constexpr int LDS_WORDS = N + N / 32;
+    // Mapping 4 (K3 = 5 only): wave w holds coefficients [2048 w, 2048 (w+1)), lane <-> consecutive coefficients.
+    // At K3 = 5 a wave holds exactly that range in mappings 2 and 3 as well (both keep the top bits `a` in the
+    // thread index), so the transposes 2 <-> 3 <-> 4 stay inside a wave and need no workgroup barrier.
+    static constexpr bool WAVE_LOCAL = K3 == 5;
     template <int M> static __device__ __forceinline__ int thread_idx(int t) {
         if (M == 1) return t;
         if (M == 2) return ((t >> K3) << TB) | (t & CM);
-        return ((t >> 5) << TB) | ((t & 31) << K3);
+        if (M == 3) return ((t >> 5) << TB) | ((t & 31) << K3);
+        return ((t >> 6) << 11) | (t & 63);
     }
     template <int M> static constexpr int reg_idx(int r) {
-        return M == 1 ? (r << TB) : (M == 2 ? (r << K3) : (((r >> K3) << (K3 + TB)) | (r & CM)));
+        return M == 1 ? (r << TB)
+                      : (M == 2 ? (r << K3) : (M == 3 ? (((r >> K3) << (K3 + TB)) | (r & CM)) : (r << 6)));
     }
     template <int M> static __device__ __forceinline__ int thread_lds(int t) {
         if (M == 1) return t + (t >> 5);
         if (M == 2) return ((t >> K3) << TB) + ((t >> K3) << K3) + (t & CM);
-        return ((t >> 5) << TB) + ((t & 31) << K3) + ((t >> 5) << K3) + ((t & 31) >> (5 - K3));
+        if (M == 3) return ((t >> 5) << TB) + ((t & 31) << K3) + ((t >> 5) << K3) + ((t & 31) >> (5 - K3));
+        return ((t >> 6) << 11) + ((t >> 6) << 6) + (t & 63) + ((t & 63) >> 5);
     }
     template <int M> static constexpr int reg_lds(int r) {
         return M == 1 ? r * ((1 << TB) + (1 << (TB - 5)))
                       : (M == 2 ? (r << K3) + (r >> (5 - K3))
-                                : ((r >> K3) << (K3 + TB)) + ((r >> K3) << (2 * K3)) + (r & CM));
+                                : (M == 3 ? ((r >> K3) << (K3 + TB)) + ((r >> K3) << (2 * K3)) + (r & CM) : 66 * r));
     }
 };
 
@@ -78,35 +85,42 @@ __device__ __forceinline__ uint32_t lo32(double v) { return (uint32_t)__double_a
 __device__ __forceinline__ uint32_t hi32(double v) { return (uint32_t)((u64)__double_as_longlong(v) >> 32); }
 __device__ __forceinline__ double mk64(uint32_t lo, uint32_t hi) { return __longlong_as_double((long long)(((u64)hi << 32) | lo)); }
 
+// Synchronisation between the writes and the reads of a transpose.  A transpose inside one wave needs no hardware
+// barrier: a wave's LDS instructions execute in issue order, so its reads see its earlier writes and its later
+// writes cannot overtake its earlier reads; the compiler only has to keep that order.
+template <bool LOCAL>
+__device__ __forceinline__ void xchg_sync() {
+    if (LOCAL) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else {
+        __syncthreads();
+    }
+}
+
 // transpose between two register mappings through LDS, 32-bit halves one after the other
-template <int K3, int FROM, int TO>
+template <int K3, int FROM, int TO, bool LOCAL = false>
 __device__ __forceinline__ void exchange(double (&v)[32], uint32_t* lds, int t) {
     typedef Geo<K3> G;
     uint32_t* wr = lds + G::template thread_lds<FROM>(t);
     const uint32_t* rd = lds + G::template thread_lds<TO>(t);
-#ifdef NTT_FP_SKIP_XCHG
-    return;
-#endif
-#ifdef NTT_FP_ONLY_BARRIERS
-    __syncthreads(); __syncthreads(); __syncthreads(); __syncthreads();
-    return;
-#endif
     // the low words are dead once written, so the incoming low words take their registers: 64 live, not 96
     uint32_t lo[32], hi[32];
 #pragma unroll
     for (int r = 0; r < 32; r++) { lo[r] = lo32(v[r]); hi[r] = hi32(v[r]); }
 #pragma unroll
     for (int r = 0; r < 32; r++) wr[G::template reg_lds<FROM>(r)] = lo[r];
-    __syncthreads();
+    xchg_sync<LOCAL>();
 #pragma unroll
     for (int r = 0; r < 32; r++) lo[r] = rd[G::template reg_lds<TO>(r)];
-    __syncthreads();
+    xchg_sync<LOCAL>();
 #pragma unroll
     for (int r = 0; r < 32; r++) wr[G::template reg_lds<FROM>(r)] = hi[r];
-    __syncthreads();
+    xchg_sync<LOCAL>();
 #pragma unroll
     for (int r = 0; r < 32; r++) hi[r] = rd[G::template reg_lds<TO>(r)];
-    __syncthreads();
+    xchg_sync<LOCAL>();
 #pragma unroll
     for (int r = 0; r < 32; r++) v[r] = mk64(lo[r], hi[r]);
 }
@@ -234,6 +248,12 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     const int pos = tk.pos[e], prime = tk.prime[e];
     const double p = as_const(&a.fprimes[prime].p)[0], pinv = as_const(&a.fprimes[prime].p)[1];
     constexpr bool INV = (MODE == FP_INV_PLAIN || MODE == FP_INV_TO_Y);
+    // Global memory is touched in mapping 1 (lane <-> consecutive coefficients, register r a block of THREADS
+    // further) on the side of the transform whose first/last phase works on the top bits, and on the other side
+    // in mapping 4 where the transposes can stay inside a wave, else in mapping 1 again.
+    constexpr int MIN = (INV && G::WAVE_LOCAL) ? 4 : 1;   // mapping of the inverse transform's loads
+    constexpr int MOUT = (!INV && G::WAVE_LOCAL) ? 4 : 1; // mapping of the forward transform's stores
+    const int t_in = G::template thread_idx<MIN>(t), t_out = G::template thread_idx<MOUT>(t);
     double v[32];
     STAMP(0);
 
@@ -243,11 +263,14 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         if (INV && a.galois) {
             // a private copy of the lane id: keeps the 32 gather indices from being kept alive (and spilled) for the
             // address arithmetic of the store stage
-            int tg = t;
+            int tg = t_in;
             asm volatile("" : "+v"(tg));
 #pragma unroll
             for (int r = 0; r < 32; r++)
-                v[r] = fp_from_u64(src[galois_src_fp((uint32_t)((r << G::TB) | tg), a.galois, G::LOGN)]);
+                v[r] = fp_from_u64(src[galois_src_fp((uint32_t)(G::template reg_idx<MIN>(r) | tg), a.galois, G::LOGN)]);
+        } else if (INV) {
+#pragma unroll
+            for (int r = 0; r < 32; r++) v[r] = fp_from_u64((src + G::template reg_idx<MIN>(r))[t_in]);
         } else {
 #pragma unroll
             for (int r = 0; r < 32; r++) v[r] = fp_from_u64((src + (r << G::TB))[t]);
@@ -306,6 +329,9 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
         STAMP(2);
+        // with wave-local transposes the waves run apart: all of them must have left the buffer before this
+        // workgroup-wide transpose writes to it (its own last barrier guards the other direction)
+        if (G::WAVE_LOCAL) __syncthreads();
         exchange<K3, 1, 2>(v, lds, t);
         STAMP(3);
         fwd_phase<5, 1, 32, false>(v, tw, bt2, p, pinv);
@@ -321,16 +347,16 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
         STAMP(4);
-        exchange<K3, 2, 3>(v, lds, t);
+        exchange<K3, 2, 3, G::WAVE_LOCAL>(v, lds, t);
         STAMP(5);
         fwd_phase<K3, GROUPS, 1 << K3, false>(v, tw, bt3, p, pinv);
         STAMP(6);
-        exchange<K3, 3, 1>(v, lds, t);
+        exchange<K3, 3, MOUT, G::WAVE_LOCAL>(v, lds, t);
         STAMP(7);
     } else {
         const double* utw = a.utw + (u64)prime * G::N;
         double bt[5];
-        exchange<K3, 1, 3>(v, lds, t);
+        exchange<K3, MIN, 3, G::WAVE_LOCAL>(v, lds, t);
         {   // levels t = 0..K3-1 on c
             const double none[5] = {};
             inv_phase<K3, 1 << (5 - K3), 1 << K3, true>(v, utw, none, p, pinv);
@@ -339,12 +365,13 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         SCHED_FENCE();
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
-        exchange<K3, 3, 2>(v, lds, t);
+        exchange<K3, 3, 2, G::WAVE_LOCAL>(v, lds, t);
         inv_phase<5, 1, 32, false>(v, utw, bt, p, pinv);
         load_inv_tw<5>(bt, utw, G::TB, t);        // levels 5 + K3 + j on a: k = (a mod 2^j) 2^(5+K3) + (b, c)
         SCHED_FENCE();
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
+        if (G::WAVE_LOCAL) __syncthreads();
         exchange<K3, 2, 1>(v, lds, t);
         inv_phase<5, 1, 32, false>(v, utw, bt, p, pinv);
     }
@@ -354,7 +381,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     if (MODE == FP_FWD_PLAIN || MODE == FP_FWD_CONV) {
         u64* dst = a.out + b * a.out_bs + (u64)pos * G::N;
 #pragma unroll
-        for (int r = 0; r < 32; r++) (dst + (r << G::TB))[t] = fp_canonical(v[r], p, pinv);
+        for (int r = 0; r < 32; r++) (dst + G::template reg_idx<MOUT>(r))[t_out] = fp_canonical(v[r], p, pinv);
     } else if (MODE == FP_FWD_CONV_FINAL) {
         // out = (acc - conv) * P^-1 (+ addend); operands fetched eight at a time ahead of their use
         const u64* acc = a.acc + b * a.acc_bs + (u64)(pos + a.acc_pos_shift) * G::N;
@@ -362,7 +389,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         const double pin = as_const(a.pinv_tab)[prime];
         const bool with_add = a.add && (int)(b % a.add_div) < a.add_polys;
         const u64* add = with_add ? a.add + (b / a.add_div) * a.add_bs + (b % a.add_div) * a.add_ps + (u64)pos * G::N : acc;
-        int tg = t;
+        int tg = t_out;
         asm volatile("" : "+v"(tg));
 #pragma unroll
         for (int c = 0; c < 4; c++) {
@@ -371,9 +398,10 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
 #pragma unroll
             for (int k = 0; k < 8; k++) {
                 const int r = c * 8 + k;
-                va[k] = (acc + (r << G::TB))[t];
-                if (with_add && a.add_galois) vb[k] = add[galois_src_fp((uint32_t)((r << G::TB) | tg), a.add_galois, G::LOGN)];
-                else vb[k] = (add + (r << G::TB))[t];
+                va[k] = (acc + G::template reg_idx<MOUT>(r))[t_out];
+                if (with_add && a.add_galois)
+                    vb[k] = add[galois_src_fp((uint32_t)(G::template reg_idx<MOUT>(r) | tg), a.add_galois, G::LOGN)];
+                else vb[k] = (add + G::template reg_idx<MOUT>(r))[t_out];
             }
             SCHED_FENCE();
 #pragma unroll
@@ -382,7 +410,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
                 double x = fp_from_u64(va[k]) - fp_norm(v[r], p, pinv);
                 x = fp_mulmod(x, pin, p, pinv);
                 if (with_add) x += fp_from_u64(vb[k]);
-                (dst + (r << G::TB))[t] = fp_canonical(x, p, pinv);
+                (dst + G::template reg_idx<MOUT>(r))[t_out] = fp_canonical(x, p, pinv);
             }
         }
     } else {
