@@ -50,15 +50,38 @@ def algorithmic_bytes_rot_left(N, l, K, alpha, B):
     return out
 
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the headline configuration
-# (profiles/rot_left_n15_l16_dnum3_b64_fused_fp64.md; FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0, the factors a
-# 1 GiB device-to-device copy reads back)
+def algorithmic_flops_rot_left(N, l, K, alpha, B):
+    """fp64 operations (an FMA counts two) the fused fp64 kernels of one batched rotLeft must execute, per kernel
+    name.  A modular product is mul, fma, mul, round, fma, add = 8; a butterfly is a product, an add and a
+    subtract = 10; a base-conversion term is a product and an add = 9.  Twiddle-factor products, range
+    normalisations and integer<->double conversions are implementation overhead and are not counted."""
+    log_n = N.bit_length() - 1
+    ext = l + K
+    digits = (l + alpha - 1) // alpha
+    sizes = [min(alpha, l - j * alpha) for j in range(digits)]
+    ntt = 10 * (N // 2) * log_n
+    k3 = "%d" % (log_n - 10)
+    out = {}
+    out["ntt_fp_kernel<%s, 2>" % k3] = B * (l + 2 * K) * (ntt + 2 * 8 * N)          # + untwist and (D/q)^-1 products
+    out["ntt_fp_kernel<%s, 3>" % k3] = B * sum((ext - a) * (ntt + 9 * a * N) for a in sizes)
+    out["ntt_fp_kernel<%s, 4>" % k3] = B * 2 * l * (ntt + 9 * K * N + 10 * N)       # + (acc - conv) P^-1 + addend
+    out["inner_product_fp_kernel"] = B * ext * N * 2 * 9 * digits
+    return out
+
+
+# Per launch on the headline configuration, from rocprofv3 --pmc runs (profiles/rot_left_n15_l16_dnum3_b64_fused_fp64.md):
+# HBM bytes = FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0 KiB (the factors a 1 GiB device-to-device copy reads back), and the
+# share of the CUs' vector-ALU issue slots in use = SQ_INSTS_VALU * 4 cycles / (4 SIMDs * SQ_BUSY_CU_CYCLES).
 MEASURED_TRAFFIC = {
-    "ntt_fp_kernel<5, 3>": (2 * 84585.5 + 309248.0) * 1024,
-    "ntt_fp_kernel<5, 4>": (2 * 560048.3 + 585728.0) * 1024,
-    "ntt_fp_kernel<5, 2>": (2 * 182285.8 + 254976.0) * 1024,
+    "ntt_fp_kernel<5, 3>": (2 * 66622.0 + 275114.7) * 1024,
+    "ntt_fp_kernel<5, 4>": (2 * 527930.4 + 526336.0) * 1024,
+    "ntt_fp_kernel<5, 2>": (2 * 166570.4 + 229376.0) * 1024,
     "inner_product_fp_kernel": (2 * 608301.3 + 720896.0) * 1024,
 }
+MEASURED_VALU_BUSY = {
+    "ntt_fp_kernel<5, 3>": 0.61, "ntt_fp_kernel<5, 4>": 0.55, "ntt_fp_kernel<5, 2>": 0.61, "inner_product_fp_kernel": 0.28,
+}
+FP64_PEAK_TFLOPS = 78.6   # 256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz
 
 
 def staged_bytes_rot_left(N, l, K, alpha, dnum_key, L, B):
@@ -110,7 +133,7 @@ def main():
     ap.add_argument("--dnum", type=int, default=3)
     ap.add_argument("--bits", type=int, default=50)
     ap.add_argument("--batch", type=int, default=64)
-    ap.add_argument("--cpu-sample", type=int, default=32, help="ciphertexts for the oracle baseline (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=64, help="ciphertexts for the oracle baseline (0 = skip)")
     ap.add_argument("--no-ops", action="store_true", help="skip the per-primitive timings")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run device-to-device copies of 1 GiB (a plain copy of known size, to scale rocprofv3 "
@@ -166,12 +189,28 @@ def main():
                          "avg_launch_us": round(1e3 * ms / cnt, 2), "algorithmic_GBs": round(gbs, 1)}
     dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     headline = (log_n, L, dnum, B, args.bits) == (15, 16, 3, 64, 50)
-    roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["algorithmic_GBs"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(kernels[dom]["algorithmic_GBs"] / HBM_PEAK_GBS, 4),
-                "traffic": int(MEASURED_TRAFFIC[dom]) if headline and dom in MEASURED_TRAFFIC else None,
-                "algorithmic_bytes_per_launch": int(alg.get(dom, 0) / max(kernels[dom]["launches_per_step"], 1)),
-                "avg_launch_us": kernels[dom]["avg_launch_us"],
-                "share_of_step": round(kernels[dom]["ms_per_step"] / sum(k["ms_per_step"] for k in kernels.values()), 3)}
+    flops = algorithmic_flops_rot_left(N, L, K, alpha, B)
+    for name, k in kernels.items():
+        if name in flops and k["ms_per_step"] > 0:
+            k["algorithmic_TFLOPs"] = round(flops[name] / (k["ms_per_step"] * 1e-3) / 1e12, 2)
+    launches = max(kernels[dom]["launches_per_step"], 1)
+    hbm_side = {"achieved_GBs": kernels[dom]["algorithmic_GBs"], "frac": round(kernels[dom]["algorithmic_GBs"] / HBM_PEAK_GBS, 4),
+                "algorithmic_bytes_per_launch": int(alg.get(dom, 0) / launches)}
+    if dom in flops:
+        # the transform kernels are bound by vector-ALU issue (counters: 55-61 % of the issue slots busy, 17 % of the
+        # HBM peak), so the roofline is the fp64 vector peak; the HBM reading stays beside it
+        tf = kernels[dom]["algorithmic_TFLOPs"]
+        roofline = {"kernel": dom, "bound": "alu", "achieved": tf, "peak": FP64_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tf / FP64_PEAK_TFLOPS, 4),
+                    "algorithmic_flops_per_launch": int(flops[dom] / launches),
+                    "valu_issue_busy": MEASURED_VALU_BUSY.get(dom) if headline else None, "hbm": hbm_side}
+    else:
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": hbm_side["achieved_GBs"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": hbm_side["frac"],
+                    "algorithmic_bytes_per_launch": hbm_side["algorithmic_bytes_per_launch"]}
+    roofline["traffic"] = int(MEASURED_TRAFFIC[dom]) if headline and dom in MEASURED_TRAFFIC else None
+    roofline["avg_launch_us"] = kernels[dom]["avg_launch_us"]
+    roofline["share_of_step"] = round(kernels[dom]["ms_per_step"] / sum(k["ms_per_step"] for k in kernels.values()), 3)
     staged, strict = staged_bytes_rot_left(N, L, K, alpha, dnum, L, B)
     per_ct_s = dt / (B * args.steps)
     rot = {"us_per_ct": round(per_ct_s * 1e6, 2),
