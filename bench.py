@@ -123,6 +123,30 @@ def cpu_baseline(log_n, q_bits, dnum, special_bits, seed, sample, steps):
             "sample": "%d ciphertexts of the same N, limbs, dnum, one rotLeft(%d) each, %.1f s" % (sample, steps[0], dt)}
 
 
+def network_latencies():
+    """Encrypted inference latency of the LeNet-shaped networks (BASELINE configs 3 and 4): encrypt-done to the
+    last output ciphertext ready, one image, rotation and relinearisation keys resident, weights encoded inside
+    the timed region (median of 3 after one set-up pass that also generates the keys)."""
+    import numpy as np
+    from paper_1810_00845_amd import hisa, nets
+    out = {}
+    for name, paper in (("lenet_small", "LeNet-5-small: 8 s (HEAAN, 16 Xeon threads)"),
+                        ("lenet_medium", "LeNet-5-medium: 51 s (HEAAN, 16 Xeon threads)")):
+        params, layers, x = getattr(nets, name)()
+        ctx = hisa.Context(params["log_n"], params["q_bits"], params["dnum"], params["special_bits"], seed=11)
+        ctx.keygen()
+        limbs = len(params["q_bits"])
+        nets.run_encrypted(ctx, layers, x, params["scale"], limbs, make_keys=True)
+        runs = [nets.run_encrypted(ctx, layers, x, params["scale"], limbs) for _ in range(3)]
+        lat = sorted(r[1] for r in runs)[1]
+        per_layer = runs[0][2]
+        out[name] = {"latency_ms": round(lat * 1e3, 2), "log_n": params["log_n"], "limbs": limbs, "dnum": params["dnum"],
+                     "layers_ms": [[k, round(s * 1e3, 2)] for k, s in per_layer],
+                     "paper_context": paper, "data": "seeded random weights and image"}
+        ctx.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -135,6 +159,7 @@ def main():
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--cpu-sample", type=int, default=64, help="ciphertexts for the oracle baseline (0 = skip)")
     ap.add_argument("--no-ops", action="store_true", help="skip the per-primitive timings")
+    ap.add_argument("--no-nets", action="store_true", help="skip the encrypted-network latencies")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run device-to-device copies of 1 GiB (a plain copy of known size, to scale rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -218,6 +243,10 @@ def main():
            "staged_GBs": round(staged / per_ct_s / 1e9, 1), "frac_of_hbm_staged": round(staged / per_ct_s / 1e9 / HBM_PEAK_GBS, 4),
            "frac_of_hbm_strict": round(strict / per_ct_s / 1e9 / HBM_PEAK_GBS, 4)}
 
+    nets_out = None
+    if not args.no_nets:
+        nets_out = network_latencies()
+
     if args.pmc_calibrate:
         src = torch.ones(1 << 27, dtype=torch.int64, device="cuda")   # 1 GiB
         dst = torch.empty_like(src)
@@ -275,7 +304,8 @@ def main():
         "config": {"workload": "primitive micro-benchmark: rotLeft over a batch of %d random ciphertexts, N=2^%d, "
                                "%d limbs of %d-bit primes, dnum %d, steps {1,7,64}" % (B, log_n, L, args.bits, dnum),
                    "log_n": log_n, "limbs": L, "dnum": dnum, "special_primes": K, "batch": B},
-        "roofline": roofline, "rot_left": rot, "kernels": kernels, "ops": ops, "cpu_baseline": base}))
+        "roofline": roofline, "rot_left": rot, "kernels": kernels, "ops": ops, "networks": nets_out,
+        "cpu_baseline": base}))
 
 
 if __name__ == "__main__":
