@@ -124,20 +124,22 @@ def cpu_baseline(log_n, q_bits, dnum, special_bits, seed, sample, steps):
 
 
 def network_latencies():
-    """Encrypted inference latency of the LeNet-shaped networks (BASELINE configs 3 and 4): encrypt-done to the
+    """Encrypted inference latency of the benchmark networks (BASELINE configs 3, 4 and 5): encrypt-done to the
     last output ciphertext ready, one image, rotation and relinearisation keys resident, weights encoded inside
     the timed region (median of 3 after one set-up pass that also generates the keys)."""
     import numpy as np
     from paper_1810_00845_amd import hisa, nets
     out = {}
     for name, paper in (("lenet_small", "LeNet-5-small: 8 s (HEAAN, 16 Xeon threads)"),
-                        ("lenet_medium", "LeNet-5-medium: 51 s (HEAAN, 16 Xeon threads)")):
+                        ("lenet_medium", "LeNet-5-medium: 51 s (HEAAN, 16 Xeon threads)"),
+                        ("squeezenet_cifar", "SqueezeNet-CIFAR: 1342 s (HEAAN, 16 Xeon threads)")):
         params, layers, x = getattr(nets, name)()
         ctx = hisa.Context(params["log_n"], params["q_bits"], params["dnum"], params["special_bits"], seed=11)
         ctx.keygen()
         limbs = len(params["q_bits"])
-        nets.run_encrypted(ctx, layers, x, params["scale"], limbs, make_keys=True)
-        runs = [nets.run_encrypted(ctx, layers, x, params["scale"], limbs) for _ in range(3)]
+        border = params.get("border", 0)
+        nets.run_encrypted(ctx, layers, x, params["scale"], limbs, make_keys=True, border=border)
+        runs = [nets.run_encrypted(ctx, layers, x, params["scale"], limbs, border=border) for _ in range(3)]
         lat = sorted(r[1] for r in runs)[1]
         per_layer = runs[0][2]
         out[name] = {"latency_ms": round(lat * 1e3, 2), "log_n": params["log_n"], "limbs": limbs, "dnum": params["dnum"],

@@ -201,7 +201,8 @@ typedef struct {
     hisa_ct** cts;               /* batch*channels handles                    */
 } hisa_tensor;
 
-#define HISA_CONV_SCALAR 0 /* literal Algorithm 1: mulScalar by round(w * q_last), add, one divScalar          */
+#define HISA_CONV_SCALAR 0 /* literal Algorithm 1: mulScalar by round(w * q_last), add, one divScalar; the output */
+                           /* is not clean, except for a 1x1 stride-1 filter on a clean input                   */
 #define HISA_CONV_MASKED 1 /* weights at scale q_last / 2^25, then ONE mulPlain by the 0/1 mask of the valid    */
                            /* output positions (scale 2^25) before the divScalar: the output is clean          */
 #define HISA_CONV_PLAIN 2  /* one mulPlain per tap: plaintext = w * mask encoded at scale q_last                 */

@@ -127,8 +127,11 @@ def conv2d_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, mo
             if mode == CONV_MASKED:
                 acc = o.mul_plain(acc, mask_pt)
             outs.append(o.div_scalar(acc, o.max_scalar_div(acc, float("inf"))))
-    return OTensor(outs, t.batch, oc_n, oh, ow, t.h_stride * stride, t.w_stride * stride, t.offset,
-                   0 if mode == CONV_SCALAR else 1)
+    # Without the masking multiply the slots outside the valid outputs hold sums over neighbouring slots; only a
+    # 1x1 filter at stride 1 reads no neighbour, so there a clean input stays clean.
+    pointwise = fh == 1 and fw == 1 and stride == 1
+    clean = 1 if mode != CONV_SCALAR or (pointwise and t.clean) else 0
+    return OTensor(outs, t.batch, oc_n, oh, ow, t.h_stride * stride, t.w_stride * stride, t.offset, clean)
 
 
 def fc(o: Oracle, t: OTensor, w):

@@ -316,8 +316,10 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
         return rc;
     }
     for (size_t i = 0; i < outs.size(); i++) out->cts[i] = outs[i];
+    // unmasked outputs carry neighbour sums outside the valid positions, except for a 1x1 stride-1 filter
+    const bool keeps_zeros = g->fh == 1 && g->fw == 1 && g->stride == 1 && in->clean;
     fill_out_meta(out, B, OC, plan.out_h, plan.out_w, in->h_stride * g->stride, in->w_stride * g->stride, in->offset,
-                  g->mode == HISA_CONV_SCALAR ? 0u : 1u);
+                  (g->mode != HISA_CONV_SCALAR || keeps_zeros) ? 1u : 0u);
     return HISA_OK;
 }
 

@@ -9,6 +9,10 @@ linear layer) are multiplied into the next layer's weights here, on the host, be
     ("act", a, b)                            a x^2 + b x
     ("pool",)                                2x2 average pool
     ("fc", w[OUT][C][H][W])                  fully connected over the whole tensor
+    ("conv_same", w[FH][FW][IC][OC])         SAME convolution with the masking multiply (clean output)
+    ("fire", ws, w1, w3, a, b)               SqueezeNet fire module: 1x1 squeeze, activation, 1x1 and 3x3 (SAME)
+                                             expand convolutions whose outputs are concatenated along the channels
+    ("gap",)                                 global average pool: one value per channel
 """
 import time
 
@@ -49,11 +53,50 @@ def lenet_medium(seed=4):
     return params, layers, x
 
 
-def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False):
+def squeezenet_cifar(seed=5):
+    """BASELINE config 5: N = 2^15, 21 limbs, 32x32x3 image, conv3x3 3->64, four fire modules (squeeze 16, 16, 32,
+    32; expand 64+64, 64+64, 128+128, 128+128), 1x1 convolution to 10 classes, global average pool; a degree-2
+    activation after the first convolution, inside and after every fire module.  Weights are normal; fixed gains keep every layer's values within [-2, 2]."""
+    rng = np.random.default_rng(seed)
+    ab = rng.uniform(0.1, 0.5, (9, 2))
+    def conv(k, fh, ic, oc, std):
+        return synth.conv_weights(seed + k, fh, fh, ic, oc, dist="normal", std=std)
+    # gains found once on this seeded image and these seeded weights: every linear layer's largest output is 2
+    # (degree-2 activations of random networks otherwise shrink or blow up the values within a few layers)
+    fire_gain = [(1.84, 2.55, 3.61), (4.16, 2.21, 4.62), (1.88, 1.51, 2.71), (2.2, 1.29, 2.3)]
+    layers = [("conv_same", 0.753 * conv(1, 3, 3, 64, 0.2)), ("act", ab[0, 0], ab[0, 1])]
+    ic, k = 64, 2
+    for i, (sq, ex) in enumerate([(16, 64), (16, 64), (32, 128), (32, 128)]):
+        gs, g1, g3 = fire_gain[i]
+        layers.append(("fire", gs * conv(k, 1, ic, sq, 1.0 / np.sqrt(ic)), g1 * conv(k + 1, 1, sq, ex, 1.0 / np.sqrt(sq)),
+                       g3 * conv(k + 2, 3, sq, ex, 0.33 / np.sqrt(sq)), ab[1 + 2 * i, 0], ab[1 + 2 * i, 1]))
+        layers.append(("act", ab[2 + 2 * i, 0], ab[2 + 2 * i, 1]))
+        ic, k = 2 * ex, k + 3
+    layers += [("conv", 3.46 * conv(k, 1, ic, 10, 0.05), 1), ("gap",)]
+    params = dict(log_n=15, q_bits=[50] + [45] * 20, dnum=3, special_bits=50, scale=2.0 ** 45, border=1)
+    x = synth.image(seed + 40, 3, 32, 32)[None]
+    return params, layers, x
+
+
+def _concat_channels(ctx, a, b):
+    """Channel concatenation of two tensors of one image with identical layout, level and scale."""
+    from .hisa import CipherTensor
+    assert a.batch == 1 and b.batch == 1 and a.meta()[2:] == b.meta()[2:]
+    t = CipherTensor(ctx, list(a.cts) + list(b.cts), 1, a.channels + b.channels, a.height, a.width, a.h_stride,
+                     a.w_stride, a.offset, a.clean)
+    a.cts, b.cts = [], []   # the handles now belong to the concatenation
+    return t
+
+
+def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0):
     """Encrypts x, runs the layers, decrypts.  Returns (output array, seconds from encrypt-done to the last
     ciphertext ready, per-layer seconds).  With make_keys the rotation keys each layer asks for are generated
     on the way (set-up pass); otherwise they must be resident."""
-    t = ctx.tensor_encrypt(x, scale, limbs)
+    if border:   # leave `border` rows and columns of zero slots around every plane (SAME convolutions need them)
+        hs = x.shape[3] + 2 * border
+        t = ctx.tensor_encrypt(x, scale, limbs, h_stride=hs, offset=border * hs + border)
+    else:
+        t = ctx.tensor_encrypt(x, scale, limbs)
     ctx.sync()
     t_start = time.perf_counter()
     per_layer = []
@@ -77,6 +120,34 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False):
                 ctx.gen_rot_keys(ctx.pool_rot_steps(t))
             nxt = ctx.sum_pool2x2(t)
             pending *= 0.25
+        elif kind == "conv_same":
+            w = layer[1] * pending
+            pending = 1.0
+            fh, fw = w.shape[:2]
+            if make_keys:
+                ctx.gen_rot_keys(ctx.conv2d_rot_steps(t, fh, fw, pad_same=True))
+            nxt = ctx.conv2d(t, w, fh, fw, pad_same=True, mode=1)
+        elif kind == "fire":
+            ws, w1, w3, a, b = layer[1] * pending, layer[2], layer[3], layer[4], layer[5]
+            pending = 1.0
+            s0 = ctx.conv2d(t, ws, 1, 1)
+            s1 = ctx.poly2_act(s0, a, b)
+            s0.free()
+            if make_keys:
+                ctx.gen_rot_keys(ctx.conv2d_rot_steps(s1, 3, 3, pad_same=True))
+            e1 = ctx.conv2d(s1, w1 * a, 1, 1)
+            e3 = ctx.conv2d(s1, w3 * a, 3, 3, pad_same=True, mode=1)
+            s1.free()
+            nxt = _concat_channels(ctx, e1, e3)
+        elif kind == "gap":
+            c, hw = t.channels, t.height * t.width
+            w = np.zeros((c, c, t.height, t.width))
+            for k in range(c):
+                w[k, k] = pending / hw
+            pending = 1.0
+            if make_keys:
+                ctx.gen_rot_keys(ctx.fc_rot_steps(t))
+            nxt = ctx.fc(t, w)
         elif kind == "fc":
             w = layer[1] * pending
             pending = 1.0
