@@ -293,6 +293,14 @@ def main():
         t = time_op(ctx, relin, 5) - t_mul
         ops["relinearize"] = {"ms": round(t * 1e3, 4), "per_s": round(B / t, 1)}
 
+        def hoisted():
+            for row in ctx.rot_left_hoisted_batch(cts, rot_steps):
+                for c in row:
+                    c.free()
+        t = time_op(ctx, hoisted, 5)
+        ops["rot_left_hoisted_x3"] = {"ms": round(t * 1e3, 4), "per_s": round(3 * B / t, 1),
+                                      "note": "three rotations of each ciphertext sharing one decomposition of c1"}
+
     base = None
     if args.cpu_sample > 0:
         base = cpu_baseline(log_n, q_bits, dnum, args.bits, 1, args.cpu_sample, rot_steps)

@@ -171,6 +171,13 @@ int hisa_rescale(hisa_ctx* ctx, hisa_ct* ct);
  * are views of one device allocation.  rot_left_batch shares one rotation
  * amount (one key, read once per batch).  The *_assign_batch forms mutate. */
 int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n, int32_t steps, hisa_ct** out);
+/* Several rotations of the same n ciphertexts: out[s*n + i] = rotLeft(in[i], steps[s]), bit for bit what
+ * hisa_rot_left gives.  The digit decomposition and extension of c1 to the special primes (the first half of a key
+ * switch) is computed once and shared by all steps: it works coefficient by coefficient on centred values, so it
+ * commutes with the automorphism (the code motion of rotations of Sec. "Runtime", taken below the HISA boundary).
+ * Needs every step's key (HISA_ERR_NO_KEY before any work is queued); on error no handle is returned. */
+int hisa_rot_left_hoisted_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n, const int32_t* steps,
+                                size_t n_steps, hisa_ct** out);
 int hisa_relinearize_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n);
 int hisa_rescale_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n);
 int hisa_add_batch(hisa_ctx* ctx, const hisa_ct* const* a, const hisa_ct* const* b, size_t n, hisa_ct** out);

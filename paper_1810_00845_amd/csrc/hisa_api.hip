@@ -1143,51 +1143,79 @@ static int fp_post_tables(hisa_ctx* ctx, int l, double** post_q, double** post_p
 //   IP inner product with the key; a digit's own limbs are read from d itself             -> acc (l + K limbs, b|a)
 //   C  inverse transform of the K special limbs of acc times (P/p_m)^-1                    -> y2
 //   D  base conversion of y2 to q_i fused into the forward transform, then (acc - conv) P^-1 + addend -> out
-static int key_switch_core_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois, size_t B, int l, const SwitchKey& key,
-                              const u64* add, u64 add_bs, int add_polys, u64* out) {
-    const size_t n = ctx->N;
-    const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total;
-    const int ext_limbs = l + K, digits = (l + alpha - 1) / alpha, log_n = (int)ctx->log_n;
-    hipStream_t st = ctx->stream;
-    Temp y(ctx, B * l * n * sizeof(double));
-    Temp ext(ctx, B * (size_t)digits * ext_limbs * n * sizeof(u64));
-    Temp acc(ctx, B * 2 * (size_t)ext_limbs * n * sizeof(u64));
-    Temp y2(ctx, B * 2 * (size_t)K * n * sizeof(double));
-    if (!y.ok() || !ext.ok() || !acc.ok() || !y2.ok()) return HISA_ERR_OOM;
-    double *post_q, *post_p;
-    TRY(fp_post_tables(ctx, l, &post_q, &post_p));
+// A and B (the decomposition and ModUp) are one function, IP, C and D another, so that several rotations of the same
+// ciphertexts can share the first: the conversion works coefficient by coefficient on centred values, so it commutes
+// with the automorphism, which then becomes a gather on the extended digits inside IP.
+struct FpExt {
+    Temp y, ext;
+    int l, digits, ext_limbs;
+    u64 ext_bs;
+    FpExt(hisa_ctx* ctx, size_t B, int l_, int K, int alpha)
+        : y(ctx, B * (size_t)l_ * ctx->N * sizeof(double)),
+          ext(ctx, B * (size_t)((l_ + alpha - 1) / alpha) * (size_t)(l_ + K) * ctx->N * sizeof(u64)),
+          l(l_), digits((l_ + alpha - 1) / alpha), ext_limbs(l_ + K), ext_bs((u64)digits * ext_limbs * ctx->N) {}
+    bool ok() const { return y.ok() && ext.ok(); }
+};
+
+static FpArgs fp_base(hisa_ctx* ctx) {
     FpArgs base = {};
     base.fprimes = ctx->tabs.fprimes; base.ftw = ctx->tabs.ftw; base.utw = ctx->tabs.utw; base.vtw = ctx->tabs.vtw;
+    return base;
+}
+
+static int key_switch_modup_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois, size_t B, FpExt& x) {
+    const size_t n = ctx->N;
+    const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total, l = x.l;
+    const int log_n = (int)ctx->log_n;
+    hipStream_t st = ctx->stream;
+    double *post_q, *post_p;
+    TRY(fp_post_tables(ctx, l, &post_q, &post_p));
+    const FpArgs base = fp_base(ctx);
     {   // A
         FpArgs a = base;
         FpTask tk = {};
         tk.period = l;
         for (int i = 0; i < l; i++) { tk.pos[i] = (int16_t)i; tk.prime[i] = (int16_t)i; }
         a.in = d; a.in_bs = d_bs; a.galois = galois; a.post = post_q;
-        a.yout = y.as<double>(); a.yout_bs = (u64)l * n;
+        a.yout = x.y.as<double>(); a.yout_bs = (u64)l * n;
         HIP_TRY(ctx, launch_ntt_fp(FP_INV_TO_Y, log_n, a, tk, B, st));
     }
-    const u64 ext_bs = (u64)digits * ext_limbs * n;
-    for (int j = 0; j < digits; j++) {  // B
+    for (int j = 0; j < x.digits; j++) {  // B
         const int lo = j * alpha, hi = std::min(lo + alpha, l);
         ConvTable* tab;
         TRY(modup_table(ctx, j, hi - lo, &tab));
         FpArgs a = base;
         FpTask tk = {};
         int cnt = 0;
-        for (int x = 0; x < ext_limbs; x++) {
-            if (x >= lo && x < hi) continue;
-            tk.pos[cnt] = (int16_t)(j * ext_limbs + x);
-            tk.prime[cnt] = (int16_t)(x < l ? x : L + (x - l));
+        for (int e = 0; e < x.ext_limbs; e++) {
+            if (e >= lo && e < hi) continue;
+            tk.pos[cnt] = (int16_t)(j * x.ext_limbs + e);
+            tk.prime[cnt] = (int16_t)(e < l ? e : L + (e - l));
             cnt++;
         }
         tk.period = cnt;
-        a.y = y.as<double>(); a.y_bs = (u64)l * n; a.y_pos0 = lo; a.conv_a = hi - lo; a.total = total; a.hat = tab->d_hat_f;
-        a.out = ext.u(); a.out_bs = ext_bs;
+        a.y = x.y.as<double>(); a.y_bs = (u64)l * n; a.y_pos0 = lo; a.conv_a = hi - lo; a.total = total; a.hat = tab->d_hat_f;
+        a.out = x.ext.u(); a.out_bs = x.ext_bs;
         HIP_TRY(ctx, launch_ntt_fp(FP_FWD_CONV, log_n, a, tk, B, st));
     }
-    HIP_TRY(ctx, launch_inner_product_fp(ctx->tabs.fprimes, ext.u(), ext_bs, digits, l, K, L, alpha, key.data, total, d, d_bs,
-                                         galois, acc.u(), (u64)2 * ext_limbs * n, B, log_n, st));
+    return HISA_OK;
+}
+
+// IP, C, D.  `galois` is applied to the own-digit limbs read from d, to the addend, and (gather_ext) to the digits.
+static int key_switch_finish_fp(hisa_ctx* ctx, const FpExt& x, const u64* d, u64 d_bs, u64 galois, int gather_ext, size_t B,
+                                const SwitchKey& key, const u64* add, u64 add_bs, int add_polys, u64* out) {
+    const size_t n = ctx->N;
+    const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total, l = x.l;
+    const int ext_limbs = x.ext_limbs, log_n = (int)ctx->log_n;
+    hipStream_t st = ctx->stream;
+    Temp acc(ctx, B * 2 * (size_t)ext_limbs * n * sizeof(u64));
+    Temp y2(ctx, B * 2 * (size_t)K * n * sizeof(double));
+    if (!acc.ok() || !y2.ok()) return HISA_ERR_OOM;
+    double *post_q, *post_p;
+    TRY(fp_post_tables(ctx, l, &post_q, &post_p));
+    const FpArgs base = fp_base(ctx);
+    HIP_TRY(ctx, launch_inner_product_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, key.data, total, d,
+                                         d_bs, galois, gather_ext, acc.u(), (u64)2 * ext_limbs * n, B, log_n, st));
     {   // C: batch entries are (ciphertext, b|a) pairs
         FpArgs a = base;
         FpTask tk = {};
@@ -1209,6 +1237,14 @@ static int key_switch_core_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois,
         HIP_TRY(ctx, launch_ntt_fp(FP_FWD_CONV_FINAL, log_n, a, tk, B * 2, st));
     }
     return HISA_OK;
+}
+
+static int key_switch_core_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois, size_t B, int l, const SwitchKey& key,
+                              const u64* add, u64 add_bs, int add_polys, u64* out) {
+    FpExt x(ctx, B, l, (int)ctx->K, (int)ctx->alpha);
+    if (!x.ok()) return HISA_ERR_OOM;
+    TRY(key_switch_modup_fp(ctx, d, d_bs, galois, B, x));
+    return key_switch_finish_fp(ctx, x, d, d_bs, galois, 0, B, key, add, add_bs, add_polys, out);
 }
 
 extern "C" int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n, int32_t steps, hisa_ct** out) {
@@ -1254,6 +1290,51 @@ extern "C" int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size
         }
     }
     dev_release(ctx, bi.tmp);
+    return rc;
+}
+
+extern "C" int hisa_rot_left_hoisted_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n, const int32_t* steps,
+                                           size_t n_steps, hisa_ct** out) {
+    if (!ctx || !out || !steps || n_steps == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_batch_shape(ctx, in, n, 2));
+    for (size_t s = 0; s < n * n_steps; s++) out[s] = nullptr;
+    // every key must be there before any work is queued
+    std::vector<u64> gs(n_steps);
+    size_t switched = 0;
+    for (size_t s = 0; s < n_steps; s++) {
+        gs[s] = galois_of(ctx, steps[s]);
+        if (gs[s] == 0) continue;
+        switched++;
+        if (ctx->keys.find(gs[s]) == ctx->keys.end())
+            return fail(ctx, HISA_ERR_NO_KEY, "no rotation key for %d slots (galois element %llu)", steps[s],
+                        (unsigned long long)gs[s]);
+    }
+    const int l = (int)in[0]->limbs;
+    int rc = HISA_OK;
+    if (switched < 2 || !(ctx->tabs.fp_ok && ctx->dnum <= 8)) {   // nothing to share, or no fused path: one by one
+        for (size_t s = 0; s < n_steps && rc == HISA_OK; s++) rc = hisa_rot_left_batch(ctx, in, n, steps[s], out + s * n);
+    } else {
+        BatchIn bi;
+        TRY(gather_batch(ctx, in, n, &bi));
+        const size_t lw = (size_t)l * ctx->N;
+        {
+            FpExt x(ctx, n, l, (int)ctx->K, (int)ctx->alpha);
+            if (!x.ok()) rc = HISA_ERR_OOM;
+            if (rc == HISA_OK) rc = key_switch_modup_fp(ctx, bi.base + lw, bi.stride, 0, n, x);
+            for (size_t s = 0; s < n_steps && rc == HISA_OK; s++) {
+                if (gs[s] == 0) { rc = hisa_rot_left_batch(ctx, in, n, steps[s], out + s * n); continue; }
+                rc = alloc_ct_batch(ctx, n, 2, (uint32_t)l, 0.0, out + s * n);
+                if (rc != HISA_OK) break;
+                for (size_t i = 0; i < n; i++) out[s * n + i]->scale = in[i]->scale;
+                rc = key_switch_finish_fp(ctx, x, bi.base + lw, bi.stride, gs[s], 1, n, ctx->keys.find(gs[s])->second, bi.base,
+                                          bi.stride, 1, out[s * n]->data);
+            }
+        }
+        dev_release(ctx, bi.tmp);
+    }
+    if (rc != HISA_OK)
+        for (size_t s = 0; s < n * n_steps; s++)
+            if (out[s]) { hisa_free(ctx, out[s]); out[s] = nullptr; }
     return rc;
 }
 

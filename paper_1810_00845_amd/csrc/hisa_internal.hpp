@@ -245,8 +245,8 @@ hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk,
 // acc[b][p][x] = sum_j e_j[x] * key[j][p][prime(x)] in fp64; e_j[x] comes from ext unless x lies in digit j, then
 // from own_src (the NTT-form input itself, read through sigma_g when galois != 0)
 hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
-                                   int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois, u64* acc,
-                                   u64 acc_bs, u64 n_batch, int log_n, hipStream_t st);
+                                   int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois,
+                                   int gather_ext, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st);
 
 // sampling (counter-based generator, both sides of the parity tests implement it)
 hipError_t launch_sample_uniform(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, const PolyMap& map, int n_polys,

@@ -280,12 +280,21 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
     std::vector<hisa_ct*> outs((size_t)B * OC, nullptr);
     MacArgs ma = {};
     int rc = HISA_OK;
-    for (int t = 0; t < n_taps && rc == HISA_OK; t++) {
-        if (plan.steps[t] == 0) { ma.tap_base[t] = bi.base; continue; }
-        rotated[t].assign(nct, nullptr);
-        rc = hisa_rot_left_batch(ctx, (const hisa_ct* const*)in->cts, nct, plan.steps[t], rotated[t].data());
-        if (rc != HISA_OK) rotated[t].clear();
-        else ma.tap_base[t] = rotated[t][0]->data;
+    {   // all taps rotate the same inputs: one call, so that the decomposition of c1 is shared by the taps
+        std::vector<int32_t> nz;
+        std::vector<int> tap_of;
+        for (int t = 0; t < n_taps; t++) {
+            if (plan.steps[t] == 0) ma.tap_base[t] = bi.base;
+            else { nz.push_back(plan.steps[t]); tap_of.push_back(t); }
+        }
+        if (!nz.empty()) {
+            std::vector<hisa_ct*> all(nz.size() * nct, nullptr);
+            rc = hisa_rot_left_hoisted_batch(ctx, (const hisa_ct* const*)in->cts, nct, nz.data(), nz.size(), all.data());
+            for (size_t k = 0; k < nz.size() && rc == HISA_OK; k++) {
+                rotated[tap_of[k]].assign(all.begin() + k * nct, all.begin() + (k + 1) * nct);
+                ma.tap_base[tap_of[k]] = rotated[tap_of[k]][0]->data;
+            }
+        }
     }
     const double in_scale = in->cts[0]->scale;
     double mac_scale = in_scale * (g->mode == HISA_CONV_PLAIN ? pt_scale : w_scale);
@@ -522,14 +531,17 @@ extern "C" int hisa_sum_pool2x2(hisa_ctx* ctx, const hisa_tensor* in, hisa_tenso
     }
     dev_release(ctx, bi.tmp);
     const i64 shifts[3] = {(i64)in->w_stride, (i64)in->h_stride, (i64)in->h_stride + in->w_stride};
-    for (int k = 0; k < 3 && rc == HISA_OK; k++) {
-        std::vector<hisa_ct*> rot(nct, nullptr);
-        rc = hisa_rot_left_batch(ctx, (const hisa_ct* const*)in->cts, nct, norm_step(ctx, shifts[k]), rot.data());
-        if (rc != HISA_OK) break;
-        hipError_t e = launch_addsub(ctx->d_primes, acc[0]->data, rot[0]->data, acc[0]->data, OP_ADD, (int)l, 2, 2, nct, words,
-                                     words, words, (int)ctx->log_n, ctx->stream);
-        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "pool add: %s", hipGetErrorString(e));
-        free_handles(ctx, rot);
+    if (rc == HISA_OK) {   // three rotations of the same inputs share the decomposition of c1
+        int32_t steps3[3];
+        for (int k = 0; k < 3; k++) steps3[k] = norm_step(ctx, shifts[k]);
+        std::vector<hisa_ct*> rot(3 * nct, nullptr);
+        rc = hisa_rot_left_hoisted_batch(ctx, (const hisa_ct* const*)in->cts, nct, steps3, 3, rot.data());
+        for (int k = 0; k < 3 && rc == HISA_OK; k++) {
+            hipError_t e = launch_addsub(ctx->d_primes, acc[0]->data, rot[k * nct]->data, acc[0]->data, OP_ADD, (int)l, 2, 2, nct,
+                                         words, words, words, (int)ctx->log_n, ctx->stream);
+            if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "pool add: %s", hipGetErrorString(e));
+        }
+        if (rc == HISA_OK || rot[0]) free_handles(ctx, rot);
     }
     if (rc != HISA_OK) {
         free_handles(ctx, acc);

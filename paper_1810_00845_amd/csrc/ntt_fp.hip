@@ -530,8 +530,8 @@ hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk,
 // thread walks over its share of the batch, so the key is read IPF_ZSPLIT times per batch, not once per ciphertext.
 __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits,
                                                                   int l, int K, int L, int alpha, const u64* key, int total,
-                                                                  const u64* own_src, u64 own_bs, u64 galois, u64* acc, u64 acc_bs,
-                                                                  u64 n_batch, int log_n) {
+                                                                  const u64* own_src, u64 own_bs, u64 galois, int gather_ext,
+                                                                  u64* acc, u64 acc_bs, u64 n_batch, int log_n) {
     const u64 n = (u64)1 << log_n;
     const uint32_t j = blockIdx.x * IPF_NT + threadIdx.x;
     const int x = blockIdx.y;
@@ -539,7 +539,10 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime*
     const int prime = x < l ? x : L + (x - l);
     const int own_digit = x < l ? x / alpha : -1;
     const double p = as_const(&fprimes[prime].p)[0], pinv = as_const(&fprimes[prime].p)[1];
+    // own limbs always read through the automorphism; the extended digits too when they were computed from the
+    // unrotated polynomial (hoisted rotations: ModUp commutes with the automorphism)
     const uint32_t jsrc = galois ? galois_src_fp(j, galois, log_n) : j;
+    const uint32_t jext = gather_ext ? jsrc : j;
     const u64 per = (n_batch + IPF_ZSPLIT - 1) / IPF_ZSPLIT;
     const u64 b0 = (u64)blockIdx.z * per;
     const u64 b1 = b0 + per < n_batch ? b0 + per : n_batch;
@@ -557,7 +560,7 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime*
         for (int d = 0; d < IPF_MAXD; d++) {
             if (d < digits) {
                 const u64 ev = d == own_digit ? own_src[b * own_bs + (u64)x * n + jsrc]
-                                              : ext[b * ext_bs + ((u64)d * ext_limbs + x) * n + j];
+                                              : ext[b * ext_bs + ((u64)d * ext_limbs + x) * n + jext];
                 const double e = fp_from_u64(ev);
                 sb += fp_mulmod(e, kb[d], p, pinv);
                 sa += fp_mulmod(e, ka[d], p, pinv);
@@ -569,12 +572,13 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime*
 }
 
 hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
-                                   int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois, u64* acc,
-                                   u64 acc_bs, u64 n_batch, int log_n, hipStream_t st) {
+                                   int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois,
+                                   int gather_ext, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st) {
     if (digits > IPF_MAXD) return hipErrorInvalidValue;  // the caller falls back to the integer path
+    if (!fprimes || !ext || !key || !own_src || !acc) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / IPF_NT, l + K, IPF_ZSPLIT);
     ProfScope prof__("inner_product_fp_kernel", st);
     hipLaunchKernelGGL(inner_product_fp_kernel, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha, key,
-                       total, own_src, own_bs, galois, acc, acc_bs, n_batch, log_n);
+                       total, own_src, own_bs, galois, gather_ext, acc, acc_bs, n_batch, log_n);
     return hipGetLastError();
 }

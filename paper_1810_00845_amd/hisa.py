@@ -310,6 +310,14 @@ class Context:
     def rot_left_batch(self, cts, steps):
         return self._batch_out("hisa_rot_left_batch", len(cts), self._harr(cts), C.c_size_t(len(cts)), C.c_int32(steps))
 
+    def rot_left_hoisted_batch(self, cts, steps):
+        """[len(steps)][len(cts)] rotated ciphertexts; the decomposition of c1 is shared by all steps."""
+        n, ns = len(cts), len(steps)
+        arr = (C.c_void_p * (n * ns))()
+        st = (C.c_int32 * ns)(*[int(x) for x in steps])
+        self._ck(load().hisa_rot_left_hoisted_batch(self._vp, self._harr(cts), C.c_size_t(n), st, C.c_size_t(ns), arr))
+        return [[self._new_ct(int(arr[s * n + i])) for i in range(n)] for s in range(ns)]
+
     def add_batch(self, a, b):
         return self._batch_out("hisa_add_batch", len(a), self._harr(a), self._harr(b), C.c_size_t(len(a)))
 

@@ -202,6 +202,31 @@ def test_batched_forms_match_single_calls(pair):
         same(g, o, a, o.rescale(b))
 
 
+def test_hoisted_rotations_equal_single_rotations(pair):
+    """Several rotations sharing one decomposition of c1 give, bit for bit, what the oracle's rotLeft gives, at the
+    top level and two levels down, with a step that is a plain copy and handles from different allocations."""
+    g, o = pair
+    cts = [fresh_pair(g, o, 40 + i, g.L) for i in range(3)]
+    gs, os_ = [c[0] for c in cts], [c[1] for c in cts]
+    steps = [1, 0, 7, 64, g.slots - 3]
+    for _ in range(2):
+        out = g.rot_left_hoisted_batch([gs[2], gs[0], gs[1]], steps)
+        assert len(out) == len(steps) and all(len(row) == 3 for row in out)
+        for row, r in zip(out, steps):
+            for gr, oc in zip(row, [os_[2], os_[0], os_[1]]):
+                same(g, o, gr, o.rot_left(oc, r))
+        if gs[0].limbs <= 2:
+            break
+        for i in range(3):
+            g.rescale(gs[i]); os_[i] = o.rescale(os_[i])
+            if gs[i].limbs > 2:
+                g.rescale(gs[i]); os_[i] = o.rescale(os_[i])
+    from paper_1810_00845_amd import hisa
+    with pytest.raises(hisa.HisaError) as e:
+        g.rot_left_hoisted_batch(gs, [1, 5])          # no key for 5
+    assert e.value.code == -4
+
+
 def test_import_export_roundtrip(pair):
     from paper_1810_00845_amd import synth
     g, o = pair
