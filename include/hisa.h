@@ -246,14 +246,30 @@ int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* w_int
 /* Fully connected layer over all elements of all channels (Sec. "Homomorphic
  * matmul", the version without replicas): host w[OUT][C][H][W]; per output o:
  * sum_c mulPlain(in[c], encode(w[o][c] placed on the element slots, zero
- * elsewhere, scale q_last)), one divScalar, then log2 rotate-and-add steps over
- * the power-of-two window that covers the plane; output o is a 1x1 plane in
+ * elsewhere, scale q_last)), one divScalar, then a log-step rotate-and-add
+ * (Sec. "Homomorphic Tensor Operations": reductions over equally strided
+ * elements): amounts w_stride*2^k then h_stride*2^k with each dimension
+ * rounded up to a power of two (the extra positions are zero after the masked
+ * multiply) when the padded rows do not overlap and the padded plane stays
+ * inside the slot vector, else -- or when that is not shorter -- 1, 2, 4, ..
+ * over the contiguous window that covers the plane; hisa_fc_rot_steps lists
+ * them.  Output o is a 1x1 plane in
  * slot `offset` (other slots hold partial sums: clean = 0).  On a 1x1 input it
  * is Algorithm 1 with a 1x1 filter (mulScalar, no rotations).
  * hisa_fc_fixed: pt_coeffs[OUT][C][N] signed plaintext coefficients at pt_scale. */
 int hisa_fc(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t out_features, hisa_tensor* out);
 int hisa_fc_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* pt_coeffs, double pt_scale,
                   uint32_t out_features, hisa_tensor* out);
+/* The same layer with its weights encoded ahead of time (they are constants of the circuit; Sec. "Runtime" keeps
+ * PlainTensors beside CipherTensors).  hisa_fc_prepare encodes w[OUT][C][H][W] for tensors with the layout and level
+ * of `like` (only its metadata and its ciphertexts' limb count are read) into a plan that owns OUT*C plaintexts in
+ * device memory (OUT*C*limbs*N*8 bytes) until hisa_fc_plan_free.  hisa_fc_apply(in, plan) returns bit for bit what
+ * hisa_fc(in, w) returns; a tensor with another layout is HISA_ERR_ARG, another level HISA_ERR_LEVEL_MISMATCH.
+ * Not for 1x1 planes (those multiply by scalars: HISA_ERR_ARG). */
+typedef struct hisa_fc_plan hisa_fc_plan;
+int hisa_fc_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t out_features, hisa_fc_plan** plan);
+int hisa_fc_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_fc_plan* plan, hisa_tensor* out);
+int hisa_fc_plan_free(hisa_ctx* ctx, hisa_fc_plan* plan);
 /* 2x2 sum pool, stride 2 (the 1/4 of the average belongs in the next layer's
  * weights): x + rot(w_stride) + rot(h_stride) + rot(h_stride + w_stride);
  * strides double, no level is used. */

@@ -153,13 +153,29 @@ def fc(o: Oracle, t: OTensor, w):
     return fc_fixed(o, t, coeffs, pt_scale), {"pt_coeffs": coeffs, "pt_scale": pt_scale}
 
 
+def fc_reduce_steps(o: Oracle, t: OTensor):
+    """Rotation amounts of the log-step sum over a plane (Sec. "Homomorphic Tensor Operations": reductions over
+    equally strided elements take log-many rotations with additions in between).  Along the width the amounts are
+    w_stride * 2^k, along the height h_stride * 2^k, each up to the next power of two of the dimension; the padding
+    positions this reads are zero after the masked multiply.  That needs the padded rows not to overlap and the padded
+    plane not to wrap around the slot vector; otherwise (or if it is not shorter) the sum runs over the contiguous
+    power-of-two window 1, 2, 4, ... that covers the plane."""
+    span = (t.height - 1) * t.h_stride + (t.width - 1) * t.w_stride
+    window = []
+    while (1 << len(window)) < span + 1:
+        window.append(1 << len(window))
+    wl = max(t.width - 1, 0).bit_length()
+    hl = max(t.height - 1, 0).bit_length()
+    fits = (t.w_stride << wl) <= t.h_stride and \
+        t.offset + ((1 << hl) - 1) * t.h_stride + ((1 << wl) - 1) * t.w_stride < o.slots
+    strided = [t.w_stride << k for k in range(wl)] + [t.h_stride << k for k in range(hl)]
+    return strided if fits and len(strided) < len(window) else window
+
+
 def fc_fixed(o: Oracle, t: OTensor, coeffs, pt_scale):
     out_n = coeffs.shape[0]
     l = t.cts[0].limbs
-    span = (t.height - 1) * t.h_stride + (t.width - 1) * t.w_stride
-    window_log = 0
-    while (1 << window_log) < span + 1:
-        window_log += 1
+    steps = fc_reduce_steps(o, t)
     outs = []
     for b in range(t.batch):
         for k in range(out_n):
@@ -168,8 +184,8 @@ def fc_fixed(o: Oracle, t: OTensor, coeffs, pt_scale):
                 temp = o.mul_plain(t.cts[b * t.channels + c], o.pt_from_coeffs(coeffs[k, c], pt_scale, l))
                 acc = temp if acc is None else o.add(acc, temp)
             acc = o.rescale(acc)
-            for s in range(window_log):   # rotate-and-add: slot `offset` collects the whole window
-                acc = o.add(acc, o.rot_left(acc, 1 << s))
+            for r in steps:               # rotate-and-add: slot `offset` collects every element of the plane
+                acc = o.add(acc, o.rot_left(acc, r))
             outs.append(acc)
     return OTensor(outs, t.batch, out_n, 1, 1, 1, 1, t.offset, 0)
 

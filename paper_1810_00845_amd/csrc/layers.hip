@@ -151,17 +151,29 @@ extern "C" int hisa_conv2d_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, const
     return write_steps(conv_tap_steps(ctx, in, geom), steps, cap, n);
 }
 
-static int fc_window_log(const hisa_tensor* in) {
+// Rotation amounts of the rotate-and-add that brings the sum over a plane into slot `offset`.  Strided form:
+// w_stride * 2^k then h_stride * 2^k, each dimension rounded up to a power of two (the extra positions are zero after
+// the masked multiply); it needs padded rows that do not overlap and a padded plane that does not wrap around the
+// slot vector.  Otherwise, or when it is not shorter: the contiguous window 1, 2, 4, .. covering the plane.
+static std::vector<i64> fc_reduce_steps(const hisa_ctx* ctx, const hisa_tensor* in) {
     const u64 span = (u64)(in->height - 1) * in->h_stride + (u64)(in->width - 1) * in->w_stride;
-    int t = 0;
-    while (((u64)1 << t) < span + 1) t++;
-    return t;
+    std::vector<i64> window;
+    while (((u64)1 << window.size()) < span + 1) window.push_back((i64)1 << window.size());
+    int wl = 0, hl = 0;
+    while (((u64)1 << wl) < in->width) wl++;
+    while (((u64)1 << hl) < in->height) hl++;
+    const u64 last = (u64)in->offset + (((u64)1 << hl) - 1) * in->h_stride + (((u64)1 << wl) - 1) * in->w_stride;
+    const bool fits = ((u64)in->w_stride << wl) <= in->h_stride && last < ctx->N / 2;
+    std::vector<i64> strided;
+    for (int k = 0; k < wl; k++) strided.push_back((i64)in->w_stride << k);
+    for (int k = 0; k < hl; k++) strided.push_back((i64)in->h_stride << k);
+    return (fits && strided.size() < window.size()) ? strided : window;
 }
 
 extern "C" int hisa_fc_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n) {
     if (!ctx || !in) return HISA_ERR_ARG;
     std::vector<int32_t> all;
-    for (int t = 0; t < fc_window_log(in); t++) all.push_back(norm_step(ctx, (i64)1 << t));
+    for (i64 r : fc_reduce_steps(ctx, in)) all.push_back(norm_step(ctx, r));
     return write_steps(all, steps, cap, n);
 }
 
@@ -431,11 +443,11 @@ static int fc_chunk(hisa_ctx* ctx, const hisa_tensor* in, const BatchIn& bi, con
 
 static int fc_finish(hisa_ctx* ctx, const hisa_tensor* in, std::vector<hisa_ct*>& outs, uint32_t OUT, hisa_tensor* out) {
     int rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
-    // rotate-and-add over the power-of-two window that covers the plane: slot s ends up with the sum of
-    // slots s .. s + 2^T - 1, so slot `offset` holds the sum over all elements
-    for (int t = 0; t < fc_window_log(in) && rc == HISA_OK; t++) {
+    // rotate-and-add: after the last step slot `offset` holds the sum over all elements of the plane
+    for (i64 r : fc_reduce_steps(ctx, in)) {
+        if (rc != HISA_OK) break;
         std::vector<hisa_ct*> rot(outs.size(), nullptr);
-        rc = hisa_rot_left_batch(ctx, (const hisa_ct* const*)outs.data(), outs.size(), norm_step(ctx, (i64)1 << t), rot.data());
+        rc = hisa_rot_left_batch(ctx, (const hisa_ct* const*)outs.data(), outs.size(), norm_step(ctx, r), rot.data());
         if (rc != HISA_OK) break;
         hipError_t e = launch_addsub(ctx->d_primes, outs[0]->data, rot[0]->data, outs[0]->data, OP_ADD, (int)outs[0]->limbs, 2,
                                      2, outs.size(), ct_words(ctx, 2, outs[0]->limbs), ct_words(ctx, 2, outs[0]->limbs),
@@ -510,6 +522,81 @@ extern "C" int hisa_fc(hisa_ctx* ctx, const hisa_tensor* in, const double* w, ui
     }
     TRY(check_tensor(ctx, in));
     return fc_common(ctx, in, w, nullptr, (double)ctx->mod[in->cts[0]->limbs - 1], OUT, out);
+}
+
+// Weights of a fully connected layer encoded once for a given input layout and level (constants of the circuit:
+// the encode, reduction and transform of OUT*C plaintexts is most of the cost of hisa_fc and need not be paid per
+// inference).
+#define HISA_MAGIC_FCPLAN 0x46435031u
+struct hisa_fc_plan {
+    uint32_t magic;
+    uint32_t out_features, channels, height, width, h_stride, w_stride, offset, limbs;
+    double pt_scale;
+    DevBlock* pts;   // [OUT][C][limbs][N], NTT form
+};
+
+extern "C" int hisa_fc_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t OUT, hisa_fc_plan** plan) {
+    if (!ctx || !like || !w || !plan || OUT == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_tensor(ctx, like));
+    if (like->height == 1 && like->width == 1)
+        return fail(ctx, HISA_ERR_ARG, "a fully connected layer on 1x1 planes multiplies by scalars: nothing to prepare");
+    const uint32_t C = like->channels, l = like->cts[0]->limbs;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "fc needs a level to rescale into");
+    const size_t n = ctx->N, hw = (size_t)like->height * like->width;
+    const size_t pt_bytes = (size_t)C * l * n * sizeof(u64);
+    DevBlock* blk = dev_alloc(ctx, (size_t)OUT * pt_bytes);
+    if (!blk) return HISA_ERR_OOM;
+    const double pt_scale = (double)ctx->mod[l - 1];
+    const std::vector<uint32_t> slots = plane_slots(like->height, like->width, like->h_stride, like->w_stride, like->offset);
+    const uint32_t OUTC = (uint32_t)std::max<size_t>(1, std::min<size_t>(OUT, ((size_t)2 << 30) / pt_bytes));
+    int rc = HISA_OK;
+    for (uint32_t o0 = 0; o0 < OUT && rc == HISA_OK; o0 += OUTC) {
+        const uint32_t cnt = std::min(OUTC, OUT - o0);
+        rc = encode_sparse_batch(ctx, slots, w + (size_t)o0 * C * hw, (size_t)cnt * C, pt_scale, (int)l,
+                                 (u64*)blk->ptr + (size_t)o0 * C * l * n);
+    }
+    if (rc != HISA_OK) { dev_release(ctx, blk); return rc; }
+    hisa_fc_plan* p = new hisa_fc_plan{HISA_MAGIC_FCPLAN, OUT, C, like->height, like->width, like->h_stride, like->w_stride,
+                                       like->offset, l, pt_scale, blk};
+    *plan = p;
+    return HISA_OK;
+}
+
+extern "C" int hisa_fc_plan_free(hisa_ctx* ctx, hisa_fc_plan* plan) {
+    if (!ctx || !plan || plan->magic != HISA_MAGIC_FCPLAN) return fail(ctx, HISA_ERR_ARG, "not a fully connected plan");
+    dev_release(ctx, plan->pts);
+    plan->magic = 0;
+    delete plan;
+    return HISA_OK;
+}
+
+extern "C" int hisa_fc_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_fc_plan* plan, hisa_tensor* out) {
+    if (!ctx || !in || !plan || plan->magic != HISA_MAGIC_FCPLAN) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
+    const uint32_t B = in->batch, C = in->channels, l = in->cts[0]->limbs, OUT = plan->out_features;
+    if (C != plan->channels || in->height != plan->height || in->width != plan->width || in->h_stride != plan->h_stride ||
+        in->w_stride != plan->w_stride || in->offset != plan->offset)
+        return fail(ctx, HISA_ERR_ARG, "the plan was prepared for another tensor layout");
+    if (l != plan->limbs) return fail(ctx, HISA_ERR_LEVEL_MISMATCH, "the plan was prepared for %u limbs, the tensor has %u",
+                                      plan->limbs, l);
+    BatchIn bi;
+    TRY(gather_batch(ctx, (const hisa_ct* const*)in->cts, (size_t)B * C, &bi));
+    std::vector<hisa_ct*> outs((size_t)B * OUT, nullptr);
+    int rc = alloc_ct_batch(ctx, outs.size(), 2, l, in->cts[0]->scale * plan->pt_scale, outs.data());
+    for (uint32_t b = 0; b < B && rc == HISA_OK; b++) {
+        BatchIn one = bi;
+        one.base = bi.base + (size_t)b * C * bi.stride;
+        hisa_tensor view = *in;
+        view.batch = 1;
+        rc = fc_chunk(ctx, &view, one, (const u64*)plan->pts->ptr, plan->pt_scale, OUT, &outs[(size_t)b * OUT]);
+    }
+    dev_release(ctx, bi.tmp);
+    if (rc != HISA_OK) {
+        free_handles(ctx, outs);
+        return rc;
+    }
+    return fc_finish(ctx, in, outs, OUT, out);
 }
 
 // ---------------------------------------------------------------------------

@@ -414,6 +414,23 @@ class Context:
         assert w.size == out_features * t.channels * t.height * t.width
         return self._layer("hisa_fc", t, t.batch * out_features, _dp(w), C.c_uint32(out_features))
 
+    def fc_prepare(self, like, w):
+        """Encodes fc weights once for tensors laid out like `like`; returns a plan for fc_apply (free with
+        fc_plan_free)."""
+        w = np.ascontiguousarray(w, dtype=np.float64)
+        out_features = w.shape[0]
+        assert w.size == out_features * like.channels * like.height * like.width
+        st, _arr = like._struct()
+        plan = C.c_void_p()
+        self._ck(load().hisa_fc_prepare(self._vp, C.byref(st), _dp(w), C.c_uint32(out_features), C.byref(plan)))
+        return (plan, out_features)
+
+    def fc_apply(self, t, plan):
+        return self._layer("hisa_fc_apply", t, t.batch * plan[1], plan[0])
+
+    def fc_plan_free(self, plan):
+        self._ck(load().hisa_fc_plan_free(self._vp, plan[0]))
+
     def fc_fixed(self, t, pt_coeffs, pt_scale):
         pc = np.ascontiguousarray(pt_coeffs, dtype=np.int64)
         out_features = pc.shape[0]

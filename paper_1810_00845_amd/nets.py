@@ -88,10 +88,12 @@ def _concat_channels(ctx, a, b):
     return t
 
 
-def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0):
+def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans=None):
     """Encrypts x, runs the layers, decrypts.  Returns (output array, seconds from encrypt-done to the last
     ciphertext ready, per-layer seconds).  With make_keys the rotation keys each layer asks for are generated
-    on the way (set-up pass); otherwise they must be resident."""
+    on the way (set-up pass); otherwise they must be resident.  `plans` (a dict, filled by the set-up pass and
+    reused afterwards) holds the fully connected layers' weights encoded ahead of time; without it they are
+    encoded inside the call."""
     if border:   # leave `border` rows and columns of zero slots around every plane (SAME convolutions need them)
         hs = x.shape[3] + 2 * border
         t = ctx.tensor_encrypt(x, scale, limbs, h_stride=hs, offset=border * hs + border)
@@ -101,7 +103,14 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0):
     t_start = time.perf_counter()
     per_layer = []
     pending = 1.0     # constant factor the previous layers left to the next linear layer
-    for layer in layers:
+    def fully_connected(idx, t, w):
+        if plans is None or t.height * t.width == 1:
+            return ctx.fc(t, w)
+        if idx not in plans:
+            plans[idx] = ctx.fc_prepare(t, w)
+        return ctx.fc_apply(t, plans[idx])
+
+    for idx, layer in enumerate(layers):
         t0 = time.perf_counter()
         kind = layer[0]
         if kind == "conv":
@@ -147,13 +156,13 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0):
             pending = 1.0
             if make_keys:
                 ctx.gen_rot_keys(ctx.fc_rot_steps(t))
-            nxt = ctx.fc(t, w)
+            nxt = fully_connected(idx, t, w)
         elif kind == "fc":
             w = layer[1] * pending
             pending = 1.0
             if make_keys and t.height * t.width > 1:
                 ctx.gen_rot_keys(ctx.fc_rot_steps(t))
-            nxt = ctx.fc(t, w)
+            nxt = fully_connected(idx, t, w)
         else:
             raise ValueError(kind)
         t.free()
@@ -164,3 +173,9 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0):
     out = ctx.tensor_decrypt(t) * pending
     t.free()
     return out, latency, per_layer
+
+
+def free_plans(ctx, plans):
+    for plan in plans.values():
+        ctx.fc_plan_free(plan)
+    plans.clear()

@@ -98,7 +98,7 @@ def test_multichannel_same_strided_masked_conv():
 
 def test_activation_pool_fc_chain_bit_exact():
     from oracle import layers
-    from paper_1810_00845_amd import synth
+    from paper_1810_00845_amd import hisa, synth
     g, o = make_pair(11, [50, 45, 45, 45, 45], 5, 55, 4)
     g.keygen(); o.keygen()
     x = synth.image(6, 2, 4, 4)[None]
@@ -112,13 +112,23 @@ def test_activation_pool_fc_chain_bit_exact():
     ref = plain_net.sum_pool2x2(plain_net.poly2_act_without_a(x, 0.3, 0.2))
     assert np.abs(g.tensor_decrypt(gpool) - ref).max() <= 1e-3
     w1 = synth.fc_weights(7, 3, 2, 2, 2, std=0.3)
-    assert g.fc_rot_steps(gpool) == [1, 2, 4, 8]
+    assert g.fc_rot_steps(gpool) == [2, 8] == layers.fc_reduce_steps(o, opool)
     of1, ints = layers.fc(o, opool, w1)
     gf1 = g.fc_fixed(gpool, ints["pt_coeffs"], ints["pt_scale"])
     same_tensor(g, o, gf1, of1)
     ref1 = plain_net.fc(ref, w1)
     assert np.abs(g.tensor_decrypt(gf1) - ref1).max() <= 1e-3
     assert np.abs(g.tensor_decrypt(g.fc(gpool, w1)) - ref1).max() <= 1e-3
+    # weights encoded ahead of time: bit for bit the result of the call that encodes them itself
+    plan = g.fc_prepare(gpool, w1)
+    gplain, gplan = g.fc(gpool, w1), g.fc_apply(gpool, plan)
+    for a, b in zip(gplain.cts, gplan.cts):
+        assert np.array_equal(g.ct_export(a), g.ct_export(b)) and a.scale == b.scale
+    assert gplan.meta() == gplain.meta()
+    with pytest.raises(hisa.HisaError) as e:
+        g.fc_apply(gact, plan)                            # another layout
+    assert e.value.code == -1
+    g.fc_plan_free(plan)
     w2 = synth.fc_weights(8, 2, 3, 1, 1, std=0.5)
     of2, _ = layers.fc(o, of1, w2)
     gf2 = g.fc(gf1, w2)                                   # 1x1 planes: scalar weights, no encodes, bit-exact as is

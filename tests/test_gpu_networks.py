@@ -49,4 +49,11 @@ def test_network_matches_plaintext(name):
     got2, latency, per_layer = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, border=border)
     print(name, "latency %.3f s" % latency, [(k, round(s, 4)) for k, s in per_layer], flush=True)
     assert np.abs(got2 - want).max() <= 1e-3
+    # fully connected weights encoded ahead of time: same ciphertext operations, so the same numbers
+    plans = {}
+    nets.run_encrypted(ctx, layers, x, params["scale"], limbs, border=border, plans=plans)
+    got3, latency, per_layer = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, border=border, plans=plans)
+    print(name, "latency with prepared weights %.3f s" % latency, [(k, round(s, 4)) for k, s in per_layer], flush=True)
+    assert np.abs(got3 - want).max() <= 1e-3
+    nets.free_plans(ctx, plans)
     ctx.close()

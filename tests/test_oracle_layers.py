@@ -92,7 +92,8 @@ def test_fc_pool_activation_chain():
     assert np.abs(layers.tensor_decrypt(o, pool) - ref).max() <= 1e-3
     # fully connected over 2 channels x 2 x 2 elements -> 3 outputs, then 3 -> 2 on 1x1 planes
     w1 = synth.fc_weights(7, 3, 2, 2, 2, std=0.3)
-    o.gen_rot_keys([1, 2, 4, 8])
+    assert layers.fc_reduce_steps(o, pool) == [2, 8]     # strided log-step sum: one step per dimension of the 2x2 plane
+    o.gen_rot_keys([2, 8])
     f1, _ = layers.fc(o, pool, w1)
     ref1 = plain_net.fc(ref, w1)
     assert (f1.channels, f1.height, f1.width) == (3, 1, 1)
@@ -111,3 +112,22 @@ def test_plain_reference_conv_is_cross_correlation():
     assert out[0, 0].tolist() == [[5.0, 4.0], [2.0, 1.0]]
     same = plain_net.conv2d(x, w, pad_same=True)
     assert same.shape == (1, 1, 4, 4) and same[0, 0, 1, 2] == 4.0 and same[0, 0, 2, 3] == 0.0 and same[0, 0, 0, 1] == 8.0
+
+
+def test_fc_reduction_rule_and_zero_padding():
+    """The log-step sum of the FC layer: strided amounts when the padded rows do not overlap (a 3x3 plane summed as
+    4x4: the extra positions are zero after the masked multiply), the contiguous window otherwise; both give the
+    plaintext FC."""
+    from oracle import Oracle, layers
+    from paper_1810_00845_amd import synth
+    o = Oracle(10, [50, 40], 2, 55, 9)
+    o.keygen()
+    x = synth.image(3, 2, 3, 3)[None]
+    w = synth.fc_weights(4, 2, 2, 3, 3, std=0.4)
+    want = plain_net.fc(x, w)
+    for hs, off, expect in ((8, 9, [1, 2, 8, 16]), (3, 0, [1, 2, 4, 8])):
+        t = layers.tensor_encrypt(o, x, 2.0 ** 40, 2, h_stride=hs, offset=off)
+        assert layers.fc_reduce_steps(o, t) == expect
+        o.gen_rot_keys(expect)
+        f, _ = layers.fc(o, t, w)
+        assert np.abs(layers.tensor_decrypt(o, f) - want).max() <= 1e-3
