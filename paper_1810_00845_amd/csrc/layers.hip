@@ -10,6 +10,7 @@
 
 #include "hisa_internal.hpp"
 #include "modarith.cuh"
+#include "fparith.cuh"
 
 #define NT 256
 #define OCB 4
@@ -53,6 +54,67 @@ __global__ __launch_bounds__(NT) void scalar_mac_kernel(const PrimeConst* primes
             g.out[((u64)b * g.OC + oc0 + o) * g.ct_words + (u64)pl * n + j] = acc_reduce(acc[o], pc.q, pc.r1, pc.r0);
 }
 
+// The same sum in exact fp64 arithmetic (every prime below 2^50): a modular product is six full-rate instructions
+// instead of a 64x64 high/low product pair at quarter rate, and OCF outputs share each load of x.  The weights
+// (centred doubles) are the same for every thread and arrive through scalar loads.
+// Range: a term is at most 0.7 p in magnitude, eight of them on top of a normalised value stay below 6.1 p < 2^53.
+#define OCF 16
+#define ICU 4
+typedef const __attribute__((address_space(4))) double* mac_cdouble_ptr;
+// wf: [l][T][OC] (the OCF weights of one x value are contiguous: wide scalar loads)
+__global__ __launch_bounds__(NT) void scalar_mac_fp_kernel(const FpPrime* fprimes, MacArgs g, const double* wf, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    const int pl = blockIdx.y, limb = pl % g.l;
+    const int ocblocks = (g.OC + OCF - 1) / OCF;
+    const int b = blockIdx.z / ocblocks, oc0 = (blockIdx.z % ocblocks) * OCF;
+    const mac_cdouble_ptr fp = (mac_cdouble_ptr)(unsigned long long)&fprimes[limb].p;
+    const double p = fp[0], pinv = fp[1];
+    const bool full = oc0 + OCF <= g.OC;     // all OCF outputs exist (uniform over the workgroup)
+    double acc[OCF];
+#pragma unroll
+    for (int o = 0; o < OCF; o++) acc[o] = 0.0;
+    int pending = 0;
+    for (int t = 0; t < g.n_taps; t++) {
+        const u64* x = g.tap_base[t] + (u64)b * g.IC * g.ct_words + (u64)pl * n + j;
+        const mac_cdouble_ptr w =
+            (mac_cdouble_ptr)(unsigned long long)(wf + ((u64)limb * g.n_taps + t) * g.IC * g.OC + oc0);
+        for (int ic0 = 0; ic0 < g.IC; ic0 += ICU) {
+            // the loads of ICU input channels first, then their arithmetic
+            double xv[ICU];
+#pragma unroll
+            for (int u = 0; u < ICU; u++) {
+                const int ic = ic0 + u < g.IC ? ic0 + u : g.IC - 1;
+                xv[u] = fp_from_u64(x[(u64)ic * g.ct_words]);
+            }
+#pragma unroll
+            for (int u = 0; u < ICU; u++) {
+                if (ic0 + u < g.IC) {
+                    const mac_cdouble_ptr wi = w + (u64)(ic0 + u) * g.OC;
+                    if (full) {
+#pragma unroll
+                        for (int o = 0; o < OCF; o++) acc[o] += fp_mulmod(xv[u], wi[o], p, pinv);
+                    } else {
+#pragma unroll
+                        for (int o = 0; o < OCF; o++)
+                            if (oc0 + o < g.OC) acc[o] += fp_mulmod(xv[u], wi[o], p, pinv);
+                    }
+                }
+            }
+            pending += ICU;
+            if (pending >= 8) {
+#pragma unroll
+                for (int o = 0; o < OCF; o++) acc[o] = fp_norm(acc[o], p, pinv);
+                pending = 0;
+            }
+        }
+    }
+#pragma unroll
+    for (int o = 0; o < OCF; o++)
+        if (oc0 + o < g.OC)
+            g.out[((u64)b * g.OC + oc0 + o) * g.ct_words + (u64)pl * n + j] = fp_canonical(acc[o], p, pinv);
+}
+
 // out[b][oc] = sum over T = (tap, ic) of  pt[T][oc] (slot-wise) x[tap][b][ic]
 __global__ __launch_bounds__(NT) void plain_mac_kernel(const PrimeConst* primes, MacArgs g, int log_n) {
     const u64 n = (u64)1 << log_n;
@@ -86,6 +148,15 @@ static hipError_t launch_scalar_mac(const PrimeConst* primes, const MacArgs& g, 
     dim3 grid((1u << log_n) / NT, 2 * g.l, batch * ((g.OC + OCB - 1) / OCB));
     ProfScope prof__("scalar_mac_kernel", st);
     hipLaunchKernelGGL(scalar_mac_kernel, grid, dim3(NT), 0, st, primes, g, log_n);
+    return hipGetLastError();
+}
+
+static hipError_t launch_scalar_mac_fp(const FpPrime* fprimes, const MacArgs& g, const double* wf, int batch, int log_n,
+                                       hipStream_t st) {
+    if (!fprimes || !wf || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS) return hipErrorInvalidValue;
+    dim3 grid((1u << log_n) / NT, 2 * g.l, batch * ((g.OC + OCF - 1) / OCF));
+    ProfScope prof__("scalar_mac_fp_kernel", st);
+    hipLaunchKernelGGL(scalar_mac_fp_kernel, grid, dim3(NT), 0, st, fprimes, g, wf, log_n);
     return hipGetLastError();
 }
 
@@ -279,9 +350,10 @@ static int conv_plan(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom*
     return HISA_OK;
 }
 
-// d_w: SCALAR/MASKED residues [T][OC][l]; d_pts: MASKED [l][N], PLAIN [T][OC][l][N]
+// d_w: SCALAR/MASKED residues [T][OC][l] (d_wf: the same as centred doubles when every prime is below 2^50, else null);
+// d_pts: MASKED [l][N], PLAIN [T][OC][l][N]
 static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
-                    const u64* d_w, double w_scale, const u64* d_pts, double pt_scale, hisa_tensor* out) {
+                    const u64* d_w, const double* d_wf, double w_scale, const u64* d_pts, double pt_scale, hisa_tensor* out) {
     const uint32_t B = in->batch, IC = in->channels, l = in->cts[0]->limbs;
     const size_t nct = (size_t)B * IC, n = ctx->N;
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
@@ -320,7 +392,8 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
             e = launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
         } else {
             ma.w = d_w;
-            e = launch_scalar_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+            if (d_wf) e = launch_scalar_mac_fp(ctx->tabs.fprimes, ma, d_wf, (int)B, (int)ctx->log_n, ctx->stream);
+            else e = launch_scalar_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
             if (e == hipSuccess && g->mode == HISA_CONV_MASKED) {
                 e = launch_mul_plain(ctx->d_primes, outs[0]->data, d_pts, outs[0]->data, (int)l, 2, (u64)B * OC, ma.ct_words,
                                      ma.ct_words, (int)ctx->log_n, ctx->stream);
@@ -344,11 +417,29 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
     return HISA_OK;
 }
 
-static int upload_weight_residues(hisa_ctx* ctx, const int64_t* w_int, size_t count, uint32_t l, Temp& dst) {
+// fixed-point weights on the device: residues per limb, and centred doubles for the fp64 multiply-accumulate
+struct DevWeights {
+    Temp res, resf;
+    bool fp;
+    DevWeights(hisa_ctx* ctx, size_t count, uint32_t l)
+        : res(ctx, count * l * sizeof(u64)), resf(ctx, ctx->tabs.fp_ok ? count * l * sizeof(double) : 8), fp(ctx->tabs.fp_ok) {}
+    bool ok() const { return res.ok() && resf.ok(); }
+    const double* f() { return fp ? resf.as<double>() : nullptr; }
+};
+
+static int upload_weight_residues(hisa_ctx* ctx, const int64_t* w_int, size_t count, uint32_t l, DevWeights& dst) {
     std::vector<u64> res(count * l);
+    std::vector<double> resf(dst.fp ? count * l : 0);
     for (size_t i = 0; i < count; i++)
-        for (uint32_t k = 0; k < l; k++) res[i * l + k] = mod_i64(w_int[i], ctx->mod[k]);
-    HIP_TRY(ctx, hipMemcpyAsync(dst.blk->ptr, res.data(), res.size() * sizeof(u64), hipMemcpyHostToDevice, ctx->stream));
+        for (uint32_t k = 0; k < l; k++) {
+            const u64 q = ctx->mod[k], r = mod_i64(w_int[i], q);
+            res[i * l + k] = r;
+            if (dst.fp) resf[(size_t)k * count + i] = r > q / 2 ? -(double)(q - r) : (double)r;   // [l][T][OC]
+        }
+    HIP_TRY(ctx, hipMemcpyAsync(dst.res.blk->ptr, res.data(), res.size() * sizeof(u64), hipMemcpyHostToDevice, ctx->stream));
+    if (dst.fp)
+        HIP_TRY(ctx, hipMemcpyAsync(dst.resf.blk->ptr, resf.data(), resf.size() * sizeof(double), hipMemcpyHostToDevice,
+                                    ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     return HISA_OK;
 }
@@ -367,10 +458,10 @@ extern "C" int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int
         Temp pts(ctx, T * OC * l * n * sizeof(u64));
         if (!pts.ok()) return HISA_ERR_OOM;
         TRY(coeffs_to_plain_batch(ctx, pt_coeffs, T * OC, (int)l, pts.u()));
-        return conv_run(ctx, in, geom, plan, OC, nullptr, 1.0, pts.u(), pt_scale, out);
+        return conv_run(ctx, in, geom, plan, OC, nullptr, nullptr, 1.0, pts.u(), pt_scale, out);
     }
     if (!w_int) return fail(ctx, HISA_ERR_ARG, "null weights");
-    Temp dw(ctx, T * OC * l * sizeof(u64));
+    DevWeights dw(ctx, T * OC, l);
     if (!dw.ok()) return HISA_ERR_OOM;
     TRY(upload_weight_residues(ctx, w_int, T * OC, l, dw));
     if (geom->mode == HISA_CONV_MASKED) {
@@ -378,9 +469,9 @@ extern "C" int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int
         Temp mask(ctx, (size_t)l * n * sizeof(u64));
         if (!mask.ok()) return HISA_ERR_OOM;
         TRY(coeffs_to_plain_batch(ctx, pt_coeffs, 1, (int)l, mask.u()));
-        return conv_run(ctx, in, geom, plan, OC, dw.u(), w_scale, mask.u(), pt_scale, out);
+        return conv_run(ctx, in, geom, plan, OC, dw.res.u(), dw.f(), w_scale, mask.u(), pt_scale, out);
     }
-    return conv_run(ctx, in, geom, plan, OC, dw.u(), w_scale, nullptr, 1.0, out);
+    return conv_run(ctx, in, geom, plan, OC, dw.res.u(), dw.f(), w_scale, nullptr, 1.0, out);
 }
 
 extern "C" int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t OC, const hisa_conv_geom* geom,
@@ -402,7 +493,7 @@ extern "C" int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w
         std::vector<double> vals(T * OC * vslots.size());
         for (size_t i = 0; i < T * OC; i++) std::fill_n(vals.begin() + i * vslots.size(), vslots.size(), w[i]);
         TRY(encode_sparse_batch(ctx, vslots, vals.data(), T * OC, q_last, (int)l, pts.u()));
-        return conv_run(ctx, in, geom, plan, OC, nullptr, 1.0, pts.u(), q_last, out);
+        return conv_run(ctx, in, geom, plan, OC, nullptr, nullptr, 1.0, pts.u(), q_last, out);
     }
     const double w_scale = geom->mode == HISA_CONV_MASKED ? q_last / HISA_MASK_SCALE : q_last;
     std::vector<int64_t> w_int(T * OC);
@@ -411,7 +502,7 @@ extern "C" int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w
         if (!(fabs(v) < 9.2e18)) return fail(ctx, HISA_ERR_ARG, "weight %g does not fit the fixed-point range", w[i]);
         w_int[i] = (int64_t)round(v);
     }
-    Temp dw(ctx, T * OC * l * sizeof(u64));
+    DevWeights dw(ctx, T * OC, l);
     if (!dw.ok()) return HISA_ERR_OOM;
     TRY(upload_weight_residues(ctx, w_int.data(), T * OC, l, dw));
     if (geom->mode == HISA_CONV_MASKED) {
@@ -419,9 +510,9 @@ extern "C" int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w
         if (!mask.ok()) return HISA_ERR_OOM;
         std::vector<double> ones(vslots.size(), 1.0);
         TRY(encode_sparse_batch(ctx, vslots, ones.data(), 1, HISA_MASK_SCALE, (int)l, mask.u()));
-        return conv_run(ctx, in, geom, plan, OC, dw.u(), w_scale, mask.u(), HISA_MASK_SCALE, out);
+        return conv_run(ctx, in, geom, plan, OC, dw.res.u(), dw.f(), w_scale, mask.u(), HISA_MASK_SCALE, out);
     }
-    return conv_run(ctx, in, geom, plan, OC, dw.u(), w_scale, nullptr, 1.0, out);
+    return conv_run(ctx, in, geom, plan, OC, dw.res.u(), dw.f(), w_scale, nullptr, 1.0, out);
 }
 
 // ---------------------------------------------------------------------------
