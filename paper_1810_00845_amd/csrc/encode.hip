@@ -72,10 +72,12 @@ hipError_t launch_crt_to_double(const PrimeConst* primes, const u64* coeff_form,
     return hipGetLastError();
 }
 
-// z_j = sum_k m_k exp(i*pi*e/N),  e = 5^j k mod 2N
+// z_j = sum_k m_k exp(i*pi*e/N),  e = 5^j k mod 2N.  One workgroup per slot: thread t sums the coefficients
+// k = t, t + NT, ..., then the partial sums are added pairwise through LDS (fixed order: reruns give the same bits).
 __global__ __launch_bounds__(NT) void decode_kernel(const double* cs, const double* sn, const double* m, int count,
                                                     double* re, double* im, int log_n) {
-    const int j = blockIdx.x * NT + threadIdx.x;
+    __shared__ double sr[NT], si[NT];
+    const int j = blockIdx.x;
     if (j >= count) return;
     const uint32_t n = 1u << log_n, mask = 2 * n - 1;
     // 5^j mod 2N by square and multiply
@@ -86,20 +88,28 @@ __global__ __launch_bounds__(NT) void decode_kernel(const double* cs, const doub
         ex >>= 1;
     }
     double ar = 0.0, ai = 0.0;
-    uint32_t e = 0;
-    for (uint32_t k = 0; k < n; k++) {
-        double v = m[k];
+    for (uint32_t k = threadIdx.x; k < n; k += NT) {
+        const uint32_t e = (g * k) & mask;
+        const double v = m[k];
         ar += v * cs[e];
         ai += v * sn[e];
-        e = (e + g) & mask;
     }
-    re[j] = ar;
-    if (im) im[j] = ai;
+    sr[threadIdx.x] = ar; si[threadIdx.x] = ai;
+    __syncthreads();
+    for (int h = NT / 2; h > 0; h >>= 1) {
+        if ((int)threadIdx.x < h) { sr[threadIdx.x] += sr[threadIdx.x + h]; si[threadIdx.x] += si[threadIdx.x + h]; }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        re[j] = sr[0];
+        if (im) im[j] = si[0];
+    }
 }
 
 hipError_t launch_decode(const double* cs, const double* sn, const double* m, int count, double* re, double* im, int log_n,
                          hipStream_t st) {
+    if (count <= 0) return hipSuccess;
     ProfScope prof__("decode_kernel", st);
-    hipLaunchKernelGGL(decode_kernel, dim3((count + NT - 1) / NT), dim3(NT), 0, st, cs, sn, m, count, re, im, log_n);
+    hipLaunchKernelGGL(decode_kernel, dim3(count), dim3(NT), 0, st, cs, sn, m, count, re, im, log_n);
     return hipGetLastError();
 }
