@@ -4,58 +4,54 @@
 //
 // One workgroup transforms one limb-polynomial.  N/32 threads hold 32
 // coefficients each in registers (the whole polynomial lives in the register
-// file: 256 KiB at N = 2^15, one 1024-thread workgroup per CU).  The log2 N
+// file: at N = 2^15 one 1024-thread workgroup fills a CU's registers).  The log2 N
 // butterfly levels run as three register-resident radix-32 phases; between
 // phases the polynomial is transposed through LDS as two 32-bit halves, so the
 // staging buffer is N*4 bytes plus padding (132 KiB at N = 2^15) and the transposes
-// need no extra registers.  One pad word per 32 makes every transpose access
-// bank-conflict free.  Global loads and stores always use
-// the mapping "lane <-> consecutive coefficient", i.e. they are coalesced.
+// need no extra registers.  Global loads and stores are coalesced.
 //
-// Index bit fields of a coefficient index: idx = (a:5)(b:5)(c:K3), K3 = log2 N - 10.
-//   mapping P1: thread (b,c), registers a      (coalesced global access)
-//   mapping P2: thread (a,c), registers b
-//   mapping P3: thread (a_low:K3, b), registers (a_high:5-K3, c)
+// Index bit fields of a coefficient index: idx = (a:5)(b:5)(c:K3), K3 = log2 N - 10
+// (the four register mappings are listed at struct Geo).
 // Forward (natural in, value at psi^(2 bitrev(i)+1) at index i out): decimation
-// in time, levels 1..5 on a (P1), 6..10 on b (P2), 11.. on c (P3).
-// Inverse: the cyclic inverse transform as decimation in time from bit-reversed
-// input (levels on c in P3, then b in P2, then a in P1) followed by the
-// untwist psi^-j / N (and an optional extra constant per limb).
+// in time, levels 1..5 on a (mapping 1), 6..10 on b (2), 11.. on c (3), stores in
+// mapping 4.  Inverse: the cyclic inverse transform as decimation in time from
+// bit-reversed input (loads in mapping 4, levels on c in 3, then b in 2, then a
+// in 1) followed by the untwist psi^-j / N (and an optional extra constant per
+// limb).  Only the transpose 1 <-> 2 crosses waves (five workgroup barriers per
+// transform); after it the waves run apart and overlap one another's LDS
+// traffic, stores and next loads.
 #include "hisa_internal.hpp"
 #include "fparith.cuh"
 
 template <int K3>
 struct Geo {
     static constexpr int LOGN = 10 + K3, TB = 5 + K3, THREADS = 1 << TB, N = 1 << LOGN, CM = (1 << K3) - 1;
-    // Every mapping splits a coefficient index (and its LDS word address) into a term of the thread plus a
-    // compile-time term of the register, so addressing needs one register per mapping, not one per element.
-    // LDS word address = idx + (idx >> 5): one pad word per 32 keeps all three transposes bank-conflict free.
-    static constexpr int LDS_WORDS = N + N / 32;
-    // Mapping 4 (K3 = 5 only): wave w holds coefficients [2048 w, 2048 (w+1)), lane <-> consecutive coefficients.
-    // At K3 = 5 a wave holds exactly that range in mappings 2 and 3 as well (both keep the top bits `a` in the
-    // thread index), so the transposes 2 <-> 3 <-> 4 stay inside a wave and need no workgroup barrier.
-    static constexpr bool WAVE_LOCAL = K3 == 5;
+    // A coefficient index is (a:5)(b:5)(c:K3), b = (b_high : 5-K3)(b_low : K3).  Four ways to spread the N coefficients
+    // over THREADS threads x 32 registers; in each the index is (a term of the thread) | (a compile-time term of the
+    // register) with disjoint bits, so addressing needs one register per mapping, not one per element:
+    //   1  thread (b, c),      register a             loads/stores of the side whose phase works on a; phase on a
+    //   2  thread (a, c),      register b             phase on b
+    //   3  thread (a, b_low),  register (b_high, c)   phase on c (2^(5-K3) groups of 2^K3 registers)
+    //   4  thread (wave w, lane), register r: index 2048 w + 64 r + lane     coalesced loads/stores
+    // In mappings 2, 3 and 4 wave w holds exactly the coefficients [2048 w, 2048 (w+1)), so the transposes between
+    // them stay inside a wave and need no workgroup barrier; only 1 <-> 2 crosses waves.
     template <int M> static __device__ __forceinline__ int thread_idx(int t) {
         if (M == 1) return t;
         if (M == 2) return ((t >> K3) << TB) | (t & CM);
-        if (M == 3) return ((t >> 5) << TB) | ((t & 31) << K3);
+        if (M == 3) return ((t >> K3) << TB) | ((t & CM) << K3);
         return ((t >> 6) << 11) | (t & 63);
     }
     template <int M> static constexpr int reg_idx(int r) {
-        return M == 1 ? (r << TB)
-                      : (M == 2 ? (r << K3) : (M == 3 ? (((r >> K3) << (K3 + TB)) | (r & CM)) : (r << 6)));
+        return M == 1 ? (r << TB) : (M == 2 ? (r << K3) : (M == 3 ? (((r >> K3) << (2 * K3)) | (r & CM)) : (r << 6)));
     }
-    template <int M> static __device__ __forceinline__ int thread_lds(int t) {
-        if (M == 1) return t + (t >> 5);
-        if (M == 2) return ((t >> K3) << TB) + ((t >> K3) << K3) + (t & CM);
-        if (M == 3) return ((t >> 5) << TB) + ((t & 31) << K3) + ((t >> 5) << K3) + ((t & 31) >> (5 - K3));
-        return ((t >> 6) << 11) + ((t >> 6) << 6) + (t & 63) + ((t & 63) >> 5);
-    }
-    template <int M> static constexpr int reg_lds(int r) {
-        return M == 1 ? r * ((1 << TB) + (1 << (TB - 5)))
-                      : (M == 2 ? (r << K3) + (r >> (5 - K3))
-                                : (M == 3 ? ((r >> K3) << (K3 + TB)) + ((r >> K3) << (2 * K3)) + (r & CM) : 66 * r));
-    }
+    // LDS word address of index x: x plus pad words (x >> 5, and one more shift for the small rings) that spread the
+    // strided accesses of the mappings over the banks (conflict-free at N = 2^15, at most two-way below).  The
+    // shifts act on disjoint bit fields, so the address of (thread | register) is the sum of the two addresses.
+    static constexpr int PAD2 = K3 == 3 ? 7 : (K3 == 2 ? 8 : 0);
+    static constexpr int LDS_WORDS = N + N / 32 + (PAD2 ? (N >> PAD2) : 0);
+    static __device__ __forceinline__ constexpr int lds_of(int x) { return x + (x >> 5) + (PAD2 ? (x >> PAD2) : 0); }
+    template <int M> static __device__ __forceinline__ int thread_lds(int t) { return lds_of(thread_idx<M>(t)); }
+    template <int M> static constexpr int reg_lds(int r) { return lds_of(reg_idx<M>(r)); }
 };
 
 // Read-only tables indexed by wave-uniform values go through the constant address space, which makes the
@@ -249,10 +245,10 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     const double p = as_const(&a.fprimes[prime].p)[0], pinv = as_const(&a.fprimes[prime].p)[1];
     constexpr bool INV = (MODE == FP_INV_PLAIN || MODE == FP_INV_TO_Y);
     // Global memory is touched in mapping 1 (lane <-> consecutive coefficients, register r a block of THREADS
-    // further) on the side of the transform whose first/last phase works on the top bits, and on the other side
-    // in mapping 4 where the transposes can stay inside a wave, else in mapping 1 again.
-    constexpr int MIN = (INV && G::WAVE_LOCAL) ? 4 : 1;   // mapping of the inverse transform's loads
-    constexpr int MOUT = (!INV && G::WAVE_LOCAL) ? 4 : 1; // mapping of the forward transform's stores
+    // further) on the side of the transform whose first/last phase works on the top bits, and in mapping 4 on the
+    // other side, where the transposes stay inside a wave.
+    constexpr int MIN = INV ? 4 : 1;    // mapping of the inverse transform's loads
+    constexpr int MOUT = INV ? 1 : 4;   // mapping of the forward transform's stores
     const int t_in = G::template thread_idx<MIN>(t), t_out = G::template thread_idx<MOUT>(t);
     double v[32];
     STAMP(0);
@@ -329,34 +325,34 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
         STAMP(2);
-        // with wave-local transposes the waves run apart: all of them must have left the buffer before this
+        // the waves run apart between the wave-local transposes: all of them must have left the buffer before this
         // workgroup-wide transpose writes to it (its own last barrier guards the other direction)
-        if (G::WAVE_LOCAL) __syncthreads();
+        __syncthreads();
         exchange<K3, 1, 2>(v, lds, t);
         STAMP(3);
         fwd_phase<5, 1, 32, false>(v, tw, bt2, p, pinv);
         constexpr int GROUPS = 1 << (5 - K3);
         double bt3[GROUPS][5];
-        {   // levels 11.. on c: index 2^(10+j) + (a 32 + b), one group per a_high
+        {   // levels 11.. on c: index 2^(10+j) + (a 32 + b), one group per b_high
             int tp[GROUPS];
 #pragma unroll
-            for (int grp = 0; grp < GROUPS; grp++) tp[grp] = ((((grp << K3) | (t >> 5)) << 5) | (t & 31));
+            for (int grp = 0; grp < GROUPS; grp++) tp[grp] = ((t >> K3) << 5) | (grp << K3) | (t & G::CM);
             load_fwd_tw<K3, GROUPS>(bt3, tw, 1024, tp);
             SCHED_FENCE();
         }
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
         STAMP(4);
-        exchange<K3, 2, 3, G::WAVE_LOCAL>(v, lds, t);
+        exchange<K3, 2, 3, true>(v, lds, t);
         STAMP(5);
         fwd_phase<K3, GROUPS, 1 << K3, false>(v, tw, bt3, p, pinv);
         STAMP(6);
-        exchange<K3, 3, MOUT, G::WAVE_LOCAL>(v, lds, t);
+        exchange<K3, 3, MOUT, true>(v, lds, t);
         STAMP(7);
     } else {
         const double* utw = a.utw + (u64)prime * G::N;
         double bt[5];
-        exchange<K3, MIN, 3, G::WAVE_LOCAL>(v, lds, t);
+        exchange<K3, MIN, 3, true>(v, lds, t);
         {   // levels t = 0..K3-1 on c
             const double none[5] = {};
             inv_phase<K3, 1 << (5 - K3), 1 << K3, true>(v, utw, none, p, pinv);
@@ -365,13 +361,13 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         SCHED_FENCE();
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
-        exchange<K3, 3, 2, G::WAVE_LOCAL>(v, lds, t);
+        exchange<K3, 3, 2, true>(v, lds, t);
         inv_phase<5, 1, 32, false>(v, utw, bt, p, pinv);
         load_inv_tw<5>(bt, utw, G::TB, t);        // levels 5 + K3 + j on a: k = (a mod 2^j) 2^(5+K3) + (b, c)
         SCHED_FENCE();
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
-        if (G::WAVE_LOCAL) __syncthreads();
+        __syncthreads();
         exchange<K3, 2, 1>(v, lds, t);
         inv_phase<5, 1, 32, false>(v, utw, bt, p, pinv);
     }
