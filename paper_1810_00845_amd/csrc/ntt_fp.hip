@@ -60,6 +60,31 @@ struct Geo {
 typedef const __attribute__((address_space(4))) double* cdouble_ptr;
 __device__ __forceinline__ cdouble_ptr as_const(const double* p) { return (cdouble_ptr)(unsigned long long)p; }
 
+// Per-lane global accesses go through buffer resources: one (base, size) descriptor per object in scalar registers,
+// the lane's byte offset in ONE vector register per mapping and the row's offset in a scalar register or the
+// instruction.  Plain pointers cost one or two 64-bit vector additions per access (hundreds per task) and a register
+// pair each; this form costs none, and the hardware drops any access beyond `bytes` instead of faulting.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ u64 bload(rsrc_t r, uint32_t lane_off, uint32_t row_off) {
+    const u32x2_t d = __builtin_amdgcn_raw_buffer_load_b64(r, (int)lane_off, (int)row_off, 0);
+    return ((u64)d.y << 32) | d.x;
+}
+__device__ __forceinline__ double bloadf(rsrc_t r, uint32_t lane_off, uint32_t row_off) {
+    return __longlong_as_double((long long)bload(r, lane_off, row_off));
+}
+__device__ __forceinline__ void bstore(rsrc_t r, uint32_t lane_off, uint32_t row_off, u64 x) {
+    u32x2_t d;
+    d.x = (uint32_t)x; d.y = (uint32_t)(x >> 32);
+    __builtin_amdgcn_raw_buffer_store_b64(d, r, (int)lane_off, (int)row_off, 0);
+}
+__device__ __forceinline__ void bstoref(rsrc_t r, uint32_t lane_off, uint32_t row_off, double x) {
+    bstore(r, lane_off, row_off, (u64)__double_as_longlong(x));
+}
+
 #ifdef NTT_FP_NO_FENCE
 #define SCHED_FENCE() do { } while (0)
 #else
@@ -143,11 +168,11 @@ __device__ __forceinline__ void bfly(double& x, double& y, double w, double p, d
 // The per-thread values are fetched one phase ahead, before the transpose, so that their latency hides behind
 // the LDS traffic; the products cost 26 modular multiplications per phase.
 template <int BITS, int GROUPS>
-__device__ __forceinline__ void load_fwd_tw(double (&bt)[GROUPS][5], const double* tw, int first, const int (&tpart)[GROUPS]) {
+__device__ __forceinline__ void load_fwd_tw(double (&bt)[GROUPS][5], rsrc_t tw, int first, const int (&tpart)[GROUPS]) {
 #pragma unroll
     for (int grp = 0; grp < GROUPS; grp++)
 #pragma unroll
-        for (int j = 0; j < BITS; j++) bt[grp][j] = (tw + (first << j))[tpart[grp]];
+        for (int j = 0; j < BITS; j++) bt[grp][j] = bloadf(tw, (uint32_t)tpart[grp] * 8u, (uint32_t)(first << j) * 8u);
 }
 
 // BITS levels over the register-index field of each group of 2^BITS registers (GROUPS groups), largest distance
@@ -176,9 +201,9 @@ __device__ __forceinline__ void fwd_phase(double (&v)[32], const double* tw, con
 }
 
 template <int BITS>
-__device__ __forceinline__ void load_inv_tw(double (&bt)[5], const double* utw, int t0, int tlow) {
+__device__ __forceinline__ void load_inv_tw(double (&bt)[5], rsrc_t utw, int t0, int tlow) {
 #pragma unroll
-    for (int j = 0; j < BITS; j++) bt[j] = utw[(1 << (t0 + j)) + tlow];
+    for (int j = 0; j < BITS; j++) bt[j] = bloadf(utw, (uint32_t)tlow * 8u, (8u << (t0 + j)));
 }
 
 // Inverse phase (decimation in time from bit-reversed input): level j pairs bit j of the field, smallest distance
@@ -250,12 +275,14 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     constexpr int MIN = INV ? 4 : 1;    // mapping of the inverse transform's loads
     constexpr int MOUT = INV ? 1 : 4;   // mapping of the forward transform's stores
     const int t_in = G::template thread_idx<MIN>(t), t_out = G::template thread_idx<MOUT>(t);
+    constexpr uint32_t LB = (uint32_t)G::N * 8u;   // bytes of one limb-polynomial
+    const uint32_t t8 = (uint32_t)t * 8u, t8_in = (uint32_t)t_in * 8u, t8_out = (uint32_t)t_out * 8u;
     double v[32];
     STAMP(0);
 
     // ---- load (mapping P1: lane <-> consecutive coefficients; register r holds coefficient r*THREADS + t) ----
     if (MODE == FP_FWD_PLAIN || INV) {
-        const u64* src = a.in + b * a.in_bs + (u64)(pos + a.in_pos_shift) * G::N;
+        const rsrc_t src = make_rsrc(a.in + b * a.in_bs + (u64)(pos + a.in_pos_shift) * G::N, LB);
         if (INV && a.galois) {
             // a private copy of the lane id: keeps the 32 gather indices from being kept alive (and spilled) for the
             // address arithmetic of the store stage
@@ -263,37 +290,38 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
             asm volatile("" : "+v"(tg));
 #pragma unroll
             for (int r = 0; r < 32; r++)
-                v[r] = fp_from_u64(src[galois_src_fp((uint32_t)(G::template reg_idx<MIN>(r) | tg), a.galois, G::LOGN)]);
+                v[r] = fp_from_u64(bload(src, galois_src_fp((uint32_t)(G::template reg_idx<MIN>(r) | tg), a.galois, G::LOGN) * 8u, 0));
         } else if (INV) {
 #pragma unroll
-            for (int r = 0; r < 32; r++) v[r] = fp_from_u64((src + G::template reg_idx<MIN>(r))[t_in]);
+            for (int r = 0; r < 32; r++) v[r] = fp_from_u64(bload(src, t8_in, (uint32_t)G::template reg_idx<MIN>(r) * 8u));
         } else {
 #pragma unroll
-            for (int r = 0; r < 32; r++) v[r] = fp_from_u64((src + (r << G::TB))[t]);
+            for (int r = 0; r < 32; r++) v[r] = fp_from_u64(bload(src, t8, (uint32_t)(r << G::TB) * 8u));
         }
     } else {
         // fast base conversion: sum_i y_i * hat_i mod p, y_i centred source digits (already times (D/c_i)^-1).
         // Loads are issued eight at a time, one batch ahead of the arithmetic (two explicit buffers; the fences keep
         // the compiler from sinking each load to its use, which would expose one memory latency per element).
-        const double* y = a.y + b * a.y_bs + (u64)a.y_pos0 * G::N;
+        const rsrc_t y = make_rsrc(a.y + b * a.y_bs + (u64)a.y_pos0 * G::N, (uint32_t)a.conv_a * LB);
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = 0.0;
         double bufa[8], bufb[8];
 #pragma unroll
-        for (int k = 0; k < 8; k++) bufa[k] = (y + (k << G::TB))[t];
+        for (int k = 0; k < 8; k++) bufa[k] = bloadf(y, t8, (uint32_t)(k << G::TB) * 8u);
         for (int i = 0; i < a.conv_a; i++) {
             const double h = as_const(a.hat)[(u64)i * a.total + prime];
-            const double* yi = y + (u64)i * G::N;
-            const double* yn = (i + 1 < a.conv_a) ? yi + G::N : yi;  // next source limb (dummy reload on the last)
+            const uint32_t yi = (uint32_t)i * LB;
+            const uint32_t yn = (i + 1 < a.conv_a) ? yi + LB : yi;  // next source limb (dummy reload on the last)
 #pragma unroll
             for (int c = 0; c < 4; c++) {
                 SCHED_FENCE();
                 if (c < 3) {
 #pragma unroll
-                    for (int k = 0; k < 8; k++) ((c & 1) ? bufa : bufb)[k] = (yi + (((c + 1) * 8 + k) << G::TB))[t];
+                    for (int k = 0; k < 8; k++)
+                        ((c & 1) ? bufa : bufb)[k] = bloadf(y, t8, yi + (uint32_t)(((c + 1) * 8 + k) << G::TB) * 8u);
                 } else {
 #pragma unroll
-                    for (int k = 0; k < 8; k++) bufa[k] = (yn + (k << G::TB))[t];
+                    for (int k = 0; k < 8; k++) bufa[k] = bloadf(y, t8, yn + (uint32_t)(k << G::TB) * 8u);
                 }
                 SCHED_FENCE();
 #pragma unroll
@@ -312,6 +340,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     STAMP(1);
     if (!INV) {
         const double* tw = a.ftw + (u64)prime * G::N;
+        const rsrc_t twr = make_rsrc(tw, LB);
         double bt2[1][5];
         {   // levels 1..5 on a: twiddles depend on the register index only
             const double none[1][5] = {};
@@ -319,7 +348,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         }
         {   // per-thread twiddles of levels 6..10 (index 2^(5+j) + a), fetched before the transpose
             const int tp[1] = {t >> K3};
-            load_fwd_tw<5, 1>(bt2, tw, 32, tp);
+            load_fwd_tw<5, 1>(bt2, twr, 32, tp);
             SCHED_FENCE();
         }
 #pragma unroll
@@ -337,7 +366,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
             int tp[GROUPS];
 #pragma unroll
             for (int grp = 0; grp < GROUPS; grp++) tp[grp] = ((t >> K3) << 5) | (grp << K3) | (t & G::CM);
-            load_fwd_tw<K3, GROUPS>(bt3, tw, 1024, tp);
+            load_fwd_tw<K3, GROUPS>(bt3, twr, 1024, tp);
             SCHED_FENCE();
         }
 #pragma unroll
@@ -351,19 +380,20 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         STAMP(7);
     } else {
         const double* utw = a.utw + (u64)prime * G::N;
+        const rsrc_t utwr = make_rsrc(utw, LB);
         double bt[5];
         exchange<K3, MIN, 3, true>(v, lds, t);
         {   // levels t = 0..K3-1 on c
             const double none[5] = {};
             inv_phase<K3, 1 << (5 - K3), 1 << K3, true>(v, utw, none, p, pinv);
         }
-        load_inv_tw<5>(bt, utw, K3, t & G::CM);   // levels K3 + j on b: k = (b mod 2^j) 2^K3 + c
+        load_inv_tw<5>(bt, utwr, K3, t & G::CM);   // levels K3 + j on b: k = (b mod 2^j) 2^K3 + c
         SCHED_FENCE();
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
         exchange<K3, 3, 2, true>(v, lds, t);
         inv_phase<5, 1, 32, false>(v, utw, bt, p, pinv);
-        load_inv_tw<5>(bt, utw, G::TB, t);        // levels 5 + K3 + j on a: k = (a mod 2^j) 2^(5+K3) + (b, c)
+        load_inv_tw<5>(bt, utwr, G::TB, t);        // levels 5 + K3 + j on a: k = (a mod 2^j) 2^(5+K3) + (b, c)
         SCHED_FENCE();
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
@@ -375,16 +405,19 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     // ---- store (mapping P1) ----
     STAMP(8);
     if (MODE == FP_FWD_PLAIN || MODE == FP_FWD_CONV) {
-        u64* dst = a.out + b * a.out_bs + (u64)pos * G::N;
+        const rsrc_t dst = make_rsrc(a.out + b * a.out_bs + (u64)pos * G::N, LB);
 #pragma unroll
-        for (int r = 0; r < 32; r++) (dst + G::template reg_idx<MOUT>(r))[t_out] = fp_canonical(v[r], p, pinv);
+        for (int r = 0; r < 32; r++)
+            bstore(dst, t8_out, (uint32_t)G::template reg_idx<MOUT>(r) * 8u, fp_canonical(v[r], p, pinv));
     } else if (MODE == FP_FWD_CONV_FINAL) {
         // out = (acc - conv) * P^-1 (+ addend); operands fetched eight at a time ahead of their use
-        const u64* acc = a.acc + b * a.acc_bs + (u64)(pos + a.acc_pos_shift) * G::N;
-        u64* dst = a.out + b * a.out_bs + (u64)pos * G::N;
+        const u64* acc_p = a.acc + b * a.acc_bs + (u64)(pos + a.acc_pos_shift) * G::N;
+        const rsrc_t acc = make_rsrc(acc_p, LB);
+        const rsrc_t dst = make_rsrc(a.out + b * a.out_bs + (u64)pos * G::N, LB);
         const double pin = as_const(a.pinv_tab)[prime];
         const bool with_add = a.add && (int)(b % a.add_div) < a.add_polys;
-        const u64* add = with_add ? a.add + (b / a.add_div) * a.add_bs + (b % a.add_div) * a.add_ps + (u64)pos * G::N : acc;
+        const rsrc_t add = make_rsrc(
+            with_add ? a.add + (b / a.add_div) * a.add_bs + (b % a.add_div) * a.add_ps + (u64)pos * G::N : acc_p, LB);
         int tg = t_out;
         asm volatile("" : "+v"(tg));
 #pragma unroll
@@ -394,10 +427,11 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
 #pragma unroll
             for (int k = 0; k < 8; k++) {
                 const int r = c * 8 + k;
-                va[k] = (acc + G::template reg_idx<MOUT>(r))[t_out];
+                const uint32_t row = (uint32_t)G::template reg_idx<MOUT>(r) * 8u;
+                va[k] = bload(acc, t8_out, row);
                 if (with_add && a.add_galois)
-                    vb[k] = add[galois_src_fp((uint32_t)(G::template reg_idx<MOUT>(r) | tg), a.add_galois, G::LOGN)];
-                else vb[k] = (add + G::template reg_idx<MOUT>(r))[t_out];
+                    vb[k] = bload(add, galois_src_fp((uint32_t)(G::template reg_idx<MOUT>(r) | tg), a.add_galois, G::LOGN) * 8u, 0);
+                else vb[k] = bload(add, t8_out, row);
             }
             SCHED_FENCE();
 #pragma unroll
@@ -406,27 +440,28 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
                 double x = fp_from_u64(va[k]) - fp_norm(v[r], p, pinv);
                 x = fp_mulmod(x, pin, p, pinv);
                 if (with_add) x += fp_from_u64(vb[k]);
-                (dst + G::template reg_idx<MOUT>(r))[t_out] = fp_canonical(x, p, pinv);
+                bstore(dst, t8_out, (uint32_t)G::template reg_idx<MOUT>(r) * 8u, fp_canonical(x, p, pinv));
             }
         }
     } else {
-        const double* vtw = a.vtw + (u64)prime * G::N;
+        const rsrc_t vtw = make_rsrc(a.vtw + (u64)prime * G::N, LB);
         const double post = MODE == FP_INV_TO_Y ? as_const(a.post)[e] : 1.0;
-        u64* dst = a.out + b * a.out_bs + (u64)pos * G::N;
-        double* ydst = a.yout + b * a.yout_bs + (u64)pos * G::N;
+        // one of the two outputs is null, according to the mode; its descriptor is then never used
+        const rsrc_t dst = make_rsrc(MODE == FP_INV_PLAIN ? (const void*)(a.out + b * a.out_bs + (u64)pos * G::N)
+                                                          : (const void*)(a.yout + b * a.yout_bs + (u64)pos * G::N), LB);
 #pragma unroll
         for (int c = 0; c < 4; c++) {
             double w8[8];
             SCHED_FENCE();
 #pragma unroll
-            for (int k = 0; k < 8; k++) w8[k] = (vtw + ((c * 8 + k) << G::TB))[t];
+            for (int k = 0; k < 8; k++) w8[k] = bloadf(vtw, t8, (uint32_t)((c * 8 + k) << G::TB) * 8u);
             SCHED_FENCE();
 #pragma unroll
             for (int k = 0; k < 8; k++) {
                 const int r = c * 8 + k;
                 const double x = fp_mulmod(v[r], w8[k], p, pinv);
-                if (MODE == FP_INV_PLAIN) (dst + (r << G::TB))[t] = fp_canonical(x, p, pinv);
-                else (ydst + (r << G::TB))[t] = fp_norm(fp_mulmod(x, post, p, pinv), p, pinv);
+                if (MODE == FP_INV_PLAIN) bstore(dst, t8, (uint32_t)(r << G::TB) * 8u, fp_canonical(x, p, pinv));
+                else bstoref(dst, t8, (uint32_t)(r << G::TB) * 8u, fp_norm(fp_mulmod(x, post, p, pinv), p, pinv));
             }
         }
     }
