@@ -144,6 +144,70 @@ __global__ __launch_bounds__(NT) void plain_mac_kernel(const PrimeConst* primes,
     o[ln] = acc_reduce(a1, pc.q, pc.r1, pc.r0);
 }
 
+// The slot-wise sum in exact fp64 arithmetic (every prime below 2^50).  A thread forms OCP outputs from each pair of
+// ciphertext words it loads (the inputs are re-read once per group of OCP outputs, not once per output), and two
+// (tap, channel) terms are loaded before their arithmetic.
+#define OCP 4
+#define ICP 2
+__global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes, MacArgs g, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    const int limb = blockIdx.y;
+    const int ocblocks = (g.OC + OCP - 1) / OCP;
+    const int b = blockIdx.z / ocblocks, oc0 = (blockIdx.z % ocblocks) * OCP;
+    const mac_cdouble_ptr fp = (mac_cdouble_ptr)(unsigned long long)&fprimes[limb].p;
+    const double p = fp[0], pinv = fp[1];
+    const u64 ln = (u64)g.l * n;
+    double a0[OCP], a1[OCP];
+#pragma unroll
+    for (int o = 0; o < OCP; o++) a0[o] = a1[o] = 0.0;
+    int pending = 0;
+    for (int t = 0; t < g.n_taps; t++) {
+        const u64* x = g.tap_base[t] + (u64)b * g.IC * g.ct_words + (u64)limb * n + j;
+        const u64* w = g.w + ((u64)t * g.IC * g.w_stride_t + (u64)oc0 * g.w_stride_oc) * ln + (u64)limb * n + j;
+        for (int ic0 = 0; ic0 < g.IC; ic0 += ICP) {
+            u64 xb[ICP], xa[ICP], wv[ICP][OCP];
+#pragma unroll
+            for (int u = 0; u < ICP; u++) {
+                const int ic = ic0 + u < g.IC ? ic0 + u : g.IC - 1;
+                xb[u] = x[(u64)ic * g.ct_words];
+                xa[u] = x[(u64)ic * g.ct_words + ln];
+#pragma unroll
+                for (int o = 0; o < OCP; o++) {
+                    const int oo = oc0 + o < g.OC ? o : 0;
+                    wv[u][o] = w[((u64)ic * g.w_stride_t + (u64)oo * g.w_stride_oc) * ln];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < ICP; u++) {
+                if (ic0 + u < g.IC) {
+                    const double fb = fp_from_u64(xb[u]), fa = fp_from_u64(xa[u]);
+#pragma unroll
+                    for (int o = 0; o < OCP; o++) {
+                        const double wf = fp_from_u64(wv[u][o]);
+                        a0[o] += fp_mulmod(fb, wf, p, pinv);
+                        a1[o] += fp_mulmod(fa, wf, p, pinv);
+                    }
+                }
+            }
+            pending += ICP;
+            if (pending >= 4) {   // canonical operands: a term can reach 0.9 p, four of them on a normalised value 4.1 p
+#pragma unroll
+                for (int o = 0; o < OCP; o++) { a0[o] = fp_norm(a0[o], p, pinv); a1[o] = fp_norm(a1[o], p, pinv); }
+                pending = 0;
+            }
+        }
+    }
+#pragma unroll
+    for (int o = 0; o < OCP; o++) {
+        if (oc0 + o < g.OC) {
+            u64* dst = g.out + ((u64)b * g.OC + oc0 + o) * g.ct_words + (u64)limb * n + j;
+            dst[0] = fp_canonical(a0[o], p, pinv);
+            dst[ln] = fp_canonical(a1[o], p, pinv);
+        }
+    }
+}
+
 static hipError_t launch_scalar_mac(const PrimeConst* primes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
     dim3 grid((1u << log_n) / NT, 2 * g.l, batch * ((g.OC + OCB - 1) / OCB));
     ProfScope prof__("scalar_mac_kernel", st);
@@ -157,6 +221,14 @@ static hipError_t launch_scalar_mac_fp(const FpPrime* fprimes, const MacArgs& g,
     dim3 grid((1u << log_n) / NT, 2 * g.l, batch * ((g.OC + OCF - 1) / OCF));
     ProfScope prof__("scalar_mac_fp_kernel", st);
     hipLaunchKernelGGL(scalar_mac_fp_kernel, grid, dim3(NT), 0, st, fprimes, g, wf, log_n);
+    return hipGetLastError();
+}
+
+static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
+    if (!fprimes || !g.w || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS) return hipErrorInvalidValue;
+    dim3 grid((1u << log_n) / NT, g.l, batch * ((g.OC + OCP - 1) / OCP));
+    ProfScope prof__("plain_mac_fp_kernel", st);
+    hipLaunchKernelGGL(plain_mac_fp_kernel, grid, dim3(NT), 0, st, fprimes, g, log_n);
     return hipGetLastError();
 }
 
@@ -389,7 +461,8 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
         hipError_t e;
         if (g->mode == HISA_CONV_PLAIN) {
             ma.w = d_pts; ma.w_stride_t = OC; ma.w_stride_oc = 1;
-            e = launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+            if (ctx->tabs.fp_ok) e = launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+            else e = launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
         } else {
             ma.w = d_w;
             if (d_wf) e = launch_scalar_mac_fp(ctx->tabs.fprimes, ma, d_wf, (int)B, (int)ctx->log_n, ctx->stream);
@@ -528,7 +601,8 @@ static int fc_chunk(hisa_ctx* ctx, const hisa_tensor* in, const BatchIn& bi, con
     ma.w = pts; ma.w_stride_t = 1; ma.w_stride_oc = C;
     ma.out = outs[0]->data;
     (void)pt_scale;
-    HIP_TRY(ctx, launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream));
+    if (ctx->tabs.fp_ok) HIP_TRY(ctx, launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream));
+    else HIP_TRY(ctx, launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream));
     return HISA_OK;
 }
 
