@@ -125,9 +125,9 @@ def cpu_baseline(log_n, q_bits, dnum, special_bits, seed, sample, steps):
 
 def network_latencies():
     """Encrypted inference latency of the benchmark networks (BASELINE configs 3, 4 and 5): encrypt-done to the
-    last output ciphertext ready, one image, rotation and relinearisation keys resident, fully connected weights
-    encoded ahead of time (hisa_fc_prepare), convolution weights converted inside the timed region (median of 3
-    after one set-up pass that generates the keys and the plans)."""
+    last output ciphertext ready, one image, rotation and relinearisation keys resident, weights converted and
+    encoded ahead of time (hisa_conv2d_prepare, hisa_fc_prepare) (median of 3 after one set-up pass that generates
+    the keys and the plans)."""
     import numpy as np
     from paper_1810_00845_amd import hisa, nets
     out = {}

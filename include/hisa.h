@@ -243,6 +243,16 @@ int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t 
 int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* w_int, double w_scale,
                       const int64_t* pt_coeffs, double pt_scale, uint32_t out_channels, const hisa_conv_geom* geom,
                       hisa_tensor* out);
+/* The same convolution with its weights converted ahead of time (fixed-point residues per limb, the forms the
+ * multiply-accumulate kernels read, the mask or per-tap plaintexts): hisa_conv2d_prepare builds a plan for tensors
+ * with the layout, clean flag and level of `like`; hisa_conv2d_apply(in, plan) returns bit for bit what
+ * hisa_conv2d(in, w, ...) returns.  Another layout is HISA_ERR_ARG, another level HISA_ERR_LEVEL_MISMATCH.  The plan
+ * owns device memory until hisa_conv_plan_free. */
+typedef struct hisa_conv_plan hisa_conv_plan;
+int hisa_conv2d_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t out_channels,
+                        const hisa_conv_geom* geom, hisa_conv_plan** plan);
+int hisa_conv2d_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_plan* plan, hisa_tensor* out);
+int hisa_conv_plan_free(hisa_ctx* ctx, hisa_conv_plan* plan);
 /* Fully connected layer over all elements of all channels (Sec. "Homomorphic
  * matmul", the version without replicas): host w[OUT][C][H][W]; per output o:
  * sum_c mulPlain(in[c], encode(w[o][c] placed on the element slots, zero

@@ -144,6 +144,120 @@ __global__ __launch_bounds__(NT) void plain_mac_kernel(const PrimeConst* primes,
     o[ln] = acc_reduce(a1, pc.q, pc.r1, pc.r0);
 }
 
+// The same sum on the matrix cores.  Over k = (tap, channel) it is a dense contraction out[oc][e] = sum_k W[k][oc] X[k][e]
+// of integers below 2^50 in magnitude.  Both factors are split into seven signed base-256 digits; the 49 digit-by-digit
+// products are int8 MFMAs accumulating exactly in int32, summed per diagonal a + b = s (13 accumulators per output);
+// the value sum_s D_s 256^s is then reduced modulo p in fp64.  Exact, so bit-identical to the other two kernels.
+//   block: 4 waves; 64 coefficients x 64 outputs; wave w owns outputs 16 w .. 16 w + 15 (rows of the MFMA tile) and
+//   four 16-coefficient column tiles; k advances 64 at a time (one 16x16x64 MFMA per digit pair and column tile).
+//   The digits of X are staged in LDS as [digit][k / 16][e][k % 16]: a thread converts 16 consecutive k of one
+//   coefficient and writes 16 bytes per digit, exactly the operand a lane reads back.  The next 16 words are loaded
+//   from global memory before the MFMAs of the current ones.
+//   Operand slots: lane l of an operand holds row or column l % 16 and the sixteen k values of group l / 16; both
+//   operands use the same k <-> slot assignment, which is all the contraction needs.  Result: lane l, register r
+//   holds row 4 (l / 16) + r, column l % 16.
+#define MT_E 64
+#define MT_OC 64
+#define MT_K 64
+#define MAC_DIGITS 7
+#define MAC_DIAGS (2 * MAC_DIGITS - 1)
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+
+// the seven signed base-256 digits of x (|x| < 2^55) in the low seven bytes: (x + B) ^ B with B = 0x80 in each of them
+__host__ __device__ __forceinline__ u64 balanced_digits(u64 x) {
+    const u64 B = 0x0080808080808080ULL;
+    return (x + B) ^ B;
+}
+
+__global__ __launch_bounds__(256) void scalar_mac_mfma_kernel(const FpPrime* fprimes, MacArgs g, const int8_t* wd, int K,
+                                                              int K_pad, int OC_pad, const double* c3, int log_n) {
+    __shared__ v4i_t xd[MAC_DIGITS][MT_K / 16][MT_E];
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const u64 n = (u64)1 << log_n;
+    const u64 e0 = (u64)blockIdx.x * MT_E;
+    const int pl = blockIdx.y, limb = pl % g.l;
+    const int ocblocks = OC_pad / MT_OC;
+    const int b = blockIdx.z / ocblocks, oc0 = (blockIdx.z % ocblocks) * MT_OC + wave * 16;
+
+    v4i_t acc[4][MAC_DIAGS];
+#pragma unroll
+    for (int ct = 0; ct < 4; ct++)
+#pragma unroll
+        for (int sdiag = 0; sdiag < MAC_DIAGS; sdiag++) acc[ct][sdiag] = (v4i_t){0, 0, 0, 0};
+
+    // the 16 words X[k][e0 + lane], k = kc + 16 wave + s (zero beyond K)
+    u64 xs[16];
+    auto load_x = [&](int kc) {
+        int k = kc + wave * 16;
+        int tap = k / g.IC, ic = k - tap * g.IC;
+#pragma unroll
+        for (int sl = 0; sl < 16; sl++) {
+            xs[sl] = 0;
+            if (k + sl < K) xs[sl] = g.tap_base[tap][((u64)b * g.IC + ic) * g.ct_words + (u64)pl * n + e0 + lane];
+            if (++ic == g.IC) { ic = 0; tap++; }
+        }
+    };
+    load_x(0);
+    for (int kc = 0; kc < K_pad; kc += MT_K) {
+#pragma unroll
+        for (int sl = 0; sl < 16; sl++) xs[sl] = balanced_digits(xs[sl]);
+#pragma unroll
+        for (int a = 0; a < MAC_DIGITS; a++) {
+            v4i_t d;
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                uint32_t wq = 0;
+#pragma unroll
+                for (int i = 0; i < 4; i++) wq |= (uint32_t)((xs[4 * q + i] >> (8 * a)) & 0xFF) << (8 * i);
+                d[q] = (int)wq;
+            }
+            xd[a][wave][lane] = d;
+        }
+        __syncthreads();
+        if (kc + MT_K < K_pad) load_x(kc + MT_K);
+        v4i_t A[MAC_DIGITS];
+#pragma unroll
+        for (int a = 0; a < MAC_DIGITS; a++)
+            A[a] = *(const v4i_t*)(wd + (((u64)(limb * MAC_DIGITS + a) * OC_pad + oc0 + (lane & 15)) * K_pad + kc + 16 * (lane >> 4)));
+#pragma unroll
+        for (int ct = 0; ct < 4; ct++) {
+            v4i_t Bv[MAC_DIGITS];
+#pragma unroll
+            for (int bb = 0; bb < MAC_DIGITS; bb++) Bv[bb] = xd[bb][lane >> 4][ct * 16 + (lane & 15)];
+#pragma unroll
+            for (int a = 0; a < MAC_DIGITS; a++)
+#pragma unroll
+                for (int bb = 0; bb < MAC_DIGITS; bb++)
+                    acc[ct][a + bb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[a], Bv[bb], acc[ct][a + bb], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // sum_s D_s 256^s mod p: three diagonals at a time are combined exactly in a double (below 2^48), then five
+    // modular products with 2^(24 g) mod p
+    const mac_cdouble_ptr fp = (mac_cdouble_ptr)(unsigned long long)&fprimes[limb].p;
+    const double p = fp[0], pinv = fp[1];
+    const mac_cdouble_ptr cg = (mac_cdouble_ptr)(unsigned long long)(c3 + limb * 5);
+#pragma unroll
+    for (int ct = 0; ct < 4; ct++) {
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const int oc = oc0 + 4 * (lane >> 4) + r;
+            double sum = 0.0;
+#pragma unroll
+            for (int gq = 0; gq < 5; gq++) {
+                double G = (double)acc[ct][3 * gq][r];
+                if (3 * gq + 1 < MAC_DIAGS) G = __builtin_fma((double)acc[ct][3 * gq + 1][r], 256.0, G);
+                if (3 * gq + 2 < MAC_DIAGS) G = __builtin_fma((double)acc[ct][3 * gq + 2][r], 65536.0, G);
+                sum += fp_mulmod(G, cg[gq], p, pinv);
+            }
+            if (oc < g.OC)
+                g.out[((u64)b * g.OC + oc) * g.ct_words + (u64)pl * n + e0 + ct * 16 + (lane & 15)] = fp_canonical(sum, p, pinv);
+        }
+    }
+}
+
 // The slot-wise sum in exact fp64 arithmetic (every prime below 2^50).  A thread forms OCP outputs from each pair of
 // ciphertext words it loads (the inputs are re-read once per group of OCP outputs, not once per output), and two
 // (tap, channel) terms are loaded before their arithmetic.
@@ -221,6 +335,17 @@ static hipError_t launch_scalar_mac_fp(const FpPrime* fprimes, const MacArgs& g,
     dim3 grid((1u << log_n) / NT, 2 * g.l, batch * ((g.OC + OCF - 1) / OCF));
     ProfScope prof__("scalar_mac_fp_kernel", st);
     hipLaunchKernelGGL(scalar_mac_fp_kernel, grid, dim3(NT), 0, st, fprimes, g, wf, log_n);
+    return hipGetLastError();
+}
+
+static hipError_t launch_scalar_mac_mfma(const FpPrime* fprimes, const MacArgs& g, const int8_t* wd, int K, int K_pad, int OC_pad,
+                                         const double* c3, int batch, int log_n, hipStream_t st) {
+    if (!fprimes || !wd || !c3 || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || K != g.n_taps * g.IC || K_pad % MT_K ||
+        K_pad < K || OC_pad % MT_OC || OC_pad < g.OC || log_n < 6)
+        return hipErrorInvalidValue;
+    dim3 grid((1u << log_n) / MT_E, 2 * g.l, batch * (OC_pad / MT_OC));
+    ProfScope prof__("scalar_mac_mfma_kernel", st);
+    hipLaunchKernelGGL(scalar_mac_mfma_kernel, grid, dim3(256), 0, st, fprimes, g, wd, K, K_pad, OC_pad, c3, log_n);
     return hipGetLastError();
 }
 
@@ -422,10 +547,69 @@ static int conv_plan(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom*
     return HISA_OK;
 }
 
-// d_w: SCALAR/MASKED residues [T][OC][l] (d_wf: the same as centred doubles when every prime is below 2^50, else null);
-// d_pts: MASKED [l][N], PLAIN [T][OC][l][N]
+// Fixed-point weights w[K][OC] (K = taps x input channels) on the device: residues per limb for the integer kernel;
+// when every prime is below 2^50 also centred doubles [l][K][OC] for the fp64 kernel and, for contractions long enough
+// to fill the matrix cores, signed base-256 digits [l][7][OC_pad][K_pad] with the constants 2^(24 g) mod q.
+#define MFMA_MIN_K 32
+#define MFMA_MAX_K 16384   // 7 K 2^14 must stay below 2^31
+struct DevWeights {
+    size_t K, OC, K_pad, OC_pad;
+    bool fp, mfma;
+    Temp res, resf, digits, c3;
+    DevWeights(hisa_ctx* ctx, size_t K_, size_t OC_, uint32_t l)
+        : K(K_), OC(OC_), K_pad((K_ + MT_K - 1) / MT_K * MT_K), OC_pad((OC_ + MT_OC - 1) / MT_OC * MT_OC),
+          fp(ctx->tabs.fp_ok), mfma(ctx->tabs.fp_ok && K_ >= MFMA_MIN_K && K_ <= MFMA_MAX_K),
+          res(ctx, K_ * OC_ * l * sizeof(u64)), resf(ctx, fp ? K_ * OC_ * l * sizeof(double) : 8),
+          digits(ctx, mfma ? (size_t)l * MAC_DIGITS * OC_pad * K_pad : 8), c3(ctx, mfma ? (size_t)l * 5 * sizeof(double) : 8) {}
+    bool ok() const { return res.ok() && resf.ok() && digits.ok() && c3.ok(); }
+};
+
+static int upload_weight_residues(hisa_ctx* ctx, const int64_t* w_int, uint32_t l, DevWeights& dst) {
+    const size_t count = dst.K * dst.OC;
+    std::vector<u64> res(count * l);
+    std::vector<double> resf(dst.fp ? count * l : 0), c3(dst.mfma ? (size_t)l * 5 : 0);
+    std::vector<int8_t> dig(dst.mfma ? (size_t)l * MAC_DIGITS * dst.OC_pad * dst.K_pad : 0, 0);
+    for (uint32_t k = 0; k < l; k++) {
+        const u64 q = ctx->mod[k];
+        for (size_t oc = 0; oc < dst.OC; oc++) {       // digit rows are contiguous in the contraction index
+            for (size_t kk = 0; kk < dst.K; kk++) {
+                const size_t i = kk * dst.OC + oc;
+                const i64 wv = w_int[i];
+                // weights are almost always far below the modulus: the remainder is then the value itself
+                const u64 r = (wv >= 0 && (u64)wv < q) ? (u64)wv : ((wv < 0 && wv > -(i64)q) ? q - (u64)(-wv) : mod_i64(wv, q));
+                res[i * l + k] = r;
+                if (!dst.fp) continue;
+                const i64 c = r > q / 2 ? -(i64)(q - r) : (i64)r;
+                resf[(size_t)k * count + i] = (double)c;   // [l][K][OC]
+                if (!dst.mfma) continue;
+                const u64 d = balanced_digits((u64)c);
+                int8_t* row = dig.data() + ((size_t)k * MAC_DIGITS * dst.OC_pad + oc) * dst.K_pad + kk;
+                for (int a = 0; a < MAC_DIGITS; a++) row[(size_t)a * dst.OC_pad * dst.K_pad] = (int8_t)(uint8_t)(d >> (8 * a));
+            }
+        }
+        if (dst.mfma) {
+            u64 pw = 1 % q;
+            for (int gq = 0; gq < 5; gq++) {
+                c3[(size_t)k * 5 + gq] = pw > q / 2 ? -(double)(q - pw) : (double)pw;
+                for (int i = 0; i < 24; i++) pw = (pw << 1) % q;
+            }
+        }
+    }
+    HIP_TRY(ctx, hipMemcpyAsync(dst.res.blk->ptr, res.data(), res.size() * sizeof(u64), hipMemcpyHostToDevice, ctx->stream));
+    if (dst.fp)
+        HIP_TRY(ctx, hipMemcpyAsync(dst.resf.blk->ptr, resf.data(), resf.size() * sizeof(double), hipMemcpyHostToDevice,
+                                    ctx->stream));
+    if (dst.mfma) {
+        HIP_TRY(ctx, hipMemcpyAsync(dst.digits.blk->ptr, dig.data(), dig.size(), hipMemcpyHostToDevice, ctx->stream));
+        HIP_TRY(ctx, hipMemcpyAsync(dst.c3.blk->ptr, c3.data(), c3.size() * sizeof(double), hipMemcpyHostToDevice, ctx->stream));
+    }
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HISA_OK;
+}
+
+// dw: SCALAR/MASKED weights (null for PLAIN); d_pts: MASKED [l][N], PLAIN [T][OC][l][N]
 static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
-                    const u64* d_w, const double* d_wf, double w_scale, const u64* d_pts, double pt_scale, hisa_tensor* out) {
+                    DevWeights* dw, double w_scale, const u64* d_pts, double pt_scale, hisa_tensor* out) {
     const uint32_t B = in->batch, IC = in->channels, l = in->cts[0]->limbs;
     const size_t nct = (size_t)B * IC, n = ctx->N;
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
@@ -464,8 +648,12 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
             if (ctx->tabs.fp_ok) e = launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
             else e = launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
         } else {
-            ma.w = d_w;
-            if (d_wf) e = launch_scalar_mac_fp(ctx->tabs.fprimes, ma, d_wf, (int)B, (int)ctx->log_n, ctx->stream);
+            ma.w = dw->res.u();
+            if (dw->mfma)
+                e = launch_scalar_mac_mfma(ctx->tabs.fprimes, ma, (const int8_t*)dw->digits.blk->ptr, (int)dw->K, (int)dw->K_pad,
+                                           (int)dw->OC_pad, dw->c3.as<double>(), (int)B, (int)ctx->log_n, ctx->stream);
+            else if (dw->fp)
+                e = launch_scalar_mac_fp(ctx->tabs.fprimes, ma, dw->resf.as<double>(), (int)B, (int)ctx->log_n, ctx->stream);
             else e = launch_scalar_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
             if (e == hipSuccess && g->mode == HISA_CONV_MASKED) {
                 e = launch_mul_plain(ctx->d_primes, outs[0]->data, d_pts, outs[0]->data, (int)l, 2, (u64)B * OC, ma.ct_words,
@@ -490,33 +678,6 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
     return HISA_OK;
 }
 
-// fixed-point weights on the device: residues per limb, and centred doubles for the fp64 multiply-accumulate
-struct DevWeights {
-    Temp res, resf;
-    bool fp;
-    DevWeights(hisa_ctx* ctx, size_t count, uint32_t l)
-        : res(ctx, count * l * sizeof(u64)), resf(ctx, ctx->tabs.fp_ok ? count * l * sizeof(double) : 8), fp(ctx->tabs.fp_ok) {}
-    bool ok() const { return res.ok() && resf.ok(); }
-    const double* f() { return fp ? resf.as<double>() : nullptr; }
-};
-
-static int upload_weight_residues(hisa_ctx* ctx, const int64_t* w_int, size_t count, uint32_t l, DevWeights& dst) {
-    std::vector<u64> res(count * l);
-    std::vector<double> resf(dst.fp ? count * l : 0);
-    for (size_t i = 0; i < count; i++)
-        for (uint32_t k = 0; k < l; k++) {
-            const u64 q = ctx->mod[k], r = mod_i64(w_int[i], q);
-            res[i * l + k] = r;
-            if (dst.fp) resf[(size_t)k * count + i] = r > q / 2 ? -(double)(q - r) : (double)r;   // [l][T][OC]
-        }
-    HIP_TRY(ctx, hipMemcpyAsync(dst.res.blk->ptr, res.data(), res.size() * sizeof(u64), hipMemcpyHostToDevice, ctx->stream));
-    if (dst.fp)
-        HIP_TRY(ctx, hipMemcpyAsync(dst.resf.blk->ptr, resf.data(), resf.size() * sizeof(double), hipMemcpyHostToDevice,
-                                    ctx->stream));
-    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-    return HISA_OK;
-}
-
 extern "C" int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* w_int, double w_scale,
                                  const int64_t* pt_coeffs, double pt_scale, uint32_t OC, const hisa_conv_geom* geom,
                                  hisa_tensor* out) {
@@ -531,28 +692,33 @@ extern "C" int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int
         Temp pts(ctx, T * OC * l * n * sizeof(u64));
         if (!pts.ok()) return HISA_ERR_OOM;
         TRY(coeffs_to_plain_batch(ctx, pt_coeffs, T * OC, (int)l, pts.u()));
-        return conv_run(ctx, in, geom, plan, OC, nullptr, nullptr, 1.0, pts.u(), pt_scale, out);
+        return conv_run(ctx, in, geom, plan, OC, nullptr, 1.0, pts.u(), pt_scale, out);
     }
     if (!w_int) return fail(ctx, HISA_ERR_ARG, "null weights");
-    DevWeights dw(ctx, T * OC, l);
+    DevWeights dw(ctx, T, OC, l);
     if (!dw.ok()) return HISA_ERR_OOM;
-    TRY(upload_weight_residues(ctx, w_int, T * OC, l, dw));
+    TRY(upload_weight_residues(ctx, w_int, l, dw));
     if (geom->mode == HISA_CONV_MASKED) {
         if (!pt_coeffs) return fail(ctx, HISA_ERR_ARG, "MASKED mode needs the mask plaintext");
         Temp mask(ctx, (size_t)l * n * sizeof(u64));
         if (!mask.ok()) return HISA_ERR_OOM;
         TRY(coeffs_to_plain_batch(ctx, pt_coeffs, 1, (int)l, mask.u()));
-        return conv_run(ctx, in, geom, plan, OC, dw.res.u(), dw.f(), w_scale, mask.u(), pt_scale, out);
+        return conv_run(ctx, in, geom, plan, OC, &dw, w_scale, mask.u(), pt_scale, out);
     }
-    return conv_run(ctx, in, geom, plan, OC, dw.res.u(), dw.f(), w_scale, nullptr, 1.0, out);
+    return conv_run(ctx, in, geom, plan, OC, &dw, w_scale, nullptr, 1.0, out);
 }
 
-extern "C" int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t OC, const hisa_conv_geom* geom,
-                           hisa_tensor* out) {
-    TRY(check_tensor(ctx, in));
-    if (!w || !out || !out->cts || OC == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
-    ConvPlan plan;
-    TRY(conv_plan(ctx, in, geom, &plan));
+// Everything a convolution needs besides its input: weights in the forms the kernels read, the mask or the per-tap
+// plaintexts, and the scales.  Built from float weights per call by hisa_conv2d, or once by hisa_conv2d_prepare.
+struct ConvWeights {
+    DevWeights* dw = nullptr;   // SCALAR / MASKED
+    Temp* pts = nullptr;        // MASKED: the mask [l][N]; PLAIN: [T][OC][l][N]
+    double w_scale = 1.0, pt_scale = 1.0;
+    ~ConvWeights() { delete dw; delete pts; }
+};
+
+static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t OC, const hisa_conv_geom* geom,
+                      const ConvPlan& plan, ConvWeights& cw) {
     const uint32_t l = in->cts[0]->limbs, IC = in->channels;
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
     const size_t taps = plan.steps.size(), T = taps * IC, n = ctx->N;
@@ -561,31 +727,91 @@ extern "C" int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w
                                                      in->w_stride * geom->stride, in->offset);
     if (geom->mode == HISA_CONV_PLAIN) {
         // plaintext (tap, ic, oc) = weight on every valid output position, zero elsewhere, at scale q_last
-        Temp pts(ctx, T * OC * l * n * sizeof(u64));
-        if (!pts.ok()) return HISA_ERR_OOM;
+        cw.pts = new Temp(ctx, T * OC * l * n * sizeof(u64));
+        if (!cw.pts->ok()) return HISA_ERR_OOM;
         std::vector<double> vals(T * OC * vslots.size());
         for (size_t i = 0; i < T * OC; i++) std::fill_n(vals.begin() + i * vslots.size(), vslots.size(), w[i]);
-        TRY(encode_sparse_batch(ctx, vslots, vals.data(), T * OC, q_last, (int)l, pts.u()));
-        return conv_run(ctx, in, geom, plan, OC, nullptr, nullptr, 1.0, pts.u(), q_last, out);
+        TRY(encode_sparse_batch(ctx, vslots, vals.data(), T * OC, q_last, (int)l, cw.pts->u()));
+        cw.pt_scale = q_last;
+        return HISA_OK;
     }
-    const double w_scale = geom->mode == HISA_CONV_MASKED ? q_last / HISA_MASK_SCALE : q_last;
+    cw.w_scale = geom->mode == HISA_CONV_MASKED ? q_last / HISA_MASK_SCALE : q_last;
     std::vector<int64_t> w_int(T * OC);
     for (size_t i = 0; i < T * OC; i++) {
-        const double v = w[i] * w_scale;
+        const double v = w[i] * cw.w_scale;
         if (!(fabs(v) < 9.2e18)) return fail(ctx, HISA_ERR_ARG, "weight %g does not fit the fixed-point range", w[i]);
         w_int[i] = (int64_t)round(v);
     }
-    DevWeights dw(ctx, T * OC, l);
-    if (!dw.ok()) return HISA_ERR_OOM;
-    TRY(upload_weight_residues(ctx, w_int.data(), T * OC, l, dw));
+    cw.dw = new DevWeights(ctx, T, OC, l);
+    if (!cw.dw->ok()) return HISA_ERR_OOM;
+    TRY(upload_weight_residues(ctx, w_int.data(), l, *cw.dw));
     if (geom->mode == HISA_CONV_MASKED) {
-        Temp mask(ctx, (size_t)l * n * sizeof(u64));
-        if (!mask.ok()) return HISA_ERR_OOM;
+        cw.pts = new Temp(ctx, (size_t)l * n * sizeof(u64));
+        if (!cw.pts->ok()) return HISA_ERR_OOM;
         std::vector<double> ones(vslots.size(), 1.0);
-        TRY(encode_sparse_batch(ctx, vslots, ones.data(), 1, HISA_MASK_SCALE, (int)l, mask.u()));
-        return conv_run(ctx, in, geom, plan, OC, dw.res.u(), dw.f(), w_scale, mask.u(), HISA_MASK_SCALE, out);
+        TRY(encode_sparse_batch(ctx, vslots, ones.data(), 1, HISA_MASK_SCALE, (int)l, cw.pts->u()));
+        cw.pt_scale = HISA_MASK_SCALE;
     }
-    return conv_run(ctx, in, geom, plan, OC, dw.res.u(), dw.f(), w_scale, nullptr, 1.0, out);
+    return HISA_OK;
+}
+
+extern "C" int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t OC, const hisa_conv_geom* geom,
+                           hisa_tensor* out) {
+    TRY(check_tensor(ctx, in));
+    if (!w || !out || !out->cts || OC == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    ConvPlan plan;
+    TRY(conv_plan(ctx, in, geom, &plan));
+    ConvWeights cw;
+    TRY(conv_build(ctx, in, w, OC, geom, plan, cw));
+    return conv_run(ctx, in, geom, plan, OC, cw.dw, cw.w_scale, cw.pts ? cw.pts->u() : nullptr, cw.pt_scale, out);
+}
+
+// A convolution whose weights were converted ahead of time for one input layout and level.
+#define HISA_MAGIC_CONVPLAN 0x43565031u
+struct hisa_conv_plan {
+    uint32_t magic;
+    hisa_conv_geom geom;
+    uint32_t out_channels, channels, height, width, h_stride, w_stride, offset, clean, limbs;
+    ConvWeights cw;
+};
+
+extern "C" int hisa_conv2d_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t OC,
+                                   const hisa_conv_geom* geom, hisa_conv_plan** plan_out) {
+    if (!ctx || !plan_out || !w || OC == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_tensor(ctx, like));
+    ConvPlan plan;
+    TRY(conv_plan(ctx, like, geom, &plan));
+    hisa_conv_plan* p = new hisa_conv_plan{HISA_MAGIC_CONVPLAN, *geom, OC, like->channels, like->height, like->width,
+                                           like->h_stride, like->w_stride, like->offset, like->clean, like->cts[0]->limbs, {}};
+    const int rc = conv_build(ctx, like, w, OC, geom, plan, p->cw);
+    if (rc != HISA_OK) { delete p; return rc; }
+    *plan_out = p;
+    return HISA_OK;
+}
+
+extern "C" int hisa_conv_plan_free(hisa_ctx* ctx, hisa_conv_plan* plan) {
+    if (!ctx || !plan || plan->magic != HISA_MAGIC_CONVPLAN) return fail(ctx, HISA_ERR_ARG, "not a convolution plan");
+    plan->magic = 0;
+    delete plan;
+    return HISA_OK;
+}
+
+extern "C" int hisa_conv2d_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_plan* plan, hisa_tensor* out) {
+    if (!ctx || !plan || plan->magic != HISA_MAGIC_CONVPLAN) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
+    if (in->channels != plan->channels || in->height != plan->height || in->width != plan->width ||
+        in->h_stride != plan->h_stride || in->w_stride != plan->w_stride || in->offset != plan->offset ||
+        in->clean != plan->clean)
+        return fail(ctx, HISA_ERR_ARG, "the plan was prepared for another tensor layout");
+    if (in->cts[0]->limbs != plan->limbs)
+        return fail(ctx, HISA_ERR_LEVEL_MISMATCH, "the plan was prepared for %u limbs, the tensor has %u", plan->limbs,
+                    in->cts[0]->limbs);
+    ConvPlan cp;
+    TRY(conv_plan(ctx, in, &plan->geom, &cp));
+    const ConvWeights& cw = plan->cw;
+    return conv_run(ctx, in, &plan->geom, cp, plan->out_channels, cw.dw, cw.w_scale, cw.pts ? cw.pts->u() : nullptr,
+                    cw.pt_scale, out);
 }
 
 // ---------------------------------------------------------------------------

@@ -399,6 +399,24 @@ class Context:
         g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode)
         return self._layer("hisa_conv2d", t, t.batch * oc, _dp(w), C.c_uint32(oc), C.byref(g))
 
+    def conv2d_prepare(self, like, w, fh, fw, stride=1, pad_same=False, mode=CONV_SCALAR):
+        """Converts conv weights once for tensors laid out like `like`; returns a plan for conv2d_apply (free with
+        conv_plan_free)."""
+        w = np.ascontiguousarray(w, dtype=np.float64)
+        assert w.shape[:3] == (fh, fw, like.channels)
+        oc = w.shape[3]
+        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode)
+        st, _arr = like._struct()
+        plan = C.c_void_p()
+        self._ck(load().hisa_conv2d_prepare(self._vp, C.byref(st), _dp(w), C.c_uint32(oc), C.byref(g), C.byref(plan)))
+        return (plan, oc)
+
+    def conv2d_apply(self, t, plan):
+        return self._layer("hisa_conv2d_apply", t, t.batch * plan[1], plan[0])
+
+    def conv_plan_free(self, plan):
+        self._ck(load().hisa_conv_plan_free(self._vp, plan[0]))
+
     def conv2d_fixed(self, t, w_int, w_scale, pt_coeffs, pt_scale, oc, fh, fw, stride=1, pad_same=False, mode=CONV_SCALAR):
         i64p = C.POINTER(C.c_int64)
         wi = np.ascontiguousarray(w_int, dtype=np.int64) if w_int is not None else None

@@ -92,8 +92,8 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
     """Encrypts x, runs the layers, decrypts.  Returns (output array, seconds from encrypt-done to the last
     ciphertext ready, per-layer seconds).  With make_keys the rotation keys each layer asks for are generated
     on the way (set-up pass); otherwise they must be resident.  `plans` (a dict, filled by the set-up pass and
-    reused afterwards) holds the fully connected layers' weights encoded ahead of time; without it they are
-    encoded inside the call."""
+    reused afterwards) holds the layers' weights converted and encoded ahead of time; without it that is done
+    inside every call."""
     if border:   # leave `border` rows and columns of zero slots around every plane (SAME convolutions need them)
         hs = x.shape[3] + 2 * border
         t = ctx.tensor_encrypt(x, scale, limbs, h_stride=hs, offset=border * hs + border)
@@ -107,8 +107,15 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
         if plans is None or t.height * t.width == 1:
             return ctx.fc(t, w)
         if idx not in plans:
-            plans[idx] = ctx.fc_prepare(t, w)
-        return ctx.fc_apply(t, plans[idx])
+            plans[idx] = ("fc", ctx.fc_prepare(t, w))
+        return ctx.fc_apply(t, plans[idx][1])
+
+    def convolution(key, t, w, fh, fw, **kw):
+        if plans is None:
+            return ctx.conv2d(t, w, fh, fw, **kw)
+        if key not in plans:
+            plans[key] = ("conv", ctx.conv2d_prepare(t, w, fh, fw, **kw))
+        return ctx.conv2d_apply(t, plans[key][1])
 
     for idx, layer in enumerate(layers):
         t0 = time.perf_counter()
@@ -119,7 +126,7 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             fh, fw = w.shape[:2]
             if make_keys:
                 ctx.gen_rot_keys(ctx.conv2d_rot_steps(t, fh, fw, stride=stride))
-            nxt = ctx.conv2d(t, w, fh, fw, stride=stride)
+            nxt = convolution(idx, t, w, fh, fw, stride=stride)
         elif kind == "act":
             a, b = layer[1], layer[2]
             nxt = ctx.poly2_act(t, a, b)
@@ -135,17 +142,17 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             fh, fw = w.shape[:2]
             if make_keys:
                 ctx.gen_rot_keys(ctx.conv2d_rot_steps(t, fh, fw, pad_same=True))
-            nxt = ctx.conv2d(t, w, fh, fw, pad_same=True, mode=1)
+            nxt = convolution(idx, t, w, fh, fw, pad_same=True, mode=1)
         elif kind == "fire":
             ws, w1, w3, a, b = layer[1] * pending, layer[2], layer[3], layer[4], layer[5]
             pending = 1.0
-            s0 = ctx.conv2d(t, ws, 1, 1)
+            s0 = convolution((idx, "squeeze"), t, ws, 1, 1)
             s1 = ctx.poly2_act(s0, a, b)
             s0.free()
             if make_keys:
                 ctx.gen_rot_keys(ctx.conv2d_rot_steps(s1, 3, 3, pad_same=True))
-            e1 = ctx.conv2d(s1, w1 * a, 1, 1)
-            e3 = ctx.conv2d(s1, w3 * a, 3, 3, pad_same=True, mode=1)
+            e1 = convolution((idx, "expand1"), s1, w1 * a, 1, 1)
+            e3 = convolution((idx, "expand3"), s1, w3 * a, 3, 3, pad_same=True, mode=1)
             s1.free()
             nxt = _concat_channels(ctx, e1, e3)
         elif kind == "gap":
@@ -176,6 +183,9 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
 
 
 def free_plans(ctx, plans):
-    for plan in plans.values():
-        ctx.fc_plan_free(plan)
+    for kind, plan in plans.values():
+        if kind == "fc":
+            ctx.fc_plan_free(plan)
+        else:
+            ctx.conv_plan_free(plan)
     plans.clear()

@@ -96,6 +96,43 @@ def test_multichannel_same_strided_masked_conv():
     g.close()
 
 
+def test_long_contraction_conv_bit_exact():
+    """A convolution whose sum over (tap, input channel) is long enough for the matrix-core multiply-accumulate
+    (36 and 72 terms, ragged against its 64-wide tiles; 5 and 3 outputs against its 64-output blocks), compared bit
+    for bit with the oracle, unmasked and masked, at two levels."""
+    from oracle import layers
+    from paper_1810_00845_amd import synth
+    g, o = make_pair(11, [50, 45, 45, 45], 2, 50, 8)
+    x = synth.image(5, 4, 6, 6)[None]
+    gt, ot = both_tensors(g, o, x, 2.0 ** 40, 4, h_stride=8, offset=9)
+    steps = sorted(set(g.conv2d_rot_steps(gt, 3, 3, pad_same=True)) | set(g.conv2d_rot_steps(gt, 3, 3)))
+    g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+    w = synth.conv_weights(6, 3, 3, 4, 5)                       # K = 36
+    oout, ints = layers.conv2d(o, ot, w, mode=layers.CONV_SCALAR)
+    gout = g.conv2d_fixed(gt, ints["w_int"], ints["w_scale"], None, 1.0, 5, 3, 3, mode=layers.CONV_SCALAR)
+    same_tensor(g, o, gout, oout)
+    assert np.abs(g.tensor_decrypt(gout) - plain_net.conv2d(x, w)).max() <= 1e-3
+    plan = g.conv2d_prepare(gt, w, 3, 3)                        # weights converted ahead of time: the same bits
+    ga, gb = g.conv2d(gt, w, 3, 3), g.conv2d_apply(gt, plan)
+    for ca, cb in zip(ga.cts, gb.cts):
+        assert np.array_equal(g.ct_export(ca), g.ct_export(cb)) and ca.scale == cb.scale
+    assert ga.meta() == gb.meta()
+    g.conv_plan_free(plan)
+    w2 = synth.conv_weights(7, 3, 3, 4, 8)                      # masked SAME convolution, 8 outputs
+    omid, ints = layers.conv2d(o, ot, w2, pad_same=True, mode=layers.CONV_MASKED)
+    gmid = g.conv2d_fixed(gt, ints["w_int"], ints["w_scale"], ints["pt_coeffs"], ints["pt_scale"], 8, 3, 3, pad_same=True,
+                          mode=layers.CONV_MASKED)
+    same_tensor(g, o, gmid, omid)
+    w3 = synth.conv_weights(8, 3, 3, 8, 3)                      # K = 72 on the masked result, one level down
+    o3, ints = layers.conv2d(o, omid, w3, pad_same=True, mode=layers.CONV_MASKED)
+    g3 = g.conv2d_fixed(gmid, ints["w_int"], ints["w_scale"], ints["pt_coeffs"], ints["pt_scale"], 3, 3, 3, pad_same=True,
+                        mode=layers.CONV_MASKED)
+    same_tensor(g, o, g3, o3)
+    want = plain_net.conv2d(plain_net.conv2d(x, w2, pad_same=True), w3, pad_same=True)
+    assert np.abs(g.tensor_decrypt(g3) - want).max() <= 1e-3
+    g.close()
+
+
 def test_activation_pool_fc_chain_bit_exact():
     from oracle import layers
     from paper_1810_00845_amd import hisa, synth
