@@ -145,9 +145,11 @@ __global__ __launch_bounds__(NT) void plain_mac_kernel(const PrimeConst* primes,
 }
 
 // The same sum on the matrix cores.  Over k = (tap, channel) it is a dense contraction out[oc][e] = sum_k W[k][oc] X[k][e]
-// of integers below 2^50 in magnitude.  Both factors are split into seven signed base-256 digits; the 49 digit-by-digit
-// products are int8 MFMAs accumulating exactly in int32, summed per diagonal a + b = s (13 accumulators per output);
-// the value sum_s D_s 256^s is then reduced modulo p in fp64.  Exact, so bit-identical to the other two kernels.
+// of integers below 2^50 in magnitude.  Both factors are split into signed base-256 digits (DA for the weights: three
+// for masked convolutions, whose fixed-point weights are about 20 bits, up to seven; DB = 6 or 7 for the residues,
+// by the size of the largest prime); the DA x DB digit-by-digit products are int8 MFMAs accumulating exactly in
+// int32, summed per diagonal a + b = s; the value sum_s D_s 256^s is then reduced modulo p in fp64.  Exact, so
+// bit-identical to the other two kernels.
 //   block: 4 waves; 64 coefficients x 64 outputs; wave w owns outputs 16 w .. 16 w + 15 (rows of the MFMA tile) and
 //   four 16-coefficient column tiles; k advances 64 at a time (one 16x16x64 MFMA per digit pair and column tile).
 //   The digits of X are staged in LDS as [digit][k / 16][e][k % 16]: a thread converts 16 consecutive k of one
@@ -159,8 +161,7 @@ __global__ __launch_bounds__(NT) void plain_mac_kernel(const PrimeConst* primes,
 #define MT_E 64
 #define MT_OC 64
 #define MT_K 64
-#define MAC_DIGITS 7
-#define MAC_DIAGS (2 * MAC_DIGITS - 1)
+#define MAC_DIGITS 7   // most digits of either factor
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 
 // the seven signed base-256 digits of x (|x| < 2^55) in the low seven bytes: (x + B) ^ B with B = 0x80 in each of them
@@ -169,9 +170,11 @@ __host__ __device__ __forceinline__ u64 balanced_digits(u64 x) {
     return (x + B) ^ B;
 }
 
+template <int DA, int DB>
 __global__ __launch_bounds__(256) void scalar_mac_mfma_kernel(const FpPrime* fprimes, MacArgs g, const int8_t* wd, int K,
                                                               int K_pad, int OC_pad, const double* c3, int log_n) {
-    __shared__ v4i_t xd[MAC_DIGITS][MT_K / 16][MT_E];
+    constexpr int MAC_DIAGS = DA + DB - 1;
+    __shared__ v4i_t xd[DB][MT_K / 16][MT_E];
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const u64 n = (u64)1 << log_n;
@@ -198,12 +201,20 @@ __global__ __launch_bounds__(256) void scalar_mac_mfma_kernel(const FpPrime* fpr
             if (++ic == g.IC) { ic = 0; tap++; }
         }
     };
+    // the wave's weight digits of the next 64 k (lane: row lane % 16, k group lane / 16), fetched one step ahead as well
+    v4i_t A[DA], An[DA];
+    auto load_a = [&](int kc, v4i_t (&dst)[DA]) {
+#pragma unroll
+        for (int a = 0; a < DA; a++)
+            dst[a] = *(const v4i_t*)(wd + (((u64)(limb * MAC_DIGITS + a) * OC_pad + oc0 + (lane & 15)) * K_pad + kc + 16 * (lane >> 4)));
+    };
     load_x(0);
+    load_a(0, An);
     for (int kc = 0; kc < K_pad; kc += MT_K) {
 #pragma unroll
         for (int sl = 0; sl < 16; sl++) xs[sl] = balanced_digits(xs[sl]);
 #pragma unroll
-        for (int a = 0; a < MAC_DIGITS; a++) {
+        for (int a = 0; a < DB; a++) {
             v4i_t d;
 #pragma unroll
             for (int q = 0; q < 4; q++) {
@@ -215,20 +226,18 @@ __global__ __launch_bounds__(256) void scalar_mac_mfma_kernel(const FpPrime* fpr
             xd[a][wave][lane] = d;
         }
         __syncthreads();
-        if (kc + MT_K < K_pad) load_x(kc + MT_K);
-        v4i_t A[MAC_DIGITS];
 #pragma unroll
-        for (int a = 0; a < MAC_DIGITS; a++)
-            A[a] = *(const v4i_t*)(wd + (((u64)(limb * MAC_DIGITS + a) * OC_pad + oc0 + (lane & 15)) * K_pad + kc + 16 * (lane >> 4)));
+        for (int a = 0; a < DA; a++) A[a] = An[a];
+        if (kc + MT_K < K_pad) { load_x(kc + MT_K); load_a(kc + MT_K, An); }
 #pragma unroll
         for (int ct = 0; ct < 4; ct++) {
-            v4i_t Bv[MAC_DIGITS];
+            v4i_t Bv[DB];
 #pragma unroll
-            for (int bb = 0; bb < MAC_DIGITS; bb++) Bv[bb] = xd[bb][lane >> 4][ct * 16 + (lane & 15)];
+            for (int bb = 0; bb < DB; bb++) Bv[bb] = xd[bb][lane >> 4][ct * 16 + (lane & 15)];
 #pragma unroll
-            for (int a = 0; a < MAC_DIGITS; a++)
+            for (int a = 0; a < DA; a++)
 #pragma unroll
-                for (int bb = 0; bb < MAC_DIGITS; bb++)
+                for (int bb = 0; bb < DB; bb++)
                     acc[ct][a + bb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[a], Bv[bb], acc[ct][a + bb], 0, 0, 0);
         }
         __syncthreads();
@@ -246,7 +255,7 @@ __global__ __launch_bounds__(256) void scalar_mac_mfma_kernel(const FpPrime* fpr
             const int oc = oc0 + 4 * (lane >> 4) + r;
             double sum = 0.0;
 #pragma unroll
-            for (int gq = 0; gq < 5; gq++) {
+            for (int gq = 0; 3 * gq < MAC_DIAGS; gq++) {
                 double G = (double)acc[ct][3 * gq][r];
                 if (3 * gq + 1 < MAC_DIAGS) G = __builtin_fma((double)acc[ct][3 * gq + 1][r], 256.0, G);
                 if (3 * gq + 2 < MAC_DIAGS) G = __builtin_fma((double)acc[ct][3 * gq + 2][r], 65536.0, G);
@@ -338,15 +347,27 @@ static hipError_t launch_scalar_mac_fp(const FpPrime* fprimes, const MacArgs& g,
     return hipGetLastError();
 }
 
+template <int DA, int DB>
+static hipError_t launch_mfma_one(const FpPrime* fprimes, const MacArgs& g, const int8_t* wd, int K, int K_pad, int OC_pad,
+                                  const double* c3, dim3 grid, int log_n, hipStream_t st) {
+    hipLaunchKernelGGL((scalar_mac_mfma_kernel<DA, DB>), grid, dim3(256), 0, st, fprimes, g, wd, K, K_pad, OC_pad, c3, log_n);
+    return hipGetLastError();
+}
+
+// da: digits the weights need (1..7); db: digits the residues need (6: every prime below 2^46, else 7)
 static hipError_t launch_scalar_mac_mfma(const FpPrime* fprimes, const MacArgs& g, const int8_t* wd, int K, int K_pad, int OC_pad,
-                                         const double* c3, int batch, int log_n, hipStream_t st) {
+                                         const double* c3, int da, int db, int batch, int log_n, hipStream_t st) {
     if (!fprimes || !wd || !c3 || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || K != g.n_taps * g.IC || K_pad % MT_K ||
-        K_pad < K || OC_pad % MT_OC || OC_pad < g.OC || log_n < 6)
+        K_pad < K || OC_pad % MT_OC || OC_pad < g.OC || log_n < 6 || da < 1 || da > MAC_DIGITS || (db != 6 && db != 7))
         return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / MT_E, 2 * g.l, batch * (OC_pad / MT_OC));
     ProfScope prof__("scalar_mac_mfma_kernel", st);
-    hipLaunchKernelGGL(scalar_mac_mfma_kernel, grid, dim3(256), 0, st, fprimes, g, wd, K, K_pad, OC_pad, c3, log_n);
-    return hipGetLastError();
+    if (da < 3) da = 3;
+#define MFMA_CASE(A_, B_) if (da == A_ && db == B_) return launch_mfma_one<A_, B_>(fprimes, g, wd, K, K_pad, OC_pad, c3, grid, log_n, st)
+    MFMA_CASE(3, 6); MFMA_CASE(4, 6); MFMA_CASE(5, 6); MFMA_CASE(6, 6); MFMA_CASE(7, 6);
+    MFMA_CASE(3, 7); MFMA_CASE(4, 7); MFMA_CASE(5, 7); MFMA_CASE(6, 7); MFMA_CASE(7, 7);
+#undef MFMA_CASE
+    return hipErrorInvalidValue;
 }
 
 static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
@@ -554,6 +575,7 @@ static int conv_plan(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom*
 #define MFMA_MAX_K 16384   // 7 K 2^14 must stay below 2^31
 struct DevWeights {
     size_t K, OC, K_pad, OC_pad;
+    int da = MAC_DIGITS;   // signed base-256 digits the largest weight needs
     bool fp, mfma;
     Temp res, resf, digits, c3;
     DevWeights(hisa_ctx* ctx, size_t K_, size_t OC_, uint32_t l)
@@ -569,6 +591,7 @@ static int upload_weight_residues(hisa_ctx* ctx, const int64_t* w_int, uint32_t 
     std::vector<u64> res(count * l);
     std::vector<double> resf(dst.fp ? count * l : 0), c3(dst.mfma ? (size_t)l * 5 : 0);
     std::vector<int8_t> dig(dst.mfma ? (size_t)l * MAC_DIGITS * dst.OC_pad * dst.K_pad : 0, 0);
+    u64 used = 0;   // OR of all digit words: its highest non-zero byte is the last digit in use
     for (uint32_t k = 0; k < l; k++) {
         const u64 q = ctx->mod[k];
         for (size_t oc = 0; oc < dst.OC; oc++) {       // digit rows are contiguous in the contraction index
@@ -583,6 +606,7 @@ static int upload_weight_residues(hisa_ctx* ctx, const int64_t* w_int, uint32_t 
                 resf[(size_t)k * count + i] = (double)c;   // [l][K][OC]
                 if (!dst.mfma) continue;
                 const u64 d = balanced_digits((u64)c);
+                used |= d;
                 int8_t* row = dig.data() + ((size_t)k * MAC_DIGITS * dst.OC_pad + oc) * dst.K_pad + kk;
                 for (int a = 0; a < MAC_DIGITS; a++) row[(size_t)a * dst.OC_pad * dst.K_pad] = (int8_t)(uint8_t)(d >> (8 * a));
             }
@@ -595,6 +619,9 @@ static int upload_weight_residues(hisa_ctx* ctx, const int64_t* w_int, uint32_t 
             }
         }
     }
+    dst.da = 1;
+    for (int a = 1; a < MAC_DIGITS; a++)
+        if ((used >> (8 * a)) & 0xFF) dst.da = a + 1;
     HIP_TRY(ctx, hipMemcpyAsync(dst.res.blk->ptr, res.data(), res.size() * sizeof(u64), hipMemcpyHostToDevice, ctx->stream));
     if (dst.fp)
         HIP_TRY(ctx, hipMemcpyAsync(dst.resf.blk->ptr, resf.data(), resf.size() * sizeof(double), hipMemcpyHostToDevice,
@@ -649,9 +676,13 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
             else e = launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
         } else {
             ma.w = dw->res.u();
-            if (dw->mfma)
+            if (dw->mfma) {
+                u64 qmax = 0;
+                for (uint32_t k = 0; k < l; k++) qmax = std::max(qmax, ctx->mod[k]);
+                const int db = qmax < ((u64)1 << 46) ? 6 : 7;   // six balanced digits reach 0.498 * 2^48 (just under 2^47)
                 e = launch_scalar_mac_mfma(ctx->tabs.fprimes, ma, (const int8_t*)dw->digits.blk->ptr, (int)dw->K, (int)dw->K_pad,
-                                           (int)dw->OC_pad, dw->c3.as<double>(), (int)B, (int)ctx->log_n, ctx->stream);
+                                           (int)dw->OC_pad, dw->c3.as<double>(), dw->da, db, (int)B, (int)ctx->log_n, ctx->stream);
+            }
             else if (dw->fp)
                 e = launch_scalar_mac_fp(ctx->tabs.fprimes, ma, dw->resf.as<double>(), (int)B, (int)ctx->log_n, ctx->stream);
             else e = launch_scalar_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
