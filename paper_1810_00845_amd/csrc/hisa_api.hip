@@ -451,6 +451,8 @@ extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** 
             std::vector<double> pf(ctx->total, 0.0);
             for (uint32_t i = 0; i < ctx->L; i++) pf[i] = centred_double(pinv[i], ctx->mod[i]);
             HIP_TRY(ctx, upload(&ctx->d_pinv_f, pf));
+            ctx->fp_scratch_polys = ctx->log_n <= 13 ? 1024 : 512;
+            HIP_TRY(ctx, hipMalloc(&ctx->d_fp_scratch, (size_t)ctx->fp_scratch_polys * ctx->N * sizeof(double)));
         }
     }
     // 2N-th roots of unity for encode / decode
@@ -488,6 +490,7 @@ extern "C" int hisa_destroy(hisa_ctx* ctx) {
     (void)hipFree(ctx->d_itw_sh); (void)hipFree(ctx->d_secret); (void)hipFree(ctx->d_pinv); (void)hipFree(ctx->d_pinv_sh);
     (void)hipFree(ctx->d_fprimes); (void)hipFree(ctx->d_ftw); (void)hipFree(ctx->d_utw); (void)hipFree(ctx->d_vtw);
     (void)hipFree(ctx->d_pinv_f);
+    (void)hipFree(ctx->d_fp_scratch);
     (void)hipFree(ctx->d_pmod); (void)hipFree(ctx->d_cos); (void)hipFree(ctx->d_sin); (void)hipFree(ctx->d_pow5);
     delete ctx;
     return HISA_OK;
@@ -1160,6 +1163,7 @@ struct FpExt {
 static FpArgs fp_base(hisa_ctx* ctx) {
     FpArgs base = {};
     base.fprimes = ctx->tabs.fprimes; base.ftw = ctx->tabs.ftw; base.utw = ctx->tabs.utw; base.vtw = ctx->tabs.vtw;
+    base.scratch = ctx->d_fp_scratch; base.scratch_polys = ctx->fp_scratch_polys;
     return base;
 }
 
@@ -1448,8 +1452,7 @@ static int rescale_core_fp(hisa_ctx* ctx, const u64* in, size_t n_bp, int l, u64
     if (!y.ok()) return HISA_ERR_OOM;
     double *ones, *qlinv;
     TRY(fp_rescale_tables(ctx, l, &ones, &qlinv));
-    FpArgs base = {};
-    base.fprimes = ctx->tabs.fprimes; base.ftw = ctx->tabs.ftw; base.utw = ctx->tabs.utw; base.vtw = ctx->tabs.vtw;
+    const FpArgs base = fp_base(ctx);
     {
         FpArgs a = base;
         FpTask tk = {};

@@ -126,6 +126,8 @@ struct hisa_ctx {
     FpPrime* d_fprimes;     // fp64 path tables (null when not applicable)
     double *d_ftw, *d_utw, *d_vtw, *d_pinv_f;
     uint32_t* d_pow5;       // [N/2] 5^j mod 2N
+    double* d_fp_scratch;   // fp64 path: one polynomial per resident workgroup of the conversion kernels
+    int fp_scratch_polys;
     std::unordered_map<size_t, std::vector<void*>> pool;
     size_t pool_bytes;
     u64 enc_counter;
@@ -234,6 +236,7 @@ struct FpArgs {
     const double* y; u64 y_bs;         // [batch][..][N] centred doubles, source limbs at y_pos0 ..
     int y_pos0, conv_a, total;
     const double* hat;                 // [a][total] (D/c_i) mod t, centred
+    double* scratch; int scratch_polys; // one polynomial of doubles per workgroup (at most scratch_polys workgroups)
     // final combine (FP_FWD_CONV_FINAL): batch entries are (ciphertext, polynomial) pairs
     const u64* acc; u64 acc_bs; int acc_pos_shift;
     const double* pinv_tab;            // [prime] P^-1 mod q, centred

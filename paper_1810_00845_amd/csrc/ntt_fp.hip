@@ -73,6 +73,11 @@ __device__ __forceinline__ u64 bload(rsrc_t r, uint32_t lane_off, uint32_t row_o
     const u32x2_t d = __builtin_amdgcn_raw_buffer_load_b64(r, (int)lane_off, (int)row_off, 0);
     return ((u64)d.y << 32) | d.x;
 }
+// the same, bypassing the CU's L1 (data that another point in time of this workgroup wrote)
+__device__ __forceinline__ u64 bload_glc(rsrc_t r, uint32_t lane_off, uint32_t row_off) {
+    const u32x2_t d = __builtin_amdgcn_raw_buffer_load_b64(r, (int)lane_off, (int)row_off, 1);
+    return ((u64)d.y << 32) | d.x;
+}
 __device__ __forceinline__ double bloadf(rsrc_t r, uint32_t lane_off, uint32_t row_off) {
     return __longlong_as_double((long long)bload(r, lane_off, row_off));
 }
@@ -263,12 +268,22 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
     const int per_xcd = (a.n_tasks + 7) >> 3;
     const int task_end = min((xcd + 1) * per_xcd, a.n_tasks);
+    constexpr bool INV = (MODE == FP_INV_PLAIN || MODE == FP_INV_TO_Y);
+    // The base-conversion modes take the target limbs of a batch entry two at a time: both read the same source
+    // digits, so one pass over them forms both sums (half the loads per sum; the loads, not the arithmetic, bound that
+    // stage).  The second sum waits in this workgroup's scratch rows (every thread reads back what it wrote itself)
+    // while the first is transformed, and is transformed next.
+    constexpr bool CONV = (MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL);
+    constexpr int SUB = CONV ? 2 : 1;
+    const int per_entry = (tk.period + SUB - 1) / SUB;
     for (int task = xcd * per_xcd + slot; task < task_end; task += slots) {
-    const int e = task % tk.period;
-    const u64 b = task / tk.period;
+    const u64 b = task / per_entry;
+    const int e_first = (task % per_entry) * SUB;
+    for (int half = 0; half < SUB; half++) {
+    const int e = e_first + half;
+    if (e >= tk.period) break;
     const int pos = tk.pos[e], prime = tk.prime[e];
     const double p = as_const(&a.fprimes[prime].p)[0], pinv = as_const(&a.fprimes[prime].p)[1];
-    constexpr bool INV = (MODE == FP_INV_PLAIN || MODE == FP_INV_TO_Y);
     // Global memory is touched in mapping 1 (lane <-> consecutive coefficients, register r a block of THREADS
     // further) on the side of the transform whose first/last phase works on the top bits, and in mapping 4 on the
     // other side, where the transposes stay inside a wave.
@@ -299,42 +314,98 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
             for (int r = 0; r < 32; r++) v[r] = fp_from_u64(bload(src, t8, (uint32_t)(r << G::TB) * 8u));
         }
     } else {
-        // fast base conversion: sum_i y_i * hat_i mod p, y_i centred source digits (already times (D/c_i)^-1).
-        // Loads are issued eight at a time, one batch ahead of the arithmetic (two explicit buffers; the fences keep
-        // the compiler from sinking each load to its use, which would expose one memory latency per element).
-        const rsrc_t y = make_rsrc(a.y + b * a.y_bs + (u64)a.y_pos0 * G::N, (uint32_t)a.conv_a * LB);
+        // fast base conversion: sum_i y_i * hat_i mod p, y_i centred source digits (already times (D/c_i)^-1), for
+        // this limb and (half 0) for its partner, eight rows at a time.  Loads are issued eight at a time, one batch
+        // ahead of the arithmetic (two explicit buffers; the fences keep the compiler from sinking each load to its
+        // use, which would expose one memory latency per element).
+        const rsrc_t scr = make_rsrc(a.scratch + (u64)blockIdx.x * G::N, LB);
+        if (half == 0) {
+            const rsrc_t y = make_rsrc(a.y + b * a.y_bs + (u64)a.y_pos0 * G::N, (uint32_t)a.conv_a * LB);
+            const bool two = e + 1 < tk.period;
+            const int prime2 = tk.prime[two ? e + 1 : e];
+            const double p2 = as_const(&a.fprimes[prime2].p)[0], pinv2 = as_const(&a.fprimes[prime2].p)[1];
+            double bufa[8], bufb[8];
+            double* park = (double*)(lds + G::lds_of((t >> 6) << 11)) + (t & 63);   // 16 doubles per lane, lane-interleaved
 #pragma unroll
-        for (int r = 0; r < 32; r++) v[r] = 0.0;
-        double bufa[8], bufb[8];
-#pragma unroll
-        for (int k = 0; k < 8; k++) bufa[k] = bloadf(y, t8, (uint32_t)(k << G::TB) * 8u);
-        for (int i = 0; i < a.conv_a; i++) {
-            const double h = as_const(a.hat)[(u64)i * a.total + prime];
-            const uint32_t yi = (uint32_t)i * LB;
-            const uint32_t yn = (i + 1 < a.conv_a) ? yi + LB : yi;  // next source limb (dummy reload on the last)
+            for (int k = 0; k < 8; k++) bufa[k] = bloadf(y, t8, (uint32_t)(k << G::TB) * 8u);
 #pragma unroll
             for (int c = 0; c < 4; c++) {
-                SCHED_FENCE();
-                if (c < 3) {
+                double w2[8];
 #pragma unroll
-                    for (int k = 0; k < 8; k++)
-                        ((c & 1) ? bufa : bufb)[k] = bloadf(y, t8, yi + (uint32_t)(((c + 1) * 8 + k) << G::TB) * 8u);
-                } else {
+                for (int k = 0; k < 8; k++) { v[c * 8 + k] = 0.0; w2[k] = 0.0; }
+                // rows 8c .. 8c+7 of source limbs i and i+1 per turn (bufa, then bufb); the batch after the last
+                // limb is the first one of the next eight rows
+                for (int i = 0; i < a.conv_a; i += 2) {
+                    const bool has1 = i + 1 < a.conv_a;
+                    SCHED_FENCE();
+                    {
+                        const uint32_t off = has1 ? (uint32_t)(i + 1) * LB + (uint32_t)((c * 8) << G::TB) * 8u
+                                                  : (uint32_t)(((c < 3 ? c + 1 : c) * 8) << G::TB) * 8u;
 #pragma unroll
-                    for (int k = 0; k < 8; k++) bufa[k] = bloadf(y, t8, yn + (uint32_t)(k << G::TB) * 8u);
+                        for (int k = 0; k < 8; k++) bufb[k] = bloadf(y, t8, off + (uint32_t)(k << G::TB) * 8u);
+                    }
+                    SCHED_FENCE();
+                    {
+                        const double h1 = as_const(a.hat)[(u64)i * a.total + prime], h2 = as_const(a.hat)[(u64)i * a.total + prime2];
+#pragma unroll
+                        for (int k = 0; k < 8; k++) {
+                            v[c * 8 + k] += fp_mulmod(bufa[k], h1, p, pinv);
+                            w2[k] += fp_mulmod(bufa[k], h2, p2, pinv2);
+                        }
+                    }
+                    SCHED_FENCE();
+                    {
+                        const bool more = i + 2 < a.conv_a;
+                        const uint32_t off = more ? (uint32_t)(i + 2) * LB + (uint32_t)((c * 8) << G::TB) * 8u
+                                                  : (uint32_t)(((c < 3 ? c + 1 : c) * 8) << G::TB) * 8u;
+                        if (has1) {   // otherwise bufb already holds the first batch of the next rows: hand it over below
+#pragma unroll
+                            for (int k = 0; k < 8; k++) bufa[k] = bloadf(y, t8, off + (uint32_t)(k << G::TB) * 8u);
+                        }
+                    }
+                    SCHED_FENCE();
+                    if (has1) {
+                        const double h1 = as_const(a.hat)[(u64)(i + 1) * a.total + prime],
+                                     h2 = as_const(a.hat)[(u64)(i + 1) * a.total + prime2];
+#pragma unroll
+                        for (int k = 0; k < 8; k++) {
+                            v[c * 8 + k] += fp_mulmod(bufb[k], h1, p, pinv);
+                            w2[k] += fp_mulmod(bufb[k], h2, p2, pinv2);
+                        }
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < 8; k++) bufa[k] = bufb[k];
+                    }
+                    if ((i & 6) == 6) {   // after every eight terms
+#pragma unroll
+                        for (int k = 0; k < 8; k++) { v[c * 8 + k] = fp_norm(v[c * 8 + k], p, pinv); w2[k] = fp_norm(w2[k], p2, pinv2); }
+                    }
                 }
-                SCHED_FENCE();
 #pragma unroll
-                for (int k = 0; k < 8; k++) v[c * 8 + k] += fp_mulmod(((c & 1) ? bufb : bufa)[k], h, p, pinv);
-            }
-            if ((i & 7) == 7) {
+                for (int k = 0; k < 8; k++) v[c * 8 + k] = fp_norm(v[c * 8 + k], p, pinv);
+                if (two) {
 #pragma unroll
-                for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
+                    for (int k = 0; k < 8; k++) bstoref(scr, t8, (uint32_t)((c * 8 + k) << G::TB) * 8u, fp_norm(w2[k], p2, pinv2));
+                }
+                // Rows 0..15 wait in this wave's own part of the transpose buffer while rows 16..31 are formed: with
+                // both sums, their buffers and all 32 rows live the stage would not fit the register file.  The part
+                // is free here: the wave is past its last transpose of the previous task, and the workgroup-wide
+                // transpose of this one starts behind a barrier that this wave has not reached yet.
+                if (c == 1) {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) park[r * 64] = v[r];
+                }
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+#pragma unroll
+            for (int r = 0; r < 16; r++) v[r] = park[r * 64];
+        } else {
+            // the partner's sum, left in the scratch rows by the step before (read past the L1: the lines may be
+            // there from an earlier task)
+#pragma unroll
+            for (int r = 0; r < 32; r++)
+                v[r] = __longlong_as_double((long long)bload_glc(scr, t8, (uint32_t)(r << G::TB) * 8u));
         }
-        SCHED_FENCE();
-#pragma unroll
-        for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
     }
 
     STAMP(1);
@@ -466,6 +537,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         }
     }
     STAMP(9);
+    }  // the one or two limbs of a task
     }  // task loop
 }
 
@@ -488,7 +560,8 @@ static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hip
         {"ntt_fp_kernel<5, 0>", "ntt_fp_kernel<5, 1>", "ntt_fp_kernel<5, 2>", "ntt_fp_kernel<5, 3>", "ntt_fp_kernel<5, 4>"}};
     ProfScope prof__(names[K3 - 2][MODE], st);
     FpArgs args = a;
-    args.n_tasks = (int)(n_batch * tk.period);
+    constexpr bool conv_mode = MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL;
+    args.n_tasks = (int)(n_batch * (conv_mode ? (tk.period + 1) / 2 : tk.period));
     static int n_cu = 0;
     if (!n_cu) {
         hipDeviceProp_t prop;
@@ -508,6 +581,11 @@ static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hip
     unsigned grid = (unsigned)(n_cu * per_cu) & ~7u;
     const unsigned need = (unsigned)((args.n_tasks + 7) / 8) * 8;
     if (grid > need) grid = need;
+    if (conv_mode) {   // one scratch polynomial per workgroup
+        const unsigned fit = (unsigned)(a.scratch_polys) & ~7u;
+        if (fit < 8) return hipErrorInvalidValue;
+        if (grid > fit) grid = fit;
+    }
 #ifdef NTT_FP_NONPERSISTENT
     grid = need;
 #endif
@@ -539,7 +617,7 @@ hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk,
     if (mode == FP_FWD_PLAIN && !a.in) return hipErrorInvalidValue;
     if (mode == FP_INV_TO_Y && (!a.yout || !a.post)) return hipErrorInvalidValue;
     if (mode != FP_INV_TO_Y && !a.out) return hipErrorInvalidValue;
-    if (conv && (!a.y || !a.hat || a.conv_a <= 0 || a.total <= 0)) return hipErrorInvalidValue;
+    if (conv && (!a.y || !a.hat || a.conv_a <= 0 || a.total <= 0 || !a.scratch || a.scratch_polys < 8)) return hipErrorInvalidValue;
     if (mode == FP_FWD_CONV_FINAL && (!a.acc || !a.pinv_tab || (a.add && a.add_div <= 0))) return hipErrorInvalidValue;
     switch (mode) {
         case FP_FWD_PLAIN: return dispatch_k3<FP_FWD_PLAIN>(log_n, a, tk, n_batch, st);
