@@ -73,13 +73,13 @@ def algorithmic_flops_rot_left(N, l, K, alpha, B):
 # HBM bytes = FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0 KiB (the factors a 1 GiB device-to-device copy reads back), and the
 # share of the CUs' vector-ALU issue slots in use = SQ_INSTS_VALU * 4 cycles / (4 SIMDs * SQ_BUSY_CU_CYCLES).
 MEASURED_TRAFFIC = {
-    "ntt_fp_kernel<5, 3>": (2 * 62845.2 + 273066.7) * 1024,
-    "ntt_fp_kernel<5, 4>": (2 * 524533.9 + 524288.0) * 1024,
-    "ntt_fp_kernel<5, 2>": (2 * 167662.7 + 230400.0) * 1024,
+    "ntt_fp_kernel<5, 3>": (2 * 122649.6 + 409600.1) * 1024,
+    "ntt_fp_kernel<5, 4>": (2 * 644043.6 + 786432.0) * 1024,
+    "ntt_fp_kernel<5, 2>": (2 * 166824.7 + 230400.0) * 1024,
     "inner_product_fp_kernel": (2 * 608300.8 + 720896.0) * 1024,
 }
 MEASURED_VALU_BUSY = {
-    "ntt_fp_kernel<5, 3>": 0.57, "ntt_fp_kernel<5, 4>": 0.51, "ntt_fp_kernel<5, 2>": 0.58, "inner_product_fp_kernel": 0.27,
+    "ntt_fp_kernel<5, 3>": 0.64, "ntt_fp_kernel<5, 4>": 0.55, "ntt_fp_kernel<5, 2>": 0.58, "inner_product_fp_kernel": 0.27,
 }
 FP64_PEAK_TFLOPS = 78.6   # 256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz
 
@@ -227,7 +227,7 @@ def main():
     hbm_side = {"achieved_GBs": kernels[dom]["algorithmic_GBs"], "frac": round(kernels[dom]["algorithmic_GBs"] / HBM_PEAK_GBS, 4),
                 "algorithmic_bytes_per_launch": int(alg.get(dom, 0) / launches)}
     if dom in flops:
-        # the transform kernels are bound by vector-ALU issue (counters: 51-58 % of the issue slots busy, 17-20 % of the
+        # the transform kernels are bound by vector-ALU issue (counters: 55-64 % of the issue slots busy, 17-20 % of the
         # HBM peak), so the roofline is the fp64 vector peak; the HBM reading stays beside it
         tf = kernels[dom]["algorithmic_TFLOPs"]
         roofline = {"kernel": dom, "bound": "alu", "achieved": tf, "peak": FP64_PEAK_TFLOPS, "unit": "TFLOP/s",
