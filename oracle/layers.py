@@ -2,7 +2,8 @@
 
 The schedules of the paper's runtime (Sec. "Runtime"; Algorithm 1 for conv2d
 with VALID padding, its SAME-padding variant with a mask, homomorphic matmul
-without replicas, pooling, degree-2 activation) written as plain loops over the
+without and with replicas (the latter with a CHW-tiled output), pooling,
+degree-2 activation) written as plain loops over the
 oracle's HISA instructions, one instruction per statement, in the paper's
 order.  Each layer also returns the fixed-point integers it used, so that a
 test can hand the very same integers to another implementation.
@@ -30,6 +31,19 @@ class OTensor:
     w_stride: int
     offset: int
     clean: int
+    c_inner: int = 1     # channels per ciphertext: 1 = HW-tiling, more = CHW-tiling (cts index b*ceil(C/c_inner) + c//c_inner)
+    c_stride: int = 0    # slots between two channels of one ciphertext
+
+
+def cts_per_image(t: OTensor):
+    return -(-t.channels // t.c_inner)
+
+
+def tensor_slots(t: OTensor):
+    """Slots of the elements of one ciphertext, channel-major: element (c mod c_inner, y, x) sits in slot
+    offset + (c mod c_inner)*c_stride + y*h_stride + x*w_stride (Sec. "Runtime": physical strides per inner dimension)."""
+    return [t.offset + cl * t.c_stride + y * t.h_stride + x * t.w_stride
+            for cl in range(t.c_inner) for y in range(t.height) for x in range(t.width)]
 
 
 def plane_slots(h, w, hs, ws, off):
@@ -48,7 +62,32 @@ def tensor_encrypt(o: Oracle, x, scale, limbs, h_stride=None, w_stride=1, offset
     return OTensor(cts, b, c, h, w, hs, w_stride, offset, 1)
 
 
+def tensor_encrypt_chw(o: Oracle, x, scale, limbs, c_inner, c_stride, h_stride=None, w_stride=1, offset=0) -> OTensor:
+    """CHW-tiling: c_inner channels per ciphertext, c_stride slots apart."""
+    b, c, h, w = x.shape
+    hs = h_stride if h_stride else w * w_stride
+    t = OTensor([], b, c, h, w, hs, w_stride, offset, 1, c_inner, c_stride)
+    sl = np.asarray(tensor_slots(t)).reshape(c_inner, h * w)
+    assert len(set(sl.reshape(-1).tolist())) == sl.size and sl.max() < o.slots
+    for bi in range(b):
+        for j in range(cts_per_image(t)):
+            z = np.zeros(o.slots)
+            for cl in range(min(c_inner, c - j * c_inner)):
+                z[sl[cl]] = x[bi, j * c_inner + cl].reshape(-1)
+            t.cts.append(o.encrypt(o.encode(z, scale, limbs)))
+    return t
+
+
 def tensor_decrypt(o: Oracle, t: OTensor):
+    if t.c_inner > 1:
+        out = np.zeros((t.batch, t.channels, t.height, t.width))
+        sl = np.asarray(tensor_slots(t)).reshape(t.c_inner, t.height, t.width)
+        per = cts_per_image(t)
+        for i, ct in enumerate(t.cts):
+            z = o.decode(o.decrypt(ct)).real
+            for cl in range(min(t.c_inner, t.channels - (i % per) * t.c_inner)):
+                out[i // per, (i % per) * t.c_inner + cl] = z[sl[cl]]
+        return out
     out = np.zeros((t.batch, t.channels, t.height, t.width))
     sl = plane_slots(t.height, t.width, t.h_stride, t.w_stride, t.offset)
     for i, ct in enumerate(t.cts):
@@ -160,16 +199,107 @@ def fc_reduce_steps(o: Oracle, t: OTensor):
     positions this reads are zero after the masked multiply.  That needs the padded rows not to overlap and the padded
     plane not to wrap around the slot vector; otherwise (or if it is not shorter) the sum runs over the contiguous
     power-of-two window 1, 2, 4, ... that covers the plane."""
-    span = (t.height - 1) * t.h_stride + (t.width - 1) * t.w_stride
+    return reduce_steps(t, o.slots)
+
+
+def reduce_steps(t: OTensor, limit):
+    """The same rule for the elements of one ciphertext of a tensor with c_inner channels (a third strided
+    dimension, c_stride * 2^k, whose padded planes must not overlap either); the padded elements have to stay
+    below slot `limit`."""
+    span = (t.c_inner - 1) * t.c_stride + (t.height - 1) * t.h_stride + (t.width - 1) * t.w_stride
     window = []
     while (1 << len(window)) < span + 1:
         window.append(1 << len(window))
     wl = max(t.width - 1, 0).bit_length()
     hl = max(t.height - 1, 0).bit_length()
-    fits = (t.w_stride << wl) <= t.h_stride and \
-        t.offset + ((1 << hl) - 1) * t.h_stride + ((1 << wl) - 1) * t.w_stride < o.slots
-    strided = [t.w_stride << k for k in range(wl)] + [t.h_stride << k for k in range(hl)]
+    cl = max(t.c_inner - 1, 0).bit_length()
+    fits = (t.w_stride << wl) <= t.h_stride and (t.c_inner == 1 or (t.h_stride << hl) <= t.c_stride) and \
+        t.offset + ((1 << cl) - 1) * t.c_stride + ((1 << hl) - 1) * t.h_stride + ((1 << wl) - 1) * t.w_stride < limit
+    strided = [t.w_stride << k for k in range(wl)] + [t.h_stride << k for k in range(hl)] + \
+        [t.c_stride << k for k in range(cl)]
     return strided if fits and len(strided) < len(window) else window
+
+
+def matmul_geometry(o: Oracle, t: OTensor, replicas):
+    """Block length P (the power of two that covers every element slot of a ciphertext), the number of replicas R
+    actually used (a power of two, at most `replicas` and at most slots / P), the rotRight amounts that build the
+    replicas (log-many, adding in between) and the rotLeft amounts of the reduction inside a block
+    (Sec. "Homomorphic Tensor Operations", matmul and CHW paragraphs)."""
+    top = t.offset + (t.c_inner - 1) * t.c_stride + (t.height - 1) * t.h_stride + (t.width - 1) * t.w_stride + 1
+    block = 1 << (top - 1).bit_length()
+    assert block <= o.slots
+    r = 1
+    while 2 * r <= min(replicas, o.slots // block):
+        r *= 2
+    replicate = [block << k for k in range(r.bit_length() - 1)]
+    return block, r, replicate, reduce_steps(t, block if r > 1 else o.slots)
+
+
+def matmul(o: Oracle, t: OTensor, w, replicas):
+    """Homomorphic matmul with replicas.  w[OUT][C][H][W].  Returns (CHW-tiled output tensor with R 1x1 channels per
+    ciphertext, dict of the fixed-point integers used)."""
+    out_n = w.shape[0]
+    w = np.asarray(w, dtype=np.float64).reshape(out_n, t.channels, t.height * t.width)
+    block, r, _, _ = matmul_geometry(o, t, replicas)
+    l = t.cts[0].limbs
+    per = cts_per_image(t)
+    sl = np.asarray(tensor_slots(t)).reshape(t.c_inner, t.height * t.width)
+    needs_mask = r > 1 and not t.clean
+    ints = {"mask_coeffs": None, "mask_scale": 1.0}
+    if needs_mask:   # 0/1 on the element slots, encoded at the scale of the modulus the divScalar removes
+        mask_scale = float(o.primes[l - 1])
+        masks = np.zeros((per, o.N), dtype=np.int64)
+        for j in range(per):
+            z = np.zeros(o.slots)
+            z[sl[:min(t.c_inner, t.channels - j * t.c_inner)].reshape(-1)] = 1.0
+            masks[j] = o.encode_coeffs(z, mask_scale)
+        ints.update(mask_coeffs=masks, mask_scale=mask_scale)
+        l -= 1
+    pt_scale = float(o.primes[l - 1])
+    groups = -(-out_n // r)
+    coeffs = np.zeros((groups, per, o.N), dtype=np.int64)
+    for g in range(groups):
+        for j in range(per):
+            z = np.zeros(o.slots)
+            for rep in range(min(r, out_n - g * r)):
+                for cl in range(min(t.c_inner, t.channels - j * t.c_inner)):
+                    z[rep * block + sl[cl]] = w[g * r + rep, j * t.c_inner + cl]
+            coeffs[g, j] = o.encode_coeffs(z, pt_scale)
+    ints.update(pt_coeffs=coeffs, pt_scale=pt_scale)
+    return matmul_fixed(o, t, ints, out_n, replicas), ints
+
+
+def matmul_fixed(o: Oracle, t: OTensor, ints, out_n, replicas):
+    """1. (input not clean, R > 1) mulPlain by the 0/1 mask + divScalar, so that step 2 copies zeros and not leftovers;
+    2. log2 R times x += rotRight(x, P 2^k): R copies of the elements, P slots apart;  3. per group g of R outputs:
+    sum over the input ciphertexts of mulPlain(x_j, weights of outputs gR..gR+R-1, output gR+r on the r-th copy),
+    divScalar;  4. rotate-and-add inside the blocks: output gR+r ends in slot r P + offset."""
+    block, r, replicate, reduce = matmul_geometry(o, t, replicas)
+    per = cts_per_image(t)
+    groups = -(-out_n // r)
+    outs = []
+    for b in range(t.batch):
+        xs = t.cts[b * per:(b + 1) * per]
+        if r > 1:
+            if not t.clean:
+                masked = []
+                for j, x in enumerate(xs):
+                    pt = o.pt_from_coeffs(ints["mask_coeffs"][j], ints["mask_scale"], x.limbs)
+                    temp = o.mul_plain(x, pt)
+                    masked.append(o.div_scalar(temp, o.max_scalar_div(temp, float("inf"))))
+                xs = masked
+            for amount in replicate:
+                xs = [o.add(x, o.rot_right(x, amount)) for x in xs]
+        for g in range(groups):
+            acc = None
+            for j, x in enumerate(xs):
+                temp = o.mul_plain(x, o.pt_from_coeffs(ints["pt_coeffs"][g, j], ints["pt_scale"], x.limbs))
+                acc = temp if acc is None else o.add(acc, temp)
+            acc = o.rescale(acc)
+            for amount in reduce:
+                acc = o.add(acc, o.rot_left(acc, amount))
+            outs.append(acc)
+    return OTensor(outs, t.batch, out_n, 1, 1, 1, 1, t.offset, 0, r, block)
 
 
 def fc_fixed(o: Oracle, t: OTensor, coeffs, pt_scale):

@@ -131,3 +131,76 @@ def test_fc_reduction_rule_and_zero_padding():
         o.gen_rot_keys(expect)
         f, _ = layers.fc(o, t, w)
         assert np.abs(layers.tensor_decrypt(o, f) - want).max() <= 1e-3
+
+
+def test_matmul_with_replicas_chw_output_and_op_counts():
+    """Homomorphic matmul with replicas (Sec. "Homomorphic Tensor Operations"): the number of mulPlain drops by the
+    number of replicas, replicas and reduction take log-many rotations, the output is CHW-tiled (R outputs per
+    ciphertext, one block apart), and a CHW-tiled tensor feeds the next matmul.  Values against the fp64 layers."""
+    o = Oracle(11, [50, 45, 45, 45, 45, 45], 3, 55, seed=12)
+    o.keygen()
+    x = synth.image(21, 3, 4, 4)[None]
+    t = layers.tensor_encrypt(o, x, 2.0 ** 45, 6)
+    o.gen_rot_keys([1, 4, 5])
+    pool = layers.sum_pool2x2(o, t)                       # 3 channels of 2x2, strides (8, 2), not clean
+    ref = plain_net.sum_pool2x2(x)
+    assert pool.clean == 0
+    block, r, replicate, reduce = layers.matmul_geometry(o, pool, 64)
+    # last element in slot 8 + 2 = 10 -> blocks of 16 slots; 1024 slots hold 64 of them
+    assert (block, r, replicate, reduce) == (16, 64, [16, 32, 64, 128, 256, 512], [2, 8])
+    assert layers.matmul_geometry(o, pool, 5)[1] == 4     # rounded down to a power of two
+    o.gen_rot_keys([o.slots - a for a in replicate[:2]] + reduce)
+    counts = {"mul_plain": 0, "rot_left": 0, "rot_right": 0, "div_scalar": 0}
+    real = {n: getattr(o, n) for n in counts}
+    for name in counts:
+        def f(*a, _n=name, **k):
+            counts[_n] += 1
+            return real[_n](*a, **k)
+        setattr(o, name, f)
+    w1 = synth.fc_weights(22, 10, 3, 2, 2, std=0.3)
+    m1, ints = layers.matmul(o, pool, w1, 4)
+    for name in counts:
+        setattr(o, name, real[name])
+    groups = 3                                            # ceil(10 / 4)
+    assert counts["mul_plain"] == 3 + groups * 3          # the mask on each input, then one per (group, input)
+    assert counts["rot_right"] == 3 * 2                   # two doubling steps per input ciphertext
+    assert counts["rot_left"] - counts["rot_right"] == groups * 2   # (rotRight is a rotLeft by the complement)
+    assert counts["div_scalar"] == 3 + groups
+    assert (m1.channels, m1.height, m1.width, m1.c_inner, m1.c_stride, m1.offset, m1.clean) == (10, 1, 1, 4, 16, 0, 0)
+    assert len(m1.cts) == groups and m1.cts[0].limbs == 4
+    assert ints["mask_coeffs"].shape == (3, o.N) and ints["pt_coeffs"].shape == (groups, 3, o.N)
+    ref1 = plain_net.fc(ref, w1)
+    assert np.abs(layers.tensor_decrypt(o, m1) - ref1).max() <= 1e-3
+    # the same layer without replicas is the plain FC layer, bit for bit
+    m0, _ = layers.matmul(o, pool, w1, 1)
+    f0, _ = layers.fc(o, pool, w1)
+    assert m0.c_inner == 1 and len(m0.cts) == 10
+    assert all(np.array_equal(a.data, b.data) for a, b in zip(m0.cts, f0.cts))
+    # activation on the CHW-tiled tensor, then a matmul that reads it (elements 16 slots apart: strided reduction)
+    act = layers.poly2_act(o, m1, 0.5, 0.25)
+    ref_act = plain_net.poly2_act_without_a(ref1, 0.5, 0.25)
+    assert (act.c_inner, act.c_stride) == (4, 16)
+    assert np.abs(layers.tensor_decrypt(o, act) - ref_act).max() <= 1e-3
+    assert layers.matmul_geometry(o, act, 8) == (64, 8, [64, 128, 256], [16, 32])
+    o.gen_rot_keys([o.slots - 64, 16, 32])
+    w2 = synth.fc_weights(23, 3, 10, 1, 1, std=0.4)
+    m2, _ = layers.matmul(o, act, w2, 2)
+    assert (m2.c_inner, m2.c_stride, len(m2.cts)) == (2, 64, 2)
+    assert np.abs(layers.tensor_decrypt(o, m2) - plain_net.fc(ref_act, w2)).max() <= 1e-3
+
+
+def test_chw_tensor_round_trip_and_clean_input_needs_no_mask():
+    o = Oracle(10, [50, 40, 40], 3, 55, seed=13)
+    o.keygen()
+    x = synth.image(31, 5, 3, 3)[None]
+    t = layers.tensor_encrypt_chw(o, x, 2.0 ** 40, 3, c_inner=2, c_stride=16, h_stride=4)
+    assert len(t.cts) == 3 and t.clean == 1               # channels (0,1), (2,3), (4)
+    assert np.abs(layers.tensor_decrypt(o, t) - x).max() <= 1e-6
+    z = o.decode(o.decrypt(t.cts[2])).real                # the last ciphertext holds one channel only
+    assert np.abs(z[16:]).max() <= 1e-6
+    assert layers.matmul_geometry(o, t, 1 << 20) == (32, 16, [32, 64, 128, 256], [1, 2, 4, 8, 16])
+    o.gen_rot_keys([o.slots - 32, 1, 2, 4, 8, 16])
+    w = synth.fc_weights(32, 4, 5, 3, 3, std=0.3)
+    m, ints = layers.matmul(o, t, w, 2)
+    assert ints["mask_coeffs"] is None and m.cts[0].limbs == 2
+    assert np.abs(layers.tensor_decrypt(o, m) - plain_net.fc(x, w)).max() <= 1e-3
