@@ -190,22 +190,30 @@ int hisa_encrypt_batch(hisa_ctx* ctx, const hisa_pt* const* pts, size_t n, hisa_
  * indistinguishable from encryptions. */
 int hisa_ct_random_batch(hisa_ctx* ctx, size_t n, uint32_t limbs, double scale, uint64_t counter, hisa_ct** out);
 
-/* ---- tensor layer (Sec. "Runtime": CipherTensor, HW-tiling, Algorithm 1) ----
- * A CipherTensor is a vector of ciphertexts plus plain-integer metadata: the
- * outer (batch, channel) dimensions index ciphertexts cts[b*channels + c]; one
- * ciphertext holds the height x width plane of one channel (HW-tiling), element
- * (y, x) in slot offset + y*h_stride + x*w_stride (strides leave room for
- * padding between rows).  `clean` is the runtime's flag that every slot that
- * holds no element is zero.  The struct is host memory owned by the caller; the
- * handles in cts are owned like any other handle.  Layer calls fill *out:
- * out->cts must point to room for the output handles (batch * out channels). */
+/* ---- tensor layer (Sec. "Runtime": CipherTensor, HW- and CHW-tiling, Algorithm 1) ----
+ * A CipherTensor is a vector of ciphertexts plus plain-integer metadata.
+ * HW-tiling (c_inner = 1): the outer (batch, channel) dimensions index
+ * ciphertexts cts[b*channels + c]; one ciphertext holds the height x width
+ * plane of one channel, element (y, x) in slot offset + y*h_stride + x*w_stride
+ * (strides leave room for padding between rows).  CHW-tiling (c_inner > 1):
+ * c_inner channels share a ciphertext, c_stride slots apart: channel c of image
+ * b is in cts[b*ceil(channels/c_inner) + c/c_inner], element (y, x) in slot
+ * offset + (c mod c_inner)*c_stride + y*h_stride + x*w_stride; a last
+ * ciphertext with fewer channels leaves the rest of its slots unused.  `clean`
+ * is the runtime's flag that every slot that holds no element is zero.  The
+ * struct is host memory owned by the caller; the handles in cts are owned like
+ * any other handle.  Layer calls fill *out: out->cts must point to room for the
+ * output handles.  conv2d and fc take HW-tiled tensors (HISA_ERR_ARG
+ * otherwise); pool, activation, matmul, encrypt and decrypt take both. */
 typedef struct {
-    uint32_t batch, channels;    /* outer (vector) dimensions                 */
+    uint32_t batch, channels;    /* logical outer dimensions                  */
     uint32_t height, width;      /* logical inner dimensions                  */
     uint32_t h_stride, w_stride; /* physical strides in slots                 */
-    uint32_t offset;             /* slot of element (0,0)                     */
+    uint32_t offset;             /* slot of element (0,0) of the first channel of a ciphertext */
     uint32_t clean;              /* 1: slots outside the elements hold zeros  */
-    hisa_ct** cts;               /* batch*channels handles                    */
+    uint32_t c_inner;            /* channels per ciphertext (0 is read as 1)  */
+    uint32_t c_stride;           /* slots between channels of one ciphertext  */
+    hisa_ct** cts;               /* batch*ceil(channels/c_inner) handles      */
 } hisa_tensor;
 
 #define HISA_CONV_SCALAR 0 /* literal Algorithm 1: mulScalar by round(w * q_last), add, one divScalar; the output */
@@ -280,6 +288,49 @@ typedef struct hisa_fc_plan hisa_fc_plan;
 int hisa_fc_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t out_features, hisa_fc_plan** plan);
 int hisa_fc_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_fc_plan* plan, hisa_tensor* out);
 int hisa_fc_plan_free(hisa_ctx* ctx, hisa_fc_plan* plan);
+/* Homomorphic matmul with replicas (Sec. "Homomorphic Tensor Operations",
+ * paragraphs "Homomorphic matmul" and "CHW-tiled convolution": replicas cost
+ * log-many rotations and divide the number of mulPlain; reductions over equally
+ * strided elements take log-many rotations).  Input: any tensor, HW- or
+ * CHW-tiled; host w[OUT][C][H][W].  With P the power of two that covers the
+ * element slots of a ciphertext and R the largest power of two that is at most
+ * `replicas` and at most slots/P:
+ *   1. (R > 1, input not clean) mulPlain by the 0/1 mask of the element slots,
+ *      encoded at the scale of the last modulus, and divScalar: one level;
+ *   2. (R > 1) log2 R times x += rotRight(x, P*2^k): R copies, P slots apart;
+ *   3. per group g of R outputs: sum over the input ciphertexts of
+ *      mulPlain(x_j, plaintext holding the weights of output gR+r on copy r),
+ *      one divScalar;
+ *   4. rotate-and-add inside the blocks (amounts as in hisa_fc, with the channel
+ *      stride as a third strided dimension and the padded elements confined to
+ *      the block when R > 1).
+ * Output: OUT channels of 1x1 planes, CHW-tiled: c_inner = R, c_stride = P,
+ * output gR+r in slot r*P + offset of ciphertext g; batch*ceil(OUT/R) handles
+ * (hisa_matmul_geometry gives P, R and that count), clean = 0.  With R = 1 on an
+ * HW-tiled input this is hisa_fc bit for bit.  Needs the rotation keys listed
+ * by hisa_matmul_rot_steps, and two levels (one when R = 1 or the input is
+ * clean): HISA_ERR_DEPTH_EXHAUSTED otherwise.
+ * hisa_matmul_fixed takes the fixed-point plaintexts directly:
+ * pt_coeffs[ceil(OUT/R)][ceil(C/c_inner)][N] signed coefficients at pt_scale and
+ * (when step 1 applies, else null) mask_coeffs[ceil(C/c_inner)][N] at mask_scale.
+ * hisa_matmul_prepare encodes the weights once for tensors with the layout,
+ * clean flag and level of `like` into a plan that owns device memory until
+ * hisa_matmul_plan_free; hisa_matmul_apply(in, plan) returns bit for bit what
+ * hisa_matmul(in, w, ...) returns (another layout: HISA_ERR_ARG, another level:
+ * HISA_ERR_LEVEL_MISMATCH). */
+typedef struct hisa_matmul_plan hisa_matmul_plan;
+int hisa_matmul_geometry(hisa_ctx* ctx, const hisa_tensor* in, uint32_t out_features, uint32_t replicas,
+                         uint32_t* block, uint32_t* used_replicas, uint32_t* out_cts);
+int hisa_matmul_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, uint32_t replicas, int32_t* steps, size_t cap, size_t* n);
+int hisa_matmul(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t out_features, uint32_t replicas,
+                hisa_tensor* out);
+int hisa_matmul_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* pt_coeffs, double pt_scale,
+                      const int64_t* mask_coeffs, double mask_scale, uint32_t out_features, uint32_t replicas,
+                      hisa_tensor* out);
+int hisa_matmul_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t out_features, uint32_t replicas,
+                        hisa_matmul_plan** plan);
+int hisa_matmul_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_matmul_plan* plan, hisa_tensor* out);
+int hisa_matmul_plan_free(hisa_ctx* ctx, hisa_matmul_plan* plan);
 /* 2x2 sum pool, stride 2 (the 1/4 of the average belongs in the next layer's
  * weights): x + rot(w_stride) + rot(h_stride) + rot(h_stride + w_stride);
  * strides double, no level is used. */
@@ -296,7 +347,9 @@ int hisa_conv2d_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_
 int hisa_fc_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n);
 int hisa_pool_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n);
 /* Encrypts a plain tensor host x[batch][channels][height][width] into a clean
- * HW-tiled CipherTensor with the given strides and offset, at `limbs` limbs. */
+ * CipherTensor with the tiling (c_inner, c_stride), strides and offset that
+ * *inout names, at `limbs` limbs; elements that would share a slot are
+ * HISA_ERR_ARG. */
 int hisa_tensor_encrypt(hisa_ctx* ctx, const double* x, double scale, uint32_t limbs, hisa_tensor* inout);
 /* Decrypts and decodes the elements back: host x[batch][channels][height][width]. */
 int hisa_tensor_decrypt(hisa_ctx* ctx, const hisa_tensor* t, double* x);

@@ -1,9 +1,10 @@
-// HW-tiled homomorphic tensor kernels of the paper's runtime (Sec. "Runtime":
-// CipherTensor metadata, Algorithm 1 and its SAME-padding variant, homomorphic
-// matmul without replicas, pooling, degree-2 activation) on top of the batched
-// HISA primitives.  Host code here only orders launches; the multiply-accumulate
+// Homomorphic tensor kernels of the paper's runtime (Sec. "Runtime":
+// CipherTensor metadata for HW- and CHW-tiling, Algorithm 1 and its SAME-padding
+// variant, homomorphic matmul without and with replicas, pooling, degree-2
+// activation) on top of the batched HISA primitives.  Host code here only orders launches; the multiply-accumulate
 // over (input channel, tap) pairs runs in the two kernels below.
 #include <math.h>
+#include <string.h>
 
 #include <algorithm>
 #include <set>
@@ -388,13 +389,34 @@ static hipError_t launch_plain_mac(const PrimeConst* primes, const MacArgs& g, i
 // ---------------------------------------------------------------------------
 // helpers
 // ---------------------------------------------------------------------------
-static int check_tensor(hisa_ctx* ctx, const hisa_tensor* t) {
-    if (!ctx) return HISA_ERR_ARG;
+// channels per ciphertext (0 in a zero-initialised struct means HW-tiling), ciphertexts per image, ciphertexts in all
+static inline uint32_t t_ci(const hisa_tensor* t) { return t->c_inner ? t->c_inner : 1; }
+static inline size_t t_per(const hisa_tensor* t) { return ((size_t)t->channels + t_ci(t) - 1) / t_ci(t); }
+static inline size_t t_ncts(const hisa_tensor* t) { return (size_t)t->batch * t_per(t); }
+// slot of the last element of a ciphertext
+static inline u64 t_last(const hisa_tensor* t) {
+    return (u64)t->offset + (u64)(t_ci(t) - 1) * t->c_stride + (u64)(t->height - 1) * t->h_stride +
+           (u64)(t->width - 1) * t->w_stride;
+}
+
+static int check_layout(hisa_ctx* ctx, const hisa_tensor* t) {
     if (!t || !t->cts || t->batch == 0 || t->channels == 0 || t->height == 0 || t->width == 0)
         return fail(ctx, HISA_ERR_ARG, "empty tensor");
-    const u64 last = (u64)t->offset + (u64)(t->height - 1) * t->h_stride + (u64)(t->width - 1) * t->w_stride;
-    if (last >= ctx->N / 2) return fail(ctx, HISA_ERR_ARG, "tensor plane does not fit the %u slots", ctx->N / 2);
-    return check_batch_shape(ctx, (const hisa_ct* const*)t->cts, (size_t)t->batch * t->channels, 2);
+    if (t_ci(t) > 1 && t->c_stride == 0) return fail(ctx, HISA_ERR_ARG, "several channels per ciphertext need a channel stride");
+    if (t_last(t) >= ctx->N / 2) return fail(ctx, HISA_ERR_ARG, "tensor elements do not fit the %u slots", ctx->N / 2);
+    return HISA_OK;
+}
+
+static int check_tensor(hisa_ctx* ctx, const hisa_tensor* t) {
+    if (!ctx) return HISA_ERR_ARG;
+    TRY(check_layout(ctx, t));
+    return check_batch_shape(ctx, (const hisa_ct* const*)t->cts, t_ncts(t), 2);
+}
+
+// the layers that read neighbouring slots of one channel are written for one channel per ciphertext
+static int require_hw_tiling(hisa_ctx* ctx, const hisa_tensor* t, const char* what) {
+    if (t && t_ci(t) > 1) return fail(ctx, HISA_ERR_ARG, "%s takes HW-tiled tensors (one channel per ciphertext)", what);
+    return HISA_OK;
 }
 
 static void free_handles(hisa_ctx* ctx, std::vector<hisa_ct*>& v) {
@@ -444,20 +466,29 @@ extern "C" int hisa_conv2d_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, const
 // w_stride * 2^k then h_stride * 2^k, each dimension rounded up to a power of two (the extra positions are zero after
 // the masked multiply); it needs padded rows that do not overlap and a padded plane that does not wrap around the
 // slot vector.  Otherwise, or when it is not shorter: the contiguous window 1, 2, 4, .. covering the plane.
-static std::vector<i64> fc_reduce_steps(const hisa_ctx* ctx, const hisa_tensor* in) {
-    const u64 span = (u64)(in->height - 1) * in->h_stride + (u64)(in->width - 1) * in->w_stride;
+// With several channels per ciphertext the channel stride is a third strided dimension (c_stride * 2^k) under the
+// same conditions; the padded elements have to stay below slot `limit`.
+static std::vector<i64> reduce_steps(const hisa_tensor* in, u64 limit) {
+    const uint32_t ci = t_ci(in);
+    const u64 span = t_last(in) - in->offset;
     std::vector<i64> window;
     while (((u64)1 << window.size()) < span + 1) window.push_back((i64)1 << window.size());
-    int wl = 0, hl = 0;
+    int wl = 0, hl = 0, cl = 0;
     while (((u64)1 << wl) < in->width) wl++;
     while (((u64)1 << hl) < in->height) hl++;
-    const u64 last = (u64)in->offset + (((u64)1 << hl) - 1) * in->h_stride + (((u64)1 << wl) - 1) * in->w_stride;
-    const bool fits = ((u64)in->w_stride << wl) <= in->h_stride && last < ctx->N / 2;
+    while (((u64)1 << cl) < ci) cl++;
+    const u64 last = (u64)in->offset + (((u64)1 << cl) - 1) * in->c_stride + (((u64)1 << hl) - 1) * in->h_stride +
+                     (((u64)1 << wl) - 1) * in->w_stride;
+    const bool fits = ((u64)in->w_stride << wl) <= in->h_stride && (ci == 1 || ((u64)in->h_stride << hl) <= in->c_stride) &&
+                      last < limit;
     std::vector<i64> strided;
     for (int k = 0; k < wl; k++) strided.push_back((i64)in->w_stride << k);
     for (int k = 0; k < hl; k++) strided.push_back((i64)in->h_stride << k);
+    for (int k = 0; k < cl; k++) strided.push_back((i64)in->c_stride << k);
     return (fits && strided.size() < window.size()) ? strided : window;
 }
+
+static std::vector<i64> fc_reduce_steps(const hisa_ctx* ctx, const hisa_tensor* in) { return reduce_steps(in, ctx->N / 2); }
 
 extern "C" int hisa_fc_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n) {
     if (!ctx || !in) return HISA_ERR_ARG;
@@ -478,6 +509,14 @@ static std::vector<uint32_t> plane_slots(uint32_t h, uint32_t w, uint32_t hs, ui
     std::vector<uint32_t> s;
     for (uint32_t y = 0; y < h; y++)
         for (uint32_t x = 0; x < w; x++) s.push_back(off + y * hs + x * ws);
+    return s;
+}
+
+// slots of the elements of one ciphertext, channel-major
+static std::vector<uint32_t> tensor_slots(const hisa_tensor* t) {
+    std::vector<uint32_t> s;
+    for (uint32_t c = 0; c < t_ci(t); c++)
+        for (uint32_t v : plane_slots(t->height, t->width, t->h_stride, t->w_stride, t->offset + c * t->c_stride)) s.push_back(v);
     return s;
 }
 
@@ -539,9 +578,10 @@ static u64 mod_i64(i64 v, u64 q) {
 }
 
 static void fill_out_meta(hisa_tensor* out, uint32_t batch, uint32_t channels, uint32_t h, uint32_t w, uint32_t hs,
-                          uint32_t ws, uint32_t off, uint32_t clean) {
+                          uint32_t ws, uint32_t off, uint32_t clean, uint32_t c_inner = 1, uint32_t c_stride = 0) {
     out->batch = batch; out->channels = channels; out->height = h; out->width = w;
     out->h_stride = hs; out->w_stride = ws; out->offset = off; out->clean = clean;
+    out->c_inner = c_inner; out->c_stride = c_stride;
 }
 
 // ---------------------------------------------------------------------------
@@ -555,6 +595,7 @@ struct ConvPlan {
 static int conv_plan(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, ConvPlan* p) {
     if (!g || g->fh == 0 || g->fw == 0 || g->stride == 0 || g->fh * g->fw > MAX_TAPS || g->mode > HISA_CONV_PLAIN)
         return fail(ctx, HISA_ERR_ARG, "bad conv geometry");
+    TRY(require_hw_tiling(ctx, in, "conv2d"));
     if (g->pad_same) {
         if (!in->clean) return fail(ctx, HISA_ERR_ARG, "SAME padding needs a clean input tensor (zeros around the plane)");
         p->out_h = (in->height + g->stride - 1) / g->stride;
@@ -889,6 +930,7 @@ static int fc_finish(hisa_ctx* ctx, const hisa_tensor* in, std::vector<hisa_ct*>
 static int fc_common(hisa_ctx* ctx, const hisa_tensor* in, const double* w, const int64_t* pt_coeffs, double pt_scale,
                      uint32_t OUT, hisa_tensor* out) {
     TRY(check_tensor(ctx, in));
+    TRY(require_hw_tiling(ctx, in, "fc (hisa_matmul reads CHW-tiled tensors)"));
     if (!out || !out->cts || OUT == 0) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
     const uint32_t B = in->batch, C = in->channels, l = in->cts[0]->limbs;
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "fc needs a level to rescale into");
@@ -960,6 +1002,7 @@ struct hisa_fc_plan {
 extern "C" int hisa_fc_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t OUT, hisa_fc_plan** plan) {
     if (!ctx || !like || !w || !plan || OUT == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
     TRY(check_tensor(ctx, like));
+    TRY(require_hw_tiling(ctx, like, "fc (hisa_matmul reads CHW-tiled tensors)"));
     if (like->height == 1 && like->width == 1)
         return fail(ctx, HISA_ERR_ARG, "a fully connected layer on 1x1 planes multiplies by scalars: nothing to prepare");
     const uint32_t C = like->channels, l = like->cts[0]->limbs;
@@ -995,6 +1038,7 @@ extern "C" int hisa_fc_plan_free(hisa_ctx* ctx, hisa_fc_plan* plan) {
 extern "C" int hisa_fc_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_fc_plan* plan, hisa_tensor* out) {
     if (!ctx || !in || !plan || plan->magic != HISA_MAGIC_FCPLAN) return fail(ctx, HISA_ERR_ARG, "bad argument");
     TRY(check_tensor(ctx, in));
+    TRY(require_hw_tiling(ctx, in, "fc (hisa_matmul reads CHW-tiled tensors)"));
     if (!out || !out->cts) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
     const uint32_t B = in->batch, C = in->channels, l = in->cts[0]->limbs, OUT = plan->out_features;
     if (C != plan->channels || in->height != plan->height || in->width != plan->width || in->h_stride != plan->h_stride ||
@@ -1022,12 +1066,278 @@ extern "C" int hisa_fc_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_fc
 }
 
 // ---------------------------------------------------------------------------
+// matmul with replicas (Sec. "Homomorphic Tensor Operations", "Homomorphic matmul" and the CHW paragraph)
+// ---------------------------------------------------------------------------
+// The element slots of a ciphertext lie inside a block of P slots (P a power of two).  R copies of the block, made
+// with log2 R rotations, let one mulPlain serve R outputs, so a layer takes ceil(OUT/R) * (ciphertexts per image)
+// multiplications instead of OUT * (ciphertexts per image); the sum inside each block is again a log-step
+// rotate-and-add.  Output o = gR + r ends in slot r P + offset of ciphertext g: a CHW-tiled tensor of 1x1 planes.
+struct MatmulGeom {
+    uint32_t block, R;
+    std::vector<i64> replicate;   // rotRight amounts P 2^k
+    std::vector<i64> reduce;      // rotLeft amounts
+};
+
+static int matmul_geom(hisa_ctx* ctx, const hisa_tensor* in, uint32_t replicas, MatmulGeom* g) {
+    if (replicas == 0) return fail(ctx, HISA_ERR_ARG, "replicas must be at least 1");
+    const u64 top = t_last(in) + 1, slots = ctx->N / 2;
+    u64 block = 1;
+    while (block < top) block <<= 1;
+    if (block > slots) return fail(ctx, HISA_ERR_ARG, "tensor elements do not fit the slots");
+    u64 r = 1;
+    while (2 * r <= std::min<u64>(replicas, slots / block)) r *= 2;
+    g->block = (uint32_t)block;
+    g->R = (uint32_t)r;
+    g->replicate.clear();
+    for (u64 k = 1; k < r; k <<= 1) g->replicate.push_back((i64)(block * k));
+    g->reduce = reduce_steps(in, r > 1 ? block : slots);
+    return HISA_OK;
+}
+
+extern "C" int hisa_matmul_geometry(hisa_ctx* ctx, const hisa_tensor* in, uint32_t out_features, uint32_t replicas,
+                                    uint32_t* block, uint32_t* used_replicas, uint32_t* out_cts) {
+    if (!ctx) return HISA_ERR_ARG;
+    TRY(check_layout(ctx, in));
+    MatmulGeom g;
+    TRY(matmul_geom(ctx, in, replicas, &g));
+    if (block) *block = g.block;
+    if (used_replicas) *used_replicas = g.R;
+    if (out_cts) *out_cts = in->batch * ((out_features + g.R - 1) / g.R);
+    return HISA_OK;
+}
+
+extern "C" int hisa_matmul_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, uint32_t replicas, int32_t* steps, size_t cap,
+                                     size_t* n) {
+    if (!ctx) return HISA_ERR_ARG;
+    TRY(check_layout(ctx, in));
+    MatmulGeom g;
+    TRY(matmul_geom(ctx, in, replicas, &g));
+    std::vector<int32_t> all;
+    for (i64 r : g.replicate) all.push_back(norm_step(ctx, -r));
+    for (i64 r : g.reduce) all.push_back(norm_step(ctx, r));
+    return write_steps(all, steps, cap, n);
+}
+
+// x += rot(x, step) for a batch of ciphertexts, in place
+static int rotate_add_batch(hisa_ctx* ctx, std::vector<hisa_ct*>& xs, int32_t step) {
+    std::vector<hisa_ct*> rot(xs.size(), nullptr);
+    TRY(hisa_rot_left_batch(ctx, (const hisa_ct* const*)xs.data(), xs.size(), step, rot.data()));
+    const u64 words = ct_words(ctx, 2, xs[0]->limbs);
+    hipError_t e = launch_addsub(ctx->d_primes, xs[0]->data, rot[0]->data, xs[0]->data, OP_ADD, (int)xs[0]->limbs, 2, 2, xs.size(),
+                                 words, words, words, (int)ctx->log_n, ctx->stream);
+    free_handles(ctx, rot);
+    if (e != hipSuccess) return fail(ctx, HISA_ERR_HIP, "rotate-and-add: %s", hipGetErrorString(e));
+    return HISA_OK;
+}
+
+// masks: NTT-form plaintexts [per][l][N] (needed when R > 1 and the input is not clean), pts: [groups][per][l'][N] with
+// l' = l - 1 after the masking multiply, else l.
+static int matmul_run(hisa_ctx* ctx, const hisa_tensor* in, const MatmulGeom& g, const u64* masks, double mask_scale,
+                      const u64* pts, double pt_scale, uint32_t OUT, hisa_tensor* out) {
+    const uint32_t B = in->batch, per = (uint32_t)t_per(in), groups = (OUT + g.R - 1) / g.R;
+    uint32_t l = in->cts[0]->limbs;
+    const size_t n_in = (size_t)B * per, n = ctx->N;
+    const bool masked = g.R > 1 && !in->clean;
+    if (l < (masked ? 3u : 2u)) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "matmul needs %d levels to rescale into", masked ? 2 : 1);
+    if (masked && !masks) return fail(ctx, HISA_ERR_ARG, "the input is not clean: replicas need the mask");
+    std::vector<hisa_ct*> xs;     // working copies of the inputs (R > 1 only)
+    int rc = HISA_OK;
+    if (g.R > 1) {
+        xs.assign(n_in, nullptr);
+        BatchIn bi;
+        TRY(gather_batch(ctx, (const hisa_ct* const*)in->cts, n_in, &bi));
+        const u64 words = ct_words(ctx, 2, l);
+        rc = alloc_ct_batch(ctx, n_in, 2, l, in->cts[0]->scale * (masked ? mask_scale : 1.0), xs.data());
+        if (rc == HISA_OK) {
+            hipError_t e = hipSuccess;
+            if (masked) {
+                // ciphertext j of every image takes mask j (they differ only where a last ciphertext holds fewer channels)
+                for (uint32_t j = 0; j < per && e == hipSuccess; j++)
+                    e = launch_mul_plain(ctx->d_primes, bi.base + (u64)j * bi.stride, masks + (u64)j * l * n,
+                                         xs[0]->data + (u64)j * words, (int)l, 2, B, (u64)per * bi.stride, (u64)per * words,
+                                         (int)ctx->log_n, ctx->stream);
+            } else {
+                e = hipMemcpyAsync(xs[0]->data, bi.base, n_in * words * sizeof(u64), hipMemcpyDeviceToDevice, ctx->stream);
+            }
+            if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "matmul input: %s", hipGetErrorString(e));
+        }
+        dev_release(ctx, bi.tmp);
+        if (rc == HISA_OK && masked) {
+            rc = hisa_rescale_batch(ctx, xs.data(), n_in);
+            l -= 1;
+        }
+        for (size_t k = 0; k < g.replicate.size() && rc == HISA_OK; k++)
+            rc = rotate_add_batch(ctx, xs, norm_step(ctx, -g.replicate[k]));
+        if (rc != HISA_OK) { free_handles(ctx, xs); return rc; }
+    }
+    hisa_ct* const* src = g.R > 1 ? xs.data() : in->cts;
+    std::vector<hisa_ct*> outs((size_t)B * groups, nullptr);
+    BatchIn bi;
+    rc = gather_batch(ctx, (const hisa_ct* const*)src, n_in, &bi);
+    if (rc == HISA_OK) rc = alloc_ct_batch(ctx, outs.size(), 2, l, src[0]->scale * pt_scale, outs.data());
+    if (rc == HISA_OK) {
+        MacArgs ma = {};
+        ma.tap_base[0] = bi.base; ma.n_taps = 1; ma.IC = (int)per; ma.OC = (int)groups; ma.l = (int)l;
+        ma.ct_words = 2 * (u64)l * n;
+        ma.w = pts; ma.w_stride_t = 1; ma.w_stride_oc = per;
+        ma.out = outs[0]->data;
+        hipError_t e = ctx->tabs.fp_ok ? launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream)
+                                       : launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "matmul multiply-accumulate: %s", hipGetErrorString(e));
+    }
+    dev_release(ctx, bi.tmp);
+    free_handles(ctx, xs);
+    if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
+    for (size_t k = 0; k < g.reduce.size() && rc == HISA_OK; k++) rc = rotate_add_batch(ctx, outs, norm_step(ctx, g.reduce[k]));
+    if (rc != HISA_OK) {
+        free_handles(ctx, outs);
+        return rc;
+    }
+    for (size_t i = 0; i < outs.size(); i++) out->cts[i] = outs[i];
+    fill_out_meta(out, B, OUT, 1, 1, 1, 1, in->offset, 0, g.R, g.block);
+    return HISA_OK;
+}
+
+#define HISA_MAGIC_MMPLAN 0x4d4d5031u
+struct hisa_matmul_plan {
+    uint32_t magic;
+    uint32_t out_features, replicas;
+    uint32_t channels, height, width, h_stride, w_stride, offset, clean, c_inner, c_stride, limbs;   // built for this input
+    double pt_scale, mask_scale;
+    DevBlock* pts;     // [groups][per][l'][N]
+    DevBlock* masks;   // [per][l][N], or null
+};
+
+extern "C" int hisa_matmul_plan_free(hisa_ctx* ctx, hisa_matmul_plan* plan) {
+    if (!ctx || !plan || plan->magic != HISA_MAGIC_MMPLAN) return fail(ctx, HISA_ERR_ARG, "not a matmul plan");
+    if (plan->pts) dev_release(ctx, plan->pts);
+    if (plan->masks) dev_release(ctx, plan->masks);
+    plan->magic = 0;
+    delete plan;
+    return HISA_OK;
+}
+
+static hisa_matmul_plan* new_matmul_plan(const hisa_tensor* like, uint32_t OUT, uint32_t replicas) {
+    return new hisa_matmul_plan{HISA_MAGIC_MMPLAN, OUT, replicas, like->channels, like->height, like->width, like->h_stride,
+                                like->w_stride, like->offset, like->clean, t_ci(like), like->c_stride, like->cts[0]->limbs,
+                                1.0, 1.0, nullptr, nullptr};
+}
+
+extern "C" int hisa_matmul_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t OUT, uint32_t replicas,
+                                   hisa_matmul_plan** plan_out) {
+    if (!ctx || !w || !plan_out || OUT == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_tensor(ctx, like));
+    MatmulGeom g;
+    TRY(matmul_geom(ctx, like, replicas, &g));
+    const uint32_t ci = t_ci(like), per = (uint32_t)t_per(like), C = like->channels, groups = (OUT + g.R - 1) / g.R;
+    uint32_t l = like->cts[0]->limbs;
+    const bool masked = g.R > 1 && !like->clean;
+    if (l < (masked ? 3u : 2u)) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "matmul needs %d levels to rescale into", masked ? 2 : 1);
+    const size_t n = ctx->N, hw = (size_t)like->height * like->width, elems = (size_t)ci * hw;
+    const std::vector<uint32_t> slots = tensor_slots(like);
+    hisa_matmul_plan* p = new_matmul_plan(like, OUT, replicas);
+    int rc = HISA_OK;
+    if (masked) {   // 0/1 on the element slots at the scale of the modulus the divScalar removes: the scale is unchanged
+        p->mask_scale = (double)ctx->mod[l - 1];
+        p->masks = dev_alloc(ctx, (size_t)per * l * n * sizeof(u64));
+        if (!p->masks) rc = HISA_ERR_OOM;
+        std::vector<double> ones((size_t)per * elems, 0.0);
+        for (uint32_t j = 0; j < per; j++)
+            for (uint32_t c = 0; c < std::min(ci, C - j * ci); c++)
+                for (size_t k = 0; k < hw; k++) ones[((size_t)j * ci + c) * hw + k] = 1.0;
+        if (rc == HISA_OK) rc = encode_sparse_batch(ctx, slots, ones.data(), per, p->mask_scale, (int)l, (u64*)p->masks->ptr);
+        l -= 1;
+    }
+    if (rc == HISA_OK) {
+        p->pt_scale = (double)ctx->mod[l - 1];
+        p->pts = dev_alloc(ctx, (size_t)groups * per * l * n * sizeof(u64));
+        if (!p->pts) rc = HISA_ERR_OOM;
+    }
+    if (rc == HISA_OK) {
+        // plaintext (g, j): weight of output gR + r and channel j ci + c on element k of the r-th copy
+        std::vector<uint32_t> rslots;
+        for (uint32_t r = 0; r < g.R; r++)
+            for (uint32_t v : slots) rslots.push_back(r * g.block + v);
+        const size_t nnz = rslots.size();
+        const size_t chunk = std::max<size_t>(1, std::min<size_t>((size_t)groups * per, ((size_t)256 << 20) / (nnz * sizeof(double) + n * 8)));
+        std::vector<double> vals;
+        for (size_t p0 = 0; p0 < (size_t)groups * per && rc == HISA_OK; p0 += chunk) {
+            const size_t cnt = std::min(chunk, (size_t)groups * per - p0);
+            vals.assign(cnt * nnz, 0.0);
+            for (size_t q = 0; q < cnt; q++) {
+                const uint32_t gi = (uint32_t)((p0 + q) / per), j = (uint32_t)((p0 + q) % per);
+                for (uint32_t r = 0; r < g.R && gi * g.R + r < OUT; r++)
+                    for (uint32_t c = 0; c < std::min(ci, C - j * ci); c++)
+                        memcpy(&vals[q * nnz + ((size_t)r * ci + c) * hw], w + ((size_t)(gi * g.R + r) * C + j * ci + c) * hw,
+                               hw * sizeof(double));
+            }
+            rc = encode_sparse_batch(ctx, rslots, vals.data(), cnt, p->pt_scale, (int)l, (u64*)p->pts->ptr + p0 * l * n);
+        }
+    }
+    if (rc != HISA_OK) { hisa_matmul_plan_free(ctx, p); return rc; }
+    *plan_out = p;
+    return HISA_OK;
+}
+
+extern "C" int hisa_matmul_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_matmul_plan* plan, hisa_tensor* out) {
+    if (!ctx || !plan || plan->magic != HISA_MAGIC_MMPLAN) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
+    if (in->channels != plan->channels || in->height != plan->height || in->width != plan->width ||
+        in->h_stride != plan->h_stride || in->w_stride != plan->w_stride || in->offset != plan->offset ||
+        (in->clean != 0) != (plan->clean != 0) || t_ci(in) != plan->c_inner || (t_ci(in) > 1 && in->c_stride != plan->c_stride))
+        return fail(ctx, HISA_ERR_ARG, "the plan was prepared for another tensor layout");
+    if (in->cts[0]->limbs != plan->limbs)
+        return fail(ctx, HISA_ERR_LEVEL_MISMATCH, "the plan was prepared for %u limbs, the tensor has %u", plan->limbs,
+                    in->cts[0]->limbs);
+    MatmulGeom g;
+    TRY(matmul_geom(ctx, in, plan->replicas, &g));
+    return matmul_run(ctx, in, g, plan->masks ? (const u64*)plan->masks->ptr : nullptr, plan->mask_scale,
+                      (const u64*)plan->pts->ptr, plan->pt_scale, plan->out_features, out);
+}
+
+extern "C" int hisa_matmul(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t OUT, uint32_t replicas,
+                           hisa_tensor* out) {
+    hisa_matmul_plan* plan = nullptr;
+    TRY(hisa_matmul_prepare(ctx, in, w, OUT, replicas, &plan));
+    const int rc = hisa_matmul_apply(ctx, in, plan, out);
+    hisa_matmul_plan_free(ctx, plan);
+    return rc;
+}
+
+extern "C" int hisa_matmul_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* pt_coeffs, double pt_scale,
+                                 const int64_t* mask_coeffs, double mask_scale, uint32_t OUT, uint32_t replicas,
+                                 hisa_tensor* out) {
+    if (!ctx || !pt_coeffs || OUT == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
+    MatmulGeom g;
+    TRY(matmul_geom(ctx, in, replicas, &g));
+    const uint32_t per = (uint32_t)t_per(in), groups = (OUT + g.R - 1) / g.R;
+    uint32_t l = in->cts[0]->limbs;
+    const bool masked = g.R > 1 && !in->clean;
+    if (masked && !mask_coeffs) return fail(ctx, HISA_ERR_ARG, "the input is not clean: replicas need the mask");
+    if (l < (masked ? 3u : 2u)) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "matmul needs %d levels to rescale into", masked ? 2 : 1);
+    const size_t n = ctx->N;
+    Temp masks(ctx, masked ? (size_t)per * l * n * sizeof(u64) : 8);
+    if (!masks.ok()) return HISA_ERR_OOM;
+    if (masked) {
+        TRY(coeffs_to_plain_batch(ctx, mask_coeffs, per, (int)l, masks.u()));
+        l -= 1;
+    }
+    Temp pts(ctx, (size_t)groups * per * l * n * sizeof(u64));
+    if (!pts.ok()) return HISA_ERR_OOM;
+    TRY(coeffs_to_plain_batch(ctx, pt_coeffs, (size_t)groups * per, (int)l, pts.u()));
+    return matmul_run(ctx, in, g, masked ? masks.u() : nullptr, mask_scale, pts.u(), pt_scale, OUT, out);
+}
+
+// ---------------------------------------------------------------------------
 // pooling, activation
 // ---------------------------------------------------------------------------
 extern "C" int hisa_sum_pool2x2(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out) {
     TRY(check_tensor(ctx, in));
     if (!out || !out->cts || in->height < 2 || in->width < 2) return fail(ctx, HISA_ERR_ARG, "bad argument");
-    const size_t nct = (size_t)in->batch * in->channels;
+    const size_t nct = t_ncts(in);   // every channel of a ciphertext is pooled by the same three rotations
     const uint32_t l = in->cts[0]->limbs;
     const u64 words = ct_words(ctx, 2, l);
     std::vector<hisa_ct*> acc(nct, nullptr);
@@ -1057,14 +1367,15 @@ extern "C" int hisa_sum_pool2x2(hisa_ctx* ctx, const hisa_tensor* in, hisa_tenso
         return rc;
     }
     for (size_t i = 0; i < nct; i++) { acc[i]->scale = in->cts[i]->scale; out->cts[i] = acc[i]; }
-    fill_out_meta(out, in->batch, in->channels, in->height / 2, in->width / 2, in->h_stride * 2, in->w_stride * 2, in->offset, 0);
+    fill_out_meta(out, in->batch, in->channels, in->height / 2, in->width / 2, in->h_stride * 2, in->w_stride * 2, in->offset, 0,
+                  t_ci(in), in->c_stride);
     return HISA_OK;
 }
 
 extern "C" int hisa_poly2_act(hisa_ctx* ctx, const hisa_tensor* in, double a, double b, hisa_tensor* out) {
     TRY(check_tensor(ctx, in));
     if (!out || !out->cts || a == 0.0 || !isfinite(b / a)) return fail(ctx, HISA_ERR_ARG, "bad argument");
-    const size_t nct = (size_t)in->batch * in->channels;
+    const size_t nct = t_ncts(in);
     const uint32_t l = in->cts[0]->limbs;
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "activation needs a level to rescale into");
     std::vector<hisa_ct*> sq(nct, nullptr);
@@ -1099,7 +1410,8 @@ extern "C" int hisa_poly2_act(hisa_ctx* ctx, const hisa_tensor* in, double a, do
         return rc;
     }
     for (size_t i = 0; i < nct; i++) out->cts[i] = sq[i];
-    fill_out_meta(out, in->batch, in->channels, in->height, in->width, in->h_stride, in->w_stride, in->offset, in->clean);
+    fill_out_meta(out, in->batch, in->channels, in->height, in->width, in->h_stride, in->w_stride, in->offset, in->clean,
+                  t_ci(in), in->c_stride);
     return HISA_OK;
 }
 
@@ -1107,15 +1419,28 @@ extern "C" int hisa_poly2_act(hisa_ctx* ctx, const hisa_tensor* in, double a, do
 // tensor <-> host
 // ---------------------------------------------------------------------------
 extern "C" int hisa_tensor_encrypt(hisa_ctx* ctx, const double* x, double scale, uint32_t limbs, hisa_tensor* t) {
-    if (!ctx || !x || !t || !t->cts || t->batch == 0 || t->channels == 0 || limbs < 1 || limbs > ctx->L)
-        return fail(ctx, HISA_ERR_ARG, "bad argument");
-    const u64 last = (u64)t->offset + (u64)(t->height - 1) * t->h_stride + (u64)(t->width - 1) * t->w_stride;
-    if (t->height == 0 || t->width == 0 || last >= ctx->N / 2) return fail(ctx, HISA_ERR_ARG, "plane does not fit the slots");
-    const size_t nct = (size_t)t->batch * t->channels, n = ctx->N;
-    const std::vector<uint32_t> slots = plane_slots(t->height, t->width, t->h_stride, t->w_stride, t->offset);
+    if (!ctx || !x || limbs < 1 || limbs > ctx->L) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_layout(ctx, t));
+    const size_t nct = t_ncts(t), n = ctx->N, per = t_per(t), hw = (size_t)t->height * t->width;
+    const uint32_t ci = t_ci(t);
+    const std::vector<uint32_t> slots = tensor_slots(t);
+    {   // the elements of one ciphertext must not share slots
+        std::set<uint32_t> uniq(slots.begin(), slots.end());
+        if (uniq.size() != slots.size()) return fail(ctx, HISA_ERR_ARG, "tensor elements overlap in the slots");
+    }
+    // values per ciphertext, channel-major; a last ciphertext with fewer channels is padded with zeros
+    std::vector<double> packed;
+    const double* values = x;
+    if (ci > 1) {
+        packed.assign(nct * ci * hw, 0.0);
+        for (size_t b = 0; b < t->batch; b++)
+            for (size_t c = 0; c < t->channels; c++)
+                memcpy(&packed[((b * per + c / ci) * ci + c % ci) * hw], x + (b * t->channels + c) * hw, hw * sizeof(double));
+        values = packed.data();
+    }
     DevBlock* blk = dev_alloc(ctx, nct * limbs * n * sizeof(u64));
     if (!blk) return HISA_ERR_OOM;
-    int rc = encode_sparse_batch(ctx, slots, x, nct, scale, (int)limbs, (u64*)blk->ptr);
+    int rc = encode_sparse_batch(ctx, slots, values, nct, scale, (int)limbs, (u64*)blk->ptr);
     std::vector<hisa_pt*> pts(nct, nullptr);
     if (rc == HISA_OK) {
         blk->refs = (int)nct + 1;
@@ -1132,9 +1457,10 @@ extern "C" int hisa_tensor_encrypt(hisa_ctx* ctx, const double* x, double scale,
 extern "C" int hisa_tensor_decrypt(hisa_ctx* ctx, const hisa_tensor* t, double* x) {
     TRY(check_tensor(ctx, t));
     if (!x) return fail(ctx, HISA_ERR_ARG, "null output");
-    const size_t nct = (size_t)t->batch * t->channels, hw = (size_t)t->height * t->width;
-    const std::vector<uint32_t> slots = plane_slots(t->height, t->width, t->h_stride, t->w_stride, t->offset);
-    const size_t count = (size_t)slots.back() + 1;
+    const size_t nct = t_ncts(t), per = t_per(t), hw = (size_t)t->height * t->width;
+    const uint32_t ci = t_ci(t);
+    const std::vector<uint32_t> slots = tensor_slots(t);
+    const size_t count = (size_t)*std::max_element(slots.begin(), slots.end()) + 1;
     std::vector<double> re(count);
     for (size_t i = 0; i < nct; i++) {
         hisa_pt* pt = nullptr;
@@ -1142,7 +1468,9 @@ extern "C" int hisa_tensor_decrypt(hisa_ctx* ctx, const hisa_tensor* t, double* 
         int rc = hisa_decode(ctx, pt, re.data(), nullptr, count);
         hisa_free(ctx, pt);
         if (rc != HISA_OK) return rc;
-        for (size_t k = 0; k < hw; k++) x[i * hw + k] = re[slots[k]];
+        const size_t b = i / per, c0 = (i % per) * ci;
+        for (size_t c = c0; c < std::min<size_t>(c0 + ci, t->channels); c++)
+            for (size_t k = 0; k < hw; k++) x[(b * t->channels + c) * hw + k] = re[slots[(c - c0) * hw + k]];
     }
     return HISA_OK;
 }
@@ -1150,7 +1478,7 @@ extern "C" int hisa_tensor_decrypt(hisa_ctx* ctx, const hisa_tensor* t, double* 
 extern "C" int hisa_tensor_free(hisa_ctx* ctx, hisa_tensor* t) {
     if (!ctx || !t) return HISA_ERR_ARG;
     if (t->cts)
-        for (size_t i = 0; i < (size_t)t->batch * t->channels; i++) {
+        for (size_t i = 0; i < t_ncts(t); i++) {
             hisa_free(ctx, t->cts[i]);
             t->cts[i] = nullptr;
         }

@@ -38,7 +38,7 @@ class Params(C.Structure):
 class TensorStruct(C.Structure):
     _fields_ = [("batch", C.c_uint32), ("channels", C.c_uint32), ("height", C.c_uint32), ("width", C.c_uint32),
                 ("h_stride", C.c_uint32), ("w_stride", C.c_uint32), ("offset", C.c_uint32), ("clean", C.c_uint32),
-                ("cts", C.POINTER(C.c_void_p))]
+                ("c_inner", C.c_uint32), ("c_stride", C.c_uint32), ("cts", C.POINTER(C.c_void_p))]
 
 
 class ConvGeom(C.Structure):
@@ -368,11 +368,12 @@ class Context:
                                      C.c_size_t(n_polys), C.c_int(1 if inverse else 0)))
 
     # ---- tensor layer ----
-    def tensor_encrypt(self, x, scale, limbs, h_stride=None, w_stride=1, offset=0):
-        """x[batch][channels][height][width] -> clean HW-tiled CipherTensor."""
+    def tensor_encrypt(self, x, scale, limbs, h_stride=None, w_stride=1, offset=0, c_inner=1, c_stride=0):
+        """x[batch][channels][height][width] -> clean CipherTensor, HW-tiled or (c_inner > 1) CHW-tiled."""
         x = np.ascontiguousarray(x, dtype=np.float64)
         b, c, h, w = x.shape
-        t = CipherTensor(self, [None] * (b * c), b, c, h, w, h_stride if h_stride else w * w_stride, w_stride, offset, 1)
+        t = CipherTensor(self, [None] * (b * -(-c // c_inner)), b, c, h, w, h_stride if h_stride else w * w_stride, w_stride,
+                         offset, 1, c_inner, c_stride)
         st, arr = t._struct()
         self._ck(load().hisa_tensor_encrypt(self._vp, _dp(x), C.c_double(scale), C.c_uint32(limbs), C.byref(st)))
         t._adopt(st, arr)
@@ -386,7 +387,7 @@ class Context:
 
     def _layer(self, fn, t, n_out_cts, *args):
         st, _arr = t._struct()
-        out = CipherTensor(self, [None] * n_out_cts, 0, 0, 0, 0, 0, 0, 0, 0)
+        out = CipherTensor(self, [None] * n_out_cts, 0, 0, 0, 0, 0, 0, 0, 0, 1, 0)
         ost, oarr = out._struct()
         self._ck(getattr(load(), fn)(self._vp, C.byref(st), *args, C.byref(ost)))
         out._adopt(ost, oarr)
@@ -456,11 +457,59 @@ class Context:
         return self._layer("hisa_fc_fixed", t, t.batch * out_features, pc.ctypes.data_as(C.POINTER(C.c_int64)),
                            C.c_double(pt_scale), C.c_uint32(out_features))
 
+    def matmul_geometry(self, t, out_features, replicas):
+        """(block length P, replicas used R, number of output ciphertexts) of matmul on tensors laid out like t."""
+        st, _arr = t._struct()
+        block, used, n_out = C.c_uint32(), C.c_uint32(), C.c_uint32()
+        self._ck(load().hisa_matmul_geometry(self._vp, C.byref(st), C.c_uint32(out_features), C.c_uint32(replicas),
+                                             C.byref(block), C.byref(used), C.byref(n_out)))
+        return block.value, used.value, n_out.value
+
+    def matmul(self, t, w, replicas):
+        """Homomorphic matmul with replicas: w[OUT][C][H][W] -> CHW-tiled tensor of OUT 1x1 channels."""
+        w = np.ascontiguousarray(w, dtype=np.float64)
+        out_features = w.shape[0]
+        assert w.size == out_features * t.channels * t.height * t.width
+        n_out = self.matmul_geometry(t, out_features, replicas)[2]
+        return self._layer("hisa_matmul", t, n_out, _dp(w), C.c_uint32(out_features), C.c_uint32(replicas))
+
+    def matmul_fixed(self, t, pt_coeffs, pt_scale, mask_coeffs, mask_scale, out_features, replicas):
+        i64p = C.POINTER(C.c_int64)
+        pc = np.ascontiguousarray(pt_coeffs, dtype=np.int64)
+        mc = np.ascontiguousarray(mask_coeffs, dtype=np.int64) if mask_coeffs is not None else None
+        _block, used, n_out = self.matmul_geometry(t, out_features, replicas)
+        per = -(-t.channels // t.c_inner)
+        assert pc.shape == (-(-out_features // used), per, self.N) and (mc is None or mc.shape == (per, self.N))
+        return self._layer("hisa_matmul_fixed", t, n_out, pc.ctypes.data_as(i64p), C.c_double(pt_scale),
+                           mc.ctypes.data_as(i64p) if mc is not None else None, C.c_double(mask_scale),
+                           C.c_uint32(out_features), C.c_uint32(replicas))
+
+    def matmul_prepare(self, like, w, replicas):
+        """Encodes matmul weights once for tensors laid out like `like`; returns a plan for matmul_apply (free with
+        matmul_plan_free)."""
+        w = np.ascontiguousarray(w, dtype=np.float64)
+        out_features = w.shape[0]
+        assert w.size == out_features * like.channels * like.height * like.width
+        st, _arr = like._struct()
+        plan = C.c_void_p()
+        self._ck(load().hisa_matmul_prepare(self._vp, C.byref(st), _dp(w), C.c_uint32(out_features), C.c_uint32(replicas),
+                                            C.byref(plan)))
+        return (plan, self.matmul_geometry(like, out_features, replicas)[2] // like.batch)
+
+    def matmul_apply(self, t, plan):
+        return self._layer("hisa_matmul_apply", t, t.batch * plan[1], plan[0])
+
+    def matmul_plan_free(self, plan):
+        self._ck(load().hisa_matmul_plan_free(self._vp, plan[0]))
+
+    def matmul_rot_steps(self, t, replicas):
+        return self._steps("hisa_matmul_rot_steps", t, C.c_uint32(replicas))
+
     def sum_pool2x2(self, t):
-        return self._layer("hisa_sum_pool2x2", t, t.batch * t.channels)
+        return self._layer("hisa_sum_pool2x2", t, len(t.cts))
 
     def poly2_act(self, t, a, b):
-        return self._layer("hisa_poly2_act", t, t.batch * t.channels, C.c_double(a), C.c_double(b))
+        return self._layer("hisa_poly2_act", t, len(t.cts), C.c_double(a), C.c_double(b))
 
     def _steps(self, fn, t, *args):
         st, _arr = t._struct()
@@ -504,15 +553,18 @@ class Context:
 
 
 class CipherTensor:
-    """Vector of ciphertexts + layout metadata (the paper's CipherTensor, HW-tiled)."""
+    """Vector of ciphertexts + layout metadata (the paper's CipherTensor; HW-tiled when c_inner == 1, CHW-tiled with
+    c_inner channels per ciphertext, c_stride slots apart, otherwise)."""
 
-    def __init__(self, ctx, cts, batch, channels, height, width, h_stride, w_stride, offset, clean):
+    def __init__(self, ctx, cts, batch, channels, height, width, h_stride, w_stride, offset, clean, c_inner=1, c_stride=0):
         self.ctx, self.cts = ctx, cts
         self.batch, self.channels, self.height, self.width = batch, channels, height, width
         self.h_stride, self.w_stride, self.offset, self.clean = h_stride, w_stride, offset, clean
+        self.c_inner, self.c_stride = max(1, c_inner), c_stride
 
     def meta(self):
-        return (self.batch, self.channels, self.height, self.width, self.h_stride, self.w_stride, self.offset, self.clean)
+        return (self.batch, self.channels, self.height, self.width, self.h_stride, self.w_stride, self.offset, self.clean,
+                self.c_inner, self.c_stride)
 
     def shaped_like(self, cts=None, **kw):
         t = CipherTensor(self.ctx, self.cts if cts is None else cts, *self.meta())
@@ -524,12 +576,13 @@ class CipherTensor:
         n = len(self.cts)
         arr = (C.c_void_p * n)(*[(c.h if c is not None else None) for c in self.cts])
         st = TensorStruct(self.batch, self.channels, self.height, self.width, self.h_stride, self.w_stride, self.offset,
-                          self.clean, C.cast(arr, C.POINTER(C.c_void_p)))
+                          self.clean, self.c_inner, self.c_stride, C.cast(arr, C.POINTER(C.c_void_p)))
         return st, arr
 
     def _adopt(self, st, arr):
         self.batch, self.channels, self.height, self.width = st.batch, st.channels, st.height, st.width
         self.h_stride, self.w_stride, self.offset, self.clean = st.h_stride, st.w_stride, st.offset, st.clean
+        self.c_inner, self.c_stride = max(1, st.c_inner), st.c_stride
         self.cts = [Ciphertext(self.ctx, int(arr[i])) for i in range(len(arr))]
 
     def free(self):

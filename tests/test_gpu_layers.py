@@ -39,7 +39,9 @@ def both_tensors(g, o, x, scale, limbs, **layout):
 
 
 def same_tensor(g, o, gt, ot):
-    assert gt.meta() == (ot.batch, ot.channels, ot.height, ot.width, ot.h_stride, ot.w_stride, ot.offset, ot.clean)
+    assert gt.meta() == (ot.batch, ot.channels, ot.height, ot.width, ot.h_stride, ot.w_stride, ot.offset, ot.clean,
+                         ot.c_inner, ot.c_stride if ot.c_inner > 1 else gt.c_stride)
+    assert len(gt.cts) == len(ot.cts)
     for gc, oc in zip(gt.cts, ot.cts):
         assert np.array_equal(g.ct_export(gc), o.export(oc))
         assert abs(gc.scale - oc.scale) <= 1e-12 * oc.scale
@@ -193,4 +195,108 @@ def test_layer_error_paths():
     with pytest.raises(hisa.HisaError) as e:
         g.conv2d(out, w, 3, 3, pad_same=True)             # SAME needs a clean input; SCALAR output is not
     assert e.value.code == -1
+    g.close()
+
+
+def test_matmul_with_replicas_bit_exact():
+    """Homomorphic matmul with replicas through the C ABI against the oracle, bit for bit: a batch of two images, a
+    pooled (not clean) HW-tiled input that needs the masking multiply, 10 outputs in ragged groups of 4, then the
+    activation and a second matmul on the CHW-tiled result; the plan and the float entry point besides."""
+    from oracle import layers
+    from paper_1810_00845_amd import synth
+    g, o = make_pair(11, [50, 45, 45, 45, 45, 45], 3, 55, 12)
+    g.keygen(); o.keygen()
+    x = synth.image(21, 3, 4, 4)[None].repeat(2, axis=0) * np.array([1.0, -0.5])[:, None, None, None]
+    gt, ot = both_tensors(g, o, x, 2.0 ** 45, 6)
+    g.gen_rot_keys([1, 4, 5]); o.gen_rot_keys([1, 4, 5])
+    gp, op = g.sum_pool2x2(gt), layers.sum_pool2x2(o, ot)
+    same_tensor(g, o, gp, op)
+    ref = plain_net.sum_pool2x2(x)
+    assert g.matmul_geometry(gp, 10, 4) == (16, 4, 2 * 3) and layers.matmul_geometry(o, op, 4)[:2] == (16, 4)
+    steps = g.matmul_rot_steps(gp, 4)
+    assert steps == sorted([2, 8, o.slots - 16, o.slots - 32])
+    g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+    w1 = synth.fc_weights(22, 10, 3, 2, 2, std=0.3)
+    om, ints = layers.matmul(o, op, w1, 4)
+    gm = g.matmul_fixed(gp, ints["pt_coeffs"], ints["pt_scale"], ints["mask_coeffs"], ints["mask_scale"], 10, 4)
+    same_tensor(g, o, gm, om)
+    ref1 = plain_net.fc(ref, w1)
+    assert np.abs(g.tensor_decrypt(gm) - ref1).max() <= 1e-3
+    gfloat = g.matmul(gp, w1, 4)                                # encodes weights and mask on the GPU
+    assert gfloat.meta() == gm.meta()
+    assert np.abs(g.tensor_decrypt(gfloat) - ref1).max() <= 1e-3
+    plan = g.matmul_prepare(gp, w1, 4)
+    gplan = g.matmul_apply(gp, plan)
+    for ca, cb in zip(gfloat.cts, gplan.cts):
+        assert np.array_equal(g.ct_export(ca), g.ct_export(cb)) and ca.scale == cb.scale
+    g.matmul_plan_free(plan)
+    # without replicas: the FC layer, bit for bit
+    g0, gf = g.matmul(gp, w1, 1), g.fc(gp, w1)
+    assert g0.c_inner == 1 and len(g0.cts) == 20
+    for ca, cb in zip(g0.cts, gf.cts):
+        assert np.array_equal(g.ct_export(ca), g.ct_export(cb))
+    # activation on the CHW-tiled tensor, then a matmul that reads it
+    ga, oa = g.poly2_act(gm, 0.5, 0.25), layers.poly2_act(o, om, 0.5, 0.25)
+    same_tensor(g, o, ga, oa)
+    steps = g.matmul_rot_steps(ga, 2)
+    assert steps == sorted([16, 32, o.slots - 64])
+    g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+    w2 = synth.fc_weights(23, 3, 10, 1, 1, std=0.4)
+    o2, ints = layers.matmul(o, oa, w2, 2)
+    g2 = g.matmul_fixed(ga, ints["pt_coeffs"], ints["pt_scale"], ints["mask_coeffs"], ints["mask_scale"], 3, 2)
+    same_tensor(g, o, g2, o2)
+    want = plain_net.fc(plain_net.poly2_act_without_a(ref1, 0.5, 0.25), w2)
+    assert np.abs(g.tensor_decrypt(g2) - want).max() <= 1e-3
+    assert np.abs(g.tensor_decrypt(g.matmul(ga, w2, 2)) - want).max() <= 1e-3
+    g.close()
+
+
+def test_chw_tensor_layers_and_errors():
+    """CHW-tiled tensors through encrypt / decrypt / pool / activation / matmul (clean input: no mask, one level),
+    a last ciphertext with fewer channels, and the error paths: conv2d and fc refuse CHW tiling, overlapping
+    elements and a missing level are reported."""
+    from oracle import layers
+    from paper_1810_00845_amd import hisa, synth
+    g, o = make_pair(10, [50, 40, 40], 3, 55, 13)
+    x = synth.image(31, 5, 4, 4)[None]
+    gt = g.tensor_encrypt(x, 2.0 ** 40, 3, h_stride=4, c_inner=2, c_stride=16)
+    assert len(gt.cts) == 3 and gt.clean == 1 and (gt.c_inner, gt.c_stride) == (2, 16)
+    assert np.abs(g.tensor_decrypt(gt) - x).max() <= 1e-6
+    # the same tensor on both sides, from the oracle's encodings
+    ot = layers.tensor_encrypt_chw(o, x, 2.0 ** 40, 3, 2, 16, h_stride=4)
+    gcs = []
+    g.set_enc_counter(700); o.enc_counter = 700
+    sl = np.asarray(layers.tensor_slots(ot)).reshape(2, 16)
+    ocs = []
+    for j in range(3):
+        z = np.zeros(o.slots)
+        for cl in range(min(2, 5 - 2 * j)):
+            z[sl[cl]] = x[0, 2 * j + cl].reshape(-1)
+        co = o.encode_coeffs(z, 2.0 ** 40)
+        ocs.append(o.encrypt(o.pt_from_coeffs(co, 2.0 ** 40, 3)))
+        gcs.append(g.encrypt(g.pt_from_coeffs(co, 2.0 ** 40, 3)))
+    ot.cts = ocs
+    gt2 = hisa.CipherTensor(g, gcs, 1, 5, 4, 4, 4, 1, 0, 1, 2, 16)
+    same_tensor(g, o, gt2, ot)
+    steps = sorted(set(g.pool_rot_steps(gt2)) | set(g.matmul_rot_steps(gt2, 1 << 20)))
+    g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+    w = synth.fc_weights(32, 4, 5, 4, 4, std=0.3)
+    om, ints = layers.matmul(o, ot, w, 1 << 20)
+    assert ints["mask_coeffs"] is None
+    gm = g.matmul_fixed(gt2, ints["pt_coeffs"], ints["pt_scale"], None, 1.0, 4, 1 << 20)
+    same_tensor(g, o, gm, om)
+    assert gm.cts[0].limbs == 2 and np.abs(g.tensor_decrypt(gm) - plain_net.fc(x, w)).max() <= 1e-3
+    gp, op = g.sum_pool2x2(gt2), layers.sum_pool2x2(o, ot)
+    same_tensor(g, o, gp, op)
+    assert np.abs(g.tensor_decrypt(gp) - plain_net.sum_pool2x2(x)).max() <= 1e-3
+    # errors
+    with pytest.raises(hisa.HisaError):
+        g.conv2d(gt2, synth.conv_weights(1, 3, 3, 5, 2), 3, 3)
+    with pytest.raises(hisa.HisaError):
+        g.fc(gt2, w)
+    with pytest.raises(hisa.HisaError):                          # channels 8 slots apart overlap 4x4 planes
+        g.tensor_encrypt(x, 2.0 ** 40, 3, h_stride=4, c_inner=2, c_stride=8)
+    with pytest.raises(hisa.HisaError):                          # one level left, the masked form needs two
+        g.rescale_batch(gp.cts)
+        g.matmul(gp, w[:, :, :2, :2], 2)
     g.close()
