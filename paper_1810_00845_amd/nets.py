@@ -8,7 +8,8 @@ linear layer) are multiplied into the next layer's weights here, on the host, be
     ("conv", w[FH][FW][IC][OC], stride)      VALID convolution, Algorithm 1 with scalar weights
     ("act", a, b)                            a x^2 + b x
     ("pool",)                                2x2 average pool
-    ("fc", w[OUT][C][H][W])                  fully connected over the whole tensor
+    ("fc", w[OUT][C][H][W])                  fully connected over the whole tensor (with layout "chw_fc": homomorphic
+                                             matmul with replicas, CHW-tiled from there on)
     ("conv_same", w[FH][FW][IC][OC])         SAME convolution with the masking multiply (clean output)
     ("fire", ws, w1, w3, a, b)               SqueezeNet fire module: 1x1 squeeze, activation, 1x1 and 3x3 (SAME)
                                              expand convolutions whose outputs are concatenated along the channels
@@ -88,12 +89,19 @@ def _concat_channels(ctx, a, b):
     return t
 
 
-def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans=None):
+LAYOUTS = ("hw", "chw_fc")
+
+
+def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans=None, layout="hw"):
     """Encrypts x, runs the layers, decrypts.  Returns (output array, seconds from encrypt-done to the last
     ciphertext ready, per-layer seconds).  With make_keys the rotation keys each layer asks for are generated
     on the way (set-up pass); otherwise they must be resident.  `plans` (a dict, filled by the set-up pass and
     reused afterwards) holds the layers' weights converted and encoded ahead of time; without it that is done
-    inside every call."""
+    inside every call.  layout: "hw" keeps one channel per ciphertext throughout; "chw_fc" (the paper's "CHW-fc and
+    HW-before", Sec. "Data Layout Selection") is HW-tiled up to the first fully connected layer, which runs as a
+    matmul with as many replicas as the slots hold and leaves a CHW-tiled tensor for the layers after it."""
+    assert layout in LAYOUTS
+    replicas = 1 << 30 if layout == "chw_fc" else 1
     if border:   # leave `border` rows and columns of zero slots around every plane (SAME convolutions need them)
         hs = x.shape[3] + 2 * border
         t = ctx.tensor_encrypt(x, scale, limbs, h_stride=hs, offset=border * hs + border)
@@ -103,7 +111,17 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
     t_start = time.perf_counter()
     per_layer = []
     pending = 1.0     # constant factor the previous layers left to the next linear layer
-    def fully_connected(idx, t, w):
+    def fully_connected(idx, t, w, replicas=1):
+        if replicas > 1 or t.c_inner > 1:
+            if make_keys:
+                ctx.gen_rot_keys(ctx.matmul_rot_steps(t, replicas))
+            if plans is None:
+                return ctx.matmul(t, w, replicas)
+            if idx not in plans:
+                plans[idx] = ("matmul", ctx.matmul_prepare(t, w, replicas))
+            return ctx.matmul_apply(t, plans[idx][1])
+        if make_keys and t.height * t.width > 1:
+            ctx.gen_rot_keys(ctx.fc_rot_steps(t))
         if plans is None or t.height * t.width == 1:
             return ctx.fc(t, w)
         if idx not in plans:
@@ -161,15 +179,11 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             for k in range(c):
                 w[k, k] = pending / hw
             pending = 1.0
-            if make_keys:
-                ctx.gen_rot_keys(ctx.fc_rot_steps(t))
             nxt = fully_connected(idx, t, w)
         elif kind == "fc":
             w = layer[1] * pending
             pending = 1.0
-            if make_keys and t.height * t.width > 1:
-                ctx.gen_rot_keys(ctx.fc_rot_steps(t))
-            nxt = fully_connected(idx, t, w)
+            nxt = fully_connected(idx, t, w, replicas)
         else:
             raise ValueError(kind)
         t.free()
@@ -186,6 +200,8 @@ def free_plans(ctx, plans):
     for kind, plan in plans.values():
         if kind == "fc":
             ctx.fc_plan_free(plan)
+        elif kind == "matmul":
+            ctx.matmul_plan_free(plan)
         else:
             ctx.conv_plan_free(plan)
     plans.clear()

@@ -57,3 +57,27 @@ def test_network_matches_plaintext(name):
     assert np.abs(got3 - want).max() <= 1e-3
     nets.free_plans(ctx, plans)
     ctx.close()
+
+
+@pytest.mark.parametrize("name", ["lenet_small", "lenet_medium"])
+def test_network_chw_fc_layout_matches_plaintext(name):
+    """The layout "CHW-fc and HW-before" of Sec. "Data Layout Selection": HW-tiled convolutions, the first fully
+    connected layer as a matmul with replicas, CHW-tiled after it.  Same networks, same tolerance."""
+    from paper_1810_00845_amd import hisa, nets
+    params, layers, x = getattr(nets, name)()
+    want = plain_forward(layers, x)
+    ctx = hisa.Context(params["log_n"], params["q_bits"], params["dnum"], params["special_bits"], seed=11)
+    ctx.keygen()
+    limbs = len(params["q_bits"])
+    plans = {}
+    got, _, _ = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, make_keys=True, plans=plans, layout="chw_fc")
+    err = np.abs(got - want).max()
+    print(name, "chw_fc max abs error", err, flush=True)
+    assert err <= 1e-3
+    got2, latency, per_layer = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, plans=plans, layout="chw_fc")
+    print(name, "chw_fc latency %.4f s" % latency, [(k, round(s, 4)) for k, s in per_layer], flush=True)
+    assert np.abs(got2 - want).max() <= 1e-3
+    got3, _, _ = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, layout="chw_fc")   # without plans
+    assert np.abs(got3 - want).max() <= 1e-3
+    nets.free_plans(ctx, plans)
+    ctx.close()
