@@ -190,6 +190,33 @@ int hisa_encrypt_batch(hisa_ctx* ctx, const hisa_pt* const* pts, size_t n, hisa_
  * indistinguishable from encryptions. */
 int hisa_ct_random_batch(hisa_ctx* ctx, size_t n, uint32_t limbs, double scale, uint64_t counter, hisa_ct** out);
 
+/* ---- analysis backend (Sec. "Compiler": the analyser executes the circuit on a
+ * HISA backend that records instead of computing; used for the rotation-key
+ * selection, the depth a circuit needs and the operation counts of the layout
+ * cost model) ----
+ * Between hisa_analysis_begin and hisa_analysis_end every call on this context
+ * is a dry run: no kernel is launched, handles are still allocated and carry
+ * their level and scale as in a real run (their contents are undefined), a
+ * rotation whose key is missing is recorded instead of failing, and the
+ * relinearisation key is not needed.  hisa_analysis_end leaves the mode and
+ * returns what was recorded: the operation counts (in ciphertext operations;
+ * the multiply-accumulate kernels of the layers count one multiply per term),
+ * the lowest limb count any ciphertext reached, and the sorted left-rotation
+ * amounts that needed a key (at most cap of them into host rot_steps, the count
+ * into *n; rot_steps may be null).  Handles made during the analysis stay valid
+ * handles and are freed as usual.  Not re-entrant: begin while already in
+ * analysis mode, or end outside it, is HISA_ERR_ARG.  One context per thread at
+ * a time may be in analysis mode. */
+typedef struct {
+    uint64_t rot_left;     /* key-switched rotations (rotRight counts here too) */
+    uint64_t rot_shared;   /* of those, rotations that reused another rotation's decomposition */
+    uint64_t relinearize, mul, mul_plain, mul_scalar, add, rescale;
+    uint32_t min_limbs;    /* 0 if no ciphertext was made */
+    uint32_t reserved;
+} hisa_op_counts;
+int hisa_analysis_begin(hisa_ctx* ctx);
+int hisa_analysis_end(hisa_ctx* ctx, hisa_op_counts* counts, int32_t* rot_steps, size_t cap, size_t* n);
+
 /* ---- tensor layer (Sec. "Runtime": CipherTensor, HW- and CHW-tiling, Algorithm 1) ----
  * A CipherTensor is a vector of ciphertexts plus plain-integer metadata.
  * HW-tiling (c_inner = 1): the outer (batch, channel) dimensions index

@@ -44,6 +44,7 @@ __global__ __launch_bounds__(NT) void sample_uniform_kernel(const PrimeConst* pr
 
 hipError_t launch_sample_uniform(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, const PolyMap& map, int n_polys,
                                  u64 batch_stride, u64 ctr_step, u64* out, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, n_polys);
     ProfScope prof__("sample_uniform_kernel", st);
     hipLaunchKernelGGL(sample_uniform_kernel, grid, dim3(NT), 0, st, primes, seed, kind, ctr, map, batch_stride, ctr_step,
@@ -86,6 +87,7 @@ __global__ __launch_bounds__(NT) void sample_small_kernel(const PrimeConst* prim
 hipError_t launch_sample_small(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, int noise_on, int ternary,
                                const PolyMap& map, int n_polys, u64 batch_stride, u64 ctr_step, u64* out, i64* raw,
                                int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, n_polys);  // n_polys = batch entries here
     ProfScope prof__("sample_small_kernel", st);
     hipLaunchKernelGGL(sample_small_kernel, grid, dim3(NT), 0, st, primes, seed, kind, ctr, noise_on, ternary, map,
@@ -114,6 +116,8 @@ __global__ __launch_bounds__(NT) void addsub_kernel(const PrimeConst* primes, co
 
 hipError_t launch_addsub(const PrimeConst* primes, const u64* a, const u64* b, u64* out, int op, int limbs, int polys_a,
                          int polys_b, u64 n_batch, u64 a_bs, u64 b_bs, u64 o_bs, int log_n, hipStream_t st) {
+    if (t_analysis) t_analysis->c.add += n_batch;
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, limbs * polys_a, (unsigned)n_batch);
     ProfScope prof__("addsub_kernel", st);
     hipLaunchKernelGGL(addsub_kernel, grid, dim3(NT), 0, st, primes, a, b, out, op, limbs, polys_a, polys_b, a_bs, b_bs,
@@ -140,6 +144,8 @@ __global__ __launch_bounds__(NT) void add_const_kernel(const PrimeConst* primes,
 
 hipError_t launch_add_const(const PrimeConst* primes, const u64* a, u64* out, const u64* consts, int op, int limbs,
                             int polys, int log_n, hipStream_t st) {
+    if (t_analysis) t_analysis->c.add += (uint64_t)(polys + 1) / 2;
+    DRY_RUN_RETURN();
     LimbConsts c = {};
     for (int i = 0; i < limbs; i++) c.v[i] = consts[i];
     dim3 grid((1u << log_n) / NT, limbs * polys);
@@ -162,6 +168,8 @@ __global__ __launch_bounds__(NT) void mul_plain_kernel(const PrimeConst* primes,
 
 hipError_t launch_mul_plain(const PrimeConst* primes, const u64* a, const u64* pt, u64* out, int limbs, int polys,
                             u64 n_batch, u64 a_bs, u64 o_bs, int log_n, hipStream_t st) {
+    if (t_analysis) t_analysis->c.mul_plain += n_batch;
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, limbs * polys, (unsigned)n_batch);
     ProfScope prof__("mul_plain_kernel", st);
     hipLaunchKernelGGL(mul_plain_kernel, grid, dim3(NT), 0, st, primes, a, pt, out, limbs, a_bs, o_bs, log_n);
@@ -179,6 +187,8 @@ __global__ __launch_bounds__(NT) void mul_const_kernel(const PrimeConst* primes,
 
 hipError_t launch_mul_const(const PrimeConst* primes, const u64* a, u64* out, const u64* consts, int limbs, int polys,
                             int log_n, hipStream_t st) {
+    if (t_analysis) t_analysis->c.mul_scalar += (uint64_t)(polys + 1) / 2;
+    DRY_RUN_RETURN();
     // consts: [limbs] values followed by [limbs] Shoup companions
     LimbConsts c = {};
     for (int i = 0; i < limbs; i++) { c.v[i] = consts[i]; c.v_sh[i] = consts[limbs + i]; }
@@ -209,6 +219,8 @@ __global__ __launch_bounds__(NT) void mul_no_relin_kernel(const PrimeConst* prim
 
 hipError_t launch_mul_no_relin(const PrimeConst* primes, const u64* a, const u64* b, u64* out, int limbs, u64 n_batch,
                                u64 a_bs, u64 b_bs, u64 o_bs, int log_n, hipStream_t st) {
+    if (t_analysis) t_analysis->c.mul += n_batch;
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, limbs, (unsigned)n_batch);
     ProfScope prof__("mul_no_relin_kernel", st);
     hipLaunchKernelGGL(mul_no_relin_kernel, grid, dim3(NT), 0, st, primes, a, b, out, limbs, a_bs, b_bs, o_bs, log_n);
@@ -233,6 +245,7 @@ __global__ __launch_bounds__(NT) void encrypt_combine_kernel(const PrimeConst* p
 
 hipError_t launch_encrypt_combine(const PrimeConst* primes, const u64* secret, const u64* pt, const u64* e, u64* ct,
                                   int limbs, u64 n_batch, u64 pt_bs, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, limbs, (unsigned)n_batch);
     ProfScope prof__("encrypt_combine_kernel", st);
     hipLaunchKernelGGL(encrypt_combine_kernel, grid, dim3(NT), 0, st, primes, secret, pt, e, ct, limbs, pt_bs, log_n);
@@ -257,6 +270,7 @@ __global__ __launch_bounds__(NT) void decrypt_kernel(const PrimeConst* primes, c
 
 hipError_t launch_decrypt(const PrimeConst* primes, const u64* secret, const u64* ct, u64* pt, int limbs, int polys,
                           int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, limbs);
     ProfScope prof__("decrypt_kernel", st);
     hipLaunchKernelGGL(decrypt_kernel, grid, dim3(NT), 0, st, primes, secret, ct, pt, limbs, polys, log_n);
@@ -281,6 +295,7 @@ __global__ __launch_bounds__(NT) void key_combine_kernel(const PrimeConst* prime
 hipError_t launch_key_combine(const PrimeConst* primes, const u64* secret, const u64* target, const u64* e,
                               const u64* pmod_all, u64* key_digit, int total, int L, int alpha, int digit, int log_n,
                               hipStream_t st) {
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, total);
     ProfScope prof__("key_combine_kernel", st);
     hipLaunchKernelGGL(key_combine_kernel, grid, dim3(NT), 0, st, primes, secret, target, e, pmod_all, key_digit, total, L,
@@ -296,6 +311,7 @@ __global__ __launch_bounds__(NT) void square_kernel(const PrimeConst* primes, co
 }
 
 hipError_t launch_pointwise_square(const PrimeConst* primes, const u64* s, u64* out, int total, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, total);
     ProfScope prof__("square_kernel", st);
     hipLaunchKernelGGL(square_kernel, grid, dim3(NT), 0, st, primes, s, out, log_n);
@@ -317,6 +333,7 @@ __global__ __launch_bounds__(NT) void automorph_ntt_kernel(const u64* in, u64 in
 
 hipError_t launch_automorph_ntt(const u64* in, u64 in_bs, u64* out, u64 out_bs, u64 galois, int n_polys, u64 n_batch,
                                 int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, n_polys, (unsigned)n_batch);
     ProfScope prof__("automorph_ntt_kernel", st);
     hipLaunchKernelGGL(automorph_ntt_kernel, grid, dim3(NT), 0, st, in, in_bs, out, out_bs, galois, log_n);
@@ -338,6 +355,7 @@ __global__ __launch_bounds__(NT) void reduce_i64_kernel(const PrimeConst* primes
 
 hipError_t launch_reduce_i64(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs, int n_pts, int log_n,
                              hipStream_t st) {
+    DRY_RUN_RETURN();
     if (n_pts <= 0) return hipSuccess;
     dim3 grid((1u << log_n) / NT, limbs, n_pts);
     ProfScope prof__("reduce_i64_kernel", st);

@@ -28,6 +28,7 @@ __global__ __launch_bounds__(NT) void encode_kernel(const double* cs, const doub
 
 hipError_t launch_encode(const double* cs, const double* sn, const uint32_t* g, const double* re, const double* im,
                          int count, int n_pts, double factor, i64* coeffs, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     if (n_pts <= 0) return hipSuccess;
     ProfScope prof__("encode_kernel", st);
     hipLaunchKernelGGL(encode_kernel, dim3((1u << log_n) / NT, n_pts), dim3(NT), 0, st, cs, sn, g, re, im, count, factor,
@@ -66,6 +67,7 @@ __global__ __launch_bounds__(NT) void crt_to_double_kernel(const PrimeConst* pri
 
 hipError_t launch_crt_to_double(const PrimeConst* primes, const u64* coeff_form, int limbs, const u64* garner_inv,
                                 const u64* garner_inv_sh, int L, double inv_scale, double* out, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     ProfScope prof__("crt_to_double_kernel", st);
     hipLaunchKernelGGL(crt_to_double_kernel, dim3((1u << log_n) / NT), dim3(NT), 0, st, primes, coeff_form, limbs,
                        garner_inv, garner_inv_sh, L, inv_scale, out, log_n);
@@ -108,6 +110,7 @@ __global__ __launch_bounds__(NT) void decode_kernel(const double* cs, const doub
 
 hipError_t launch_decode(const double* cs, const double* sn, const double* m, int count, double* re, double* im, int log_n,
                          hipStream_t st) {
+    DRY_RUN_RETURN();
     if (count <= 0) return hipSuccess;
     ProfScope prof__("decode_kernel", st);
     hipLaunchKernelGGL(decode_kernel, dim3(count), dim3(NT), 0, st, cs, sn, m, count, re, im, log_n);

@@ -99,6 +99,7 @@ u64 double_to_residue(double v, u64 q) { return hm::double_to_residue(v, q); }
 // per-kernel timing (HIP events on the launch stream)
 // ---------------------------------------------------------------------------
 bool g_prof_on = false;
+thread_local Analysis* t_analysis = nullptr;
 namespace {
 struct ProfRec { std::string kernel; hipEvent_t t0, t1; };
 std::vector<ProfRec> g_prof_recs;
@@ -207,6 +208,7 @@ int alloc_ct_batch(hisa_ctx* ctx, size_t n, uint32_t polys, uint32_t limbs, doub
     blk->refs = (int)n;
     for (size_t i = 0; i < n; i++)
         out[i] = new hisa_ct{HISA_MAGIC_CT, blk, (u64*)blk->ptr + i * words, polys, limbs, scale};
+    if (t_analysis && n && (t_analysis->c.min_limbs == 0 || limbs < t_analysis->c.min_limbs)) t_analysis->c.min_limbs = limbs;
     return HISA_OK;
 }
 
@@ -479,6 +481,10 @@ extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** 
 extern "C" int hisa_destroy(hisa_ctx* ctx) {
     if (!ctx) return HISA_OK;
     (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->analysis) {
+        if (t_analysis == ctx->analysis) t_analysis = nullptr;
+        delete ctx->analysis;
+    }
     for (auto* m : {&ctx->keys, &ctx->aux})
         for (auto& kv : *m)
             if (kv.second.blk) { (void)hipFree(kv.second.blk->ptr); delete kv.second.blk; }
@@ -545,6 +551,7 @@ static int gen_switch_key(hisa_ctx* ctx, u64 key_id, const u64* target) {
 
 extern "C" int hisa_keygen(hisa_ctx* ctx) {
     if (!ctx) return HISA_ERR_ARG;
+    if (t_analysis) return fail(ctx, HISA_ERR_ARG, "keys cannot be generated during an analysis (no kernel runs)");
     if (ctx->keys.count(0)) return HISA_OK;
     Temp s2(ctx, (size_t)ctx->total * ctx->N * sizeof(u64));
     if (!s2.ok()) return HISA_ERR_OOM;
@@ -571,6 +578,7 @@ extern "C" int hisa_galois_elt(hisa_ctx* ctx, int32_t left_steps, uint64_t* g) {
 
 extern "C" int hisa_gen_rot_keys(hisa_ctx* ctx, const int32_t* left_steps, size_t count) {
     if (!ctx || (!left_steps && count)) return fail(ctx, HISA_ERR_ARG, "null steps");
+    if (t_analysis) return fail(ctx, HISA_ERR_ARG, "keys cannot be generated during an analysis (no kernel runs)");
     for (size_t i = 0; i < count; i++) {
         const u64 g = galois_of(ctx, left_steps[i]);
         if (g == 0 || ctx->keys.count(g)) continue;
@@ -1251,6 +1259,35 @@ static int key_switch_core_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois,
     return key_switch_finish_fp(ctx, x, d, d_bs, galois, 0, B, key, add, add_bs, add_polys, out);
 }
 
+extern "C" int hisa_analysis_begin(hisa_ctx* ctx) {
+    if (!ctx) return HISA_ERR_ARG;
+    if (t_analysis) return fail(ctx, HISA_ERR_ARG, "a context of this thread is already in analysis mode");
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->analysis = new Analysis();
+    t_analysis = ctx->analysis;
+    return HISA_OK;
+}
+
+extern "C" int hisa_analysis_end(hisa_ctx* ctx, hisa_op_counts* counts, int32_t* rot_steps, size_t cap, size_t* n) {
+    if (!ctx) return HISA_ERR_ARG;
+    if (!ctx->analysis || t_analysis != ctx->analysis) return fail(ctx, HISA_ERR_ARG, "the context is not in analysis mode");
+    Analysis* a = ctx->analysis;
+    ctx->analysis = nullptr;
+    t_analysis = nullptr;
+    int rc = HISA_OK;
+    if (counts) *counts = a->c;
+    if (n) *n = a->steps.size();
+    if (rot_steps) {
+        size_t i = 0;
+        for (int32_t s : a->steps) {
+            if (i >= cap) { rc = fail(ctx, HISA_ERR_ARG, "%zu rotation amounts do not fit %zu entries", a->steps.size(), cap); break; }
+            rot_steps[i++] = s;
+        }
+    }
+    delete a;
+    return rc;
+}
+
 extern "C" int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n, int32_t steps, hisa_ct** out) {
     if (!ctx || !out) return fail(ctx, HISA_ERR_ARG, "bad argument");
     TRY(check_batch_shape(ctx, in, n, 2));
@@ -1263,6 +1300,14 @@ extern "C" int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size
             HIP_TRY(ctx, hipMemcpyAsync(out[i]->data, in[i]->data, ct_words(ctx, 2, l) * sizeof(u64), hipMemcpyDeviceToDevice,
                                         ctx->stream));
         }
+        return HISA_OK;
+    }
+    if (t_analysis) {   // dry run: note the amount, hand out ciphertexts of the right level and scale
+        const int32_t half = (int32_t)(ctx->N / 2);
+        t_analysis->steps.insert(((steps % half) + half) % half);
+        t_analysis->c.rot_left += n;
+        TRY(alloc_ct_batch(ctx, n, 2, (uint32_t)l, 0.0, out));
+        for (size_t i = 0; i < n; i++) out[i]->scale = in[i]->scale;
         return HISA_OK;
     }
     auto it = ctx->keys.find(g);
@@ -1309,13 +1354,16 @@ extern "C" int hisa_rot_left_hoisted_batch(hisa_ctx* ctx, const hisa_ct* const* 
         gs[s] = galois_of(ctx, steps[s]);
         if (gs[s] == 0) continue;
         switched++;
-        if (ctx->keys.find(gs[s]) == ctx->keys.end())
+        if (!t_analysis && ctx->keys.find(gs[s]) == ctx->keys.end())
             return fail(ctx, HISA_ERR_NO_KEY, "no rotation key for %d slots (galois element %llu)", steps[s],
                         (unsigned long long)gs[s]);
     }
     const int l = (int)in[0]->limbs;
     int rc = HISA_OK;
-    if (switched < 2 || !(ctx->tabs.fp_ok && ctx->dnum <= 8)) {   // nothing to share, or no fused path: one by one
+    if (t_analysis) {
+        for (size_t s = 0; s < n_steps && rc == HISA_OK; s++) rc = hisa_rot_left_batch(ctx, in, n, steps[s], out + s * n);
+        if (rc == HISA_OK && switched >= 2 && ctx->tabs.fp_ok && ctx->dnum <= 8) t_analysis->c.rot_shared += (switched - 1) * n;
+    } else if (switched < 2 || !(ctx->tabs.fp_ok && ctx->dnum <= 8)) {   // nothing to share, or no fused path: one by one
         for (size_t s = 0; s < n_steps && rc == HISA_OK; s++) rc = hisa_rot_left_batch(ctx, in, n, steps[s], out + s * n);
     } else {
         BatchIn bi;
@@ -1374,6 +1422,16 @@ extern "C" int hisa_relinearize_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t
     TRY(check_batch_shape(ctx, (const hisa_ct* const*)cts, n, 0));
     if (cts[0]->polys == 2) return HISA_OK;
     if (cts[0]->polys != 3) return fail(ctx, HISA_ERR_SIZE, "relinearize needs 2 or 3 polynomials");
+    if (t_analysis) {
+        t_analysis->c.relinearize += n;
+        std::vector<hisa_ct*> two(n);
+        TRY(alloc_ct_batch(ctx, n, 2, cts[0]->limbs, 0.0, two.data()));
+        for (size_t i = 0; i < n; i++) {
+            two[i]->scale = cts[i]->scale;
+            adopt(ctx, cts[i], two[i]);
+        }
+        return HISA_OK;
+    }
     auto it = ctx->keys.find(0);
     if (it == ctx->keys.end()) return fail(ctx, HISA_ERR_NO_KEY, "no relinearisation key: call hisa_keygen");
     const int l = (int)cts[0]->limbs;
@@ -1479,6 +1537,7 @@ extern "C" int hisa_rescale_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n) 
     TRY(check_batch_shape(ctx, (const hisa_ct* const*)cts, n, 0));
     const int l = (int)cts[0]->limbs, polys = (int)cts[0]->polys;
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "rescale of a one-limb ciphertext");
+    if (t_analysis) t_analysis->c.rescale += n;
     const size_t nn = ctx->N, n_bp = n * polys;
     BatchIn bi;
     TRY(gather_batch(ctx, (const hisa_ct* const*)cts, n, &bi));

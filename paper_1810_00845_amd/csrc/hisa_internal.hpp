@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include <map>
+#include <set>
 #include <string>
 #include <unordered_map>
 #include <vector>
@@ -116,6 +117,7 @@ struct hisa_ctx {
     NttTables tabs;
     u64* d_secret;  // [total][N], NTT form
     std::map<u64, SwitchKey> keys;  // 0: relinearisation, else Galois element
+    struct Analysis* analysis = nullptr;   // non-null between hisa_analysis_begin and hisa_analysis_end
     std::map<u64, SwitchKey> aux;   // small derived device tables, built on first use
     std::map<std::pair<int, int>, ConvTable> modup_tabs;  // (digit, size)
     ConvTable* moddown_tab;
@@ -192,6 +194,16 @@ u64 double_to_residue(double v, u64 q);
 void prof_begin(const char* kernel, hipStream_t st);
 void prof_end(hipStream_t st);
 extern bool g_prof_on;
+
+// Analysis backend (Sec. "Compiler": the analyser runs the circuit on a HISA backend that records instead of
+// computing).  While a context is in analysis mode every launch wrapper returns at once (no kernel runs; memory is
+// still allocated, so handles, levels and scales evolve as in a real run) and the primitives count themselves here.
+struct Analysis {
+    hisa_op_counts c = {};
+    std::set<int32_t> steps;    // left-rotation amounts that needed a key
+};
+extern thread_local Analysis* t_analysis;   // non-null while the calling thread's context is in analysis mode
+#define DRY_RUN_RETURN() do { if (t_analysis) return hipSuccess; } while (0)
 struct ProfScope {
     hipStream_t st;
     bool on;

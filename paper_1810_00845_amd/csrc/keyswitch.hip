@@ -32,6 +32,7 @@ __global__ __launch_bounds__(NT) void base_conv_kernel(const PrimeConst* primes,
 }
 
 hipError_t launch_base_conv(const PrimeConst* primes, const ConvArgs& args, u64 n_batch, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     if (args.n_targets <= 0 || n_batch == 0) return hipSuccess;
     dim3 grid((1u << log_n) / NT, args.n_targets, (unsigned)n_batch);
     ProfScope prof__("base_conv_kernel", st);
@@ -69,6 +70,7 @@ __global__ __launch_bounds__(NT) void inner_product_kernel(const PrimeConst* pri
 
 hipError_t launch_inner_product(const PrimeConst* primes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
                                 const u64* key, int total, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, l + K, (unsigned)((n_batch + IP_BCHUNK - 1) / IP_BCHUNK));
     ProfScope prof__("inner_product_kernel", st);
     hipLaunchKernelGGL(inner_product_kernel, grid, dim3(NT), 0, st, primes, ext, ext_bs, digits, l, K, L, key, total, acc,
@@ -103,6 +105,7 @@ __global__ __launch_bounds__(NT) void moddown_final_kernel(const PrimeConst* pri
 hipError_t launch_moddown_final(const PrimeConst* primes, const u64* acc, u64 acc_bs, const u64* conv, u64 conv_bs,
                                 const u64* pinv, const u64* pinv_sh, const u64* add, u64 add_bs, int add_polys, u64 galois,
                                 u64* out, u64 out_bs, int l, int K, u64 n_batch, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, 2 * l, (unsigned)n_batch);
     ProfScope prof__("moddown_final_kernel", st);
     hipLaunchKernelGGL(moddown_final_kernel, grid, dim3(NT), 0, st, primes, acc, acc_bs, conv, conv_bs, pinv, pinv_sh, add,
@@ -118,6 +121,7 @@ __global__ __launch_bounds__(NT) void copy_limbs_kernel(const u64* src, u64 src_
 
 hipError_t launch_copy_limbs(const u64* src, u64 src_bs, u64* dst, u64 dst_bs, int limbs, u64 n_batch, int log_n,
                              hipStream_t st) {
+    DRY_RUN_RETURN();
     if (limbs <= 0 || n_batch == 0) return hipSuccess;
     dim3 grid((1u << log_n) / NT, limbs, (unsigned)n_batch);
     ProfScope prof__("copy_limbs_kernel", st);
@@ -142,6 +146,7 @@ __global__ __launch_bounds__(NT) void rescale_spread_kernel(const PrimeConst* pr
 
 hipError_t launch_rescale_spread(const PrimeConst* primes, const u64* last, u64* r, int l, u64 n_bp, int log_n,
                                  hipStream_t st) {
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, l - 1, (unsigned)n_bp);
     ProfScope prof__("rescale_spread_kernel", st);
     hipLaunchKernelGGL(rescale_spread_kernel, grid, dim3(NT), 0, st, primes, last, r, l, log_n);
@@ -165,6 +170,7 @@ __global__ __launch_bounds__(NT) void rescale_final_kernel(const PrimeConst* pri
 
 hipError_t launch_rescale_final(const PrimeConst* primes, const u64* ct, const u64* r, const u64* qlinv, const u64* qlinv_sh,
                                 u64* out, int l, u64 n_bp, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     RescaleConsts c = {};
     for (int i = 0; i < l - 1; i++) { c.v[i] = qlinv[i]; c.v_sh[i] = qlinv_sh[i]; }
     dim3 grid((1u << log_n) / NT, l - 1, (unsigned)n_bp);

@@ -332,7 +332,18 @@ __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes
     }
 }
 
+// analysis mode: a multiply-accumulate launch stands for one multiply per (image, output, tap, input) and one add fewer
+// per (image, output)
+static void count_mac(const MacArgs& g, int batch, bool plain) {
+    if (!t_analysis) return;
+    const uint64_t terms = (uint64_t)batch * g.OC * g.n_taps * g.IC;
+    (plain ? t_analysis->c.mul_plain : t_analysis->c.mul_scalar) += terms;
+    t_analysis->c.add += terms - (uint64_t)batch * g.OC;
+}
+
 static hipError_t launch_scalar_mac(const PrimeConst* primes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
+    count_mac(g, batch, false);
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, 2 * g.l, batch * ((g.OC + OCB - 1) / OCB));
     ProfScope prof__("scalar_mac_kernel", st);
     hipLaunchKernelGGL(scalar_mac_kernel, grid, dim3(NT), 0, st, primes, g, log_n);
@@ -341,6 +352,8 @@ static hipError_t launch_scalar_mac(const PrimeConst* primes, const MacArgs& g, 
 
 static hipError_t launch_scalar_mac_fp(const FpPrime* fprimes, const MacArgs& g, const double* wf, int batch, int log_n,
                                        hipStream_t st) {
+    count_mac(g, batch, false);
+    DRY_RUN_RETURN();
     if (!fprimes || !wf || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / NT, 2 * g.l, batch * ((g.OC + OCF - 1) / OCF));
     ProfScope prof__("scalar_mac_fp_kernel", st);
@@ -351,6 +364,7 @@ static hipError_t launch_scalar_mac_fp(const FpPrime* fprimes, const MacArgs& g,
 template <int DA, int DB>
 static hipError_t launch_mfma_one(const FpPrime* fprimes, const MacArgs& g, const int8_t* wd, int K, int K_pad, int OC_pad,
                                   const double* c3, dim3 grid, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     hipLaunchKernelGGL((scalar_mac_mfma_kernel<DA, DB>), grid, dim3(256), 0, st, fprimes, g, wd, K, K_pad, OC_pad, c3, log_n);
     return hipGetLastError();
 }
@@ -358,6 +372,8 @@ static hipError_t launch_mfma_one(const FpPrime* fprimes, const MacArgs& g, cons
 // da: digits the weights need (1..7); db: digits the residues need (6: every prime below 2^46, else 7)
 static hipError_t launch_scalar_mac_mfma(const FpPrime* fprimes, const MacArgs& g, const int8_t* wd, int K, int K_pad, int OC_pad,
                                          const double* c3, int da, int db, int batch, int log_n, hipStream_t st) {
+    count_mac(g, batch, false);
+    DRY_RUN_RETURN();
     if (!fprimes || !wd || !c3 || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || K != g.n_taps * g.IC || K_pad % MT_K ||
         K_pad < K || OC_pad % MT_OC || OC_pad < g.OC || log_n < 6 || da < 1 || da > MAC_DIGITS || (db != 6 && db != 7))
         return hipErrorInvalidValue;
@@ -372,6 +388,8 @@ static hipError_t launch_scalar_mac_mfma(const FpPrime* fprimes, const MacArgs& 
 }
 
 static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
+    count_mac(g, batch, true);
+    DRY_RUN_RETURN();
     if (!fprimes || !g.w || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / NT, g.l, batch * ((g.OC + OCP - 1) / OCP));
     ProfScope prof__("plain_mac_fp_kernel", st);
@@ -380,6 +398,8 @@ static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, 
 }
 
 static hipError_t launch_plain_mac(const PrimeConst* primes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
+    count_mac(g, batch, true);
+    DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, g.l, batch * g.OC);
     ProfScope prof__("plain_mac_kernel", st);
     hipLaunchKernelGGL(plain_mac_kernel, grid, dim3(NT), 0, st, primes, g, log_n);
@@ -850,6 +870,7 @@ struct hisa_conv_plan {
 extern "C" int hisa_conv2d_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t OC,
                                    const hisa_conv_geom* geom, hisa_conv_plan** plan_out) {
     if (!ctx || !plan_out || !w || OC == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    if (t_analysis) return fail(ctx, HISA_ERR_ARG, "plans cannot be prepared during an analysis (no kernel runs)");
     TRY(check_tensor(ctx, like));
     ConvPlan plan;
     TRY(conv_plan(ctx, like, geom, &plan));
@@ -1001,6 +1022,7 @@ struct hisa_fc_plan {
 
 extern "C" int hisa_fc_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t OUT, hisa_fc_plan** plan) {
     if (!ctx || !like || !w || !plan || OUT == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    if (t_analysis) return fail(ctx, HISA_ERR_ARG, "plans cannot be prepared during an analysis (no kernel runs)");
     TRY(check_tensor(ctx, like));
     TRY(require_hw_tiling(ctx, like, "fc (hisa_matmul reads CHW-tiled tensors)"));
     if (like->height == 1 && like->width == 1)
@@ -1223,8 +1245,8 @@ static hisa_matmul_plan* new_matmul_plan(const hisa_tensor* like, uint32_t OUT, 
                                 1.0, 1.0, nullptr, nullptr};
 }
 
-extern "C" int hisa_matmul_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t OUT, uint32_t replicas,
-                                   hisa_matmul_plan** plan_out) {
+static int matmul_build(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t OUT, uint32_t replicas,
+                        hisa_matmul_plan** plan_out) {
     if (!ctx || !w || !plan_out || OUT == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
     TRY(check_tensor(ctx, like));
     MatmulGeom g;
@@ -1279,6 +1301,12 @@ extern "C" int hisa_matmul_prepare(hisa_ctx* ctx, const hisa_tensor* like, const
     return HISA_OK;
 }
 
+extern "C" int hisa_matmul_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t OUT, uint32_t replicas,
+                                   hisa_matmul_plan** plan_out) {
+    if (t_analysis) return fail(ctx, HISA_ERR_ARG, "plans cannot be prepared during an analysis (no kernel runs)");
+    return matmul_build(ctx, like, w, OUT, replicas, plan_out);
+}
+
 extern "C" int hisa_matmul_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_matmul_plan* plan, hisa_tensor* out) {
     if (!ctx || !plan || plan->magic != HISA_MAGIC_MMPLAN) return fail(ctx, HISA_ERR_ARG, "bad argument");
     TRY(check_tensor(ctx, in));
@@ -1299,7 +1327,7 @@ extern "C" int hisa_matmul_apply(hisa_ctx* ctx, const hisa_tensor* in, const his
 extern "C" int hisa_matmul(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t OUT, uint32_t replicas,
                            hisa_tensor* out) {
     hisa_matmul_plan* plan = nullptr;
-    TRY(hisa_matmul_prepare(ctx, in, w, OUT, replicas, &plan));
+    TRY(matmul_build(ctx, in, w, OUT, replicas, &plan));
     const int rc = hisa_matmul_apply(ctx, in, plan, out);
     hisa_matmul_plan_free(ctx, plan);
     return rc;

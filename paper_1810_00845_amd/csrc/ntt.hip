@@ -150,6 +150,7 @@ static FpArgs fp_base_args(const NttTables& t) {
 
 hipError_t launch_ntt(const NttTables& t, int log_n, u64* data, u64 batch_stride, int n_polys, const PolyMap& map,
                       hipStream_t st) {
+    DRY_RUN_RETURN();
     if (n_polys <= 0) return hipSuccess;
     FpTask tk;
     if (fp_tasks(t, log_n, map, n_polys, 0, &tk)) {
@@ -172,6 +173,7 @@ hipError_t launch_ntt(const NttTables& t, int log_n, u64* data, u64 batch_stride
 
 hipError_t launch_intt(const NttTables& t, int log_n, u64* data, u64 batch_stride, int n_polys, const PolyMap& map,
                        const InttExtra* extra, hipStream_t st) {
+    DRY_RUN_RETURN();
     if (n_polys <= 0) return hipSuccess;
     FpTask tk;
     if ((!extra || !extra->post) && fp_tasks(t, log_n, map, n_polys, extra ? extra->out_entry0 : 0, &tk)) {

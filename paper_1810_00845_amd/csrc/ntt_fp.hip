@@ -543,6 +543,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
 
 template <int K3, int MODE>
 static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
+    DRY_RUN_RETURN();
     typedef Geo<K3> G;
     static bool attr_set = false;
     const size_t lds_bytes = (size_t)G::LDS_WORDS * 4;
@@ -605,6 +606,7 @@ static hipError_t dispatch_k3(int log_n, const FpArgs& a, const FpTask& tk, u64 
 }
 
 hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
+    DRY_RUN_RETURN();
     if (n_batch == 0 || tk.period <= 0) return hipSuccess;
     // every pointer a mode dereferences must be set: a missing one is a host error, not a device fault
     if (tk.period > HISA_MAX_PRIMES || !a.fprimes) return hipErrorInvalidValue;
@@ -683,6 +685,7 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime*
 hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
                                    int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois,
                                    int gather_ext, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
     if (digits > IPF_MAXD) return hipErrorInvalidValue;  // the caller falls back to the integer path
     if (!fprimes || !ext || !key || !own_src || !acc) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / IPF_NT, l + K, IPF_ZSPLIT);

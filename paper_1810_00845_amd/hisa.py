@@ -41,6 +41,11 @@ class TensorStruct(C.Structure):
                 ("c_inner", C.c_uint32), ("c_stride", C.c_uint32), ("cts", C.POINTER(C.c_void_p))]
 
 
+class OpCounts(C.Structure):
+    _fields_ = [(name, C.c_uint64) for name in ("rot_left", "rot_shared", "relinearize", "mul", "mul_plain", "mul_scalar",
+                                                "add", "rescale")] + [("min_limbs", C.c_uint32), ("reserved", C.c_uint32)]
+
+
 class ConvGeom(C.Structure):
     _fields_ = [("fh", C.c_uint32), ("fw", C.c_uint32), ("stride", C.c_uint32), ("pad_same", C.c_uint32),
                 ("mode", C.c_uint32)]
@@ -527,6 +532,19 @@ class Context:
 
     def pool_rot_steps(self, t):
         return self._steps("hisa_pool_rot_steps", t)
+
+    # ---- analysis backend ----
+    def analysis_begin(self):
+        """From here to analysis_end the calls on this context are dry runs that only record."""
+        self._ck(load().hisa_analysis_begin(self._vp))
+
+    def analysis_end(self):
+        """(operation counts as a dict incl. 'min_limbs', sorted left-rotation amounts that needed a key)."""
+        counts, n = OpCounts(), C.c_size_t()
+        buf = (C.c_int32 * 4096)()
+        self._ck(load().hisa_analysis_end(self._vp, C.byref(counts), buf, C.c_size_t(4096), C.byref(n)))
+        d = {name: int(getattr(counts, name)) for name, _ in OpCounts._fields_ if name != "reserved"}
+        return d, [int(buf[i]) for i in range(n.value)]
 
     def profile_enable(self, on=True):
         self._ck(load().hisa_profile_enable(self._vp, C.c_int(1 if on else 0)))

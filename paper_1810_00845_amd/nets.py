@@ -205,3 +205,81 @@ def free_plans(ctx, plans):
         else:
             ctx.conv_plan_free(plan)
     plans.clear()
+
+
+# ---------------------------------------------------------------------------
+# analysis passes of the compiler (Sec. "Compiler"): each is a dry run of the schedule on the library's analysis
+# backend, which records what the circuit would do instead of computing it
+# ---------------------------------------------------------------------------
+def analyse(ctx, layers, x, scale, limbs, border=0, layout="hw"):
+    """Dry run: ({operation: count, "min_limbs": lowest level reached}, left-rotation amounts that need keys).  The
+    rotation amounts are the rotation-key selection of Sec. "Rotation Keys Selection"; limbs - min_limbs is the
+    number of moduli the circuit consumes (the depth the parameter selection has to provide)."""
+    ctx.analysis_begin()
+    try:
+        run_encrypted(ctx, layers, x, scale, limbs, border=border, layout=layout)
+    finally:
+        counts, steps = ctx.analysis_end()
+    return counts, steps
+
+
+COST_OPS = ("rot_left", "rot_shared", "relinearize", "mul", "mul_plain", "mul_scalar", "add", "rescale")
+
+
+def measure_costs(ctx, limbs, batch=64, reps=5):
+    """Seconds per ciphertext operation at `limbs` limbs, from timing each primitive on a batch of random ciphertexts
+    (Sec. "Data Layout Selection": the costs may come from micro-benchmarks).  "rot_shared" is what a rotation saves
+    when it shares another one's decomposition (a negative cost)."""
+    import numpy as np
+    cts = ctx.ct_random_batch(batch, limbs, 2.0 ** 40, 900)
+    pt = ctx.encode(np.ones(8), float(ctx.primes[limbs - 1]), limbs)
+    ctx.gen_rot_keys([1, 2, 3])
+
+    def timed(fn):
+        fn()
+        ctx.sync()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        ctx.sync()
+        return (time.perf_counter() - t0) / (reps * batch)
+
+    def free(out):
+        for c in out:
+            free(c) if isinstance(c, list) else c.free()
+
+    costs = {}
+    costs["rot_left"] = timed(lambda: free(ctx.rot_left_batch(cts, 1)))
+    hoisted = timed(lambda: free(ctx.rot_left_hoisted_batch(cts, [1, 2, 3])))      # three rotations per ciphertext
+    costs["rot_shared"] = min(0.0, (hoisted - 3 * costs["rot_left"]) / 2)
+    costs["add"] = timed(lambda: free(ctx.add_batch(cts, cts)))
+    costs["mul"] = timed(lambda: free(ctx.mul_no_relin_batch(cts, cts)))
+    costs["mul_plain"] = timed(lambda: free(ctx.mul_plain_batch(cts, pt)))
+    costs["mul_scalar"] = costs["mul_plain"]          # both stream a ciphertext through one multiply per residue
+
+    def relin():
+        sq = ctx.mul_no_relin_batch(cts, cts)
+        ctx.relinearize_batch(sq)
+        free(sq)
+    costs["relinearize"] = max(0.0, timed(relin) - costs["mul"])
+
+    def rescale():
+        cp = ctx.add_batch(cts, cts)
+        ctx.rescale_batch(cp)
+        free(cp)
+    costs["rescale"] = max(0.0, timed(rescale) - costs["add"])
+    pt.free()
+    free(cts)
+    return costs
+
+
+def estimate_cost(counts, costs):
+    """The analyser's figure for a circuit: sum over the operations of occurrences times cost."""
+    return sum(counts[op] * costs[op] for op in COST_OPS)
+
+
+def select_layout(ctx, layers, x, scale, limbs, costs, border=0, layouts=LAYOUTS):
+    """Data layout selection (Sec. "Data Layout Selection"): build the circuit for every layout, let the analyser
+    cost it, keep the cheapest.  Returns (layout, {layout: estimated seconds})."""
+    est = {lay: estimate_cost(analyse(ctx, layers, x, scale, limbs, border, lay)[0], costs) for lay in layouts}
+    return min(est, key=est.get), est

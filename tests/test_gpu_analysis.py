@@ -1,0 +1,112 @@
+"""The analysis backend of the library (dry runs that record rotation amounts, depth and operation counts) and the
+compiler passes built on it: rotation-key selection, depth, data layout selection by cost."""
+import numpy as np
+import pytest
+
+import plain_net
+
+pytestmark = pytest.mark.gpu
+
+
+def test_analysis_counts_match_the_schedule_and_leave_the_context_usable():
+    """The matmul-with-replicas schedule of the oracle's pin test (3 pooled input ciphertexts, 10 outputs, 4
+    replicas): the dry run reports the instruction counts that the oracle's loop executes, needs no key, and the
+    same context afterwards computes the real layer."""
+    from paper_1810_00845_amd import hisa, synth
+    g = hisa.Context(12, [50, 45, 45, 45, 45, 45], 3, 50, 12)   # N and primes within the fused fp64 path
+    x = synth.image(21, 3, 4, 4)[None]
+    w1 = synth.fc_weights(22, 10, 3, 2, 2, std=0.3)
+    t = g.tensor_encrypt(x, 2.0 ** 45, 6)
+    g.analysis_begin()
+    pool = g.sum_pool2x2(t)                      # no rotation key exists yet: recorded, not an error
+    m = g.matmul(pool, w1, 4)
+    counts, steps = g.analysis_end()
+    assert (m.c_inner, m.c_stride, len(m.cts), m.cts[0].limbs) == (4, 16, 3, 4)
+    slots = g.N // 2
+    assert steps == sorted([1, 4, 5, 2, 8, slots - 16, slots - 32])
+    # pool: 3 rotations per ciphertext, two of them sharing the first one's decomposition, 3 adds each;
+    # matmul: 3 masks + 3 x 3 weights, 2 replica steps x 3 inputs + 2 reduction steps x 3 groups, 3 + 3 divScalar
+    assert counts["rot_left"] == 9 + 6 + 6 and counts["rot_shared"] == 6
+    assert counts["mul_plain"] == 3 + 9 and counts["rescale"] == 3 + 3
+    assert counts["add"] == 9 + 6 + (9 - 3) + 6
+    assert counts["mul"] == 0 and counts["relinearize"] == 0 and counts["mul_scalar"] == 0
+    assert counts["min_limbs"] == 4
+    pool.free(); m.free()
+    # outside the analysis the same calls compute: the missing keys are now an error, and with them the result is right
+    with pytest.raises(hisa.HisaError):
+        g.sum_pool2x2(t)
+    g.gen_rot_keys(steps)
+    pool = g.sum_pool2x2(t)
+    m = g.matmul(pool, w1, 4)
+    want = plain_net.fc(plain_net.sum_pool2x2(x), w1)
+    assert np.abs(g.tensor_decrypt(m) - want).max() <= 1e-3
+    g.close()
+
+
+def test_analysis_mode_errors():
+    from paper_1810_00845_amd import hisa, synth
+    g = hisa.Context(10, [50, 40, 40], 3, 55, 5)
+    with pytest.raises(hisa.HisaError):
+        g.analysis_end()                         # not in analysis mode
+    g.analysis_begin()
+    with pytest.raises(hisa.HisaError):
+        g.analysis_begin()                       # not re-entrant
+    with pytest.raises(hisa.HisaError):
+        g.gen_rot_keys([1])                      # keys made without kernels would be garbage that outlives the analysis
+    with pytest.raises(hisa.HisaError):
+        g.keygen()
+    t = g.tensor_encrypt(synth.image(1, 2, 4, 4)[None], 2.0 ** 40, 3)
+    with pytest.raises(hisa.HisaError):
+        g.fc_prepare(t, synth.fc_weights(2, 3, 2, 4, 4))
+    act = g.poly2_act(t, 0.5, 0.25)              # no relinearisation key either
+    counts, steps = g.analysis_end()
+    assert counts["mul"] == 2 and counts["relinearize"] == 2 and counts["mul_scalar"] == 2 and counts["rescale"] == 2
+    assert steps == [] and counts["min_limbs"] == 2
+    g.close()
+
+
+@pytest.mark.parametrize("layout,levels,mul_plain,mul_scalar,mul", [("hw", 5, 500, 1125, 105), ("chw_fc", 6, 5 + 125 + 250, 125, 30)])
+def test_rotation_key_selection_and_depth_by_dry_run(layout, levels, mul_plain, mul_scalar, mul):
+    """LeNet-small: the keys named by the dry run are exactly enough to run the network (a context that holds only
+    those keys computes the right answer), the depth is the number of divScalar levels of the schedule, and the
+    multiply counts are those of the layers (conv 25 taps x 5 outputs; FC 845 -> 100 -> 10 per layout)."""
+    from paper_1810_00845_amd import hisa, nets
+    params, layers, x = nets.lenet_small()
+    limbs = len(params["q_bits"])
+    ctx = hisa.Context(params["log_n"], params["q_bits"], params["dnum"], params["special_bits"], seed=11)
+    counts, steps = nets.analyse(ctx, layers, x, params["scale"], limbs, layout=layout)
+    assert limbs - counts["min_limbs"] == levels
+    assert (counts["mul_plain"], counts["mul_scalar"], counts["mul"], counts["relinearize"]) == (mul_plain, mul_scalar, mul, mul)
+    assert counts["rot_left"] >= 24 and len(steps) >= 24
+    ctx.keygen()
+    ctx.gen_rot_keys(steps)
+    got, _, _ = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, layout=layout)   # make_keys off
+    from test_gpu_networks import plain_forward
+    assert np.abs(got - plain_forward(layers, x)).max() <= 1e-3
+    ctx.close()
+
+
+def test_layout_selection_by_cost_agrees_with_the_clock():
+    """LeNet-medium: the analyser's cost (operation counts x micro-benchmarked unit costs) ranks the two layouts the
+    way the measured latencies do, and picks CHW-fc."""
+    from paper_1810_00845_amd import hisa, nets
+    params, layers, x = nets.lenet_medium()
+    limbs = len(params["q_bits"])
+    ctx = hisa.Context(params["log_n"], params["q_bits"], params["dnum"], params["special_bits"], seed=11)
+    ctx.keygen()
+    costs = nets.measure_costs(ctx, limbs)
+    assert costs["rot_left"] > costs["add"] > 0 and costs["rot_shared"] <= 0
+    best, est = nets.select_layout(ctx, layers, x, params["scale"], limbs, costs)
+    print("unit costs (us):", {k: round(v * 1e6, 2) for k, v in costs.items()}, "estimates (ms):",
+          {k: round(v * 1e3, 2) for k, v in est.items()}, flush=True)
+    assert best == "chw_fc" and est["chw_fc"] < est["hw"]
+    measured = {}
+    for layout in nets.LAYOUTS:
+        plans = {}
+        nets.run_encrypted(ctx, layers, x, params["scale"], limbs, make_keys=True, plans=plans, layout=layout)
+        measured[layout] = min(nets.run_encrypted(ctx, layers, x, params["scale"], limbs, plans=plans, layout=layout)[1]
+                               for _ in range(3))
+        nets.free_plans(ctx, plans)
+    print("measured (ms):", {k: round(v * 1e3, 2) for k, v in measured.items()}, flush=True)
+    assert measured["chw_fc"] < measured["hw"]
+    ctx.close()
