@@ -2,8 +2,9 @@
 
 The schedules of the paper's runtime (Sec. "Runtime"; Algorithm 1 for conv2d
 with VALID padding, its SAME-padding variant with a mask, homomorphic matmul
-without and with replicas (the latter with a CHW-tiled output), pooling,
-degree-2 activation) written as plain loops over the
+without and with replicas (the latter with a CHW-tiled output), CHW-tiled
+conv2d, the masking multiply, pooling, degree-2 activation) written as plain
+loops over the
 oracle's HISA instructions, one instruction per statement, in the paper's
 order.  Each layer also returns the fixed-point integers it used, so that a
 test can hand the very same integers to another implementation.
@@ -345,3 +346,112 @@ def poly2_act(o: Oracle, t: OTensor, a, b):
 def rot_steps_conv(o: Oracle, t: OTensor, fh, fw, pad_same=False):
     ph, pw = (fh // 2, fw // 2) if pad_same else (0, 0)
     return sorted({((fy - ph) * t.h_stride + (fx - pw) * t.w_stride) % o.slots for fy in range(fh) for fx in range(fw)} - {0})
+
+
+def mask_tensor(o: Oracle, t: OTensor):
+    """The masking multiply of Sec. "Homomorphic Tensor Operations" (SAME-padding paragraph) as a layer of its own:
+    one mulPlain by the 0/1 vector of the element slots (at the scale of the last modulus, so that the divScalar that
+    follows leaves the ciphertext scale unchanged) per ciphertext.  Returns (clean tensor, the integers used)."""
+    l = t.cts[0].limbs
+    per = cts_per_image(t)
+    mask_scale = float(o.primes[l - 1])
+    sl = np.asarray(tensor_slots(t)).reshape(t.c_inner, t.height * t.width)
+    masks = np.zeros((per, o.N), dtype=np.int64)
+    for j in range(per):
+        z = np.zeros(o.slots)
+        z[sl[:min(t.c_inner, t.channels - j * t.c_inner)].reshape(-1)] = 1.0
+        masks[j] = o.encode_coeffs(z, mask_scale)
+    ints = {"mask_coeffs": masks, "mask_scale": mask_scale}
+    return mask_tensor_fixed(o, t, ints), ints
+
+
+def mask_tensor_fixed(o: Oracle, t: OTensor, ints):
+    per = cts_per_image(t)
+    outs = []
+    for i, ct in enumerate(t.cts):
+        temp = o.mul_plain(ct, o.pt_from_coeffs(ints["mask_coeffs"][i % per], ints["mask_scale"], ct.limbs))
+        outs.append(o.div_scalar(temp, o.max_scalar_div(temp, float("inf"))))
+    return replace(t, cts=outs, clean=1)
+
+
+def chw_conv_geometry(o: Oracle, t: OTensor, fh, fw, pad_same=False):
+    """CHW-tiled convolution: the c_inner channel blocks of a ciphertext are combined along diagonals, output block b
+    reading input block (b + d) mod c_inner for d = 0 .. c_inner-1, so one rotation per (tap, d) brings every needed
+    input channel under every output channel.  The wrap-around of the blocks is a cyclic rotation only if the blocks
+    fill the slot vector; otherwise one copy of the blocks is first placed behind them (rotRight by `wrap` and add; the
+    slots there must be free, and zero because the input is clean).  Returns (wrap or 0, rotLeft amounts
+    [fh][fw][c_inner])."""
+    ci, cs = t.c_inner, t.c_stride
+    assert ci > 1 and t.clean
+    if ci * cs == o.slots:
+        wrap = 0
+    else:
+        assert 2 * ci * cs <= o.slots, "no room behind the channel blocks for their copy"
+        wrap = ci * cs
+    ph, pw = (fh // 2, fw // 2) if pad_same else (0, 0)
+    amounts = [[[((fy - ph) * t.h_stride + (fx - pw) * t.w_stride + d * cs) % o.slots for d in range(ci)]
+                for fx in range(fw)] for fy in range(fh)]
+    return wrap, amounts
+
+
+def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False):
+    """w[FH][FW][IC][OC] on a clean CHW-tiled tensor -> clean CHW-tiled tensor with the same channel blocks.  The
+    plaintext of (tap, d, input ciphertext j, output ciphertext g) holds, on the valid output positions of block b,
+    the weight from input channel j c_inner + (b + d) mod c_inner to output channel g c_inner + b (zero where either
+    does not exist), encoded at the scale of the last modulus.  Returns (output, the integers used)."""
+    fh, fw, ic_n, oc_n = w.shape
+    assert ic_n == t.channels
+    ci, cs = t.c_inner, t.c_stride
+    l = t.cts[0].limbs
+    pt_scale = float(o.primes[l - 1])
+    if pad_same:
+        oh, ow = -(-t.height // stride), -(-t.width // stride)
+    else:
+        oh, ow = (t.height - fh) // stride + 1, (t.width - fw) // stride + 1
+    per_in, per_out = cts_per_image(t), -(-oc_n // ci)
+    plane = np.asarray(plane_slots(oh, ow, t.h_stride * stride, t.w_stride * stride, t.offset))
+    coeffs = np.zeros((fh, fw, ci, per_in, per_out, o.N), dtype=np.int64)
+    for fy, fx, d, j, g in np.ndindex(fh, fw, ci, per_in, per_out):
+        z = np.zeros(o.slots)
+        for b in range(ci):
+            ic, oc = j * ci + (b + d) % ci, g * ci + b
+            if ic < ic_n and oc < oc_n:
+                z[plane + b * cs] = float(w[fy, fx, ic, oc])
+        coeffs[fy, fx, d, j, g] = o.encode_coeffs(z, pt_scale)
+    ints = {"pt_coeffs": coeffs, "pt_scale": pt_scale}
+    return conv2d_chw_fixed(o, t, ints, oc_n, fh, fw, stride, pad_same), ints
+
+
+def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same):
+    ci = t.c_inner
+    wrap, amounts = chw_conv_geometry(o, t, fh, fw, pad_same)
+    if pad_same:
+        oh, ow = -(-t.height // stride), -(-t.width // stride)
+    else:
+        oh, ow = (t.height - fh) // stride + 1, (t.width - fw) // stride + 1
+    per_in, per_out = cts_per_image(t), -(-oc_n // ci)
+    outs = []
+    for b in range(t.batch):
+        xs = t.cts[b * per_in:(b + 1) * per_in]
+        if wrap:
+            xs = [o.add(x, o.rot_right(x, wrap)) for x in xs]
+        # the rotations do not depend on the output ciphertext: computed once
+        rotated = {(j, fy, fx, d): o.rot_left(xs[j], amounts[fy][fx][d])
+                   for j in range(per_in) for fy in range(fh) for fx in range(fw) for d in range(ci)}
+        for g in range(per_out):
+            acc = None
+            for fy in range(fh):
+                for fx in range(fw):
+                    for d in range(ci):
+                        for j in range(per_in):
+                            pt = o.pt_from_coeffs(ints["pt_coeffs"][fy, fx, d, j, g], ints["pt_scale"], xs[j].limbs)
+                            temp = o.mul_plain(rotated[(j, fy, fx, d)], pt)
+                            acc = temp if acc is None else o.add(acc, temp)
+            outs.append(o.div_scalar(acc, o.max_scalar_div(acc, float("inf"))))
+    return OTensor(outs, t.batch, oc_n, oh, ow, t.h_stride * stride, t.w_stride * stride, t.offset, 1, ci, t.c_stride)
+
+
+def rot_steps_conv_chw(o: Oracle, t: OTensor, fh, fw, pad_same=False):
+    wrap, amounts = chw_conv_geometry(o, t, fh, fw, pad_same)
+    steps = {a for plane in amounts for row in plane for a in row} | ({o.slots - wrap} if wrap else set())
+    return sorted(steps - {0})

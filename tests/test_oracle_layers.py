@@ -204,3 +204,60 @@ def test_chw_tensor_round_trip_and_clean_input_needs_no_mask():
     m, ints = layers.matmul(o, t, w, 2)
     assert ints["mask_coeffs"] is None and m.cts[0].limbs == 2
     assert np.abs(layers.tensor_decrypt(o, m) - plain_net.fc(x, w)).max() <= 1e-3
+
+
+def test_chw_conv_matches_plain_conv_and_op_counts():
+    """CHW-tiled convolution against the fp64 convolution: 5 -> 6 channels, 4 channel blocks per ciphertext (ragged
+    last ciphertexts on both sides), VALID and SAME (the SAME one reads the zero border the layout provides), once
+    with the blocks filling the slot vector (cyclic for free) and once with the copy behind them; clean outputs; the
+    multiplication count is OC*IC*taps / c_inner with whole ciphertexts, one rotation per (input ciphertext, tap, d)."""
+    x = synth.image(41, 5, 4, 4)[None]
+    w = synth.conv_weights(42, 3, 3, 5, 6)
+    for log_n, expect_wrap in ((9, 0), (10, 256)):
+        o = Oracle(log_n, [50, 40, 40], 3, 55, seed=14)
+        # planes of 4x4 inside a 6x6 frame (one zero slot around): row stride 6, first element at slot 7, blocks of 64
+        t = layers.tensor_encrypt_chw(o, x, 2.0 ** 40, 3, c_inner=4, c_stride=64, h_stride=6, offset=7)
+        wrap, amounts = layers.chw_conv_geometry(o, t, 3, 3, pad_same=True)
+        assert wrap == expect_wrap and amounts[1][1] == [0, 64, 128, 192] and amounts[0][0][0] == o.slots - 7
+        o.gen_rot_keys(sorted(set(layers.rot_steps_conv_chw(o, t, 3, 3, True)) | set(layers.rot_steps_conv_chw(o, t, 3, 3))))
+        counts = {"mul_plain": 0, "rot_left": 0, "div_scalar": 0}
+        real = {n: getattr(o, n) for n in counts}
+        for name in counts:
+            def f(*a, _n=name, **k):
+                counts[_n] += 1
+                return real[_n](*a, **k)
+            setattr(o, name, f)
+        same, _ = layers.conv2d_chw(o, t, w, pad_same=True)
+        for name in counts:
+            setattr(o, name, real[name])
+        per_in, per_out = 2, 2
+        assert counts["mul_plain"] == per_out * per_in * 9 * 4 and counts["div_scalar"] == per_out
+        assert counts["rot_left"] == per_in * 9 * 4 + (per_in if wrap else 0)
+        assert (same.channels, same.height, same.c_inner, same.c_stride, same.clean, len(same.cts)) == (6, 4, 4, 64, 1, 2)
+        assert np.abs(layers.tensor_decrypt(o, same) - plain_net.conv2d(x, w, pad_same=True)).max() <= 1e-3
+        z = o.decode(o.decrypt(same.cts[1])).real          # clean: channels 4, 5 in blocks 0, 1; nothing anywhere else
+        z[np.asarray(layers.tensor_slots(same)).reshape(4, 16)[:2].reshape(-1)] = 0
+        assert np.abs(z).max() <= 1e-3
+        valid, _ = layers.conv2d_chw(o, t, w)
+        assert (valid.height, valid.width) == (2, 2)
+        assert np.abs(layers.tensor_decrypt(o, valid) - plain_net.conv2d(x, w)).max() <= 1e-3
+
+
+def test_mask_tensor_cleans_a_pooled_tensor():
+    o = Oracle(10, [50, 40, 40], 3, 55, seed=15)
+    x = synth.image(51, 3, 4, 4)[None]
+    t = layers.tensor_encrypt_chw(o, x, 2.0 ** 40, 3, c_inner=2, c_stride=32, h_stride=4)
+    o.gen_rot_keys([1, 4, 5])
+    pool = layers.sum_pool2x2(o, t)
+    assert pool.clean == 0
+    z = o.decode(o.decrypt(pool.cts[0])).real
+    z[layers.tensor_slots(pool)] = 0
+    assert np.abs(z).max() > 0.1                           # leftovers between the pooled elements
+    m, ints = layers.mask_tensor(o, pool)
+    assert m.clean == 1 and m.cts[0].limbs == 2 and abs(m.cts[0].scale - pool.cts[0].scale) < 1e-6 * m.cts[0].scale
+    assert ints["mask_coeffs"].shape == (2, o.N)
+    assert np.abs(layers.tensor_decrypt(o, m) - plain_net.sum_pool2x2(x)).max() <= 1e-3
+    for ct in m.cts:
+        z = o.decode(o.decrypt(ct)).real
+        z[layers.tensor_slots(m)] = 0
+        assert np.abs(z).max() <= 1e-3
