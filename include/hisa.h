@@ -230,8 +230,8 @@ int hisa_analysis_end(hisa_ctx* ctx, hisa_op_counts* counts, int32_t* rot_steps,
  * is the runtime's flag that every slot that holds no element is zero.  The
  * struct is host memory owned by the caller; the handles in cts are owned like
  * any other handle.  Layer calls fill *out: out->cts must point to room for the
- * output handles.  conv2d and fc take HW-tiled tensors (HISA_ERR_ARG
- * otherwise); pool, activation, matmul, encrypt and decrypt take both. */
+ * output handles.  hisa_fc takes HW-tiled tensors (HISA_ERR_ARG otherwise);
+ * conv2d, pool, activation, matmul, mask, encrypt and decrypt take both. */
 typedef struct {
     uint32_t batch, channels;    /* logical outer dimensions                  */
     uint32_t height, width;      /* logical inner dimensions                  */
@@ -273,6 +273,25 @@ typedef struct {
  *   PLAIN: pt_coeffs[FH][FW][IC][OC][N] (scale pt_scale), w_int unused.
  * w_scale * pt_scale (or pt_scale alone for PLAIN, w_scale for SCALAR) should
  * equal the last modulus for the ciphertext scale to be preserved. */
+/* CHW-tiled input (c_inner > 1; Sec. "Homomorphic Tensor Operations", CHW
+ * paragraph: different weights on the channels of one ciphertext need mulPlain,
+ * and the channels of a ciphertext are combined with rotations by the channel
+ * stride): the mode must be HISA_CONV_PLAIN and the input clean (HISA_ERR_ARG
+ * otherwise; hisa_tensor_mask cleans a tensor).  The c_inner channel blocks are
+ * combined along diagonals: for d = 0..c_inner-1 output block b reads input
+ * block (b+d) mod c_inner, so every input ciphertext is rotated once per
+ * (tap, d), by tap amount + d*c_stride, and output ciphertext g is
+ *   divScalar( sum over taps, d, input ciphertexts j of
+ *              mulPlain(rot(x_j, tap, d), P[tap][d][j][g]) ),
+ * P holding on the valid output positions of block b the weight from input
+ * channel j*c_inner + (b+d) mod c_inner to output channel g*c_inner + b (zero
+ * where either does not exist), at scale q_last.  The block rotation is cyclic
+ * only if c_inner*c_stride equals the slot count; otherwise the blocks are first
+ * copied once behind themselves (x += rotRight(x, c_inner*c_stride); needs
+ * 2*c_inner*c_stride <= slots, else HISA_ERR_ARG).  fh*fw*c_inner is at most 256.
+ * Output: clean, CHW-tiled with the same c_inner and c_stride,
+ * batch*ceil(out_channels/c_inner) handles.  hisa_conv2d_fixed then takes
+ * pt_coeffs[FH][FW][c_inner][ceil(IC/c_inner)][ceil(OC/c_inner)][N]. */
 int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t out_channels,
                 const hisa_conv_geom* geom, hisa_tensor* out);
 int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* w_int, double w_scale,
@@ -315,6 +334,14 @@ typedef struct hisa_fc_plan hisa_fc_plan;
 int hisa_fc_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t out_features, hisa_fc_plan** plan);
 int hisa_fc_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_fc_plan* plan, hisa_tensor* out);
 int hisa_fc_plan_free(hisa_ctx* ctx, hisa_fc_plan* plan);
+/* The masking multiply as a layer (Sec. "Homomorphic Tensor Operations", SAME
+ * padding: invalid elements are masked out with one mulPlain): every ciphertext
+ * times the 0/1 vector of its element slots, encoded at the scale of the last
+ * modulus, then divScalar: same values and scale, one level lower, clean = 1.
+ * hisa_tensor_mask_fixed takes mask_coeffs[ceil(C/c_inner)][N] at mask_scale. */
+int hisa_tensor_mask(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out);
+int hisa_tensor_mask_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* mask_coeffs, double mask_scale,
+                           hisa_tensor* out);
 /* Homomorphic matmul with replicas (Sec. "Homomorphic Tensor Operations",
  * paragraphs "Homomorphic matmul" and "CHW-tiled convolution": replicas cost
  * log-many rotations and divide the number of mulPlain; reductions over equally

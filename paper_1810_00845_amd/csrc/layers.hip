@@ -15,7 +15,7 @@
 
 #define NT 256
 #define OCB 4
-#define MAX_TAPS 64
+#define MAX_TAPS 256   // rotation amounts per input ciphertext: filter taps (x channel blocks for CHW-tiling)
 
 struct MacArgs {
     const u64* tap_base[MAX_TAPS];  // per tap: [batch*IC][2][l][N]
@@ -451,13 +451,25 @@ static int32_t norm_step(const hisa_ctx* ctx, i64 r) {
     return (int32_t)r;
 }
 
+// Rotation amounts of a convolution, one per (tap, d): HW-tiling has d = 0 only; with c_inner channel blocks per
+// ciphertext the blocks are combined along diagonals (output block b reads input block (b + d) mod c_inner), so every
+// tap is also rotated by d blocks.
 static std::vector<int32_t> conv_tap_steps(const hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g) {
     std::vector<int32_t> steps;
     const i64 ph = g->pad_same ? g->fh / 2 : 0, pw = g->pad_same ? g->fw / 2 : 0;
     for (uint32_t fy = 0; fy < g->fh; fy++)
         for (uint32_t fx = 0; fx < g->fw; fx++)
-            steps.push_back(norm_step(ctx, ((i64)fy - ph) * in->h_stride + ((i64)fx - pw) * in->w_stride));
+            for (uint32_t d = 0; d < t_ci(in); d++)
+                steps.push_back(norm_step(ctx, ((i64)fy - ph) * in->h_stride + ((i64)fx - pw) * in->w_stride + (i64)d * in->c_stride));
     return steps;
+}
+
+// The block rotation above wraps around cyclically only if the blocks fill the slot vector; otherwise a copy of the
+// blocks is first placed behind them (rotRight by this amount and add).  0: not needed.  -1: no room for the copy.
+static i64 conv_wrap_amount(const hisa_ctx* ctx, const hisa_tensor* in) {
+    const u64 span = (u64)t_ci(in) * in->c_stride, slots = ctx->N / 2;
+    if (t_ci(in) == 1 || span == slots) return 0;
+    return 2 * span <= slots ? (i64)span : -1;
 }
 
 static int write_steps(const std::vector<int32_t>& all, int32_t* steps, size_t cap, size_t* n) {
@@ -479,7 +491,10 @@ static int write_steps(const std::vector<int32_t>& all, int32_t* steps, size_t c
 extern "C" int hisa_conv2d_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* geom, int32_t* steps,
                                      size_t cap, size_t* n) {
     if (!ctx || !in || !geom) return HISA_ERR_ARG;
-    return write_steps(conv_tap_steps(ctx, in, geom), steps, cap, n);
+    std::vector<int32_t> all = conv_tap_steps(ctx, in, geom);
+    const i64 wrap = conv_wrap_amount(ctx, in);
+    if (wrap > 0) all.push_back(norm_step(ctx, -wrap));
+    return write_steps(all, steps, cap, n);
 }
 
 // Rotation amounts of the rotate-and-add that brings the sum over a plane into slot `offset`.  Strided form:
@@ -609,13 +624,20 @@ static void fill_out_meta(hisa_tensor* out, uint32_t batch, uint32_t channels, u
 // ---------------------------------------------------------------------------
 struct ConvPlan {
     uint32_t out_h, out_w;
-    std::vector<int32_t> steps;
+    std::vector<int32_t> steps;   // one per (tap, d)
+    i64 wrap = 0;                 // CHW-tiling: rotRight amount of the copy behind the channel blocks, 0 if none
 };
 
 static int conv_plan(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, ConvPlan* p) {
-    if (!g || g->fh == 0 || g->fw == 0 || g->stride == 0 || g->fh * g->fw > MAX_TAPS || g->mode > HISA_CONV_PLAIN)
-        return fail(ctx, HISA_ERR_ARG, "bad conv geometry");
-    TRY(require_hw_tiling(ctx, in, "conv2d"));
+    if (!g || g->fh == 0 || g->fw == 0 || g->stride == 0 || (u64)g->fh * g->fw * t_ci(in) > MAX_TAPS || g->mode > HISA_CONV_PLAIN)
+        return fail(ctx, HISA_ERR_ARG, "bad conv geometry (at most %d rotation amounts per input ciphertext)", MAX_TAPS);
+    if (t_ci(in) > 1) {
+        // several channels per ciphertext: different weights on different slots, so mulPlain, and zeros between the elements
+        if (g->mode != HISA_CONV_PLAIN) return fail(ctx, HISA_ERR_ARG, "CHW-tiled convolution multiplies by plaintexts: mode HISA_CONV_PLAIN");
+        if (!in->clean) return fail(ctx, HISA_ERR_ARG, "CHW-tiled convolution needs a clean input tensor (hisa_tensor_mask makes one)");
+        p->wrap = conv_wrap_amount(ctx, in);
+        if (p->wrap < 0) return fail(ctx, HISA_ERR_ARG, "the channel blocks must fill the slots or leave room for one copy behind them");
+    }
     if (g->pad_same) {
         if (!in->clean) return fail(ctx, HISA_ERR_ARG, "SAME padding needs a clean input tensor (zeros around the plane)");
         p->out_h = (in->height + g->stride - 1) / g->stride;
@@ -698,14 +720,35 @@ static int upload_weight_residues(hisa_ctx* ctx, const int64_t* w_int, uint32_t 
 // dw: SCALAR/MASKED weights (null for PLAIN); d_pts: MASKED [l][N], PLAIN [T][OC][l][N]
 static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
                     DevWeights* dw, double w_scale, const u64* d_pts, double pt_scale, hisa_tensor* out) {
-    const uint32_t B = in->batch, IC = in->channels, l = in->cts[0]->limbs;
+    // in units of ciphertexts: IC inputs and OCm outputs per image (HW-tiling: the channels themselves)
+    const uint32_t B = in->batch, ci = t_ci(in), IC = (uint32_t)t_per(in), OCm = (OC + ci - 1) / ci, l = in->cts[0]->limbs;
     const size_t nct = (size_t)B * IC, n = ctx->N;
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
     const int n_taps = (int)plan.steps.size();
+    std::vector<hisa_ct*> wrapped;   // inputs with the copy of their channel blocks behind them
+    hisa_ct* const* src = in->cts;
+    if (plan.wrap > 0) {
+        wrapped.assign(nct, nullptr);
+        TRY(hisa_rot_left_batch(ctx, (const hisa_ct* const*)in->cts, nct, norm_step(ctx, -plan.wrap), wrapped.data()));
+        BatchIn orig;
+        int rcw = gather_batch(ctx, (const hisa_ct* const*)in->cts, nct, &orig);
+        if (rcw == HISA_OK) {
+            const u64 words = ct_words(ctx, 2, l);
+            hipError_t e = launch_addsub(ctx->d_primes, wrapped[0]->data, orig.base, wrapped[0]->data, OP_ADD, (int)l, 2, 2, nct, words,
+                                         orig.stride, words, (int)ctx->log_n, ctx->stream);
+            if (e != hipSuccess) rcw = fail(ctx, HISA_ERR_HIP, "conv wrap: %s", hipGetErrorString(e));
+        }
+        dev_release(ctx, orig.tmp);
+        if (rcw != HISA_OK) { free_handles(ctx, wrapped); return rcw; }
+        src = wrapped.data();
+    }
     BatchIn bi;
-    TRY(gather_batch(ctx, (const hisa_ct* const*)in->cts, nct, &bi));
+    {
+        const int rcg = gather_batch(ctx, (const hisa_ct* const*)src, nct, &bi);
+        if (rcg != HISA_OK) { free_handles(ctx, wrapped); return rcg; }
+    }
     std::vector<std::vector<hisa_ct*>> rotated(n_taps);
-    std::vector<hisa_ct*> outs((size_t)B * OC, nullptr);
+    std::vector<hisa_ct*> outs((size_t)B * OCm, nullptr);
     MacArgs ma = {};
     int rc = HISA_OK;
     {   // all taps rotate the same inputs: one call, so that the decomposition of c1 is shared by the taps
@@ -717,7 +760,7 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
         }
         if (!nz.empty()) {
             std::vector<hisa_ct*> all(nz.size() * nct, nullptr);
-            rc = hisa_rot_left_hoisted_batch(ctx, (const hisa_ct* const*)in->cts, nct, nz.data(), nz.size(), all.data());
+            rc = hisa_rot_left_hoisted_batch(ctx, (const hisa_ct* const*)src, nct, nz.data(), nz.size(), all.data());
             for (size_t k = 0; k < nz.size() && rc == HISA_OK; k++) {
                 rotated[tap_of[k]].assign(all.begin() + k * nct, all.begin() + (k + 1) * nct);
                 ma.tap_base[tap_of[k]] = rotated[tap_of[k]][0]->data;
@@ -726,13 +769,13 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
     }
     const double in_scale = in->cts[0]->scale;
     double mac_scale = in_scale * (g->mode == HISA_CONV_PLAIN ? pt_scale : w_scale);
-    if (rc == HISA_OK) rc = alloc_ct_batch(ctx, (size_t)B * OC, 2, l, mac_scale, outs.data());
+    if (rc == HISA_OK) rc = alloc_ct_batch(ctx, (size_t)B * OCm, 2, l, mac_scale, outs.data());
     if (rc == HISA_OK) {
-        ma.n_taps = n_taps; ma.IC = (int)IC; ma.OC = (int)OC; ma.l = (int)l; ma.ct_words = 2 * (u64)l * n;
+        ma.n_taps = n_taps; ma.IC = (int)IC; ma.OC = (int)OCm; ma.l = (int)l; ma.ct_words = 2 * (u64)l * n;
         ma.out = outs[0]->data;
         hipError_t e;
         if (g->mode == HISA_CONV_PLAIN) {
-            ma.w = d_pts; ma.w_stride_t = OC; ma.w_stride_oc = 1;
+            ma.w = d_pts; ma.w_stride_t = OCm; ma.w_stride_oc = 1;
             if (ctx->tabs.fp_ok) e = launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
             else e = launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
         } else {
@@ -757,6 +800,7 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
     }
     for (auto& v : rotated) free_handles(ctx, v);
     dev_release(ctx, bi.tmp);
+    free_handles(ctx, wrapped);
     if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
     if (rc != HISA_OK) {
         for (hisa_ct* c : outs) hisa_free(ctx, c);
@@ -766,7 +810,7 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
     // unmasked outputs carry neighbour sums outside the valid positions, except for a 1x1 stride-1 filter
     const bool keeps_zeros = g->fh == 1 && g->fw == 1 && g->stride == 1 && in->clean;
     fill_out_meta(out, B, OC, plan.out_h, plan.out_w, in->h_stride * g->stride, in->w_stride * g->stride, in->offset,
-                  (g->mode != HISA_CONV_SCALAR || keeps_zeros) ? 1u : 0u);
+                  (g->mode != HISA_CONV_SCALAR || keeps_zeros) ? 1u : 0u, ci, in->c_stride);
     return HISA_OK;
 }
 
@@ -777,13 +821,13 @@ extern "C" int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int
     if (!out || !out->cts || OC == 0) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
     ConvPlan plan;
     TRY(conv_plan(ctx, in, geom, &plan));
-    const uint32_t l = in->cts[0]->limbs, IC = in->channels;
+    const uint32_t l = in->cts[0]->limbs, IC = (uint32_t)t_per(in), OCm = (OC + t_ci(in) - 1) / t_ci(in);
     const size_t T = plan.steps.size() * IC, n = ctx->N;
     if (geom->mode == HISA_CONV_PLAIN) {
         if (!pt_coeffs) return fail(ctx, HISA_ERR_ARG, "PLAIN mode needs plaintext coefficients");
-        Temp pts(ctx, T * OC * l * n * sizeof(u64));
+        Temp pts(ctx, T * OCm * l * n * sizeof(u64));
         if (!pts.ok()) return HISA_ERR_OOM;
-        TRY(coeffs_to_plain_batch(ctx, pt_coeffs, T * OC, (int)l, pts.u()));
+        TRY(coeffs_to_plain_batch(ctx, pt_coeffs, T * OCm, (int)l, pts.u()));
         return conv_run(ctx, in, geom, plan, OC, nullptr, 1.0, pts.u(), pt_scale, out);
     }
     if (!w_int) return fail(ctx, HISA_ERR_ARG, "null weights");
@@ -817,6 +861,34 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
     const double q_last = (double)ctx->mod[l - 1];
     const std::vector<uint32_t> vslots = plane_slots(plan.out_h, plan.out_w, in->h_stride * geom->stride,
                                                      in->w_stride * geom->stride, in->offset);
+    if (t_ci(in) > 1) {
+        // plaintext (tap, d, input ciphertext j, output ciphertext g): on the valid output positions of block b the
+        // weight from input channel j ci + (b + d) mod ci to output channel g ci + b, zero where either does not exist
+        const uint32_t ci = t_ci(in), per_in = (uint32_t)t_per(in), per_out = (OC + ci - 1) / ci;
+        const size_t n_pts = taps * per_in * per_out, pos = vslots.size(), nnz = ci * pos;
+        std::vector<uint32_t> slots;
+        for (uint32_t b = 0; b < ci; b++)
+            for (uint32_t v : vslots) slots.push_back(v + b * in->c_stride);
+        cw.pts = new Temp(ctx, n_pts * l * n * sizeof(u64));
+        if (!cw.pts->ok()) return HISA_ERR_OOM;
+        cw.pt_scale = q_last;
+        const size_t chunk = std::max<size_t>(1, std::min<size_t>(n_pts, ((size_t)256 << 20) / (nnz * sizeof(double) + n * 8)));
+        std::vector<double> vals;
+        for (size_t p0 = 0; p0 < n_pts; p0 += chunk) {
+            const size_t cnt = std::min(chunk, n_pts - p0);
+            vals.assign(cnt * nnz, 0.0);
+            for (size_t q = 0; q < cnt; q++) {
+                const size_t idx = p0 + q, g_ = idx % per_out, j = (idx / per_out) % per_in, td = idx / per_out / per_in;
+                const size_t d = td % ci, tap = td / ci;
+                for (uint32_t b = 0; b < ci; b++) {
+                    const size_t ic = j * ci + (b + d) % ci, oc = g_ * ci + b;
+                    if (ic < IC && oc < OC) std::fill_n(vals.begin() + q * nnz + b * pos, pos, w[(tap * IC + ic) * OC + oc]);
+                }
+            }
+            TRY(encode_sparse_batch(ctx, slots, vals.data(), cnt, q_last, (int)l, cw.pts->u() + p0 * l * n));
+        }
+        return HISA_OK;
+    }
     if (geom->mode == HISA_CONV_PLAIN) {
         // plaintext (tap, ic, oc) = weight on every valid output position, zero elsewhere, at scale q_last
         cw.pts = new Temp(ctx, T * OC * l * n * sizeof(u64));
@@ -863,7 +935,7 @@ extern "C" int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w
 struct hisa_conv_plan {
     uint32_t magic;
     hisa_conv_geom geom;
-    uint32_t out_channels, channels, height, width, h_stride, w_stride, offset, clean, limbs;
+    uint32_t out_channels, channels, height, width, h_stride, w_stride, offset, clean, limbs, c_inner, c_stride;
     ConvWeights cw;
 };
 
@@ -875,7 +947,8 @@ extern "C" int hisa_conv2d_prepare(hisa_ctx* ctx, const hisa_tensor* like, const
     ConvPlan plan;
     TRY(conv_plan(ctx, like, geom, &plan));
     hisa_conv_plan* p = new hisa_conv_plan{HISA_MAGIC_CONVPLAN, *geom, OC, like->channels, like->height, like->width,
-                                           like->h_stride, like->w_stride, like->offset, like->clean, like->cts[0]->limbs, {}};
+                                           like->h_stride, like->w_stride, like->offset, like->clean, like->cts[0]->limbs,
+                                           t_ci(like), like->c_stride, {}};
     const int rc = conv_build(ctx, like, w, OC, geom, plan, p->cw);
     if (rc != HISA_OK) { delete p; return rc; }
     *plan_out = p;
@@ -895,7 +968,7 @@ extern "C" int hisa_conv2d_apply(hisa_ctx* ctx, const hisa_tensor* in, const his
     if (!out || !out->cts) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
     if (in->channels != plan->channels || in->height != plan->height || in->width != plan->width ||
         in->h_stride != plan->h_stride || in->w_stride != plan->w_stride || in->offset != plan->offset ||
-        in->clean != plan->clean)
+        in->clean != plan->clean || t_ci(in) != plan->c_inner || (t_ci(in) > 1 && in->c_stride != plan->c_stride))
         return fail(ctx, HISA_ERR_ARG, "the plan was prepared for another tensor layout");
     if (in->cts[0]->limbs != plan->limbs)
         return fail(ctx, HISA_ERR_LEVEL_MISMATCH, "the plan was prepared for %u limbs, the tensor has %u", plan->limbs,
@@ -1152,6 +1225,76 @@ static int rotate_add_batch(hisa_ctx* ctx, std::vector<hisa_ct*>& xs, int32_t st
     return HISA_OK;
 }
 
+// The masking multiply (Sec. "Homomorphic Tensor Operations", SAME-padding paragraph): xs = rescale(in * mask), the
+// mask being 0/1 on the element slots at the scale of the last modulus.  masks: NTT-form plaintexts [per][l][N];
+// ciphertext j of every image takes mask j (they differ only where a last ciphertext holds fewer channels).
+static int mask_run(hisa_ctx* ctx, const hisa_tensor* in, const u64* masks, double mask_scale, std::vector<hisa_ct*>& xs) {
+    const uint32_t B = in->batch, per = (uint32_t)t_per(in), l = in->cts[0]->limbs;
+    const size_t n_in = (size_t)B * per, n = ctx->N;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "the masking multiply needs a level to rescale into");
+    xs.assign(n_in, nullptr);
+    BatchIn bi;
+    TRY(gather_batch(ctx, (const hisa_ct* const*)in->cts, n_in, &bi));
+    const u64 words = ct_words(ctx, 2, l);
+    int rc = alloc_ct_batch(ctx, n_in, 2, l, in->cts[0]->scale * mask_scale, xs.data());
+    if (rc == HISA_OK) {
+        hipError_t e = hipSuccess;
+        for (uint32_t j = 0; j < per && e == hipSuccess; j++)
+            e = launch_mul_plain(ctx->d_primes, bi.base + (u64)j * bi.stride, masks + (u64)j * l * n, xs[0]->data + (u64)j * words,
+                                 (int)l, 2, B, (u64)per * bi.stride, (u64)per * words, (int)ctx->log_n, ctx->stream);
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "masking multiply: %s", hipGetErrorString(e));
+    }
+    dev_release(ctx, bi.tmp);
+    if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, xs.data(), n_in);
+    if (rc != HISA_OK) free_handles(ctx, xs);
+    return rc;
+}
+
+// 0/1 masks of the element slots of every ciphertext of an image, NTT form [per][l][N]
+static int encode_masks(hisa_ctx* ctx, const hisa_tensor* t, double scale, uint32_t l, u64* out) {
+    const uint32_t ci = t_ci(t), per = (uint32_t)t_per(t);
+    const size_t hw = (size_t)t->height * t->width;
+    std::vector<double> ones((size_t)per * ci * hw, 0.0);
+    for (uint32_t j = 0; j < per; j++)
+        for (uint32_t c = 0; c < std::min(ci, t->channels - j * ci); c++)
+            for (size_t k = 0; k < hw; k++) ones[((size_t)j * ci + c) * hw + k] = 1.0;
+    return encode_sparse_batch(ctx, tensor_slots(t), ones.data(), per, scale, (int)l, out);
+}
+
+static int mask_finish(hisa_ctx* ctx, const hisa_tensor* in, std::vector<hisa_ct*>& xs, hisa_tensor* out) {
+    for (size_t i = 0; i < xs.size(); i++) out->cts[i] = xs[i];
+    fill_out_meta(out, in->batch, in->channels, in->height, in->width, in->h_stride, in->w_stride, in->offset, 1, t_ci(in),
+                  in->c_stride);
+    return HISA_OK;
+}
+
+extern "C" int hisa_tensor_mask(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out) {
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
+    const uint32_t l = in->cts[0]->limbs;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "the masking multiply needs a level to rescale into");
+    Temp masks(ctx, t_per(in) * l * ctx->N * sizeof(u64));
+    if (!masks.ok()) return HISA_ERR_OOM;
+    const double mask_scale = (double)ctx->mod[l - 1];
+    TRY(encode_masks(ctx, in, mask_scale, l, masks.u()));
+    std::vector<hisa_ct*> xs;
+    TRY(mask_run(ctx, in, masks.u(), mask_scale, xs));
+    return mask_finish(ctx, in, xs, out);
+}
+
+extern "C" int hisa_tensor_mask_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* mask_coeffs, double mask_scale,
+                                      hisa_tensor* out) {
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts || !mask_coeffs) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    const uint32_t l = in->cts[0]->limbs;
+    Temp masks(ctx, t_per(in) * l * ctx->N * sizeof(u64));
+    if (!masks.ok()) return HISA_ERR_OOM;
+    TRY(coeffs_to_plain_batch(ctx, mask_coeffs, t_per(in), (int)l, masks.u()));
+    std::vector<hisa_ct*> xs;
+    TRY(mask_run(ctx, in, masks.u(), mask_scale, xs));
+    return mask_finish(ctx, in, xs, out);
+}
+
 // masks: NTT-form plaintexts [per][l][N] (needed when R > 1 and the input is not clean), pts: [groups][per][l'][N] with
 // l' = l - 1 after the masking multiply, else l.
 static int matmul_run(hisa_ctx* ctx, const hisa_tensor* in, const MatmulGeom& g, const u64* masks, double mask_scale,
@@ -1165,28 +1308,20 @@ static int matmul_run(hisa_ctx* ctx, const hisa_tensor* in, const MatmulGeom& g,
     std::vector<hisa_ct*> xs;     // working copies of the inputs (R > 1 only)
     int rc = HISA_OK;
     if (g.R > 1) {
-        xs.assign(n_in, nullptr);
-        BatchIn bi;
-        TRY(gather_batch(ctx, (const hisa_ct* const*)in->cts, n_in, &bi));
-        const u64 words = ct_words(ctx, 2, l);
-        rc = alloc_ct_batch(ctx, n_in, 2, l, in->cts[0]->scale * (masked ? mask_scale : 1.0), xs.data());
-        if (rc == HISA_OK) {
-            hipError_t e = hipSuccess;
-            if (masked) {
-                // ciphertext j of every image takes mask j (they differ only where a last ciphertext holds fewer channels)
-                for (uint32_t j = 0; j < per && e == hipSuccess; j++)
-                    e = launch_mul_plain(ctx->d_primes, bi.base + (u64)j * bi.stride, masks + (u64)j * l * n,
-                                         xs[0]->data + (u64)j * words, (int)l, 2, B, (u64)per * bi.stride, (u64)per * words,
-                                         (int)ctx->log_n, ctx->stream);
-            } else {
-                e = hipMemcpyAsync(xs[0]->data, bi.base, n_in * words * sizeof(u64), hipMemcpyDeviceToDevice, ctx->stream);
-            }
-            if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "matmul input: %s", hipGetErrorString(e));
-        }
-        dev_release(ctx, bi.tmp);
-        if (rc == HISA_OK && masked) {
-            rc = hisa_rescale_batch(ctx, xs.data(), n_in);
+        if (masked) {
+            rc = mask_run(ctx, in, masks, mask_scale, xs);
             l -= 1;
+        } else {
+            xs.assign(n_in, nullptr);
+            BatchIn bi;
+            TRY(gather_batch(ctx, (const hisa_ct* const*)in->cts, n_in, &bi));
+            const u64 words = ct_words(ctx, 2, l);
+            rc = alloc_ct_batch(ctx, n_in, 2, l, in->cts[0]->scale, xs.data());
+            if (rc == HISA_OK) {
+                hipError_t e = hipMemcpyAsync(xs[0]->data, bi.base, n_in * words * sizeof(u64), hipMemcpyDeviceToDevice, ctx->stream);
+                if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "matmul input: %s", hipGetErrorString(e));
+            }
+            dev_release(ctx, bi.tmp);
         }
         for (size_t k = 0; k < g.replicate.size() && rc == HISA_OK; k++)
             rc = rotate_add_batch(ctx, xs, norm_step(ctx, -g.replicate[k]));
@@ -1255,7 +1390,7 @@ static int matmul_build(hisa_ctx* ctx, const hisa_tensor* like, const double* w,
     uint32_t l = like->cts[0]->limbs;
     const bool masked = g.R > 1 && !like->clean;
     if (l < (masked ? 3u : 2u)) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "matmul needs %d levels to rescale into", masked ? 2 : 1);
-    const size_t n = ctx->N, hw = (size_t)like->height * like->width, elems = (size_t)ci * hw;
+    const size_t n = ctx->N, hw = (size_t)like->height * like->width;
     const std::vector<uint32_t> slots = tensor_slots(like);
     hisa_matmul_plan* p = new_matmul_plan(like, OUT, replicas);
     int rc = HISA_OK;
@@ -1263,11 +1398,7 @@ static int matmul_build(hisa_ctx* ctx, const hisa_tensor* like, const double* w,
         p->mask_scale = (double)ctx->mod[l - 1];
         p->masks = dev_alloc(ctx, (size_t)per * l * n * sizeof(u64));
         if (!p->masks) rc = HISA_ERR_OOM;
-        std::vector<double> ones((size_t)per * elems, 0.0);
-        for (uint32_t j = 0; j < per; j++)
-            for (uint32_t c = 0; c < std::min(ci, C - j * ci); c++)
-                for (size_t k = 0; k < hw; k++) ones[((size_t)j * ci + c) * hw + k] = 1.0;
-        if (rc == HISA_OK) rc = encode_sparse_batch(ctx, slots, ones.data(), per, p->mask_scale, (int)l, (u64*)p->masks->ptr);
+        if (rc == HISA_OK) rc = encode_masks(ctx, like, p->mask_scale, l, (u64*)p->masks->ptr);
         l -= 1;
     }
     if (rc == HISA_OK) {

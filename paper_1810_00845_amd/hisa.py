@@ -403,7 +403,7 @@ class Context:
         assert w.shape[:3] == (fh, fw, t.channels)
         oc = w.shape[3]
         g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode)
-        return self._layer("hisa_conv2d", t, t.batch * oc, _dp(w), C.c_uint32(oc), C.byref(g))
+        return self._layer("hisa_conv2d", t, t.batch * -(-oc // t.c_inner), _dp(w), C.c_uint32(oc), C.byref(g))
 
     def conv2d_prepare(self, like, w, fh, fw, stride=1, pad_same=False, mode=CONV_SCALAR):
         """Converts conv weights once for tensors laid out like `like`; returns a plan for conv2d_apply (free with
@@ -415,7 +415,7 @@ class Context:
         st, _arr = like._struct()
         plan = C.c_void_p()
         self._ck(load().hisa_conv2d_prepare(self._vp, C.byref(st), _dp(w), C.c_uint32(oc), C.byref(g), C.byref(plan)))
-        return (plan, oc)
+        return (plan, -(-oc // like.c_inner))
 
     def conv2d_apply(self, t, plan):
         return self._layer("hisa_conv2d_apply", t, t.batch * plan[1], plan[0])
@@ -428,7 +428,7 @@ class Context:
         wi = np.ascontiguousarray(w_int, dtype=np.int64) if w_int is not None else None
         pc = np.ascontiguousarray(pt_coeffs, dtype=np.int64) if pt_coeffs is not None else None
         g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode)
-        return self._layer("hisa_conv2d_fixed", t, t.batch * oc, wi.ctypes.data_as(i64p) if wi is not None else None,
+        return self._layer("hisa_conv2d_fixed", t, t.batch * -(-oc // t.c_inner), wi.ctypes.data_as(i64p) if wi is not None else None,
                            C.c_double(w_scale), pc.ctypes.data_as(i64p) if pc is not None else None, C.c_double(pt_scale),
                            C.c_uint32(oc), C.byref(g))
 
@@ -461,6 +461,15 @@ class Context:
         assert pc.shape == (out_features, t.channels, self.N)
         return self._layer("hisa_fc_fixed", t, t.batch * out_features, pc.ctypes.data_as(C.POINTER(C.c_int64)),
                            C.c_double(pt_scale), C.c_uint32(out_features))
+
+    def tensor_mask(self, t):
+        """The masking multiply: same tensor, one level lower, zeros outside the elements."""
+        return self._layer("hisa_tensor_mask", t, len(t.cts))
+
+    def tensor_mask_fixed(self, t, mask_coeffs, mask_scale):
+        mc = np.ascontiguousarray(mask_coeffs, dtype=np.int64)
+        assert mc.shape == (-(-t.channels // t.c_inner), self.N)
+        return self._layer("hisa_tensor_mask_fixed", t, len(t.cts), mc.ctypes.data_as(C.POINTER(C.c_int64)), C.c_double(mask_scale))
 
     def matmul_geometry(self, t, out_features, replicas):
         """(block length P, replicas used R, number of output ciphertexts) of matmul on tensors laid out like t."""

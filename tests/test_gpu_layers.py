@@ -300,3 +300,90 @@ def test_chw_tensor_layers_and_errors():
         g.rescale_batch(gp.cts)
         g.matmul(gp, w[:, :, :2, :2], 2)
     g.close()
+
+
+def chw_pair(g, o, x, scale, limbs, c_inner, c_stride, counter, **layout):
+    """The same CHW-tiled encrypted tensor on both sides, from the oracle's encodings."""
+    from oracle import layers
+    from paper_1810_00845_amd import hisa
+    b, c, h, w = x.shape
+    ot = layers.tensor_encrypt_chw(o, x, scale, limbs, c_inner, c_stride, **layout)
+    sl = np.asarray(layers.tensor_slots(ot)).reshape(c_inner, h * w)
+    per = layers.cts_per_image(ot)
+    g.set_enc_counter(counter); o.enc_counter = counter
+    ocs, gcs = [], []
+    for bi in range(b):
+        for j in range(per):
+            z = np.zeros(o.slots)
+            for cl in range(min(c_inner, c - j * c_inner)):
+                z[sl[cl]] = x[bi, j * c_inner + cl].reshape(-1)
+            co = o.encode_coeffs(z, scale)
+            ocs.append(o.encrypt(o.pt_from_coeffs(co, scale, limbs)))
+            gcs.append(g.encrypt(g.pt_from_coeffs(co, scale, limbs)))
+    ot.cts = ocs
+    gt = hisa.CipherTensor(g, gcs, b, c, h, w, ot.h_stride, ot.w_stride, ot.offset, 1, c_inner, c_stride)
+    return gt, ot
+
+
+@pytest.mark.parametrize("log_n,c_stride", [(10, 128), (10, 64), (12, 64), (12, 512)])
+def test_chw_conv_bit_exact(log_n, c_stride):
+    """CHW-tiled convolution through the C ABI against the oracle, bit for bit: batch of two, 5 -> 6 channels in
+    blocks of 4 (ragged last ciphertexts), SAME and VALID, stride 1 and 2; blocks filling the slots (4 x 128 = 512 slots
+    at N = 2^10, 4 x 512 at N = 2^12: cyclic for free) and with the copy behind them; both arithmetic paths (N = 2^12:
+    fp64); plan and float entry point."""
+    from oracle import layers
+    from paper_1810_00845_amd import synth
+    g, o = make_pair(log_n, [50, 40, 40], 3, 50, 14)
+    x = synth.image(41, 5, 4, 4)[None].repeat(2, axis=0) * np.array([1.0, -0.7])[:, None, None, None]
+    w = synth.conv_weights(42, 3, 3, 5, 6)
+    gt, ot = chw_pair(g, o, x, 2.0 ** 40, 3, 4, c_stride, 900, h_stride=6, offset=7)
+    same_tensor(g, o, gt, ot)
+    assert (layers.chw_conv_geometry(o, ot, 3, 3)[0] == 0) == (4 * c_stride == o.slots)
+    steps = sorted(set(g.conv2d_rot_steps(gt, 3, 3, pad_same=True)) | set(g.conv2d_rot_steps(gt, 3, 3)))
+    assert steps == sorted(set(layers.rot_steps_conv_chw(o, ot, 3, 3, True)) | set(layers.rot_steps_conv_chw(o, ot, 3, 3)))
+    g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+    for kw, ref in ((dict(pad_same=True), plain_net.conv2d(x, w, pad_same=True)), (dict(), plain_net.conv2d(x, w)),
+                    (dict(stride=2, pad_same=True), plain_net.conv2d(x, w, stride=2, pad_same=True))):
+        oout, ints = layers.conv2d_chw(o, ot, w, **kw)
+        gout = g.conv2d_fixed(gt, None, 1.0, ints["pt_coeffs"], ints["pt_scale"], 6, 3, 3, mode=layers.CONV_PLAIN, **kw)
+        same_tensor(g, o, gout, oout)
+        assert np.abs(g.tensor_decrypt(gout) - ref).max() <= 1e-3
+        gfloat = g.conv2d(gt, w, 3, 3, mode=layers.CONV_PLAIN, **kw)
+        assert gfloat.meta() == gout.meta() and np.abs(g.tensor_decrypt(gfloat) - ref).max() <= 1e-3
+        plan = g.conv2d_prepare(gt, w, 3, 3, mode=layers.CONV_PLAIN, **kw)
+        gplan = g.conv2d_apply(gt, plan)
+        for ca, cb in zip(gfloat.cts, gplan.cts):
+            assert np.array_equal(g.ct_export(ca), g.ct_export(cb))
+        g.conv_plan_free(plan)
+    from paper_1810_00845_amd import hisa
+    with pytest.raises(hisa.HisaError):                    # scalar weights cannot tell the channels of a ciphertext apart
+        g.conv2d(gt, w, 3, 3, mode=layers.CONV_SCALAR)
+    g.close()
+
+
+def test_mask_layer_then_chw_conv_on_a_pooled_tensor():
+    """pool (not clean) -> masking multiply -> CHW convolution, every step bit for bit; the convolution refuses the
+    unmasked tensor."""
+    from oracle import layers
+    from paper_1810_00845_amd import hisa, synth
+    g, o = make_pair(10, [50, 40, 40, 40], 2, 50, 15)
+    x = synth.image(51, 3, 4, 4)[None]
+    gt, ot = chw_pair(g, o, x, 2.0 ** 40, 4, 2, 32, 901, h_stride=4)
+    g.gen_rot_keys([1, 4, 5]); o.gen_rot_keys([1, 4, 5])
+    gp, op = g.sum_pool2x2(gt), layers.sum_pool2x2(o, ot)
+    same_tensor(g, o, gp, op)
+    w = synth.conv_weights(52, 1, 1, 3, 4)
+    with pytest.raises(hisa.HisaError):
+        g.conv2d(gp, w, 1, 1, mode=layers.CONV_PLAIN)
+    om, ints = layers.mask_tensor(o, op)
+    gm = g.tensor_mask_fixed(gp, ints["mask_coeffs"], ints["mask_scale"])
+    same_tensor(g, o, gm, om)
+    gm2 = g.tensor_mask(gp)
+    assert gm2.meta() == gm.meta() and np.abs(g.tensor_decrypt(gm2) - plain_net.sum_pool2x2(x)).max() <= 1e-3
+    steps = g.conv2d_rot_steps(gm, 1, 1)
+    g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+    oc_, ints = layers.conv2d_chw(o, om, w)
+    gc_ = g.conv2d_fixed(gm, None, 1.0, ints["pt_coeffs"], ints["pt_scale"], 4, 1, 1, mode=layers.CONV_PLAIN)
+    same_tensor(g, o, gc_, oc_)
+    assert np.abs(g.tensor_decrypt(gc_) - plain_net.conv2d(plain_net.sum_pool2x2(x), w)).max() <= 1e-3
+    g.close()
