@@ -36,6 +36,47 @@ hipError_t launch_encode(const double* cs, const double* sn, const uint32_t* g, 
     return hipGetLastError();
 }
 
+// Plaintexts that are piecewise constant -- value v[p][b] on slot set S_b, zero elsewhere -- are linear combinations of
+// the nb encodings of the indicator vectors of the S_b: coeffs[p][k] = round(factor * sum_b v[p][b] basis[b][k]) with
+// basis[b][k] = sum_{j in S_b} cos(pi g_j k / N), which costs nb terms per coefficient instead of one per slot.
+__global__ __launch_bounds__(NT) void encode_basis_kernel(const double* cs, const uint32_t* g, const int* set_begin,
+                                                          double* basis, int log_n) {
+    const uint32_t k = blockIdx.x * NT + threadIdx.x;
+    const uint32_t mask = (2u << log_n) - 1;
+    const int b = blockIdx.y;
+    double acc = 0.0;
+    for (int j = set_begin[b]; j < set_begin[b + 1]; j++) acc += cs[(g[j] * k) & mask];
+    basis[((size_t)b << log_n) + k] = acc;
+}
+
+__global__ __launch_bounds__(NT) void encode_combine_kernel(const double* basis, int nb, const double* v, double factor,
+                                                            i64* coeffs, int log_n) {
+    const uint32_t k = blockIdx.x * NT + threadIdx.x;
+    const size_t p = blockIdx.y;
+    double acc = 0.0;
+    for (int b = 0; b < nb; b++) acc += v[p * nb + b] * basis[((size_t)b << log_n) + k];
+    coeffs[(p << log_n) + k] = (i64)round(acc * factor);
+}
+
+hipError_t launch_encode_basis(const double* cs, const uint32_t* g, const int* set_begin, int nb, double* basis, int log_n,
+                               hipStream_t st) {
+    DRY_RUN_RETURN();
+    if (nb <= 0) return hipSuccess;
+    ProfScope prof__("encode_basis_kernel", st);
+    hipLaunchKernelGGL(encode_basis_kernel, dim3((1u << log_n) / NT, nb), dim3(NT), 0, st, cs, g, set_begin, basis, log_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_combine(const double* basis, int nb, const double* v, int n_pts, double factor, i64* coeffs,
+                                 int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
+    if (n_pts <= 0) return hipSuccess;
+    ProfScope prof__("encode_combine_kernel", st);
+    hipLaunchKernelGGL(encode_combine_kernel, dim3((1u << log_n) / NT, n_pts), dim3(NT), 0, st, basis, nb, v, factor, coeffs,
+                       log_n);
+    return hipGetLastError();
+}
+
 // Centred mixed-radix digits v_i in (-q_i/2, q_i/2] with x = v_0 + q_0 (v_1 + q_1 (v_2 + ...)), then Horner in fp64.
 // Small centred values have zero top digits, so the float result is accurate for them.
 __global__ __launch_bounds__(NT) void crt_to_double_kernel(const PrimeConst* primes, const u64* x, int limbs,

@@ -222,7 +222,9 @@ int alloc_pt(hisa_ctx* ctx, uint32_t limbs, double scale, hisa_pt** out) {
 int gather_batch(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, BatchIn* bi) {
     const size_t words = ct_words(ctx, cts[0]->polys, cts[0]->limbs);
     bool even = true;
-    for (size_t i = 1; i < n && even; i++) even = cts[i]->data == cts[0]->data + i * words;
+    // views of ONE allocation only: separately allocated ciphertexts can be neighbours in the address space, and a
+    // device-to-device copy over the whole batch must not cross an allocation boundary
+    for (size_t i = 1; i < n && even; i++) even = cts[i]->blk == cts[0]->blk && cts[i]->data == cts[0]->data + i * words;
     if (even) {
         bi->base = cts[0]->data;
         bi->stride = words;

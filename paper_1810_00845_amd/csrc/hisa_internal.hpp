@@ -334,6 +334,12 @@ hipError_t launch_rescale_final(const PrimeConst* primes, const u64* ct, const u
 // encode / decode
 hipError_t launch_encode(const double* cs, const double* sn, const uint32_t* g, const double* re, const double* im,
                          int count, int n_pts, double factor, i64* coeffs, int log_n, hipStream_t st);
+// piecewise-constant plaintexts: indicator encodings of nb slot sets (g[set_begin[b] .. set_begin[b+1]) lists 5^slot
+// mod 2N of set b), then coeffs[p] = round(factor * sum_b v[p][b] * basis[b])
+hipError_t launch_encode_basis(const double* cs, const uint32_t* g, const int* set_begin, int nb, double* basis, int log_n,
+                               hipStream_t st);
+hipError_t launch_encode_combine(const double* basis, int nb, const double* v, int n_pts, double factor, i64* coeffs,
+                                 int log_n, hipStream_t st);
 hipError_t launch_crt_to_double(const PrimeConst* primes, const u64* coeff_form, int limbs, const u64* garner_inv,
                                 const u64* garner_inv_sh, int L, double inv_scale, double* out, int log_n, hipStream_t st);
 hipError_t launch_decode(const double* cs, const double* sn, const double* m, int count, double* re, double* im, int log_n,

@@ -589,6 +589,50 @@ static int encode_sparse_batch(hisa_ctx* ctx, const std::vector<uint32_t>& slots
     return HISA_OK;
 }
 
+// Encodes n_pts slot vectors that are constant on each of nb slot sets (values[n_pts][nb], host; sets[b] = the slots
+// of set b) and zero elsewhere into NTT-form plaintexts out[n_pts][limbs][N] (device): the same numbers as
+// encode_sparse_batch up to the rounding order of the fp64 sums, at nb instead of (number of slots) terms per
+// coefficient.
+static int encode_piecewise_batch(hisa_ctx* ctx, const std::vector<std::vector<uint32_t>>& sets, const double* values,
+                                  size_t n_pts, double scale, int limbs, u64* out) {
+    const size_t n = ctx->N, nb = sets.size();
+    std::vector<uint32_t> g;
+    std::vector<int> begin(1, 0);
+    const uint32_t mask = 2 * ctx->N - 1;
+    for (const auto& set : sets) {
+        for (uint32_t slot : set) {
+            uint32_t e = 1, b = 5;
+            for (uint32_t k = slot; k; k >>= 1, b = (b * b) & mask)
+                if (k & 1) e = (e * b) & mask;
+            g.push_back(e);
+        }
+        begin.push_back((int)g.size());
+    }
+    Temp dg(ctx, std::max<size_t>(1, g.size()) * sizeof(uint32_t)), db(ctx, begin.size() * sizeof(int));
+    Temp basis(ctx, nb * n * sizeof(double)), dv(ctx, n_pts * nb * sizeof(double));
+    if (!dg.ok() || !db.ok() || !basis.ok() || !dv.ok()) return HISA_ERR_OOM;
+    HIP_TRY(ctx, hipMemcpyAsync(dg.blk->ptr, g.data(), g.size() * sizeof(uint32_t), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(db.blk->ptr, begin.data(), begin.size() * sizeof(int), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(dv.blk->ptr, values, n_pts * nb * sizeof(double), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    HIP_TRY(ctx, launch_encode_basis(ctx->d_cos, dg.as<uint32_t>(), db.as<int>(), (int)nb, basis.as<double>(), (int)ctx->log_n,
+                                     ctx->stream));
+    const size_t chunk = std::min<size_t>(32768, std::max<size_t>(1, ((size_t)512 << 20) / (n * sizeof(i64))));
+    Temp co(ctx, std::min(chunk, n_pts) * n * sizeof(i64));
+    if (!co.ok()) return HISA_ERR_OOM;
+    for (size_t p0 = 0; p0 < n_pts; p0 += chunk) {
+        const size_t cnt = std::min(chunk, n_pts - p0);
+        HIP_TRY(ctx, launch_encode_combine(basis.as<double>(), (int)nb, dv.as<double>() + p0 * nb, (int)cnt,
+                                           2.0 * scale / (double)n, co.as<i64>(), (int)ctx->log_n, ctx->stream));
+        HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>(), out + p0 * limbs * n, limbs, (int)cnt, (int)ctx->log_n,
+                                       ctx->stream));
+        for (size_t q0 = 0; q0 < cnt; q0 += 4096)
+            HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, out + (p0 + q0) * limbs * n, (u64)limbs * n,
+                                    (int)(std::min<size_t>(4096, cnt - q0) * limbs), identity_map(limbs), ctx->stream));
+    }
+    return HISA_OK;
+}
+
 // host signed coefficients [n_pts][N] -> NTT-form plaintexts out[n_pts][limbs][N]
 static int coeffs_to_plain_batch(hisa_ctx* ctx, const int64_t* host, size_t n_pts, int limbs, u64* out) {
     const size_t n = ctx->N;
@@ -865,37 +909,29 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
         // plaintext (tap, d, input ciphertext j, output ciphertext g): on the valid output positions of block b the
         // weight from input channel j ci + (b + d) mod ci to output channel g ci + b, zero where either does not exist
         const uint32_t ci = t_ci(in), per_in = (uint32_t)t_per(in), per_out = (OC + ci - 1) / ci;
-        const size_t n_pts = taps * per_in * per_out, pos = vslots.size(), nnz = ci * pos;
-        std::vector<uint32_t> slots;
+        const size_t n_pts = taps * per_in * per_out;
+        std::vector<std::vector<uint32_t>> sets(ci);
         for (uint32_t b = 0; b < ci; b++)
-            for (uint32_t v : vslots) slots.push_back(v + b * in->c_stride);
+            for (uint32_t v : vslots) sets[b].push_back(v + b * in->c_stride);
         cw.pts = new Temp(ctx, n_pts * l * n * sizeof(u64));
         if (!cw.pts->ok()) return HISA_ERR_OOM;
         cw.pt_scale = q_last;
-        const size_t chunk = std::max<size_t>(1, std::min<size_t>(n_pts, ((size_t)256 << 20) / (nnz * sizeof(double) + n * 8)));
-        std::vector<double> vals;
-        for (size_t p0 = 0; p0 < n_pts; p0 += chunk) {
-            const size_t cnt = std::min(chunk, n_pts - p0);
-            vals.assign(cnt * nnz, 0.0);
-            for (size_t q = 0; q < cnt; q++) {
-                const size_t idx = p0 + q, g_ = idx % per_out, j = (idx / per_out) % per_in, td = idx / per_out / per_in;
-                const size_t d = td % ci, tap = td / ci;
-                for (uint32_t b = 0; b < ci; b++) {
-                    const size_t ic = j * ci + (b + d) % ci, oc = g_ * ci + b;
-                    if (ic < IC && oc < OC) std::fill_n(vals.begin() + q * nnz + b * pos, pos, w[(tap * IC + ic) * OC + oc]);
-                }
+        std::vector<double> vals(n_pts * ci, 0.0);   // one value per (plaintext, block)
+        for (size_t idx = 0; idx < n_pts; idx++) {
+            const size_t g_ = idx % per_out, j = (idx / per_out) % per_in, td = idx / per_out / per_in;
+            const size_t d = td % ci, tap = td / ci;
+            for (uint32_t b = 0; b < ci; b++) {
+                const size_t ic = j * ci + (b + d) % ci, oc = g_ * ci + b;
+                if (ic < IC && oc < OC) vals[idx * ci + b] = w[(tap * IC + ic) * OC + oc];
             }
-            TRY(encode_sparse_batch(ctx, slots, vals.data(), cnt, q_last, (int)l, cw.pts->u() + p0 * l * n));
         }
-        return HISA_OK;
+        return encode_piecewise_batch(ctx, sets, vals.data(), n_pts, q_last, (int)l, cw.pts->u());
     }
     if (geom->mode == HISA_CONV_PLAIN) {
         // plaintext (tap, ic, oc) = weight on every valid output position, zero elsewhere, at scale q_last
         cw.pts = new Temp(ctx, T * OC * l * n * sizeof(u64));
         if (!cw.pts->ok()) return HISA_ERR_OOM;
-        std::vector<double> vals(T * OC * vslots.size());
-        for (size_t i = 0; i < T * OC; i++) std::fill_n(vals.begin() + i * vslots.size(), vslots.size(), w[i]);
-        TRY(encode_sparse_batch(ctx, vslots, vals.data(), T * OC, q_last, (int)l, cw.pts->u()));
+        TRY(encode_piecewise_batch(ctx, {vslots}, w, T * OC, q_last, (int)l, cw.pts->u()));
         cw.pt_scale = q_last;
         return HISA_OK;
     }

@@ -82,14 +82,31 @@ def squeezenet_cifar(seed=5):
 def _concat_channels(ctx, a, b):
     """Channel concatenation of two tensors of one image with identical layout, level and scale."""
     from .hisa import CipherTensor
-    assert a.batch == 1 and b.batch == 1 and a.meta()[2:] == b.meta()[2:]
+    assert a.batch == 1 and b.batch == 1 and a.meta()[2:] == b.meta()[2:] and a.channels % a.c_inner == 0
     t = CipherTensor(ctx, list(a.cts) + list(b.cts), 1, a.channels + b.channels, a.height, a.width, a.h_stride,
-                     a.w_stride, a.offset, a.clean)
+                     a.w_stride, a.offset, a.clean, a.c_inner, a.c_stride)
     a.cts, b.cts = [], []   # the handles now belong to the concatenation
     return t
 
 
-LAYOUTS = ("hw", "chw_fc")
+LAYOUTS = ("hw", "chw_fc", "chw")
+
+
+def chw_blocks(slots, plane_slots_needed, layers):
+    """CHW-tiling of the input: (channels per ciphertext, channel stride).  The stride is the power of two that holds
+    a plane with its border; as many blocks as the slots hold, and no more than the convolutions can rotate through
+    (taps x blocks rotation amounts per input ciphertext, at most 256)."""
+    c_stride = 1 << max(0, plane_slots_needed - 1).bit_length()
+    taps = [1]
+    for layer in layers:
+        if layer[0] in ("conv", "conv_same"):
+            taps.append(layer[1].shape[0] * layer[1].shape[1])
+        elif layer[0] == "fire":
+            taps.append(layer[3].shape[0] * layer[3].shape[1])
+    c_inner = 1
+    while 2 * c_inner * c_stride <= slots and 2 * c_inner * max(taps) <= 256:
+        c_inner *= 2
+    return c_inner, c_stride
 
 
 def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans=None, layout="hw"):
@@ -99,14 +116,21 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
     reused afterwards) holds the layers' weights converted and encoded ahead of time; without it that is done
     inside every call.  layout: "hw" keeps one channel per ciphertext throughout; "chw_fc" (the paper's "CHW-fc and
     HW-before", Sec. "Data Layout Selection") is HW-tiled up to the first fully connected layer, which runs as a
-    matmul with as many replicas as the slots hold and leaves a CHW-tiled tensor for the layers after it."""
+    matmul with as many replicas as the slots hold and leaves a CHW-tiled tensor for the layers after it; "chw" packs
+    several channels into every ciphertext from the input on (CHW-tiled convolutions multiply by plaintexts and need
+    clean inputs: a masking multiply follows each pool)."""
     assert layout in LAYOUTS
-    replicas = 1 << 30 if layout == "chw_fc" else 1
+    replicas = 1 if layout == "hw" else 1 << 30
+    tiling = {}
+    if layout == "chw":
+        hs = x.shape[3] + 2 * border
+        ci, cs = chw_blocks(ctx.N // 2, (x.shape[2] + 2 * border) * hs, layers)
+        tiling = dict(c_inner=ci, c_stride=cs)
     if border:   # leave `border` rows and columns of zero slots around every plane (SAME convolutions need them)
         hs = x.shape[3] + 2 * border
-        t = ctx.tensor_encrypt(x, scale, limbs, h_stride=hs, offset=border * hs + border)
+        t = ctx.tensor_encrypt(x, scale, limbs, h_stride=hs, offset=border * hs + border, **tiling)
     else:
-        t = ctx.tensor_encrypt(x, scale, limbs)
+        t = ctx.tensor_encrypt(x, scale, limbs, **tiling)
     ctx.sync()
     t_start = time.perf_counter()
     per_layer = []
@@ -129,11 +153,22 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
         return ctx.fc_apply(t, plans[idx][1])
 
     def convolution(key, t, w, fh, fw, **kw):
+        cleaned = None
+        if t.c_inner > 1:                 # CHW-tiled: plaintext weights on a clean input
+            kw["mode"] = 2
+            if not t.clean:
+                t = cleaned = ctx.tensor_mask(t)
+        if make_keys:
+            ctx.gen_rot_keys(ctx.conv2d_rot_steps(t, fh, fw, stride=kw.get("stride", 1), pad_same=kw.get("pad_same", False)))
         if plans is None:
-            return ctx.conv2d(t, w, fh, fw, **kw)
-        if key not in plans:
-            plans[key] = ("conv", ctx.conv2d_prepare(t, w, fh, fw, **kw))
-        return ctx.conv2d_apply(t, plans[key][1])
+            out = ctx.conv2d(t, w, fh, fw, **kw)
+        else:
+            if key not in plans:
+                plans[key] = ("conv", ctx.conv2d_prepare(t, w, fh, fw, **kw))
+            out = ctx.conv2d_apply(t, plans[key][1])
+        if cleaned is not None:
+            cleaned.free()
+        return out
 
     for idx, layer in enumerate(layers):
         t0 = time.perf_counter()
@@ -142,8 +177,6 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             w, stride = layer[1] * pending, layer[2]
             pending = 1.0
             fh, fw = w.shape[:2]
-            if make_keys:
-                ctx.gen_rot_keys(ctx.conv2d_rot_steps(t, fh, fw, stride=stride))
             nxt = convolution(idx, t, w, fh, fw, stride=stride)
         elif kind == "act":
             a, b = layer[1], layer[2]
@@ -158,8 +191,6 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             w = layer[1] * pending
             pending = 1.0
             fh, fw = w.shape[:2]
-            if make_keys:
-                ctx.gen_rot_keys(ctx.conv2d_rot_steps(t, fh, fw, pad_same=True))
             nxt = convolution(idx, t, w, fh, fw, pad_same=True, mode=1)
         elif kind == "fire":
             ws, w1, w3, a, b = layer[1] * pending, layer[2], layer[3], layer[4], layer[5]
@@ -167,8 +198,6 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             s0 = convolution((idx, "squeeze"), t, ws, 1, 1)
             s1 = ctx.poly2_act(s0, a, b)
             s0.free()
-            if make_keys:
-                ctx.gen_rot_keys(ctx.conv2d_rot_steps(s1, 3, 3, pad_same=True))
             e1 = convolution((idx, "expand1"), s1, w1 * a, 1, 1)
             e3 = convolution((idx, "expand3"), s1, w3 * a, 3, 3, pad_same=True, mode=1)
             s1.free()

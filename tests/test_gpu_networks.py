@@ -59,25 +59,31 @@ def test_network_matches_plaintext(name):
     ctx.close()
 
 
-@pytest.mark.parametrize("name", ["lenet_small", "lenet_medium"])
-def test_network_chw_fc_layout_matches_plaintext(name):
-    """The layout "CHW-fc and HW-before" of Sec. "Data Layout Selection": HW-tiled convolutions, the first fully
-    connected layer as a matmul with replicas, CHW-tiled after it.  Same networks, same tolerance."""
+@pytest.mark.parametrize("name,layout", [("lenet_small", "chw_fc"), ("lenet_medium", "chw_fc"), ("lenet_small", "chw"),
+                                         ("lenet_medium", "chw"), ("squeezenet_cifar", "chw")])
+def test_network_other_layouts_match_plaintext(name, layout):
+    """The other layouts of Sec. "Data Layout Selection": "CHW-fc and HW-before" (HW-tiled convolutions, the first
+    fully connected layer as a matmul with replicas, CHW-tiled after it) and CHW throughout (several channels per
+    ciphertext from the input on).  Same networks, same tolerance."""
     from paper_1810_00845_amd import hisa, nets
     params, layers, x = getattr(nets, name)()
     want = plain_forward(layers, x)
     ctx = hisa.Context(params["log_n"], params["q_bits"], params["dnum"], params["special_bits"], seed=11)
     ctx.keygen()
     limbs = len(params["q_bits"])
+    border = params.get("border", 0)
     plans = {}
-    got, _, _ = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, make_keys=True, plans=plans, layout="chw_fc")
+    got, _, _ = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, make_keys=True, border=border, plans=plans,
+                                   layout=layout)
     err = np.abs(got - want).max()
-    print(name, "chw_fc max abs error", err, flush=True)
+    print(name, layout, "max abs error", err, flush=True)
     assert err <= 1e-3
-    got2, latency, per_layer = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, plans=plans, layout="chw_fc")
-    print(name, "chw_fc latency %.4f s" % latency, [(k, round(s, 4)) for k, s in per_layer], flush=True)
+    got2, latency, per_layer = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, border=border, plans=plans,
+                                                  layout=layout)
+    print(name, layout, "latency %.4f s" % latency, [(k, round(s, 4)) for k, s in per_layer], flush=True)
     assert np.abs(got2 - want).max() <= 1e-3
-    got3, _, _ = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, layout="chw_fc")   # without plans
-    assert np.abs(got3 - want).max() <= 1e-3
+    if name != "squeezenet_cifar":     # without plans (the weights are encoded inside every call)
+        got3, _, _ = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, border=border, layout=layout)
+        assert np.abs(got3 - want).max() <= 1e-3
     nets.free_plans(ctx, plans)
     ctx.close()
