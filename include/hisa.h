@@ -200,7 +200,8 @@ int hisa_ct_random_batch(hisa_ctx* ctx, size_t n, uint32_t limbs, double scale, 
  * rotation whose key is missing is recorded instead of failing, and the
  * relinearisation key is not needed.  hisa_analysis_end leaves the mode and
  * returns what was recorded: the operation counts (in ciphertext operations;
- * the multiply-accumulate kernels of the layers count one multiply per term),
+ * the terms of the layers' fused multiply-accumulate launches are counted apart
+ * from stand-alone multiplications and their additions are not counted),
  * the lowest limb count any ciphertext reached, and the sorted left-rotation
  * amounts that needed a key (at most cap of them into host rot_steps, the count
  * into *n; rot_steps may be null).  Handles made during the analysis stay valid
@@ -211,6 +212,10 @@ typedef struct {
     uint64_t rot_left;     /* key-switched rotations (rotRight counts here too) */
     uint64_t rot_shared;   /* of those, rotations that reused another rotation's decomposition */
     uint64_t relinearize, mul, mul_plain, mul_scalar, add, rescale;
+    uint64_t mac_plain;    /* terms x * plaintext summed inside the layers' fused multiply-accumulate launches */
+    uint64_t mac_scalar;   /* terms x * scalar weight summed there */
+    uint64_t key_switch_calls; /* batched launches behind rot_left and relinearize: one per (call, rotation amount);
+                                  a small batch costs its launch latency, not its share of the throughput */
     uint32_t min_limbs;    /* 0 if no ciphertext was made */
     uint32_t reserved;
 } hisa_op_counts;

@@ -1308,6 +1308,7 @@ extern "C" int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size
         const int32_t half = (int32_t)(ctx->N / 2);
         t_analysis->steps.insert(((steps % half) + half) % half);
         t_analysis->c.rot_left += n;
+        t_analysis->c.key_switch_calls += 1;
         TRY(alloc_ct_batch(ctx, n, 2, (uint32_t)l, 0.0, out));
         for (size_t i = 0; i < n; i++) out[i]->scale = in[i]->scale;
         return HISA_OK;
@@ -1426,6 +1427,7 @@ extern "C" int hisa_relinearize_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t
     if (cts[0]->polys != 3) return fail(ctx, HISA_ERR_SIZE, "relinearize needs 2 or 3 polynomials");
     if (t_analysis) {
         t_analysis->c.relinearize += n;
+        t_analysis->c.key_switch_calls += 1;
         std::vector<hisa_ct*> two(n);
         TRY(alloc_ct_batch(ctx, n, 2, cts[0]->limbs, 0.0, two.data()));
         for (size_t i = 0; i < n; i++) {

@@ -332,13 +332,10 @@ __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes
     }
 }
 
-// analysis mode: a multiply-accumulate launch stands for one multiply per (image, output, tap, input) and one add fewer
-// per (image, output)
+// analysis mode: a multiply-accumulate launch stands for one term per (image, output, tap, input)
 static void count_mac(const MacArgs& g, int batch, bool plain) {
     if (!t_analysis) return;
-    const uint64_t terms = (uint64_t)batch * g.OC * g.n_taps * g.IC;
-    (plain ? t_analysis->c.mul_plain : t_analysis->c.mul_scalar) += terms;
-    t_analysis->c.add += terms - (uint64_t)batch * g.OC;
+    (plain ? t_analysis->c.mac_plain : t_analysis->c.mac_scalar) += (uint64_t)batch * g.OC * g.n_taps * g.IC;
 }
 
 static hipError_t launch_scalar_mac(const PrimeConst* primes, const MacArgs& g, int batch, int log_n, hipStream_t st) {

@@ -43,7 +43,7 @@ class TensorStruct(C.Structure):
 
 class OpCounts(C.Structure):
     _fields_ = [(name, C.c_uint64) for name in ("rot_left", "rot_shared", "relinearize", "mul", "mul_plain", "mul_scalar",
-                                                "add", "rescale")] + [("min_limbs", C.c_uint32), ("reserved", C.c_uint32)]
+                                                "add", "rescale", "mac_plain", "mac_scalar", "key_switch_calls")] + [("min_limbs", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class ConvGeom(C.Structure):

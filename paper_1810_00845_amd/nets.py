@@ -252,13 +252,16 @@ def analyse(ctx, layers, x, scale, limbs, border=0, layout="hw"):
     return counts, steps
 
 
-COST_OPS = ("rot_left", "rot_shared", "relinearize", "mul", "mul_plain", "mul_scalar", "add", "rescale")
+COST_OPS = ("rot_left", "rot_shared", "relinearize", "mul", "mul_plain", "mul_scalar", "add", "rescale", "mac_plain",
+            "mac_scalar", "key_switch_calls")
 
 
 def measure_costs(ctx, limbs, batch=64, reps=5):
     """Seconds per ciphertext operation at `limbs` limbs, from timing each primitive on a batch of random ciphertexts
     (Sec. "Data Layout Selection": the costs may come from micro-benchmarks).  "rot_shared" is what a rotation saves
-    when it shares another one's decomposition (a negative cost)."""
+    when it shares another one's decomposition (a negative cost); "mac_plain" and "mac_scalar" are the terms of the
+    layers' fused multiply-accumulate, timed on 1x1 convolutions (which rotate nothing)."""
+    from .hisa import CipherTensor
     import numpy as np
     cts = ctx.ct_random_batch(batch, limbs, 2.0 ** 40, 900)
     pt = ctx.encode(np.ones(8), float(ctx.primes[limbs - 1]), limbs)
@@ -278,9 +281,14 @@ def measure_costs(ctx, limbs, batch=64, reps=5):
             free(c) if isinstance(c, list) else c.free()
 
     costs = {}
-    costs["rot_left"] = timed(lambda: free(ctx.rot_left_batch(cts, 1)))
+    # a key switch of n ciphertexts takes about t0 + n t1: t1 from the full batch, t0 (what a call costs however small
+    # its batch: the launches' latency) from a batch of one
+    full = timed(lambda: free(ctx.rot_left_batch(cts, 1)))                          # seconds per ciphertext
+    single = timed(lambda: free(ctx.rot_left_batch(cts[:1], 1))) * batch           # seconds per call of one ciphertext
+    costs["rot_left"] = max(0.0, (full * batch - single) / (batch - 1))
+    costs["key_switch_calls"] = max(0.0, single - costs["rot_left"])
     hoisted = timed(lambda: free(ctx.rot_left_hoisted_batch(cts, [1, 2, 3])))      # three rotations per ciphertext
-    costs["rot_shared"] = min(0.0, (hoisted - 3 * costs["rot_left"]) / 2)
+    costs["rot_shared"] = min(0.0, (hoisted - 3 * full) / 2)
     costs["add"] = timed(lambda: free(ctx.add_batch(cts, cts)))
     costs["mul"] = timed(lambda: free(ctx.mul_no_relin_batch(cts, cts)))
     costs["mul_plain"] = timed(lambda: free(ctx.mul_plain_batch(cts, pt)))
@@ -290,13 +298,22 @@ def measure_costs(ctx, limbs, batch=64, reps=5):
         sq = ctx.mul_no_relin_batch(cts, cts)
         ctx.relinearize_batch(sq)
         free(sq)
-    costs["relinearize"] = max(0.0, timed(relin) - costs["mul"])
+    costs["relinearize"] = max(0.0, timed(relin) - costs["mul"] - costs["key_switch_calls"] / batch)
 
     def rescale():
         cp = ctx.add_batch(cts, cts)
         ctx.rescale_batch(cp)
         free(cp)
     costs["rescale"] = max(0.0, timed(rescale) - costs["add"])
+    # fused multiply-accumulate: a 1x1 convolution over `batch` channels is batch * outputs terms and one divScalar per output
+    t = CipherTensor(ctx, cts, 1, batch, 1, 1, 1, 1, 0, 1)
+    w = np.random.default_rng(0).normal(0.0, 0.1, (1, 1, batch, batch))
+    for name, mode in (("mac_scalar", 0), ("mac_plain", 2)):
+        plan = ctx.conv2d_prepare(t, w, 1, 1, mode=mode)
+        per_ct = timed(lambda: free(ctx.conv2d_apply(t, plan).cts))      # seconds / batch
+        costs[name] = max(0.0, per_ct - costs["rescale"]) / batch
+        ctx.conv_plan_free(plan)
+    t.cts = []
     pt.free()
     free(cts)
     return costs

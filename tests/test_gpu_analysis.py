@@ -26,10 +26,10 @@ def test_analysis_counts_match_the_schedule_and_leave_the_context_usable():
     assert steps == sorted([1, 4, 5, 2, 8, slots - 16, slots - 32])
     # pool: 3 rotations per ciphertext, two of them sharing the first one's decomposition, 3 adds each;
     # matmul: 3 masks + 3 x 3 weights, 2 replica steps x 3 inputs + 2 reduction steps x 3 groups, 3 + 3 divScalar
-    assert counts["rot_left"] == 9 + 6 + 6 and counts["rot_shared"] == 6
-    assert counts["mul_plain"] == 3 + 9 and counts["rescale"] == 3 + 3
-    assert counts["add"] == 9 + 6 + (9 - 3) + 6
-    assert counts["mul"] == 0 and counts["relinearize"] == 0 and counts["mul_scalar"] == 0
+    assert counts["rot_left"] == 9 + 6 + 6 and counts["rot_shared"] == 6 and counts["key_switch_calls"] == 3 + 2 + 2
+    assert counts["mul_plain"] == 3 and counts["mac_plain"] == 9 and counts["rescale"] == 3 + 3
+    assert counts["add"] == 9 + 6 + 6                       # (the additions inside the fused multiply-accumulate are not counted)
+    assert counts["mul"] == 0 and counts["relinearize"] == 0 and counts["mul_scalar"] == 0 and counts["mac_scalar"] == 0
     assert counts["min_limbs"] == 4
     pool.free(); m.free()
     # outside the analysis the same calls compute: the missing keys are now an error, and with them the result is right
@@ -65,8 +65,9 @@ def test_analysis_mode_errors():
     g.close()
 
 
-@pytest.mark.parametrize("layout,levels,mul_plain,mul_scalar,mul", [("hw", 5, 500, 1125, 105), ("chw_fc", 6, 5 + 125 + 250, 125, 30)])
-def test_rotation_key_selection_and_depth_by_dry_run(layout, levels, mul_plain, mul_scalar, mul):
+@pytest.mark.parametrize("layout,levels,masks,mac_plain,mac_scalar,mul", [("hw", 5, 0, 500, 1125, 105),
+                                                                          ("chw_fc", 6, 5, 125 + 250, 125, 30)])
+def test_rotation_key_selection_and_depth_by_dry_run(layout, levels, masks, mac_plain, mac_scalar, mul):
     """LeNet-small: the keys named by the dry run are exactly enough to run the network (a context that holds only
     those keys computes the right answer), the depth is the number of divScalar levels of the schedule, and the
     multiply counts are those of the layers (conv 25 taps x 5 outputs; FC 845 -> 100 -> 10 per layout)."""
@@ -76,7 +77,8 @@ def test_rotation_key_selection_and_depth_by_dry_run(layout, levels, mul_plain, 
     ctx = hisa.Context(params["log_n"], params["q_bits"], params["dnum"], params["special_bits"], seed=11)
     counts, steps = nets.analyse(ctx, layers, x, params["scale"], limbs, layout=layout)
     assert limbs - counts["min_limbs"] == levels
-    assert (counts["mul_plain"], counts["mul_scalar"], counts["mul"], counts["relinearize"]) == (mul_plain, mul_scalar, mul, mul)
+    assert (counts["mul_plain"], counts["mac_plain"], counts["mac_scalar"]) == (masks, mac_plain, mac_scalar)
+    assert (counts["mul"], counts["relinearize"], counts["mul_scalar"]) == (mul, mul, 0)
     assert counts["rot_left"] >= 24 and len(steps) >= 24
     ctx.keygen()
     ctx.gen_rot_keys(steps)
@@ -95,11 +97,11 @@ def test_layout_selection_by_cost_agrees_with_the_clock():
     ctx = hisa.Context(params["log_n"], params["q_bits"], params["dnum"], params["special_bits"], seed=11)
     ctx.keygen()
     costs = nets.measure_costs(ctx, limbs)
-    assert costs["rot_left"] > costs["add"] > 0 and costs["rot_shared"] <= 0
+    assert costs["rot_left"] > costs["add"] > 0 and costs["rot_shared"] <= 0 and costs["key_switch_calls"] > costs["rot_left"]
     best, est = nets.select_layout(ctx, layers, x, params["scale"], limbs, costs)
     print("unit costs (us):", {k: round(v * 1e6, 2) for k, v in costs.items()}, "estimates (ms):",
           {k: round(v * 1e3, 2) for k, v in est.items()}, flush=True)
-    assert best == "chw_fc" and est["chw_fc"] < est["hw"]
+    assert best == "chw_fc" and est["chw_fc"] < est["hw"] < est["chw"]
     measured = {}
     for layout in nets.LAYOUTS:
         plans = {}
@@ -108,5 +110,5 @@ def test_layout_selection_by_cost_agrees_with_the_clock():
                                for _ in range(3))
         nets.free_plans(ctx, plans)
     print("measured (ms):", {k: round(v * 1e3, 2) for k, v in measured.items()}, flush=True)
-    assert measured["chw_fc"] < measured["hw"]
+    assert measured["chw_fc"] < measured["hw"] < measured["chw"]
     ctx.close()
