@@ -1253,6 +1253,51 @@ static int key_switch_finish_fp(hisa_ctx* ctx, const FpExt& x, const u64* d, u64
     return HISA_OK;
 }
 
+// IP, C, D for n_steps rotations of the same B ciphertexts in one set of launches (entries rotation-major): a
+// convolution's taps rotate few ciphertexts many times, and a launch over B entries alone would leave most of the chip
+// idle.  out: [n_steps][B] ciphertexts.  Same arithmetic per entry as key_switch_finish_fp with gather_ext = 1.
+static int key_switch_finish_steps_fp(hisa_ctx* ctx, const FpExt& x, const u64* d, u64 d_bs, const u64* galois,
+                                      const SwitchKey* const* keys, int n_steps, size_t B, const u64* add, u64 add_bs, u64* out) {
+    const size_t n = ctx->N, E = (size_t)n_steps * B;
+    const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total, l = x.l;
+    const int ext_limbs = x.ext_limbs, log_n = (int)ctx->log_n;
+    hipStream_t st = ctx->stream;
+    if (n_steps < 1 || n_steps > FP_MAX_STEPS) return fail(ctx, HISA_ERR_ARG, "bad rotation count");
+    Temp acc(ctx, E * 2 * (size_t)ext_limbs * n * sizeof(u64));
+    Temp y2(ctx, E * 2 * (size_t)K * n * sizeof(double));
+    if (!acc.ok() || !y2.ok()) return HISA_ERR_OOM;
+    double *post_q, *post_p;
+    TRY(fp_post_tables(ctx, l, &post_q, &post_p));
+    const FpArgs base = fp_base(ctx);
+    IpSteps steps = {};
+    for (int s = 0; s < n_steps; s++) { steps.key[s] = keys[s]->data; steps.galois[s] = (uint32_t)galois[s]; }
+    HIP_TRY(ctx, launch_inner_product_steps_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, steps, n_steps,
+                                               total, d, d_bs, acc.u(), (u64)2 * ext_limbs * n, B, log_n, st));
+    {   // C
+        FpArgs a = base;
+        FpTask tk = {};
+        tk.period = K;
+        for (int m = 0; m < K; m++) { tk.pos[m] = (int16_t)m; tk.prime[m] = (int16_t)(L + m); }
+        a.in = acc.u(); a.in_bs = (u64)ext_limbs * n; a.in_pos_shift = l; a.post = post_p;
+        a.yout = y2.as<double>(); a.yout_bs = (u64)K * n;
+        HIP_TRY(ctx, launch_ntt_fp(FP_INV_TO_Y, log_n, a, tk, E * 2, st));
+    }
+    {   // D
+        FpArgs a = base;
+        FpTask tk = {};
+        tk.period = l;
+        for (int i = 0; i < l; i++) { tk.pos[i] = (int16_t)i; tk.prime[i] = (int16_t)i; }
+        a.y = y2.as<double>(); a.y_bs = (u64)K * n; a.y_pos0 = 0; a.conv_a = K; a.total = total; a.hat = ctx->moddown_tab->d_hat_f;
+        a.acc = acc.u(); a.acc_bs = (u64)ext_limbs * n; a.acc_pos_shift = 0; a.pinv_tab = ctx->d_pinv_f;
+        a.add = add; a.add_bs = add_bs; a.add_ps = (u64)l * n; a.add_div = 2; a.add_polys = 1;
+        a.step_B = (int)B;
+        for (int s = 0; s < n_steps; s++) a.galois_tab[s] = (uint32_t)galois[s];
+        a.out = out; a.out_bs = (u64)l * n;
+        HIP_TRY(ctx, launch_ntt_fp(FP_FWD_CONV_FINAL, log_n, a, tk, E * 2, st));
+    }
+    return HISA_OK;
+}
+
 static int key_switch_core_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois, size_t B, int l, const SwitchKey& key,
                               const u64* add, u64 add_bs, int add_polys, u64* out) {
     FpExt x(ctx, B, l, (int)ctx->K, (int)ctx->alpha);
@@ -1365,7 +1410,13 @@ extern "C" int hisa_rot_left_hoisted_batch(hisa_ctx* ctx, const hisa_ct* const* 
     int rc = HISA_OK;
     if (t_analysis) {
         for (size_t s = 0; s < n_steps && rc == HISA_OK; s++) rc = hisa_rot_left_batch(ctx, in, n, steps[s], out + s * n);
-        if (rc == HISA_OK && switched >= 2 && ctx->tabs.fp_ok && ctx->dnum <= 8) t_analysis->c.rot_shared += (switched - 1) * n;
+        if (rc == HISA_OK && switched >= 2 && ctx->tabs.fp_ok && ctx->dnum <= 8) {
+            // one decomposition, then one set of launches per group of rotations (as in the branch below)
+            const size_t group = std::max<size_t>(1, std::min<size_t>(FP_MAX_STEPS, 1024 / n));
+            t_analysis->c.rot_shared += (switched - 1) * n;
+            t_analysis->c.key_switch_calls -= switched;
+            t_analysis->c.key_switch_calls += (switched + group - 1) / group;
+        }
     } else if (switched < 2 || !(ctx->tabs.fp_ok && ctx->dnum <= 8)) {   // nothing to share, or no fused path: one by one
         for (size_t s = 0; s < n_steps && rc == HISA_OK; s++) rc = hisa_rot_left_batch(ctx, in, n, steps[s], out + s * n);
     } else {
@@ -1376,13 +1427,31 @@ extern "C" int hisa_rot_left_hoisted_batch(hisa_ctx* ctx, const hisa_ct* const* 
             FpExt x(ctx, n, l, (int)ctx->K, (int)ctx->alpha);
             if (!x.ok()) rc = HISA_ERR_OOM;
             if (rc == HISA_OK) rc = key_switch_modup_fp(ctx, bi.base + lw, bi.stride, 0, n, x);
+            // rotations by a multiple of the slot count are copies; the others go through the key switch in groups
+            // of at most FP_MAX_STEPS rotations (and a bounded number of entries) per set of launches
+            std::vector<size_t> sw;
             for (size_t s = 0; s < n_steps && rc == HISA_OK; s++) {
-                if (gs[s] == 0) { rc = hisa_rot_left_batch(ctx, in, n, steps[s], out + s * n); continue; }
-                rc = alloc_ct_batch(ctx, n, 2, (uint32_t)l, 0.0, out + s * n);
+                if (gs[s] == 0) rc = hisa_rot_left_batch(ctx, in, n, steps[s], out + s * n);
+                else sw.push_back(s);
+            }
+            const size_t group = std::max<size_t>(1, std::min<size_t>(FP_MAX_STEPS, 1024 / n));
+            for (size_t g0 = 0; g0 < sw.size() && rc == HISA_OK; g0 += group) {
+                const size_t cnt = std::min(group, sw.size() - g0);
+                std::vector<hisa_ct*> fresh(cnt * n, nullptr);
+                rc = alloc_ct_batch(ctx, cnt * n, 2, (uint32_t)l, 0.0, fresh.data());
                 if (rc != HISA_OK) break;
-                for (size_t i = 0; i < n; i++) out[s * n + i]->scale = in[i]->scale;
-                rc = key_switch_finish_fp(ctx, x, bi.base + lw, bi.stride, gs[s], 1, n, ctx->keys.find(gs[s])->second, bi.base,
-                                          bi.stride, 1, out[s * n]->data);
+                u64 gal[FP_MAX_STEPS];
+                const SwitchKey* keys[FP_MAX_STEPS];
+                for (size_t k = 0; k < cnt; k++) {
+                    gal[k] = gs[sw[g0 + k]];
+                    keys[k] = &ctx->keys.find(gal[k])->second;
+                    for (size_t i = 0; i < n; i++) {
+                        fresh[k * n + i]->scale = in[i]->scale;
+                        out[sw[g0 + k] * n + i] = fresh[k * n + i];
+                    }
+                }
+                rc = key_switch_finish_steps_fp(ctx, x, bi.base + lw, bi.stride, gal, keys, (int)cnt, n, bi.base, bi.stride,
+                                                fresh[0]->data);
             }
         }
         dev_release(ctx, bi.tmp);

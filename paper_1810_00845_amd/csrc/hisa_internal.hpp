@@ -232,6 +232,7 @@ struct FpTask {
     int16_t prime[HISA_MAX_PRIMES];      // its prime
 };
 
+#define FP_MAX_STEPS 32   // rotations per launch of the shared-decomposition path
 struct FpArgs {
     const FpPrime* fprimes;
     const double* ftw;
@@ -254,6 +255,11 @@ struct FpArgs {
     const double* pinv_tab;            // [prime] P^-1 mod q, centred
     const u64* add; u64 add_bs, add_ps; int add_div, add_polys;  // addend of entry b: add + (b / add_div) * add_bs +
     u64 add_galois;                                              // (b % add_div) * add_ps, if b % add_div < add_polys
+    // several rotations of the same step_B ciphertexts in one launch (entries ordered rotation-major): entry b's
+    // addend is that of ciphertext (b / add_div) % step_B, gathered through galois_tab[(b / add_div) / step_B];
+    // step_B = 0: one rotation, add_galois applies
+    int step_B;
+    uint32_t galois_tab[FP_MAX_STEPS];
 };
 hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st);
 
@@ -262,6 +268,15 @@ hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk,
 hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
                                    int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois,
                                    int gather_ext, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st);
+// The same for n_steps rotations of the same n_batch ciphertexts (extended digits computed once from the unrotated
+// polynomial): rotation s uses keys[s] and gathers through galois[s]; acc entries are ordered rotation-major.
+struct IpSteps {
+    const u64* key[FP_MAX_STEPS];
+    uint32_t galois[FP_MAX_STEPS];
+};
+hipError_t launch_inner_product_steps_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
+                                         int alpha, const IpSteps& steps, int n_steps, int total, const u64* own_src,
+                                         u64 own_bs, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st);
 
 // sampling (counter-based generator, both sides of the parity tests implement it)
 hipError_t launch_sample_uniform(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, const PolyMap& map, int n_polys,

@@ -487,8 +487,10 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         const rsrc_t dst = make_rsrc(a.out + b * a.out_bs + (u64)pos * G::N, LB);
         const double pin = as_const(a.pinv_tab)[prime];
         const bool with_add = a.add && (int)(b % a.add_div) < a.add_polys;
+        const u64 add_ct = a.step_B ? (b / a.add_div) % (u64)a.step_B : b / a.add_div;
+        const u64 add_g = a.step_B ? (u64)a.galois_tab[(b / a.add_div) / (u64)a.step_B] : a.add_galois;
         const rsrc_t add = make_rsrc(
-            with_add ? a.add + (b / a.add_div) * a.add_bs + (b % a.add_div) * a.add_ps + (u64)pos * G::N : acc_p, LB);
+            with_add ? a.add + add_ct * a.add_bs + (b % a.add_div) * a.add_ps + (u64)pos * G::N : acc_p, LB);
         int tg = t_out;
         asm volatile("" : "+v"(tg));
 #pragma unroll
@@ -500,8 +502,8 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
                 const int r = c * 8 + k;
                 const uint32_t row = (uint32_t)G::template reg_idx<MOUT>(r) * 8u;
                 va[k] = bload(acc, t8_out, row);
-                if (with_add && a.add_galois)
-                    vb[k] = bload(add, galois_src_fp((uint32_t)(G::template reg_idx<MOUT>(r) | tg), a.add_galois, G::LOGN) * 8u, 0);
+                if (with_add && add_g)
+                    vb[k] = bload(add, galois_src_fp((uint32_t)(G::template reg_idx<MOUT>(r) | tg), add_g, G::LOGN) * 8u, 0);
                 else vb[k] = bload(add, t8_out, row);
             }
             SCHED_FENCE();
@@ -621,6 +623,10 @@ hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk,
     if (mode != FP_INV_TO_Y && !a.out) return hipErrorInvalidValue;
     if (conv && (!a.y || !a.hat || a.conv_a <= 0 || a.total <= 0 || !a.scratch || a.scratch_polys < 8)) return hipErrorInvalidValue;
     if (mode == FP_FWD_CONV_FINAL && (!a.acc || !a.pinv_tab || (a.add && a.add_div <= 0))) return hipErrorInvalidValue;
+    // rotation-major entries: every entry's rotation index must fall inside galois_tab
+    if (mode == FP_FWD_CONV_FINAL && a.add && (a.step_B < 0 ||
+        (a.step_B > 0 && (n_batch + (u64)a.add_div * a.step_B - 1) / ((u64)a.add_div * a.step_B) > FP_MAX_STEPS)))
+        return hipErrorInvalidValue;
     switch (mode) {
         case FP_FWD_PLAIN: return dispatch_k3<FP_FWD_PLAIN>(log_n, a, tk, n_batch, st);
         case FP_INV_PLAIN: return dispatch_k3<FP_INV_PLAIN>(log_n, a, tk, n_batch, st);
@@ -680,6 +686,63 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime*
         acc[b * acc_bs + (u64)x * n + j] = fp_canonical(sb, p, pinv);
         acc[b * acc_bs + ((u64)ext_limbs + x) * n + j] = fp_canonical(sa, p, pinv);
     }
+}
+
+// Several rotations of the same ciphertexts: blockIdx.z is the rotation; its key values stay in registers while the
+// thread walks over the batch.  The extended digits come from the unrotated polynomial and are gathered through the
+// rotation's automorphism like the own-digit limbs.
+__global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs,
+                                                                        int digits, int l, int K, int L, int alpha, IpSteps steps,
+                                                                        int total, const u64* own_src, u64 own_bs, u64* acc,
+                                                                        u64 acc_bs, u64 n_batch, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const uint32_t j = blockIdx.x * IPF_NT + threadIdx.x;
+    const int x = blockIdx.y, s = blockIdx.z;
+    const int ext_limbs = l + K;
+    const int prime = x < l ? x : L + (x - l);
+    const int own_digit = x < l ? x / alpha : -1;
+    const double p = as_const(&fprimes[prime].p)[0], pinv = as_const(&fprimes[prime].p)[1];
+    const u64* key = steps.key[s];
+    const uint32_t jsrc = galois_src_fp(j, steps.galois[s], log_n);
+    double kb[IPF_MAXD], ka[IPF_MAXD];
+#pragma unroll
+    for (int d = 0; d < IPF_MAXD; d++) {
+        if (d < digits) {
+            kb[d] = fp_from_u64(key[(((u64)d * 2 + 0) * total + prime) * n + j]);
+            ka[d] = fp_from_u64(key[(((u64)d * 2 + 1) * total + prime) * n + j]);
+        }
+    }
+    for (u64 b = 0; b < n_batch; b++) {
+        double sb = 0.0, sa = 0.0;
+#pragma unroll
+        for (int d = 0; d < IPF_MAXD; d++) {
+            if (d < digits) {
+                const u64 ev = d == own_digit ? own_src[b * own_bs + (u64)x * n + jsrc]
+                                              : ext[b * ext_bs + ((u64)d * ext_limbs + x) * n + jsrc];
+                const double e = fp_from_u64(ev);
+                sb += fp_mulmod(e, kb[d], p, pinv);
+                sa += fp_mulmod(e, ka[d], p, pinv);
+            }
+        }
+        u64* dst = acc + ((u64)s * n_batch + b) * acc_bs;
+        dst[(u64)x * n + j] = fp_canonical(sb, p, pinv);
+        dst[((u64)ext_limbs + x) * n + j] = fp_canonical(sa, p, pinv);
+    }
+}
+
+hipError_t launch_inner_product_steps_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
+                                         int alpha, const IpSteps& steps, int n_steps, int total, const u64* own_src,
+                                         u64 own_bs, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
+    if (digits > IPF_MAXD || n_steps < 1 || n_steps > FP_MAX_STEPS) return hipErrorInvalidValue;
+    if (!fprimes || !ext || !own_src || !acc || n_batch == 0) return hipErrorInvalidValue;
+    for (int s = 0; s < n_steps; s++)
+        if (!steps.key[s] || steps.galois[s] == 0) return hipErrorInvalidValue;
+    dim3 grid((1u << log_n) / IPF_NT, l + K, n_steps);
+    ProfScope prof__("inner_product_steps_fp_kernel", st);
+    hipLaunchKernelGGL(inner_product_steps_fp_kernel, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha,
+                       steps, total, own_src, own_bs, acc, acc_bs, n_batch, log_n);
+    return hipGetLastError();
 }
 
 hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
