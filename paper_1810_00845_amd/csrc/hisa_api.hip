@@ -232,9 +232,14 @@ int gather_batch(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, BatchIn* bi
     }
     bi->tmp = dev_alloc(ctx, n * words * sizeof(u64));
     if (!bi->tmp) return HISA_ERR_OOM;
-    for (size_t i = 0; i < n; i++)
-        HIP_TRY(ctx, hipMemcpyAsync((u64*)bi->tmp->ptr + i * words, cts[i]->data, words * sizeof(u64),
+    // one copy per run of neighbouring views of one allocation (a concatenation of two batches is two runs)
+    for (size_t i = 0; i < n;) {
+        size_t j = i + 1;
+        while (j < n && cts[j]->blk == cts[i]->blk && cts[j]->data == cts[i]->data + (j - i) * words) j++;
+        HIP_TRY(ctx, hipMemcpyAsync((u64*)bi->tmp->ptr + i * words, cts[i]->data, (j - i) * words * sizeof(u64),
                                     hipMemcpyDeviceToDevice, ctx->stream));
+        i = j;
+    }
     bi->base = (u64*)bi->tmp->ptr;
     bi->stride = words;
     return HISA_OK;
