@@ -119,8 +119,15 @@ def cpu_baseline(log_n, q_bits, dnum, special_bits, seed, sample, steps):
     with ThreadPoolExecutor(max_workers=cores) as ex:
         list(ex.map(lambda c: o.rot_left(c, steps[0]), cts))
     dt = time.perf_counter() - t0
+    one = min(4, sample)                       # the same call on one thread, for the per-core figure
+    t1 = time.perf_counter()
+    for c in cts[:one]:
+        o.rot_left(c, steps[0])
+    dt1 = time.perf_counter() - t1
     return {"value": sample / dt, "unit": "rotLeft/s", "cores": cores, "kind": "oracle",
-            "sample": "%d ciphertexts of the same N, limbs, dnum, one rotLeft(%d) each, %.1f s" % (sample, steps[0], dt)}
+            "single_thread_value": one / dt1,
+            "sample": "%d ciphertexts of the same N, limbs, dnum, one rotLeft(%d) each, %.1f s on %d threads; %d of them "
+                      "again on one thread, %.1f s" % (sample, steps[0], dt, cores, one, dt1)}
 
 
 def network_latencies():
