@@ -3,8 +3,8 @@
 The schedules of the paper's runtime (Sec. "Runtime"; Algorithm 1 for conv2d
 with VALID padding, its SAME-padding variant with a mask, homomorphic matmul
 without and with replicas (the latter with a CHW-tiled output), CHW-tiled
-conv2d, the masking multiply, pooling, degree-2 activation) written as plain
-loops over the
+conv2d, the masking multiply, the conversions between the two tilings,
+pooling, degree-2 activation) written as plain loops over the
 oracle's HISA instructions, one instruction per statement, in the paper's
 order.  Each layer also returns the fixed-point integers it used, so that a
 test can hand the very same integers to another implementation.
@@ -455,3 +455,46 @@ def rot_steps_conv_chw(o: Oracle, t: OTensor, fh, fw, pad_same=False):
     wrap, amounts = chw_conv_geometry(o, t, fh, fw, pad_same)
     steps = {a for plane in amounts for row in plane for a in row} | ({o.slots - wrap} if wrap else set())
     return sorted(steps - {0})
+
+
+def to_chw(o: Oracle, t: OTensor, c_inner, c_stride):
+    """Layout switch HW -> CHW (Sec. "Data Layout Selection", the layouts that change tiling around a layer): channel
+    g c_inner + b moves b blocks to the right (rotRight by b c_stride) and the c_inner channels of a group are added
+    into one ciphertext.  The input must be clean (what lies between the elements would land on other channels); no
+    level is used."""
+    assert t.c_inner == 1 and t.clean
+    assert t.offset + (c_inner - 1) * c_stride + (t.height - 1) * t.h_stride + (t.width - 1) * t.w_stride < o.slots
+    per = -(-t.channels // c_inner)
+    outs = []
+    for b in range(t.batch):
+        for g in range(per):
+            acc = t.cts[b * t.channels + g * c_inner]
+            for k in range(1, min(c_inner, t.channels - g * c_inner)):
+                acc = o.add(acc, o.rot_right(t.cts[b * t.channels + g * c_inner + k], k * c_stride))
+            outs.append(acc)
+    return replace(t, cts=outs, c_inner=c_inner, c_stride=c_stride)
+
+
+def to_hw(o: Oracle, t: OTensor):
+    """Layout switch CHW -> HW: block b of a ciphertext is rotated to the front (rotLeft by b c_stride) and everything
+    but the plane is masked away (mulPlain by the 0/1 vector of the plane's slots at the scale of the last modulus,
+    divScalar): one level, clean HW-tiled output.  Returns (tensor, the integers used)."""
+    l = t.cts[0].limbs
+    mask_scale = float(o.primes[l - 1])
+    z = np.zeros(o.slots)
+    z[plane_slots(t.height, t.width, t.h_stride, t.w_stride, t.offset)] = 1.0
+    ints = {"mask_coeffs": o.encode_coeffs(z, mask_scale), "mask_scale": mask_scale}
+    return to_hw_fixed(o, t, ints), ints
+
+
+def to_hw_fixed(o: Oracle, t: OTensor, ints):
+    per = cts_per_image(t)
+    outs = []
+    for b in range(t.batch):
+        for c in range(t.channels):
+            ct = t.cts[b * per + c // t.c_inner]
+            k = c % t.c_inner
+            temp = o.rot_left(ct, k * t.c_stride) if k else ct
+            temp = o.mul_plain(temp, o.pt_from_coeffs(ints["mask_coeffs"], ints["mask_scale"], ct.limbs))
+            outs.append(o.div_scalar(temp, o.max_scalar_div(temp, float("inf"))))
+    return replace(t, cts=outs, c_inner=1, c_stride=0, clean=1)

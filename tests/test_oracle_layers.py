@@ -261,3 +261,25 @@ def test_mask_tensor_cleans_a_pooled_tensor():
         z = o.decode(o.decrypt(ct)).real
         z[layers.tensor_slots(m)] = 0
         assert np.abs(z).max() <= 1e-3
+
+
+def test_layout_switches_round_trip():
+    """HW -> CHW -> HW: values unchanged, the CHW tensor is what tensor_encrypt_chw would hold, the way back costs one
+    level and leaves a clean tensor even from a pooled (not clean) CHW tensor."""
+    o = Oracle(10, [50, 40, 40], 3, 55, seed=16)
+    x = synth.image(61, 5, 4, 4)[None]
+    t = layers.tensor_encrypt(o, x, 2.0 ** 40, 3, h_stride=4)
+    o.gen_rot_keys([o.slots - 32, 32, 1, 4, 5])
+    c = layers.to_chw(o, t, 2, 32)
+    assert (c.c_inner, c.c_stride, len(c.cts), c.clean, c.cts[0].limbs) == (2, 32, 3, 1, 3)
+    assert np.abs(layers.tensor_decrypt(o, c) - x).max() <= 1e-6
+    z = o.decode(o.decrypt(c.cts[2])).real                # channel 4 alone in the last ciphertext
+    assert np.abs(z[32:]).max() <= 1e-6
+    pooled = layers.sum_pool2x2(o, c)
+    h, _ = layers.to_hw(o, pooled)
+    assert (h.c_inner, len(h.cts), h.clean, h.cts[0].limbs, h.height, h.h_stride) == (1, 5, 1, 2, 2, 8)
+    assert np.abs(layers.tensor_decrypt(o, h) - plain_net.sum_pool2x2(x)).max() <= 1e-3
+    for ct in h.cts:
+        z = o.decode(o.decrypt(ct)).real
+        z[layers.plane_slots(2, 2, 8, 2, 0)] = 0
+        assert np.abs(z).max() <= 1e-3
