@@ -136,13 +136,14 @@ def network_latencies():
     encoded ahead of time (hisa_conv2d_prepare, hisa_fc_prepare, hisa_matmul_prepare) (median of 3 after one set-up
     pass that generates the keys and the plans).  Every data layout is timed (Sec. "Data Layout Selection":
     HW-tiling throughout, HW-tiling up to the first fully connected layer and CHW-tiling after it, CHW-tiling
-    throughout); latency_ms is that of the layout the cost model selects from dry runs on the analysis backend
+    throughout, CHW-tiling with HW-tiled convolutions; the last needs two more levels than the SqueezeNet-style
+    parameters have); latency_ms is that of the layout the cost model selects from dry runs on the analysis backend
     (operation counts x micro-benchmarked unit costs), as the paper's compiler does; layouts_ms shows whether that was
     the fastest."""
     from paper_1810_00845_amd import hisa, nets
     out = {}
-    for name, paper, layouts in (("lenet_small", "LeNet-5-small: 8 s (HEAAN, 16 Xeon threads)", ("hw", "chw_fc", "chw")),
-                                 ("lenet_medium", "LeNet-5-medium: 51 s (HEAAN, 16 Xeon threads)", ("hw", "chw_fc", "chw")),
+    for name, paper, layouts in (("lenet_small", "LeNet-5-small: 8 s (HEAAN, 16 Xeon threads)", ("hw", "chw_fc", "chw", "hw_conv")),
+                                 ("lenet_medium", "LeNet-5-medium: 51 s (HEAAN, 16 Xeon threads)", ("hw", "chw_fc", "chw", "hw_conv")),
                                  ("squeezenet_cifar", "SqueezeNet-CIFAR: 1342 s (HEAAN, 16 Xeon threads)", ("hw", "chw"))):
         params, layers, x = getattr(nets, name)()
         limbs = len(params["q_bits"])

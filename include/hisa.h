@@ -347,6 +347,25 @@ int hisa_fc_plan_free(hisa_ctx* ctx, hisa_fc_plan* plan);
 int hisa_tensor_mask(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out);
 int hisa_tensor_mask_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* mask_coeffs, double mask_scale,
                            hisa_tensor* out);
+/* Layout switches (Sec. "Data Layout Selection": the layouts that change the
+ * tiling around a layer).
+ * hisa_tensor_to_chw: clean HW-tiled tensor -> CHW-tiled with c_inner channels
+ * per ciphertext, c_stride slots apart: channel g*c_inner + k is rotated right
+ * by k*c_stride and the channels of a group are added; no level is used; a
+ * tensor that is not clean, or blocks that do not fit the slots: HISA_ERR_ARG.
+ * hisa_tensor_to_hw: CHW-tiled tensor -> clean HW-tiled tensor: every
+ * ciphertext is rotated left by k*c_stride for its blocks k (one shared
+ * decomposition), each result times the 0/1 vector of the plane's slots
+ * (scale of the last modulus), divScalar: one level.  The _fixed form takes the
+ * mask as mask_coeffs[N] at mask_scale.  hisa_tensor_layout_rot_steps lists the
+ * rotation amounts: of to_hw if `in` is CHW-tiled (c_inner, c_stride ignored),
+ * else of to_chw(c_inner, c_stride). */
+int hisa_tensor_to_chw(hisa_ctx* ctx, const hisa_tensor* in, uint32_t c_inner, uint32_t c_stride, hisa_tensor* out);
+int hisa_tensor_to_hw(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out);
+int hisa_tensor_to_hw_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* mask_coeffs, double mask_scale,
+                            hisa_tensor* out);
+int hisa_tensor_layout_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, uint32_t c_inner, uint32_t c_stride, int32_t* steps,
+                                 size_t cap, size_t* n);
 /* Homomorphic matmul with replicas (Sec. "Homomorphic Tensor Operations",
  * paragraphs "Homomorphic matmul" and "CHW-tiled convolution": replicas cost
  * log-many rotations and divide the number of mulPlain; reductions over equally

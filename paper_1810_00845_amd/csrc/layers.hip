@@ -1328,6 +1328,112 @@ extern "C" int hisa_tensor_mask_fixed(hisa_ctx* ctx, const hisa_tensor* in, cons
     return mask_finish(ctx, in, xs, out);
 }
 
+// ---------------------------------------------------------------------------
+// layout switches (Sec. "Data Layout Selection": layouts that change the tiling around a layer)
+// ---------------------------------------------------------------------------
+extern "C" int hisa_tensor_layout_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, uint32_t c_inner, uint32_t c_stride,
+                                            int32_t* steps, size_t cap, size_t* n) {
+    if (!ctx) return HISA_ERR_ARG;
+    TRY(check_layout(ctx, in));
+    std::vector<int32_t> all;
+    if (t_ci(in) > 1) for (uint32_t k = 1; k < t_ci(in); k++) all.push_back(norm_step(ctx, (i64)k * in->c_stride));
+    else for (uint32_t k = 1; k < c_inner; k++) all.push_back(norm_step(ctx, -(i64)k * c_stride));
+    return write_steps(all, steps, cap, n);
+}
+
+// HW -> CHW: channel g c_inner + k moves k blocks to the right and the channels of a group are added up.
+extern "C" int hisa_tensor_to_chw(hisa_ctx* ctx, const hisa_tensor* in, uint32_t c_inner, uint32_t c_stride, hisa_tensor* out) {
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts || c_inner < 2 || c_stride == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(require_hw_tiling(ctx, in, "the switch to CHW-tiling"));
+    if (!in->clean) return fail(ctx, HISA_ERR_ARG, "the switch to CHW-tiling needs a clean tensor (hisa_tensor_mask makes one)");
+    hisa_tensor probe = *in;
+    probe.c_inner = c_inner; probe.c_stride = c_stride;
+    TRY(check_layout(ctx, &probe));
+    const uint32_t B = in->batch, C = in->channels, per = (C + c_inner - 1) / c_inner, l = in->cts[0]->limbs;
+    const u64 words = ct_words(ctx, 2, l);
+    std::vector<hisa_ct*> acc((size_t)B * per, nullptr);
+    TRY(alloc_ct_batch(ctx, acc.size(), 2, l, in->cts[0]->scale, acc.data()));
+    int rc = HISA_OK;
+    // channel k of every group: one batch per k, rotated together and added into the groups' ciphertexts
+    for (uint32_t k = 0; k < c_inner && rc == HISA_OK; k++) {
+        std::vector<const hisa_ct*> src;
+        std::vector<hisa_ct*> dst;
+        for (uint32_t b = 0; b < B; b++)
+            for (uint32_t g = 0; g < per; g++)
+                if (g * c_inner + k < C) { src.push_back(in->cts[(size_t)b * C + g * c_inner + k]); dst.push_back(acc[(size_t)b * per + g]); }
+        if (src.empty()) break;
+        std::vector<hisa_ct*> rot(src.size(), nullptr);
+        rc = hisa_rot_left_batch(ctx, src.data(), src.size(), norm_step(ctx, -(i64)k * c_stride), rot.data());
+        for (size_t i = 0; i < src.size() && rc == HISA_OK; i++) {
+            hipError_t e = k == 0 ? hipMemcpyAsync(dst[i]->data, rot[i]->data, words * sizeof(u64), hipMemcpyDeviceToDevice, ctx->stream)
+                                  : launch_addsub(ctx->d_primes, dst[i]->data, rot[i]->data, dst[i]->data, OP_ADD, (int)l, 2, 2, 1, words,
+                                                  words, words, (int)ctx->log_n, ctx->stream);
+            if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "layout switch: %s", hipGetErrorString(e));
+        }
+        free_handles(ctx, rot);
+    }
+    if (rc != HISA_OK) { free_handles(ctx, acc); return rc; }
+    for (size_t i = 0; i < acc.size(); i++) out->cts[i] = acc[i];
+    fill_out_meta(out, B, C, in->height, in->width, in->h_stride, in->w_stride, in->offset, 1, c_inner, c_stride);
+    return HISA_OK;
+}
+
+// CHW -> HW: block k of every ciphertext rotated to the front (the rotations of one ciphertext share its
+// decomposition), then everything but the plane masked away.  mask: NTT-form plaintext [l][N].
+static int to_hw_run(hisa_ctx* ctx, const hisa_tensor* in, const u64* mask, double mask_scale, hisa_tensor* out) {
+    const uint32_t B = in->batch, C = in->channels, ci = t_ci(in), per = (uint32_t)t_per(in), l = in->cts[0]->limbs;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "the switch to HW-tiling needs a level to rescale into");
+    const size_t n_in = (size_t)B * per;
+    const u64 words = ct_words(ctx, 2, l);
+    std::vector<int32_t> steps;
+    for (uint32_t k = 0; k < ci; k++) steps.push_back(norm_step(ctx, (i64)k * in->c_stride));
+    std::vector<hisa_ct*> rot(steps.size() * n_in, nullptr);
+    TRY(hisa_rot_left_hoisted_batch(ctx, (const hisa_ct* const*)in->cts, n_in, steps.data(), steps.size(), rot.data()));
+    std::vector<hisa_ct*> outs((size_t)B * C, nullptr);
+    int rc = alloc_ct_batch(ctx, outs.size(), 2, l, in->cts[0]->scale * mask_scale, outs.data());
+    for (uint32_t b = 0; b < B && rc == HISA_OK; b++)
+        for (uint32_t c = 0; c < C && rc == HISA_OK; c++) {
+            const hisa_ct* src = rot[(size_t)(c % ci) * n_in + (size_t)b * per + c / ci];
+            hipError_t e = launch_mul_plain(ctx->d_primes, src->data, mask, outs[(size_t)b * C + c]->data, (int)l, 2, 1, words, words,
+                                            (int)ctx->log_n, ctx->stream);
+            if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "layout switch: %s", hipGetErrorString(e));
+        }
+    free_handles(ctx, rot);
+    if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
+    if (rc != HISA_OK) { free_handles(ctx, outs); return rc; }
+    for (size_t i = 0; i < outs.size(); i++) out->cts[i] = outs[i];
+    fill_out_meta(out, B, C, in->height, in->width, in->h_stride, in->w_stride, in->offset, 1);
+    return HISA_OK;
+}
+
+extern "C" int hisa_tensor_to_hw(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out) {
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
+    if (t_ci(in) < 2) return fail(ctx, HISA_ERR_ARG, "the tensor is HW-tiled already");
+    const uint32_t l = in->cts[0]->limbs;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "the switch to HW-tiling needs a level to rescale into");
+    Temp mask(ctx, (size_t)l * ctx->N * sizeof(u64));
+    if (!mask.ok()) return HISA_ERR_OOM;
+    const double mask_scale = (double)ctx->mod[l - 1];
+    const std::vector<uint32_t> slots = plane_slots(in->height, in->width, in->h_stride, in->w_stride, in->offset);
+    std::vector<double> ones(slots.size(), 1.0);
+    TRY(encode_sparse_batch(ctx, slots, ones.data(), 1, mask_scale, (int)l, mask.u()));
+    return to_hw_run(ctx, in, mask.u(), mask_scale, out);
+}
+
+extern "C" int hisa_tensor_to_hw_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* mask_coeffs, double mask_scale,
+                                       hisa_tensor* out) {
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts || !mask_coeffs) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    if (t_ci(in) < 2) return fail(ctx, HISA_ERR_ARG, "the tensor is HW-tiled already");
+    const uint32_t l = in->cts[0]->limbs;
+    Temp mask(ctx, (size_t)l * ctx->N * sizeof(u64));
+    if (!mask.ok()) return HISA_ERR_OOM;
+    TRY(coeffs_to_plain_batch(ctx, mask_coeffs, 1, (int)l, mask.u()));
+    return to_hw_run(ctx, in, mask.u(), mask_scale, out);
+}
+
 // masks: NTT-form plaintexts [per][l][N] (needed when R > 1 and the input is not clean), pts: [groups][per][l'][N] with
 // l' = l - 1 after the masking multiply, else l.
 static int matmul_run(hisa_ctx* ctx, const hisa_tensor* in, const MatmulGeom& g, const u64* masks, double mask_scale,

@@ -471,6 +471,23 @@ class Context:
         assert mc.shape == (-(-t.channels // t.c_inner), self.N)
         return self._layer("hisa_tensor_mask_fixed", t, len(t.cts), mc.ctypes.data_as(C.POINTER(C.c_int64)), C.c_double(mask_scale))
 
+    def tensor_to_chw(self, t, c_inner, c_stride):
+        """Clean HW-tiled tensor -> CHW-tiled (c_inner channels per ciphertext, c_stride slots apart)."""
+        return self._layer("hisa_tensor_to_chw", t, t.batch * -(-t.channels // c_inner), C.c_uint32(c_inner), C.c_uint32(c_stride))
+
+    def tensor_to_hw(self, t):
+        """CHW-tiled tensor -> clean HW-tiled tensor, one level lower."""
+        return self._layer("hisa_tensor_to_hw", t, t.batch * t.channels)
+
+    def tensor_to_hw_fixed(self, t, mask_coeffs, mask_scale):
+        mc = np.ascontiguousarray(mask_coeffs, dtype=np.int64)
+        assert mc.shape == (self.N,)
+        return self._layer("hisa_tensor_to_hw_fixed", t, t.batch * t.channels, mc.ctypes.data_as(C.POINTER(C.c_int64)),
+                           C.c_double(mask_scale))
+
+    def tensor_layout_rot_steps(self, t, c_inner=1, c_stride=0):
+        return self._steps("hisa_tensor_layout_rot_steps", t, C.c_uint32(c_inner), C.c_uint32(c_stride))
+
     def matmul_geometry(self, t, out_features, replicas):
         """(block length P, replicas used R, number of output ciphertexts) of matmul on tensors laid out like t."""
         st, _arr = t._struct()

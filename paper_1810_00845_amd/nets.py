@@ -89,16 +89,16 @@ def _concat_channels(ctx, a, b):
     return t
 
 
-LAYOUTS = ("hw", "chw_fc", "chw")
+LAYOUTS = ("hw", "chw_fc", "chw", "hw_conv")
 
 
-def chw_blocks(slots, plane_slots_needed, layers):
+def chw_blocks(slots, plane_slots_needed, layers, chw_convs=True):
     """CHW-tiling of the input: (channels per ciphertext, channel stride).  The stride is the power of two that holds
     a plane with its border; as many blocks as the slots hold, and no more than the convolutions can rotate through
     (taps x blocks rotation amounts per input ciphertext, at most 256)."""
     c_stride = 1 << max(0, plane_slots_needed - 1).bit_length()
     taps = [1]
-    for layer in layers:
+    for layer in layers if chw_convs else ():
         if layer[0] in ("conv", "conv_same"):
             taps.append(layer[1].shape[0] * layer[1].shape[1])
         elif layer[0] == "fire":
@@ -118,14 +118,17 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
     HW-before", Sec. "Data Layout Selection") is HW-tiled up to the first fully connected layer, which runs as a
     matmul with as many replicas as the slots hold and leaves a CHW-tiled tensor for the layers after it; "chw" packs
     several channels into every ciphertext from the input on (CHW-tiled convolutions multiply by plaintexts and need
-    clean inputs: a masking multiply follows each pool)."""
+    clean inputs: a masking multiply follows each pool); "hw_conv" (the paper's "HW-conv and CHW-rest") keeps the tensor
+    CHW-tiled between the layers but switches to HW-tiling before every convolution and back after it (one level
+    for the way to HW, one for the masking multiply that makes Algorithm 1's output clean enough to pack)."""
     assert layout in LAYOUTS
     replicas = 1 if layout == "hw" else 1 << 30
     tiling = {}
-    if layout == "chw":
+    if layout in ("chw", "hw_conv"):
         hs = x.shape[3] + 2 * border
-        ci, cs = chw_blocks(ctx.N // 2, (x.shape[2] + 2 * border) * hs, layers)
-        tiling = dict(c_inner=ci, c_stride=cs)
+        ci, cs = chw_blocks(ctx.N // 2, (x.shape[2] + 2 * border) * hs, layers, chw_convs=layout == "chw")
+        if layout == "chw":
+            tiling = dict(c_inner=ci, c_stride=cs)
     if border:   # leave `border` rows and columns of zero slots around every plane (SAME convolutions need them)
         hs = x.shape[3] + 2 * border
         t = ctx.tensor_encrypt(x, scale, limbs, h_stride=hs, offset=border * hs + border, **tiling)
@@ -153,6 +156,26 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
         return ctx.fc_apply(t, plans[idx][1])
 
     def convolution(key, t, w, fh, fw, **kw):
+        if layout == "hw_conv":           # to HW-tiling, Algorithm 1, masking multiply, back to CHW-tiling
+            unpacked = None
+            if t.c_inner > 1:
+                if make_keys:
+                    ctx.gen_rot_keys(ctx.tensor_layout_rot_steps(t))
+                t = unpacked = ctx.tensor_to_hw(t)
+            out = hw_or_chw_convolution(key, t, w, fh, fw, **kw)
+            if unpacked is not None:
+                unpacked.free()
+            if not out.clean:
+                dirty, out = out, ctx.tensor_mask(out)
+                dirty.free()
+            if make_keys:
+                ctx.gen_rot_keys(ctx.tensor_layout_rot_steps(out, ci, cs))
+            flat, out = out, ctx.tensor_to_chw(out, ci, cs)
+            flat.free()
+            return out
+        return hw_or_chw_convolution(key, t, w, fh, fw, **kw)
+
+    def hw_or_chw_convolution(key, t, w, fh, fw, **kw):
         cleaned = None
         if t.c_inner > 1:                 # CHW-tiled: plaintext weights on a clean input
             kw["mode"] = 2

@@ -387,3 +387,35 @@ def test_mask_layer_then_chw_conv_on_a_pooled_tensor():
     same_tensor(g, o, gc_, oc_)
     assert np.abs(g.tensor_decrypt(gc_) - plain_net.conv2d(plain_net.sum_pool2x2(x), w)).max() <= 1e-3
     g.close()
+
+
+def test_layout_switches_bit_exact():
+    """HW -> CHW -> pool -> HW through the C ABI against the oracle, bit for bit (batch of two, ragged last group);
+    a tensor that is not clean cannot be packed."""
+    from oracle import layers
+    from paper_1810_00845_amd import hisa
+    from paper_1810_00845_amd import synth
+    for log_n in (10, 12):
+        g, o = make_pair(log_n, [50, 40, 40], 3, 50, 16)
+        x = synth.image(61, 5, 4, 4)[None].repeat(2, axis=0) * np.array([1.0, 0.3])[:, None, None, None]
+        gt, ot = both_tensors(g, o, x, 2.0 ** 40, 3, h_stride=4)
+        steps = g.tensor_layout_rot_steps(gt, 2, 32)
+        assert steps == [o.slots - 32]
+        g.gen_rot_keys(steps + [1, 4, 5, 32]); o.gen_rot_keys(steps + [1, 4, 5, 32])
+        gc, oc = g.tensor_to_chw(gt, 2, 32), layers.to_chw(o, ot, 2, 32)
+        same_tensor(g, o, gc, oc)
+        assert np.abs(g.tensor_decrypt(gc) - x).max() <= 1e-6
+        gp, op = g.sum_pool2x2(gc), layers.sum_pool2x2(o, oc)
+        same_tensor(g, o, gp, op)
+        assert g.tensor_layout_rot_steps(gp) == [32]
+        oh, ints = layers.to_hw(o, op)
+        gh = g.tensor_to_hw_fixed(gp, ints["mask_coeffs"], ints["mask_scale"])
+        same_tensor(g, o, gh, oh)
+        gh2 = g.tensor_to_hw(gp)
+        assert gh2.meta() == gh.meta() and np.abs(g.tensor_decrypt(gh2) - plain_net.sum_pool2x2(x)).max() <= 1e-3
+        hw_pool = g.sum_pool2x2(gt)
+        with pytest.raises(hisa.HisaError):
+            g.tensor_to_chw(hw_pool, 2, 32)
+        with pytest.raises(hisa.HisaError):
+            g.tensor_to_hw(gt)
+        g.close()

@@ -60,11 +60,13 @@ def test_network_matches_plaintext(name):
 
 
 @pytest.mark.parametrize("name,layout", [("lenet_small", "chw_fc"), ("lenet_medium", "chw_fc"), ("lenet_small", "chw"),
-                                         ("lenet_medium", "chw"), ("squeezenet_cifar", "chw")])
+                                         ("lenet_medium", "chw"), ("squeezenet_cifar", "chw"), ("lenet_small", "hw_conv"),
+                                         ("lenet_medium", "hw_conv")])
 def test_network_other_layouts_match_plaintext(name, layout):
     """The other layouts of Sec. "Data Layout Selection": "CHW-fc and HW-before" (HW-tiled convolutions, the first
     fully connected layer as a matmul with replicas, CHW-tiled after it) and CHW throughout (several channels per
-    ciphertext from the input on).  Same networks, same tolerance."""
+    ciphertext from the input on), "HW-conv and CHW-rest" (CHW-tiled between the layers, HW-tiled inside every
+    convolution).  Same networks, same tolerance."""
     from paper_1810_00845_amd import hisa, nets
     params, layers, x = getattr(nets, name)()
     want = plain_forward(layers, x)
