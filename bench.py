@@ -162,7 +162,13 @@ def network_latencies():
             nets.run_encrypted(ctx, layers, x, params["scale"], limbs, make_keys=True, **kw)
             runs = sorted((nets.run_encrypted(ctx, layers, x, params["scale"], limbs, **kw) for _ in range(3)),
                           key=lambda r: r[1])
-            res[layout] = (runs[1][1], runs[1][2])
+            res[layout] = (runs[1][1], runs[1][2], None)
+            if layout == selected:     # one more inference with HIP events around every kernel: where the time goes
+                ctx.profile_enable(True)
+                nets.run_encrypted(ctx, layers, x, params["scale"], limbs, **kw)
+                prof = sorted(ctx.profile_read().items(), key=lambda kv: -kv[1][1])
+                ctx.profile_enable(False)
+                res[layout] = (runs[1][1], runs[1][2], {k: [c, round(ms, 3)] for k, (c, ms) in prof[:8]})
             nets.free_plans(ctx, plans)
             ctx.close()
         best = selected
@@ -171,6 +177,7 @@ def network_latencies():
                      "cost_model_ms": {k: round(v * 1e3, 2) for k, v in est.items()},
                      "log_n": params["log_n"], "limbs": limbs, "dnum": params["dnum"],
                      "layers_ms": [[k, round(s * 1e3, 2)] for k, s in res[best][1]],
+                     "kernels_launches_ms": res[best][2],
                      "paper_context": paper, "data": "seeded random weights and image"}
     return out
 
