@@ -98,6 +98,9 @@ def lib():
         L.orc_secret_automorph.argtypes = [vp, C.c_uint64, u64p]
         L.orc_mod_down.argtypes = [vp, u64p, C.c_int, u64p]
         L.orc_key_switch.argtypes = [vp, u64p, C.c_int, u64p, u64p, u64p]
+        L.orc_key_switch_acc.argtypes = [vp, u64p, C.c_int, u64p, u64p, u64p]
+        L.orc_fma_const.argtypes = [vp, u64p, u64p, u64p, C.POINTER(C.c_int), C.c_int]
+        L.orc_fma_plain.argtypes = [vp, u64p, u64p, u64p, C.POINTER(C.c_int), C.c_int]
         L.orc_rotate.argtypes = [vp, u64p, C.c_int, C.c_uint64, u64p, u64p]
         L.orc_relinearize.argtypes = [vp, u64p, C.c_int, u64p, u64p]
         L.orc_rescale.argtypes = [vp, u64p, C.c_int, C.c_int, u64p]
@@ -416,6 +419,50 @@ class Oracle:
         ks1 = np.zeros((l, self.N), dtype=np.uint64)
         lib().orc_key_switch(self._h, _p(np.ascontiguousarray(d)), l, _p(self.keys[key_id]), _p(ks0), _p(ks1))
         return ks0, ks1
+
+    # ---- the key switch in two halves, for sums formed before the division by P ----
+    def ext_primes(self, l: int):
+        """Indices (into self.primes) of the l + K limbs a key-switch accumulator lives on."""
+        return list(range(l)) + [self.L + m for m in range(self.K)]
+
+    def key_switch_acc(self, d: np.ndarray, key_id: int):
+        """Decompose, ModUp and inner product with the key: the accumulators (acc_b, acc_a), each [l + K][N], whose
+        mod_down gives the key switch of d."""
+        l = d.shape[0]
+        acc_b = np.zeros((l + self.K, self.N), dtype=np.uint64)
+        acc_a = np.zeros((l + self.K, self.N), dtype=np.uint64)
+        lib().orc_key_switch_acc(self._h, _p(np.ascontiguousarray(d)), l, _p(self.keys[key_id]), _p(acc_b), _p(acc_a))
+        return acc_b, acc_a
+
+    def mod_down(self, acc: np.ndarray, l: int) -> np.ndarray:
+        out = np.zeros((l, self.N), dtype=np.uint64)
+        lib().orc_mod_down(self._h, _p(np.ascontiguousarray(acc)), l, _p(out))
+        return out
+
+    def automorph_ntt(self, x: np.ndarray, g: int) -> np.ndarray:
+        """sigma_g of an NTT-form polynomial [l][N] on the primes q_0..q_{l-1}."""
+        out = np.zeros_like(x)
+        lib().orc_automorph_ntt(self._h, _p(np.ascontiguousarray(x)), g, 0, x.shape[0], _p(out))
+        return out
+
+    def fma_const(self, acc: np.ndarray, x: np.ndarray, v: int, primes):
+        """acc += x * v limb-wise on the listed primes (in place)."""
+        idx = (C.c_int * len(primes))(*primes)
+        w = np.array([int(v) % self.primes[i] for i in primes], dtype=np.uint64)
+        lib().orc_fma_const(self._h, _p(acc), _p(np.ascontiguousarray(x)), _p(w), idx, len(primes))
+
+    def fma_plain(self, acc: np.ndarray, x: np.ndarray, pt: np.ndarray, primes):
+        """acc += x (.) pt slot-wise on the listed primes (in place)."""
+        idx = (C.c_int * len(primes))(*primes)
+        lib().orc_fma_plain(self._h, _p(acc), _p(np.ascontiguousarray(x)), _p(np.ascontiguousarray(pt)), idx, len(primes))
+
+    def residues_ntt(self, coeffs, primes) -> np.ndarray:
+        """Signed integer coefficients -> NTT-form residues on the listed primes, [len(primes)][N]."""
+        co = np.ascontiguousarray(coeffs, dtype=np.int64)
+        out = np.zeros((len(primes), self.N), dtype=np.uint64)
+        for k, i in enumerate(primes):
+            lib().orc_signed_to_ntt(self._h, co.ctypes.data_as(i64p), i, _p(out[k]))
+        return out
 
     # ---- division profile -------------------------------------------------
     def max_scalar_div(self, a: Ct, ub: float) -> int:

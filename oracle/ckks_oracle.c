@@ -718,14 +718,15 @@ void orc_mod_down(const orc_ctx *c, const u64 *acc, int l, u64 *out) {
  *  5. both accumulators are brought down by P (orc_mod_down).
  * Output ks0, ks1: l limbs each, NTT form, with ks0 + ks1*s ~ d*s'.
  */
-void orc_key_switch(const orc_ctx *c, const u64 *d, int l, const u64 *key, u64 *ks0, u64 *ks1) {
+/* steps 1-4 above: the two accumulators over the l + K limbs, before the division by P (zeroed here) */
+void orc_key_switch_acc(const orc_ctx *c, const u64 *d, int l, const u64 *key, u64 *acc_b, u64 *acc_a) {
     u64 n = c->n;
     int total = c->L + c->K, ext = l + c->K;
     int digits = (l + c->alpha - 1) / c->alpha;
     u64 *dc = malloc((size_t)l * n * sizeof(u64));
     u64 *e = malloc(n * sizeof(u64));
-    u64 *acc_b = calloc((size_t)ext * n, sizeof(u64));
-    u64 *acc_a = calloc((size_t)ext * n, sizeof(u64));
+    memset(acc_b, 0, (size_t)ext * n * sizeof(u64));
+    memset(acc_a, 0, (size_t)ext * n * sizeof(u64));
     memcpy(dc, d, (size_t)l * n * sizeof(u64));
     for (int i = 0; i < l; i++) orc_intt(c, i, dc + (size_t)i * n);
     for (int j = 0; j < digits; j++) {
@@ -747,9 +748,40 @@ void orc_key_switch(const orc_ctx *c, const u64 *d, int l, const u64 *key, u64 *
             }
         }
     }
+    free(dc); free(e);
+}
+
+void orc_key_switch(const orc_ctx *c, const u64 *d, int l, const u64 *key, u64 *ks0, u64 *ks1) {
+    int ext = l + c->K;
+    u64 *acc_b = malloc((size_t)ext * c->n * sizeof(u64));
+    u64 *acc_a = malloc((size_t)ext * c->n * sizeof(u64));
+    orc_key_switch_acc(c, d, l, key, acc_b, acc_a);
     orc_mod_down(c, acc_b, l, ks0);
     orc_mod_down(c, acc_a, l, ks1);
-    free(dc); free(e); free(acc_b); free(acc_a);
+    free(acc_b); free(acc_a);
+}
+
+/*
+ * Limb-wise multiply-accumulate on an arbitrary list of primes (indices into c->mod), for sums that are formed
+ * before the division by P: acc[i] += x[i] * w[i] with one constant w[i] per limb (scalar) ...
+ */
+void orc_fma_const(const orc_ctx *c, u64 *acc, const u64 *x, const u64 *w_mod, const int *primes, int limbs) {
+    u64 n = c->n;
+    for (int i = 0; i < limbs; i++) {
+        u64 q = c->mod[primes[i]];
+        for (u64 j = 0; j < n; j++)
+            acc[(size_t)i * n + j] = addmod(acc[(size_t)i * n + j], mulmod(x[(size_t)i * n + j], w_mod[i], q), q);
+    }
+}
+
+/* ... or slot-wise with a plaintext given on the same primes, NTT form */
+void orc_fma_plain(const orc_ctx *c, u64 *acc, const u64 *x, const u64 *pt, const int *primes, int limbs) {
+    u64 n = c->n;
+    for (int i = 0; i < limbs; i++) {
+        u64 q = c->mod[primes[i]];
+        for (u64 j = 0; j < n; j++)
+            acc[(size_t)i * n + j] = addmod(acc[(size_t)i * n + j], mulmod(x[(size_t)i * n + j], pt[(size_t)i * n + j], q), q);
+    }
 }
 
 /*

@@ -97,7 +97,66 @@ def tensor_decrypt(o: Oracle, t: OTensor):
     return out
 
 
-def conv2d(o: Oracle, t: OTensor, w, stride=1, pad_same=False, mode=CONV_SCALAR):
+class SharedModDown:
+    """sum_k weight_k * rotLeft(x_k, amount_k) with the division by P taken once for the whole sum instead of once per
+    rotation (the rotations of a convolution are only ever used inside such sums): every rotated term contributes its
+    key-switch accumulators -- on the l + K limbs, before the division -- times the weight taken on those same limbs,
+    and sigma(c0) times the weight on the l limbs; an unrotated term contributes weight * (c0, c1); at the end
+    (ModDown(E_b) + Z_0, ModDown(E_a) + Z_1).  Up to the rounding of the division this is the sum of the rotated
+    ciphertexts; ciphertext bits differ from the term-by-term schedule.  The accumulators of an (input, amount) pair
+    are computed once and shared by all the sums over the same inputs."""
+
+    def __init__(self, o: Oracle, inputs):
+        self.o, self.inputs = o, inputs
+        self.acc = {}      # (input index, amount) -> (acc_b, acc_a, sigma(c0))
+        self.res = {}      # (weight key, basis) -> residues of a plaintext weight
+
+    def rotated(self, i, amount):
+        if (i, amount) not in self.acc:
+            ct, g = self.inputs[i], self.o.galois_elt(amount)
+            if g not in self.o.keys:
+                raise KeyError("no key for rotation by %d" % amount)
+            acc_b, acc_a = self.o.key_switch_acc(self.o.automorph_ntt(ct.data[1], g), g)
+            self.acc[(i, amount)] = (acc_b, acc_a, self.o.automorph_ntt(ct.data[0], g))
+        return self.acc[(i, amount)]
+
+    def total(self, terms, scale):
+        """terms: (input index, rotLeft amount, weight, weight key); weight is an integer (key None) or an array of N
+        signed plaintext coefficients (key: anything hashable that names it).  Returns the sum as a ciphertext."""
+        from .ckks import Ct
+        o = self.o
+        l = self.inputs[0].limbs
+        ext, qs = o.ext_primes(l), list(range(l))
+        e_b = np.zeros((l + o.K, o.N), dtype=np.uint64)
+        e_a = np.zeros((l + o.K, o.N), dtype=np.uint64)
+        z = np.zeros((2, l, o.N), dtype=np.uint64)
+
+        def fma(acc, x, w, wkey, primes, basis):
+            if wkey is None:
+                o.fma_const(acc, x, int(w), primes)
+            else:
+                if (wkey, basis) not in self.res:
+                    self.res[(wkey, basis)] = o.residues_ntt(w, primes)
+                o.fma_plain(acc, x, self.res[(wkey, basis)], primes)
+
+        any_rotated = False
+        for i, amount, w, wkey in terms:
+            if amount % o.slots == 0:
+                fma(z[0], self.inputs[i].data[0], w, wkey, qs, "q")
+                fma(z[1], self.inputs[i].data[1], w, wkey, qs, "q")
+            else:
+                acc_b, acc_a, r0 = self.rotated(i, amount % o.slots)
+                fma(e_b, acc_b, w, wkey, ext, "ext")
+                fma(e_a, acc_a, w, wkey, ext, "ext")
+                fma(z[0], r0, w, wkey, qs, "q")
+                any_rotated = True
+        out = Ct(z, scale)
+        if any_rotated:
+            out = o.add(Ct(np.stack([o.mod_down(e_b, l), o.mod_down(e_a, l)]), scale), out)
+        return out
+
+
+def conv2d(o: Oracle, t: OTensor, w, stride=1, pad_same=False, mode=CONV_SCALAR, shared_moddown=False):
     """Algorithm 1.  w[FH][FW][IC][OC].  Returns (output tensor, dict of the integers used)."""
     fh, fw, ic_n, oc_n = w.shape
     assert ic_n == t.channels
@@ -127,11 +186,12 @@ def conv2d(o: Oracle, t: OTensor, w, stride=1, pad_same=False, mode=CONV_SCALAR)
         ints.update(w_int=w_int, w_scale=w_scale)
         if mode == CONV_MASKED:
             ints.update(pt_coeffs=o.encode_coeffs(valid, MASK_SCALE), pt_scale=MASK_SCALE)
-    out = conv2d_fixed(o, t, ints, oc_n, fh, fw, stride, pad_same, mode)
+    out = conv2d_fixed(o, t, ints, oc_n, fh, fw, stride, pad_same, mode, shared_moddown)
     return out, ints
 
 
-def conv2d_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, mode):
+def conv2d_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, mode, shared_moddown=False):
+    """shared_moddown: the sum over (input channel, tap) goes through SharedModDown (scalar modes only)."""
     l = t.cts[0].limbs
     ph, pw = (fh // 2, fw // 2) if pad_same else (0, 0)
     if pad_same:
@@ -152,7 +212,18 @@ def conv2d_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, mo
         mask_pt = o.pt_from_coeffs(ints["pt_coeffs"], ints["pt_scale"], l)
     outs = []
     for b in range(t.batch):
+        shared = SharedModDown(o, t.cts[b * t.channels:(b + 1) * t.channels]) if shared_moddown else None
         for oc in range(oc_n):
+            if shared is not None:
+                assert mode != CONV_PLAIN
+                terms = [(ic, ((fy - ph) * t.h_stride + (fx - pw) * t.w_stride) % o.slots,
+                          int(ints["w_int"][fy, fx, ic, oc]), None)
+                         for ic in range(t.channels) for fy in range(fh) for fx in range(fw)]
+                acc = shared.total(terms, t.cts[0].scale * ints["w_scale"])
+                if mode == CONV_MASKED:
+                    acc = o.mul_plain(acc, mask_pt)
+                outs.append(o.div_scalar(acc, o.max_scalar_div(acc, float("inf"))))
+                continue
             acc = None
             for ic in range(t.channels):
                 for fy in range(fh):
@@ -394,7 +465,7 @@ def chw_conv_geometry(o: Oracle, t: OTensor, fh, fw, pad_same=False):
     return wrap, amounts
 
 
-def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False):
+def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False, shared_moddown=False):
     """w[FH][FW][IC][OC] on a clean CHW-tiled tensor -> clean CHW-tiled tensor with the same channel blocks.  The
     plaintext of (tap, d, input ciphertext j, output ciphertext g) holds, on the valid output positions of block b,
     the weight from input channel j c_inner + (b + d) mod c_inner to output channel g c_inner + b (zero where either
@@ -419,10 +490,10 @@ def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False):
                 z[plane + b * cs] = float(w[fy, fx, ic, oc])
         coeffs[fy, fx, d, j, g] = o.encode_coeffs(z, pt_scale)
     ints = {"pt_coeffs": coeffs, "pt_scale": pt_scale}
-    return conv2d_chw_fixed(o, t, ints, oc_n, fh, fw, stride, pad_same), ints
+    return conv2d_chw_fixed(o, t, ints, oc_n, fh, fw, stride, pad_same, shared_moddown), ints
 
 
-def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same):
+def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, shared_moddown=False):
     ci = t.c_inner
     wrap, amounts = chw_conv_geometry(o, t, fh, fw, pad_same)
     if pad_same:
@@ -436,9 +507,17 @@ def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same
         if wrap:
             xs = [o.add(x, o.rot_right(x, wrap)) for x in xs]
         # the rotations do not depend on the output ciphertext: computed once
-        rotated = {(j, fy, fx, d): o.rot_left(xs[j], amounts[fy][fx][d])
-                   for j in range(per_in) for fy in range(fh) for fx in range(fw) for d in range(ci)}
+        shared = SharedModDown(o, xs) if shared_moddown else None
+        rotated = {} if shared_moddown else {
+            (j, fy, fx, d): o.rot_left(xs[j], amounts[fy][fx][d])
+            for j in range(per_in) for fy in range(fh) for fx in range(fw) for d in range(ci)}
         for g in range(per_out):
+            if shared is not None:
+                terms = [(j, amounts[fy][fx][d], ints["pt_coeffs"][fy, fx, d, j, g], (fy, fx, d, j, g))
+                         for fy in range(fh) for fx in range(fw) for d in range(ci) for j in range(per_in)]
+                acc = shared.total(terms, xs[0].scale * ints["pt_scale"])
+                outs.append(o.div_scalar(acc, o.max_scalar_div(acc, float("inf"))))
+                continue
             acc = None
             for fy in range(fh):
                 for fx in range(fw):

@@ -283,3 +283,46 @@ def test_layout_switches_round_trip():
         z = o.decode(o.decrypt(ct)).real
         z[layers.plane_slots(2, 2, 8, 2, 0)] = 0
         assert np.abs(z).max() <= 1e-3
+
+
+def test_shared_moddown_convolutions():
+    """The convolution with one division by P per output (SharedModDown): same plaintext result as Algorithm 1 to
+    1e-3, ciphertexts that differ from the term-by-term schedule by a few units per coefficient only (the rounding of
+    the division), and the halves of the key switch it is built from reproduce the whole.  HW-tiled (scalar and
+    masked) and CHW-tiled."""
+    o = Oracle(10, [50, 45, 45], 3, 50, seed=17)
+    o.keygen()
+    rng = np.random.default_rng(0)
+    d = np.stack([rng.integers(0, o.primes[i], o.N, dtype=np.uint64) for i in range(3)])
+    o.gen_rot_keys([3])
+    g = o.galois_elt(3)
+    acc_b, acc_a = o.key_switch_acc(d, g)
+    ks0, ks1 = o.key_switch(d, g)
+    assert np.array_equal(o.mod_down(acc_b, 3), ks0) and np.array_equal(o.mod_down(acc_a, 3), ks1)
+    # HW-tiled: 3 -> 4 channels, 3x3, SAME with the mask and VALID literal
+    x = synth.image(71, 3, 4, 4)[None]
+    w = synth.conv_weights(72, 3, 3, 3, 4)
+    t = layers.tensor_encrypt(o, x, 2.0 ** 40, 3, h_stride=6, offset=7)
+    o.gen_rot_keys(sorted(set(layers.rot_steps_conv(o, t, 3, 3, True)) | set(layers.rot_steps_conv(o, t, 3, 3))))
+    for kw, mode, ref in ((dict(pad_same=True), layers.CONV_MASKED, plain_net.conv2d(x, w, pad_same=True)),
+                          (dict(), layers.CONV_SCALAR, plain_net.conv2d(x, w))):
+        plain, _ = layers.conv2d(o, t, w, mode=mode, **kw)
+        lazy, _ = layers.conv2d(o, t, w, mode=mode, shared_moddown=True, **kw)
+        assert lazy.cts[0].limbs == 2 and (lazy.height, lazy.clean) == (plain.height, plain.clean)
+        assert np.abs(layers.tensor_decrypt(o, lazy) - ref).max() <= 1e-3
+        diff = 0
+        for a, b in zip(lazy.cts, plain.cts):
+            for i in range(2):
+                q = o.primes[i]
+                ca, cb = o.export(a), o.export(b)          # coefficient form
+                dd = (ca[:, i].astype(object) - cb[:, i].astype(object)) % q
+                diff = max(diff, max(min(int(v), q - int(v)) for v in dd.reshape(-1)))
+        assert 0 < diff <= 64            # not bit-identical, but only by the rounding of 8 x 3 divisions, rescaled
+    # CHW-tiled
+    xc = synth.image(73, 5, 4, 4)[None]
+    wc = synth.conv_weights(74, 3, 3, 5, 6)
+    tc = layers.tensor_encrypt_chw(o, xc, 2.0 ** 40, 3, c_inner=4, c_stride=64, h_stride=6, offset=7)
+    o.gen_rot_keys(layers.rot_steps_conv_chw(o, tc, 3, 3, True))
+    lazy, _ = layers.conv2d_chw(o, tc, wc, pad_same=True, shared_moddown=True)
+    assert (lazy.c_inner, lazy.clean, len(lazy.cts), lazy.cts[0].limbs) == (4, 1, 2, 2)
+    assert np.abs(layers.tensor_decrypt(o, lazy) - plain_net.conv2d(xc, wc, pad_same=True)).max() <= 1e-3
