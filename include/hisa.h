@@ -261,6 +261,12 @@ typedef struct {
     uint32_t pad_same;    /* 0: VALID.  1: SAME -- the input tensor must be clean and its layout must   */
                           /* leave fh/2 rows and fw/2 columns of zero slots around the plane           */
     uint32_t mode;        /* HISA_CONV_*                                                              */
+    uint32_t shared_moddown; /* 1: one division by P per output ciphertext instead of one per rotation: the   */
+                          /* rotated taps enter the sum as their key-switch accumulators on the l + K limbs   */
+                          /* (weights taken on those limbs), ModDown once at the end.  Same values up to the  */
+                          /* rounding of that division; ciphertext bits differ from the schedule with         */
+                          /* shared_moddown = 0.  Needs N >= 2^12, every prime below 2^50, dnum <= 8           */
+                          /* (HISA_ERR_ARG otherwise); hisa_conv2d_fixed takes the same arguments              */
 } hisa_conv_geom;
 
 /* HW-tiled conv2d (Algorithm 1; cross-correlation, no kernel flip): for every

@@ -191,7 +191,7 @@ def conv2d(o: Oracle, t: OTensor, w, stride=1, pad_same=False, mode=CONV_SCALAR,
 
 
 def conv2d_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, mode, shared_moddown=False):
-    """shared_moddown: the sum over (input channel, tap) goes through SharedModDown (scalar modes only)."""
+    """shared_moddown: the sum over (input channel, tap) goes through SharedModDown."""
     l = t.cts[0].limbs
     ph, pw = (fh // 2, fw // 2) if pad_same else (0, 0)
     if pad_same:
@@ -215,11 +215,15 @@ def conv2d_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, mo
         shared = SharedModDown(o, t.cts[b * t.channels:(b + 1) * t.channels]) if shared_moddown else None
         for oc in range(oc_n):
             if shared is not None:
-                assert mode != CONV_PLAIN
-                terms = [(ic, ((fy - ph) * t.h_stride + (fx - pw) * t.w_stride) % o.slots,
-                          int(ints["w_int"][fy, fx, ic, oc]), None)
-                         for ic in range(t.channels) for fy in range(fh) for fx in range(fw)]
-                acc = shared.total(terms, t.cts[0].scale * ints["w_scale"])
+                amount = lambda fy, fx: ((fy - ph) * t.h_stride + (fx - pw) * t.w_stride) % o.slots
+                if mode == CONV_PLAIN:
+                    terms = [(ic, amount(fy, fx), ints["pt_coeffs"][fy, fx, ic, oc], (fy, fx, ic, oc))
+                             for ic in range(t.channels) for fy in range(fh) for fx in range(fw)]
+                    acc = shared.total(terms, t.cts[0].scale * ints["pt_scale"])
+                else:
+                    terms = [(ic, amount(fy, fx), int(ints["w_int"][fy, fx, ic, oc]), None)
+                             for ic in range(t.channels) for fy in range(fh) for fx in range(fw)]
+                    acc = shared.total(terms, t.cts[0].scale * ints["w_scale"])
                 if mode == CONV_MASKED:
                     acc = o.mul_plain(acc, mask_pt)
                 outs.append(o.div_scalar(acc, o.max_scalar_div(acc, float("inf"))))

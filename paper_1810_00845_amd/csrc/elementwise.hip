@@ -340,8 +340,9 @@ hipError_t launch_automorph_ntt(const u64* in, u64 in_bs, u64* out, u64 out_bs, 
     return hipGetLastError();
 }
 
-// signed integer coefficients [n_pts][N] -> residues [n_pts][limbs][N] modulo q_0..q_{limbs-1}
-__global__ __launch_bounds__(NT) void reduce_i64_kernel(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs,
+// signed integer coefficients [n_pts][N] -> residues modulo primes[0..limbs-1] at out[p][0..limbs-1][N], the entries of
+// out being out_limbs limbs apart
+__global__ __launch_bounds__(NT) void reduce_i64_kernel(const PrimeConst* primes, const i64* coeffs, u64* out, int out_limbs,
                                                         int log_n) {
     const u64 n = (u64)1 << log_n;
     const PrimeConst pc = primes[blockIdx.y];
@@ -350,15 +351,20 @@ __global__ __launch_bounds__(NT) void reduce_i64_kernel(const PrimeConst* primes
     i64 v = coeffs[p * n + j];
     u64 mag = v < 0 ? (u64)0 - (u64)v : (u64)v;
     u64 r = barrett128(0, mag, pc.q, pc.r1, pc.r0);
-    out[(p * limbs + blockIdx.y) * n + j] = v < 0 ? negmod(r, pc.q) : r;
+    out[(p * out_limbs + blockIdx.y) * n + j] = v < 0 ? negmod(r, pc.q) : r;
 }
 
 hipError_t launch_reduce_i64(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs, int n_pts, int log_n,
                              hipStream_t st) {
+    return launch_reduce_i64(primes, coeffs, out, limbs, limbs, n_pts, log_n, st);
+}
+
+hipError_t launch_reduce_i64(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs, int out_limbs, int n_pts,
+                             int log_n, hipStream_t st) {
     DRY_RUN_RETURN();
-    if (n_pts <= 0) return hipSuccess;
+    if (n_pts <= 0 || limbs <= 0) return hipSuccess;
     dim3 grid((1u << log_n) / NT, limbs, n_pts);
     ProfScope prof__("reduce_i64_kernel", st);
-    hipLaunchKernelGGL(reduce_i64_kernel, grid, dim3(NT), 0, st, primes, coeffs, out, limbs, log_n);
+    hipLaunchKernelGGL(reduce_i64_kernel, grid, dim3(NT), 0, st, primes, coeffs, out, out_limbs, log_n);
     return hipGetLastError();
 }

@@ -1221,26 +1221,23 @@ static int key_switch_modup_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois
 }
 
 // IP, C, D.  `galois` is applied to the own-digit limbs read from d, to the addend, and (gather_ext) to the digits.
-static int key_switch_finish_fp(hisa_ctx* ctx, const FpExt& x, const u64* d, u64 d_bs, u64 galois, int gather_ext, size_t B,
-                                const SwitchKey& key, const u64* add, u64 add_bs, int add_polys, u64* out) {
+// C, D: acc [B][2][l + K][N] (NTT form) -> out[B][2][l][N] = ModDown(acc) (+ addend, gathered through add_galois if set)
+int moddown_add_fp(hisa_ctx* ctx, const u64* acc, size_t B, int l, const u64* add, u64 add_bs, int add_polys, u64 add_galois,
+                   u64* out) {
     const size_t n = ctx->N;
-    const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total, l = x.l;
-    const int ext_limbs = x.ext_limbs, log_n = (int)ctx->log_n;
+    const int K = (int)ctx->K, L = (int)ctx->L, total = (int)ctx->total, ext_limbs = l + K, log_n = (int)ctx->log_n;
     hipStream_t st = ctx->stream;
-    Temp acc(ctx, B * 2 * (size_t)ext_limbs * n * sizeof(u64));
     Temp y2(ctx, B * 2 * (size_t)K * n * sizeof(double));
-    if (!acc.ok() || !y2.ok()) return HISA_ERR_OOM;
+    if (!y2.ok()) return HISA_ERR_OOM;
     double *post_q, *post_p;
     TRY(fp_post_tables(ctx, l, &post_q, &post_p));
     const FpArgs base = fp_base(ctx);
-    HIP_TRY(ctx, launch_inner_product_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, key.data, total, d,
-                                         d_bs, galois, gather_ext, acc.u(), (u64)2 * ext_limbs * n, B, log_n, st));
     {   // C: batch entries are (ciphertext, b|a) pairs
         FpArgs a = base;
         FpTask tk = {};
         tk.period = K;
         for (int m = 0; m < K; m++) { tk.pos[m] = (int16_t)m; tk.prime[m] = (int16_t)(L + m); }
-        a.in = acc.u(); a.in_bs = (u64)ext_limbs * n; a.in_pos_shift = l; a.post = post_p;
+        a.in = acc; a.in_bs = (u64)ext_limbs * n; a.in_pos_shift = l; a.post = post_p;
         a.yout = y2.as<double>(); a.yout_bs = (u64)K * n;
         HIP_TRY(ctx, launch_ntt_fp(FP_INV_TO_Y, log_n, a, tk, B * 2, st));
     }
@@ -1250,12 +1247,24 @@ static int key_switch_finish_fp(hisa_ctx* ctx, const FpExt& x, const u64* d, u64
         tk.period = l;
         for (int i = 0; i < l; i++) { tk.pos[i] = (int16_t)i; tk.prime[i] = (int16_t)i; }
         a.y = y2.as<double>(); a.y_bs = (u64)K * n; a.y_pos0 = 0; a.conv_a = K; a.total = total; a.hat = ctx->moddown_tab->d_hat_f;
-        a.acc = acc.u(); a.acc_bs = (u64)ext_limbs * n; a.acc_pos_shift = 0; a.pinv_tab = ctx->d_pinv_f;
-        a.add = add; a.add_bs = add_bs; a.add_ps = (u64)l * n; a.add_div = 2; a.add_polys = add_polys; a.add_galois = galois;
+        a.acc = acc; a.acc_bs = (u64)ext_limbs * n; a.acc_pos_shift = 0; a.pinv_tab = ctx->d_pinv_f;
+        a.add = add; a.add_bs = add_bs; a.add_ps = (u64)l * n; a.add_div = 2; a.add_polys = add_polys; a.add_galois = add_galois;
         a.out = out; a.out_bs = (u64)l * n;
         HIP_TRY(ctx, launch_ntt_fp(FP_FWD_CONV_FINAL, log_n, a, tk, B * 2, st));
     }
     return HISA_OK;
+}
+
+static int key_switch_finish_fp(hisa_ctx* ctx, const FpExt& x, const u64* d, u64 d_bs, u64 galois, int gather_ext, size_t B,
+                                const SwitchKey& key, const u64* add, u64 add_bs, int add_polys, u64* out) {
+    const size_t n = ctx->N;
+    const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total, l = x.l;
+    const int ext_limbs = x.ext_limbs, log_n = (int)ctx->log_n;
+    Temp acc(ctx, B * 2 * (size_t)ext_limbs * n * sizeof(u64));
+    if (!acc.ok()) return HISA_ERR_OOM;
+    HIP_TRY(ctx, launch_inner_product_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, key.data, total, d,
+                                         d_bs, galois, gather_ext, acc.u(), (u64)2 * ext_limbs * n, B, log_n, ctx->stream));
+    return moddown_add_fp(ctx, acc.u(), B, l, add, add_bs, add_polys, galois, out);
 }
 
 // IP, C, D for n_steps rotations of the same B ciphertexts in one set of launches (entries rotation-major): a
@@ -1299,6 +1308,38 @@ static int key_switch_finish_steps_fp(hisa_ctx* ctx, const FpExt& x, const u64* 
         for (int s = 0; s < n_steps; s++) a.galois_tab[s] = (uint32_t)galois[s];
         a.out = out; a.out_bs = (u64)l * n;
         HIP_TRY(ctx, launch_ntt_fp(FP_FWD_CONV_FINAL, log_n, a, tk, E * 2, st));
+    }
+    return HISA_OK;
+}
+
+bool fused_key_switch_available(const hisa_ctx* ctx) { return ctx->tabs.fp_ok && ctx->dnum <= 8; }
+
+// The key-switch accumulators -- before the division by P -- of n_steps rotations of B ciphertexts (cts: [B][2][l][N],
+// ct_bs words apart): one decomposition + ModUp of c1, then per rotation the inner product with its key, gathered
+// through its automorphism.  acc: [n_steps][B][2][l + K][N].  Every amount must be a real rotation with its key present.
+int rotation_accumulators_fp(hisa_ctx* ctx, const u64* cts, u64 ct_bs, size_t B, int l, const int32_t* steps, int n_steps,
+                             u64* acc) {
+    if (!fused_key_switch_available(ctx)) return fail(ctx, HISA_ERR_ARG, "no fused key-switch path for these parameters");
+    const size_t n = ctx->N;
+    const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total, ext_limbs = l + K;
+    std::vector<u64> gs(n_steps);
+    for (int s = 0; s < n_steps; s++) {
+        gs[s] = galois_of(ctx, steps[s]);
+        if (gs[s] == 0) return fail(ctx, HISA_ERR_ARG, "rotation by a multiple of the slot count");
+        if (ctx->keys.find(gs[s]) == ctx->keys.end())
+            return fail(ctx, HISA_ERR_NO_KEY, "no rotation key for %d slots (galois element %llu)", steps[s], (unsigned long long)gs[s]);
+    }
+    FpExt x(ctx, B, l, K, alpha);
+    if (!x.ok()) return HISA_ERR_OOM;
+    const u64* c1 = cts + (size_t)l * n;
+    TRY(key_switch_modup_fp(ctx, c1, ct_bs, 0, B, x));
+    const u64 acc_bs = (u64)2 * ext_limbs * n;
+    for (int g0 = 0; g0 < n_steps; g0 += FP_MAX_STEPS) {
+        const int cnt = std::min(FP_MAX_STEPS, n_steps - g0);
+        IpSteps st = {};
+        for (int k = 0; k < cnt; k++) { st.key[k] = ctx->keys.find(gs[g0 + k])->second.data; st.galois[k] = (uint32_t)gs[g0 + k]; }
+        HIP_TRY(ctx, launch_inner_product_steps_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, st, cnt, total,
+                                                   c1, ct_bs, acc + (u64)g0 * B * acc_bs, acc_bs, B, (int)ctx->log_n, ctx->stream));
     }
     return HISA_OK;
 }

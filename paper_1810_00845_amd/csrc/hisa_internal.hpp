@@ -186,6 +186,12 @@ struct BatchIn {
 int gather_batch(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, BatchIn* bi);
 int check_batch_shape(hisa_ctx* ctx, const hisa_ct* const* cts, size_t n, uint32_t polys);
 PolyMap identity_map(int limbs);
+// pieces of the fused fp64 key switch for sums that are formed before the division by P (hisa_api.hip)
+bool fused_key_switch_available(const hisa_ctx* ctx);
+int rotation_accumulators_fp(hisa_ctx* ctx, const u64* cts, u64 ct_bs, size_t B, int l, const int32_t* steps, int n_steps,
+                             u64* acc);
+int moddown_add_fp(hisa_ctx* ctx, const u64* acc, size_t B, int l, const u64* add, u64 add_bs, int add_polys, u64 add_galois,
+                   u64* out);
 // exact integer nearest to the double v (ties away from zero), reduced modulo q
 u64 double_to_residue(double v, u64 q);
 
@@ -309,6 +315,9 @@ hipError_t launch_automorph_ntt(const u64* in, u64 in_bs, u64* out, u64 out_bs, 
                                 int log_n, hipStream_t st);
 hipError_t launch_reduce_i64(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs, int n_pts, int log_n,
                              hipStream_t st);
+// the same with the output entries out_limbs limbs apart (residues on a second list of primes go behind the first)
+hipError_t launch_reduce_i64(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs, int out_limbs, int n_pts,
+                             int log_n, hipStream_t st);
 
 // Fast base conversion (centred): for every batch entry and target,
 //   out[target] = ( sum_i y[src_pos0+i] * hat[i][prime(target)]  -  #{i : y_i > c_i/2} * D ) mod t

@@ -23,8 +23,16 @@ struct MacArgs {
     u64 ct_words;                   // 2*l*N
     const u64* w;                   // scalar: residues [T][OC][l]; plain: plaintexts, NTT form
     u64 w_stride_t, w_stride_oc;    // plain: strides in units of l*N words
-    u64* out;                       // [batch*OC][2][l][N]
+    u64* out;                       // [batch*OC][polys][l][N]
+    // the fp64 kernels only:
+    int polys;                      // polynomials per input / output entry: 2 (0 is read as 2) or 1
+    int lq, gap;                    // limb i uses prime i for i < lq and prime i + gap beyond (the special primes of a
+                                    // key-switch accumulator's l + K limbs); lq = 0: prime i throughout
+    u64 w_words;                    // plain: words per plaintext in memory (0: l * N)
 };
+
+__device__ __forceinline__ int mac_prime(const MacArgs& g, int limb) { return (g.lq && limb >= g.lq) ? limb + g.gap : limb; }
+static inline int mac_polys(const MacArgs& g) { return g.polys == 1 ? 1 : 2; }
 
 // out[b][oc] = sum over T = (tap, ic) of  w[T][oc] * x[tap][b][ic]   (integer weights, one per limb)
 __global__ __launch_bounds__(NT) void scalar_mac_kernel(const PrimeConst* primes, MacArgs g, int log_n) {
@@ -69,7 +77,7 @@ __global__ __launch_bounds__(NT) void scalar_mac_fp_kernel(const FpPrime* fprime
     const int pl = blockIdx.y, limb = pl % g.l;
     const int ocblocks = (g.OC + OCF - 1) / OCF;
     const int b = blockIdx.z / ocblocks, oc0 = (blockIdx.z % ocblocks) * OCF;
-    const mac_cdouble_ptr fp = (mac_cdouble_ptr)(unsigned long long)&fprimes[limb].p;
+    const mac_cdouble_ptr fp = (mac_cdouble_ptr)(unsigned long long)&fprimes[mac_prime(g, limb)].p;
     const double p = fp[0], pinv = fp[1];
     const bool full = oc0 + OCF <= g.OC;     // all OCF outputs exist (uniform over the workgroup)
     double acc[OCF];
@@ -246,7 +254,7 @@ __global__ __launch_bounds__(256) void scalar_mac_mfma_kernel(const FpPrime* fpr
 
     // sum_s D_s 256^s mod p: three diagonals at a time are combined exactly in a double (below 2^48), then five
     // modular products with 2^(24 g) mod p
-    const mac_cdouble_ptr fp = (mac_cdouble_ptr)(unsigned long long)&fprimes[limb].p;
+    const mac_cdouble_ptr fp = (mac_cdouble_ptr)(unsigned long long)&fprimes[mac_prime(g, limb)].p;
     const double p = fp[0], pinv = fp[1];
     const mac_cdouble_ptr cg = (mac_cdouble_ptr)(unsigned long long)(c3 + limb * 5);
 #pragma unroll
@@ -279,27 +287,28 @@ __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes
     const int limb = blockIdx.y;
     const int ocblocks = (g.OC + OCP - 1) / OCP;
     const int b = blockIdx.z / ocblocks, oc0 = (blockIdx.z % ocblocks) * OCP;
-    const mac_cdouble_ptr fp = (mac_cdouble_ptr)(unsigned long long)&fprimes[limb].p;
+    const mac_cdouble_ptr fp = (mac_cdouble_ptr)(unsigned long long)&fprimes[mac_prime(g, limb)].p;
     const double p = fp[0], pinv = fp[1];
-    const u64 ln = (u64)g.l * n;
+    const u64 ln = (u64)g.l * n, wl = g.w_words ? g.w_words : ln;
+    const bool two = g.polys != 1;      // one-polynomial entries: the second accumulator idles
     double a0[OCP], a1[OCP];
 #pragma unroll
     for (int o = 0; o < OCP; o++) a0[o] = a1[o] = 0.0;
     int pending = 0;
     for (int t = 0; t < g.n_taps; t++) {
         const u64* x = g.tap_base[t] + (u64)b * g.IC * g.ct_words + (u64)limb * n + j;
-        const u64* w = g.w + ((u64)t * g.IC * g.w_stride_t + (u64)oc0 * g.w_stride_oc) * ln + (u64)limb * n + j;
+        const u64* w = g.w + ((u64)t * g.IC * g.w_stride_t + (u64)oc0 * g.w_stride_oc) * wl + (u64)limb * n + j;
         for (int ic0 = 0; ic0 < g.IC; ic0 += ICP) {
             u64 xb[ICP], xa[ICP], wv[ICP][OCP];
 #pragma unroll
             for (int u = 0; u < ICP; u++) {
                 const int ic = ic0 + u < g.IC ? ic0 + u : g.IC - 1;
                 xb[u] = x[(u64)ic * g.ct_words];
-                xa[u] = x[(u64)ic * g.ct_words + ln];
+                xa[u] = two ? x[(u64)ic * g.ct_words + ln] : 0;
 #pragma unroll
                 for (int o = 0; o < OCP; o++) {
                     const int oo = oc0 + o < g.OC ? o : 0;
-                    wv[u][o] = w[((u64)ic * g.w_stride_t + (u64)oo * g.w_stride_oc) * ln];
+                    wv[u][o] = w[((u64)ic * g.w_stride_t + (u64)oo * g.w_stride_oc) * wl];
                 }
             }
 #pragma unroll
@@ -327,7 +336,7 @@ __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes
         if (oc0 + o < g.OC) {
             u64* dst = g.out + ((u64)b * g.OC + oc0 + o) * g.ct_words + (u64)limb * n + j;
             dst[0] = fp_canonical(a0[o], p, pinv);
-            dst[ln] = fp_canonical(a1[o], p, pinv);
+            if (two) dst[ln] = fp_canonical(a1[o], p, pinv);
         }
     }
 }
@@ -352,7 +361,7 @@ static hipError_t launch_scalar_mac_fp(const FpPrime* fprimes, const MacArgs& g,
     count_mac(g, batch, false);
     DRY_RUN_RETURN();
     if (!fprimes || !wf || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS) return hipErrorInvalidValue;
-    dim3 grid((1u << log_n) / NT, 2 * g.l, batch * ((g.OC + OCF - 1) / OCF));
+    dim3 grid((1u << log_n) / NT, mac_polys(g) * g.l, batch * ((g.OC + OCF - 1) / OCF));
     ProfScope prof__("scalar_mac_fp_kernel", st);
     hipLaunchKernelGGL(scalar_mac_fp_kernel, grid, dim3(NT), 0, st, fprimes, g, wf, log_n);
     return hipGetLastError();
@@ -374,7 +383,7 @@ static hipError_t launch_scalar_mac_mfma(const FpPrime* fprimes, const MacArgs& 
     if (!fprimes || !wd || !c3 || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || K != g.n_taps * g.IC || K_pad % MT_K ||
         K_pad < K || OC_pad % MT_OC || OC_pad < g.OC || log_n < 6 || da < 1 || da > MAC_DIGITS || (db != 6 && db != 7))
         return hipErrorInvalidValue;
-    dim3 grid((1u << log_n) / MT_E, 2 * g.l, batch * (OC_pad / MT_OC));
+    dim3 grid((1u << log_n) / MT_E, mac_polys(g) * g.l, batch * (OC_pad / MT_OC));
     ProfScope prof__("scalar_mac_mfma_kernel", st);
     if (da < 3) da = 3;
 #define MFMA_CASE(A_, B_) if (da == A_ && db == B_) return launch_mfma_one<A_, B_>(fprimes, g, wd, K, K_pad, OC_pad, c3, grid, log_n, st)
@@ -590,8 +599,25 @@ static int encode_sparse_batch(hisa_ctx* ctx, const std::vector<uint32_t>& slots
 // of set b) and zero elsewhere into NTT-form plaintexts out[n_pts][limbs][N] (device): the same numbers as
 // encode_sparse_batch up to the rounding order of the fp64 sums, at nb instead of (number of slots) terms per
 // coefficient.
+// Residues of n_pts signed coefficient vectors (device, [n_pts][N]) in NTT form: on q_0..q_{limbs-1}, and with `ext`
+// also on the K special primes behind them (out[n_pts][limbs (+K)][N]: the limbs of a key-switch accumulator).
+static int coeffs_to_ntt(hisa_ctx* ctx, const i64* co, size_t n_pts, int limbs, bool ext, u64* out) {
+    const size_t n = ctx->N;
+    const int K = ext ? (int)ctx->K : 0, tot = limbs + K;
+    HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co, out, limbs, tot, (int)n_pts, (int)ctx->log_n, ctx->stream));
+    if (ext)
+        HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes + ctx->L, co, out + (size_t)limbs * n, K, tot, (int)n_pts, (int)ctx->log_n,
+                                       ctx->stream));
+    PolyMap pm = identity_map(tot);
+    for (int m = 0; m < K; m++) pm.prime_of[limbs + m] = (int16_t)(ctx->L + m);
+    for (size_t q0 = 0; q0 < n_pts; q0 += 4096)
+        HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, out + q0 * tot * n, (u64)tot * n,
+                                (int)(std::min<size_t>(4096, n_pts - q0) * tot), pm, ctx->stream));
+    return HISA_OK;
+}
+
 static int encode_piecewise_batch(hisa_ctx* ctx, const std::vector<std::vector<uint32_t>>& sets, const double* values,
-                                  size_t n_pts, double scale, int limbs, u64* out) {
+                                  size_t n_pts, double scale, int limbs, u64* out, bool ext = false) {
     const size_t n = ctx->N, nb = sets.size();
     std::vector<uint32_t> g;
     std::vector<int> begin(1, 0);
@@ -621,28 +647,21 @@ static int encode_piecewise_batch(hisa_ctx* ctx, const std::vector<std::vector<u
         const size_t cnt = std::min(chunk, n_pts - p0);
         HIP_TRY(ctx, launch_encode_combine(basis.as<double>(), (int)nb, dv.as<double>() + p0 * nb, (int)cnt,
                                            2.0 * scale / (double)n, co.as<i64>(), (int)ctx->log_n, ctx->stream));
-        HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>(), out + p0 * limbs * n, limbs, (int)cnt, (int)ctx->log_n,
-                                       ctx->stream));
-        for (size_t q0 = 0; q0 < cnt; q0 += 4096)
-            HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, out + (p0 + q0) * limbs * n, (u64)limbs * n,
-                                    (int)(std::min<size_t>(4096, cnt - q0) * limbs), identity_map(limbs), ctx->stream));
+        TRY(coeffs_to_ntt(ctx, co.as<i64>(), cnt, limbs, ext, out + p0 * (limbs + (ext ? ctx->K : 0)) * n));
     }
     return HISA_OK;
 }
 
 // host signed coefficients [n_pts][N] -> NTT-form plaintexts out[n_pts][limbs][N]
-static int coeffs_to_plain_batch(hisa_ctx* ctx, const int64_t* host, size_t n_pts, int limbs, u64* out) {
-    const size_t n = ctx->N;
+static int coeffs_to_plain_batch(hisa_ctx* ctx, const int64_t* host, size_t n_pts, int limbs, u64* out, bool ext = false) {
+    const size_t n = ctx->N, tot = limbs + (ext ? ctx->K : 0);
     for (size_t p0 = 0; p0 < n_pts; p0 += 4096) {
         const size_t cnt = std::min<size_t>(4096, n_pts - p0);
         Temp co(ctx, cnt * n * sizeof(i64));
         if (!co.ok()) return HISA_ERR_OOM;
         HIP_TRY(ctx, hipMemcpyAsync(co.blk->ptr, host + p0 * n, cnt * n * sizeof(i64), hipMemcpyHostToDevice, ctx->stream));
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-        HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>(), out + p0 * limbs * n, limbs, (int)cnt, (int)ctx->log_n,
-                                       ctx->stream));
-        HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, out + p0 * limbs * n, (u64)limbs * n, (int)(cnt * limbs),
-                                identity_map(limbs), ctx->stream));
+        TRY(coeffs_to_ntt(ctx, co.as<i64>(), cnt, limbs, ext, out + p0 * tot * n));
     }
     return HISA_OK;
 }
@@ -701,6 +720,7 @@ struct DevWeights {
     size_t K, OC, K_pad, OC_pad;
     int da = MAC_DIGITS;   // signed base-256 digits the largest weight needs
     bool fp, mfma;
+    std::vector<int> primes;   // prime of every limb position (empty: position i is prime i)
     Temp res, resf, digits, c3;
     DevWeights(hisa_ctx* ctx, size_t K_, size_t OC_, uint32_t l)
         : K(K_), OC(OC_), K_pad((K_ + MT_K - 1) / MT_K * MT_K), OC_pad((OC_ + MT_OC - 1) / MT_OC * MT_OC),
@@ -717,7 +737,7 @@ static int upload_weight_residues(hisa_ctx* ctx, const int64_t* w_int, uint32_t 
     std::vector<int8_t> dig(dst.mfma ? (size_t)l * MAC_DIGITS * dst.OC_pad * dst.K_pad : 0, 0);
     u64 used = 0;   // OR of all digit words: its highest non-zero byte is the last digit in use
     for (uint32_t k = 0; k < l; k++) {
-        const u64 q = ctx->mod[k];
+        const u64 q = ctx->mod[dst.primes.empty() ? k : (uint32_t)dst.primes[k]];
         for (size_t oc = 0; oc < dst.OC; oc++) {       // digit rows are contiguous in the contraction index
             for (size_t kk = 0; kk < dst.K; kk++) {
                 const size_t i = kk * dst.OC + oc;
@@ -855,44 +875,106 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
     return HISA_OK;
 }
 
-extern "C" int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* w_int, double w_scale,
-                                 const int64_t* pt_coeffs, double pt_scale, uint32_t OC, const hisa_conv_geom* geom,
-                                 hisa_tensor* out) {
-    TRY(check_tensor(ctx, in));
-    if (!out || !out->cts || OC == 0) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
-    ConvPlan plan;
-    TRY(conv_plan(ctx, in, geom, &plan));
-    const uint32_t l = in->cts[0]->limbs, IC = (uint32_t)t_per(in), OCm = (OC + t_ci(in) - 1) / t_ci(in);
-    const size_t T = plan.steps.size() * IC, n = ctx->N;
-    if (geom->mode == HISA_CONV_PLAIN) {
-        if (!pt_coeffs) return fail(ctx, HISA_ERR_ARG, "PLAIN mode needs plaintext coefficients");
-        Temp pts(ctx, T * OCm * l * n * sizeof(u64));
-        if (!pts.ok()) return HISA_ERR_OOM;
-        TRY(coeffs_to_plain_batch(ctx, pt_coeffs, T * OCm, (int)l, pts.u()));
-        return conv_run(ctx, in, geom, plan, OC, nullptr, 1.0, pts.u(), pt_scale, out);
-    }
-    if (!w_int) return fail(ctx, HISA_ERR_ARG, "null weights");
-    DevWeights dw(ctx, T, OC, l);
-    if (!dw.ok()) return HISA_ERR_OOM;
-    TRY(upload_weight_residues(ctx, w_int, l, dw));
-    if (geom->mode == HISA_CONV_MASKED) {
-        if (!pt_coeffs) return fail(ctx, HISA_ERR_ARG, "MASKED mode needs the mask plaintext");
-        Temp mask(ctx, (size_t)l * n * sizeof(u64));
-        if (!mask.ok()) return HISA_ERR_OOM;
-        TRY(coeffs_to_plain_batch(ctx, pt_coeffs, 1, (int)l, mask.u()));
-        return conv_run(ctx, in, geom, plan, OC, &dw, w_scale, mask.u(), pt_scale, out);
-    }
-    return conv_run(ctx, in, geom, plan, OC, &dw, w_scale, nullptr, 1.0, out);
-}
-
 // Everything a convolution needs besides its input: weights in the forms the kernels read, the mask or the per-tap
 // plaintexts, and the scales.  Built from float weights per call by hisa_conv2d, or once by hisa_conv2d_prepare.
+// With `shared` (one division by P per output ciphertext, conv_run_shared) the terms of the rotated taps and of the
+// unrotated ones are kept apart, the former on the l + K limbs of the key-switch accumulators: dw / pts hold the
+// rotated taps' weights ([T_rot][OC], plaintexts with l + K limbs), dw_zero / pts_zero the others (l limbs); the mask
+// of MASKED mode is then in `mask`.
 struct ConvWeights {
     DevWeights* dw = nullptr;   // SCALAR / MASKED
     Temp* pts = nullptr;        // MASKED: the mask [l][N]; PLAIN: [T][OC][l][N]
     double w_scale = 1.0, pt_scale = 1.0;
-    ~ConvWeights() { delete dw; delete pts; }
+    bool shared = false;
+    DevWeights* dw_zero = nullptr;
+    Temp* pts_zero = nullptr;
+    Temp* mask = nullptr;
+    ~ConvWeights() { delete dw; delete pts; delete dw_zero; delete pts_zero; delete mask; }
 };
+
+// taps (entries of plan.steps) with and without a rotation
+struct TapSplit { std::vector<int> rot, zero; };
+static TapSplit split_taps(const ConvPlan& plan) {
+    TapSplit t;
+    for (size_t k = 0; k < plan.steps.size(); k++) (plan.steps[k] ? t.rot : t.zero).push_back((int)k);
+    return t;
+}
+
+// rows (tap * rows_per_tap + r) of a [taps][rows_per_tap][items] array, for the listed taps
+template <class T>
+static std::vector<T> pick_taps(const T* src, const std::vector<int>& taps, size_t rows_per_tap, size_t items) {
+    std::vector<T> out(taps.size() * rows_per_tap * items);
+    for (size_t k = 0; k < taps.size(); k++)
+        memcpy(out.data() + k * rows_per_tap * items, src + (size_t)taps[k] * rows_per_tap * items, rows_per_tap * items * sizeof(T));
+    return out;
+}
+
+// Does this convolution take the shared-ModDown schedule?  Asked for and impossible is an error.
+static int conv_wants_shared(hisa_ctx* ctx, const hisa_conv_geom* g, const ConvPlan& plan, bool* shared) {
+    *shared = false;
+    if (!g->shared_moddown) return HISA_OK;
+    if (!fused_key_switch_available(ctx))
+        return fail(ctx, HISA_ERR_ARG, "shared_moddown needs the fused key-switch path (N >= 2^12, every prime below 2^50, dnum <= 8)");
+    if (t_analysis) return HISA_OK;      // dry runs count the term-by-term schedule
+    for (int32_t st : plan.steps)
+        if (st) *shared = true;
+    return HISA_OK;
+}
+
+static std::vector<int> ext_prime_list(const hisa_ctx* ctx, uint32_t l) {
+    std::vector<int> p;
+    for (uint32_t i = 0; i < l; i++) p.push_back((int)i);
+    for (uint32_t m = 0; m < ctx->K; m++) p.push_back((int)(ctx->L + m));
+    return p;
+}
+
+// scalar weights w_int[T][OC] -> device forms; shared: split by tap, the rotated ones on the l + K limbs
+static int build_scalar_weights(hisa_ctx* ctx, const int64_t* w_int, const ConvPlan& plan, uint32_t ICm, uint32_t OC, uint32_t l,
+                                bool shared, ConvWeights& cw) {
+    cw.shared = shared;
+    if (!shared) {
+        cw.dw = new DevWeights(ctx, plan.steps.size() * ICm, OC, l);
+        if (!cw.dw->ok()) return HISA_ERR_OOM;
+        return upload_weight_residues(ctx, w_int, l, *cw.dw);
+    }
+    const TapSplit ts = split_taps(plan);
+    const std::vector<int64_t> wr = pick_taps(w_int, ts.rot, ICm, OC), wz = pick_taps(w_int, ts.zero, ICm, OC);
+    cw.dw = new DevWeights(ctx, ts.rot.size() * ICm, OC, l + ctx->K);
+    if (!cw.dw->ok()) return HISA_ERR_OOM;
+    cw.dw->primes = ext_prime_list(ctx, l);
+    TRY(upload_weight_residues(ctx, wr.data(), l + ctx->K, *cw.dw));
+    if (!ts.zero.empty()) {
+        cw.dw_zero = new DevWeights(ctx, ts.zero.size() * ICm, OC, l);
+        if (!cw.dw_zero->ok()) return HISA_ERR_OOM;
+        TRY(upload_weight_residues(ctx, wz.data(), l, *cw.dw_zero));
+    }
+    return HISA_OK;
+}
+
+// piecewise-constant plaintext weights vals[T][OCm][sets.size()] -> NTT-form plaintexts; shared: split as above
+static int build_plain_weights(hisa_ctx* ctx, const std::vector<std::vector<uint32_t>>& sets, const double* vals,
+                               const ConvPlan& plan, uint32_t ICm, uint32_t OCm, uint32_t l, double scale, bool shared,
+                               ConvWeights& cw) {
+    const size_t n = ctx->N, nb = sets.size(), T = plan.steps.size() * ICm;
+    cw.shared = shared;
+    cw.pt_scale = scale;
+    if (!shared) {
+        cw.pts = new Temp(ctx, T * OCm * l * n * sizeof(u64));
+        if (!cw.pts->ok()) return HISA_ERR_OOM;
+        return encode_piecewise_batch(ctx, sets, vals, T * OCm, scale, (int)l, cw.pts->u());
+    }
+    const TapSplit ts = split_taps(plan);
+    const std::vector<double> vr = pick_taps(vals, ts.rot, ICm, OCm * nb), vz = pick_taps(vals, ts.zero, ICm, OCm * nb);
+    cw.pts = new Temp(ctx, ts.rot.size() * ICm * OCm * (l + ctx->K) * n * sizeof(u64));
+    if (!cw.pts->ok()) return HISA_ERR_OOM;
+    TRY(encode_piecewise_batch(ctx, sets, vr.data(), ts.rot.size() * ICm * OCm, scale, (int)l, cw.pts->u(), true));
+    if (!ts.zero.empty()) {
+        cw.pts_zero = new Temp(ctx, ts.zero.size() * ICm * OCm * l * n * sizeof(u64));
+        if (!cw.pts_zero->ok()) return HISA_ERR_OOM;
+        TRY(encode_piecewise_batch(ctx, sets, vz.data(), ts.zero.size() * ICm * OCm, scale, (int)l, cw.pts_zero->u()));
+    }
+    return HISA_OK;
+}
 
 static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t OC, const hisa_conv_geom* geom,
                       const ConvPlan& plan, ConvWeights& cw) {
@@ -900,6 +982,8 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
     const size_t taps = plan.steps.size(), T = taps * IC, n = ctx->N;
     const double q_last = (double)ctx->mod[l - 1];
+    bool shared;
+    TRY(conv_wants_shared(ctx, geom, plan, &shared));
     const std::vector<uint32_t> vslots = plane_slots(plan.out_h, plan.out_w, in->h_stride * geom->stride,
                                                      in->w_stride * geom->stride, in->offset);
     if (t_ci(in) > 1) {
@@ -910,9 +994,6 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
         std::vector<std::vector<uint32_t>> sets(ci);
         for (uint32_t b = 0; b < ci; b++)
             for (uint32_t v : vslots) sets[b].push_back(v + b * in->c_stride);
-        cw.pts = new Temp(ctx, n_pts * l * n * sizeof(u64));
-        if (!cw.pts->ok()) return HISA_ERR_OOM;
-        cw.pt_scale = q_last;
         std::vector<double> vals(n_pts * ci, 0.0);   // one value per (plaintext, block)
         for (size_t idx = 0; idx < n_pts; idx++) {
             const size_t g_ = idx % per_out, j = (idx / per_out) % per_in, td = idx / per_out / per_in;
@@ -922,16 +1003,10 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
                 if (ic < IC && oc < OC) vals[idx * ci + b] = w[(tap * IC + ic) * OC + oc];
             }
         }
-        return encode_piecewise_batch(ctx, sets, vals.data(), n_pts, q_last, (int)l, cw.pts->u());
+        return build_plain_weights(ctx, sets, vals.data(), plan, per_in, per_out, l, q_last, shared, cw);
     }
-    if (geom->mode == HISA_CONV_PLAIN) {
-        // plaintext (tap, ic, oc) = weight on every valid output position, zero elsewhere, at scale q_last
-        cw.pts = new Temp(ctx, T * OC * l * n * sizeof(u64));
-        if (!cw.pts->ok()) return HISA_ERR_OOM;
-        TRY(encode_piecewise_batch(ctx, {vslots}, w, T * OC, q_last, (int)l, cw.pts->u()));
-        cw.pt_scale = q_last;
-        return HISA_OK;
-    }
+    if (geom->mode == HISA_CONV_PLAIN)   // plaintext (tap, ic, oc) = weight on every valid output position, zero elsewhere
+        return build_plain_weights(ctx, {vslots}, w, plan, IC, OC, l, q_last, shared, cw);
     cw.w_scale = geom->mode == HISA_CONV_MASKED ? q_last / HISA_MASK_SCALE : q_last;
     std::vector<int64_t> w_int(T * OC);
     for (size_t i = 0; i < T * OC; i++) {
@@ -939,17 +1014,198 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
         if (!(fabs(v) < 9.2e18)) return fail(ctx, HISA_ERR_ARG, "weight %g does not fit the fixed-point range", w[i]);
         w_int[i] = (int64_t)round(v);
     }
-    cw.dw = new DevWeights(ctx, T, OC, l);
-    if (!cw.dw->ok()) return HISA_ERR_OOM;
-    TRY(upload_weight_residues(ctx, w_int.data(), l, *cw.dw));
+    TRY(build_scalar_weights(ctx, w_int.data(), plan, IC, OC, l, shared, cw));
     if (geom->mode == HISA_CONV_MASKED) {
-        cw.pts = new Temp(ctx, (size_t)l * n * sizeof(u64));
-        if (!cw.pts->ok()) return HISA_ERR_OOM;
+        cw.mask = new Temp(ctx, (size_t)l * n * sizeof(u64));
+        if (!cw.mask->ok()) return HISA_ERR_OOM;
         std::vector<double> ones(vslots.size(), 1.0);
-        TRY(encode_sparse_batch(ctx, vslots, ones.data(), 1, HISA_MASK_SCALE, (int)l, cw.pts->u()));
+        TRY(encode_sparse_batch(ctx, vslots, ones.data(), 1, HISA_MASK_SCALE, (int)l, cw.mask->u()));
         cw.pt_scale = HISA_MASK_SCALE;
     }
     return HISA_OK;
+}
+
+// the same from fixed-point inputs (what the oracle derived): w_int[T][OC], or plaintext coefficients
+static int conv_build_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* w_int, double w_scale, const int64_t* pt_coeffs,
+                            double pt_scale, uint32_t OC, const hisa_conv_geom* geom, const ConvPlan& plan, ConvWeights& cw) {
+    const uint32_t l = in->cts[0]->limbs, ICm = (uint32_t)t_per(in), OCm = (OC + t_ci(in) - 1) / t_ci(in);
+    const size_t n = ctx->N, T = plan.steps.size() * ICm;
+    bool shared;
+    TRY(conv_wants_shared(ctx, geom, plan, &shared));
+    cw.w_scale = w_scale; cw.pt_scale = pt_scale; cw.shared = shared;
+    if (geom->mode == HISA_CONV_PLAIN) {
+        if (!pt_coeffs) return fail(ctx, HISA_ERR_ARG, "PLAIN mode needs plaintext coefficients");
+        cw.w_scale = 1.0;
+        if (!shared) {
+            cw.pts = new Temp(ctx, T * OCm * l * n * sizeof(u64));
+            if (!cw.pts->ok()) return HISA_ERR_OOM;
+            return coeffs_to_plain_batch(ctx, pt_coeffs, T * OCm, (int)l, cw.pts->u());
+        }
+        const TapSplit ts = split_taps(plan);
+        const std::vector<int64_t> cr = pick_taps(pt_coeffs, ts.rot, ICm, OCm * n), cz = pick_taps(pt_coeffs, ts.zero, ICm, OCm * n);
+        cw.pts = new Temp(ctx, ts.rot.size() * ICm * OCm * (l + ctx->K) * n * sizeof(u64));
+        if (!cw.pts->ok()) return HISA_ERR_OOM;
+        TRY(coeffs_to_plain_batch(ctx, cr.data(), ts.rot.size() * ICm * OCm, (int)l, cw.pts->u(), true));
+        if (!ts.zero.empty()) {
+            cw.pts_zero = new Temp(ctx, ts.zero.size() * ICm * OCm * l * n * sizeof(u64));
+            if (!cw.pts_zero->ok()) return HISA_ERR_OOM;
+            TRY(coeffs_to_plain_batch(ctx, cz.data(), ts.zero.size() * ICm * OCm, (int)l, cw.pts_zero->u()));
+        }
+        return HISA_OK;
+    }
+    if (!w_int) return fail(ctx, HISA_ERR_ARG, "null weights");
+    TRY(build_scalar_weights(ctx, w_int, plan, ICm, OC, l, shared, cw));
+    if (geom->mode == HISA_CONV_MASKED) {
+        if (!pt_coeffs) return fail(ctx, HISA_ERR_ARG, "MASKED mode needs the mask plaintext");
+        cw.mask = new Temp(ctx, (size_t)l * n * sizeof(u64));
+        if (!cw.mask->ok()) return HISA_ERR_OOM;
+        TRY(coeffs_to_plain_batch(ctx, pt_coeffs, 1, (int)l, cw.mask->u()));
+    } else {
+        cw.pt_scale = 1.0;
+    }
+    return HISA_OK;
+}
+
+// One multiply-accumulate launch of the shared-ModDown convolution: scalar weights (dw) or plaintexts (pts).
+// entry_polys / entry_limbs describe the entries read and written; q_only: weights' first l limbs only (dw built on the
+// l + K limbs of the accumulators, or plaintexts stored with pt_limbs limbs).
+static hipError_t shared_mac(hisa_ctx* ctx, MacArgs ma, const DevWeights* dw, const u64* pts, uint32_t pt_limbs, int batch) {
+    if (pts) {
+        ma.w = pts; ma.w_stride_t = (u64)ma.OC; ma.w_stride_oc = 1; ma.w_words = (u64)pt_limbs * ctx->N;
+        return launch_plain_mac_fp(ctx->tabs.fprimes, ma, batch, (int)ctx->log_n, ctx->stream);
+    }
+    if (dw->mfma) {
+        u64 qmax = 0;
+        for (int k = 0; k < ma.l; k++) qmax = std::max(qmax, ctx->mod[(ma.lq && k >= ma.lq) ? k + ma.gap : k]);
+        const int db = qmax < ((u64)1 << 46) ? 6 : 7;
+        return launch_scalar_mac_mfma(ctx->tabs.fprimes, ma, (const int8_t*)dw->digits.blk->ptr, (int)dw->K, (int)dw->K_pad,
+                                      (int)dw->OC_pad, dw->c3.as<double>(), dw->da, db, batch, (int)ctx->log_n, ctx->stream);
+    }
+    return launch_scalar_mac_fp(ctx->tabs.fprimes, ma, dw->resf.as<double>(), batch, (int)ctx->log_n, ctx->stream);
+}
+
+// The convolution with ONE division by P per output ciphertext (the rotations of a convolution are only ever used
+// inside its sums): the inputs' c1 is decomposed and raised once, every rotated tap contributes its key-switch
+// accumulators -- on l + K limbs, before the division -- times its weight taken on those limbs (E), and sigma(c0)
+// times the weight on the l limbs (Q0); unrotated taps contribute weight * (c0, c1) (Z); out = ModDown(E) + (Z0 + Q0,
+// Z1), then the mask (MASKED) and the divScalar as usual.  Same result as conv_run up to the rounding of the division.
+static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
+                           const ConvWeights& cw, hisa_tensor* out) {
+    const uint32_t B = in->batch, ci = t_ci(in), IC = (uint32_t)t_per(in), OCm = (OC + ci - 1) / ci, l = in->cts[0]->limbs;
+    const uint32_t K = ctx->K, le = l + K;
+    const size_t nct = (size_t)B * IC, n = ctx->N, n_out = (size_t)B * OCm;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
+    const bool plain = g->mode == HISA_CONV_PLAIN;
+    const TapSplit ts = split_taps(plan);
+    const size_t S = ts.rot.size();
+    if (S == 0 || S > MAX_TAPS || ts.zero.size() > MAX_TAPS) return fail(ctx, HISA_ERR_ARG, "bad tap count");
+    std::vector<hisa_ct*> wrapped;
+    hisa_ct* const* src = in->cts;
+    if (plan.wrap > 0) {
+        wrapped.assign(nct, nullptr);
+        TRY(hisa_rot_left_batch(ctx, (const hisa_ct* const*)in->cts, nct, norm_step(ctx, -plan.wrap), wrapped.data()));
+        BatchIn orig;
+        int rcw = gather_batch(ctx, (const hisa_ct* const*)in->cts, nct, &orig);
+        if (rcw == HISA_OK) {
+            const u64 words = ct_words(ctx, 2, l);
+            hipError_t e = launch_addsub(ctx->d_primes, wrapped[0]->data, orig.base, wrapped[0]->data, OP_ADD, (int)l, 2, 2, nct, words,
+                                         orig.stride, words, (int)ctx->log_n, ctx->stream);
+            if (e != hipSuccess) rcw = fail(ctx, HISA_ERR_HIP, "conv wrap: %s", hipGetErrorString(e));
+        }
+        dev_release(ctx, orig.tmp);
+        if (rcw != HISA_OK) { free_handles(ctx, wrapped); return rcw; }
+        src = wrapped.data();
+    }
+    BatchIn bi;
+    int rc = gather_batch(ctx, (const hisa_ct* const*)src, nct, &bi);
+    const u64 acc_bs = (u64)2 * le * n, lw = (u64)l * n;
+    Temp acc(ctx, S * nct * acc_bs * sizeof(u64));      // [S][nct][2][l + K][N]
+    Temp r0(ctx, S * nct * lw * sizeof(u64));           // sigma(c0): [S][nct][l][N]
+    Temp E(ctx, n_out * acc_bs * sizeof(u64)), Q0(ctx, n_out * lw * sizeof(u64)), Z(ctx, n_out * 2 * lw * sizeof(u64));
+    std::vector<hisa_ct*> outs(n_out, nullptr);
+    if (rc == HISA_OK && !(acc.ok() && r0.ok() && E.ok() && Q0.ok() && Z.ok())) rc = HISA_ERR_OOM;
+    std::vector<int32_t> rot_steps;
+    for (int t : ts.rot) rot_steps.push_back(plan.steps[t]);
+    if (rc == HISA_OK) rc = rotation_accumulators_fp(ctx, bi.base, bi.stride, nct, (int)l, rot_steps.data(), (int)S, acc.u());
+    for (size_t k = 0; k < S && rc == HISA_OK; k++) {
+        uint64_t gal = 0;
+        rc = hisa_galois_elt(ctx, rot_steps[k], &gal);
+        if (rc != HISA_OK) break;
+        hipError_t e = launch_automorph_ntt(bi.base, bi.stride, r0.u() + k * nct * lw, lw, gal, (int)l, nct, (int)ctx->log_n, ctx->stream);
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv automorphism: %s", hipGetErrorString(e));
+    }
+    const double mac_scale = in->cts[0]->scale * (plain ? cw.pt_scale : cw.w_scale);
+    if (rc == HISA_OK) rc = alloc_ct_batch(ctx, n_out, 2, l, mac_scale, outs.data());
+    if (rc == HISA_OK) {
+        hipError_t e;
+        MacArgs ma = {};
+        ma.IC = (int)IC; ma.OC = (int)OCm;
+        // E: the accumulators times the weights on the l + K limbs
+        ma.n_taps = (int)S; ma.l = (int)le; ma.ct_words = acc_bs; ma.polys = 2; ma.lq = (int)l; ma.gap = (int)(ctx->L - l);
+        for (size_t k = 0; k < S; k++) ma.tap_base[k] = acc.u() + k * nct * acc_bs;
+        ma.out = E.u();
+        e = shared_mac(ctx, ma, cw.dw, plain ? cw.pts->u() : nullptr, le, (int)B);
+        // Q0: sigma(c0) times the same weights on the l limbs
+        if (e == hipSuccess) {
+            ma.l = (int)l; ma.ct_words = lw; ma.polys = 1; ma.lq = 0; ma.gap = 0;
+            for (size_t k = 0; k < S; k++) ma.tap_base[k] = r0.u() + k * nct * lw;
+            ma.out = Q0.u();
+            e = shared_mac(ctx, ma, cw.dw, plain ? cw.pts->u() : nullptr, le, (int)B);
+        }
+        // Z: the unrotated taps
+        if (e == hipSuccess) {
+            if (ts.zero.empty()) {
+                e = hipMemsetAsync(Z.u(), 0, n_out * 2 * lw * sizeof(u64), ctx->stream);
+            } else {
+                ma.n_taps = (int)ts.zero.size(); ma.ct_words = 2 * lw; ma.polys = 2;
+                for (size_t k = 0; k < ts.zero.size(); k++) ma.tap_base[k] = bi.base;
+                ma.out = Z.u();
+                e = shared_mac(ctx, ma, cw.dw_zero, plain ? cw.pts_zero->u() : nullptr, l, (int)B);
+            }
+        }
+        if (e == hipSuccess)   // Z0 += Q0
+            e = launch_addsub(ctx->d_primes, Z.u(), Q0.u(), Z.u(), OP_ADD, (int)l, 1, 1, n_out, 2 * lw, lw, 2 * lw, (int)ctx->log_n,
+                              ctx->stream);
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));
+    }
+    if (rc == HISA_OK) rc = moddown_add_fp(ctx, E.u(), n_out, (int)l, Z.u(), 2 * lw, 2, 0, outs[0]->data);
+    if (rc == HISA_OK && g->mode == HISA_CONV_MASKED) {
+        hipError_t e = launch_mul_plain(ctx->d_primes, outs[0]->data, cw.mask->u(), outs[0]->data, (int)l, 2, n_out, 2 * lw, 2 * lw,
+                                        (int)ctx->log_n, ctx->stream);
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv mask: %s", hipGetErrorString(e));
+        for (hisa_ct* c : outs) c->scale = mac_scale * cw.pt_scale;
+    }
+    dev_release(ctx, bi.tmp);
+    free_handles(ctx, wrapped);
+    if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
+    if (rc != HISA_OK) {
+        free_handles(ctx, outs);
+        return rc;
+    }
+    for (size_t i = 0; i < outs.size(); i++) out->cts[i] = outs[i];
+    const bool keeps_zeros = g->fh == 1 && g->fw == 1 && g->stride == 1 && in->clean;
+    fill_out_meta(out, B, OC, plan.out_h, plan.out_w, in->h_stride * g->stride, in->w_stride * g->stride, in->offset,
+                  (g->mode != HISA_CONV_SCALAR || keeps_zeros) ? 1u : 0u, ci, in->c_stride);
+    return HISA_OK;
+}
+
+static int conv_dispatch(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
+                         const ConvWeights& cw, hisa_tensor* out) {
+    if (cw.shared) return conv_run_shared(ctx, in, g, plan, OC, cw, out);
+    const u64* d_pts = g->mode == HISA_CONV_MASKED ? (cw.mask ? cw.mask->u() : nullptr) : (cw.pts ? cw.pts->u() : nullptr);
+    return conv_run(ctx, in, g, plan, OC, cw.dw, cw.w_scale, d_pts, cw.pt_scale, out);
+}
+
+extern "C" int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* w_int, double w_scale,
+                                 const int64_t* pt_coeffs, double pt_scale, uint32_t OC, const hisa_conv_geom* geom,
+                                 hisa_tensor* out) {
+    TRY(check_tensor(ctx, in));
+    if (!out || !out->cts || OC == 0) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
+    ConvPlan plan;
+    TRY(conv_plan(ctx, in, geom, &plan));
+    ConvWeights cw;
+    TRY(conv_build_fixed(ctx, in, w_int, w_scale, pt_coeffs, pt_scale, OC, geom, plan, cw));
+    return conv_dispatch(ctx, in, geom, plan, OC, cw, out);
 }
 
 extern "C" int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t OC, const hisa_conv_geom* geom,
@@ -960,7 +1216,7 @@ extern "C" int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w
     TRY(conv_plan(ctx, in, geom, &plan));
     ConvWeights cw;
     TRY(conv_build(ctx, in, w, OC, geom, plan, cw));
-    return conv_run(ctx, in, geom, plan, OC, cw.dw, cw.w_scale, cw.pts ? cw.pts->u() : nullptr, cw.pt_scale, out);
+    return conv_dispatch(ctx, in, geom, plan, OC, cw, out);
 }
 
 // A convolution whose weights were converted ahead of time for one input layout and level.
@@ -1008,9 +1264,7 @@ extern "C" int hisa_conv2d_apply(hisa_ctx* ctx, const hisa_tensor* in, const his
                     in->cts[0]->limbs);
     ConvPlan cp;
     TRY(conv_plan(ctx, in, &plan->geom, &cp));
-    const ConvWeights& cw = plan->cw;
-    return conv_run(ctx, in, &plan->geom, cp, plan->out_channels, cw.dw, cw.w_scale, cw.pts ? cw.pts->u() : nullptr,
-                    cw.pt_scale, out);
+    return conv_dispatch(ctx, in, &plan->geom, cp, plan->out_channels, plan->cw, out);
 }
 
 // ---------------------------------------------------------------------------

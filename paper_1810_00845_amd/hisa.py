@@ -48,7 +48,7 @@ class OpCounts(C.Structure):
 
 class ConvGeom(C.Structure):
     _fields_ = [("fh", C.c_uint32), ("fw", C.c_uint32), ("stride", C.c_uint32), ("pad_same", C.c_uint32),
-                ("mode", C.c_uint32)]
+                ("mode", C.c_uint32), ("shared_moddown", C.c_uint32)]
 
 
 _lib = None
@@ -398,20 +398,20 @@ class Context:
         out._adopt(ost, oarr)
         return out
 
-    def conv2d(self, t, w, fh, fw, stride=1, pad_same=False, mode=CONV_SCALAR):
+    def conv2d(self, t, w, fh, fw, stride=1, pad_same=False, mode=CONV_SCALAR, shared_moddown=False):
         w = np.ascontiguousarray(w, dtype=np.float64)
         assert w.shape[:3] == (fh, fw, t.channels)
         oc = w.shape[3]
-        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode)
+        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode, 1 if shared_moddown else 0)
         return self._layer("hisa_conv2d", t, t.batch * -(-oc // t.c_inner), _dp(w), C.c_uint32(oc), C.byref(g))
 
-    def conv2d_prepare(self, like, w, fh, fw, stride=1, pad_same=False, mode=CONV_SCALAR):
+    def conv2d_prepare(self, like, w, fh, fw, stride=1, pad_same=False, mode=CONV_SCALAR, shared_moddown=False):
         """Converts conv weights once for tensors laid out like `like`; returns a plan for conv2d_apply (free with
         conv_plan_free)."""
         w = np.ascontiguousarray(w, dtype=np.float64)
         assert w.shape[:3] == (fh, fw, like.channels)
         oc = w.shape[3]
-        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode)
+        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode, 1 if shared_moddown else 0)
         st, _arr = like._struct()
         plan = C.c_void_p()
         self._ck(load().hisa_conv2d_prepare(self._vp, C.byref(st), _dp(w), C.c_uint32(oc), C.byref(g), C.byref(plan)))
@@ -423,11 +423,11 @@ class Context:
     def conv_plan_free(self, plan):
         self._ck(load().hisa_conv_plan_free(self._vp, plan[0]))
 
-    def conv2d_fixed(self, t, w_int, w_scale, pt_coeffs, pt_scale, oc, fh, fw, stride=1, pad_same=False, mode=CONV_SCALAR):
+    def conv2d_fixed(self, t, w_int, w_scale, pt_coeffs, pt_scale, oc, fh, fw, stride=1, pad_same=False, mode=CONV_SCALAR, shared_moddown=False):
         i64p = C.POINTER(C.c_int64)
         wi = np.ascontiguousarray(w_int, dtype=np.int64) if w_int is not None else None
         pc = np.ascontiguousarray(pt_coeffs, dtype=np.int64) if pt_coeffs is not None else None
-        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode)
+        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode, 1 if shared_moddown else 0)
         return self._layer("hisa_conv2d_fixed", t, t.batch * -(-oc // t.c_inner), wi.ctypes.data_as(i64p) if wi is not None else None,
                            C.c_double(w_scale), pc.ctypes.data_as(i64p) if pc is not None else None, C.c_double(pt_scale),
                            C.c_uint32(oc), C.byref(g))
@@ -550,7 +550,7 @@ class Context:
         return [int(buf[i]) for i in range(n.value)]
 
     def conv2d_rot_steps(self, t, fh, fw, stride=1, pad_same=False):
-        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, 0)
+        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, 0, 0)
         return self._steps("hisa_conv2d_rot_steps", t, C.byref(g))
 
     def fc_rot_steps(self, t):

@@ -419,3 +419,56 @@ def test_layout_switches_bit_exact():
         with pytest.raises(hisa.HisaError):
             g.tensor_to_hw(gt)
         g.close()
+
+
+def test_shared_moddown_convolutions_bit_exact():
+    """The convolution with one division by P per output ciphertext through the C ABI against the oracle's
+    SharedModDown schedule, bit for bit: HW-tiled with scalar weights (literal and masked; short contraction on the
+    fp64 kernel, long one on the matrix cores), HW-tiled with plaintext weights, CHW-tiled (with the copy behind the
+    blocks); batch of two; plan and float entry point; and against the fp64 convolution."""
+    from oracle import layers
+    from paper_1810_00845_amd import hisa, synth
+    g, o = make_pair(12, [50, 45, 45], 3, 50, 17)
+    x = synth.image(71, 4, 4, 4)[None].repeat(2, axis=0) * np.array([1.0, -0.6])[:, None, None, None]
+    gt, ot = both_tensors(g, o, x, 2.0 ** 40, 3, h_stride=6, offset=7)
+    steps = sorted(set(g.conv2d_rot_steps(gt, 3, 3, pad_same=True)) | set(g.conv2d_rot_steps(gt, 3, 3)))
+    g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+    for oc_n, kw, mode in ((5, dict(pad_same=True), layers.CONV_MASKED),      # K = 32 rotated terms: matrix cores
+                           (3, dict(), layers.CONV_SCALAR), (2, dict(stride=2, pad_same=True), layers.CONV_PLAIN)):
+        w = synth.conv_weights(72 + oc_n, 3, 3, 4, oc_n)
+        ref = plain_net.conv2d(x, w, **kw)
+        oout, ints = layers.conv2d(o, ot, w, mode=mode, shared_moddown=True, **kw)
+        gout = g.conv2d_fixed(gt, ints["w_int"], ints["w_scale"], ints["pt_coeffs"], ints["pt_scale"], oc_n, 3, 3, mode=mode,
+                              shared_moddown=True, **kw)
+        same_tensor(g, o, gout, oout)
+        assert np.abs(g.tensor_decrypt(gout) - ref).max() <= 1e-3
+        gfloat = g.conv2d(gt, w, 3, 3, mode=mode, shared_moddown=True, **kw)
+        assert gfloat.meta() == gout.meta() and np.abs(g.tensor_decrypt(gfloat) - ref).max() <= 1e-3
+        plan = g.conv2d_prepare(gt, w, 3, 3, mode=mode, shared_moddown=True, **kw)
+        gplan = g.conv2d_apply(gt, plan)
+        for ca, cb in zip(gfloat.cts, gplan.cts):
+            assert np.array_equal(g.ct_export(ca), g.ct_export(cb))
+        g.conv_plan_free(plan)
+        exact = g.conv2d(gt, w, 3, 3, mode=mode, **kw)              # the term-by-term schedule: other bits, same values
+        assert not np.array_equal(g.ct_export(exact.cts[0]), g.ct_export(gfloat.cts[0]))
+        assert np.abs(g.tensor_decrypt(exact) - g.tensor_decrypt(gfloat)).max() <= 1e-6
+    # CHW-tiled: 5 -> 6 channels in blocks of 4, 64 slots apart (copy behind the blocks)
+    xc = synth.image(73, 5, 4, 4)[None]
+    wc = synth.conv_weights(74, 3, 3, 5, 6)
+    gc, oc = chw_pair(g, o, xc, 2.0 ** 40, 3, 4, 64, 910, h_stride=6, offset=7)
+    steps = g.conv2d_rot_steps(gc, 3, 3, pad_same=True)
+    g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+    oout, ints = layers.conv2d_chw(o, oc, wc, pad_same=True, shared_moddown=True)
+    gout = g.conv2d_fixed(gc, None, 1.0, ints["pt_coeffs"], ints["pt_scale"], 6, 3, 3, pad_same=True, mode=layers.CONV_PLAIN,
+                          shared_moddown=True)
+    same_tensor(g, o, gout, oout)
+    assert np.abs(g.tensor_decrypt(gout) - plain_net.conv2d(xc, wc, pad_same=True)).max() <= 1e-3
+    gfloat = g.conv2d(gc, wc, 3, 3, pad_same=True, mode=layers.CONV_PLAIN, shared_moddown=True)
+    assert np.abs(g.tensor_decrypt(gfloat) - plain_net.conv2d(xc, wc, pad_same=True)).max() <= 1e-3
+    g.close()
+    # parameters without the fused key-switch path refuse the request
+    g2, _ = make_pair(10, [50, 40, 40], 3, 50, 17)
+    t2 = g2.tensor_encrypt(synth.image(1, 1, 4, 4)[None], 2.0 ** 40, 3)
+    with pytest.raises(hisa.HisaError):
+        g2.conv2d(t2, synth.conv_weights(1, 3, 3, 1, 1), 3, 3, shared_moddown=True)
+    g2.close()
