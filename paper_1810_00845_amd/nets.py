@@ -109,7 +109,7 @@ def chw_blocks(slots, plane_slots_needed, layers, chw_convs=True):
     return c_inner, c_stride
 
 
-def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans=None, layout="hw"):
+def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans=None, layout="hw", shared_moddown=True):
     """Encrypts x, runs the layers, decrypts.  Returns (output array, seconds from encrypt-done to the last
     ciphertext ready, per-layer seconds).  With make_keys the rotation keys each layer asks for are generated
     on the way (set-up pass); otherwise they must be resident.  `plans` (a dict, filled by the set-up pass and
@@ -120,7 +120,9 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
     several channels into every ciphertext from the input on (CHW-tiled convolutions multiply by plaintexts and need
     clean inputs: a masking multiply follows each pool); "hw_conv" (the paper's "HW-conv and CHW-rest") keeps the tensor
     CHW-tiled between the layers but switches to HW-tiling before every convolution and back after it (one level
-    for the way to HW, one for the masking multiply that makes Algorithm 1's output clean enough to pack)."""
+    for the way to HW, one for the masking multiply that makes Algorithm 1's output clean enough to pack).
+    shared_moddown: the convolutions divide by P once per output ciphertext instead of once per rotation (where the
+    parameters have the fused key-switch path)."""
     assert layout in LAYOUTS
     replicas = 1 if layout == "hw" else 1 << 30
     tiling = {}
@@ -183,6 +185,12 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
                 t = cleaned = ctx.tensor_mask(t)
         if make_keys:
             ctx.gen_rot_keys(ctx.conv2d_rot_steps(t, fh, fw, stride=kw.get("stride", 1), pad_same=kw.get("pad_same", False)))
+        # one division by P per output instead of one per rotation pays when there are clearly more rotations than
+        # outputs and the weights are scalars (with plaintext weights the sum on the l + K limbs streams that many
+        # more plaintext limbs, which costs what the divisions save)
+        scalar = t.c_inner == 1 and kw.get("mode", 0) != 2
+        kw["shared_moddown"] = (shared_moddown and scalar and ctx.log_n >= 12 and max(ctx.primes) < 2 ** 50 and
+                                (fh * fw - 1) * t.channels >= 4 * w.shape[3] and t.channels * (fh * fw - 1) >= 64)
         if plans is None:
             out = ctx.conv2d(t, w, fh, fw, **kw)
         else:
