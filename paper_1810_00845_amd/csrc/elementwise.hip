@@ -340,6 +340,32 @@ hipError_t launch_automorph_ntt(const u64* in, u64 in_bs, u64* out, u64 out_bs, 
     return hipGetLastError();
 }
 
+// The same gather for several automorphisms of the same n_batch inputs in one launch: blockIdx.z = s * n_batch + b,
+// out entry (s, b) = sigma_{g[s]}(in entry b).
+__global__ __launch_bounds__(NT) void automorph_steps_kernel(const u64* in, u64 in_bs, u64* out, u64 out_bs, GaloisTab tab,
+                                                             unsigned n_batch, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const uint32_t i = blockIdx.x * NT + threadIdx.x;
+    const uint32_t mask = (2u << log_n) - 1;
+    const unsigned s = blockIdx.z / n_batch, b = blockIdx.z % n_batch;
+    uint32_t e = 2 * (__brev(i) >> (32 - log_n)) + 1;
+    uint32_t e2 = (uint32_t)((u64)e * tab.g[s]) & mask;
+    uint32_t src = __brev((e2 - 1) >> 1) >> (32 - log_n);
+    out[(u64)blockIdx.z * out_bs + (u64)blockIdx.y * n + i] = in[(u64)b * in_bs + (u64)blockIdx.y * n + src];
+}
+
+hipError_t launch_automorph_steps(const u64* in, u64 in_bs, u64* out, u64 out_bs, const GaloisTab& tab, int n_steps,
+                                  int n_polys, u64 n_batch, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
+    if (n_steps < 1 || n_steps > GALOIS_TAB_MAX || n_batch == 0 || (u64)n_steps * n_batch > 65535) return hipErrorInvalidValue;
+    for (int s = 0; s < n_steps; s++)
+        if (tab.g[s] == 0) return hipErrorInvalidValue;
+    dim3 grid((1u << log_n) / NT, n_polys, (unsigned)(n_steps * n_batch));
+    ProfScope prof__("automorph_steps_kernel", st);
+    hipLaunchKernelGGL(automorph_steps_kernel, grid, dim3(NT), 0, st, in, in_bs, out, out_bs, tab, (unsigned)n_batch, log_n);
+    return hipGetLastError();
+}
+
 // signed integer coefficients [n_pts][N] -> residues modulo primes[0..limbs-1] at out[p][0..limbs-1][N], the entries of
 // out being out_limbs limbs apart
 __global__ __launch_bounds__(NT) void reduce_i64_kernel(const PrimeConst* primes, const i64* coeffs, u64* out, int out_limbs,

@@ -313,6 +313,11 @@ hipError_t launch_key_combine(const PrimeConst* primes, const u64* secret, const
 hipError_t launch_pointwise_square(const PrimeConst* primes, const u64* s, u64* out, int total, int log_n, hipStream_t st);
 hipError_t launch_automorph_ntt(const u64* in, u64 in_bs, u64* out, u64 out_bs, u64 galois, int n_polys, u64 n_batch,
                                 int log_n, hipStream_t st);
+#define GALOIS_TAB_MAX 256
+struct GaloisTab { uint32_t g[GALOIS_TAB_MAX]; };
+// several automorphisms of the same inputs: out entry (s, b) = sigma_{tab.g[s]}(in entry b), entries out_bs words apart
+hipError_t launch_automorph_steps(const u64* in, u64 in_bs, u64* out, u64 out_bs, const GaloisTab& tab, int n_steps,
+                                  int n_polys, u64 n_batch, int log_n, hipStream_t st);
 hipError_t launch_reduce_i64(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs, int n_pts, int log_n,
                              hipStream_t st);
 // the same with the output entries out_limbs limbs apart (residues on a second list of primes go behind the first)

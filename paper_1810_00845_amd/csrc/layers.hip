@@ -29,6 +29,10 @@ struct MacArgs {
     int lq, gap;                    // limb i uses prime i for i < lq and prime i + gap beyond (the special primes of a
                                     // key-switch accumulator's l + K limbs); lq = 0: prime i throughout
     u64 w_words;                    // plain: words per plaintext in memory (0: l * N)
+    // plain, optional: a second, one-polynomial input per term on the limbs below lq, multiplied by the same plaintext
+    // in the same pass (term (t, b, ic) at x2 + t * x2_tap_words + (b * IC + ic) * x2_words), summed into
+    // out2[b * OC + oc] (x2_words apart)
+    const u64* x2; u64 x2_tap_words, x2_words; u64* out2;
 };
 
 __device__ __forceinline__ int mac_prime(const MacArgs& g, int limb) { return (g.lq && limb >= g.lq) ? limb + g.gap : limb; }
@@ -291,20 +295,23 @@ __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes
     const double p = fp[0], pinv = fp[1];
     const u64 ln = (u64)g.l * n, wl = g.w_words ? g.w_words : ln;
     const bool two = g.polys != 1;      // one-polynomial entries: the second accumulator idles
-    double a0[OCP], a1[OCP];
+    const bool third = g.x2 && limb < g.lq;
+    double a0[OCP], a1[OCP], a2[OCP];
 #pragma unroll
-    for (int o = 0; o < OCP; o++) a0[o] = a1[o] = 0.0;
+    for (int o = 0; o < OCP; o++) a0[o] = a1[o] = a2[o] = 0.0;
     int pending = 0;
     for (int t = 0; t < g.n_taps; t++) {
         const u64* x = g.tap_base[t] + (u64)b * g.IC * g.ct_words + (u64)limb * n + j;
         const u64* w = g.w + ((u64)t * g.IC * g.w_stride_t + (u64)oc0 * g.w_stride_oc) * wl + (u64)limb * n + j;
+        const u64* x2 = third ? g.x2 + (u64)t * g.x2_tap_words + (u64)b * g.IC * g.x2_words + (u64)limb * n + j : nullptr;
         for (int ic0 = 0; ic0 < g.IC; ic0 += ICP) {
-            u64 xb[ICP], xa[ICP], wv[ICP][OCP];
+            u64 xb[ICP], xa[ICP], xc[ICP], wv[ICP][OCP];
 #pragma unroll
             for (int u = 0; u < ICP; u++) {
                 const int ic = ic0 + u < g.IC ? ic0 + u : g.IC - 1;
                 xb[u] = x[(u64)ic * g.ct_words];
                 xa[u] = two ? x[(u64)ic * g.ct_words + ln] : 0;
+                xc[u] = third ? x2[(u64)ic * g.x2_words] : 0;
 #pragma unroll
                 for (int o = 0; o < OCP; o++) {
                     const int oo = oc0 + o < g.OC ? o : 0;
@@ -314,19 +321,23 @@ __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes
 #pragma unroll
             for (int u = 0; u < ICP; u++) {
                 if (ic0 + u < g.IC) {
-                    const double fb = fp_from_u64(xb[u]), fa = fp_from_u64(xa[u]);
+                    const double fb = fp_from_u64(xb[u]), fa = fp_from_u64(xa[u]), fc = fp_from_u64(xc[u]);
 #pragma unroll
                     for (int o = 0; o < OCP; o++) {
                         const double wf = fp_from_u64(wv[u][o]);
                         a0[o] += fp_mulmod(fb, wf, p, pinv);
                         a1[o] += fp_mulmod(fa, wf, p, pinv);
+                        if (third) a2[o] += fp_mulmod(fc, wf, p, pinv);
                     }
                 }
             }
             pending += ICP;
             if (pending >= 4) {   // canonical operands: a term can reach 0.9 p, four of them on a normalised value 4.1 p
 #pragma unroll
-                for (int o = 0; o < OCP; o++) { a0[o] = fp_norm(a0[o], p, pinv); a1[o] = fp_norm(a1[o], p, pinv); }
+                for (int o = 0; o < OCP; o++) {
+                    a0[o] = fp_norm(a0[o], p, pinv); a1[o] = fp_norm(a1[o], p, pinv);
+                    if (third) a2[o] = fp_norm(a2[o], p, pinv);
+                }
                 pending = 0;
             }
         }
@@ -337,6 +348,7 @@ __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes
             u64* dst = g.out + ((u64)b * g.OC + oc0 + o) * g.ct_words + (u64)limb * n + j;
             dst[0] = fp_canonical(a0[o], p, pinv);
             if (two) dst[ln] = fp_canonical(a1[o], p, pinv);
+            if (third) g.out2[((u64)b * g.OC + oc0 + o) * g.x2_words + (u64)limb * n + j] = fp_canonical(a2[o], p, pinv);
         }
     }
 }
@@ -397,6 +409,7 @@ static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, 
     count_mac(g, batch, true);
     DRY_RUN_RETURN();
     if (!fprimes || !g.w || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS) return hipErrorInvalidValue;
+    if (g.x2 && (!g.out2 || g.lq <= 0 || g.lq > g.l || g.x2_words == 0)) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / NT, g.l, batch * ((g.OC + OCP - 1) / OCP));
     ProfScope prof__("plain_mac_fp_kernel", st);
     hipLaunchKernelGGL(plain_mac_fp_kernel, grid, dim3(NT), 0, st, fprimes, g, log_n);
@@ -1127,12 +1140,21 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
     std::vector<int32_t> rot_steps;
     for (int t : ts.rot) rot_steps.push_back(plan.steps[t]);
     if (rc == HISA_OK) rc = rotation_accumulators_fp(ctx, bi.base, bi.stride, nct, (int)l, rot_steps.data(), (int)S, acc.u());
-    for (size_t k = 0; k < S && rc == HISA_OK; k++) {
-        uint64_t gal = 0;
-        rc = hisa_galois_elt(ctx, rot_steps[k], &gal);
-        if (rc != HISA_OK) break;
-        hipError_t e = launch_automorph_ntt(bi.base, bi.stride, r0.u() + k * nct * lw, lw, gal, (int)l, nct, (int)ctx->log_n, ctx->stream);
-        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv automorphism: %s", hipGetErrorString(e));
+    {   // sigma(c0) for every rotated tap, as many taps per launch as the grid allows
+        const size_t per_launch = std::max<size_t>(1, std::min<size_t>(GALOIS_TAB_MAX, 65535 / nct));
+        for (size_t k0 = 0; k0 < S && rc == HISA_OK; k0 += per_launch) {
+            const size_t cnt = std::min(per_launch, S - k0);
+            GaloisTab tab = {};
+            for (size_t k = 0; k < cnt && rc == HISA_OK; k++) {
+                uint64_t gal = 0;
+                rc = hisa_galois_elt(ctx, rot_steps[k0 + k], &gal);
+                tab.g[k] = (uint32_t)gal;
+            }
+            if (rc != HISA_OK) break;
+            hipError_t e = launch_automorph_steps(bi.base, bi.stride, r0.u() + k0 * nct * lw, lw, tab, (int)cnt, (int)l, nct,
+                                                  (int)ctx->log_n, ctx->stream);
+            if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv automorphism: %s", hipGetErrorString(e));
+        }
     }
     const double mac_scale = in->cts[0]->scale * (plain ? cw.pt_scale : cw.w_scale);
     if (rc == HISA_OK) rc = alloc_ct_batch(ctx, n_out, 2, l, mac_scale, outs.data());
@@ -1144,9 +1166,13 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
         ma.n_taps = (int)S; ma.l = (int)le; ma.ct_words = acc_bs; ma.polys = 2; ma.lq = (int)l; ma.gap = (int)(ctx->L - l);
         for (size_t k = 0; k < S; k++) ma.tap_base[k] = acc.u() + k * nct * acc_bs;
         ma.out = E.u();
+        if (plain) {   // the plaintexts are read once: sigma(c0) rides along on the limbs below l (Q0)
+            ma.x2 = r0.u(); ma.x2_tap_words = nct * lw; ma.x2_words = lw; ma.out2 = Q0.u();
+        }
         e = shared_mac(ctx, ma, cw.dw, plain ? cw.pts->u() : nullptr, le, (int)B);
+        ma.x2 = nullptr; ma.out2 = nullptr;
         // Q0: sigma(c0) times the same weights on the l limbs
-        if (e == hipSuccess) {
+        if (e == hipSuccess && !plain) {
             ma.l = (int)l; ma.ct_words = lw; ma.polys = 1; ma.lq = 0; ma.gap = 0;
             for (size_t k = 0; k < S; k++) ma.tap_base[k] = r0.u() + k * nct * lw;
             ma.out = Q0.u();
@@ -1157,7 +1183,9 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
             if (ts.zero.empty()) {
                 e = hipMemsetAsync(Z.u(), 0, n_out * 2 * lw * sizeof(u64), ctx->stream);
             } else {
-                ma.n_taps = (int)ts.zero.size(); ma.ct_words = 2 * lw; ma.polys = 2;
+                // (every field the launches above changed is set again: with plaintext weights the Q0 block is skipped)
+                ma.n_taps = (int)ts.zero.size(); ma.l = (int)l; ma.ct_words = 2 * lw; ma.polys = 2; ma.lq = 0; ma.gap = 0;
+                ma.x2 = nullptr; ma.out2 = nullptr;
                 for (size_t k = 0; k < ts.zero.size(); k++) ma.tap_base[k] = bi.base;
                 ma.out = Z.u();
                 e = shared_mac(ctx, ma, cw.dw_zero, plain ? cw.pts_zero->u() : nullptr, l, (int)B);
