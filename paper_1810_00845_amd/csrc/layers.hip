@@ -37,6 +37,15 @@ struct MacArgs {
 
 __device__ __forceinline__ int mac_prime(const MacArgs& g, int limb) { return (g.lq && limb >= g.lq) ? limb + g.gap : limb; }
 static inline int mac_polys(const MacArgs& g) { return g.polys == 1 ? 1 : 2; }
+// host check of every multiply-accumulate launch: an entry (ct_words apart) must hold the polys * l limbs the kernel
+// walks over, and the optional second input its lq limbs
+static inline bool mac_shape_ok(const MacArgs& g, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    if (g.l <= 0 || g.IC <= 0 || g.OC <= 0 || (u64)mac_polys(g) * g.l * n > g.ct_words) return false;
+    if (g.lq < 0 || g.lq > g.l) return false;
+    if (g.x2 && (u64)g.lq * n > g.x2_words) return false;
+    return true;
+}
 
 // out[b][oc] = sum over T = (tap, ic) of  w[T][oc] * x[tap][b][ic]   (integer weights, one per limb)
 __global__ __launch_bounds__(NT) void scalar_mac_kernel(const PrimeConst* primes, MacArgs g, int log_n) {
@@ -362,6 +371,10 @@ static void count_mac(const MacArgs& g, int batch, bool plain) {
 static hipError_t launch_scalar_mac(const PrimeConst* primes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
     count_mac(g, batch, false);
     DRY_RUN_RETURN();
+    // the integer kernels know two-polynomial entries on the primes q_0.. only
+    if (!primes || !g.w || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || g.polys == 1 || g.lq || g.x2 || g.w_words ||
+        !mac_shape_ok(g, log_n))
+        return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / NT, 2 * g.l, batch * ((g.OC + OCB - 1) / OCB));
     ProfScope prof__("scalar_mac_kernel", st);
     hipLaunchKernelGGL(scalar_mac_kernel, grid, dim3(NT), 0, st, primes, g, log_n);
@@ -372,7 +385,7 @@ static hipError_t launch_scalar_mac_fp(const FpPrime* fprimes, const MacArgs& g,
                                        hipStream_t st) {
     count_mac(g, batch, false);
     DRY_RUN_RETURN();
-    if (!fprimes || !wf || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS) return hipErrorInvalidValue;
+    if (!fprimes || !wf || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || !mac_shape_ok(g, log_n)) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / NT, mac_polys(g) * g.l, batch * ((g.OC + OCF - 1) / OCF));
     ProfScope prof__("scalar_mac_fp_kernel", st);
     hipLaunchKernelGGL(scalar_mac_fp_kernel, grid, dim3(NT), 0, st, fprimes, g, wf, log_n);
@@ -393,7 +406,8 @@ static hipError_t launch_scalar_mac_mfma(const FpPrime* fprimes, const MacArgs& 
     count_mac(g, batch, false);
     DRY_RUN_RETURN();
     if (!fprimes || !wd || !c3 || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || K != g.n_taps * g.IC || K_pad % MT_K ||
-        K_pad < K || OC_pad % MT_OC || OC_pad < g.OC || log_n < 6 || da < 1 || da > MAC_DIGITS || (db != 6 && db != 7))
+        K_pad < K || OC_pad % MT_OC || OC_pad < g.OC || log_n < 6 || da < 1 || da > MAC_DIGITS || (db != 6 && db != 7) ||
+        !mac_shape_ok(g, log_n))
         return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / MT_E, mac_polys(g) * g.l, batch * (OC_pad / MT_OC));
     ProfScope prof__("scalar_mac_mfma_kernel", st);
@@ -408,7 +422,8 @@ static hipError_t launch_scalar_mac_mfma(const FpPrime* fprimes, const MacArgs& 
 static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
     count_mac(g, batch, true);
     DRY_RUN_RETURN();
-    if (!fprimes || !g.w || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS) return hipErrorInvalidValue;
+    if (!fprimes || !g.w || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || !mac_shape_ok(g, log_n)) return hipErrorInvalidValue;
+    if (g.w_words && (u64)g.l * ((u64)1 << log_n) > g.w_words) return hipErrorInvalidValue;   // plaintexts shorter than the limbs walked
     if (g.x2 && (!g.out2 || g.lq <= 0 || g.lq > g.l || g.x2_words == 0)) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / NT, g.l, batch * ((g.OC + OCP - 1) / OCP));
     ProfScope prof__("plain_mac_fp_kernel", st);
@@ -419,6 +434,10 @@ static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, 
 static hipError_t launch_plain_mac(const PrimeConst* primes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
     count_mac(g, batch, true);
     DRY_RUN_RETURN();
+    // the integer kernels know two-polynomial entries on the primes q_0.. only
+    if (!primes || !g.w || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || g.polys == 1 || g.lq || g.x2 || g.w_words ||
+        !mac_shape_ok(g, log_n))
+        return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / NT, g.l, batch * g.OC);
     ProfScope prof__("plain_mac_kernel", st);
     hipLaunchKernelGGL(plain_mac_kernel, grid, dim3(NT), 0, st, primes, g, log_n);
