@@ -362,3 +362,30 @@ def select_layout(ctx, layers, x, scale, limbs, costs, border=0, layouts=LAYOUTS
     cost it, keep the cheapest.  Returns (layout, {layout: estimated seconds})."""
     est = {lay: estimate_cost(analyse(ctx, layers, x, scale, limbs, border, lay)[0], costs) for lay in layouts}
     return min(est, key=est.get), est
+
+
+# 128-bit security for ternary secrets: largest log2(Q P) per ring degree (the table of the Homomorphic Encryption
+# Standard that the paper's parameter selection consults)
+HE_STANDARD_128 = {10: 27, 11: 54, 12: 109, 13: 218, 14: 438, 15: 881}
+
+
+def select_parameters(layers, x, log_n, scale_bits, first_bits=50, dnum=3, special_bits=50, border=0, layout="hw",
+                      probe_limbs=28):
+    """Encryption parameter selection (Sec. "Encryption Parameters Selection"): a dry run of the schedule on a context
+    with more moduli than any circuit here needs measures the depth (the number of moduli the divScalar calls
+    consume); the modulus chain is then one first prime and one prime of the scale's size per level.  Returns the
+    parameters for hisa.Context, the rotation amounts that need keys, and whether the ring degree meets the 128-bit
+    table for the resulting modulus."""
+    from .hisa import Context
+    probe = Context(log_n, [first_bits] + [scale_bits] * (probe_limbs - 1), dnum, special_bits, seed=1)
+    try:
+        counts, steps = analyse(probe, layers, x, 2.0 ** scale_bits, probe_limbs, border=border, layout=layout)
+    finally:
+        probe.close()
+    depth = probe_limbs - counts["min_limbs"]
+    q_bits = [first_bits] + [scale_bits] * depth
+    k = -(-len(q_bits) // dnum)
+    total_bits = sum(q_bits) + k * special_bits
+    return {"log_n": log_n, "q_bits": q_bits, "dnum": dnum, "special_bits": special_bits, "scale": 2.0 ** scale_bits,
+            "depth": depth, "rot_steps": steps, "modulus_bits": total_bits,
+            "secure_128": total_bits <= HE_STANDARD_128.get(log_n, 0)}

@@ -112,3 +112,25 @@ def test_layout_selection_by_cost_agrees_with_the_clock():
     print("measured (ms):", {k: round(v * 1e3, 2) for k, v in measured.items()}, flush=True)
     assert measured["chw_fc"] < measured["hw"] < measured["chw"]
     ctx.close()
+
+
+def test_parameter_selection_gives_exactly_the_levels_the_network_needs():
+    """The depth measured by the dry run is tight: LeNet-small runs (<= 1e-3) on the modulus chain the pass selects
+    and runs out of levels with one prime fewer."""
+    from paper_1810_00845_amd import hisa, nets
+    from test_gpu_networks import plain_forward
+    params, layers, x = nets.lenet_small()
+    sel = nets.select_parameters(layers, x, params["log_n"], 40, dnum=params["dnum"], layout="chw_fc")
+    assert sel["depth"] == 6 and sel["q_bits"] == [50] + [40] * 6 and not sel["secure_128"]   # 2^13 allows 218 bits
+    want = plain_forward(layers, x)
+    ctx = hisa.Context(sel["log_n"], sel["q_bits"], sel["dnum"], sel["special_bits"], seed=11)
+    ctx.keygen()
+    ctx.gen_rot_keys(sel["rot_steps"])
+    got, _, _ = nets.run_encrypted(ctx, layers, x, sel["scale"], len(sel["q_bits"]), layout="chw_fc")
+    assert np.abs(got - want).max() <= 1e-3
+    ctx.close()
+    short = hisa.Context(sel["log_n"], sel["q_bits"][:-1], sel["dnum"], sel["special_bits"], seed=11)
+    short.keygen()
+    with pytest.raises(hisa.HisaError):
+        nets.run_encrypted(short, layers, x, sel["scale"], len(sel["q_bits"]) - 1, make_keys=True, layout="chw_fc")
+    short.close()
