@@ -544,9 +544,9 @@ class Context:
 
     def _steps(self, fn, t, *args):
         st, _arr = t._struct()
-        buf = (C.c_int32 * 256)()
+        buf = (C.c_int32 * 1024)()      # a CHW-tiled convolution alone can ask for 257 amounts
         n = C.c_size_t()
-        self._ck(getattr(load(), fn)(self._vp, C.byref(st), *args, buf, C.c_size_t(256), C.byref(n)))
+        self._ck(getattr(load(), fn)(self._vp, C.byref(st), *args, buf, C.c_size_t(1024), C.byref(n)))
         return [int(buf[i]) for i in range(n.value)]
 
     def conv2d_rot_steps(self, t, fh, fw, stride=1, pad_same=False):
