@@ -160,15 +160,18 @@ def network_latencies():
             plans = {}
             kw = dict(border=border, plans=plans, layout=layout)
             nets.run_encrypted(ctx, layers, x, params["scale"], limbs, make_keys=True, **kw)
-            runs = sorted((nets.run_encrypted(ctx, layers, x, params["scale"], limbs, **kw) for _ in range(3)),
-                          key=lambda r: r[1])
-            res[layout] = (runs[1][1], runs[1][2], None)
+            # latency: the host queues the whole network, one wait at the end; the per-layer times come from one more
+            # inference that waits after every layer
+            runs = sorted((nets.run_encrypted(ctx, layers, x, params["scale"], limbs, layer_times=False, **kw)
+                           for _ in range(3)), key=lambda r: r[1])
+            per_layer = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, **kw)[2]
+            res[layout] = (runs[1][1], per_layer, None)
             if layout == selected:     # one more inference with HIP events around every kernel: where the time goes
                 ctx.profile_enable(True)
                 nets.run_encrypted(ctx, layers, x, params["scale"], limbs, **kw)
                 prof = sorted(ctx.profile_read().items(), key=lambda kv: -kv[1][1])
                 ctx.profile_enable(False)
-                res[layout] = (runs[1][1], runs[1][2], {k: [c, round(ms, 3)] for k, (c, ms) in prof[:8]})
+                res[layout] = (runs[1][1], per_layer, {k: [c, round(ms, 3)] for k, (c, ms) in prof[:8]})
             nets.free_plans(ctx, plans)
             ctx.close()
         best = selected

@@ -294,6 +294,9 @@ __global__ __launch_bounds__(256) void scalar_mac_mfma_kernel(const FpPrime* fpr
 // (tap, channel) terms are loaded before their arithmetic.
 #define OCP 4
 #define ICP 2
+// WITH_X2: the optional second input is present (a separate instantiation, so that the common form keeps its
+// straight-line loads)
+template <bool WITH_X2>
 __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes, MacArgs g, int log_n) {
     const u64 n = (u64)1 << log_n;
     const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
@@ -304,7 +307,7 @@ __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes
     const double p = fp[0], pinv = fp[1];
     const u64 ln = (u64)g.l * n, wl = g.w_words ? g.w_words : ln;
     const bool two = g.polys != 1;      // one-polynomial entries: the second accumulator idles
-    const bool third = g.x2 && limb < g.lq;
+    const bool third = WITH_X2 && limb < g.lq;
     double a0[OCP], a1[OCP], a2[OCP];
 #pragma unroll
     for (int o = 0; o < OCP; o++) a0[o] = a1[o] = a2[o] = 0.0;
@@ -427,7 +430,8 @@ static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, 
     if (g.x2 && (!g.out2 || g.lq <= 0 || g.lq > g.l || g.x2_words == 0)) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / NT, g.l, batch * ((g.OC + OCP - 1) / OCP));
     ProfScope prof__("plain_mac_fp_kernel", st);
-    hipLaunchKernelGGL(plain_mac_fp_kernel, grid, dim3(NT), 0, st, fprimes, g, log_n);
+    if (g.x2) hipLaunchKernelGGL(plain_mac_fp_kernel<true>, grid, dim3(NT), 0, st, fprimes, g, log_n);
+    else hipLaunchKernelGGL(plain_mac_fp_kernel<false>, grid, dim3(NT), 0, st, fprimes, g, log_n);
     return hipGetLastError();
 }
 

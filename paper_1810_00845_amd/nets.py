@@ -109,7 +109,8 @@ def chw_blocks(slots, plane_slots_needed, layers, chw_convs=True):
     return c_inner, c_stride
 
 
-def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans=None, layout="hw", shared_moddown=True):
+def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans=None, layout="hw", shared_moddown=True,
+                  layer_times=True):
     """Encrypts x, runs the layers, decrypts.  Returns (output array, seconds from encrypt-done to the last
     ciphertext ready, per-layer seconds).  With make_keys the rotation keys each layer asks for are generated
     on the way (set-up pass); otherwise they must be resident.  `plans` (a dict, filled by the set-up pass and
@@ -122,7 +123,9 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
     CHW-tiled between the layers but switches to HW-tiling before every convolution and back after it (one level
     for the way to HW, one for the masking multiply that makes Algorithm 1's output clean enough to pack).
     shared_moddown: the convolutions divide by P once per output ciphertext instead of once per rotation (where the
-    parameters have the fused key-switch path)."""
+    parameters have the fused key-switch path).  layer_times: wait for the GPU after every layer to time it; without,
+    the host queues the whole network ahead of the GPU and only the end-to-end latency is measured (per-layer entries
+    are then host queueing times)."""
     assert layout in LAYOUTS
     replicas = 1 if layout == "hw" else 1 << 30
     tiling = {}
@@ -250,8 +253,10 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             raise ValueError(kind)
         t.free()
         t = nxt
-        ctx.sync()
+        if layer_times:
+            ctx.sync()
         per_layer.append((kind, time.perf_counter() - t0))
+    ctx.sync()
     latency = time.perf_counter() - t_start
     out = ctx.tensor_decrypt(t) * pending
     t.free()
