@@ -289,14 +289,14 @@ __global__ __launch_bounds__(256) void scalar_mac_mfma_kernel(const FpPrime* fpr
     }
 }
 
-// The slot-wise sum in exact fp64 arithmetic (every prime below 2^50).  A thread forms OCP outputs from each pair of
+// The slot-wise sum in exact fp64 arithmetic (every prime below 2^50).  A thread forms OCP outputs (4, or 8 when there
+// are at least 8) from each pair of
 // ciphertext words it loads (the inputs are re-read once per group of OCP outputs, not once per output), and two
 // (tap, channel) terms are loaded before their arithmetic.
-#define OCP 4
 #define ICP 2
 // WITH_X2: the optional second input is present (a separate instantiation, so that the common form keeps its
 // straight-line loads)
-template <bool WITH_X2>
+template <bool WITH_X2, int OCP>
 __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes, MacArgs g, int log_n) {
     const u64 n = (u64)1 << log_n;
     const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
@@ -428,10 +428,13 @@ static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, 
     if (!fprimes || !g.w || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || !mac_shape_ok(g, log_n)) return hipErrorInvalidValue;
     if (g.w_words && (u64)g.l * ((u64)1 << log_n) > g.w_words) return hipErrorInvalidValue;   // plaintexts shorter than the limbs walked
     if (g.x2 && (!g.out2 || g.lq <= 0 || g.lq > g.l || g.x2_words == 0)) return hipErrorInvalidValue;
-    dim3 grid((1u << log_n) / NT, g.l, batch * ((g.OC + OCP - 1) / OCP));
+    const int ocp = g.OC >= 8 ? 8 : 4;
+    dim3 grid((1u << log_n) / NT, g.l, batch * ((g.OC + ocp - 1) / ocp));
     ProfScope prof__("plain_mac_fp_kernel", st);
-    if (g.x2) hipLaunchKernelGGL(plain_mac_fp_kernel<true>, grid, dim3(NT), 0, st, fprimes, g, log_n);
-    else hipLaunchKernelGGL(plain_mac_fp_kernel<false>, grid, dim3(NT), 0, st, fprimes, g, log_n);
+    if (g.x2 && ocp == 8) hipLaunchKernelGGL((plain_mac_fp_kernel<true, 8>), grid, dim3(NT), 0, st, fprimes, g, log_n);
+    else if (g.x2) hipLaunchKernelGGL((plain_mac_fp_kernel<true, 4>), grid, dim3(NT), 0, st, fprimes, g, log_n);
+    else if (ocp == 8) hipLaunchKernelGGL((plain_mac_fp_kernel<false, 8>), grid, dim3(NT), 0, st, fprimes, g, log_n);
+    else hipLaunchKernelGGL((plain_mac_fp_kernel<false, 4>), grid, dim3(NT), 0, st, fprimes, g, log_n);
     return hipGetLastError();
 }
 
