@@ -205,9 +205,12 @@ int hisa_ct_random_batch(hisa_ctx* ctx, size_t n, uint32_t limbs, double scale, 
  * the lowest limb count any ciphertext reached, and the sorted left-rotation
  * amounts that needed a key (at most cap of them into host rot_steps, the count
  * into *n; rot_steps may be null).  Handles made during the analysis stay valid
- * handles and are freed as usual.  Not re-entrant: begin while already in
- * analysis mode, or end outside it, is HISA_ERR_ARG.  One context per thread at
- * a time may be in analysis mode. */
+ * handles and are freed as usual.  Keys and plans cannot be made in this mode
+ * (hisa_keygen, hisa_gen_rot_keys, hisa_*_prepare: HISA_ERR_ARG -- they would
+ * hold no data), and a convolution asked for shared_moddown is counted in its
+ * term-by-term schedule.  Not re-entrant: begin while already in analysis mode,
+ * or end outside it, is HISA_ERR_ARG.  One context per thread at a time may be
+ * in analysis mode. */
 typedef struct {
     uint64_t rot_left;     /* key-switched rotations (rotRight counts here too) */
     uint64_t rot_shared;   /* of those, rotations that reused another rotation's decomposition */
