@@ -472,3 +472,34 @@ def test_shared_moddown_convolutions_bit_exact():
     with pytest.raises(hisa.HisaError):
         g2.conv2d(t2, synth.conv_weights(1, 3, 3, 1, 1), 3, 3, shared_moddown=True)
     g2.close()
+
+
+def test_new_layer_entry_points_reject_bad_arguments():
+    """Error paths of the CHW / matmul / layout entry points: every one is a host-side check that returns an error
+    code (nothing reaches a kernel)."""
+    from paper_1810_00845_amd import hisa, synth
+    g = hisa.Context(12, [50, 40, 40], 3, 50, 21)
+    x = synth.image(81, 4, 4, 4)[None]
+    t = g.tensor_encrypt(x, 2.0 ** 40, 3, h_stride=4)
+    with pytest.raises(hisa.HisaError):
+        g.matmul_geometry(t, 3, 0)                                   # no replicas at all
+    with pytest.raises(hisa.HisaError):
+        g.tensor_to_chw(t, 4, 1024)                                  # four blocks of 1024 slots do not fit 2048
+    with pytest.raises(hisa.HisaError):
+        g.tensor_to_chw(t, 4, 0)                                     # no channel stride
+    with pytest.raises(hisa.HisaError):
+        g.matmul(t, synth.fc_weights(1, 3, 4, 4, 4), 4)              # no rotation keys yet
+    with pytest.raises(hisa.HisaError):
+        g.rot_left_hoisted_batch(t.cts, [1, 2, 3])                   # nor here; nothing is queued, nothing leaks
+    c = g.tensor_encrypt(x, 2.0 ** 40, 3, h_stride=4, c_inner=4, c_stride=16)
+    with pytest.raises(hisa.HisaError):                              # 9 x 9 taps x 4 blocks > 256 rotation amounts
+        g.conv2d(c, np.zeros((9, 9, 4, 4)), 9, 9, pad_same=True, mode=2)
+    with pytest.raises(hisa.HisaError):                              # 4 blocks of 16 slots neither fill 2048 slots ...
+        pass_through = g.tensor_encrypt(x, 2.0 ** 40, 3, h_stride=4, c_inner=4, c_stride=300)
+        g.conv2d(pass_through, np.zeros((1, 1, 4, 4)), 1, 1, mode=2)  # ... nor leave room for a copy: 2 x 4 x 300 > 2048
+    with pytest.raises(hisa.HisaError):
+        g.fc_prepare(c, synth.fc_weights(1, 3, 4, 4, 4))             # fc is HW-tiled only
+    low = g.tensor_encrypt(x, 2.0 ** 40, 1, h_stride=4)
+    with pytest.raises(hisa.HisaError):
+        g.tensor_mask(low)                                           # no level to rescale into
+    g.close()
