@@ -256,7 +256,7 @@ __device__ __forceinline__ uint32_t galois_src_fp(uint32_t i, u64 g, int log_n) 
 #ifndef NTT_FP_MIN_WAVES
 #define NTT_FP_MIN_WAVES(K3) ((K3) >= 4 ? 4 : 2)
 #endif
-template <int K3, int MODE>
+template <int K3, int MODE, bool PAIR>
 __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp_kernel(FpArgs a, FpTask tk) {
     typedef Geo<K3> G;
     extern __shared__ uint32_t lds[];
@@ -273,8 +273,10 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     // digits, so one pass over them forms both sums (half the loads per sum; the loads, not the arithmetic, bound that
     // stage).  The second sum waits in this workgroup's scratch rows (every thread reads back what it wrote itself)
     // while the first is transformed, and is transformed next.
+    // PAIR = false: one target limb per task (few source limbs: the loads are not what bounds the stage then, and the
+    // round trip of the second sum through the scratch rows costs more than the shared pass saves).
     constexpr bool CONV = (MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL);
-    constexpr int SUB = CONV ? 2 : 1;
+    constexpr int SUB = (CONV && PAIR) ? 2 : 1;
     const int per_entry = (tk.period + SUB - 1) / SUB;
     for (int task = xcd * per_xcd + slot; task < task_end; task += slots) {
     const u64 b = task / per_entry;
@@ -321,7 +323,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         const rsrc_t scr = make_rsrc(a.scratch + (u64)blockIdx.x * G::N, LB);
         if (half == 0) {
             const rsrc_t y = make_rsrc(a.y + b * a.y_bs + (u64)a.y_pos0 * G::N, (uint32_t)a.conv_a * LB);
-            const bool two = e + 1 < tk.period;
+            const bool two = PAIR && e + 1 < tk.period;
             const int prime2 = tk.prime[two ? e + 1 : e];
             const double p2 = as_const(&a.fprimes[prime2].p)[0], pinv2 = as_const(&a.fprimes[prime2].p)[1];
             double bufa[8], bufb[8];
@@ -350,7 +352,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
 #pragma unroll
                         for (int k = 0; k < 8; k++) {
                             v[c * 8 + k] += fp_mulmod(bufa[k], h1, p, pinv);
-                            w2[k] += fp_mulmod(bufa[k], h2, p2, pinv2);
+                            if (PAIR) w2[k] += fp_mulmod(bufa[k], h2, p2, pinv2);
                         }
                     }
                     SCHED_FENCE();
@@ -370,7 +372,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
 #pragma unroll
                         for (int k = 0; k < 8; k++) {
                             v[c * 8 + k] += fp_mulmod(bufb[k], h1, p, pinv);
-                            w2[k] += fp_mulmod(bufb[k], h2, p2, pinv2);
+                            if (PAIR) w2[k] += fp_mulmod(bufb[k], h2, p2, pinv2);
                         }
                     } else {
 #pragma unroll
@@ -378,7 +380,10 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
                     }
                     if ((i & 6) == 6) {   // after every eight terms
 #pragma unroll
-                        for (int k = 0; k < 8; k++) { v[c * 8 + k] = fp_norm(v[c * 8 + k], p, pinv); w2[k] = fp_norm(w2[k], p2, pinv2); }
+                        for (int k = 0; k < 8; k++) {
+                            v[c * 8 + k] = fp_norm(v[c * 8 + k], p, pinv);
+                            if (PAIR) w2[k] = fp_norm(w2[k], p2, pinv2);
+                        }
                     }
                 }
 #pragma unroll
@@ -391,14 +396,16 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
                 // both sums, their buffers and all 32 rows live the stage would not fit the register file.  The part
                 // is free here: the wave is past its last transpose of the previous task, and the workgroup-wide
                 // transpose of this one starts behind a barrier that this wave has not reached yet.
-                if (c == 1) {
+                if (PAIR && c == 1) {
 #pragma unroll
                     for (int r = 0; r < 16; r++) park[r * 64] = v[r];
                 }
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            if (PAIR) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
 #pragma unroll
-            for (int r = 0; r < 16; r++) v[r] = park[r * 64];
+                for (int r = 0; r < 16; r++) v[r] = park[r * 64];
+            }
         } else {
             // the partner's sum, left in the scratch rows by the step before (read past the L1: the lines may be
             // there from an earlier task)
@@ -543,14 +550,14 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     }  // task loop
 }
 
-template <int K3, int MODE>
+template <int K3, int MODE, bool PAIR>
 static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
     DRY_RUN_RETURN();
     typedef Geo<K3> G;
     static bool attr_set = false;
     const size_t lds_bytes = (size_t)G::LDS_WORDS * 4;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)ntt_fp_kernel<K3, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        hipError_t e = hipFuncSetAttribute((const void*)ntt_fp_kernel<K3, MODE, PAIR>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -563,7 +570,7 @@ static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hip
         {"ntt_fp_kernel<5, 0>", "ntt_fp_kernel<5, 1>", "ntt_fp_kernel<5, 2>", "ntt_fp_kernel<5, 3>", "ntt_fp_kernel<5, 4>"}};
     ProfScope prof__(names[K3 - 2][MODE], st);
     FpArgs args = a;
-    constexpr bool conv_mode = MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL;
+    constexpr bool conv_mode = (MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL) && PAIR;   // two target limbs per task
     args.n_tasks = (int)(n_batch * (conv_mode ? (tk.period + 1) / 2 : tk.period));
     static int n_cu = 0;
     if (!n_cu) {
@@ -576,7 +583,7 @@ static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hip
     static int per_cu = 0;
     if (!per_cu) {
         int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ntt_fp_kernel<K3, MODE>, G::THREADS, lds_bytes) !=
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ntt_fp_kernel<K3, MODE, PAIR>, G::THREADS, lds_bytes) !=
                 hipSuccess || nb < 1)
             nb = 1;
         per_cu = nb;
@@ -592,17 +599,32 @@ static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hip
 #ifdef NTT_FP_NONPERSISTENT
     grid = need;
 #endif
-    hipLaunchKernelGGL((ntt_fp_kernel<K3, MODE>), dim3(grid), dim3(G::THREADS), lds_bytes, st, args, tk);
+    hipLaunchKernelGGL((ntt_fp_kernel<K3, MODE, PAIR>), dim3(grid), dim3(G::THREADS), lds_bytes, st, args, tk);
     return hipGetLastError();
 }
 
+// Conversions from at least this many source limbs take two target limbs per pass (measured on batches of 64: with
+// 6 and 16 source limbs the shared pass gains 5-11 %, with 1 to 4 it loses 5-20 % to the scratch round trip).
+#ifndef NTT_FP_PAIR_MIN_SOURCES
+#define NTT_FP_PAIR_MIN_SOURCES 5
+#endif
 template <int MODE>
 static hipError_t dispatch_k3(int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
+    constexpr bool conv_mode = MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL;
+    if (conv_mode && a.conv_a < NTT_FP_PAIR_MIN_SOURCES) {
+        switch (log_n) {
+            case 12: return launch_one<2, MODE, !conv_mode>(a, tk, n_batch, st);
+            case 13: return launch_one<3, MODE, !conv_mode>(a, tk, n_batch, st);
+            case 14: return launch_one<4, MODE, !conv_mode>(a, tk, n_batch, st);
+            case 15: return launch_one<5, MODE, !conv_mode>(a, tk, n_batch, st);
+            default: return hipErrorInvalidValue;
+        }
+    }
     switch (log_n) {
-        case 12: return launch_one<2, MODE>(a, tk, n_batch, st);
-        case 13: return launch_one<3, MODE>(a, tk, n_batch, st);
-        case 14: return launch_one<4, MODE>(a, tk, n_batch, st);
-        case 15: return launch_one<5, MODE>(a, tk, n_batch, st);
+        case 12: return launch_one<2, MODE, true>(a, tk, n_batch, st);
+        case 13: return launch_one<3, MODE, true>(a, tk, n_batch, st);
+        case 14: return launch_one<4, MODE, true>(a, tk, n_batch, st);
+        case 15: return launch_one<5, MODE, true>(a, tk, n_batch, st);
         default: return hipErrorInvalidValue;
     }
 }
