@@ -603,15 +603,31 @@ static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hip
     return hipGetLastError();
 }
 
-// Conversions from at least this many source limbs take two target limbs per pass (measured on batches of 64: with
-// 6 and 16 source limbs the shared pass gains 5-11 %, with 1 to 4 it loses 5-20 % to the scratch round trip).
-#ifndef NTT_FP_PAIR_MIN_SOURCES
-#define NTT_FP_PAIR_MIN_SOURCES 5
-#endif
+// Two target limbs per pass, or one?  A paired task costs r(a) times a single one (a = source limbs: 1.71 at a = 6
+// from the tuning harness, falling slowly with more sources, rising with fewer, where the scratch round trip of the
+// second sum outweighs the shared loads) and there are half as many; what decides is the number of rounds the chip
+// needs for the tasks of the launch.  Measured on batches of 64 at N = 2^15: a = 6 and 16 gain 5-11 % paired, a <= 4
+// lose 5-20 %, a = 5 gains with 15 target limbs (2 rounds against 4) and loses with 10 (2 against 3); launches that
+// do not fill the chip once are always faster unpaired (twice the parallelism, shorter tasks).
+static bool pair_conversions(int log_n, int conv_a, int period, u64 n_batch) {
+    static int n_cu = 0;
+    if (!n_cu) {
+        hipDeviceProp_t prop;
+        int dev = 0;
+        n_cu = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 8)
+                   ? prop.multiProcessorCount : 256;
+    }
+    const u64 resident = (u64)n_cu << (log_n >= 15 ? 0 : 15 - log_n);   // workgroups the chip holds at once: 16 waves a compute unit
+    const u64 rounds_p = (n_batch * (u64)((period + 1) / 2) + resident - 1) / resident;
+    const u64 rounds_u = (n_batch * (u64)period + resident - 1) / resident;
+    const double r = conv_a >= 6 ? fmax(1.6, 1.71 - 0.01 * (conv_a - 6)) : 1.71 + 0.07 * (6 - conv_a);
+    return (double)rounds_p * r < (double)rounds_u;
+}
+
 template <int MODE>
 static hipError_t dispatch_k3(int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
     constexpr bool conv_mode = MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL;
-    if (conv_mode && a.conv_a < NTT_FP_PAIR_MIN_SOURCES) {
+    if (conv_mode && !pair_conversions(log_n, a.conv_a, tk.period, n_batch)) {
         switch (log_n) {
             case 12: return launch_one<2, MODE, !conv_mode>(a, tk, n_batch, st);
             case 13: return launch_one<3, MODE, !conv_mode>(a, tk, n_batch, st);
