@@ -1199,23 +1199,42 @@ static int key_switch_modup_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois
         a.yout = x.y.as<double>(); a.yout_bs = (u64)l * n;
         HIP_TRY(ctx, launch_ntt_fp(FP_INV_TO_Y, log_n, a, tk, B, st));
     }
-    for (int j = 0; j < x.digits; j++) {  // B
+    // B.  One launch per digit, or one for all digits (single target limbs) where that takes fewer rounds of
+    // workgroups: small batches, whose per-digit launches would each run one sparse round after the other
+    size_t all_targets = 0;
+    double separate = 0.0;
+    for (int j = 0; j < x.digits; j++) {
+        const int own = std::min(j * alpha + alpha, l) - j * alpha;
+        all_targets += (size_t)(x.ext_limbs - own);
+        separate += fp_conversion_cost(log_n, own, x.ext_limbs - own, B, nullptr);
+    }
+    const u64 resident = fp_resident_workgroups(log_n);
+    const bool one_launch = x.digits > 1 && x.digits <= FP_MAX_DIGITS && all_targets <= HISA_MAX_PRIMES &&
+                            (double)((B * all_targets + resident - 1) / resident) <= separate;
+    FpArgs a = base;
+    FpTask tk = {};
+    int cnt = 0;
+    a.y = x.y.as<double>(); a.y_bs = (u64)l * n; a.total = total;
+    a.out = x.ext.u(); a.out_bs = x.ext_bs;
+    for (int j = 0; j < x.digits; j++) {
         const int lo = j * alpha, hi = std::min(lo + alpha, l);
         ConvTable* tab;
         TRY(modup_table(ctx, j, hi - lo, &tab));
-        FpArgs a = base;
-        FpTask tk = {};
-        int cnt = 0;
+        const int slot = one_launch ? j : 0;
+        a.dg[slot].hat = tab->d_hat_f; a.dg[slot].y_pos0 = lo; a.dg[slot].conv_a = hi - lo;
+        if (!one_launch) cnt = 0;
         for (int e = 0; e < x.ext_limbs; e++) {
             if (e >= lo && e < hi) continue;
             tk.pos[cnt] = (int16_t)(j * x.ext_limbs + e);
             tk.prime[cnt] = (int16_t)(e < l ? e : L + (e - l));
+            tk.digit[cnt] = (int8_t)slot;
             cnt++;
         }
-        tk.period = cnt;
-        a.y = x.y.as<double>(); a.y_bs = (u64)l * n; a.y_pos0 = lo; a.conv_a = hi - lo; a.total = total; a.hat = tab->d_hat_f;
-        a.out = x.ext.u(); a.out_bs = x.ext_bs;
-        HIP_TRY(ctx, launch_ntt_fp(FP_FWD_CONV, log_n, a, tk, B, st));
+        if (!one_launch || j == x.digits - 1) {
+            tk.period = cnt;
+            a.n_digits = one_launch ? x.digits : 1;
+            HIP_TRY(ctx, launch_ntt_fp(FP_FWD_CONV, log_n, a, tk, B, st));
+        }
     }
     return HISA_OK;
 }

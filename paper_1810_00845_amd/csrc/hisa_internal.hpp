@@ -236,8 +236,10 @@ struct FpTask {
     int32_t period;                      // tasks per batch entry
     int16_t pos[HISA_MAX_PRIMES];        // limb position of the task's polynomial inside a batch entry (output side)
     int16_t prime[HISA_MAX_PRIMES];      // its prime
+    int8_t digit[HISA_MAX_PRIMES];       // base-conversion modes: which FpArgs::dg entry describes its source limbs
 };
 
+#define FP_MAX_DIGITS 8  // digits whose conversions one launch can hold
 #define FP_MAX_STEPS 32   // rotations per launch of the shared-decomposition path
 struct FpArgs {
     const FpPrime* fprimes;
@@ -255,6 +257,10 @@ struct FpArgs {
     const double* y; u64 y_bs;         // [batch][..][N] centred doubles, source limbs at y_pos0 ..
     int y_pos0, conv_a, total;
     const double* hat;                 // [a][total] (D/c_i) mod t, centred
+    // Several digits in one launch (each task entry names its digit in FpTask::digit): n_digits > 1 and dg[] filled
+    // in by the caller.  n_digits = 0: one digit, the launcher copies y_pos0, conv_a, hat into dg[0].
+    int n_digits;
+    struct Digit { const double* hat; int y_pos0, conv_a; } dg[FP_MAX_DIGITS];
     double* scratch; int scratch_polys; // one polynomial of doubles per workgroup (at most scratch_polys workgroups)
     // final combine (FP_FWD_CONV_FINAL): batch entries are (ciphertext, polynomial) pairs
     const u64* acc; u64 acc_bs; int acc_pos_shift;
@@ -268,6 +274,11 @@ struct FpArgs {
     uint32_t galois_tab[FP_MAX_STEPS];
 };
 hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st);
+// workgroups of the transform kernel that the chip holds at once (about: 16 waves per compute unit)
+u64 fp_resident_workgroups(int log_n);
+// estimated time of one base-conversion launch (conv_a source limbs, `period` target limbs per batch entry), in units
+// of one single-target task: rounds of workgroups times the task's relative cost, for the cheaper of the two forms
+double fp_conversion_cost(int log_n, int conv_a, int period, u64 n_batch, bool* paired);
 
 // acc[b][p][x] = sum_j e_j[x] * key[j][p][prime(x)] in fp64; e_j[x] comes from ext unless x lies in digit j, then
 // from own_src (the NTT-form input itself, read through sigma_g when galois != 0)

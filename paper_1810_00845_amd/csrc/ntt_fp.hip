@@ -322,7 +322,10 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         // use, which would expose one memory latency per element).
         const rsrc_t scr = make_rsrc(a.scratch + (u64)blockIdx.x * G::N, LB);
         if (half == 0) {
-            const rsrc_t y = make_rsrc(a.y + b * a.y_bs + (u64)a.y_pos0 * G::N, (uint32_t)a.conv_a * LB);
+            const int dgi = tk.digit[e];
+            const int conv_a = a.dg[dgi].conv_a;
+            const double* hat = a.dg[dgi].hat;
+            const rsrc_t y = make_rsrc(a.y + b * a.y_bs + (u64)a.dg[dgi].y_pos0 * G::N, (uint32_t)conv_a * LB);
             const bool two = PAIR && e + 1 < tk.period;
             const int prime2 = tk.prime[two ? e + 1 : e];
             const double p2 = as_const(&a.fprimes[prime2].p)[0], pinv2 = as_const(&a.fprimes[prime2].p)[1];
@@ -337,8 +340,8 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
                 for (int k = 0; k < 8; k++) { v[c * 8 + k] = 0.0; w2[k] = 0.0; }
                 // rows 8c .. 8c+7 of source limbs i and i+1 per turn (bufa, then bufb); the batch after the last
                 // limb is the first one of the next eight rows
-                for (int i = 0; i < a.conv_a; i += 2) {
-                    const bool has1 = i + 1 < a.conv_a;
+                for (int i = 0; i < conv_a; i += 2) {
+                    const bool has1 = i + 1 < conv_a;
                     SCHED_FENCE();
                     {
                         const uint32_t off = has1 ? (uint32_t)(i + 1) * LB + (uint32_t)((c * 8) << G::TB) * 8u
@@ -348,7 +351,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
                     }
                     SCHED_FENCE();
                     {
-                        const double h1 = as_const(a.hat)[(u64)i * a.total + prime], h2 = as_const(a.hat)[(u64)i * a.total + prime2];
+                        const double h1 = as_const(hat)[(u64)i * a.total + prime], h2 = as_const(hat)[(u64)i * a.total + prime2];
 #pragma unroll
                         for (int k = 0; k < 8; k++) {
                             v[c * 8 + k] += fp_mulmod(bufa[k], h1, p, pinv);
@@ -357,7 +360,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
                     }
                     SCHED_FENCE();
                     {
-                        const bool more = i + 2 < a.conv_a;
+                        const bool more = i + 2 < conv_a;
                         const uint32_t off = more ? (uint32_t)(i + 2) * LB + (uint32_t)((c * 8) << G::TB) * 8u
                                                   : (uint32_t)(((c < 3 ? c + 1 : c) * 8) << G::TB) * 8u;
                         if (has1) {   // otherwise bufb already holds the first batch of the next rows: hand it over below
@@ -367,8 +370,8 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
                     }
                     SCHED_FENCE();
                     if (has1) {
-                        const double h1 = as_const(a.hat)[(u64)(i + 1) * a.total + prime],
-                                     h2 = as_const(a.hat)[(u64)(i + 1) * a.total + prime2];
+                        const double h1 = as_const(hat)[(u64)(i + 1) * a.total + prime],
+                                     h2 = as_const(hat)[(u64)(i + 1) * a.total + prime2];
 #pragma unroll
                         for (int k = 0; k < 8; k++) {
                             v[c * 8 + k] += fp_mulmod(bufb[k], h1, p, pinv);
@@ -609,7 +612,7 @@ static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hip
 // needs for the tasks of the launch.  Measured on batches of 64 at N = 2^15: a = 6 and 16 gain 5-11 % paired, a <= 4
 // lose 5-20 %, a = 5 gains with 15 target limbs (2 rounds against 4) and loses with 10 (2 against 3); launches that
 // do not fill the chip once are always faster unpaired (twice the parallelism, shorter tasks).
-static bool pair_conversions(int log_n, int conv_a, int period, u64 n_batch) {
+u64 fp_resident_workgroups(int log_n) {
     static int n_cu = 0;
     if (!n_cu) {
         hipDeviceProp_t prop;
@@ -617,17 +620,30 @@ static bool pair_conversions(int log_n, int conv_a, int period, u64 n_batch) {
         n_cu = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 8)
                    ? prop.multiProcessorCount : 256;
     }
-    const u64 resident = (u64)n_cu << (log_n >= 15 ? 0 : 15 - log_n);   // workgroups the chip holds at once: 16 waves a compute unit
+    return (u64)n_cu << (log_n >= 15 ? 0 : 15 - log_n);   // 16 waves a compute unit
+}
+
+// estimated time of one conversion launch, in units of one unpaired task, and whether pairing gives it
+double fp_conversion_cost(int log_n, int conv_a, int period, u64 n_batch, bool* paired) {
+    const u64 resident = fp_resident_workgroups(log_n);
     const u64 rounds_p = (n_batch * (u64)((period + 1) / 2) + resident - 1) / resident;
     const u64 rounds_u = (n_batch * (u64)period + resident - 1) / resident;
     const double r = conv_a >= 6 ? fmax(1.6, 1.71 - 0.01 * (conv_a - 6)) : 1.71 + 0.07 * (6 - conv_a);
-    return (double)rounds_p * r < (double)rounds_u;
+    const bool pair = (double)rounds_p * r < (double)rounds_u;
+    if (paired) *paired = pair;
+    return pair ? (double)rounds_p * r : (double)rounds_u;
+}
+
+static bool pair_conversions(int log_n, int conv_a, int period, u64 n_batch) {
+    bool pair = false;
+    fp_conversion_cost(log_n, conv_a, period, n_batch, &pair);
+    return pair;
 }
 
 template <int MODE>
 static hipError_t dispatch_k3(int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
     constexpr bool conv_mode = MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL;
-    if (conv_mode && !pair_conversions(log_n, a.conv_a, tk.period, n_batch)) {
+    if (conv_mode && (a.n_digits > 1 || !pair_conversions(log_n, a.conv_a, tk.period, n_batch))) {
         switch (log_n) {
             case 12: return launch_one<2, MODE, !conv_mode>(a, tk, n_batch, st);
             case 13: return launch_one<3, MODE, !conv_mode>(a, tk, n_batch, st);
@@ -645,9 +661,24 @@ static hipError_t dispatch_k3(int log_n, const FpArgs& a, const FpTask& tk, u64 
     }
 }
 
-hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
+hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a_in, const FpTask& tk, u64 n_batch, hipStream_t st) {
     DRY_RUN_RETURN();
     if (n_batch == 0 || tk.period <= 0) return hipSuccess;
+    FpArgs a = a_in;
+    if (mode == FP_FWD_CONV || mode == FP_FWD_CONV_FINAL) {
+        if (a.n_digits < 0 || a.n_digits > FP_MAX_DIGITS || tk.period > HISA_MAX_PRIMES) return hipErrorInvalidValue;
+        if (a.n_digits == 0) {
+            a.n_digits = 1;
+            a.dg[0].hat = a.hat; a.dg[0].y_pos0 = a.y_pos0; a.dg[0].conv_a = a.conv_a;
+        } else {
+            // the single-digit fields then describe the first digit (the size checks below read them)
+            a.hat = a.dg[0].hat; a.y_pos0 = a.dg[0].y_pos0; a.conv_a = a.dg[0].conv_a;
+        }
+        for (int d = 0; d < a.n_digits; d++)
+            if (!a.dg[d].hat || a.dg[d].conv_a <= 0 || a.dg[d].y_pos0 < 0) return hipErrorInvalidValue;
+        for (int e = 0; e < tk.period; e++)
+            if (tk.digit[e] < 0 || tk.digit[e] >= a.n_digits) return hipErrorInvalidValue;
+    }
     // every pointer a mode dereferences must be set: a missing one is a host error, not a device fault
     if (tk.period > HISA_MAX_PRIMES || !a.fprimes) return hipErrorInvalidValue;
     for (int e = 0; e < tk.period; e++)
