@@ -469,11 +469,18 @@ def chw_conv_geometry(o: Oracle, t: OTensor, fh, fw, pad_same=False):
     return wrap, amounts
 
 
-def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False, shared_moddown=False):
+def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False, shared_moddown=False, schedule="in"):
     """w[FH][FW][IC][OC] on a clean CHW-tiled tensor -> clean CHW-tiled tensor with the same channel blocks.  The
     plaintext of (tap, d, input ciphertext j, output ciphertext g) holds, on the valid output positions of block b,
     the weight from input channel j c_inner + (b + d) mod c_inner to output channel g c_inner + b (zero where either
-    does not exist), encoded at the scale of the last modulus.  Returns (output, the integers used)."""
+    does not exist), encoded at the scale of the last modulus.  Returns (output, the integers used).
+
+    schedule "in": the inputs are rotated by (tap, d) and the products summed.  schedule "out" (the reduction over the
+    channels of a ciphertext done after the multiplication, Sec. "CHW-tiled Homomorphic Convolution 2-d"): the inputs
+    are rotated by the taps only, the products of diagonal d are summed where the input channels lie -- the plaintext
+    holds the same weight d blocks further up, under input block b + d -- and the c_inner sums are rotated down by d
+    blocks and added, with one division by P for the whole sum (SharedModDown)."""
+    assert schedule in ("in", "out")
     fh, fw, ic_n, oc_n = w.shape
     assert ic_n == t.channels
     ci, cs = t.c_inner, t.c_stride
@@ -491,13 +498,14 @@ def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False, shared_moddow
         for b in range(ci):
             ic, oc = j * ci + (b + d) % ci, g * ci + b
             if ic < ic_n and oc < oc_n:
-                z[plane + b * cs] = float(w[fy, fx, ic, oc])
+                at = b if schedule == "in" else b + d     # behind the blocks lies their copy (or, cyclically, block 0)
+                z[(plane + at * cs) % o.slots] = float(w[fy, fx, ic, oc])
         coeffs[fy, fx, d, j, g] = o.encode_coeffs(z, pt_scale)
     ints = {"pt_coeffs": coeffs, "pt_scale": pt_scale}
-    return conv2d_chw_fixed(o, t, ints, oc_n, fh, fw, stride, pad_same, shared_moddown), ints
+    return conv2d_chw_fixed(o, t, ints, oc_n, fh, fw, stride, pad_same, shared_moddown, schedule), ints
 
 
-def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, shared_moddown=False):
+def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, shared_moddown=False, schedule="in"):
     ci = t.c_inner
     wrap, amounts = chw_conv_geometry(o, t, fh, fw, pad_same)
     if pad_same:
@@ -510,6 +518,24 @@ def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same
         xs = t.cts[b * per_in:(b + 1) * per_in]
         if wrap:
             xs = [o.add(x, o.rot_right(x, wrap)) for x in xs]
+        if schedule == "out":
+            # amounts[fy][fx][0] is the tap's own amount, d * c_stride the diagonal's
+            by_tap = {(j, fy, fx): o.rot_left(xs[j], amounts[fy][fx][0])
+                      for j in range(per_in) for fy in range(fh) for fx in range(fw)}
+            for g in range(per_out):
+                sums = []
+                for d in range(ci):
+                    acc = None
+                    for fy in range(fh):
+                        for fx in range(fw):
+                            for j in range(per_in):
+                                pt = o.pt_from_coeffs(ints["pt_coeffs"][fy, fx, d, j, g], ints["pt_scale"], xs[j].limbs)
+                                temp = o.mul_plain(by_tap[(j, fy, fx)], pt)
+                                acc = temp if acc is None else o.add(acc, temp)
+                    sums.append(acc)
+                total = SharedModDown(o, sums).total([(d, d * t.c_stride, 1, None) for d in range(ci)], sums[0].scale)
+                outs.append(o.div_scalar(total, o.max_scalar_div(total, float("inf"))))
+            continue
         # the rotations do not depend on the output ciphertext: computed once
         shared = SharedModDown(o, xs) if shared_moddown else None
         rotated = {} if shared_moddown else {
@@ -534,9 +560,13 @@ def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same
     return OTensor(outs, t.batch, oc_n, oh, ow, t.h_stride * stride, t.w_stride * stride, t.offset, 1, ci, t.c_stride)
 
 
-def rot_steps_conv_chw(o: Oracle, t: OTensor, fh, fw, pad_same=False):
+def rot_steps_conv_chw(o: Oracle, t: OTensor, fh, fw, pad_same=False, schedule="in"):
     wrap, amounts = chw_conv_geometry(o, t, fh, fw, pad_same)
-    steps = {a for plane in amounts for row in plane for a in row} | ({o.slots - wrap} if wrap else set())
+    if schedule == "out":
+        steps = {row[0] for plane in amounts for row in plane} | {(d * t.c_stride) % o.slots for d in range(t.c_inner)}
+    else:
+        steps = {a for plane in amounts for row in plane for a in row}
+    steps |= {o.slots - wrap} if wrap else set()
     return sorted(steps - {0})
 
 

@@ -243,6 +243,53 @@ def test_chw_conv_matches_plain_conv_and_op_counts():
         assert np.abs(layers.tensor_decrypt(o, valid) - plain_net.conv2d(x, w)).max() <= 1e-3
 
 
+def test_chw_conv_output_side_schedule():
+    """The schedule that reduces over the channels of a ciphertext after the multiplication: against the fp64
+    convolution (VALID and SAME, cyclic blocks and blocks with their copy behind them, ragged last ciphertexts), clean
+    outputs, the same result as the input-side schedule up to noise, and the counts: (taps - 1) rotations per input
+    ciphertext, c_inner - 1 key switches per output ciphertext, the same multiplications."""
+    x = synth.image(43, 5, 4, 4)[None]
+    w = synth.conv_weights(44, 3, 3, 5, 6)
+    for log_n, expect_wrap in ((9, 0), (10, 256)):
+        o = Oracle(log_n, [50, 40, 40], 3, 55, seed=16)
+        t = layers.tensor_encrypt_chw(o, x, 2.0 ** 40, 3, c_inner=4, c_stride=64, h_stride=6, offset=7)
+        steps_out = layers.rot_steps_conv_chw(o, t, 3, 3, True, schedule="out")
+        steps_in = layers.rot_steps_conv_chw(o, t, 3, 3, True)
+        assert set(steps_out) < set(steps_in) and len(steps_out) == 8 + 3 + (1 if expect_wrap else 0)
+        assert {64, 128, 192} <= set(steps_out)
+        o.gen_rot_keys(sorted(set(steps_in) | set(layers.rot_steps_conv_chw(o, t, 3, 3))))
+        counts = {"mul_plain": 0, "rot_left": 0, "key_switch_acc": 0, "mod_down": 0, "div_scalar": 0}
+        real = {n: getattr(o, n) for n in counts}
+        for name in counts:
+            def f(*a, _n=name, **k):
+                counts[_n] += 1
+                return real[_n](*a, **k)
+            setattr(o, name, f)
+        same, _ = layers.conv2d_chw(o, t, w, pad_same=True, schedule="out")
+        for name in counts:
+            setattr(o, name, real[name])
+        per_in, per_out = 2, 2
+        assert counts["mul_plain"] == per_out * per_in * 9 * 4 and counts["div_scalar"] == per_out
+        assert counts["rot_left"] == per_in * 9 + (per_in if expect_wrap else 0)      # the centre tap is a copy
+        # per output ciphertext: c_inner - 1 key-switch accumulations, one division by P per polynomial
+        assert counts["key_switch_acc"] == per_out * 3 and counts["mod_down"] == per_out * 2
+        assert (same.channels, same.height, same.c_inner, same.c_stride, same.clean, len(same.cts)) == (6, 4, 4, 64, 1, 2)
+        want = plain_net.conv2d(x, w, pad_same=True)
+        assert np.abs(layers.tensor_decrypt(o, same) - want).max() <= 1e-3
+        z = o.decode(o.decrypt(same.cts[1])).real
+        z[np.asarray(layers.tensor_slots(same)).reshape(4, 16)[:2].reshape(-1)] = 0
+        assert np.abs(z).max() <= 1e-3
+        other, _ = layers.conv2d_chw(o, t, w, pad_same=True)
+        assert np.abs(layers.tensor_decrypt(o, same) - layers.tensor_decrypt(o, other)).max() <= 1e-5
+        valid, _ = layers.conv2d_chw(o, t, w, schedule="out")
+        assert (valid.height, valid.width) == (2, 2)
+        assert np.abs(layers.tensor_decrypt(o, valid) - plain_net.conv2d(x, w)).max() <= 1e-3
+        # a planted mistake must show: weights one block off
+        bad = np.roll(w, 1, axis=2)
+        wrong, _ = layers.conv2d_chw(o, t, bad, pad_same=True, schedule="out")
+        assert np.abs(layers.tensor_decrypt(o, wrong) - want).max() > 1e-2
+
+
 def test_mask_tensor_cleans_a_pooled_tensor():
     o = Oracle(10, [50, 40, 40], 3, 55, seed=15)
     x = synth.image(51, 3, 4, 4)[None]
