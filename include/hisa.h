@@ -178,6 +178,16 @@ int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n, int32
  * Needs every step's key (HISA_ERR_NO_KEY before any work is queued); on error no handle is returned. */
 int hisa_rot_left_hoisted_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n, const int32_t* steps,
                                 size_t n_steps, hisa_ct** out);
+/* Sums of rotated ciphertexts: out[b] = sum over s of rotLeft(in[s*n_out + b], steps[s]), for n_out outputs of
+ * n_terms terms each (the reduction over equally strided channels of Sec. "Homomorphic Tensor Operations", CHW
+ * paragraph, when each channel's term is its own ciphertext).  The terms are decomposed and multiplied by their keys
+ * one by one, but the accumulators on the l + K limbs are added up before the division by P, which is then taken once
+ * per output: the result is the sum of the rotated ciphertexts up to the rounding of that division (ciphertext bits
+ * differ from summing hisa_rot_left results).  At most one step may be a multiple of the slot count (that term is
+ * added as it is), at most 32 may rotate; all inputs share level and scale.  Needs N >= 2^12, every prime below 2^50
+ * and dnum <= 8 (HISA_ERR_ARG otherwise), and every step's key (HISA_ERR_NO_KEY before any work is queued). */
+int hisa_rot_left_sum_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n_out, const int32_t* steps, size_t n_terms,
+                            hisa_ct** out);
 int hisa_relinearize_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n);
 int hisa_rescale_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n);
 int hisa_add_batch(hisa_ctx* ctx, const hisa_ct* const* a, const hisa_ct* const* b, size_t n, hisa_ct** out);
@@ -214,6 +224,7 @@ int hisa_ct_random_batch(hisa_ctx* ctx, size_t n, uint32_t limbs, double scale, 
 typedef struct {
     uint64_t rot_left;     /* key-switched rotations (rotRight counts here too) */
     uint64_t rot_shared;   /* of those, rotations that reused another rotation's decomposition */
+    uint64_t rot_summed;   /* of those, rotations inside a sum that takes its division by P once (hisa_rot_left_sum_batch) */
     uint64_t relinearize, mul, mul_plain, mul_scalar, add, rescale;
     uint64_t mac_plain;    /* terms x * plaintext summed inside the layers' fused multiply-accumulate launches */
     uint64_t mac_scalar;   /* terms x * scalar weight summed there */

@@ -366,6 +366,45 @@ hipError_t launch_automorph_steps(const u64* in, u64 in_bs, u64* out, u64 out_bs
     return hipGetLastError();
 }
 
+// The part of a sum of rotated ciphertexts that needs no key: out[b] = (plain[b].c0 + sum_s sigma_{g[s]}(rot[s][b].c0),
+// plain[b].c1), rot entries ordered rotation-major; plain may be null (zeros).  Canonical residues in and out.
+__global__ __launch_bounds__(NT) void automorph_sum_kernel(const PrimeConst* primes, const u64* rot, u64 rot_bs, int n_rot,
+                                                           GaloisTab tab, const u64* plain, u64 plain_bs, u64* out, u64 out_bs,
+                                                           unsigned n_batch, int l, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const uint32_t i = blockIdx.x * NT + threadIdx.x;
+    const uint32_t mask = (2u << log_n) - 1;
+    const int limb = blockIdx.y;
+    const unsigned b = blockIdx.z;
+    const u64 q = primes[limb].q;
+    const uint32_t e = 2 * (__brev(i) >> (32 - log_n)) + 1;
+    u64 acc = plain ? plain[(u64)b * plain_bs + (u64)limb * n + i] : 0;
+    for (int s = 0; s < n_rot; s++) {
+        const uint32_t e2 = (uint32_t)((u64)e * tab.g[s]) & mask;
+        const uint32_t src = __brev((e2 - 1) >> 1) >> (32 - log_n);
+        acc = addmod(acc, rot[((u64)s * n_batch + b) * rot_bs + (u64)limb * n + src], q);
+    }
+    out[(u64)b * out_bs + (u64)limb * n + i] = acc;
+    out[(u64)b * out_bs + (u64)(l + limb) * n + i] = plain ? plain[(u64)b * plain_bs + (u64)(l + limb) * n + i] : 0;
+}
+
+hipError_t launch_automorph_sum(const PrimeConst* primes, const u64* rot, u64 rot_bs, int n_rot, const GaloisTab& tab,
+                                const u64* plain, u64 plain_bs, u64* out, u64 out_bs, u64 n_batch, int l, int log_n,
+                                hipStream_t st) {
+    DRY_RUN_RETURN();
+    const u64 n = (u64)1 << log_n;
+    if (!primes || !rot || !out || n_rot < 1 || n_rot > GALOIS_TAB_MAX || n_batch == 0 || n_batch > 65535 || l < 1)
+        return hipErrorInvalidValue;
+    if (rot_bs < (u64)l * n || out_bs < (u64)2 * l * n || (plain && plain_bs < (u64)2 * l * n)) return hipErrorInvalidValue;
+    for (int s = 0; s < n_rot; s++)
+        if (tab.g[s] == 0) return hipErrorInvalidValue;
+    dim3 grid((1u << log_n) / NT, l, (unsigned)n_batch);
+    ProfScope prof__("automorph_sum_kernel", st);
+    hipLaunchKernelGGL(automorph_sum_kernel, grid, dim3(NT), 0, st, primes, rot, rot_bs, n_rot, tab, plain, plain_bs, out, out_bs,
+                       (unsigned)n_batch, l, log_n);
+    return hipGetLastError();
+}
+
 // signed integer coefficients [n_pts][N] -> residues modulo primes[0..limbs-1] at out[p][0..limbs-1][N], the entries of
 // out being out_limbs limbs apart
 __global__ __launch_bounds__(NT) void reduce_i64_kernel(const PrimeConst* primes, const i64* coeffs, u64* out, int out_limbs,

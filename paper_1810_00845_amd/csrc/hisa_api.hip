@@ -1363,6 +1363,102 @@ int rotation_accumulators_fp(hisa_ctx* ctx, const u64* cts, u64 ct_bs, size_t B,
     return HISA_OK;
 }
 
+int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const int32_t* steps, size_t Bn, int l,
+                  const u64* plain, u64 plain_bs, u64* out) {
+    if (!fused_key_switch_available(ctx)) return fail(ctx, HISA_ERR_ARG, "no fused key-switch path for these parameters");
+    if (n_steps < 1 || n_steps > FP_MAX_STEPS || Bn == 0 || l < 1) return fail(ctx, HISA_ERR_ARG, "bad rotation sum");
+    const size_t n = ctx->N;
+    const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total, ext_limbs = l + K;
+    if (ct_bs < (u64)2 * l * n || (plain && plain_bs < (u64)2 * l * n)) return fail(ctx, HISA_ERR_ARG, "bad rotation sum strides");
+    IpSteps st = {};
+    GaloisTab tab = {};
+    for (int s = 0; s < n_steps; s++) {
+        const u64 g = galois_of(ctx, steps[s]);
+        if (g == 0) return fail(ctx, HISA_ERR_ARG, "rotation by a multiple of the slot count");
+        if (t_analysis) {
+            const int32_t half = (int32_t)(ctx->N / 2);
+            t_analysis->steps.insert(((steps[s] % half) + half) % half);
+            continue;
+        }
+        auto it = ctx->keys.find(g);
+        if (it == ctx->keys.end())
+            return fail(ctx, HISA_ERR_NO_KEY, "no rotation key for %d slots (galois element %llu)", steps[s], (unsigned long long)g);
+        st.key[s] = it->second.data;
+        st.galois[s] = (uint32_t)g;
+        tab.g[s] = (uint32_t)g;
+    }
+    if (t_analysis) {
+        t_analysis->c.rot_left += (u64)n_steps * Bn;
+        t_analysis->c.rot_summed += (u64)n_steps * Bn;
+        t_analysis->c.key_switch_calls += 1;
+        return HISA_OK;
+    }
+    const size_t E = (size_t)n_steps * Bn;
+    FpExt x(ctx, E, l, K, alpha);
+    Temp acc(ctx, Bn * 2 * (size_t)ext_limbs * n * sizeof(u64));
+    Temp addend(ctx, Bn * 2 * (size_t)l * n * sizeof(u64));
+    if (!x.ok() || !acc.ok() || !addend.ok()) return HISA_ERR_OOM;
+    const u64* c1 = rot + (size_t)l * n;
+    TRY(key_switch_modup_fp(ctx, c1, ct_bs, 0, E, x));
+    HIP_TRY(ctx, launch_inner_product_sum_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, st, n_steps, total,
+                                             c1, ct_bs, acc.u(), (u64)2 * ext_limbs * n, Bn, (int)ctx->log_n, ctx->stream));
+    HIP_TRY(ctx, launch_automorph_sum(ctx->d_primes, rot, ct_bs, n_steps, tab, plain, plain_bs, addend.u(), (u64)2 * l * n, Bn, l,
+                                      (int)ctx->log_n, ctx->stream));
+    return moddown_add_fp(ctx, acc.u(), Bn, l, addend.u(), (u64)2 * l * n, 2, 0, out);
+}
+
+extern "C" int hisa_rot_left_sum_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n_out, const int32_t* steps,
+                                       size_t n_terms, hisa_ct** out) {
+    if (!ctx || !out || !steps || n_terms == 0 || n_out == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    TRY(check_batch_shape(ctx, in, n_out * n_terms, 2));
+    if (!fused_key_switch_available(ctx))
+        return fail(ctx, HISA_ERR_ARG, "sums of rotations need the fused key-switch path (N >= 2^12, every prime below 2^50, dnum <= 8)");
+    for (size_t i = 1; i < n_out * n_terms; i++)
+        if (fabs(in[i]->scale - in[0]->scale) > 1e-9 * fabs(in[0]->scale)) return fail(ctx, HISA_ERR_SCALE_MISMATCH, "terms of different scales");
+    // rotated terms first, in order; the unrotated one (if any) apart
+    std::vector<int32_t> rot_steps;
+    std::vector<const hisa_ct*> rot_in, plain_in;
+    for (size_t s = 0; s < n_terms; s++) {
+        const u64 g = galois_of(ctx, steps[s]);
+        if (g == 0) {
+            if (!plain_in.empty()) return fail(ctx, HISA_ERR_ARG, "more than one term without a rotation");
+            plain_in.assign(in + s * n_out, in + (s + 1) * n_out);
+            continue;
+        }
+        if (!t_analysis && ctx->keys.find(g) == ctx->keys.end())
+            return fail(ctx, HISA_ERR_NO_KEY, "no rotation key for %d slots (galois element %llu)", steps[s], (unsigned long long)g);
+        rot_steps.push_back(steps[s]);
+        rot_in.insert(rot_in.end(), in + s * n_out, in + (s + 1) * n_out);
+    }
+    if (rot_steps.size() > FP_MAX_STEPS) return fail(ctx, HISA_ERR_ARG, "at most %d rotated terms", FP_MAX_STEPS);
+    const int l = (int)in[0]->limbs;
+    TRY(alloc_ct_batch(ctx, n_out, 2, (uint32_t)l, in[0]->scale, out));
+    int rc = HISA_OK;
+    BatchIn br = {}, bp = {};
+    if (t_analysis) {   // a dry run moves no data
+        br.stride = bp.stride = ct_words(ctx, 2, l);
+    } else {
+        if (!plain_in.empty()) rc = gather_batch(ctx, plain_in.data(), n_out, &bp);
+        if (rc == HISA_OK && !rot_in.empty()) rc = gather_batch(ctx, rot_in.data(), rot_in.size(), &br);
+    }
+    if (rc == HISA_OK) {
+        if (rot_in.empty()) {   // nothing rotates: a copy of the one term
+            hipError_t e = hipSuccess;
+            for (size_t b = 0; b < n_out && e == hipSuccess && !t_analysis; b++)
+                e = hipMemcpyAsync(out[b]->data, plain_in[b]->data, ct_words(ctx, 2, l) * sizeof(u64), hipMemcpyDeviceToDevice, ctx->stream);
+            if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "copy: %s", hipGetErrorString(e));
+        } else {
+            rc = rotate_sum_fp(ctx, br.base, br.stride, (int)rot_steps.size(), rot_steps.data(), n_out, l,
+                               plain_in.empty() ? nullptr : bp.base, bp.stride, out[0]->data);
+        }
+    }
+    dev_release(ctx, br.tmp);
+    dev_release(ctx, bp.tmp);
+    if (rc != HISA_OK)
+        for (size_t b = 0; b < n_out; b++) { hisa_free(ctx, out[b]); out[b] = nullptr; }
+    return rc;
+}
+
 static int key_switch_core_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois, size_t B, int l, const SwitchKey& key,
                               const u64* add, u64 add_bs, int add_polys, u64* out) {
     FpExt x(ctx, B, l, (int)ctx->K, (int)ctx->alpha);

@@ -799,6 +799,88 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const Fp
     }
 }
 
+// The sum over rotations of DIFFERENT ciphertexts, before the division by P: entry (s, b) of ext / own_src is term s of
+// output b (its digits computed from the unrotated polynomial, gathered here through sigma_s like the own-digit limbs),
+// acc[b] = sum_s sum_j sigma_s(e_{s,b,j}) * key_s[j].  A rotation's key values stay in registers across the IPS_BCH
+// outputs of a block; partial sums are normalised per rotation (eight terms of at most 0.875 * 2^50 stay below 2^53)
+// and the running sums every eight rotations.
+#define IPS_BCH 4
+__global__ __launch_bounds__(IPF_NT) void inner_product_sum_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs,
+                                                                      int digits, int l, int K, int L, int alpha, IpSteps steps,
+                                                                      int n_steps, int total, const u64* own_src, u64 own_bs,
+                                                                      u64* acc, u64 acc_bs, u64 n_batch, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const uint32_t j = blockIdx.x * IPF_NT + threadIdx.x;
+    const int x = blockIdx.y;
+    const u64 b0 = (u64)blockIdx.z * IPS_BCH;
+    const int ext_limbs = l + K;
+    const int prime = x < l ? x : L + (x - l);
+    const int own_digit = x < l ? x / alpha : -1;
+    const double p = as_const(&fprimes[prime].p)[0], pinv = as_const(&fprimes[prime].p)[1];
+    double tb[IPS_BCH], ta[IPS_BCH];
+#pragma unroll
+    for (int u = 0; u < IPS_BCH; u++) tb[u] = ta[u] = 0.0;
+    for (int s = 0; s < n_steps; s++) {
+        const u64* key = steps.key[s];
+        const uint32_t jsrc = galois_src_fp(j, steps.galois[s], log_n);
+        double kb[IPF_MAXD], ka[IPF_MAXD];
+#pragma unroll
+        for (int d = 0; d < IPF_MAXD; d++) {
+            if (d < digits) {
+                kb[d] = fp_from_u64(key[(((u64)d * 2 + 0) * total + prime) * n + j]);
+                ka[d] = fp_from_u64(key[(((u64)d * 2 + 1) * total + prime) * n + j]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < IPS_BCH; u++) {
+            if (b0 + u < n_batch) {
+                const u64 entry = (u64)s * n_batch + b0 + u;
+                double sb = 0.0, sa = 0.0;
+#pragma unroll
+                for (int d = 0; d < IPF_MAXD; d++) {
+                    if (d < digits) {
+                        const u64 ev = d == own_digit ? own_src[entry * own_bs + (u64)x * n + jsrc]
+                                                      : ext[entry * ext_bs + ((u64)d * ext_limbs + x) * n + jsrc];
+                        const double e = fp_from_u64(ev);
+                        sb += fp_mulmod(e, kb[d], p, pinv);
+                        sa += fp_mulmod(e, ka[d], p, pinv);
+                    }
+                }
+                tb[u] += fp_norm(sb, p, pinv);
+                ta[u] += fp_norm(sa, p, pinv);
+                if ((s & 7) == 7) { tb[u] = fp_norm(tb[u], p, pinv); ta[u] = fp_norm(ta[u], p, pinv); }
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < IPS_BCH; u++) {
+        if (b0 + u < n_batch) {
+            u64* dst = acc + (b0 + u) * acc_bs;
+            dst[(u64)x * n + j] = fp_canonical(tb[u], p, pinv);
+            dst[((u64)ext_limbs + x) * n + j] = fp_canonical(ta[u], p, pinv);
+        }
+    }
+}
+
+hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
+                                       int alpha, const IpSteps& steps, int n_steps, int total, const u64* own_src, u64 own_bs,
+                                       u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
+    if (digits < 1 || digits > IPF_MAXD || n_steps < 1 || n_steps > FP_MAX_STEPS || l < 1 || K < 1 || alpha < 1) return hipErrorInvalidValue;
+    if (!fprimes || !ext || !own_src || !acc || n_batch == 0 || n_batch > 65535u * IPS_BCH) return hipErrorInvalidValue;
+    // an entry holds `digits` extended digits of l + K limbs; an accumulator two polynomials of l + K limbs; an own-digit
+    // source the l limbs of the polynomial
+    const u64 n = (u64)1 << log_n;
+    if (ext_bs < (u64)digits * (l + K) * n || acc_bs < (u64)2 * (l + K) * n || own_bs < (u64)l * n) return hipErrorInvalidValue;
+    for (int s = 0; s < n_steps; s++)
+        if (!steps.key[s] || steps.galois[s] == 0) return hipErrorInvalidValue;
+    dim3 grid((1u << log_n) / IPF_NT, l + K, (unsigned)((n_batch + IPS_BCH - 1) / IPS_BCH));
+    ProfScope prof__("inner_product_sum_fp_kernel", st);
+    hipLaunchKernelGGL(inner_product_sum_fp_kernel, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha, steps,
+                       n_steps, total, own_src, own_bs, acc, acc_bs, n_batch, log_n);
+    return hipGetLastError();
+}
+
 hipError_t launch_inner_product_steps_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
                                          int alpha, const IpSteps& steps, int n_steps, int total, const u64* own_src,
                                          u64 own_bs, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st) {

@@ -42,7 +42,7 @@ class TensorStruct(C.Structure):
 
 
 class OpCounts(C.Structure):
-    _fields_ = [(name, C.c_uint64) for name in ("rot_left", "rot_shared", "relinearize", "mul", "mul_plain", "mul_scalar",
+    _fields_ = [(name, C.c_uint64) for name in ("rot_left", "rot_shared", "rot_summed", "relinearize", "mul", "mul_plain", "mul_scalar",
                                                 "add", "rescale", "mac_plain", "mac_scalar", "key_switch_calls")] + [("min_limbs", C.c_uint32), ("reserved", C.c_uint32)]
 
 
@@ -322,6 +322,16 @@ class Context:
         st = (C.c_int32 * ns)(*[int(x) for x in steps])
         self._ck(load().hisa_rot_left_hoisted_batch(self._vp, self._harr(cts), C.c_size_t(n), st, C.c_size_t(ns), arr))
         return [[self._new_ct(int(arr[s * n + i])) for i in range(n)] for s in range(ns)]
+
+    def rot_left_sum_batch(self, terms, steps):
+        """terms[s][b]: out[b] = sum over s of rotLeft(terms[s][b], steps[s]), one division by P per output."""
+        ns, n = len(steps), len(terms[0])
+        assert len(terms) == ns and all(len(t) == n for t in terms)
+        flat = [c for t in terms for c in t]
+        arr = (C.c_void_p * n)()
+        st = (C.c_int32 * ns)(*[int(x) for x in steps])
+        self._ck(load().hisa_rot_left_sum_batch(self._vp, self._harr(flat), C.c_size_t(n), st, C.c_size_t(ns), arr))
+        return [self._new_ct(int(arr[i])) for i in range(n)]
 
     def add_batch(self, a, b):
         return self._batch_out("hisa_add_batch", len(a), self._harr(a), self._harr(b), C.c_size_t(len(a)))

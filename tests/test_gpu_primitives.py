@@ -227,6 +227,52 @@ def test_hoisted_rotations_equal_single_rotations(pair):
     assert e.value.code == -4
 
 
+def test_rotation_sums_match_oracle(pair, request):
+    """Sums of rotated ciphertexts with one division by P per output: bit for bit the oracle's sum of key-switch
+    accumulators (SharedModDown with unit weights), at the top level and one level down, with and without an unrotated
+    term, terms from different allocations; contexts without the fused key switch refuse the call."""
+    from oracle.layers import SharedModDown
+    from paper_1810_00845_amd import hisa
+    g, o = pair
+    fused = request.node.callspec.id.endswith("_fp")
+    n_out = 3
+    cts = [fresh_pair(g, o, 60 + i, g.L) for i in range(4 * n_out)]
+    gs, os_ = [c[0] for c in cts], [c[1] for c in cts]
+    if not fused:
+        with pytest.raises(hisa.HisaError) as e:
+            g.rot_left_sum_batch([gs[:n_out], gs[n_out:2 * n_out]], [1, 7])
+        assert e.value.code == -1
+        return
+    for level in range(2):
+        for steps in ([1, 0, 7, g.slots - 3], [64, 7], [0]):
+            terms = [[gs[(s * n_out + b + level) % len(gs)] for b in range(n_out)] for s in range(len(steps))]
+            oterms = [[os_[(s * n_out + b + level) % len(gs)] for b in range(n_out)] for s in range(len(steps))]
+            out = g.rot_left_sum_batch(terms, steps)
+            assert len(out) == n_out
+            for b in range(n_out):
+                ins = [oterms[s][b] for s in range(len(steps))]
+                want = SharedModDown(o, ins).total([(s, steps[s], 1, None) for s in range(len(steps))], ins[0].scale)
+                same(g, o, out[b], want)
+        if level == 0:
+            # the decrypted sum is the sum of the decrypted rotations (top level only: the rescaling below leaves
+            # these 40-bit test messages only a few bits above its rounding)
+            steps = [1, 0, 7]
+            out = g.rot_left_sum_batch([[gs[s]] for s in range(3)], steps)
+            z = g.decode(g.decrypt(out[0]), g.slots)
+            ref = sum(np.roll(g.decode(g.decrypt(gs[s]), g.slots), -steps[s]) for s in range(3))
+            assert np.abs(z - ref).max() <= 1e-6 * max(1.0, np.abs(ref).max())
+        if gs[0].limbs <= 2:
+            break
+        for i in range(len(gs)):
+            g.rescale(gs[i]); os_[i] = o.rescale(os_[i])
+    with pytest.raises(hisa.HisaError) as e:
+        g.rot_left_sum_batch([gs[:1], gs[1:2]], [1, 5])                  # no key for 5
+    assert e.value.code == -4
+    with pytest.raises(hisa.HisaError) as e:
+        g.rot_left_sum_batch([gs[:1], gs[1:2], gs[2:3]], [0, 1, 0])      # two unrotated terms
+    assert e.value.code == -1
+
+
 def test_import_export_roundtrip(pair):
     from paper_1810_00845_amd import synth
     g, o = pair
