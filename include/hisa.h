@@ -281,7 +281,20 @@ typedef struct {
                           /* rounding of that division; ciphertext bits differ from the schedule with         */
                           /* shared_moddown = 0.  Needs N >= 2^12, every prime below 2^50, dnum <= 8           */
                           /* (HISA_ERR_ARG otherwise); hisa_conv2d_fixed takes the same arguments              */
+    uint32_t chw_schedule; /* CHW-tiled inputs only (ignored when c_inner = 1): HISA_CHW_*                    */
 } hisa_conv_geom;
+#define HISA_CHW_ROTATE_INPUTS 0 /* every input ciphertext is rotated by (tap, d); the products are summed         */
+#define HISA_CHW_ROTATE_SUMS 1   /* the reduction over the channels of a ciphertext comes after the multiplication  */
+                                 /* (Sec. "Homomorphic Tensor Operations", CHW paragraph): inputs are rotated by   */
+                                 /* the taps only; for each output ciphertext and diagonal d the products are      */
+                                 /* summed where the input channels lie (the plaintext of (tap, d, j, g) holds the */
+                                 /* weight for output block b on block b + d; behind the blocks lies their copy,   */
+                                 /* or block 0 when they fill the slots) and the c_inner sums are rotated left by  */
+                                 /* d*c_stride and added by hisa_rot_left_sum_batch's arithmetic: one division by  */
+                                 /* P per output ciphertext.  (taps - 1) rotations per input ciphertext plus       */
+                                 /* c_inner - 1 key switches per output ciphertext instead of taps*c_inner - 1 per */
+                                 /* input ciphertext; the same multiplications.  Needs what that call needs and    */
+                                 /* c_inner <= 33; not together with shared_moddown (HISA_ERR_ARG).                */
 
 /* HW-tiled conv2d (Algorithm 1; cross-correlation, no kernel flip): for every
  * output channel oc: sum over ic and filter taps (fy, fx) of weight *
@@ -316,7 +329,8 @@ typedef struct {
  * 2*c_inner*c_stride <= slots, else HISA_ERR_ARG).  fh*fw*c_inner is at most 256.
  * Output: clean, CHW-tiled with the same c_inner and c_stride,
  * batch*ceil(out_channels/c_inner) handles.  hisa_conv2d_fixed then takes
- * pt_coeffs[FH][FW][c_inner][ceil(IC/c_inner)][ceil(OC/c_inner)][N]. */
+ * pt_coeffs[FH][FW][c_inner][ceil(IC/c_inner)][ceil(OC/c_inner)][N] (for either
+ * chw_schedule; the plaintexts differ in where their blocks lie). */
 int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uint32_t out_channels,
                 const hisa_conv_geom* geom, hisa_tensor* out);
 int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* w_int, double w_scale,

@@ -499,13 +499,28 @@ static int32_t norm_step(const hisa_ctx* ctx, i64 r) {
 // Rotation amounts of a convolution, one per (tap, d): HW-tiling has d = 0 only; with c_inner channel blocks per
 // ciphertext the blocks are combined along diagonals (output block b reads input block (b + d) mod c_inner), so every
 // tap is also rotated by d blocks.
+// A CHW-tiled convolution may instead reduce over the channel blocks after the multiplication
+// (HISA_CHW_ROTATE_SUMS): the inputs are then rotated by the taps only and the c_inner sums by d blocks.
+static bool conv_rotates_sums(const hisa_tensor* in, const hisa_conv_geom* g) {
+    return t_ci(in) > 1 && g->chw_schedule == HISA_CHW_ROTATE_SUMS;
+}
+
 static std::vector<int32_t> conv_tap_steps(const hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g) {
     std::vector<int32_t> steps;
     const i64 ph = g->pad_same ? g->fh / 2 : 0, pw = g->pad_same ? g->fw / 2 : 0;
+    const uint32_t diagonals = conv_rotates_sums(in, g) ? 1 : t_ci(in);
     for (uint32_t fy = 0; fy < g->fh; fy++)
         for (uint32_t fx = 0; fx < g->fw; fx++)
-            for (uint32_t d = 0; d < t_ci(in); d++)
+            for (uint32_t d = 0; d < diagonals; d++)
                 steps.push_back(norm_step(ctx, ((i64)fy - ph) * in->h_stride + ((i64)fx - pw) * in->w_stride + (i64)d * in->c_stride));
+    return steps;
+}
+
+// rotLeft amounts of the sums of diagonals 1 .. c_inner-1 under HISA_CHW_ROTATE_SUMS
+static std::vector<int32_t> conv_sum_steps(const hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g) {
+    std::vector<int32_t> steps;
+    if (conv_rotates_sums(in, g))
+        for (uint32_t d = 1; d < t_ci(in); d++) steps.push_back(norm_step(ctx, (i64)d * in->c_stride));
     return steps;
 }
 
@@ -537,6 +552,7 @@ extern "C" int hisa_conv2d_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, const
                                      size_t cap, size_t* n) {
     if (!ctx || !in || !geom) return HISA_ERR_ARG;
     std::vector<int32_t> all = conv_tap_steps(ctx, in, geom);
+    for (int32_t st : conv_sum_steps(ctx, in, geom)) all.push_back(st);
     const i64 wrap = conv_wrap_amount(ctx, in);
     if (wrap > 0) all.push_back(norm_step(ctx, -wrap));
     return write_steps(all, steps, cap, n);
@@ -723,13 +739,24 @@ static void fill_out_meta(hisa_tensor* out, uint32_t batch, uint32_t channels, u
 // ---------------------------------------------------------------------------
 struct ConvPlan {
     uint32_t out_h, out_w;
-    std::vector<int32_t> steps;   // one per (tap, d)
+    std::vector<int32_t> steps;   // rotations of the inputs: one per (tap, d), or per tap when the sums are rotated
+    std::vector<int32_t> sum_steps;   // HISA_CHW_ROTATE_SUMS: rotations of the sums of diagonals 1 .. c_inner-1
+    bool rotate_sums = false;
     i64 wrap = 0;                 // CHW-tiling: rotRight amount of the copy behind the channel blocks, 0 if none
 };
 
 static int conv_plan(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, ConvPlan* p) {
-    if (!g || g->fh == 0 || g->fw == 0 || g->stride == 0 || (u64)g->fh * g->fw * t_ci(in) > MAX_TAPS || g->mode > HISA_CONV_PLAIN)
+    if (!g || g->chw_schedule > HISA_CHW_ROTATE_SUMS) return fail(ctx, HISA_ERR_ARG, "bad conv geometry");
+    p->rotate_sums = conv_rotates_sums(in, g);
+    if (g->fh == 0 || g->fw == 0 || g->stride == 0 || (u64)g->fh * g->fw * (p->rotate_sums ? 1 : t_ci(in)) > MAX_TAPS ||
+        g->mode > HISA_CONV_PLAIN)
         return fail(ctx, HISA_ERR_ARG, "bad conv geometry (at most %d rotation amounts per input ciphertext)", MAX_TAPS);
+    if (p->rotate_sums) {
+        if (!fused_key_switch_available(ctx))
+            return fail(ctx, HISA_ERR_ARG, "HISA_CHW_ROTATE_SUMS needs the fused key-switch path (N >= 2^12, every prime below 2^50, dnum <= 8)");
+        if (t_ci(in) - 1 > FP_MAX_STEPS) return fail(ctx, HISA_ERR_ARG, "HISA_CHW_ROTATE_SUMS: at most %d channel blocks", FP_MAX_STEPS + 1);
+        if (g->shared_moddown) return fail(ctx, HISA_ERR_ARG, "shared_moddown belongs to the schedule that rotates the inputs");
+    }
     if (t_ci(in) > 1) {
         // several channels per ciphertext: different weights on different slots, so mulPlain, and zeros between the elements
         if (g->mode != HISA_CONV_PLAIN) return fail(ctx, HISA_ERR_ARG, "CHW-tiled convolution multiplies by plaintexts: mode HISA_CONV_PLAIN");
@@ -747,6 +774,7 @@ static int conv_plan(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom*
         p->out_w = (in->width - g->fw) / g->stride + 1;
     }
     p->steps = conv_tap_steps(ctx, in, g);
+    p->sum_steps = conv_sum_steps(ctx, in, g);
     return HISA_OK;
 }
 
@@ -914,6 +942,92 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
     return HISA_OK;
 }
 
+// CHW-tiled convolution that reduces over the channel blocks after the multiplication (HISA_CHW_ROTATE_SUMS):
+// the inputs are rotated by the taps (one shared decomposition), one multiply-accumulate launch forms, for every
+// output ciphertext g and diagonal d, the sum over (tap, input ciphertext) on the blocks where the input channels lie
+// -- c_inner * OCm sums, ordered (d, g) -- and the sums of d = 1 .. c_inner-1 are rotated left by d blocks and added
+// to the sum of d = 0 with one division by P per output (rotate_sum_fp).  d_pts: [taps][IC][c_inner * OCm][l][N].
+static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
+                         const u64* d_pts, double pt_scale, hisa_tensor* out) {
+    const uint32_t B = in->batch, ci = t_ci(in), IC = (uint32_t)t_per(in), OCm = (OC + ci - 1) / ci, l = in->cts[0]->limbs;
+    const size_t nct = (size_t)B * IC, n = ctx->N;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
+    if (!d_pts || plan.sum_steps.size() != ci - 1) return fail(ctx, HISA_ERR_ARG, "bad convolution plan");
+    const int n_taps = (int)plan.steps.size();
+    const u64 ctw = 2 * (u64)l * n;
+    std::vector<hisa_ct*> wrapped;
+    hisa_ct* const* src = in->cts;
+    if (plan.wrap > 0) {
+        wrapped.assign(nct, nullptr);
+        TRY(hisa_rot_left_batch(ctx, (const hisa_ct* const*)in->cts, nct, norm_step(ctx, -plan.wrap), wrapped.data()));
+        BatchIn orig;
+        int rcw = gather_batch(ctx, (const hisa_ct* const*)in->cts, nct, &orig);
+        if (rcw == HISA_OK) {
+            hipError_t e = launch_addsub(ctx->d_primes, wrapped[0]->data, orig.base, wrapped[0]->data, OP_ADD, (int)l, 2, 2, nct, ctw,
+                                         orig.stride, ctw, (int)ctx->log_n, ctx->stream);
+            if (e != hipSuccess) rcw = fail(ctx, HISA_ERR_HIP, "conv wrap: %s", hipGetErrorString(e));
+        }
+        dev_release(ctx, orig.tmp);
+        if (rcw != HISA_OK) { free_handles(ctx, wrapped); return rcw; }
+        src = wrapped.data();
+    }
+    BatchIn bi;
+    {
+        const int rcg = gather_batch(ctx, (const hisa_ct* const*)src, nct, &bi);
+        if (rcg != HISA_OK) { free_handles(ctx, wrapped); return rcg; }
+    }
+    std::vector<std::vector<hisa_ct*>> rotated(n_taps);
+    std::vector<hisa_ct*> outs((size_t)B * OCm, nullptr);
+    MacArgs ma = {};
+    int rc = HISA_OK;
+    {
+        std::vector<int32_t> nz;
+        std::vector<int> tap_of;
+        for (int t = 0; t < n_taps; t++) {
+            if (plan.steps[t] == 0) ma.tap_base[t] = bi.base;
+            else { nz.push_back(plan.steps[t]); tap_of.push_back(t); }
+        }
+        if (!nz.empty()) {
+            std::vector<hisa_ct*> all(nz.size() * nct, nullptr);
+            rc = hisa_rot_left_hoisted_batch(ctx, (const hisa_ct* const*)src, nct, nz.data(), nz.size(), all.data());
+            for (size_t k = 0; k < nz.size() && rc == HISA_OK; k++) {
+                rotated[tap_of[k]].assign(all.begin() + k * nct, all.begin() + (k + 1) * nct);
+                ma.tap_base[tap_of[k]] = rotated[tap_of[k]][0]->data;
+            }
+        }
+    }
+    const double mac_scale = in->cts[0]->scale * pt_scale;
+    const size_t sums = (size_t)ci * OCm;          // per image, ordered (d, g)
+    Temp y(ctx, (size_t)B * sums * ctw * sizeof(u64));
+    if (rc == HISA_OK && !y.ok()) rc = HISA_ERR_OOM;
+    if (rc == HISA_OK) rc = alloc_ct_batch(ctx, (size_t)B * OCm, 2, l, mac_scale, outs.data());
+    if (rc == HISA_OK) {
+        ma.n_taps = n_taps; ma.IC = (int)IC; ma.OC = (int)sums; ma.l = (int)l; ma.ct_words = ctw;
+        ma.out = y.u();
+        ma.w = d_pts; ma.w_stride_t = sums; ma.w_stride_oc = 1;
+        hipError_t e = launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));
+    }
+    for (auto& v : rotated) free_handles(ctx, v);
+    dev_release(ctx, bi.tmp);
+    free_handles(ctx, wrapped);
+    // per image: entries (d, g) are rotation-major over the OCm outputs; d = 0 is the unrotated term
+    for (uint32_t b = 0; b < B && rc == HISA_OK; b++) {
+        const u64* yb = y.u() + (size_t)b * sums * ctw;
+        rc = rotate_sum_fp(ctx, yb + (size_t)OCm * ctw, ctw, (int)ci - 1, plan.sum_steps.data(), OCm, (int)l, yb, ctw,
+                           outs[(size_t)b * OCm]->data);
+    }
+    if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
+    if (rc != HISA_OK) {
+        for (hisa_ct* c : outs) hisa_free(ctx, c);
+        return rc;
+    }
+    for (size_t i = 0; i < outs.size(); i++) out->cts[i] = outs[i];
+    fill_out_meta(out, B, OC, plan.out_h, plan.out_w, in->h_stride * g->stride, in->w_stride * g->stride, in->offset, 1u, ci,
+                  in->c_stride);
+    return HISA_OK;
+}
+
 // Everything a convolution needs besides its input: weights in the forms the kernels read, the mask or the per-tap
 // plaintexts, and the scales.  Built from float weights per call by hisa_conv2d, or once by hisa_conv2d_prepare.
 // With `shared` (one division by P per output ciphertext, conv_run_shared) the terms of the rotated taps and of the
@@ -1029,6 +1143,26 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
         // plaintext (tap, d, input ciphertext j, output ciphertext g): on the valid output positions of block b the
         // weight from input channel j ci + (b + d) mod ci to output channel g ci + b, zero where either does not exist
         const uint32_t ci = t_ci(in), per_in = (uint32_t)t_per(in), per_out = (OC + ci - 1) / ci;
+        if (plan.rotate_sums) {
+            // plaintext (tap, input ciphertext j, d, output ciphertext g): the same weight, but on block b + d, where
+            // the input channel lies (behind the blocks their copy, or cyclically block 0); taps = filter taps here
+            const uint32_t npos = plan.wrap > 0 ? 2 * ci : ci;
+            const size_t n_pts = taps * per_in * ci * per_out;
+            std::vector<std::vector<uint32_t>> sets(npos);
+            for (uint32_t pos = 0; pos < npos; pos++)
+                for (uint32_t v : vslots) sets[pos].push_back(v + pos * in->c_stride);
+            std::vector<double> vals(n_pts * npos, 0.0);
+            for (size_t idx = 0; idx < n_pts; idx++) {
+                const size_t g_ = idx % per_out, d = (idx / per_out) % ci, j = (idx / per_out / ci) % per_in;
+                const size_t tap = idx / per_out / ci / per_in;
+                for (uint32_t b = 0; b < ci; b++) {
+                    const size_t ic = j * ci + (b + d) % ci, oc = g_ * ci + b;
+                    const size_t pos = plan.wrap > 0 ? b + d : (b + d) % ci;
+                    if (ic < IC && oc < OC) vals[idx * npos + pos] = w[(tap * IC + ic) * OC + oc];
+                }
+            }
+            return build_plain_weights(ctx, sets, vals.data(), plan, per_in, ci * per_out, l, q_last, false, cw);
+        }
         const size_t n_pts = taps * per_in * per_out;
         std::vector<std::vector<uint32_t>> sets(ci);
         for (uint32_t b = 0; b < ci; b++)
@@ -1075,6 +1209,19 @@ static int conv_build_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t*
     if (geom->mode == HISA_CONV_PLAIN) {
         if (!pt_coeffs) return fail(ctx, HISA_ERR_ARG, "PLAIN mode needs plaintext coefficients");
         cw.w_scale = 1.0;
+        if (plan.rotate_sums) {
+            // given as [tap][d][j][g][N]; the multiply-accumulate reads [tap][j][(d, g)][N]
+            const size_t ci = t_ci(in), taps = plan.steps.size();
+            std::vector<int64_t> perm(taps * ci * ICm * OCm * n);
+            for (size_t tap = 0; tap < taps; tap++)
+                for (size_t d = 0; d < ci; d++)
+                    for (size_t j = 0; j < ICm; j++)
+                        memcpy(perm.data() + (((tap * ICm + j) * ci + d) * OCm) * n,
+                               pt_coeffs + (((tap * ci + d) * ICm + j) * OCm) * n, OCm * n * sizeof(int64_t));
+            cw.pts = new Temp(ctx, perm.size() * l * sizeof(u64));
+            if (!cw.pts->ok()) return HISA_ERR_OOM;
+            return coeffs_to_plain_batch(ctx, perm.data(), perm.size() / n, (int)l, cw.pts->u());
+        }
         if (!shared) {
             cw.pts = new Temp(ctx, T * OCm * l * n * sizeof(u64));
             if (!cw.pts->ok()) return HISA_ERR_OOM;
@@ -1245,6 +1392,7 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
 
 static int conv_dispatch(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
                          const ConvWeights& cw, hisa_tensor* out) {
+    if (plan.rotate_sums) return conv_run_sums(ctx, in, g, plan, OC, cw.pts ? cw.pts->u() : nullptr, cw.pt_scale, out);
     if (cw.shared) return conv_run_shared(ctx, in, g, plan, OC, cw, out);
     const u64* d_pts = g->mode == HISA_CONV_MASKED ? (cw.mask ? cw.mask->u() : nullptr) : (cw.pts ? cw.pts->u() : nullptr);
     return conv_run(ctx, in, g, plan, OC, cw.dw, cw.w_scale, d_pts, cw.pt_scale, out);

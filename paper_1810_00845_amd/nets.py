@@ -110,7 +110,7 @@ def chw_blocks(slots, plane_slots_needed, layers, chw_convs=True):
 
 
 def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans=None, layout="hw", shared_moddown=True,
-                  layer_times=True):
+                  layer_times=True, rotate_sums=True):
     """Encrypts x, runs the layers, decrypts.  Returns (output array, seconds from encrypt-done to the last
     ciphertext ready, per-layer seconds).  With make_keys the rotation keys each layer asks for are generated
     on the way (set-up pass); otherwise they must be resident.  `plans` (a dict, filled by the set-up pass and
@@ -123,7 +123,8 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
     CHW-tiled between the layers but switches to HW-tiling before every convolution and back after it (one level
     for the way to HW, one for the masking multiply that makes Algorithm 1's output clean enough to pack).
     shared_moddown: the convolutions divide by P once per output ciphertext instead of once per rotation (where the
-    parameters have the fused key-switch path).  layer_times: wait for the GPU after every layer to time it; without,
+    parameters have the fused key-switch path).  rotate_sums: a CHW-tiled convolution reduces over the channel blocks
+    after the multiplication (HISA_CHW_ROTATE_SUMS) where that takes fewer key switches.  layer_times: wait for the GPU after every layer to time it; without,
     the host queues the whole network ahead of the GPU and only the end-to-end latency is measured (per-layer entries
     are then host queueing times)."""
     assert layout in LAYOUTS
@@ -186,8 +187,18 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             kw["mode"] = 2
             if not t.clean:
                 t = cleaned = ctx.tensor_mask(t)
+            # rotate the inputs by (tap, diagonal), or by the taps only and the sums by the diagonals: whichever takes
+            # fewer key switches (a rotation inside a sum shares the division by P, a rotation of an input the
+            # decomposition: about the same price)
+            ci, taps = t.c_inner, fh * fw
+            per_in, per_out = -(-t.channels // ci), -(-w.shape[3] // ci)
+            fused = ctx.log_n >= 12 and max(ctx.primes) < 2 ** 50 and ctx.dnum <= 8
+            if (rotate_sums and fused and ci - 1 <= 32 and
+                    1.2 * (per_in * (taps - 1) + per_out * (ci - 1)) < per_in * (taps * ci - 1)):
+                kw["chw_schedule"] = 1
         if make_keys:
-            ctx.gen_rot_keys(ctx.conv2d_rot_steps(t, fh, fw, stride=kw.get("stride", 1), pad_same=kw.get("pad_same", False)))
+            ctx.gen_rot_keys(ctx.conv2d_rot_steps(t, fh, fw, stride=kw.get("stride", 1), pad_same=kw.get("pad_same", False),
+                                                  chw_schedule=kw.get("chw_schedule", 0)))
         # one division by P per output instead of one per rotation pays when there are clearly more rotations than
         # outputs and the weights are scalars: with plaintext weights the sum on the l + K limbs reads that many more
         # limbs of every accumulator and plaintext, which costs more than the divisions it saves (measured on the
@@ -290,7 +301,7 @@ def analyse(ctx, layers, x, scale, limbs, border=0, layout="hw"):
     return counts, steps
 
 
-COST_OPS = ("rot_left", "rot_shared", "relinearize", "mul", "mul_plain", "mul_scalar", "add", "rescale", "mac_plain",
+COST_OPS = ("rot_left", "rot_shared", "rot_summed", "relinearize", "mul", "mul_plain", "mul_scalar", "add", "rescale", "mac_plain",
             "mac_scalar", "key_switch_calls")
 
 
@@ -298,7 +309,8 @@ def measure_costs(ctx, limbs, batch=64, reps=5):
     """Seconds per ciphertext operation at `limbs` limbs, from timing each primitive on a batch of random ciphertexts
     (Sec. "Data Layout Selection": the costs may come from micro-benchmarks).  "rot_shared" is what a rotation saves
     when it shares another one's decomposition (a negative cost); "mac_plain" and "mac_scalar" are the terms of the
-    layers' fused multiply-accumulate, timed on 1x1 convolutions (which rotate nothing)."""
+    layers' fused multiply-accumulate, timed on 1x1 convolutions (which rotate nothing); "rot_summed" likewise what a
+    rotation saves inside a sum of rotations that takes its division by P once."""
     from .hisa import CipherTensor
     import numpy as np
     cts = ctx.ct_random_batch(batch, limbs, 2.0 ** 40, 900)
@@ -327,6 +339,10 @@ def measure_costs(ctx, limbs, batch=64, reps=5):
     costs["key_switch_calls"] = max(0.0, single - costs["rot_left"])
     hoisted = timed(lambda: free(ctx.rot_left_hoisted_batch(cts, [1, 2, 3])))      # three rotations per ciphertext
     costs["rot_shared"] = min(0.0, (hoisted - 3 * full) / 2)
+    costs["rot_summed"] = 0.0                 # what a rotation saves inside a sum that divides by P once
+    if ctx.log_n >= 12 and max(ctx.primes) < 2 ** 50 and ctx.dnum <= 8:
+        summed = timed(lambda: free(ctx.rot_left_sum_batch([cts, cts, cts], [1, 2, 3])))   # three terms per output
+        costs["rot_summed"] = min(0.0, (summed - 3 * full) / 2)
     costs["add"] = timed(lambda: free(ctx.add_batch(cts, cts)))
     costs["mul"] = timed(lambda: free(ctx.mul_no_relin_batch(cts, cts)))
     costs["mul_plain"] = timed(lambda: free(ctx.mul_plain_batch(cts, pt)))

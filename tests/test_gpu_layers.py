@@ -361,6 +361,63 @@ def test_chw_conv_bit_exact(log_n, c_stride):
     g.close()
 
 
+@pytest.mark.parametrize("c_stride", [64, 512])
+def test_chw_conv_rotating_the_sums_bit_exact(c_stride):
+    """The CHW-tiled convolution that reduces over the channel blocks after the multiplication, against the oracle
+    bit for bit: batch of two, 5 -> 6 channels in blocks of 4 (ragged last ciphertexts), SAME and VALID, stride 1 and
+    2; blocks with their copy behind them (4 x 64 slots) and filling the slot vector (4 x 512 at N = 2^12); fixed-point,
+    float and plan entry points; the rotation amounts; the dry run's counts; what it refuses."""
+    from oracle import layers
+    from paper_1810_00845_amd import hisa, synth
+    g, o = make_pair(12, [50, 40, 40], 3, 50, 14)
+    x = synth.image(41, 5, 4, 4)[None].repeat(2, axis=0) * np.array([1.0, -0.7])[:, None, None, None]
+    w = synth.conv_weights(42, 3, 3, 5, 6)
+    gt, ot = chw_pair(g, o, x, 2.0 ** 40, 3, 4, c_stride, 900, h_stride=6, offset=7)
+    S = hisa.CHW_ROTATE_SUMS
+    steps = sorted(set(g.conv2d_rot_steps(gt, 3, 3, pad_same=True, chw_schedule=S)) | set(g.conv2d_rot_steps(gt, 3, 3, chw_schedule=S)))
+    assert steps == sorted(set(layers.rot_steps_conv_chw(o, ot, 3, 3, True, schedule="out")) |
+                           set(layers.rot_steps_conv_chw(o, ot, 3, 3, schedule="out")))
+    assert len(steps) < len(g.conv2d_rot_steps(gt, 3, 3, pad_same=True))
+    g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+    for kw, ref in ((dict(pad_same=True), plain_net.conv2d(x, w, pad_same=True)), (dict(), plain_net.conv2d(x, w)),
+                    (dict(stride=2, pad_same=True), plain_net.conv2d(x, w, stride=2, pad_same=True))):
+        oout, ints = layers.conv2d_chw(o, ot, w, schedule="out", **kw)
+        gout = g.conv2d_fixed(gt, None, 1.0, ints["pt_coeffs"], ints["pt_scale"], 6, 3, 3, mode=layers.CONV_PLAIN,
+                              chw_schedule=S, **kw)
+        same_tensor(g, o, gout, oout)
+        assert gout.clean == 1 and np.abs(g.tensor_decrypt(gout) - ref).max() <= 1e-3
+        gfloat = g.conv2d(gt, w, 3, 3, mode=layers.CONV_PLAIN, chw_schedule=S, **kw)
+        assert gfloat.meta() == gout.meta() and np.abs(g.tensor_decrypt(gfloat) - ref).max() <= 1e-3
+        plan = g.conv2d_prepare(gt, w, 3, 3, mode=layers.CONV_PLAIN, chw_schedule=S, **kw)
+        gplan = g.conv2d_apply(gt, plan)
+        for ca, cb in zip(gfloat.cts, gplan.cts):
+            assert np.array_equal(g.ct_export(ca), g.ct_export(cb))
+        g.conv_plan_free(plan)
+    # dry run: per image 2 input ciphertexts x 8 taps shared-decomposition rotations (+ the copy behind the blocks),
+    # 2 output ciphertexts x 3 rotations inside sums, 2 x 9 x 4 x 2 multiply-accumulate terms
+    g.analysis_begin()
+    dry = g.conv2d(gt, w, 3, 3, mode=layers.CONV_PLAIN, chw_schedule=S, pad_same=True)
+    counts, dry_steps = g.analysis_end()
+    wrap = 4 * c_stride != g.slots
+    assert counts["rot_summed"] == 2 * 2 * 3 and counts["rot_left"] == 2 * (2 * 8 + 2 * 3 + (2 if wrap else 0))
+    assert counts["mac_plain"] == 2 * 2 * 9 * 4 * 2 and counts["rescale"] == 4
+    assert set(dry_steps) == set(g.conv2d_rot_steps(gt, 3, 3, pad_same=True, chw_schedule=S))
+    assert dry.cts[0].limbs == 2
+    with pytest.raises(hisa.HisaError) as e:               # the two ways of sharing a division do not combine
+        g.conv2d(gt, w, 3, 3, mode=layers.CONV_PLAIN, chw_schedule=S, shared_moddown=True)
+    assert e.value.code == -1
+    with pytest.raises(hisa.HisaError) as e:
+        g.conv2d(gt, w, 3, 3, mode=layers.CONV_PLAIN, chw_schedule=7)
+    assert e.value.code == -1
+    g.close()
+    g2, _ = make_pair(10, [50, 40, 40], 3, 60, 14)         # no fused key switch: refused, not silently re-scheduled
+    gt2 = g2.tensor_encrypt(x, 2.0 ** 40, 3, c_inner=4, c_stride=64, h_stride=6, offset=7)
+    with pytest.raises(hisa.HisaError) as e:
+        g2.conv2d_rot_steps(gt2, 3, 3) and g2.conv2d(gt2, w, 3, 3, mode=layers.CONV_PLAIN, chw_schedule=S)
+    assert e.value.code == -1
+    g2.close()
+
+
 def test_mask_layer_then_chw_conv_on_a_pooled_tensor():
     """pool (not clean) -> masking multiply -> CHW convolution, every step bit for bit; the convolution refuses the
     unmasked tensor."""
