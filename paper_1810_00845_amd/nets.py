@@ -249,6 +249,23 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             e3 = convolution((idx, "expand3"), s1, w3 * a, 3, 3, pad_same=True, mode=1)
             s1.free()
             nxt = _concat_channels(ctx, e1, e3)
+        elif kind == "gap" and t.height == t.width and t.height > 1 and t.height & (t.height - 1) == 0:
+            # a square plane with a power-of-two side: halve it by 2x2 sums down to one element per channel (three
+            # rotations sharing a decomposition per halving, all channels of a ciphertext at once), then the mean's
+            # factor, and what the previous layers left, as one scalar multiplication and its division
+            hw = t.height * t.width
+            nxt = t
+            while nxt.height > 1:
+                if make_keys:
+                    ctx.gen_rot_keys(ctx.pool_rot_steps(nxt))
+                halved = ctx.sum_pool2x2(nxt)
+                if nxt is not t:
+                    nxt.free()
+                nxt = halved
+            for ct in nxt.cts:
+                ctx.mul_scalar_assign(ct, pending / hw, float(ctx.primes[ct.limbs - 1]))
+            ctx.rescale_batch(nxt.cts)
+            pending = 1.0
         elif kind == "gap":
             c, hw = t.channels, t.height * t.width
             w = np.zeros((c, c, t.height, t.width))
