@@ -453,7 +453,8 @@ int hisa_sum_pool2x2(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out);
 int hisa_poly2_act(hisa_ctx* ctx, const hisa_tensor* in, double a, double b, hisa_tensor* out);
 /* The left-rotation amounts a layer will use on this input layout, for
  * hisa_gen_rot_keys (the rotation-key selection of Sec. "Rotation Keys
- * Selection"): writes at most cap amounts to host steps[], the count to *n. */
+ * Selection"): writes at most cap amounts to host steps[], the count to *n.
+ * For a convolution they depend on geom->chw_schedule as well as on the filter. */
 int hisa_conv2d_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* geom, int32_t* steps, size_t cap,
                           size_t* n);
 int hisa_fc_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n);
