@@ -183,7 +183,9 @@ int hisa_rot_left_hoisted_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t 
  * paragraph, when each channel's term is its own ciphertext).  The terms are decomposed and multiplied by their keys
  * one by one, but the accumulators on the l + K limbs are added up before the division by P, which is then taken once
  * per output: the result is the sum of the rotated ciphertexts up to the rounding of that division (ciphertext bits
- * differ from summing hisa_rot_left results).  At most one step may be a multiple of the slot count (that term is
+ * differ from summing hisa_rot_left results).  When all rotated terms of every output are the same handle (a sum of
+ * rotations of one ciphertext), that ciphertext is decomposed once (as in hisa_rot_left_hoisted_batch): same bits,
+ * less work.  At most one step may be a multiple of the slot count (that term is
  * added as it is), at most 32 may rotate; all inputs share level and scale.  Needs N >= 2^12, every prime below 2^50
  * and dnum <= 8 (HISA_ERR_ARG otherwise), and every step's key (HISA_ERR_NO_KEY before any work is queued). */
 int hisa_rot_left_sum_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n_out, const int32_t* steps, size_t n_terms,

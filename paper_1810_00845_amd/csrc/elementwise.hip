@@ -367,10 +367,11 @@ hipError_t launch_automorph_steps(const u64* in, u64 in_bs, u64* out, u64 out_bs
 }
 
 // The part of a sum of rotated ciphertexts that needs no key: out[b] = (plain[b].c0 + sum_s sigma_{g[s]}(rot[s][b].c0),
-// plain[b].c1), rot entries ordered rotation-major; plain may be null (zeros).  Canonical residues in and out.
+// plain[b].c1), rot entries ordered rotation-major -- or, with shared_input, entry b for every s --; plain may be null
+// (zeros).  Canonical residues in and out.
 __global__ __launch_bounds__(NT) void automorph_sum_kernel(const PrimeConst* primes, const u64* rot, u64 rot_bs, int n_rot,
                                                            GaloisTab tab, const u64* plain, u64 plain_bs, u64* out, u64 out_bs,
-                                                           unsigned n_batch, int l, int log_n) {
+                                                           unsigned n_batch, int shared_input, int l, int log_n) {
     const u64 n = (u64)1 << log_n;
     const uint32_t i = blockIdx.x * NT + threadIdx.x;
     const uint32_t mask = (2u << log_n) - 1;
@@ -382,15 +383,15 @@ __global__ __launch_bounds__(NT) void automorph_sum_kernel(const PrimeConst* pri
     for (int s = 0; s < n_rot; s++) {
         const uint32_t e2 = (uint32_t)((u64)e * tab.g[s]) & mask;
         const uint32_t src = __brev((e2 - 1) >> 1) >> (32 - log_n);
-        acc = addmod(acc, rot[((u64)s * n_batch + b) * rot_bs + (u64)limb * n + src], q);
+        acc = addmod(acc, rot[((shared_input ? 0 : (u64)s * n_batch) + b) * rot_bs + (u64)limb * n + src], q);
     }
     out[(u64)b * out_bs + (u64)limb * n + i] = acc;
     out[(u64)b * out_bs + (u64)(l + limb) * n + i] = plain ? plain[(u64)b * plain_bs + (u64)(l + limb) * n + i] : 0;
 }
 
 hipError_t launch_automorph_sum(const PrimeConst* primes, const u64* rot, u64 rot_bs, int n_rot, const GaloisTab& tab,
-                                const u64* plain, u64 plain_bs, u64* out, u64 out_bs, u64 n_batch, int l, int log_n,
-                                hipStream_t st) {
+                                const u64* plain, u64 plain_bs, u64* out, u64 out_bs, u64 n_batch, int shared_input, int l,
+                                int log_n, hipStream_t st) {
     DRY_RUN_RETURN();
     const u64 n = (u64)1 << log_n;
     if (!primes || !rot || !out || n_rot < 1 || n_rot > GALOIS_TAB_MAX || n_batch == 0 || n_batch > 65535 || l < 1)
@@ -401,7 +402,7 @@ hipError_t launch_automorph_sum(const PrimeConst* primes, const u64* rot, u64 ro
     dim3 grid((1u << log_n) / NT, l, (unsigned)n_batch);
     ProfScope prof__("automorph_sum_kernel", st);
     hipLaunchKernelGGL(automorph_sum_kernel, grid, dim3(NT), 0, st, primes, rot, rot_bs, n_rot, tab, plain, plain_bs, out, out_bs,
-                       (unsigned)n_batch, l, log_n);
+                       (unsigned)n_batch, shared_input, l, log_n);
     return hipGetLastError();
 }
 

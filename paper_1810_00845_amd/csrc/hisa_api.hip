@@ -1364,7 +1364,7 @@ int rotation_accumulators_fp(hisa_ctx* ctx, const u64* cts, u64 ct_bs, size_t B,
 }
 
 int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const int32_t* steps, size_t Bn, int l,
-                  const u64* plain, u64 plain_bs, u64* out) {
+                  const u64* plain, u64 plain_bs, u64* out, bool shared_input) {
     if (!fused_key_switch_available(ctx)) return fail(ctx, HISA_ERR_ARG, "no fused key-switch path for these parameters");
     if (n_steps < 1 || n_steps > FP_MAX_STEPS || Bn == 0 || l < 1) return fail(ctx, HISA_ERR_ARG, "bad rotation sum");
     const size_t n = ctx->N;
@@ -1390,10 +1390,11 @@ int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const i
     if (t_analysis) {
         t_analysis->c.rot_left += (u64)n_steps * Bn;
         t_analysis->c.rot_summed += (u64)n_steps * Bn;
+        if (shared_input) t_analysis->c.rot_shared += (u64)(n_steps - 1) * Bn;
         t_analysis->c.key_switch_calls += 1;
         return HISA_OK;
     }
-    const size_t E = (size_t)n_steps * Bn;
+    const size_t E = shared_input ? Bn : (size_t)n_steps * Bn;
     FpExt x(ctx, E, l, K, alpha);
     Temp acc(ctx, Bn * 2 * (size_t)ext_limbs * n * sizeof(u64));
     Temp addend(ctx, Bn * 2 * (size_t)l * n * sizeof(u64));
@@ -1401,8 +1402,10 @@ int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const i
     const u64* c1 = rot + (size_t)l * n;
     TRY(key_switch_modup_fp(ctx, c1, ct_bs, 0, E, x));
     HIP_TRY(ctx, launch_inner_product_sum_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, st, n_steps, total,
-                                             c1, ct_bs, acc.u(), (u64)2 * ext_limbs * n, Bn, (int)ctx->log_n, ctx->stream));
-    HIP_TRY(ctx, launch_automorph_sum(ctx->d_primes, rot, ct_bs, n_steps, tab, plain, plain_bs, addend.u(), (u64)2 * l * n, Bn, l,
+                                             c1, ct_bs, acc.u(), (u64)2 * ext_limbs * n, Bn, shared_input ? 1 : 0, (int)ctx->log_n,
+                                             ctx->stream));
+    HIP_TRY(ctx, launch_automorph_sum(ctx->d_primes, rot, ct_bs, n_steps, tab, plain, plain_bs, addend.u(), (u64)2 * l * n, Bn,
+                                      shared_input ? 1 : 0, l,
                                       (int)ctx->log_n, ctx->stream));
     return moddown_add_fp(ctx, acc.u(), Bn, l, addend.u(), (u64)2 * l * n, 2, 0, out);
 }
@@ -1431,6 +1434,10 @@ extern "C" int hisa_rot_left_sum_batch(hisa_ctx* ctx, const hisa_ct* const* in, 
         rot_in.insert(rot_in.end(), in + s * n_out, in + (s + 1) * n_out);
     }
     if (rot_steps.size() > FP_MAX_STEPS) return fail(ctx, HISA_ERR_ARG, "at most %d rotated terms", FP_MAX_STEPS);
+    // every rotated term of an output the same ciphertext: one decomposition per output serves all its rotations
+    bool shared_input = rot_steps.size() > 1;
+    for (size_t i = n_out; i < rot_in.size() && shared_input; i++) shared_input = rot_in[i] == rot_in[i % n_out];
+    if (shared_input) rot_in.resize(n_out);
     const int l = (int)in[0]->limbs;
     TRY(alloc_ct_batch(ctx, n_out, 2, (uint32_t)l, in[0]->scale, out));
     int rc = HISA_OK;
@@ -1449,7 +1456,7 @@ extern "C" int hisa_rot_left_sum_batch(hisa_ctx* ctx, const hisa_ct* const* in, 
             if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "copy: %s", hipGetErrorString(e));
         } else {
             rc = rotate_sum_fp(ctx, br.base, br.stride, (int)rot_steps.size(), rot_steps.data(), n_out, l,
-                               plain_in.empty() ? nullptr : bp.base, bp.stride, out[0]->data);
+                               plain_in.empty() ? nullptr : bp.base, bp.stride, out[0]->data, shared_input);
         }
     }
     dev_release(ctx, br.tmp);

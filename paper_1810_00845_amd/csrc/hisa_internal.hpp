@@ -192,9 +192,10 @@ int rotation_accumulators_fp(hisa_ctx* ctx, const u64* cts, u64 ct_bs, size_t B,
                              u64* acc);
 // out[b] = plain[b] + sum_s rotLeft(rot[s * Bn + b], steps[s]) with one division by P per output: rot holds
 // n_steps * Bn ciphertexts [2][l][N], ct_bs words apart, rotation-major; every step rotates (its key is present);
-// plain ([Bn] ciphertexts, plain_bs apart) may be null; out [Bn][2][l][N].  Dry runs count and return.
+// plain ([Bn] ciphertexts, plain_bs apart) may be null; out [Bn][2][l][N].  shared_input: rot holds Bn ciphertexts and
+// every term of output b rotates rot[b] (one decomposition per output).  Dry runs count and return.
 int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const int32_t* steps, size_t Bn, int l,
-                  const u64* plain, u64 plain_bs, u64* out);
+                  const u64* plain, u64 plain_bs, u64* out, bool shared_input = false);
 int moddown_add_fp(hisa_ctx* ctx, const u64* acc, size_t B, int l, const u64* add, u64 add_bs, int add_polys, u64 add_galois,
                    u64* out);
 // exact integer nearest to the double v (ties away from zero), reduced modulo q
@@ -304,7 +305,7 @@ hipError_t launch_inner_product_steps_fp(const FpPrime* fprimes, const u64* ext,
 // (digits from the unrotated polynomial); acc[b] = sum_s sum_j sigma_s(e_j) * key_s[j] on the l + K limbs.
 hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
                                        int alpha, const IpSteps& steps, int n_steps, int total, const u64* own_src, u64 own_bs,
-                                       u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st);
+                                       u64* acc, u64 acc_bs, u64 n_batch, int shared_input, int log_n, hipStream_t st);
 
 // sampling (counter-based generator, both sides of the parity tests implement it)
 hipError_t launch_sample_uniform(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, const PolyMap& map, int n_polys,
@@ -340,10 +341,11 @@ struct GaloisTab { uint32_t g[GALOIS_TAB_MAX]; };
 // several automorphisms of the same inputs: out entry (s, b) = sigma_{tab.g[s]}(in entry b), entries out_bs words apart
 hipError_t launch_automorph_steps(const u64* in, u64 in_bs, u64* out, u64 out_bs, const GaloisTab& tab, int n_steps,
                                   int n_polys, u64 n_batch, int log_n, hipStream_t st);
-// out[b] = (plain[b].c0 + sum_s sigma_{tab.g[s]}(rot[s * n_batch + b].c0), plain[b].c1) on l limbs; plain may be null
+// out[b] = (plain[b].c0 + sum_s sigma_{tab.g[s]}(rot[s * n_batch + b].c0), plain[b].c1) on l limbs; plain may be null;
+// shared_input: every term of output b is rot[b]
 hipError_t launch_automorph_sum(const PrimeConst* primes, const u64* rot, u64 rot_bs, int n_rot, const GaloisTab& tab,
-                                const u64* plain, u64 plain_bs, u64* out, u64 out_bs, u64 n_batch, int l, int log_n,
-                                hipStream_t st);
+                                const u64* plain, u64 plain_bs, u64* out, u64 out_bs, u64 n_batch, int shared_input, int l,
+                                int log_n, hipStream_t st);
 hipError_t launch_reduce_i64(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs, int n_pts, int log_n,
                              hipStream_t st);
 // the same with the output entries out_limbs limbs apart (residues on a second list of primes go behind the first)

@@ -799,8 +799,9 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const Fp
     }
 }
 
-// The sum over rotations of DIFFERENT ciphertexts, before the division by P: entry (s, b) of ext / own_src is term s of
-// output b (its digits computed from the unrotated polynomial, gathered here through sigma_s like the own-digit limbs),
+// The sum over rotations, before the division by P: entry (s, b) of ext / own_src is term s of output b (its digits
+// computed from the unrotated polynomial, gathered here through sigma_s like the own-digit limbs) -- or, with
+// shared_input, entry b for every s: all terms of an output rotate the same ciphertext --
 // acc[b] = sum_s sum_j sigma_s(e_{s,b,j}) * key_s[j].  A rotation's key values stay in registers across the IPS_BCH
 // outputs of a block; partial sums are normalised per rotation (eight terms of at most 0.875 * 2^50 stay below 2^53)
 // and the running sums every eight rotations.
@@ -808,7 +809,8 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const Fp
 __global__ __launch_bounds__(IPF_NT) void inner_product_sum_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs,
                                                                       int digits, int l, int K, int L, int alpha, IpSteps steps,
                                                                       int n_steps, int total, const u64* own_src, u64 own_bs,
-                                                                      u64* acc, u64 acc_bs, u64 n_batch, int log_n) {
+                                                                      u64* acc, u64 acc_bs, u64 n_batch, int shared_input,
+                                                                      int log_n) {
     const u64 n = (u64)1 << log_n;
     const uint32_t j = blockIdx.x * IPF_NT + threadIdx.x;
     const int x = blockIdx.y;
@@ -834,7 +836,7 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_sum_fp_kernel(const FpPr
 #pragma unroll
         for (int u = 0; u < IPS_BCH; u++) {
             if (b0 + u < n_batch) {
-                const u64 entry = (u64)s * n_batch + b0 + u;
+                const u64 entry = (shared_input ? 0 : (u64)s * n_batch) + b0 + u;
                 double sb = 0.0, sa = 0.0;
 #pragma unroll
                 for (int d = 0; d < IPF_MAXD; d++) {
@@ -864,7 +866,7 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_sum_fp_kernel(const FpPr
 
 hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
                                        int alpha, const IpSteps& steps, int n_steps, int total, const u64* own_src, u64 own_bs,
-                                       u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st) {
+                                       u64* acc, u64 acc_bs, u64 n_batch, int shared_input, int log_n, hipStream_t st) {
     DRY_RUN_RETURN();
     if (digits < 1 || digits > IPF_MAXD || n_steps < 1 || n_steps > FP_MAX_STEPS || l < 1 || K < 1 || alpha < 1) return hipErrorInvalidValue;
     if (!fprimes || !ext || !own_src || !acc || n_batch == 0 || n_batch > 65535u * IPS_BCH) return hipErrorInvalidValue;
@@ -877,7 +879,7 @@ hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const u64* ext, u
     dim3 grid((1u << log_n) / IPF_NT, l + K, (unsigned)((n_batch + IPS_BCH - 1) / IPS_BCH));
     ProfScope prof__("inner_product_sum_fp_kernel", st);
     hipLaunchKernelGGL(inner_product_sum_fp_kernel, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha, steps,
-                       n_steps, total, own_src, own_bs, acc, acc_bs, n_batch, log_n);
+                       n_steps, total, own_src, own_bs, acc, acc_bs, n_batch, shared_input, log_n);
     return hipGetLastError();
 }
 

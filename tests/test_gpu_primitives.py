@@ -253,6 +253,16 @@ def test_rotation_sums_match_oracle(pair, request):
                 ins = [oterms[s][b] for s in range(len(steps))]
                 want = SharedModDown(o, ins).total([(s, steps[s], 1, None) for s in range(len(steps))], ins[0].scale)
                 same(g, o, out[b], want)
+        # all rotated terms the same ciphertext (one decomposition per output): the same bits as with copies of it
+        steps = [7, 0, 1, 64]
+        out = g.rot_left_sum_batch([gs[:n_out]] * 4, steps)
+        for b in range(n_out):
+            want = SharedModDown(o, [os_[b]] * 4).total([(s, steps[s], 1, None) for s in range(4)], os_[b].scale)
+            same(g, o, out[b], want)
+        out2 = g.rot_left_sum_batch([gs[:n_out], gs[n_out:2 * n_out], gs[:n_out]], [7, 0, 1])
+        for b in range(n_out):
+            ins = [os_[b], os_[n_out + b], os_[b]]
+            same(g, o, out2[b], SharedModDown(o, ins).total([(0, 7, 1, None), (1, 0, 1, None), (2, 1, 1, None)], ins[0].scale))
         if level == 0:
             # the decrypted sum is the sum of the decrypted rotations (top level only: the rescaling below leaves
             # these 40-bit test messages only a few bits above its rounding)
