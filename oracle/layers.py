@@ -249,7 +249,7 @@ def conv2d_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, mo
     return OTensor(outs, t.batch, oc_n, oh, ow, t.h_stride * stride, t.w_stride * stride, t.offset, clean)
 
 
-def fc(o: Oracle, t: OTensor, w):
+def fc(o: Oracle, t: OTensor, w, merge=0):
     """w[OUT][C][H][W].  Returns (output tensor, plaintext coefficients [OUT][C][N], their scale)."""
     out_n = w.shape[0]
     l = t.cts[0].limbs
@@ -265,7 +265,7 @@ def fc(o: Oracle, t: OTensor, w):
             z = np.zeros(o.slots)
             z[sl] = np.asarray(w[k, c], dtype=np.float64).reshape(-1)
             coeffs[k, c] = o.encode_coeffs(z, pt_scale)
-    return fc_fixed(o, t, coeffs, pt_scale), {"pt_coeffs": coeffs, "pt_scale": pt_scale}
+    return fc_fixed(o, t, coeffs, pt_scale, merge), {"pt_coeffs": coeffs, "pt_scale": pt_scale}
 
 
 def fc_reduce_steps(o: Oracle, t: OTensor):
@@ -296,6 +296,34 @@ def reduce_steps(t: OTensor, limit):
     return strided if fits and len(strided) < len(window) else window
 
 
+def merge_doublings(steps, merge):
+    """Rotate-and-add steps s, 2s, 4s, .. add up all multiples of s below 2^k s: up to `merge` consecutive doublings
+    are taken as ONE sum of the 2^c - 1 rotations by s, 2s, 3s, .. of the same ciphertext (one decomposition, one
+    division by P: SharedModDown) instead of c rotations one after the other.  Returns the groups of amounts;
+    merge < 2 leaves every step a group of its own."""
+    groups = []
+    i = 0
+    while i < len(steps):
+        c = 1
+        while merge >= 2 and c < merge and i + c < len(steps) and steps[i + c] == 2 * steps[i + c - 1]:
+            c += 1
+        groups.append([steps[i]] if c == 1 else [m * steps[i] for m in range(1, 1 << c)])
+        i += c
+    return groups
+
+
+def rotate_and_add(o: Oracle, x, groups, right=False):
+    """x += rot(x, a) for the single amounts, x = sum over {0} + group of rot(x, a) with one division by P for the
+    others (rotLeft amounts; right: rotRight amounts)."""
+    for grp in groups:
+        amounts = [(o.slots - a) % o.slots for a in grp] if right else [a % o.slots for a in grp]
+        if len(amounts) == 1:
+            x = o.add(x, o.rot_right(x, grp[0]) if right else o.rot_left(x, amounts[0]))
+        else:
+            x = SharedModDown(o, [x]).total([(0, 0, 1, None)] + [(0, a, 1, None) for a in amounts], x.scale)
+    return x
+
+
 def matmul_geometry(o: Oracle, t: OTensor, replicas):
     """Block length P (the power of two that covers every element slot of a ciphertext), the number of replicas R
     actually used (a power of two, at most `replicas` and at most slots / P), the rotRight amounts that build the
@@ -311,7 +339,7 @@ def matmul_geometry(o: Oracle, t: OTensor, replicas):
     return block, r, replicate, reduce_steps(t, block if r > 1 else o.slots)
 
 
-def matmul(o: Oracle, t: OTensor, w, replicas):
+def matmul(o: Oracle, t: OTensor, w, replicas, merge=0):
     """Homomorphic matmul with replicas.  w[OUT][C][H][W].  Returns (CHW-tiled output tensor with R 1x1 channels per
     ciphertext, dict of the fixed-point integers used)."""
     out_n = w.shape[0]
@@ -342,14 +370,15 @@ def matmul(o: Oracle, t: OTensor, w, replicas):
                     z[rep * block + sl[cl]] = w[g * r + rep, j * t.c_inner + cl]
             coeffs[g, j] = o.encode_coeffs(z, pt_scale)
     ints.update(pt_coeffs=coeffs, pt_scale=pt_scale)
-    return matmul_fixed(o, t, ints, out_n, replicas), ints
+    return matmul_fixed(o, t, ints, out_n, replicas, merge), ints
 
 
-def matmul_fixed(o: Oracle, t: OTensor, ints, out_n, replicas):
+def matmul_fixed(o: Oracle, t: OTensor, ints, out_n, replicas, merge=0):
     """1. (input not clean, R > 1) mulPlain by the 0/1 mask + divScalar, so that step 2 copies zeros and not leftovers;
     2. log2 R times x += rotRight(x, P 2^k): R copies of the elements, P slots apart;  3. per group g of R outputs:
     sum over the input ciphertexts of mulPlain(x_j, weights of outputs gR..gR+R-1, output gR+r on the r-th copy),
-    divScalar;  4. rotate-and-add inside the blocks: output gR+r ends in slot r P + offset."""
+    divScalar;  4. rotate-and-add inside the blocks: output gR+r ends in slot r P + offset.  merge: steps 2 and 4 take
+    up to that many consecutive doublings as one sum of rotations (merge_doublings)."""
     block, r, replicate, reduce = matmul_geometry(o, t, replicas)
     per = cts_per_image(t)
     groups = -(-out_n // r)
@@ -364,21 +393,18 @@ def matmul_fixed(o: Oracle, t: OTensor, ints, out_n, replicas):
                     temp = o.mul_plain(x, pt)
                     masked.append(o.div_scalar(temp, o.max_scalar_div(temp, float("inf"))))
                 xs = masked
-            for amount in replicate:
-                xs = [o.add(x, o.rot_right(x, amount)) for x in xs]
+            xs = [rotate_and_add(o, x, merge_doublings(replicate, merge), right=True) for x in xs]
         for g in range(groups):
             acc = None
             for j, x in enumerate(xs):
                 temp = o.mul_plain(x, o.pt_from_coeffs(ints["pt_coeffs"][g, j], ints["pt_scale"], x.limbs))
                 acc = temp if acc is None else o.add(acc, temp)
             acc = o.rescale(acc)
-            for amount in reduce:
-                acc = o.add(acc, o.rot_left(acc, amount))
-            outs.append(acc)
+            outs.append(rotate_and_add(o, acc, merge_doublings(reduce, merge)))
     return OTensor(outs, t.batch, out_n, 1, 1, 1, 1, t.offset, 0, r, block)
 
 
-def fc_fixed(o: Oracle, t: OTensor, coeffs, pt_scale):
+def fc_fixed(o: Oracle, t: OTensor, coeffs, pt_scale, merge=0):
     out_n = coeffs.shape[0]
     l = t.cts[0].limbs
     steps = fc_reduce_steps(o, t)
@@ -390,9 +416,8 @@ def fc_fixed(o: Oracle, t: OTensor, coeffs, pt_scale):
                 temp = o.mul_plain(t.cts[b * t.channels + c], o.pt_from_coeffs(coeffs[k, c], pt_scale, l))
                 acc = temp if acc is None else o.add(acc, temp)
             acc = o.rescale(acc)
-            for r in steps:               # rotate-and-add: slot `offset` collects every element of the plane
-                acc = o.add(acc, o.rot_left(acc, r))
-            outs.append(acc)
+            # rotate-and-add: slot `offset` collects every element of the plane
+            outs.append(rotate_and_add(o, acc, merge_doublings(steps, merge)))
     return OTensor(outs, t.batch, out_n, 1, 1, 1, 1, t.offset, 0)
 
 

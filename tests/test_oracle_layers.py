@@ -206,6 +206,53 @@ def test_chw_tensor_round_trip_and_clean_input_needs_no_mask():
     assert np.abs(layers.tensor_decrypt(o, m) - plain_net.fc(x, w)).max() <= 1e-3
 
 
+def test_merged_doublings_in_reductions():
+    """Rotate-and-add chains taken as sums of rotations: the grouping rule, and FC / matmul values against the fp64
+    layers and against the step-by-step chains (same sums up to the noise of the key switches)."""
+    assert layers.merge_doublings([2, 4, 8, 16, 60, 120, 240, 480], 4) == [[2 * m for m in range(1, 16)], [60 * m for m in range(1, 16)]]
+    assert layers.merge_doublings([1, 2, 4, 8, 16, 32], 4) == [[m for m in range(1, 16)], [16, 32, 48]]
+    assert layers.merge_doublings([2, 8], 4) == [[2], [8]] and layers.merge_doublings([1, 2, 4], 0) == [[1], [2], [4]]
+    assert layers.merge_doublings([1, 2, 4], 2) == [[1, 2, 3], [4]]
+    o = Oracle(11, [50, 45, 45, 45, 45, 45], 3, 55, seed=12)
+    o.keygen()
+    x = synth.image(23, 3, 4, 4)[None]
+    t = layers.tensor_encrypt(o, x, 2.0 ** 45, 6)
+    w = synth.fc_weights(24, 6, 3, 4, 4, std=0.3)
+    block, r, replicate, reduce = layers.matmul_geometry(o, t, 4)
+    assert (block, r, replicate, reduce) == (16, 4, [16, 32], [1, 2, 4, 8])
+    amounts = {a for g in layers.merge_doublings(reduce, 4) for a in g} | \
+        {o.slots - a for g in layers.merge_doublings(replicate, 4) for a in g} | set(reduce) | {o.slots - a for a in replicate}
+    o.gen_rot_keys(sorted(amounts))
+    counts = {"rot_left": 0, "key_switch_acc": 0, "mod_down": 0}
+    real = {n: getattr(o, n) for n in counts}
+    for name in counts:
+        def f(*a, _n=name, **k):
+            counts[_n] += 1
+            return real[_n](*a, **k)
+        setattr(o, name, f)
+    m4, _ = layers.matmul(o, t, w, 4, merge=4)
+    for name in counts:
+        setattr(o, name, real[name])
+    groups = 2                                            # ceil(6 / 4)
+    # replicas: one sum of 3 rotations per input ciphertext; reduction: one sum of 15 rotations per group
+    assert counts["rot_left"] == 0 and counts["key_switch_acc"] == 3 * 3 + groups * 15
+    assert counts["mod_down"] == 2 * (3 + groups)
+    ref = plain_net.fc(x, w)
+    assert np.abs(layers.tensor_decrypt(o, m4) - ref).max() <= 1e-3
+    m0, _ = layers.matmul(o, t, w, 4)
+    assert np.abs(layers.tensor_decrypt(o, m4) - layers.tensor_decrypt(o, m0)).max() <= 1e-5
+    f4, _ = layers.fc(o, t, w, merge=4)
+    f0, _ = layers.fc(o, t, w)
+    assert np.abs(layers.tensor_decrypt(o, f4) - ref).max() <= 1e-3
+    assert np.abs(layers.tensor_decrypt(o, f4) - layers.tensor_decrypt(o, f0)).max() <= 1e-5
+    # a planted mistake shows: one amount of a merged group left out
+    bad = layers.rotate_and_add(o, t.cts[0], [[1, 2]])
+    good = layers.rotate_and_add(o, t.cts[0], [[1, 2, 3]])
+    step = layers.rotate_and_add(o, t.cts[0], [[1], [2]])
+    assert np.abs(o.decode(o.decrypt(good)) - o.decode(o.decrypt(step))).max() <= 1e-6
+    assert np.abs(o.decode(o.decrypt(bad)) - o.decode(o.decrypt(step))).max() > 1e-2
+
+
 def test_chw_conv_matches_plain_conv_and_op_counts():
     """CHW-tiled convolution against the fp64 convolution: 5 -> 6 channels, 4 channel blocks per ciphertext (ragged
     last ciphertexts on both sides), VALID and SAME (the SAME one reads the zero border the layout provides), once
