@@ -190,6 +190,15 @@ int hisa_rot_left_hoisted_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t 
  * and dnum <= 8 (HISA_ERR_ARG otherwise), and every step's key (HISA_ERR_NO_KEY before any work is queued). */
 int hisa_rot_left_sum_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n_out, const int32_t* steps, size_t n_terms,
                             hisa_ct** out);
+/* Rotate-and-add chains x += rot(x, s); x += rot(x, 2s); x += rot(x, 4s); .. (the log-step reductions and replications of
+ * hisa_fc and hisa_matmul*) add up all multiples of s below 2^k s.  With max_doublings = 2..4 those layers take up to
+ * that many consecutive doublings as ONE sum of the 2^c - 1 rotations by s, 2s, 3s, .. of the same ciphertext
+ * (hisa_rot_left_sum_batch: one decomposition, one division by P) instead of c key switches one after the other:
+ * more rotation keys (hisa_fc_rot_steps / hisa_matmul_rot_steps list them), fewer and larger launches; the same sums
+ * up to the rounding of the divisions, other ciphertext bits.  0 (the default) keeps the chains.  Needs what
+ * hisa_rot_left_sum_batch needs (HISA_ERR_ARG otherwise, and for other values).  A plan prepared under one setting
+ * must be applied under the same one (the plaintexts do not depend on it, the rotation keys do). */
+int hisa_set_merge_doublings(hisa_ctx* ctx, uint32_t max_doublings);
 int hisa_relinearize_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n);
 int hisa_rescale_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n);
 int hisa_add_batch(hisa_ctx* ctx, const hisa_ct* const* a, const hisa_ct* const* b, size_t n, hisa_ct** out);

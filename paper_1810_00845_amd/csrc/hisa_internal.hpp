@@ -118,6 +118,7 @@ struct hisa_ctx {
     u64* d_secret;  // [total][N], NTT form
     std::map<u64, SwitchKey> keys;  // 0: relinearisation, else Galois element
     struct Analysis* analysis = nullptr;   // non-null between hisa_analysis_begin and hisa_analysis_end
+    uint32_t merge_doublings = 0;          // hisa_set_merge_doublings: rotate-and-add chains as sums of rotations (0, 2..4)
     std::map<u64, SwitchKey> aux;   // small derived device tables, built on first use
     std::map<std::pair<int, int>, ConvTable> modup_tabs;  // (digit, size)
     ConvTable* moddown_tab;

@@ -586,10 +586,39 @@ static std::vector<i64> reduce_steps(const hisa_tensor* in, u64 limit) {
 
 static std::vector<i64> fc_reduce_steps(const hisa_ctx* ctx, const hisa_tensor* in) { return reduce_steps(in, ctx->N / 2); }
 
+// Steps s, 2s, 4s, .. of a rotate-and-add chain add up all multiples of s below 2^k s: up to ctx->merge_doublings
+// consecutive doublings become one group of the 2^c - 1 amounts s, 2s, 3s, .. that is summed in one call
+// (hisa_set_merge_doublings).  Every other step is a group of its own.
+static std::vector<std::vector<i64>> merge_doublings(const hisa_ctx* ctx, const std::vector<i64>& steps) {
+    std::vector<std::vector<i64>> groups;
+    const size_t merge = ctx->merge_doublings;
+    for (size_t i = 0; i < steps.size();) {
+        size_t c = 1;
+        while (merge >= 2 && c < merge && i + c < steps.size() && steps[i + c] == 2 * steps[i + c - 1]) c++;
+        std::vector<i64> grp;
+        if (c == 1) grp.push_back(steps[i]);
+        else
+            for (i64 m = 1; m < ((i64)1 << c); m++) grp.push_back(m * steps[i]);
+        groups.push_back(grp);
+        i += c;
+    }
+    return groups;
+}
+
+extern "C" int hisa_set_merge_doublings(hisa_ctx* ctx, uint32_t max_doublings) {
+    if (!ctx) return HISA_ERR_ARG;
+    if (max_doublings == 1 || max_doublings > 4) return fail(ctx, HISA_ERR_ARG, "max_doublings is 0 or 2..4");
+    if (max_doublings && !fused_key_switch_available(ctx))
+        return fail(ctx, HISA_ERR_ARG, "sums of rotations need the fused key-switch path (N >= 2^12, every prime below 2^50, dnum <= 8)");
+    ctx->merge_doublings = max_doublings;
+    return HISA_OK;
+}
+
 extern "C" int hisa_fc_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, int32_t* steps, size_t cap, size_t* n) {
     if (!ctx || !in) return HISA_ERR_ARG;
     std::vector<int32_t> all;
-    for (i64 r : fc_reduce_steps(ctx, in)) all.push_back(norm_step(ctx, r));
+    for (const auto& grp : merge_doublings(ctx, fc_reduce_steps(ctx, in)))
+        for (i64 r : grp) all.push_back(norm_step(ctx, r));
     return write_steps(all, steps, cap, n);
 }
 
@@ -1487,20 +1516,12 @@ static int fc_chunk(hisa_ctx* ctx, const hisa_tensor* in, const BatchIn& bi, con
     return HISA_OK;
 }
 
+static int rotate_add_chain(hisa_ctx* ctx, std::vector<hisa_ct*>& xs, const std::vector<i64>& steps, int sign);
+
 static int fc_finish(hisa_ctx* ctx, const hisa_tensor* in, std::vector<hisa_ct*>& outs, uint32_t OUT, hisa_tensor* out) {
     int rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
     // rotate-and-add: after the last step slot `offset` holds the sum over all elements of the plane
-    for (i64 r : fc_reduce_steps(ctx, in)) {
-        if (rc != HISA_OK) break;
-        std::vector<hisa_ct*> rot(outs.size(), nullptr);
-        rc = hisa_rot_left_batch(ctx, (const hisa_ct* const*)outs.data(), outs.size(), norm_step(ctx, r), rot.data());
-        if (rc != HISA_OK) break;
-        hipError_t e = launch_addsub(ctx->d_primes, outs[0]->data, rot[0]->data, outs[0]->data, OP_ADD, (int)outs[0]->limbs, 2,
-                                     2, outs.size(), ct_words(ctx, 2, outs[0]->limbs), ct_words(ctx, 2, outs[0]->limbs),
-                                     ct_words(ctx, 2, outs[0]->limbs), (int)ctx->log_n, ctx->stream);
-        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "fc add: %s", hipGetErrorString(e));
-        free_handles(ctx, rot);
-    }
+    if (rc == HISA_OK) rc = rotate_add_chain(ctx, outs, fc_reduce_steps(ctx, in), 1);
     if (rc != HISA_OK) {
         free_handles(ctx, outs);
         return rc;
@@ -1697,8 +1718,10 @@ extern "C" int hisa_matmul_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, uint3
     MatmulGeom g;
     TRY(matmul_geom(ctx, in, replicas, &g));
     std::vector<int32_t> all;
-    for (i64 r : g.replicate) all.push_back(norm_step(ctx, -r));
-    for (i64 r : g.reduce) all.push_back(norm_step(ctx, r));
+    for (const auto& grp : merge_doublings(ctx, g.replicate))
+        for (i64 r : grp) all.push_back(norm_step(ctx, -r));
+    for (const auto& grp : merge_doublings(ctx, g.reduce))
+        for (i64 r : grp) all.push_back(norm_step(ctx, r));
     return write_steps(all, steps, cap, n);
 }
 
@@ -1711,6 +1734,29 @@ static int rotate_add_batch(hisa_ctx* ctx, std::vector<hisa_ct*>& xs, int32_t st
                                  words, words, words, (int)ctx->log_n, ctx->stream);
     free_handles(ctx, rot);
     if (e != hipSuccess) return fail(ctx, HISA_ERR_HIP, "rotate-and-add: %s", hipGetErrorString(e));
+    return HISA_OK;
+}
+
+// A whole rotate-and-add chain over a batch (rotLeft amounts; sign = -1: rotRight): single steps in place, merged
+// groups as one sum of rotations of the same ciphertexts (new handles replace xs)
+static int rotate_add_chain(hisa_ctx* ctx, std::vector<hisa_ct*>& xs, const std::vector<i64>& steps, int sign) {
+    for (const auto& grp : merge_doublings(ctx, steps)) {
+        if (grp.size() == 1) {
+            TRY(rotate_add_batch(ctx, xs, norm_step(ctx, sign * grp[0])));
+            continue;
+        }
+        const size_t nb = xs.size(), terms = grp.size() + 1;
+        std::vector<const hisa_ct*> in(terms * nb);
+        std::vector<int32_t> amounts(terms, 0);               // term 0: the ciphertext itself
+        for (size_t s = 0; s < terms; s++) {
+            if (s) amounts[s] = norm_step(ctx, sign * grp[s - 1]);
+            for (size_t b = 0; b < nb; b++) in[s * nb + b] = xs[b];
+        }
+        std::vector<hisa_ct*> sum(nb, nullptr);
+        TRY(hisa_rot_left_sum_batch(ctx, in.data(), nb, amounts.data(), terms, sum.data()));
+        free_handles(ctx, xs);
+        xs = sum;
+    }
     return HISA_OK;
 }
 
@@ -1918,8 +1964,7 @@ static int matmul_run(hisa_ctx* ctx, const hisa_tensor* in, const MatmulGeom& g,
             }
             dev_release(ctx, bi.tmp);
         }
-        for (size_t k = 0; k < g.replicate.size() && rc == HISA_OK; k++)
-            rc = rotate_add_batch(ctx, xs, norm_step(ctx, -g.replicate[k]));
+        if (rc == HISA_OK) rc = rotate_add_chain(ctx, xs, g.replicate, -1);
         if (rc != HISA_OK) { free_handles(ctx, xs); return rc; }
     }
     hisa_ct* const* src = g.R > 1 ? xs.data() : in->cts;
@@ -1940,7 +1985,7 @@ static int matmul_run(hisa_ctx* ctx, const hisa_tensor* in, const MatmulGeom& g,
     dev_release(ctx, bi.tmp);
     free_handles(ctx, xs);
     if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
-    for (size_t k = 0; k < g.reduce.size() && rc == HISA_OK; k++) rc = rotate_add_batch(ctx, outs, norm_step(ctx, g.reduce[k]));
+    if (rc == HISA_OK) rc = rotate_add_chain(ctx, outs, g.reduce, 1);
     if (rc != HISA_OK) {
         free_handles(ctx, outs);
         return rc;

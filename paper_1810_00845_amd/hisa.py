@@ -334,6 +334,10 @@ class Context:
         self._ck(load().hisa_rot_left_sum_batch(self._vp, self._harr(flat), C.c_size_t(n), st, C.c_size_t(ns), arr))
         return [self._new_ct(int(arr[i])) for i in range(n)]
 
+    def set_merge_doublings(self, max_doublings):
+        """FC / matmul rotate-and-add chains as sums of rotations: 0 (off) or 2..4 consecutive doublings per sum."""
+        self._ck(load().hisa_set_merge_doublings(self._vp, C.c_uint32(max_doublings)))
+
     def add_batch(self, a, b):
         return self._batch_out("hisa_add_batch", len(a), self._harr(a), self._harr(b), C.c_size_t(len(a)))
 

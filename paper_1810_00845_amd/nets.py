@@ -110,7 +110,7 @@ def chw_blocks(slots, plane_slots_needed, layers, chw_convs=True):
 
 
 def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans=None, layout="hw", shared_moddown=True,
-                  layer_times=True, rotate_sums=True):
+                  layer_times=True, rotate_sums=True, merge_doublings=4):
     """Encrypts x, runs the layers, decrypts.  Returns (output array, seconds from encrypt-done to the last
     ciphertext ready, per-layer seconds).  With make_keys the rotation keys each layer asks for are generated
     on the way (set-up pass); otherwise they must be resident.  `plans` (a dict, filled by the set-up pass and
@@ -124,10 +124,14 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
     for the way to HW, one for the masking multiply that makes Algorithm 1's output clean enough to pack).
     shared_moddown: the convolutions divide by P once per output ciphertext instead of once per rotation (where the
     parameters have the fused key-switch path).  rotate_sums: a CHW-tiled convolution reduces over the channel blocks
-    after the multiplication (HISA_CHW_ROTATE_SUMS) where that takes fewer key switches.  layer_times: wait for the GPU after every layer to time it; without,
+    after the multiplication (HISA_CHW_ROTATE_SUMS) where that takes fewer key switches.  merge_doublings: the
+    rotate-and-add chains of FC and matmul take up to that many consecutive doublings as one sum of rotations
+    (hisa_set_merge_doublings; 0: the chains as they are).  layer_times: wait for the GPU after every layer to time it; without,
     the host queues the whole network ahead of the GPU and only the end-to-end latency is measured (per-layer entries
     are then host queueing times)."""
     assert layout in LAYOUTS
+    fused = ctx.log_n >= 12 and max(ctx.primes) < 2 ** 50 and ctx.dnum <= 8
+    ctx.set_merge_doublings(merge_doublings if fused else 0)
     replicas = 1 if layout == "hw" else 1 << 30
     tiling = {}
     if layout in ("chw", "hw_conv"):
@@ -358,8 +362,13 @@ def measure_costs(ctx, limbs, batch=64, reps=5):
     costs["rot_shared"] = min(0.0, (hoisted - 3 * full) / 2)
     costs["rot_summed"] = 0.0                 # what a rotation saves inside a sum that divides by P once
     if ctx.log_n >= 12 and max(ctx.primes) < 2 ** 50 and ctx.dnum <= 8:
-        summed = timed(lambda: free(ctx.rot_left_sum_batch([cts, cts, cts], [1, 2, 3])))   # three terms per output
+        # three terms per output, each a different ciphertext (terms that rotate the same one would share the
+        # decomposition as well, which "rot_shared" already prices)
+        terms = [cts, cts[1:] + cts[:1], cts[2:] + cts[:2]]
+        summed = timed(lambda: free(ctx.rot_left_sum_batch(terms, [1, 2, 3])))
         costs["rot_summed"] = min(0.0, (summed - 3 * full) / 2)
+        # a rotation that shares both still has its inner product to pay
+        costs["rot_summed"] = max(costs["rot_summed"], -0.9 * (costs["rot_left"] + costs["rot_shared"]))
     costs["add"] = timed(lambda: free(ctx.add_batch(cts, cts)))
     costs["mul"] = timed(lambda: free(ctx.mul_no_relin_batch(cts, cts)))
     costs["mul_plain"] = timed(lambda: free(ctx.mul_plain_batch(cts, pt)))

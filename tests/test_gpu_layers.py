@@ -251,6 +251,61 @@ def test_matmul_with_replicas_bit_exact():
     g.close()
 
 
+def test_merged_doublings_in_fc_and_matmul_bit_exact():
+    """hisa_set_merge_doublings: the rotate-and-add chains of matmul (replicas and reduction) and FC as sums of
+    rotations, against the oracle's merge_doublings schedule bit for bit (fp64 key-switch path, N = 2^12), the extra
+    rotation amounts, the dry run's counts, and the refusals."""
+    from oracle import layers
+    from paper_1810_00845_amd import hisa, synth
+    g, o = make_pair(12, [50, 45, 45, 45, 45], 2, 50, 21)
+    g.keygen(); o.keygen()
+    x = synth.image(25, 3, 4, 4)[None].repeat(2, axis=0) * np.array([1.0, -0.5])[:, None, None, None]
+    gt, ot = both_tensors(g, o, x, 2.0 ** 45, 5)
+    w = synth.fc_weights(26, 6, 3, 4, 4, std=0.3)
+    ref = plain_net.fc(x, w)
+    plain_steps = g.matmul_rot_steps(gt, 4)
+    for merge in (4, 2):
+        g.set_merge_doublings(merge)
+        block, r, replicate, reduce = layers.matmul_geometry(o, ot, 4)
+        want_steps = sorted({a for grp in layers.merge_doublings(reduce, merge) for a in grp} |
+                            {o.slots - a for grp in layers.merge_doublings(replicate, merge) for a in grp})
+        steps = g.matmul_rot_steps(gt, 4)
+        assert steps == want_steps and set(plain_steps) <= set(steps) and len(steps) > len(plain_steps)
+        assert g.fc_rot_steps(gt) == sorted({a for grp in layers.merge_doublings(layers.fc_reduce_steps(o, ot), merge) for a in grp})
+        g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+        om, ints = layers.matmul(o, ot, w, 4, merge=merge)
+        gm = g.matmul_fixed(gt, ints["pt_coeffs"], ints["pt_scale"], ints["mask_coeffs"], ints["mask_scale"], 6, 4)
+        same_tensor(g, o, gm, om)
+        assert np.abs(g.tensor_decrypt(gm) - ref).max() <= 1e-3
+        plan = g.matmul_prepare(gt, w, 4)
+        gplan, gfloat = g.matmul_apply(gt, plan), g.matmul(gt, w, 4)
+        for ca, cb in zip(gfloat.cts, gplan.cts):
+            assert np.array_equal(g.ct_export(ca), g.ct_export(cb))
+        assert np.abs(g.tensor_decrypt(gfloat) - ref).max() <= 1e-3
+        g.matmul_plan_free(plan)
+        of, fints = layers.fc(o, ot, w, merge=merge)
+        gf = g.fc_fixed(gt, fints["pt_coeffs"], fints["pt_scale"])
+        same_tensor(g, o, gf, of)
+        assert np.abs(g.tensor_decrypt(gf) - ref).max() <= 1e-3
+    # dry run with merge = 2: per image 3 inputs x (one sum of 3 rotations), 2 groups x (sums of 3 + 3 rotations)
+    g.analysis_begin()
+    g.matmul(gt, w, 4)
+    counts, dry_steps = g.analysis_end()
+    assert counts["rot_summed"] == 2 * (3 * 3 + 2 * 6) and counts["rot_shared"] == 2 * (3 * 2 + 2 * 4)
+    assert dry_steps == g.matmul_rot_steps(gt, 4)
+    g.set_merge_doublings(0)
+    assert g.matmul_rot_steps(gt, 4) == plain_steps
+    with pytest.raises(hisa.HisaError) as e:
+        g.set_merge_doublings(5)
+    assert e.value.code == -1
+    g.close()
+    g2, _ = make_pair(11, [50, 45, 45], 3, 55, 12)          # no fused key switch
+    with pytest.raises(hisa.HisaError) as e:
+        g2.set_merge_doublings(4)
+    assert e.value.code == -1
+    g2.close()
+
+
 def test_chw_tensor_layers_and_errors():
     """CHW-tiled tensors through encrypt / decrypt / pool / activation / matmul (clean input: no mask, one level),
     a last ciphertext with fewer channels, and the error paths: conv2d and fc refuse CHW tiling, overlapping
