@@ -195,7 +195,8 @@ int hisa_rot_left_sum_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n_ou
  * that many consecutive doublings as ONE sum of the 2^c - 1 rotations by s, 2s, 3s, .. of the same ciphertext
  * (hisa_rot_left_sum_batch: one decomposition, one division by P) instead of c key switches one after the other:
  * more rotation keys (hisa_fc_rot_steps / hisa_matmul_rot_steps list them), fewer and larger launches; the same sums
- * up to the rounding of the divisions, other ciphertext bits.  0 (the default) keeps the chains.  Needs what
+ * up to the rounding of the divisions, other ciphertext bits.  hisa_sum_pool2x2 then takes its four corners as one
+ * such sum as well.  0 (the default) keeps the chains.  Needs what
  * hisa_rot_left_sum_batch needs (HISA_ERR_ARG otherwise, and for other values).  A plan prepared under one setting
  * must be applied under the same one (the plaintexts do not depend on it, the rotation keys do). */
 int hisa_set_merge_doublings(hisa_ctx* ctx, uint32_t max_doublings);

@@ -421,11 +421,17 @@ def fc_fixed(o: Oracle, t: OTensor, coeffs, pt_scale, merge=0):
     return OTensor(outs, t.batch, out_n, 1, 1, 1, 1, t.offset, 0)
 
 
-def sum_pool2x2(o: Oracle, t: OTensor):
+def sum_pool2x2(o: Oracle, t: OTensor, merge=0):
+    """x + rot(x, w_stride) + rot(x, h_stride) + rot(x, h_stride + w_stride); merge >= 2: as one sum with a single
+    division by P (the chain x += rot(x, w_stride); x += rot(x, h_stride) merged, as in merge_doublings)."""
     outs = []
     for ct in t.cts:
+        amounts = (t.w_stride, t.h_stride, t.h_stride + t.w_stride)
+        if merge >= 2:
+            outs.append(SharedModDown(o, [ct]).total([(0, 0, 1, None)] + [(0, r, 1, None) for r in amounts], ct.scale))
+            continue
         acc = ct
-        for r in (t.w_stride, t.h_stride, t.h_stride + t.w_stride):
+        for r in amounts:
             acc = o.add(acc, o.rot_left(ct, r))
         outs.append(acc)
     return replace(t, cts=outs, height=t.height // 2, width=t.width // 2, h_stride=2 * t.h_stride,

@@ -2139,6 +2139,20 @@ extern "C" int hisa_sum_pool2x2(hisa_ctx* ctx, const hisa_tensor* in, hisa_tenso
     const size_t nct = t_ncts(in);   // every channel of a ciphertext is pooled by the same three rotations
     const uint32_t l = in->cts[0]->limbs;
     const u64 words = ct_words(ctx, 2, l);
+    if (ctx->merge_doublings >= 2) {
+        // the two-step chain x += rot(x, w_stride); x += rot(x, h_stride) as one sum over the four corners: one
+        // decomposition and one division by P per ciphertext (hisa_set_merge_doublings)
+        std::vector<const hisa_ct*> terms(4 * nct);
+        for (size_t i = 0; i < 4 * nct; i++) terms[i] = in->cts[i % nct];
+        const int32_t amounts[4] = {0, norm_step(ctx, (i64)in->w_stride), norm_step(ctx, (i64)in->h_stride),
+                                    norm_step(ctx, (i64)in->h_stride + in->w_stride)};
+        std::vector<hisa_ct*> sum(nct, nullptr);
+        TRY(hisa_rot_left_sum_batch(ctx, terms.data(), nct, amounts, 4, sum.data()));
+        for (size_t i = 0; i < nct; i++) out->cts[i] = sum[i];
+        fill_out_meta(out, in->batch, in->channels, in->height / 2, in->width / 2, in->h_stride * 2, in->w_stride * 2, in->offset,
+                      0, t_ci(in), in->c_stride);
+        return HISA_OK;
+    }
     std::vector<hisa_ct*> acc(nct, nullptr);
     TRY(alloc_ct_batch(ctx, nct, 2, l, in->cts[0]->scale, acc.data()));
     BatchIn bi;

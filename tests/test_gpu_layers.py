@@ -287,6 +287,11 @@ def test_merged_doublings_in_fc_and_matmul_bit_exact():
         gf = g.fc_fixed(gt, fints["pt_coeffs"], fints["pt_scale"])
         same_tensor(g, o, gf, of)
         assert np.abs(g.tensor_decrypt(gf) - ref).max() <= 1e-3
+    # the 2x2 pool as one sum over its four corners
+    g.gen_rot_keys(g.pool_rot_steps(gt)); o.gen_rot_keys(g.pool_rot_steps(gt))
+    gp, op = g.sum_pool2x2(gt), layers.sum_pool2x2(o, ot, merge=2)
+    same_tensor(g, o, gp, op)
+    assert np.abs(g.tensor_decrypt(gp) - plain_net.sum_pool2x2(x)).max() <= 1e-3
     # dry run with merge = 2: per image 3 inputs x (one sum of 3 rotations), 2 groups x (sums of 3 + 3 rotations)
     g.analysis_begin()
     g.matmul(gt, w, 4)
