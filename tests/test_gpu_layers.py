@@ -619,4 +619,22 @@ def test_new_layer_entry_points_reject_bad_arguments():
     low = g.tensor_encrypt(x, 2.0 ** 40, 1, h_stride=4)
     with pytest.raises(hisa.HisaError):
         g.tensor_mask(low)                                           # no level to rescale into
+    # sums of rotations: 33 rotated terms, terms of different scale or level
+    g.keygen()
+    g.gen_rot_keys(list(range(1, 34)))
+    with pytest.raises(hisa.HisaError) as e:
+        g.rot_left_sum_batch([t.cts[:1]] * 34, [0] + list(range(1, 34)))
+    assert e.value.code == -1
+    other = g.tensor_encrypt(x, 2.0 ** 39, 3, h_stride=4)
+    with pytest.raises(hisa.HisaError) as e:
+        g.rot_left_sum_batch([t.cts[:1], other.cts[:1]], [0, 1])
+    assert e.value.code == -3
+    with pytest.raises(hisa.HisaError) as e:
+        g.rot_left_sum_batch([t.cts[:1], low.cts[:1]], [0, 1])
+    assert e.value.code == -2
+    # the convolution that rotates the sums: more than 33 channel blocks
+    many = g.tensor_encrypt(synth.image(82, 64, 2, 2)[None], 2.0 ** 40, 3, h_stride=2, c_inner=64, c_stride=32)
+    with pytest.raises(hisa.HisaError) as e:
+        g.conv2d(many, np.zeros((1, 1, 64, 64)), 1, 1, mode=2, chw_schedule=hisa.CHW_ROTATE_SUMS)
+    assert e.value.code == -1
     g.close()
