@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the HISA hot path on one MI355X.
 
-Headline metric (the benchmark spec): key-switched rotLeft per second at N = 2^15,
+Headline metric of the benchmark definition: key-switched rotLeft per second at N = 2^15,
 batch 64 -- the primitive micro-benchmark configuration (16 limbs of 50-bit
 primes, dnum 3, rotation steps {1, 7, 64}).  One "step" rotates a batch of 64
 synthetic ciphertexts, resident in HBM, by one of the three amounts (cycling).
@@ -131,7 +131,7 @@ def cpu_baseline(log_n, q_bits, dnum, special_bits, seed, sample, steps):
 
 
 def network_latencies():
-    """Encrypted inference latency of the benchmark networks (BASELINE configs 3, 4 and 5): encrypt-done to the
+    """Encrypted inference latency of the benchmark networks (benchmark configurations 3, 4 and 5): encrypt-done to the
     last output ciphertext ready, one image, rotation and relinearisation keys resident, weights converted and
     encoded ahead of time (hisa_conv2d_prepare, hisa_fc_prepare, hisa_matmul_prepare) (median of 3 after one set-up
     pass that generates the keys and the plans).  Every data layout is timed (Sec. "Data Layout Selection":
@@ -342,7 +342,7 @@ def main():
         base = cpu_baseline(log_n, q_bits, dnum, args.bits, 1, args.cpu_sample, rot_steps)
 
     print(json.dumps({
-        # BASELINE.json's metric names two figures: `value` is the first, the network latencies are under `networks`
+        # the benchmark's metric names two figures: `value` is the first, the network latencies are under `networks`
         "metric": "key-switched rotLeft/s at N=2^15 (batch 64); encrypted-network latency ms" if (log_n, B) == (15, 64) else
                   "key-switched rotLeft/s at N=2^%d (batch %d)" % (log_n, B),
         "value": round(value, 1), "unit": "rotLeft/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -23,7 +23,7 @@ from . import synth
 
 
 def lenet_small(seed=3):
-    """BASELINE config 3: N = 2^13, 8 limbs, one 28x28 image (zero border of one pixel: 30x30 encrypted, so that
+    """Benchmark configuration 3: N = 2^13, 8 limbs, one 28x28 image (zero border of one pixel: 30x30 encrypted, so that
     the stride-2 5x5 convolution gives 13x13), conv 1->5, square, FC 845->100, square, FC 100->10."""
     layers = [("conv", synth.conv_weights(seed, 5, 5, 1, 5, dist="normal", std=0.1), 2),
               ("act", 1.0, 0.0),
@@ -37,7 +37,7 @@ def lenet_small(seed=3):
 
 
 def lenet_medium(seed=4):
-    """BASELINE config 4: N = 2^14, 12 limbs, conv5x5 1->20, pool, conv5x5 20->50, pool, FC 800->500, FC 500->10,
+    """Benchmark configuration 4: N = 2^14, 12 limbs, conv5x5 1->20, pool, conv5x5 20->50, pool, FC 800->500, FC 500->10,
     a degree-2 activation a x^2 + b x (a, b uniform in [0.1, 0.5]) after each convolution and the first FC.
     The weight spreads are chosen so that every layer's values stay of order one."""
     rng = np.random.default_rng(seed)
@@ -55,7 +55,7 @@ def lenet_medium(seed=4):
 
 
 def squeezenet_cifar(seed=5):
-    """BASELINE config 5: N = 2^15, 21 limbs, 32x32x3 image, conv3x3 3->64, four fire modules (squeeze 16, 16, 32,
+    """Benchmark configuration 5: N = 2^15, 21 limbs, 32x32x3 image, conv3x3 3->64, four fire modules (squeeze 16, 16, 32,
     32; expand 64+64, 64+64, 128+128, 128+128), 1x1 convolution to 10 classes, global average pool; a degree-2
     activation after the first convolution, inside and after every fire module.  Weights are normal; fixed gains keep every layer's values within [-2, 2]."""
     rng = np.random.default_rng(seed)

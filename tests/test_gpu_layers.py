@@ -48,7 +48,7 @@ def same_tensor(g, o, gt, ot):
 
 
 def test_config1_conv_bit_exact_and_accurate():
-    """BASELINE config 1: 3x3 conv, 1 -> 1 channel, 8x8 image row-major in the slots, N = 2^12, three 30-bit
+    """Benchmark configuration 1: 3x3 conv, 1 -> 1 channel, 8x8 image row-major in the slots, N = 2^12, three 30-bit
     primes + one 60-bit special prime, scale 2^25."""
     from oracle import layers
     from paper_1810_00845_amd import synth

@@ -1,4 +1,4 @@
-"""End-to-end encrypted inference on the LeNet-shaped benchmark networks (BASELINE configs 3, 4 and 5) against the
+"""End-to-end encrypted inference on the LeNet-shaped benchmark networks (benchmark configurations 3, 4 and 5) against the
 same networks evaluated in fp64 on the plaintext: max abs error <= 1e-3.  Seeded random weights and images stand
 in for the trained networks and MNIST, which are not available."""
 import numpy as np

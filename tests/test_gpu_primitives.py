@@ -1,7 +1,7 @@
 """GPU parity: every HISA primitive through the C ABI against the CPU oracle.
 
 Integer work is compared bit for bit in coefficient form on identical seeded
-inputs; encode/decode (fp64) within the tolerances derived in the design doc.
+inputs; encode/decode (fp64) within tolerances derived from the arithmetic (stated where they are used).
 """
 import numpy as np
 import pytest
