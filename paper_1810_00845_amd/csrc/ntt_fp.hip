@@ -803,9 +803,10 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const Fp
 // computed from the unrotated polynomial, gathered here through sigma_s like the own-digit limbs) -- or, with
 // shared_input, entry b for every s: all terms of an output rotate the same ciphertext --
 // acc[b] = sum_s sum_j sigma_s(e_{s,b,j}) * key_s[j].  A rotation's key values stay in registers across the IPS_BCH
-// outputs of a block; partial sums are normalised per rotation (eight terms of at most 0.875 * 2^50 stay below 2^53)
-// and the running sums every eight rotations.
-#define IPS_BCH 4
+// outputs of a block (4: many blocks for the few outputs of a layer; 16 from 32 outputs on, where re-reading the
+// keys per block would be a third of the traffic); partial sums are normalised per rotation (eight terms of at most
+// 0.875 * 2^50 stay below 2^53) and the running sums every eight rotations.
+template <int IPS_BCH>
 __global__ __launch_bounds__(IPF_NT) void inner_product_sum_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs,
                                                                       int digits, int l, int K, int L, int alpha, IpSteps steps,
                                                                       int n_steps, int total, const u64* own_src, u64 own_bs,
@@ -869,17 +870,24 @@ hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const u64* ext, u
                                        u64* acc, u64 acc_bs, u64 n_batch, int shared_input, int log_n, hipStream_t st) {
     DRY_RUN_RETURN();
     if (digits < 1 || digits > IPF_MAXD || n_steps < 1 || n_steps > FP_MAX_STEPS || l < 1 || K < 1 || alpha < 1) return hipErrorInvalidValue;
-    if (!fprimes || !ext || !own_src || !acc || n_batch == 0 || n_batch > 65535u * IPS_BCH) return hipErrorInvalidValue;
+    if (!fprimes || !ext || !own_src || !acc || n_batch == 0 || n_batch > 65535u * 4) return hipErrorInvalidValue;
     // an entry holds `digits` extended digits of l + K limbs; an accumulator two polynomials of l + K limbs; an own-digit
     // source the l limbs of the polynomial
     const u64 n = (u64)1 << log_n;
     if (ext_bs < (u64)digits * (l + K) * n || acc_bs < (u64)2 * (l + K) * n || own_bs < (u64)l * n) return hipErrorInvalidValue;
     for (int s = 0; s < n_steps; s++)
         if (!steps.key[s] || steps.galois[s] == 0) return hipErrorInvalidValue;
-    dim3 grid((1u << log_n) / IPF_NT, l + K, (unsigned)((n_batch + IPS_BCH - 1) / IPS_BCH));
+    // sixteen outputs per block only where that still leaves a few thousand blocks (sixteen per compute unit)
+    const u64 blocks16 = (u64)((1u << log_n) / IPF_NT) * (l + K) * ((n_batch + 15) / 16);
+    const unsigned bch = (n_batch >= 32 && blocks16 >= 4096) ? 16 : 4;
+    dim3 grid((1u << log_n) / IPF_NT, l + K, (unsigned)((n_batch + bch - 1) / bch));
     ProfScope prof__("inner_product_sum_fp_kernel", st);
-    hipLaunchKernelGGL(inner_product_sum_fp_kernel, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha, steps,
-                       n_steps, total, own_src, own_bs, acc, acc_bs, n_batch, shared_input, log_n);
+    if (bch == 16)
+        hipLaunchKernelGGL(inner_product_sum_fp_kernel<16>, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha,
+                           steps, n_steps, total, own_src, own_bs, acc, acc_bs, n_batch, shared_input, log_n);
+    else
+        hipLaunchKernelGGL(inner_product_sum_fp_kernel<4>, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha,
+                           steps, n_steps, total, own_src, own_bs, acc, acc_bs, n_batch, shared_input, log_n);
     return hipGetLastError();
 }
 

@@ -54,3 +54,33 @@ def test_relinearize_rescale_batch_at_benchmark_size():
         assert np.array_equal(g.ct_export(prod[i]), o.export(want))
         assert abs(prod[i].scale - want.scale) <= 1e-12 * want.scale
     g.close()
+
+
+def test_rotation_sums_at_benchmark_size():
+    """hisa_rot_left_sum_batch on 64 outputs of three terms each at N = 2^15, 16 limbs (the launch that keeps a
+    rotation's key rows across sixteen outputs), distinct terms and terms that rotate one ciphertext; sampled outputs
+    against the oracle's sum of key-switch accumulators, bit for bit."""
+    from oracle import Oracle
+    from oracle.layers import SharedModDown
+    from paper_1810_00845_amd import hisa, synth
+    log_n, L, bits, B, seed = 15, 16, 50, 64, 1
+    g = hisa.Context(log_n, [bits] * L, 3, bits, seed)
+    o = Oracle(log_n, [bits] * L, 3, bits, seed)
+    steps = [1, 0, 64]
+    g.gen_rot_keys([1, 64]); o.gen_rot_keys([1, 64])
+    coeff = synth.uniform_residues(9, (B, 2, L, g.N), g.primes[:L])
+    gcts = g.ct_import_batch(coeff, 2.0 ** 50)
+    terms = [gcts, gcts[1:] + gcts[:1], gcts[2:] + gcts[:2]]
+    print("[case] distinct terms", flush=True)
+    out = g.rot_left_sum_batch(terms, steps)
+    for i in (0, 17, 63):
+        ins = [o.import_ct(coeff[(i + s) % B], 2.0 ** 50) for s in range(3)]
+        want = SharedModDown(o, ins).total([(s, steps[s], 1, None) for s in range(3)], ins[0].scale)
+        assert np.array_equal(g.ct_export(out[i]), o.export(want)), "output %d differs" % i
+    print("[case] one ciphertext per output", flush=True)
+    out = g.rot_left_sum_batch([gcts, gcts, gcts], steps)
+    i = 41
+    x = o.import_ct(coeff[i], 2.0 ** 50)
+    want = SharedModDown(o, [x]).total([(0, r, 1, None) for r in steps], x.scale)
+    assert np.array_equal(g.ct_export(out[i]), o.export(want))
+    g.close()
