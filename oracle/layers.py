@@ -500,6 +500,15 @@ def chw_conv_geometry(o: Oracle, t: OTensor, fh, fw, pad_same=False):
     return wrap, amounts
 
 
+def same_tap_inside(t: OTensor, fh, fw, fy, fx, stride):
+    """For a SAME convolution: which outputs (row-major over the output plane) read an element inside the input plane
+    under tap (fy, fx)."""
+    oh, ow = -(-t.height // stride), -(-t.width // stride)
+    ys = np.arange(oh) * stride + fy - fh // 2
+    xs = np.arange(ow) * stride + fx - fw // 2
+    return (((ys >= 0) & (ys < t.height))[:, None] & ((xs >= 0) & (xs < t.width))[None, :]).reshape(-1)
+
+
 def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False, shared_moddown=False, schedule="in"):
     """w[FH][FW][IC][OC] on a clean CHW-tiled tensor -> clean CHW-tiled tensor with the same channel blocks.  The
     plaintext of (tap, d, input ciphertext j, output ciphertext g) holds, on the valid output positions of block b,
@@ -526,11 +535,14 @@ def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False, shared_moddow
     coeffs = np.zeros((fh, fw, ci, per_in, per_out, o.N), dtype=np.int64)
     for fy, fx, d, j, g in np.ndindex(fh, fw, ci, per_in, per_out):
         z = np.zeros(o.slots)
+        # pad_same == 2 (SAME by masking): the layout has no zero border; the plaintext of a tap is zero on the
+        # outputs whose input element under that tap lies outside the plane
+        here = plane[same_tap_inside(t, fh, fw, fy, fx, stride)] if pad_same == 2 else plane
         for b in range(ci):
             ic, oc = j * ci + (b + d) % ci, g * ci + b
             if ic < ic_n and oc < oc_n:
                 at = b if schedule == "in" else b + d     # behind the blocks lies their copy (or, cyclically, block 0)
-                z[(plane + at * cs) % o.slots] = float(w[fy, fx, ic, oc])
+                z[(here + at * cs) % o.slots] = float(w[fy, fx, ic, oc])
         coeffs[fy, fx, d, j, g] = o.encode_coeffs(z, pt_scale)
     ints = {"pt_coeffs": coeffs, "pt_scale": pt_scale}
     return conv2d_chw_fixed(o, t, ints, oc_n, fh, fw, stride, pad_same, shared_moddown, schedule), ints

@@ -337,6 +337,28 @@ def test_chw_conv_output_side_schedule():
         assert np.abs(layers.tensor_decrypt(o, wrong) - want).max() > 1e-2
 
 
+def test_chw_conv_same_by_masking_needs_no_border():
+    """SAME padding carried by the plaintexts (pad_same = 2): densely packed planes without a zero border, both
+    schedules, stride 1 and 2, cyclic blocks and blocks with their copy behind them; against the fp64 convolution.
+    With the ordinary SAME flag the same layout gives wrong borders (the planted mistake)."""
+    x = synth.image(45, 5, 4, 4)[None]
+    w = synth.conv_weights(46, 3, 3, 5, 6)
+    assert layers.same_tap_inside(layers.OTensor([], 1, 1, 4, 4, 4, 1, 0, 1), 3, 3, 0, 1, 1).reshape(4, 4).tolist() == \
+        [[False] * 4] + [[True] * 4] * 3
+    for c_stride in (64, 16):
+        o = Oracle(9, [50, 40, 40], 3, 55, seed=17)
+        t = layers.tensor_encrypt_chw(o, x, 2.0 ** 40, 3, c_inner=4, c_stride=c_stride, h_stride=4)
+        o.gen_rot_keys(sorted(set(layers.rot_steps_conv_chw(o, t, 3, 3, True)) |
+                              set(layers.rot_steps_conv_chw(o, t, 3, 3, True, schedule="out"))))
+        for stride in (1, 2):
+            want = plain_net.conv2d(x, w, stride=stride, pad_same=True)
+            for schedule in ("in", "out"):
+                got, _ = layers.conv2d_chw(o, t, w, stride=stride, pad_same=2, schedule=schedule)
+                assert got.clean == 1 and np.abs(layers.tensor_decrypt(o, got) - want).max() <= 1e-3
+        wrong, _ = layers.conv2d_chw(o, t, w, pad_same=True)
+        assert np.abs(layers.tensor_decrypt(o, wrong) - plain_net.conv2d(x, w, pad_same=True)).max() > 1e-2
+
+
 def test_mask_tensor_cleans_a_pooled_tensor():
     o = Oracle(10, [50, 40, 40], 3, 55, seed=15)
     x = synth.image(51, 3, 4, 4)[None]
