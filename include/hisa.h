@@ -278,14 +278,22 @@ typedef struct {
                            /* is not clean, except for a 1x1 stride-1 filter on a clean input                   */
 #define HISA_CONV_MASKED 1 /* weights at scale q_last / 2^25, then ONE mulPlain by the 0/1 mask of the valid    */
                            /* output positions (scale 2^25) before the divScalar: the output is clean          */
+#define HISA_PAD_SAME 1
+#define HISA_PAD_SAME_MASKED 2
 #define HISA_CONV_PLAIN 2  /* one mulPlain per tap: plaintext = w * mask encoded at scale q_last                 */
 #define HISA_MASK_SCALE 33554432.0 /* 2^25 */
 
 typedef struct {
     uint32_t fh, fw;      /* filter height, width                                                      */
     uint32_t stride;      /* output stride (>= 1)                                                      */
-    uint32_t pad_same;    /* 0: VALID.  1: SAME -- the input tensor must be clean and its layout must   */
-                          /* leave fh/2 rows and fw/2 columns of zero slots around the plane           */
+    uint32_t pad_same;    /* 0: VALID.  1 (HISA_PAD_SAME): SAME -- the input tensor must be clean and   */
+                          /* its layout must leave fh/2 rows and fw/2 columns of zero slots around the */
+                          /* plane.  2 (HISA_PAD_SAME_MASKED): SAME with the padding carried by the     */
+                          /* weights: CHW-tiled tensors only (HISA_ERR_ARG otherwise, and with          */
+                          /* shared_moddown); the plaintext of a tap is zero on the outputs whose input */
+                          /* element under that tap lies outside the plane, so the layout needs no      */
+                          /* border (planes can be packed back to back) and whatever a rotation brings  */
+                          /* in from the neighbouring row, plane or block is multiplied by zero         */
     uint32_t mode;        /* HISA_CONV_*                                                              */
     uint32_t shared_moddown; /* 1: one division by P per output ciphertext instead of one per rotation: the   */
                           /* rotated taps enter the sum as their key-switch accumulators on the l + K limbs   */

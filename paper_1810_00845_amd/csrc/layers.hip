@@ -793,8 +793,12 @@ static int conv_plan(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom*
         p->wrap = conv_wrap_amount(ctx, in);
         if (p->wrap < 0) return fail(ctx, HISA_ERR_ARG, "the channel blocks must fill the slots or leave room for one copy behind them");
     }
+    if (g->pad_same > HISA_PAD_SAME_MASKED) return fail(ctx, HISA_ERR_ARG, "bad padding");
+    if (g->pad_same == HISA_PAD_SAME_MASKED && (g->mode != HISA_CONV_PLAIN || g->shared_moddown || t_ci(in) == 1))
+        return fail(ctx, HISA_ERR_ARG, "SAME padding by masking is for CHW-tiled tensors (HISA_CONV_PLAIN, no shared_moddown)");
     if (g->pad_same) {
-        if (!in->clean) return fail(ctx, HISA_ERR_ARG, "SAME padding needs a clean input tensor (zeros around the plane)");
+        if (g->pad_same == HISA_PAD_SAME && !in->clean)
+            return fail(ctx, HISA_ERR_ARG, "SAME padding needs a clean input tensor (zeros around the plane)");
         p->out_h = (in->height + g->stride - 1) / g->stride;
         p->out_w = (in->width + g->stride - 1) / g->stride;
     } else {
@@ -1134,12 +1138,26 @@ static int build_scalar_weights(hisa_ctx* ctx, const int64_t* w_int, const ConvP
 }
 
 // piecewise-constant plaintext weights vals[T][OCm][sets.size()] -> NTT-form plaintexts; shared: split as above
+// per_tap (SAME padding by masking): the slot sets differ from filter tap to filter tap -- per_tap[tap] replaces `sets`
+// for the plaintexts of that tap, which are contiguous (the tap is the outermost index of the plaintext order)
 static int build_plain_weights(hisa_ctx* ctx, const std::vector<std::vector<uint32_t>>& sets, const double* vals,
                                const ConvPlan& plan, uint32_t ICm, uint32_t OCm, uint32_t l, double scale, bool shared,
-                               ConvWeights& cw) {
+                               ConvWeights& cw, const std::vector<std::vector<std::vector<uint32_t>>>* per_tap = nullptr) {
     const size_t n = ctx->N, nb = sets.size(), T = plan.steps.size() * ICm;
     cw.shared = shared;
     cw.pt_scale = scale;
+    if (per_tap) {
+        if (shared || per_tap->empty() || (T * OCm) % per_tap->size()) return fail(ctx, HISA_ERR_ARG, "bad plaintext layout");
+        cw.pts = new Temp(ctx, T * OCm * l * n * sizeof(u64));
+        if (!cw.pts->ok()) return HISA_ERR_OOM;
+        const size_t rows = T * OCm / per_tap->size();
+        for (size_t tap = 0; tap < per_tap->size(); tap++) {
+            if ((*per_tap)[tap].size() != nb) return fail(ctx, HISA_ERR_ARG, "bad plaintext layout");
+            TRY(encode_piecewise_batch(ctx, (*per_tap)[tap], vals + tap * rows * nb, rows, scale, (int)l,
+                                       cw.pts->u() + tap * rows * l * n));
+        }
+        return HISA_OK;
+    }
     if (!shared) {
         cw.pts = new Temp(ctx, T * OCm * l * n * sizeof(u64));
         if (!cw.pts->ok()) return HISA_ERR_OOM;
@@ -1168,6 +1186,29 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
     TRY(conv_wants_shared(ctx, geom, plan, &shared));
     const std::vector<uint32_t> vslots = plane_slots(plan.out_h, plan.out_w, in->h_stride * geom->stride,
                                                      in->w_stride * geom->stride, in->offset);
+    // SAME padding by masking: per filter tap, the outputs whose input element under that tap lies inside the plane
+    const bool masked_same = geom->pad_same == HISA_PAD_SAME_MASKED;
+    std::vector<std::vector<uint32_t>> tap_slots;
+    if (masked_same) {
+        for (uint32_t fy = 0; fy < geom->fh; fy++)
+            for (uint32_t fx = 0; fx < geom->fw; fx++) {
+                std::vector<uint32_t> here;
+                for (uint32_t oy = 0; oy < plan.out_h; oy++)
+                    for (uint32_t ox = 0; ox < plan.out_w; ox++) {
+                        const i64 iy = (i64)oy * geom->stride + fy - geom->fh / 2, ix = (i64)ox * geom->stride + fx - geom->fw / 2;
+                        if (iy >= 0 && iy < (i64)in->height && ix >= 0 && ix < (i64)in->width) here.push_back(vslots[(size_t)oy * plan.out_w + ox]);
+                    }
+                tap_slots.push_back(here);
+            }
+    }
+    // the slot sets of the blocks at positions 0 .. npos-1 for every filter tap
+    auto block_sets = [&](uint32_t npos) {
+        std::vector<std::vector<std::vector<uint32_t>>> per_tap(tap_slots.size(), std::vector<std::vector<uint32_t>>(npos));
+        for (size_t tap = 0; tap < tap_slots.size(); tap++)
+            for (uint32_t pos = 0; pos < npos; pos++)
+                for (uint32_t v : tap_slots[tap]) per_tap[tap][pos].push_back(v + pos * in->c_stride);
+        return per_tap;
+    };
     if (t_ci(in) > 1) {
         // plaintext (tap, d, input ciphertext j, output ciphertext g): on the valid output positions of block b the
         // weight from input channel j ci + (b + d) mod ci to output channel g ci + b, zero where either does not exist
@@ -1190,6 +1231,10 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
                     if (ic < IC && oc < OC) vals[idx * npos + pos] = w[(tap * IC + ic) * OC + oc];
                 }
             }
+            if (masked_same) {
+                const auto per_tap = block_sets(npos);
+                return build_plain_weights(ctx, sets, vals.data(), plan, per_in, ci * per_out, l, q_last, false, cw, &per_tap);
+            }
             return build_plain_weights(ctx, sets, vals.data(), plan, per_in, ci * per_out, l, q_last, false, cw);
         }
         const size_t n_pts = taps * per_in * per_out;
@@ -1204,6 +1249,10 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
                 const size_t ic = j * ci + (b + d) % ci, oc = g_ * ci + b;
                 if (ic < IC && oc < OC) vals[idx * ci + b] = w[(tap * IC + ic) * OC + oc];
             }
+        }
+        if (masked_same) {
+            const auto per_tap = block_sets(ci);
+            return build_plain_weights(ctx, sets, vals.data(), plan, per_in, per_out, l, q_last, shared, cw, &per_tap);
         }
         return build_plain_weights(ctx, sets, vals.data(), plan, per_in, per_out, l, q_last, shared, cw);
     }

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libhisa.so")
 MAX_Q = 48
 CONV_SCALAR, CONV_MASKED, CONV_PLAIN = 0, 1, 2
 CHW_ROTATE_INPUTS, CHW_ROTATE_SUMS = 0, 1
+PAD_SAME, PAD_SAME_MASKED = 1, 2
 
 ERRORS = {0: "OK", -1: "ARG", -2: "LEVEL_MISMATCH", -3: "SCALE_MISMATCH", -4: "NO_KEY", -5: "BAD_DIVISOR",
           -6: "DEPTH_EXHAUSTED", -7: "OOM", -8: "HIP", -9: "SIZE"}
@@ -417,7 +418,7 @@ class Context:
         w = np.ascontiguousarray(w, dtype=np.float64)
         assert w.shape[:3] == (fh, fw, t.channels)
         oc = w.shape[3]
-        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode, 1 if shared_moddown else 0, chw_schedule)
+        g = ConvGeom(fh, fw, stride, int(pad_same), mode, 1 if shared_moddown else 0, chw_schedule)
         return self._layer("hisa_conv2d", t, t.batch * -(-oc // t.c_inner), _dp(w), C.c_uint32(oc), C.byref(g))
 
     def conv2d_prepare(self, like, w, fh, fw, stride=1, pad_same=False, mode=CONV_SCALAR, shared_moddown=False, chw_schedule=0):
@@ -426,7 +427,7 @@ class Context:
         w = np.ascontiguousarray(w, dtype=np.float64)
         assert w.shape[:3] == (fh, fw, like.channels)
         oc = w.shape[3]
-        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode, 1 if shared_moddown else 0, chw_schedule)
+        g = ConvGeom(fh, fw, stride, int(pad_same), mode, 1 if shared_moddown else 0, chw_schedule)
         st, _arr = like._struct()
         plan = C.c_void_p()
         self._ck(load().hisa_conv2d_prepare(self._vp, C.byref(st), _dp(w), C.c_uint32(oc), C.byref(g), C.byref(plan)))
@@ -443,7 +444,7 @@ class Context:
         i64p = C.POINTER(C.c_int64)
         wi = np.ascontiguousarray(w_int, dtype=np.int64) if w_int is not None else None
         pc = np.ascontiguousarray(pt_coeffs, dtype=np.int64) if pt_coeffs is not None else None
-        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, mode, 1 if shared_moddown else 0, chw_schedule)
+        g = ConvGeom(fh, fw, stride, int(pad_same), mode, 1 if shared_moddown else 0, chw_schedule)
         return self._layer("hisa_conv2d_fixed", t, t.batch * -(-oc // t.c_inner), wi.ctypes.data_as(i64p) if wi is not None else None,
                            C.c_double(w_scale), pc.ctypes.data_as(i64p) if pc is not None else None, C.c_double(pt_scale),
                            C.c_uint32(oc), C.byref(g))
@@ -566,7 +567,7 @@ class Context:
         return [int(buf[i]) for i in range(n.value)]
 
     def conv2d_rot_steps(self, t, fh, fw, stride=1, pad_same=False, chw_schedule=0):
-        g = ConvGeom(fh, fw, stride, 1 if pad_same else 0, 0, 0, chw_schedule)
+        g = ConvGeom(fh, fw, stride, int(pad_same), 0, 0, chw_schedule)
         return self._steps("hisa_conv2d_rot_steps", t, C.byref(g))
 
     def fc_rot_steps(self, t):

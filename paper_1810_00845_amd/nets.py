@@ -130,6 +130,8 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
     the host queues the whole network ahead of the GPU and only the end-to-end latency is measured (per-layer entries
     are then host queueing times)."""
     assert layout in LAYOUTS
+    if layout == "chw":
+        border = 0      # CHW-tiled convolutions multiply by plaintexts, which carry the SAME padding: planes back to back
     fused = ctx.log_n >= 12 and max(ctx.primes) < 2 ** 50 and ctx.dnum <= 8
     ctx.set_merge_doublings(merge_doublings if fused else 0)
     replicas = 1 if layout == "hw" else 1 << 30
@@ -189,6 +191,8 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
         cleaned = None
         if t.c_inner > 1:                 # CHW-tiled: plaintext weights on a clean input
             kw["mode"] = 2
+            if kw.get("pad_same") and layout == "chw":
+                kw["pad_same"] = 2        # no zero border in this layout: the plaintexts mask what the taps reach outside
             if not t.clean:
                 t = cleaned = ctx.tensor_mask(t)
             # rotate the inputs by (tap, diagonal), or by the taps only and the sums by the diagonals: whichever takes

@@ -478,6 +478,45 @@ def test_chw_conv_rotating_the_sums_bit_exact(c_stride):
     g2.close()
 
 
+@pytest.mark.parametrize("c_stride", [16, 512])
+def test_chw_conv_same_by_masking_bit_exact(c_stride):
+    """SAME padding carried by the plaintexts (pad_same = 2) on densely packed planes without a border, against the
+    oracle bit for bit: both schedules, stride 1 and 2, blocks with their copy behind them (4 x 16 slots) and filling
+    the slots (4 x 512); fixed-point, float and plan entry points; refused for HW-tiled tensors and scalar weights."""
+    from oracle import layers
+    from paper_1810_00845_amd import hisa, synth
+    g, o = make_pair(12, [50, 40, 40], 3, 50, 14)
+    x = synth.image(45, 5, 4, 4)[None].repeat(2, axis=0) * np.array([1.0, -0.7])[:, None, None, None]
+    w = synth.conv_weights(46, 3, 3, 5, 6)
+    gt, ot = chw_pair(g, o, x, 2.0 ** 40, 3, 4, c_stride, 902, h_stride=4)
+    steps = sorted(set(g.conv2d_rot_steps(gt, 3, 3, pad_same=2)) | set(g.conv2d_rot_steps(gt, 3, 3, pad_same=2, chw_schedule=1)))
+    g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+    for stride in (1, 2):
+        ref = plain_net.conv2d(x, w, stride=stride, pad_same=True)
+        for sched, name in ((0, "in"), (1, "out")):
+            oout, ints = layers.conv2d_chw(o, ot, w, stride=stride, pad_same=2, schedule=name)
+            gout = g.conv2d_fixed(gt, None, 1.0, ints["pt_coeffs"], ints["pt_scale"], 6, 3, 3, stride=stride, pad_same=2,
+                                  mode=layers.CONV_PLAIN, chw_schedule=sched)
+            same_tensor(g, o, gout, oout)
+            assert np.abs(g.tensor_decrypt(gout) - ref).max() <= 1e-3
+            gfloat = g.conv2d(gt, w, 3, 3, stride=stride, pad_same=2, mode=layers.CONV_PLAIN, chw_schedule=sched)
+            assert gfloat.meta() == gout.meta() and np.abs(g.tensor_decrypt(gfloat) - ref).max() <= 1e-3
+            plan = g.conv2d_prepare(gt, w, 3, 3, stride=stride, pad_same=2, mode=layers.CONV_PLAIN, chw_schedule=sched)
+            gplan = g.conv2d_apply(gt, plan)
+            for ca, cb in zip(gfloat.cts, gplan.cts):
+                assert np.array_equal(g.ct_export(ca), g.ct_export(cb))
+            g.conv_plan_free(plan)
+    hw = g.tensor_encrypt(x, 2.0 ** 40, 3, h_stride=4)
+    for kw in (dict(mode=layers.CONV_PLAIN), dict(mode=layers.CONV_SCALAR)):
+        with pytest.raises(hisa.HisaError) as e:
+            g.conv2d(hw, w, 3, 3, pad_same=2, **kw)
+        assert e.value.code == -1
+    with pytest.raises(hisa.HisaError) as e:
+        g.conv2d(gt, w, 3, 3, pad_same=3, mode=layers.CONV_PLAIN)
+    assert e.value.code == -1
+    g.close()
+
+
 def test_mask_layer_then_chw_conv_on_a_pooled_tensor():
     """pool (not clean) -> masking multiply -> CHW convolution, every step bit for bit; the convolution refuses the
     unmasked tensor."""
