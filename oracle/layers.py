@@ -515,12 +515,15 @@ def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False, shared_moddow
     the weight from input channel j c_inner + (b + d) mod c_inner to output channel g c_inner + b (zero where either
     does not exist), encoded at the scale of the last modulus.  Returns (output, the integers used).
 
+    schedule "taps": the other split of the same rotations -- the inputs are rotated by the diagonals only (d blocks),
+    the products of each filter tap are summed where the input elements lie (the plaintext holds the weight of output
+    position p on slot p + tap amount) and the sums are rotated by the taps and added, again with one division by P.
     schedule "in": the inputs are rotated by (tap, d) and the products summed.  schedule "out" (the reduction over the
     channels of a ciphertext done after the multiplication, Sec. "CHW-tiled Homomorphic Convolution 2-d"): the inputs
     are rotated by the taps only, the products of diagonal d are summed where the input channels lie -- the plaintext
     holds the same weight d blocks further up, under input block b + d -- and the c_inner sums are rotated down by d
     blocks and added, with one division by P for the whole sum (SharedModDown)."""
-    assert schedule in ("in", "out")
+    assert schedule in ("in", "out", "taps")
     fh, fw, ic_n, oc_n = w.shape
     assert ic_n == t.channels
     ci, cs = t.c_inner, t.c_stride
@@ -538,10 +541,13 @@ def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False, shared_moddow
         # pad_same == 2 (SAME by masking): the layout has no zero border; the plaintext of a tap is zero on the
         # outputs whose input element under that tap lies outside the plane
         here = plane[same_tap_inside(t, fh, fw, fy, fx, stride)] if pad_same == 2 else plane
+        if schedule == "taps":      # under the input elements: the tap's own rotation comes after the multiplication
+            ph, pw = (fh // 2, fw // 2) if pad_same else (0, 0)
+            here = here + (fy - ph) * t.h_stride + (fx - pw) * t.w_stride
         for b in range(ci):
             ic, oc = j * ci + (b + d) % ci, g * ci + b
             if ic < ic_n and oc < oc_n:
-                at = b if schedule == "in" else b + d     # behind the blocks lies their copy (or, cyclically, block 0)
+                at = b + d if schedule == "out" else b    # behind the blocks lies their copy (or, cyclically, block 0)
                 z[(here + at * cs) % o.slots] = float(w[fy, fx, ic, oc])
         coeffs[fy, fx, d, j, g] = o.encode_coeffs(z, pt_scale)
     ints = {"pt_coeffs": coeffs, "pt_scale": pt_scale}
@@ -561,6 +567,23 @@ def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same
         xs = t.cts[b * per_in:(b + 1) * per_in]
         if wrap:
             xs = [o.add(x, o.rot_right(x, wrap)) for x in xs]
+        if schedule == "taps":
+            by_diag = {(j, d): o.rot_left(xs[j], (d * t.c_stride) % o.slots) for j in range(per_in) for d in range(ci)}
+            for g in range(per_out):
+                sums, steps = [], []
+                for fy in range(fh):
+                    for fx in range(fw):
+                        acc = None
+                        for d in range(ci):
+                            for j in range(per_in):
+                                pt = o.pt_from_coeffs(ints["pt_coeffs"][fy, fx, d, j, g], ints["pt_scale"], xs[j].limbs)
+                                temp = o.mul_plain(by_diag[(j, d)], pt)
+                                acc = temp if acc is None else o.add(acc, temp)
+                        sums.append(acc)
+                        steps.append(amounts[fy][fx][0])
+                total = SharedModDown(o, sums).total([(k, steps[k], 1, None) for k in range(len(sums))], sums[0].scale)
+                outs.append(o.div_scalar(total, o.max_scalar_div(total, float("inf"))))
+            continue
         if schedule == "out":
             # amounts[fy][fx][0] is the tap's own amount, d * c_stride the diagonal's
             by_tap = {(j, fy, fx): o.rot_left(xs[j], amounts[fy][fx][0])
@@ -605,7 +628,7 @@ def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same
 
 def rot_steps_conv_chw(o: Oracle, t: OTensor, fh, fw, pad_same=False, schedule="in"):
     wrap, amounts = chw_conv_geometry(o, t, fh, fw, pad_same)
-    if schedule == "out":
+    if schedule in ("out", "taps"):
         steps = {row[0] for plane in amounts for row in plane} | {(d * t.c_stride) % o.slots for d in range(t.c_inner)}
     else:
         steps = {a for plane in amounts for row in plane for a in row}

@@ -352,11 +352,50 @@ def test_chw_conv_same_by_masking_needs_no_border():
                               set(layers.rot_steps_conv_chw(o, t, 3, 3, True, schedule="out"))))
         for stride in (1, 2):
             want = plain_net.conv2d(x, w, stride=stride, pad_same=True)
-            for schedule in ("in", "out"):
+            for schedule in ("in", "out", "taps"):
                 got, _ = layers.conv2d_chw(o, t, w, stride=stride, pad_same=2, schedule=schedule)
                 assert got.clean == 1 and np.abs(layers.tensor_decrypt(o, got) - want).max() <= 1e-3
         wrong, _ = layers.conv2d_chw(o, t, w, pad_same=True)
         assert np.abs(layers.tensor_decrypt(o, wrong) - plain_net.conv2d(x, w, pad_same=True)).max() > 1e-2
+
+
+def test_chw_conv_taps_on_the_sums_schedule():
+    """The schedule that rotates the inputs by the diagonals and the per-tap sums by the taps: VALID and SAME on a
+    bordered layout (cyclic blocks and blocks with their copy), against the fp64 convolution and the other schedules;
+    c_inner - 1 rotations per input ciphertext, taps - 1 key-switch accumulations per output ciphertext."""
+    x = synth.image(47, 5, 4, 4)[None]
+    w = synth.conv_weights(48, 3, 3, 5, 6)
+    for log_n, expect_wrap in ((9, 0), (10, 256)):
+        o = Oracle(log_n, [50, 40, 40], 3, 55, seed=18)
+        t = layers.tensor_encrypt_chw(o, x, 2.0 ** 40, 3, c_inner=4, c_stride=64, h_stride=6, offset=7)
+        o.gen_rot_keys(sorted(set(layers.rot_steps_conv_chw(o, t, 3, 3, True, schedule="taps")) |
+                              set(layers.rot_steps_conv_chw(o, t, 3, 3, schedule="taps"))))
+        counts = {"rot_left": 0, "key_switch_acc": 0, "mod_down": 0, "mul_plain": 0}
+        real = {n: getattr(o, n) for n in counts}
+        for name in counts:
+            def f(*a, _n=name, **k):
+                counts[_n] += 1
+                return real[_n](*a, **k)
+            setattr(o, name, f)
+        same, _ = layers.conv2d_chw(o, t, w, pad_same=True, schedule="taps")
+        for name in counts:
+            setattr(o, name, real[name])
+        per_in, per_out = 2, 2
+        assert counts["rot_left"] == per_in * 4 + (per_in if expect_wrap else 0)       # d = 0 is a copy
+        assert counts["key_switch_acc"] == per_out * 8 and counts["mod_down"] == per_out * 2
+        assert counts["mul_plain"] == per_out * per_in * 9 * 4
+        want = plain_net.conv2d(x, w, pad_same=True)
+        assert same.clean == 1 and np.abs(layers.tensor_decrypt(o, same) - want).max() <= 1e-3
+        z = o.decode(o.decrypt(same.cts[1])).real
+        z[np.asarray(layers.tensor_slots(same)).reshape(4, 16)[:2].reshape(-1)] = 0
+        assert np.abs(z).max() <= 1e-3
+        valid, _ = layers.conv2d_chw(o, t, w, schedule="taps")
+        assert np.abs(layers.tensor_decrypt(o, valid) - plain_net.conv2d(x, w)).max() <= 1e-3
+        strided, _ = layers.conv2d_chw(o, t, w, stride=2, pad_same=True, schedule="taps")
+        assert np.abs(layers.tensor_decrypt(o, strided) - plain_net.conv2d(x, w, stride=2, pad_same=True)).max() <= 1e-3
+        bad = np.roll(w, 1, axis=1)                        # a planted mistake: taps one column off
+        wrong, _ = layers.conv2d_chw(o, t, bad, pad_same=True, schedule="taps")
+        assert np.abs(layers.tensor_decrypt(o, wrong) - want).max() > 1e-2
 
 
 def test_mask_tensor_cleans_a_pooled_tensor():
