@@ -315,6 +315,13 @@ typedef struct {
                                  /* c_inner - 1 key switches per output ciphertext instead of taps*c_inner - 1 per */
                                  /* input ciphertext; the same multiplications.  Needs what that call needs and    */
                                  /* c_inner <= 33; not together with shared_moddown (HISA_ERR_ARG).                */
+#define HISA_CHW_ROTATE_SUMS_TAPS 2 /* the same with the two factors of the rotations exchanged: inputs are rotated  */
+                                 /* by the d blocks only (d = 0..c_inner-1); for each output ciphertext and filter   */
+                                 /* tap the products are summed under the input elements (the plaintext holds the    */
+                                 /* weight of output position p on slot p + tap amount) and the per-tap sums are     */
+                                 /* rotated by the taps and added, one division by P per output ciphertext.          */
+                                 /* (c_inner - 1) rotations per input ciphertext plus taps - 1 key switches per      */
+                                 /* output ciphertext; at most 33 taps, exactly one of them without a rotation.      */
 
 /* HW-tiled conv2d (Algorithm 1; cross-correlation, no kernel flip): for every
  * output channel oc: sum over ic and filter taps (fy, fx) of weight *

@@ -502,25 +502,54 @@ static int32_t norm_step(const hisa_ctx* ctx, i64 r) {
 // A CHW-tiled convolution may instead reduce over the channel blocks after the multiplication
 // (HISA_CHW_ROTATE_SUMS): the inputs are then rotated by the taps only and the c_inner sums by d blocks.
 static bool conv_rotates_sums(const hisa_tensor* in, const hisa_conv_geom* g) {
-    return t_ci(in) > 1 && g->chw_schedule == HISA_CHW_ROTATE_SUMS;
+    return t_ci(in) > 1 && (g->chw_schedule == HISA_CHW_ROTATE_SUMS || g->chw_schedule == HISA_CHW_ROTATE_SUMS_TAPS);
+}
+// ... or the other way round (HISA_CHW_ROTATE_SUMS_TAPS): the inputs by the d blocks only, the per-tap sums by the taps
+static bool conv_sums_by_taps(const hisa_tensor* in, const hisa_conv_geom* g) {
+    return t_ci(in) > 1 && g->chw_schedule == HISA_CHW_ROTATE_SUMS_TAPS;
 }
 
+static int32_t conv_tap_amount(const hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, uint32_t fy, uint32_t fx) {
+    const i64 ph = g->pad_same ? g->fh / 2 : 0, pw = g->pad_same ? g->fw / 2 : 0;
+    return norm_step(ctx, ((i64)fy - ph) * in->h_stride + ((i64)fx - pw) * in->w_stride);
+}
+
+// rotations of the inputs
 static std::vector<int32_t> conv_tap_steps(const hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g) {
     std::vector<int32_t> steps;
-    const i64 ph = g->pad_same ? g->fh / 2 : 0, pw = g->pad_same ? g->fw / 2 : 0;
+    if (conv_sums_by_taps(in, g)) {
+        for (uint32_t d = 0; d < t_ci(in); d++) steps.push_back(norm_step(ctx, (i64)d * in->c_stride));
+        return steps;
+    }
     const uint32_t diagonals = conv_rotates_sums(in, g) ? 1 : t_ci(in);
     for (uint32_t fy = 0; fy < g->fh; fy++)
         for (uint32_t fx = 0; fx < g->fw; fx++)
             for (uint32_t d = 0; d < diagonals; d++)
-                steps.push_back(norm_step(ctx, ((i64)fy - ph) * in->h_stride + ((i64)fx - pw) * in->w_stride + (i64)d * in->c_stride));
+                steps.push_back(norm_step(ctx, (i64)conv_tap_amount(ctx, in, g, fy, fx) + (i64)d * in->c_stride));
     return steps;
 }
 
-// rotLeft amounts of the sums of diagonals 1 .. c_inner-1 under HISA_CHW_ROTATE_SUMS
-static std::vector<int32_t> conv_sum_steps(const hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g) {
+// Rotations of the sums when they are rotated: the diagonals 1 .. c_inner-1 (HISA_CHW_ROTATE_SUMS), or the filter taps
+// in the order their sums are kept (HISA_CHW_ROTATE_SUMS_TAPS): the unrotated tap first, then the others row by row;
+// sum_taps receives that order (filter tap index fy * fw + fx per sum).
+static std::vector<int32_t> conv_sum_steps(const hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g,
+                                           std::vector<uint32_t>* sum_taps = nullptr) {
     std::vector<int32_t> steps;
-    if (conv_rotates_sums(in, g))
+    if (conv_sums_by_taps(in, g)) {
+        std::vector<uint32_t> order;
+        for (int pass = 0; pass < 2; pass++)
+            for (uint32_t fy = 0; fy < g->fh; fy++)
+                for (uint32_t fx = 0; fx < g->fw; fx++) {
+                    const int32_t a = conv_tap_amount(ctx, in, g, fy, fx);
+                    if ((a == 0) == (pass == 0)) {
+                        order.push_back(fy * g->fw + fx);
+                        if (a) steps.push_back(a);
+                    }
+                }
+        if (sum_taps) *sum_taps = order;
+    } else if (conv_rotates_sums(in, g)) {
         for (uint32_t d = 1; d < t_ci(in); d++) steps.push_back(norm_step(ctx, (i64)d * in->c_stride));
+    }
     return steps;
 }
 
@@ -769,21 +798,24 @@ static void fill_out_meta(hisa_tensor* out, uint32_t batch, uint32_t channels, u
 struct ConvPlan {
     uint32_t out_h, out_w;
     std::vector<int32_t> steps;   // rotations of the inputs: one per (tap, d), or per tap when the sums are rotated
-    std::vector<int32_t> sum_steps;   // HISA_CHW_ROTATE_SUMS: rotations of the sums of diagonals 1 .. c_inner-1
-    bool rotate_sums = false;
+    std::vector<int32_t> sum_steps;   // the rotations of the sums, where sums are rotated (conv_sum_steps)
+    std::vector<uint32_t> sum_taps;   // HISA_CHW_ROTATE_SUMS_TAPS: filter tap of every sum, the unrotated ones first
+    bool rotate_sums = false, sums_by_taps = false;
     i64 wrap = 0;                 // CHW-tiling: rotRight amount of the copy behind the channel blocks, 0 if none
 };
 
 static int conv_plan(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, ConvPlan* p) {
-    if (!g || g->chw_schedule > HISA_CHW_ROTATE_SUMS) return fail(ctx, HISA_ERR_ARG, "bad conv geometry");
+    if (!g || g->chw_schedule > HISA_CHW_ROTATE_SUMS_TAPS) return fail(ctx, HISA_ERR_ARG, "bad conv geometry");
     p->rotate_sums = conv_rotates_sums(in, g);
-    if (g->fh == 0 || g->fw == 0 || g->stride == 0 || (u64)g->fh * g->fw * (p->rotate_sums ? 1 : t_ci(in)) > MAX_TAPS ||
-        g->mode > HISA_CONV_PLAIN)
+    p->sums_by_taps = conv_sums_by_taps(in, g);
+    const u64 input_rotations = p->sums_by_taps ? t_ci(in) : (u64)g->fh * g->fw * (p->rotate_sums ? 1 : t_ci(in));
+    if (g->fh == 0 || g->fw == 0 || g->stride == 0 || input_rotations > MAX_TAPS || g->mode > HISA_CONV_PLAIN)
         return fail(ctx, HISA_ERR_ARG, "bad conv geometry (at most %d rotation amounts per input ciphertext)", MAX_TAPS);
     if (p->rotate_sums) {
         if (!fused_key_switch_available(ctx))
-            return fail(ctx, HISA_ERR_ARG, "HISA_CHW_ROTATE_SUMS needs the fused key-switch path (N >= 2^12, every prime below 2^50, dnum <= 8)");
-        if (t_ci(in) - 1 > FP_MAX_STEPS) return fail(ctx, HISA_ERR_ARG, "HISA_CHW_ROTATE_SUMS: at most %d channel blocks", FP_MAX_STEPS + 1);
+            return fail(ctx, HISA_ERR_ARG, "rotating the sums needs the fused key-switch path (N >= 2^12, every prime below 2^50, dnum <= 8)");
+        if ((p->sums_by_taps ? (u64)g->fh * g->fw : (u64)t_ci(in)) - 1 > FP_MAX_STEPS)
+            return fail(ctx, HISA_ERR_ARG, "rotating the sums: at most %d sums per output ciphertext", FP_MAX_STEPS + 1);
         if (g->shared_moddown) return fail(ctx, HISA_ERR_ARG, "shared_moddown belongs to the schedule that rotates the inputs");
     }
     if (t_ci(in) > 1) {
@@ -807,7 +839,9 @@ static int conv_plan(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom*
         p->out_w = (in->width - g->fw) / g->stride + 1;
     }
     p->steps = conv_tap_steps(ctx, in, g);
-    p->sum_steps = conv_sum_steps(ctx, in, g);
+    p->sum_steps = conv_sum_steps(ctx, in, g, &p->sum_taps);
+    if (p->sums_by_taps && p->sum_steps.size() + 1 != (size_t)g->fh * g->fw)
+        return fail(ctx, HISA_ERR_ARG, "rotating the sums by the taps needs exactly one tap without a rotation");
     return HISA_OK;
 }
 
@@ -985,7 +1019,8 @@ static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_g
     const uint32_t B = in->batch, ci = t_ci(in), IC = (uint32_t)t_per(in), OCm = (OC + ci - 1) / ci, l = in->cts[0]->limbs;
     const size_t nct = (size_t)B * IC, n = ctx->N;
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
-    if (!d_pts || plan.sum_steps.size() != ci - 1) return fail(ctx, HISA_ERR_ARG, "bad convolution plan");
+    if (!d_pts || plan.sum_steps.size() != (plan.sums_by_taps ? plan.sum_taps.size() : (size_t)ci) - 1)
+        return fail(ctx, HISA_ERR_ARG, "bad convolution plan");
     const int n_taps = (int)plan.steps.size();
     const u64 ctw = 2 * (u64)l * n;
     std::vector<hisa_ct*> wrapped;
@@ -1030,10 +1065,40 @@ static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_g
         }
     }
     const double mac_scale = in->cts[0]->scale * pt_scale;
-    const size_t sums = (size_t)ci * OCm;          // per image, ordered (d, g)
+    const size_t terms = plan.sum_steps.size() + 1;
+    const size_t sums = terms * OCm;               // per image: ordered (d, g), or (sum k, image, g) over all images
     Temp y(ctx, (size_t)B * sums * ctw * sizeof(u64));
     if (rc == HISA_OK && !y.ok()) rc = HISA_ERR_OOM;
     if (rc == HISA_OK) rc = alloc_ct_batch(ctx, (size_t)B * OCm, 2, l, mac_scale, outs.data());
+    if (rc == HISA_OK && plan.sums_by_taps) {
+        // one multiply-accumulate launch per sum k (its plaintexts [d][j][g] are contiguous), all images at once: the
+        // sums land rotation-major, [k][image][g], and one call adds them up for every image
+        const size_t Bn = (size_t)B * OCm, rows = (size_t)n_taps * IC * OCm;
+        ma.n_taps = n_taps; ma.IC = (int)IC; ma.OC = (int)OCm; ma.l = (int)l; ma.ct_words = ctw;
+        ma.w_stride_t = OCm; ma.w_stride_oc = 1;
+        for (size_t k = 0; k < terms && rc == HISA_OK; k++) {
+            ma.w = d_pts + k * rows * (size_t)l * n;
+            ma.out = y.u() + k * Bn * ctw;
+            hipError_t e = launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+            if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));
+        }
+        for (auto& v : rotated) free_handles(ctx, v);
+        dev_release(ctx, bi.tmp);
+        free_handles(ctx, wrapped);
+        if (rc == HISA_OK)
+            rc = rotate_sum_fp(ctx, y.u() + Bn * ctw, ctw, (int)terms - 1, plan.sum_steps.data(), Bn, (int)l, y.u(), ctw,
+                               outs[0]->data);
+        if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
+        if (rc != HISA_OK) {
+            for (hisa_ct* c : outs)
+                if (c) hisa_free(ctx, c);
+            return rc;
+        }
+        for (size_t i = 0; i < outs.size(); i++) out->cts[i] = outs[i];
+        fill_out_meta(out, B, OC, plan.out_h, plan.out_w, in->h_stride * g->stride, in->w_stride * g->stride, in->offset, 1u, ci,
+                      in->c_stride);
+        return HISA_OK;
+    }
     if (rc == HISA_OK) {
         ma.n_taps = n_taps; ma.IC = (int)IC; ma.OC = (int)sums; ma.l = (int)l; ma.ct_words = ctw;
         ma.out = y.u();
@@ -1213,6 +1278,30 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
         // plaintext (tap, d, input ciphertext j, output ciphertext g): on the valid output positions of block b the
         // weight from input channel j ci + (b + d) mod ci to output channel g ci + b, zero where either does not exist
         const uint32_t ci = t_ci(in), per_in = (uint32_t)t_per(in), per_out = (OC + ci - 1) / ci;
+        if (plan.sums_by_taps) {
+            // plaintext (sum k, d, input ciphertext j, output ciphertext g), k running over the filter taps with the
+            // unrotated one first: the weight of output block b on block b, but under the input elements -- the slots
+            // of the valid outputs moved by the tap's amount, which the rotation of sum k undoes
+            const size_t ftaps = plan.sum_taps.size(), rows = (size_t)ci * per_in * per_out, slots = ctx->N / 2;
+            std::vector<std::vector<std::vector<uint32_t>>> per_sum(ftaps, std::vector<std::vector<uint32_t>>(ci));
+            std::vector<double> vals(ftaps * rows * ci, 0.0);
+            for (size_t k = 0; k < ftaps; k++) {
+                const uint32_t tp = plan.sum_taps[k];
+                const int32_t amount = conv_tap_amount(ctx, in, geom, tp / geom->fw, tp % geom->fw);
+                for (uint32_t b = 0; b < ci; b++)
+                    for (uint32_t v : masked_same ? tap_slots[tp] : vslots)
+                        per_sum[k][b].push_back((uint32_t)(((u64)v + (u64)amount + (u64)b * in->c_stride) % slots));
+                for (size_t r = 0; r < rows; r++) {
+                    const size_t g_ = r % per_out, j = (r / per_out) % per_in, d = r / per_out / per_in;
+                    for (uint32_t b = 0; b < ci; b++) {
+                        const size_t ic = j * ci + (b + d) % ci, oc = g_ * ci + b;
+                        if (ic < IC && oc < OC) vals[(k * rows + r) * ci + b] = w[((size_t)tp * IC + ic) * OC + oc];
+                    }
+                }
+            }
+            return build_plain_weights(ctx, per_sum[0], vals.data(), plan, per_in, (uint32_t)(ftaps * per_out), l, q_last, false, cw,
+                                       &per_sum);
+        }
         if (plan.rotate_sums) {
             // plaintext (tap, input ciphertext j, d, output ciphertext g): the same weight, but on block b + d, where
             // the input channel lies (behind the blocks their copy, or cyclically block 0); taps = filter taps here
@@ -1287,6 +1376,16 @@ static int conv_build_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t*
     if (geom->mode == HISA_CONV_PLAIN) {
         if (!pt_coeffs) return fail(ctx, HISA_ERR_ARG, "PLAIN mode needs plaintext coefficients");
         cw.w_scale = 1.0;
+        if (plan.sums_by_taps) {
+            // given as [tap][d][j][g][N]; kept as [sum k][d][j][g][N], the unrotated tap first
+            const size_t ci = t_ci(in), rows = ci * ICm * OCm * n;
+            std::vector<int64_t> perm(plan.sum_taps.size() * rows);
+            for (size_t k = 0; k < plan.sum_taps.size(); k++)
+                memcpy(perm.data() + k * rows, pt_coeffs + (size_t)plan.sum_taps[k] * rows, rows * sizeof(int64_t));
+            cw.pts = new Temp(ctx, perm.size() * l * sizeof(u64));
+            if (!cw.pts->ok()) return HISA_ERR_OOM;
+            return coeffs_to_plain_batch(ctx, perm.data(), perm.size() / n, (int)l, cw.pts->u());
+        }
         if (plan.rotate_sums) {
             // given as [tap][d][j][g][N]; the multiply-accumulate reads [tap][j][(d, g)][N]
             const size_t ci = t_ci(in), taps = plan.steps.size();

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libhisa.so")
 
 MAX_Q = 48
 CONV_SCALAR, CONV_MASKED, CONV_PLAIN = 0, 1, 2
-CHW_ROTATE_INPUTS, CHW_ROTATE_SUMS = 0, 1
+CHW_ROTATE_INPUTS, CHW_ROTATE_SUMS, CHW_ROTATE_SUMS_TAPS = 0, 1, 2
 PAD_SAME, PAD_SAME_MASKED = 1, 2
 
 ERRORS = {0: "OK", -1: "ARG", -2: "LEVEL_MISMATCH", -3: "SCALE_MISMATCH", -4: "NO_KEY", -5: "BAD_DIVISOR",

@@ -453,6 +453,28 @@ def test_chw_conv_rotating_the_sums_bit_exact(c_stride):
         for ca, cb in zip(gfloat.cts, gplan.cts):
             assert np.array_equal(g.ct_export(ca), g.ct_export(cb))
         g.conv_plan_free(plan)
+    # the other split: diagonals on the inputs, taps on the sums (bordered layout, VALID and SAME, stride 2)
+    T = hisa.CHW_ROTATE_SUMS_TAPS
+    assert set(g.conv2d_rot_steps(gt, 3, 3, pad_same=True, chw_schedule=T)) == set(g.conv2d_rot_steps(gt, 3, 3, pad_same=True, chw_schedule=S))
+    for kw, ref in ((dict(pad_same=True), plain_net.conv2d(x, w, pad_same=True)), (dict(), plain_net.conv2d(x, w)),
+                    (dict(stride=2, pad_same=True), plain_net.conv2d(x, w, stride=2, pad_same=True))):
+        oout, ints = layers.conv2d_chw(o, ot, w, schedule="taps", **kw)
+        gout = g.conv2d_fixed(gt, None, 1.0, ints["pt_coeffs"], ints["pt_scale"], 6, 3, 3, mode=layers.CONV_PLAIN,
+                              chw_schedule=T, **kw)
+        same_tensor(g, o, gout, oout)
+        assert gout.clean == 1 and np.abs(g.tensor_decrypt(gout) - ref).max() <= 1e-3
+        gfloat = g.conv2d(gt, w, 3, 3, mode=layers.CONV_PLAIN, chw_schedule=T, **kw)
+        assert gfloat.meta() == gout.meta() and np.abs(g.tensor_decrypt(gfloat) - ref).max() <= 1e-3
+        plan = g.conv2d_prepare(gt, w, 3, 3, mode=layers.CONV_PLAIN, chw_schedule=T, **kw)
+        gplan = g.conv2d_apply(gt, plan)
+        for ca, cb in zip(gfloat.cts, gplan.cts):
+            assert np.array_equal(g.ct_export(ca), g.ct_export(cb))
+        g.conv_plan_free(plan)
+    g.analysis_begin()
+    g.conv2d(gt, w, 3, 3, mode=layers.CONV_PLAIN, chw_schedule=T, pad_same=True)
+    counts, _ = g.analysis_end()
+    # per image: 2 input ciphertexts x 3 diagonals (+ the copy), 2 output ciphertexts x 8 taps inside sums
+    assert counts["rot_summed"] == 2 * 2 * 8 and counts["rot_left"] == 2 * (2 * 3 + 2 * 8 + (2 if 4 * c_stride != g.slots else 0))
     # dry run: per image 2 input ciphertexts x 8 taps shared-decomposition rotations (+ the copy behind the blocks),
     # 2 output ciphertexts x 3 rotations inside sums, 2 x 9 x 4 x 2 multiply-accumulate terms
     g.analysis_begin()
@@ -465,6 +487,9 @@ def test_chw_conv_rotating_the_sums_bit_exact(c_stride):
     assert dry.cts[0].limbs == 2
     with pytest.raises(hisa.HisaError) as e:               # the two ways of sharing a division do not combine
         g.conv2d(gt, w, 3, 3, mode=layers.CONV_PLAIN, chw_schedule=S, shared_moddown=True)
+    assert e.value.code == -1
+    with pytest.raises(hisa.HisaError) as e:                # 6 x 6 = 36 sums per output: more than one call adds up
+        g.conv2d(gt, np.zeros((6, 6, 5, 6)), 6, 6, mode=layers.CONV_PLAIN, chw_schedule=T, pad_same=True)
     assert e.value.code == -1
     with pytest.raises(hisa.HisaError) as e:
         g.conv2d(gt, w, 3, 3, mode=layers.CONV_PLAIN, chw_schedule=7)
@@ -490,10 +515,11 @@ def test_chw_conv_same_by_masking_bit_exact(c_stride):
     w = synth.conv_weights(46, 3, 3, 5, 6)
     gt, ot = chw_pair(g, o, x, 2.0 ** 40, 3, 4, c_stride, 902, h_stride=4)
     steps = sorted(set(g.conv2d_rot_steps(gt, 3, 3, pad_same=2)) | set(g.conv2d_rot_steps(gt, 3, 3, pad_same=2, chw_schedule=1)))
+    assert set(g.conv2d_rot_steps(gt, 3, 3, pad_same=2, chw_schedule=2)) == set(g.conv2d_rot_steps(gt, 3, 3, pad_same=2, chw_schedule=1))
     g.gen_rot_keys(steps); o.gen_rot_keys(steps)
     for stride in (1, 2):
         ref = plain_net.conv2d(x, w, stride=stride, pad_same=True)
-        for sched, name in ((0, "in"), (1, "out")):
+        for sched, name in ((0, "in"), (1, "out"), (2, "taps")):
             oout, ints = layers.conv2d_chw(o, ot, w, stride=stride, pad_same=2, schedule=name)
             gout = g.conv2d_fixed(gt, None, 1.0, ints["pt_coeffs"], ints["pt_scale"], 6, 3, 3, stride=stride, pad_same=2,
                                   mode=layers.CONV_PLAIN, chw_schedule=sched)
