@@ -1014,6 +1014,8 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
 // output ciphertext g and diagonal d, the sum over (tap, input ciphertext) on the blocks where the input channels lie
 // -- c_inner * OCm sums, ordered (d, g) -- and the sums of d = 1 .. c_inner-1 are rotated left by d blocks and added
 // to the sum of d = 0 with one division by P per output (rotate_sum_fp).  d_pts: [taps][IC][c_inner * OCm][l][N].
+// HISA_CHW_ROTATE_SUMS_TAPS exchanges the roles: the inputs are rotated by the d blocks, the sums (one per filter tap,
+// the unrotated tap first) by the taps; d_pts: [c_inner][IC][taps * OCm][l][N].
 static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
                          const u64* d_pts, double pt_scale, hisa_tensor* out) {
     const uint32_t B = in->batch, ci = t_ci(in), IC = (uint32_t)t_per(in), OCm = (OC + ci - 1) / ci, l = in->cts[0]->limbs;
@@ -1066,39 +1068,10 @@ static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_g
     }
     const double mac_scale = in->cts[0]->scale * pt_scale;
     const size_t terms = plan.sum_steps.size() + 1;
-    const size_t sums = terms * OCm;               // per image: ordered (d, g), or (sum k, image, g) over all images
+    const size_t sums = terms * OCm;               // per image, ordered (term, g): term = diagonal d, or sum k of the taps
     Temp y(ctx, (size_t)B * sums * ctw * sizeof(u64));
     if (rc == HISA_OK && !y.ok()) rc = HISA_ERR_OOM;
     if (rc == HISA_OK) rc = alloc_ct_batch(ctx, (size_t)B * OCm, 2, l, mac_scale, outs.data());
-    if (rc == HISA_OK && plan.sums_by_taps) {
-        // one multiply-accumulate launch per sum k (its plaintexts [d][j][g] are contiguous), all images at once: the
-        // sums land rotation-major, [k][image][g], and one call adds them up for every image
-        const size_t Bn = (size_t)B * OCm, rows = (size_t)n_taps * IC * OCm;
-        ma.n_taps = n_taps; ma.IC = (int)IC; ma.OC = (int)OCm; ma.l = (int)l; ma.ct_words = ctw;
-        ma.w_stride_t = OCm; ma.w_stride_oc = 1;
-        for (size_t k = 0; k < terms && rc == HISA_OK; k++) {
-            ma.w = d_pts + k * rows * (size_t)l * n;
-            ma.out = y.u() + k * Bn * ctw;
-            hipError_t e = launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
-            if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));
-        }
-        for (auto& v : rotated) free_handles(ctx, v);
-        dev_release(ctx, bi.tmp);
-        free_handles(ctx, wrapped);
-        if (rc == HISA_OK)
-            rc = rotate_sum_fp(ctx, y.u() + Bn * ctw, ctw, (int)terms - 1, plan.sum_steps.data(), Bn, (int)l, y.u(), ctw,
-                               outs[0]->data);
-        if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
-        if (rc != HISA_OK) {
-            for (hisa_ct* c : outs)
-                if (c) hisa_free(ctx, c);
-            return rc;
-        }
-        for (size_t i = 0; i < outs.size(); i++) out->cts[i] = outs[i];
-        fill_out_meta(out, B, OC, plan.out_h, plan.out_w, in->h_stride * g->stride, in->w_stride * g->stride, in->offset, 1u, ci,
-                      in->c_stride);
-        return HISA_OK;
-    }
     if (rc == HISA_OK) {
         ma.n_taps = n_taps; ma.IC = (int)IC; ma.OC = (int)sums; ma.l = (int)l; ma.ct_words = ctw;
         ma.out = y.u();
@@ -1112,7 +1085,7 @@ static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_g
     // per image: entries (d, g) are rotation-major over the OCm outputs; d = 0 is the unrotated term
     for (uint32_t b = 0; b < B && rc == HISA_OK; b++) {
         const u64* yb = y.u() + (size_t)b * sums * ctw;
-        rc = rotate_sum_fp(ctx, yb + (size_t)OCm * ctw, ctw, (int)ci - 1, plan.sum_steps.data(), OCm, (int)l, yb, ctw,
+        rc = rotate_sum_fp(ctx, yb + (size_t)OCm * ctw, ctw, (int)terms - 1, plan.sum_steps.data(), OCm, (int)l, yb, ctw,
                            outs[(size_t)b * OCm]->data);
     }
     if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
@@ -1279,7 +1252,7 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
         // weight from input channel j ci + (b + d) mod ci to output channel g ci + b, zero where either does not exist
         const uint32_t ci = t_ci(in), per_in = (uint32_t)t_per(in), per_out = (OC + ci - 1) / ci;
         if (plan.sums_by_taps) {
-            // plaintext (sum k, d, input ciphertext j, output ciphertext g), k running over the filter taps with the
+            // plaintext (d, input ciphertext j, sum k, output ciphertext g), k running over the filter taps with the
             // unrotated one first: the weight of output block b on block b, but under the input elements -- the slots
             // of the valid outputs moved by the tap's amount, which the rotation of sum k undoes
             const size_t ftaps = plan.sum_taps.size(), rows = (size_t)ci * per_in * per_out, slots = ctx->N / 2;
@@ -1299,8 +1272,21 @@ static int conv_build(hisa_ctx* ctx, const hisa_tensor* in, const double* w, uin
                     }
                 }
             }
-            return build_plain_weights(ctx, per_sum[0], vals.data(), plan, per_in, (uint32_t)(ftaps * per_out), l, q_last, false, cw,
-                                       &per_sum);
+            // kept as [d][j][sum k][g] (one multiply-accumulate launch forms all sums): the plaintexts of a sum are
+            // encoded together -- they share their slot sets -- and copied to their places
+            cw.shared = false;
+            cw.pt_scale = q_last;
+            const size_t pt_words = (size_t)l * n;
+            cw.pts = new Temp(ctx, ftaps * rows * pt_words * sizeof(u64));
+            Temp stage(ctx, rows * pt_words * sizeof(u64));
+            if (!cw.pts->ok() || !stage.ok()) return HISA_ERR_OOM;
+            for (size_t k = 0; k < ftaps; k++) {
+                TRY(encode_piecewise_batch(ctx, per_sum[k], vals.data() + k * rows * ci, rows, q_last, (int)l, stage.u()));
+                for (size_t dj = 0; dj < (size_t)ci * per_in; dj++)
+                    HIP_TRY(ctx, hipMemcpyAsync(cw.pts->u() + ((dj * ftaps + k) * per_out) * pt_words, stage.u() + dj * per_out * pt_words,
+                                                per_out * pt_words * sizeof(u64), hipMemcpyDeviceToDevice, ctx->stream));
+            }
+            return HISA_OK;
         }
         if (plan.rotate_sums) {
             // plaintext (tap, input ciphertext j, d, output ciphertext g): the same weight, but on block b + d, where
@@ -1377,11 +1363,13 @@ static int conv_build_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t*
         if (!pt_coeffs) return fail(ctx, HISA_ERR_ARG, "PLAIN mode needs plaintext coefficients");
         cw.w_scale = 1.0;
         if (plan.sums_by_taps) {
-            // given as [tap][d][j][g][N]; kept as [sum k][d][j][g][N], the unrotated tap first
-            const size_t ci = t_ci(in), rows = ci * ICm * OCm * n;
-            std::vector<int64_t> perm(plan.sum_taps.size() * rows);
-            for (size_t k = 0; k < plan.sum_taps.size(); k++)
-                memcpy(perm.data() + k * rows, pt_coeffs + (size_t)plan.sum_taps[k] * rows, rows * sizeof(int64_t));
+            // given as [tap][d][j][g][N]; kept as [d][j][sum k][g][N], the unrotated tap first
+            const size_t ci = t_ci(in), ftaps = plan.sum_taps.size();
+            std::vector<int64_t> perm(ftaps * ci * ICm * OCm * n);
+            for (size_t k = 0; k < ftaps; k++)
+                for (size_t dj = 0; dj < ci * ICm; dj++)
+                    memcpy(perm.data() + ((dj * ftaps + k) * OCm) * n, pt_coeffs + (((size_t)plan.sum_taps[k] * ci * ICm + dj) * OCm) * n,
+                           OCm * n * sizeof(int64_t));
             cw.pts = new Temp(ctx, perm.size() * l * sizeof(u64));
             if (!cw.pts->ok()) return HISA_ERR_OOM;
             return coeffs_to_plain_batch(ctx, perm.data(), perm.size() / n, (int)l, cw.pts->u());

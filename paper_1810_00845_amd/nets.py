@@ -195,15 +195,22 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
                 kw["pad_same"] = 2        # no zero border in this layout: the plaintexts mask what the taps reach outside
             if not t.clean:
                 t = cleaned = ctx.tensor_mask(t)
-            # rotate the inputs by (tap, diagonal), or by the taps only and the sums by the diagonals: whichever takes
-            # fewer key switches (a rotation inside a sum shares the division by P, a rotation of an input the
-            # decomposition: about the same price)
+            # Where the rotations go: all on the inputs (tap and diagonal), taps on the inputs and diagonals on the
+            # sums, or diagonals on the inputs and taps on the sums -- whichever is cheapest, a rotation of an input
+            # (shared decomposition) priced at 0.5 and a rotation inside a sum (shared division by P, its own
+            # decomposition) at 0.8 of a stand-alone one
             ci, taps = t.c_inner, fh * fw
             per_in, per_out = -(-t.channels // ci), -(-w.shape[3] // ci)
             fused = ctx.log_n >= 12 and max(ctx.primes) < 2 ** 50 and ctx.dnum <= 8
-            if (rotate_sums and fused and ci - 1 <= 32 and
-                    1.2 * (per_in * (taps - 1) + per_out * (ci - 1)) < per_in * (taps * ci - 1)):
-                kw["chw_schedule"] = 1
+            price = {0: 0.5 * per_in * (taps * ci - 1)}
+            if rotate_sums and fused:
+                if ci - 1 <= 32:
+                    price[1] = 0.5 * per_in * (taps - 1) + 0.8 * per_out * (ci - 1)
+                if 1 < taps <= 33:
+                    price[2] = 0.5 * per_in * (ci - 1) + 0.8 * per_out * (taps - 1)
+            best = min(price, key=lambda k: (price[k], k))
+            if best and price[best] < price[0] / 1.2:
+                kw["chw_schedule"] = best
         if make_keys:
             ctx.gen_rot_keys(ctx.conv2d_rot_steps(t, fh, fw, stride=kw.get("stride", 1), pad_same=kw.get("pad_same", False),
                                                   chw_schedule=kw.get("chw_schedule", 0)))
