@@ -155,24 +155,27 @@ hipError_t launch_add_const(const PrimeConst* primes, const u64* a, u64* out, co
 }
 
 // ---- multiply ---------------------------------------------------------------
+// batch entry b is multiplied by plaintext b % pt_period (plaintexts [limbs][N], one after the other)
 __global__ __launch_bounds__(NT) void mul_plain_kernel(const PrimeConst* primes, const u64* a, const u64* pt, u64* out,
-                                                       int limbs, u64 a_bs, u64 o_bs, int log_n) {
+                                                       int limbs, u64 a_bs, u64 o_bs, unsigned pt_period, int log_n) {
     const u64 n = (u64)1 << log_n;
     const int limb = blockIdx.y % limbs, poly = blockIdx.y / limbs;
     const u64 bi = blockIdx.z;
     const PrimeConst pc = primes[limb];
     const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
     const u64 off = ((u64)poly * limbs + limb) * n + j;
-    out[bi * o_bs + off] = mulmod_barrett(a[bi * a_bs + off], pt[(u64)limb * n + j], pc.q, pc.r1, pc.r0);
+    const u64* p = pt + (bi % pt_period) * (u64)limbs * n;
+    out[bi * o_bs + off] = mulmod_barrett(a[bi * a_bs + off], p[(u64)limb * n + j], pc.q, pc.r1, pc.r0);
 }
 
 hipError_t launch_mul_plain(const PrimeConst* primes, const u64* a, const u64* pt, u64* out, int limbs, int polys,
-                            u64 n_batch, u64 a_bs, u64 o_bs, int log_n, hipStream_t st) {
+                            u64 n_batch, u64 a_bs, u64 o_bs, int log_n, hipStream_t st, unsigned pt_period) {
     if (t_analysis) t_analysis->c.mul_plain += n_batch;
     DRY_RUN_RETURN();
+    if (pt_period == 0 || n_batch == 0 || n_batch > 65535) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / NT, limbs * polys, (unsigned)n_batch);
     ProfScope prof__("mul_plain_kernel", st);
-    hipLaunchKernelGGL(mul_plain_kernel, grid, dim3(NT), 0, st, primes, a, pt, out, limbs, a_bs, o_bs, log_n);
+    hipLaunchKernelGGL(mul_plain_kernel, grid, dim3(NT), 0, st, primes, a, pt, out, limbs, a_bs, o_bs, pt_period, log_n);
     return hipGetLastError();
 }
 

@@ -321,8 +321,9 @@ hipError_t launch_addsub(const PrimeConst* primes, const u64* a, const u64* b, u
                          int polys_b, u64 n_batch, u64 a_bs, u64 b_bs, u64 o_bs, int log_n, hipStream_t st);
 hipError_t launch_add_const(const PrimeConst* primes, const u64* a, u64* out, const u64* consts, int op, int limbs,
                             int polys, int log_n, hipStream_t st);
+// entry b is multiplied by plaintext b % pt_period of the pt_period plaintexts at pt
 hipError_t launch_mul_plain(const PrimeConst* primes, const u64* a, const u64* pt, u64* out, int limbs, int polys,
-                            u64 n_batch, u64 a_bs, u64 o_bs, int log_n, hipStream_t st);
+                            u64 n_batch, u64 a_bs, u64 o_bs, int log_n, hipStream_t st, unsigned pt_period = 1);
 hipError_t launch_mul_const(const PrimeConst* primes, const u64* a, u64* out, const u64* consts, int limbs, int polys,
                             int log_n, hipStream_t st);
 hipError_t launch_mul_no_relin(const PrimeConst* primes, const u64* a, const u64* b, u64* out, int limbs, u64 n_batch,

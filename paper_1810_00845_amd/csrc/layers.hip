@@ -1909,10 +1909,9 @@ static int mask_run(hisa_ctx* ctx, const hisa_tensor* in, const u64* masks, doub
     const u64 words = ct_words(ctx, 2, l);
     int rc = alloc_ct_batch(ctx, n_in, 2, l, in->cts[0]->scale * mask_scale, xs.data());
     if (rc == HISA_OK) {
-        hipError_t e = hipSuccess;
-        for (uint32_t j = 0; j < per && e == hipSuccess; j++)
-            e = launch_mul_plain(ctx->d_primes, bi.base + (u64)j * bi.stride, masks + (u64)j * l * n, xs[0]->data + (u64)j * words,
-                                 (int)l, 2, B, (u64)per * bi.stride, (u64)per * words, (int)ctx->log_n, ctx->stream);
+        // entry b * per + j takes mask j: one launch
+        hipError_t e = launch_mul_plain(ctx->d_primes, bi.base, masks, xs[0]->data, (int)l, 2, n_in, bi.stride, words,
+                                        (int)ctx->log_n, ctx->stream, per);
         if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "masking multiply: %s", hipGetErrorString(e));
     }
     dev_release(ctx, bi.tmp);
