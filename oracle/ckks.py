@@ -97,6 +97,7 @@ def lib():
         L.orc_secret_squared.argtypes = [vp, u64p]
         L.orc_secret_automorph.argtypes = [vp, C.c_uint64, u64p]
         L.orc_mod_down.argtypes = [vp, u64p, C.c_int, u64p]
+        L.orc_mod_down_rescale.argtypes = [vp, u64p, C.c_int, u64p]
         L.orc_key_switch.argtypes = [vp, u64p, C.c_int, u64p, u64p, u64p]
         L.orc_key_switch_acc.argtypes = [vp, u64p, C.c_int, u64p, u64p, u64p]
         L.orc_fma_const.argtypes = [vp, u64p, u64p, u64p, C.POINTER(C.c_int), C.c_int]
@@ -437,6 +438,12 @@ class Oracle:
     def mod_down(self, acc: np.ndarray, l: int) -> np.ndarray:
         out = np.zeros((l, self.N), dtype=np.uint64)
         lib().orc_mod_down(self._h, _p(np.ascontiguousarray(acc)), l, _p(out))
+        return out
+
+    def mod_down_rescale(self, acc: np.ndarray, l: int) -> np.ndarray:
+        """acc [l + K][N] (NTT form) divided by q_{l-1} P in one base conversion: [l - 1][N]."""
+        out = np.zeros((l - 1, self.N), dtype=np.uint64)
+        lib().orc_mod_down_rescale(self._h, _p(np.ascontiguousarray(acc)), l, _p(out))
         return out
 
     def automorph_ntt(self, x: np.ndarray, g: int) -> np.ndarray:

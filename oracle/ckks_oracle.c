@@ -708,6 +708,38 @@ void orc_mod_down(const orc_ctx *c, const u64 *acc, int l, u64 *out) {
 }
 
 /*
+ * Mod-down and rescale in one division: the accumulator is divided by q_{l-1} * P instead of P, the limb of q_{l-1}
+ * joining the special limbs as a source of the base conversion; out has l - 1 limbs,
+ * out[i] = (acc[i] - conv_i) * (q_{l-1} P)^-1 mod q_i with conv the centred conversion of acc mod q_{l-1} P.
+ */
+void orc_mod_down_rescale(const orc_ctx *c, const u64 *acc, int l, u64 *out) {
+    u64 n = c->n;
+    int a = c->K + 1;
+    u64 *sp = malloc((size_t)a * n * sizeof(u64));
+    u64 *conv = malloc(n * sizeof(u64));
+    const u64 *rows[ORC_MAX_PRIMES];
+    int src[ORC_MAX_PRIMES];
+    for (int m = 0; m < a; m++) {
+        int pos = l - 1 + m, prime = m == 0 ? l - 1 : c->L + m - 1;
+        memcpy(sp + (size_t)m * n, acc + (size_t)pos * n, n * sizeof(u64));
+        orc_intt(c, prime, sp + (size_t)m * n);
+        rows[m] = sp + (size_t)m * n;
+        src[m] = prime;
+    }
+    for (int i = 0; i < l - 1; i++) {
+        u64 q = c->mod[i];
+        orc_base_conv(c, rows, src, a, i, conv);
+        orc_ntt(c, i, conv);
+        u64 d_mod = 1 % q;
+        for (int m = 0; m < a; m++) d_mod = mulmod(d_mod, c->mod[src[m]] % q, q);
+        u64 d_inv = invmod(d_mod, q);
+        for (u64 j = 0; j < n; j++)
+            out[(size_t)i * n + j] = mulmod(submod(acc[(size_t)i * n + j], conv[j], q), d_inv, q);
+    }
+    free(sp); free(conv);
+}
+
+/*
  * Hybrid key switch of one polynomial d (l limbs, NTT form) under `key`:
  *  1. d to coefficient form;
  *  2. for each digit j present at this level (primes j*alpha .. min((j+1)alpha, l)-1):

@@ -120,9 +120,12 @@ class SharedModDown:
             self.acc[(i, amount)] = (acc_b, acc_a, self.o.automorph_ntt(ct.data[0], g))
         return self.acc[(i, amount)]
 
-    def total(self, terms, scale):
+    def total(self, terms, scale, rescale=False):
         """terms: (input index, rotLeft amount, weight, weight key); weight is an integer (key None) or an array of N
-        signed plaintext coefficients (key: anything hashable that names it).  Returns the sum as a ciphertext."""
+        signed plaintext coefficients (key: anything hashable that names it).  Returns the sum as a ciphertext.
+        rescale: the sum's divScalar by the last modulus is taken together with the division by P -- the terms without
+        a rotation enter the accumulators times P, and the whole is divided by q_{l-1} P in one base conversion
+        (mod_down_rescale): one limb fewer, scale / q_{l-1}."""
         from .ckks import Ct
         o = self.o
         l = self.inputs[0].limbs
@@ -150,6 +153,14 @@ class SharedModDown:
                 fma(e_a, acc_a, w, wkey, ext, "ext")
                 fma(z[0], r0, w, wkey, qs, "q")
                 any_rotated = True
+        if rescale:
+            assert l >= 2
+            p_all = 1
+            for m in range(o.K):
+                p_all *= int(o.primes[o.L + m])
+            o.fma_const(e_b[:l], z[0], p_all, qs)
+            o.fma_const(e_a[:l], z[1], p_all, qs)
+            return Ct(np.stack([o.mod_down_rescale(e_b, l), o.mod_down_rescale(e_a, l)]), scale / float(o.primes[l - 1]))
         out = Ct(z, scale)
         if any_rotated:
             out = o.add(Ct(np.stack([o.mod_down(e_b, l), o.mod_down(e_a, l)]), scale), out)

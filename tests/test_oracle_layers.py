@@ -398,6 +398,35 @@ def test_chw_conv_taps_on_the_sums_schedule():
         assert np.abs(layers.tensor_decrypt(o, wrong) - want).max() > 1e-2
 
 
+def test_division_by_p_and_rescale_in_one():
+    """SharedModDown.total(rescale=True): the divScalar by the last modulus taken together with the division by P.
+    Against the two divisions one after the other: every coefficient within a few units (the conversion's rounding), so
+    the decrypted values agree to the noise; one limb fewer, scale / q_{l-1}; also dnum = 1 and a level with a ragged last digit."""
+    for q_bits, dnum, limbs in (([50, 40, 40, 40], 2, 4), ([50, 40, 40, 40, 40], 1, 5), ([50, 40, 40, 40, 40], 3, 4)):
+        o = Oracle(10, q_bits, dnum, 55, seed=5)
+        o.keygen(); o.gen_rot_keys([1, 3])
+        rng = np.random.default_rng(1)
+        zs = [rng.uniform(-1, 1, o.slots) for _ in range(3)]
+        big = 2.0 ** 40 * float(o.primes[limbs - 1])      # so that 2^40 is left after the division
+        cts = [o.mul_scalar(o.encrypt(o.encode(z, 2.0 ** 40, limbs)), 1.0, float(o.primes[limbs - 1])) for z in zs]
+        assert abs(cts[0].scale - big) <= 1e-9 * big
+        steps = [1, 0, 3]
+        terms = [(s, steps[s], 1, None) for s in range(3)]
+        two = o.rescale(layers.SharedModDown(o, cts).total(terms, big))
+        one = layers.SharedModDown(o, cts).total(terms, big, rescale=True)
+        assert one.limbs == two.limbs == limbs - 1 and abs(one.scale - two.scale) <= 1e-9 * two.scale
+        diff = o.export(one).astype(np.int64) - o.export(two).astype(np.int64)
+        diff = np.where(diff > 2 ** 39, diff - np.asarray(o.primes[:limbs - 1], dtype=np.int64)[None, :, None], diff)
+        diff = np.where(diff < -2 ** 39, diff + np.asarray(o.primes[:limbs - 1], dtype=np.int64)[None, :, None], diff)
+        # the fast base conversion is off by at most half a unit per source limb, the two-step rounding by a half
+        assert np.abs(diff).max() <= (o.K + 1) // 2 + 1
+        ref = sum(np.roll(zs[s], -steps[s]) for s in range(3))
+        assert np.abs(o.decode(o.decrypt(one)).real - ref).max() <= 1e-6
+        # the planted mistake: the unrotated term left out of the accumulators
+        bad = layers.SharedModDown(o, cts).total([terms[0], terms[2]], big, rescale=True)
+        assert np.abs(o.decode(o.decrypt(bad)).real - ref).max() > 1e-2
+
+
 def test_mask_tensor_cleans_a_pooled_tensor():
     o = Oracle(10, [50, 40, 40], 3, 55, seed=15)
     x = synth.image(51, 3, 4, 4)[None]
