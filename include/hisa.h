@@ -200,6 +200,14 @@ int hisa_rot_left_sum_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n_ou
  * hisa_rot_left_sum_batch needs (HISA_ERR_ARG otherwise, and for other values).  A plan prepared under one setting
  * must be applied under the same one (the plaintexts do not depend on it, the rotation keys do). */
 int hisa_set_merge_doublings(hisa_ctx* ctx, uint32_t max_doublings);
+/* Where a layer's division by P (the end of its key switches) is directly followed by its divScalar by the last
+ * modulus, on = 1 makes it take both at once: the accumulators on the l + K limbs (with the terms that were not
+ * rotated folded in, times P) are divided by q_{l-1} P in one base conversion whose sources are the limb of q_{l-1} and
+ * the special limbs.  One inverse and l - 1 forward transforms per polynomial instead of two rounds of them; the result
+ * differs from the two-step one by the rounding of the conversion (a few units per coefficient), so ciphertext bits
+ * differ.  Applies to the CHW-tiled convolutions that rotate sums; 0 (the default) keeps the two steps.  Needs what
+ * hisa_rot_left_sum_batch needs (HISA_ERR_ARG otherwise).  A setting of the context, like hisa_set_merge_doublings. */
+int hisa_set_fused_rescale(hisa_ctx* ctx, uint32_t on);
 int hisa_relinearize_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n);
 int hisa_rescale_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n);
 int hisa_add_batch(hisa_ctx* ctx, const hisa_ct* const* a, const hisa_ct* const* b, size_t n, hisa_ct** out);

@@ -520,7 +520,7 @@ def same_tap_inside(t: OTensor, fh, fw, fy, fx, stride):
     return (((ys >= 0) & (ys < t.height))[:, None] & ((xs >= 0) & (xs < t.width))[None, :]).reshape(-1)
 
 
-def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False, shared_moddown=False, schedule="in"):
+def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False, shared_moddown=False, schedule="in", fused_rescale=False):
     """w[FH][FW][IC][OC] on a clean CHW-tiled tensor -> clean CHW-tiled tensor with the same channel blocks.  The
     plaintext of (tap, d, input ciphertext j, output ciphertext g) holds, on the valid output positions of block b,
     the weight from input channel j c_inner + (b + d) mod c_inner to output channel g c_inner + b (zero where either
@@ -562,10 +562,12 @@ def conv2d_chw(o: Oracle, t: OTensor, w, stride=1, pad_same=False, shared_moddow
                 z[(here + at * cs) % o.slots] = float(w[fy, fx, ic, oc])
         coeffs[fy, fx, d, j, g] = o.encode_coeffs(z, pt_scale)
     ints = {"pt_coeffs": coeffs, "pt_scale": pt_scale}
-    return conv2d_chw_fixed(o, t, ints, oc_n, fh, fw, stride, pad_same, shared_moddown, schedule), ints
+    return conv2d_chw_fixed(o, t, ints, oc_n, fh, fw, stride, pad_same, shared_moddown, schedule, fused_rescale), ints
 
 
-def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, shared_moddown=False, schedule="in"):
+def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, shared_moddown=False, schedule="in",
+                     fused_rescale=False):
+    """fused_rescale (the schedules that rotate sums): the divScalar is taken together with the sums' division by P."""
     ci = t.c_inner
     wrap, amounts = chw_conv_geometry(o, t, fh, fw, pad_same)
     if pad_same:
@@ -592,8 +594,9 @@ def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same
                                 acc = temp if acc is None else o.add(acc, temp)
                         sums.append(acc)
                         steps.append(amounts[fy][fx][0])
-                total = SharedModDown(o, sums).total([(k, steps[k], 1, None) for k in range(len(sums))], sums[0].scale)
-                outs.append(o.div_scalar(total, o.max_scalar_div(total, float("inf"))))
+                total = SharedModDown(o, sums).total([(k, steps[k], 1, None) for k in range(len(sums))], sums[0].scale,
+                                                     rescale=fused_rescale)
+                outs.append(total if fused_rescale else o.div_scalar(total, o.max_scalar_div(total, float("inf"))))
             continue
         if schedule == "out":
             # amounts[fy][fx][0] is the tap's own amount, d * c_stride the diagonal's
@@ -610,8 +613,9 @@ def conv2d_chw_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same
                                 temp = o.mul_plain(by_tap[(j, fy, fx)], pt)
                                 acc = temp if acc is None else o.add(acc, temp)
                     sums.append(acc)
-                total = SharedModDown(o, sums).total([(d, d * t.c_stride, 1, None) for d in range(ci)], sums[0].scale)
-                outs.append(o.div_scalar(total, o.max_scalar_div(total, float("inf"))))
+                total = SharedModDown(o, sums).total([(d, d * t.c_stride, 1, None) for d in range(ci)], sums[0].scale,
+                                                     rescale=fused_rescale)
+                outs.append(total if fused_rescale else o.div_scalar(total, o.max_scalar_div(total, float("inf"))))
             continue
         # the rotations do not depend on the output ciphertext: computed once
         shared = SharedModDown(o, xs) if shared_moddown else None

@@ -409,6 +409,36 @@ hipError_t launch_automorph_sum(const PrimeConst* primes, const u64* rot, u64 ro
     return hipGetLastError();
 }
 
+// acc[b][poly] += P * add[b][poly] on the limbs of q_0 .. q_{l-1}, for the polynomials the addend has: what a
+// ciphertext contributes to key-switch accumulators that are divided by P later.  acc entries are (ciphertext,
+// polynomial) pairs acc_bs words apart; pmod[i] = P mod q_i.
+__global__ __launch_bounds__(NT) void fold_addend_kernel(const PrimeConst* primes, u64* acc, u64 acc_bs, const u64* add, u64 add_bs,
+                                                         u64 add_ps, int add_polys, const u64* pmod, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const int limb = blockIdx.y;
+    const u64 e = blockIdx.z, ct = e >> 1;
+    const int poly = (int)(e & 1);
+    if (poly >= add_polys) return;
+    const PrimeConst pc = primes[limb];
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    u64* dst = acc + e * acc_bs + (u64)limb * n + j;
+    const u64 v = add[ct * add_bs + (u64)poly * add_ps + (u64)limb * n + j];
+    *dst = addmod(*dst, mulmod_barrett(v, pmod[limb], pc.q, pc.r1, pc.r0), pc.q);
+}
+
+hipError_t launch_fold_addend(const PrimeConst* primes, u64* acc, u64 acc_bs, const u64* add, u64 add_bs, u64 add_ps,
+                              int add_polys, const u64* pmod, u64 n_cts, int l, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
+    const u64 n = (u64)1 << log_n;
+    if (!primes || !acc || !add || !pmod || n_cts == 0 || 2 * n_cts > 65535 || l < 1 || add_polys < 1 || add_polys > 2)
+        return hipErrorInvalidValue;
+    if (acc_bs < (u64)l * n || add_ps < (u64)l * n || add_bs < (u64)add_polys * l * n) return hipErrorInvalidValue;
+    dim3 grid((1u << log_n) / NT, l, (unsigned)(2 * n_cts));
+    ProfScope prof__("fold_addend_kernel", st);
+    hipLaunchKernelGGL(fold_addend_kernel, grid, dim3(NT), 0, st, primes, acc, acc_bs, add, add_bs, add_ps, add_polys, pmod, log_n);
+    return hipGetLastError();
+}
+
 // signed integer coefficients [n_pts][N] -> residues modulo primes[0..limbs-1] at out[p][0..limbs-1][N], the entries of
 // out being out_limbs limbs apart
 __global__ __launch_bounds__(NT) void reduce_i64_kernel(const PrimeConst* primes, const i64* coeffs, u64* out, int out_limbs,

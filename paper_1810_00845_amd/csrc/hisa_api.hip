@@ -1274,6 +1274,77 @@ int moddown_add_fp(hisa_ctx* ctx, const u64* acc, size_t B, int l, const u64* ad
     return HISA_OK;
 }
 
+// Tables of the combined division at level l: sources q_{l-1}, p_0 .. p_{K-1} (conversion table; (D/s_m)^-1 as centred
+// doubles, D = q_{l-1} P) and D^-1 mod q_i as centred doubles indexed by prime
+static int moddown_rescale_tables(hisa_ctx* ctx, int l, ConvTable** tab, double** post, double** dinv) {
+    const auto key = std::make_pair(-l, (int)ctx->K + 1);
+    auto it = ctx->modup_tabs.find(key);
+    if (it == ctx->modup_tabs.end()) {
+        std::vector<int> src(1, l - 1);
+        for (uint32_t m = 0; m < ctx->K; m++) src.push_back((int)(ctx->L + m));
+        ConvTable t = {};
+        TRY(make_conv_table(ctx, src, &t));
+        it = ctx->modup_tabs.emplace(key, t).first;
+    }
+    *tab = &it->second;
+    const u64 KEY = 12288 + (u64)l;     // (8192 + l: the constants of the plain rescale)
+    auto ia = ctx->aux.find(KEY);
+    if (ia == ctx->aux.end()) {
+        const ConvTable& t = it->second;
+        std::vector<double> v((size_t)t.a + ctx->total, 0.0);
+        for (int m = 0; m < t.a; m++) v[m] = centred_double(t.inv_hat[m], ctx->mod[t.src[m]]);
+        for (int i = 0; i < l - 1; i++) {
+            const u64 q = ctx->mod[i];
+            u64 d = 1 % q;
+            for (int m = 0; m < t.a; m++) d = hm::mul(d, ctx->mod[t.src[m]] % q, q);
+            v[(size_t)t.a + i] = centred_double(hm::inv(d, q), q);
+        }
+        double* dev = nullptr;
+        HIP_TRY(ctx, upload(&dev, v));
+        ia = ctx->aux.emplace(KEY, SwitchKey{new DevBlock{dev, v.size() * sizeof(double), 1}, (u64*)dev}).first;
+    }
+    *post = (double*)ia->second.data;
+    *dinv = (double*)ia->second.data + it->second.a;
+    return HISA_OK;
+}
+
+int moddown_rescale_fp(hisa_ctx* ctx, u64* acc, size_t B, int l, const u64* add, u64 add_bs, int add_polys, u64* out) {
+    if (!fused_key_switch_available(ctx)) return fail(ctx, HISA_ERR_ARG, "no fused key-switch path for these parameters");
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "no level to rescale into");
+    const size_t n = ctx->N;
+    const int K = (int)ctx->K, L = (int)ctx->L, total = (int)ctx->total, ext_limbs = l + K, log_n = (int)ctx->log_n;
+    hipStream_t st = ctx->stream;
+    ConvTable* tab;
+    double *post, *dinv;
+    TRY(moddown_rescale_tables(ctx, l, &tab, &post, &dinv));
+    Temp y2(ctx, B * 2 * (size_t)(K + 1) * n * sizeof(double));
+    if (!y2.ok()) return HISA_ERR_OOM;
+    if (add)
+        HIP_TRY(ctx, launch_fold_addend(ctx->d_primes, acc, (u64)ext_limbs * n, add, add_bs, (u64)l * n, add_polys, ctx->d_pmod, B, l,
+                                        log_n, st));
+    const FpArgs base = fp_base(ctx);
+    {   // the limb of q_{l-1} and the special limbs to coefficient form, times (D/s_m)^-1
+        FpArgs a = base;
+        FpTask tk = {};
+        tk.period = K + 1;
+        for (int m = 0; m <= K; m++) { tk.pos[m] = (int16_t)m; tk.prime[m] = (int16_t)(m == 0 ? l - 1 : L + m - 1); }
+        a.in = acc; a.in_bs = (u64)ext_limbs * n; a.in_pos_shift = l - 1; a.post = post;
+        a.yout = y2.as<double>(); a.yout_bs = (u64)(K + 1) * n;
+        HIP_TRY(ctx, launch_ntt_fp(FP_INV_TO_Y, log_n, a, tk, B * 2, st));
+    }
+    {   // conversion to q_0 .. q_{l-2}, forward transform, (acc - conv) D^-1
+        FpArgs a = base;
+        FpTask tk = {};
+        tk.period = l - 1;
+        for (int i = 0; i < l - 1; i++) { tk.pos[i] = (int16_t)i; tk.prime[i] = (int16_t)i; }
+        a.y = y2.as<double>(); a.y_bs = (u64)(K + 1) * n; a.y_pos0 = 0; a.conv_a = K + 1; a.total = total; a.hat = tab->d_hat_f;
+        a.acc = acc; a.acc_bs = (u64)ext_limbs * n; a.acc_pos_shift = 0; a.pinv_tab = dinv;
+        a.out = out; a.out_bs = (u64)(l - 1) * n;
+        HIP_TRY(ctx, launch_ntt_fp(FP_FWD_CONV_FINAL, log_n, a, tk, B * 2, st));
+    }
+    return HISA_OK;
+}
+
 static int key_switch_finish_fp(hisa_ctx* ctx, const FpExt& x, const u64* d, u64 d_bs, u64 galois, int gather_ext, size_t B,
                                 const SwitchKey& key, const u64* add, u64 add_bs, int add_polys, u64* out) {
     const size_t n = ctx->N;
@@ -1364,7 +1435,7 @@ int rotation_accumulators_fp(hisa_ctx* ctx, const u64* cts, u64 ct_bs, size_t B,
 }
 
 int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const int32_t* steps, size_t Bn, int l,
-                  const u64* plain, u64 plain_bs, u64* out, bool shared_input) {
+                  const u64* plain, u64 plain_bs, u64* out, bool shared_input, bool rescale) {
     if (!fused_key_switch_available(ctx)) return fail(ctx, HISA_ERR_ARG, "no fused key-switch path for these parameters");
     if (n_steps < 1 || n_steps > FP_MAX_STEPS || Bn == 0 || l < 1) return fail(ctx, HISA_ERR_ARG, "bad rotation sum");
     const size_t n = ctx->N;
@@ -1392,8 +1463,10 @@ int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const i
         t_analysis->c.rot_summed += (u64)n_steps * Bn;
         if (shared_input) t_analysis->c.rot_shared += (u64)(n_steps - 1) * Bn;
         t_analysis->c.key_switch_calls += 1;
+        if (rescale) t_analysis->c.rescale += Bn;
         return HISA_OK;
     }
+    if (rescale && l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "no level to rescale into");
     const size_t E = shared_input ? Bn : (size_t)n_steps * Bn;
     FpExt x(ctx, E, l, K, alpha);
     Temp acc(ctx, Bn * 2 * (size_t)ext_limbs * n * sizeof(u64));
@@ -1407,7 +1480,17 @@ int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const i
     HIP_TRY(ctx, launch_automorph_sum(ctx->d_primes, rot, ct_bs, n_steps, tab, plain, plain_bs, addend.u(), (u64)2 * l * n, Bn,
                                       shared_input ? 1 : 0, l,
                                       (int)ctx->log_n, ctx->stream));
+    if (rescale) return moddown_rescale_fp(ctx, acc.u(), Bn, l, addend.u(), (u64)2 * l * n, 2, out);
     return moddown_add_fp(ctx, acc.u(), Bn, l, addend.u(), (u64)2 * l * n, 2, 0, out);
+}
+
+extern "C" int hisa_set_fused_rescale(hisa_ctx* ctx, uint32_t on) {
+    if (!ctx) return HISA_ERR_ARG;
+    if (on > 1) return fail(ctx, HISA_ERR_ARG, "on is 0 or 1");
+    if (on && !fused_key_switch_available(ctx))
+        return fail(ctx, HISA_ERR_ARG, "the combined division needs the fused key-switch path (N >= 2^12, every prime below 2^50, dnum <= 8)");
+    ctx->fused_rescale = on;
+    return HISA_OK;
 }
 
 extern "C" int hisa_rot_left_sum_batch(hisa_ctx* ctx, const hisa_ct* const* in, size_t n_out, const int32_t* steps,

@@ -118,6 +118,7 @@ struct hisa_ctx {
     u64* d_secret;  // [total][N], NTT form
     std::map<u64, SwitchKey> keys;  // 0: relinearisation, else Galois element
     struct Analysis* analysis = nullptr;   // non-null between hisa_analysis_begin and hisa_analysis_end
+    uint32_t fused_rescale = 0;            // hisa_set_fused_rescale: layers divide by q_{l-1} P at once where they can
     uint32_t merge_doublings = 0;          // hisa_set_merge_doublings: rotate-and-add chains as sums of rotations (0, 2..4)
     std::map<u64, SwitchKey> aux;   // small derived device tables, built on first use
     std::map<std::pair<int, int>, ConvTable> modup_tabs;  // (digit, size)
@@ -195,8 +196,13 @@ int rotation_accumulators_fp(hisa_ctx* ctx, const u64* cts, u64 ct_bs, size_t B,
 // n_steps * Bn ciphertexts [2][l][N], ct_bs words apart, rotation-major; every step rotates (its key is present);
 // plain ([Bn] ciphertexts, plain_bs apart) may be null; out [Bn][2][l][N].  shared_input: rot holds Bn ciphertexts and
 // every term of output b rotates rot[b] (one decomposition per output).  Dry runs count and return.
+// rescale: the sum's divScalar is taken together with its division by P (moddown_rescale_fp): out [Bn][2][l - 1][N].
 int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const int32_t* steps, size_t Bn, int l,
-                  const u64* plain, u64 plain_bs, u64* out, bool shared_input = false);
+                  const u64* plain, u64 plain_bs, u64* out, bool shared_input = false, bool rescale = false);
+// The division by P and the divScalar by q_{l-1} in one base conversion: acc [B][2][l + K][N] (overwritten: the addend
+// [B][add_polys][l][N] is first folded in, times P) -> out [B][2][l - 1][N] = (acc + P add) / (q_{l-1} P), rounded as a
+// centred conversion rounds.  l >= 2.
+int moddown_rescale_fp(hisa_ctx* ctx, u64* acc, size_t B, int l, const u64* add, u64 add_bs, int add_polys, u64* out);
 int moddown_add_fp(hisa_ctx* ctx, const u64* acc, size_t B, int l, const u64* add, u64 add_bs, int add_polys, u64 add_galois,
                    u64* out);
 // exact integer nearest to the double v (ties away from zero), reduced modulo q
@@ -348,6 +354,9 @@ hipError_t launch_automorph_steps(const u64* in, u64 in_bs, u64* out, u64 out_bs
 hipError_t launch_automorph_sum(const PrimeConst* primes, const u64* rot, u64 rot_bs, int n_rot, const GaloisTab& tab,
                                 const u64* plain, u64 plain_bs, u64* out, u64 out_bs, u64 n_batch, int shared_input, int l,
                                 int log_n, hipStream_t st);
+// acc entries (ciphertext, polynomial), acc_bs apart: acc += P * add on the first l limbs, for polynomials < add_polys
+hipError_t launch_fold_addend(const PrimeConst* primes, u64* acc, u64 acc_bs, const u64* add, u64 add_bs, u64 add_ps,
+                              int add_polys, const u64* pmod, u64 n_cts, int l, int log_n, hipStream_t st);
 hipError_t launch_reduce_i64(const PrimeConst* primes, const i64* coeffs, u64* out, int limbs, int n_pts, int log_n,
                              hipStream_t st);
 // the same with the output entries out_limbs limbs apart (residues on a second list of primes go behind the first)

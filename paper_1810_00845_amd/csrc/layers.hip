@@ -1071,7 +1071,11 @@ static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_g
     const size_t sums = terms * OCm;               // per image, ordered (term, g): term = diagonal d, or sum k of the taps
     Temp y(ctx, (size_t)B * sums * ctw * sizeof(u64));
     if (rc == HISA_OK && !y.ok()) rc = HISA_ERR_OOM;
-    if (rc == HISA_OK) rc = alloc_ct_batch(ctx, (size_t)B * OCm, 2, l, mac_scale, outs.data());
+    // with hisa_set_fused_rescale the sums come back divided by q_{l-1} P: one limb fewer, no divScalar afterwards
+    const bool fused = ctx->fused_rescale != 0;
+    if (rc == HISA_OK)
+        rc = alloc_ct_batch(ctx, (size_t)B * OCm, 2, fused ? l - 1 : l, fused ? mac_scale / (double)ctx->mod[l - 1] : mac_scale,
+                            outs.data());
     if (rc == HISA_OK) {
         ma.n_taps = n_taps; ma.IC = (int)IC; ma.OC = (int)sums; ma.l = (int)l; ma.ct_words = ctw;
         ma.out = y.u();
@@ -1086,9 +1090,9 @@ static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_g
     for (uint32_t b = 0; b < B && rc == HISA_OK; b++) {
         const u64* yb = y.u() + (size_t)b * sums * ctw;
         rc = rotate_sum_fp(ctx, yb + (size_t)OCm * ctw, ctw, (int)terms - 1, plan.sum_steps.data(), OCm, (int)l, yb, ctw,
-                           outs[(size_t)b * OCm]->data);
+                           outs[(size_t)b * OCm]->data, false, fused);
     }
-    if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
+    if (rc == HISA_OK && !fused) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
     if (rc != HISA_OK) {
         for (hisa_ct* c : outs) hisa_free(ctx, c);
         return rc;

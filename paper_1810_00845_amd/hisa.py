@@ -339,6 +339,10 @@ class Context:
         """FC / matmul rotate-and-add chains as sums of rotations: 0 (off) or 2..4 consecutive doublings per sum."""
         self._ck(load().hisa_set_merge_doublings(self._vp, C.c_uint32(max_doublings)))
 
+    def set_fused_rescale(self, on):
+        """Layers divide by q_{l-1} P in one base conversion where their divScalar directly follows the division by P."""
+        self._ck(load().hisa_set_fused_rescale(self._vp, C.c_uint32(1 if on else 0)))
+
     def add_batch(self, a, b):
         return self._batch_out("hisa_add_batch", len(a), self._harr(a), self._harr(b), C.c_size_t(len(a)))
 

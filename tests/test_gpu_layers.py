@@ -532,6 +532,18 @@ def test_chw_conv_same_by_masking_bit_exact(c_stride):
             for ca, cb in zip(gfloat.cts, gplan.cts):
                 assert np.array_equal(g.ct_export(ca), g.ct_export(cb))
             g.conv_plan_free(plan)
+    # the sums' division by P and the divScalar in one base conversion (hisa_set_fused_rescale)
+    g.set_fused_rescale(True)
+    for sched, name in ((1, "out"), (2, "taps")):
+        oout, ints = layers.conv2d_chw(o, ot, w, pad_same=2, schedule=name, fused_rescale=True)
+        gout = g.conv2d_fixed(gt, None, 1.0, ints["pt_coeffs"], ints["pt_scale"], 6, 3, 3, pad_same=2, mode=layers.CONV_PLAIN,
+                              chw_schedule=sched)
+        same_tensor(g, o, gout, oout)
+        assert gout.cts[0].limbs == 2 and np.abs(g.tensor_decrypt(gout) - plain_net.conv2d(x, w, pad_same=True)).max() <= 1e-3
+    unfused, _ = layers.conv2d_chw(o, ot, w, pad_same=2, schedule="in")
+    gin = g.conv2d(gt, w, 3, 3, pad_same=2, mode=layers.CONV_PLAIN)              # the schedule without sums is untouched
+    assert np.abs(g.tensor_decrypt(gin) - layers.tensor_decrypt(o, unfused)).max() <= 1e-5
+    g.set_fused_rescale(False)
     hw = g.tensor_encrypt(x, 2.0 ** 40, 3, h_stride=4)
     for kw in (dict(mode=layers.CONV_PLAIN), dict(mode=layers.CONV_SCALAR)):
         with pytest.raises(hisa.HisaError) as e:
