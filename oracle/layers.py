@@ -155,12 +155,7 @@ class SharedModDown:
                 any_rotated = True
         if rescale:
             assert l >= 2
-            p_all = 1
-            for m in range(o.K):
-                p_all *= int(o.primes[o.L + m])
-            o.fma_const(e_b[:l], z[0], p_all, qs)
-            o.fma_const(e_a[:l], z[1], p_all, qs)
-            return Ct(np.stack([o.mod_down_rescale(e_b, l), o.mod_down_rescale(e_a, l)]), scale / float(o.primes[l - 1]))
+            return divide_by_p_and_last(o, e_b, e_a, z, l, scale)
         out = Ct(z, scale)
         if any_rotated:
             out = o.add(Ct(np.stack([o.mod_down(e_b, l), o.mod_down(e_a, l)]), scale), out)
@@ -449,15 +444,42 @@ def sum_pool2x2(o: Oracle, t: OTensor, merge=0):
                    w_stride=2 * t.w_stride, clean=0)
 
 
-def poly2_act(o: Oracle, t: OTensor, a, b):
-    """x^2 + (b/a) x, the factor a being left to the next layer."""
+def divide_by_p_and_last(o: Oracle, e_b, e_a, z, l, scale):
+    """(ModDown(e_b) + z_0, ModDown(e_a) + z_1) followed by the divScalar by q_{l-1}, as ONE division by q_{l-1} P: z enters
+    the accumulators times P first."""
+    from .ckks import Ct
+    p_all = 1
+    for m in range(o.K):
+        p_all *= int(o.primes[o.L + m])
+    qs = list(range(l))
+    o.fma_const(e_b[:l], z[0], p_all, qs)
+    o.fma_const(e_a[:l], z[1], p_all, qs)
+    return Ct(np.stack([o.mod_down_rescale(e_b, l), o.mod_down_rescale(e_a, l)]), scale / float(o.primes[l - 1]))
+
+
+def poly2_act(o: Oracle, t: OTensor, a, b, fused_rescale=False):
+    """x^2 + (b/a) x, the factor a being left to the next layer.  fused_rescale: the linear term joins (d0, d1) of the
+    unrelinearised square, and the relinearisation's division by P is taken together with the divScalar."""
     outs = []
     for ct in t.cts:
+        if fused_rescale:
+            sq = o.mul_no_relin(ct, ct)
+            z = sq.data[:2].copy()
+            if b != 0.0:
+                z = o.add(Ct2(z, sq.scale), o.mul_scalar(ct, b / a, ct.scale)).data
+            e_b, e_a = o.key_switch_acc(sq.data[2], 0)
+            outs.append(divide_by_p_and_last(o, e_b, e_a, z, ct.limbs, sq.scale))
+            continue
         acc = o.mul(ct, ct)
         if b != 0.0:
             acc = o.add(acc, o.mul_scalar(ct, b / a, ct.scale))
         outs.append(o.rescale(acc))
     return replace(t, cts=outs)
+
+
+def Ct2(data, scale):
+    from .ckks import Ct
+    return Ct(np.ascontiguousarray(data), scale)
 
 
 def rot_steps_conv(o: Oracle, t: OTensor, fh, fw, pad_same=False):

@@ -110,7 +110,7 @@ def chw_blocks(slots, plane_slots_needed, layers, chw_convs=True):
 
 
 def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans=None, layout="hw", shared_moddown=True,
-                  layer_times=True, rotate_sums=True, merge_doublings=4):
+                  layer_times=True, rotate_sums=True, merge_doublings=4, fused_rescale=True):
     """Encrypts x, runs the layers, decrypts.  Returns (output array, seconds from encrypt-done to the last
     ciphertext ready, per-layer seconds).  With make_keys the rotation keys each layer asks for are generated
     on the way (set-up pass); otherwise they must be resident.  `plans` (a dict, filled by the set-up pass and
@@ -126,7 +126,8 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
     parameters have the fused key-switch path).  rotate_sums: a CHW-tiled convolution reduces over the channel blocks
     after the multiplication (HISA_CHW_ROTATE_SUMS) where that takes fewer key switches.  merge_doublings: the
     rotate-and-add chains of FC and matmul take up to that many consecutive doublings as one sum of rotations
-    (hisa_set_merge_doublings; 0: the chains as they are).  layer_times: wait for the GPU after every layer to time it; without,
+    (hisa_set_merge_doublings; 0: the chains as they are).  fused_rescale: layers whose division by P is directly
+    followed by their divScalar take both in one base conversion (hisa_set_fused_rescale).  layer_times: wait for the GPU after every layer to time it; without,
     the host queues the whole network ahead of the GPU and only the end-to-end latency is measured (per-layer entries
     are then host queueing times)."""
     assert layout in LAYOUTS
@@ -134,6 +135,7 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
         border = 0      # CHW-tiled convolutions multiply by plaintexts, which carry the SAME padding: planes back to back
     fused = ctx.log_n >= 12 and max(ctx.primes) < 2 ** 50 and ctx.dnum <= 8
     ctx.set_merge_doublings(merge_doublings if fused else 0)
+    ctx.set_fused_rescale(bool(fused_rescale and fused))
     replicas = 1 if layout == "hw" else 1 << 30
     tiling = {}
     if layout in ("chw", "hw_conv"):

@@ -427,6 +427,20 @@ def test_division_by_p_and_rescale_in_one():
         assert np.abs(o.decode(o.decrypt(bad)).real - ref).max() > 1e-2
 
 
+def test_activation_with_one_division():
+    """poly2_act(fused_rescale=True) against the fp64 activation and against the two-step schedule."""
+    o = Oracle(10, [50, 40, 40, 40], 2, 55, seed=6)
+    o.keygen()
+    x = synth.image(61, 2, 4, 4)[None]
+    t = layers.tensor_encrypt(o, x, 2.0 ** 40, 4)
+    for a, b in ((0.4, 0.3), (0.5, 0.0)):
+        one, two = layers.poly2_act(o, t, a, b, fused_rescale=True), layers.poly2_act(o, t, a, b)
+        want = plain_net.poly2_act_without_a(x, a, b)
+        assert one.cts[0].limbs == 3 and abs(one.cts[0].scale - two.cts[0].scale) <= 1e-9 * two.cts[0].scale
+        assert np.abs(layers.tensor_decrypt(o, one) - want).max() <= 1e-6
+        assert np.abs(layers.tensor_decrypt(o, one) - layers.tensor_decrypt(o, two)).max() <= 1e-7
+
+
 def test_mask_tensor_cleans_a_pooled_tensor():
     o = Oracle(10, [50, 40, 40], 3, 55, seed=15)
     x = synth.image(51, 3, 4, 4)[None]
