@@ -1484,6 +1484,30 @@ int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const i
     return moddown_add_fp(ctx, acc.u(), Bn, l, addend.u(), (u64)2 * l * n, 2, 0, out);
 }
 
+int relinearize_rescale_fp(hisa_ctx* ctx, const u64* cts3, u64 stride, size_t n_cts, int l, u64* out) {
+    if (!fused_key_switch_available(ctx)) return fail(ctx, HISA_ERR_ARG, "no fused key-switch path for these parameters");
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "no level to rescale into");
+    if (t_analysis) {
+        t_analysis->c.relinearize += n_cts;
+        t_analysis->c.rescale += n_cts;
+        t_analysis->c.key_switch_calls += 1;
+        return HISA_OK;
+    }
+    auto it = ctx->keys.find(0);
+    if (it == ctx->keys.end()) return fail(ctx, HISA_ERR_NO_KEY, "no relinearisation key: call hisa_keygen");
+    const size_t n = ctx->N, lw = (size_t)l * n;
+    const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total, ext_limbs = l + K;
+    if (stride < 3 * lw) return fail(ctx, HISA_ERR_ARG, "bad stride");
+    FpExt x(ctx, n_cts, l, K, alpha);
+    Temp acc(ctx, n_cts * 2 * (size_t)ext_limbs * n * sizeof(u64));
+    if (!x.ok() || !acc.ok()) return HISA_ERR_OOM;
+    const u64* d2 = cts3 + 2 * lw;
+    TRY(key_switch_modup_fp(ctx, d2, stride, 0, n_cts, x));
+    HIP_TRY(ctx, launch_inner_product_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, it->second.data, total, d2,
+                                         stride, 0, 0, acc.u(), (u64)2 * ext_limbs * n, n_cts, (int)ctx->log_n, ctx->stream));
+    return moddown_rescale_fp(ctx, acc.u(), n_cts, l, cts3, stride, 2, out);
+}
+
 extern "C" int hisa_set_fused_rescale(hisa_ctx* ctx, uint32_t on) {
     if (!ctx) return HISA_ERR_ARG;
     if (on > 1) return fail(ctx, HISA_ERR_ARG, "on is 0 or 1");

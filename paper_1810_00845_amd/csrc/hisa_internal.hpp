@@ -203,6 +203,9 @@ int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const i
 // [B][add_polys][l][N] is first folded in, times P) -> out [B][2][l - 1][N] = (acc + P add) / (q_{l-1} P), rounded as a
 // centred conversion rounds.  l >= 2.
 int moddown_rescale_fp(hisa_ctx* ctx, u64* acc, size_t B, int l, const u64* add, u64 add_bs, int add_polys, u64* out);
+// Relinearisation of n three-polynomial ciphertexts ([3][l][N], stride words apart) whose division by P is taken
+// together with the divScalar by q_{l-1}: out [n][2][l - 1][N] = ((d0, d1) + KS_relin(d2)) / q_{l-1}.
+int relinearize_rescale_fp(hisa_ctx* ctx, const u64* cts3, u64 stride, size_t n, int l, u64* out);
 int moddown_add_fp(hisa_ctx* ctx, const u64* acc, size_t B, int l, const u64* add, u64 add_bs, int add_polys, u64 add_galois,
                    u64* out);
 // exact integer nearest to the double v (ties away from zero), reduced modulo q

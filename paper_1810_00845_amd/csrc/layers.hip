@@ -2332,6 +2332,45 @@ extern "C" int hisa_poly2_act(hisa_ctx* ctx, const hisa_tensor* in, double a, do
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "activation needs a level to rescale into");
     std::vector<hisa_ct*> sq(nct, nullptr);
     TRY(hisa_mul_no_relin_batch(ctx, (const hisa_ct* const*)in->cts, (const hisa_ct* const*)in->cts, nct, sq.data()));
+    if (ctx->fused_rescale) {
+        // the linear term joins (d0, d1) of the unrelinearised square, and the relinearisation's division by P is taken
+        // together with the divScalar (hisa_set_fused_rescale)
+        const u64 words = ct_words(ctx, 2, l), words3 = ct_words(ctx, 3, l);
+        int rc = HISA_OK;
+        if (b != 0.0) {
+            const double v = (b / a) * in->cts[0]->scale;
+            BatchIn bi;
+            rc = gather_batch(ctx, (const hisa_ct* const*)in->cts, nct, &bi);
+            Temp lin(ctx, nct * words * sizeof(u64));
+            if (rc == HISA_OK && !lin.ok()) rc = HISA_ERR_OOM;
+            if (rc == HISA_OK) {
+                u64 consts[2 * HISA_MAX_PRIMES];
+                for (uint32_t i = 0; i < l; i++) {
+                    consts[i] = double_to_residue(v, ctx->mod[i]);
+                    consts[l + i] = (u64)(((u128)consts[i] << 64) / ctx->mod[i]);
+                }
+                hipError_t e = launch_mul_const(ctx->d_primes, bi.base, lin.u(), consts, (int)l, (int)(nct * 2), (int)ctx->log_n,
+                                                ctx->stream);
+                if (e == hipSuccess)   // (d0, d1) += lin: the first two polynomials of every three-polynomial entry
+                    e = launch_addsub(ctx->d_primes, sq[0]->data, lin.u(), sq[0]->data, OP_ADD, (int)l, 2, 2, nct, words3, words, words3,
+                                      (int)ctx->log_n, ctx->stream);
+                if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "activation: %s", hipGetErrorString(e));
+            }
+            dev_release(ctx, bi.tmp);
+        }
+        std::vector<hisa_ct*> outs(nct, nullptr);
+        if (rc == HISA_OK) rc = alloc_ct_batch(ctx, nct, 2, l - 1, sq[0]->scale / (double)ctx->mod[l - 1], outs.data());
+        if (rc == HISA_OK) {
+            rc = relinearize_rescale_fp(ctx, sq[0]->data, words3, nct, (int)l, outs[0]->data);
+            if (rc != HISA_OK) free_handles(ctx, outs);
+        }
+        free_handles(ctx, sq);
+        if (rc != HISA_OK) return rc;
+        for (size_t i = 0; i < nct; i++) out->cts[i] = outs[i];
+        fill_out_meta(out, in->batch, in->channels, in->height, in->width, in->h_stride, in->w_stride, in->offset, in->clean,
+                      t_ci(in), in->c_stride);
+        return HISA_OK;
+    }
     int rc = hisa_relinearize_batch(ctx, sq.data(), nct);
     if (rc == HISA_OK && b != 0.0) {
         // (b/a) * x at scale s * s: multiply every residue by round((b/a) * s)

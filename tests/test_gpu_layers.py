@@ -555,6 +555,31 @@ def test_chw_conv_same_by_masking_bit_exact(c_stride):
     g.close()
 
 
+def test_activation_with_fused_rescale_bit_exact():
+    """hisa_set_fused_rescale on the degree-2 activation (HW- and CHW-tiled, with and without a linear term, two
+    levels): against the oracle's one-division schedule bit for bit, against the fp64 activation, and the dry run."""
+    from oracle import layers
+    from paper_1810_00845_amd import hisa, synth
+    g, o = make_pair(12, [50, 40, 40, 40], 2, 50, 31)
+    g.keygen(); o.keygen()
+    x = synth.image(71, 3, 4, 4)[None].repeat(2, axis=0) * np.array([1.0, -0.6])[:, None, None, None]
+    g.set_fused_rescale(True)
+    for make in (lambda: both_tensors(g, o, x, 2.0 ** 40, 4), lambda: chw_pair(g, o, x, 2.0 ** 40, 4, 2, 32, 903, h_stride=4)):
+        gt, ot = make()
+        want = x
+        for a, b in ((0.4, 0.3), (0.5, 0.0)):
+            gt, ot = g.poly2_act(gt, a, b), layers.poly2_act(o, ot, a, b, fused_rescale=True)
+            same_tensor(g, o, gt, ot)
+            want = plain_net.poly2_act_without_a(want, a, b)
+            assert np.abs(g.tensor_decrypt(gt) - want).max() <= 1e-5
+        assert gt.cts[0].limbs == 2
+    g.analysis_begin()
+    dry = g.poly2_act(both_tensors(g, o, x, 2.0 ** 40, 4)[0], 0.4, 0.3)
+    counts, _ = g.analysis_end()
+    assert counts["relinearize"] == 6 and counts["rescale"] == 6 and counts["mul"] == 6 and dry.cts[0].limbs == 3
+    g.close()
+
+
 def test_mask_layer_then_chw_conv_on_a_pooled_tensor():
     """pool (not clean) -> masking multiply -> CHW convolution, every step bit for bit; the convolution refuses the
     unmasked tensor."""
