@@ -266,6 +266,27 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             e3 = convolution((idx, "expand3"), s1, w3 * a, 3, 3, pad_same=True, mode=1)
             s1.free()
             nxt = _concat_channels(ctx, e1, e3)
+        elif kind == "gap" and fused and 1 < t.width <= 33 and 1 < t.height <= 33:
+            # the sum over a plane as two sums of rotations of one ciphertext: along the rows, then along the columns
+            # (one decomposition and one division by P each; all channels of a ciphertext at once), then the mean's
+            # factor, and what the previous layers left, as one scalar multiplication and its division
+            from .hisa import CipherTensor
+            hw = t.height * t.width
+            cur, own = list(t.cts), False
+            for count, stride in ((t.width, t.w_stride), (t.height, t.h_stride)):
+                amounts = [k * stride for k in range(count)]
+                if make_keys:
+                    ctx.gen_rot_keys(amounts[1:])
+                summed = ctx.rot_left_sum_batch([cur] * count, amounts)
+                if own:
+                    for ct in cur:
+                        ct.free()
+                cur, own = summed, True
+            for ct in cur:
+                ctx.mul_scalar_assign(ct, pending / hw, float(ctx.primes[ct.limbs - 1]))
+            ctx.rescale_batch(cur)
+            pending = 1.0
+            nxt = CipherTensor(ctx, cur, t.batch, t.channels, 1, 1, 1, 1, t.offset, 0, t.c_inner, t.c_stride)
         elif kind == "gap" and t.height == t.width and t.height > 1 and t.height & (t.height - 1) == 0:
             # a square plane with a power-of-two side: halve it by 2x2 sums down to one element per channel (three
             # rotations sharing a decomposition per halving, all channels of a ciphertext at once), then the mean's
