@@ -1407,8 +1407,11 @@ bool fused_key_switch_available(const hisa_ctx* ctx) { return ctx->tabs.fp_ok &&
 // The key-switch accumulators -- before the division by P -- of n_steps rotations of B ciphertexts (cts: [B][2][l][N],
 // ct_bs words apart): one decomposition + ModUp of c1, then per rotation the inner product with its key, gathered
 // through its automorphism.  acc: [n_steps][B][2][l + K][N].  Every amount must be a real rotation with its key present.
+// fold_c0: the first accumulator also takes P * sigma(c0) on the limbs of q, so that the rotated ciphertext is the
+// ModDown of the accumulators alone (exactly: P sigma(c0) leaves the special limbs, and with them the conversion, as
+// they are, and (x + P c) P^-1 = x P^-1 + c).
 int rotation_accumulators_fp(hisa_ctx* ctx, const u64* cts, u64 ct_bs, size_t B, int l, const int32_t* steps, int n_steps,
-                             u64* acc) {
+                             u64* acc, bool fold_c0) {
     if (!fused_key_switch_available(ctx)) return fail(ctx, HISA_ERR_ARG, "no fused key-switch path for these parameters");
     const size_t n = ctx->N;
     const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total, ext_limbs = l + K;
@@ -1429,7 +1432,8 @@ int rotation_accumulators_fp(hisa_ctx* ctx, const u64* cts, u64 ct_bs, size_t B,
         IpSteps st = {};
         for (int k = 0; k < cnt; k++) { st.key[k] = ctx->keys.find(gs[g0 + k])->second.data; st.galois[k] = (uint32_t)gs[g0 + k]; }
         HIP_TRY(ctx, launch_inner_product_steps_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, st, cnt, total,
-                                                   c1, ct_bs, acc + (u64)g0 * B * acc_bs, acc_bs, B, (int)ctx->log_n, ctx->stream));
+                                                   c1, ct_bs, acc + (u64)g0 * B * acc_bs, acc_bs, B, (int)ctx->log_n, ctx->stream,
+                                                   fold_c0 ? cts : nullptr, ctx->d_pmod));
     }
     return HISA_OK;
 }

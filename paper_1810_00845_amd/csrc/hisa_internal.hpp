@@ -191,7 +191,7 @@ PolyMap identity_map(int limbs);
 // pieces of the fused fp64 key switch for sums that are formed before the division by P (hisa_api.hip)
 bool fused_key_switch_available(const hisa_ctx* ctx);
 int rotation_accumulators_fp(hisa_ctx* ctx, const u64* cts, u64 ct_bs, size_t B, int l, const int32_t* steps, int n_steps,
-                             u64* acc);
+                             u64* acc, bool fold_c0 = false);
 // out[b] = plain[b] + sum_s rotLeft(rot[s * Bn + b], steps[s]) with one division by P per output: rot holds
 // n_steps * Bn ciphertexts [2][l][N], ct_bs words apart, rotation-major; every step rotates (its key is present);
 // plain ([Bn] ciphertexts, plain_bs apart) may be null; out [Bn][2][l][N].  shared_input: rot holds Bn ciphertexts and
@@ -303,13 +303,16 @@ hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 e
                                    int gather_ext, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st);
 // The same for n_steps rotations of the same n_batch ciphertexts (extended digits computed once from the unrotated
 // polynomial): rotation s uses keys[s] and gathers through galois[s]; acc entries are ordered rotation-major.
+// c0_src (with pmod[i] = P mod q_i): the b accumulator also takes P * sigma_s(c0) on the limbs of q, c0 read at
+// c0_src + b * own_bs like the own-digit limbs.
 struct IpSteps {
     const u64* key[FP_MAX_STEPS];
     uint32_t galois[FP_MAX_STEPS];
 };
 hipError_t launch_inner_product_steps_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
                                          int alpha, const IpSteps& steps, int n_steps, int total, const u64* own_src,
-                                         u64 own_bs, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st);
+                                         u64 own_bs, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st,
+                                         const u64* c0_src = nullptr, const u64* pmod = nullptr);
 
 // The sum over n_steps rotations of different ciphertexts: ext / own_src entry s * n_batch + b is term s of output b
 // (digits from the unrotated polynomial); acc[b] = sum_s sum_j sigma_s(e_j) * key_s[j] on the l + K limbs.

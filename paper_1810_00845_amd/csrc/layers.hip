@@ -1474,15 +1474,19 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
     BatchIn bi;
     int rc = gather_batch(ctx, (const hisa_ct* const*)src, nct, &bi);
     const u64 acc_bs = (u64)2 * le * n, lw = (u64)l * n;
+    // scalar weights: sigma(c0) enters the first accumulators times P (rotation_accumulators_fp), so the weighted sum
+    // of the accumulators is all there is; plaintext weights keep sigma(c0) apart (it rides along in their one pass
+    // over the plaintexts, on l limbs instead of l + K)
+    const bool fold_c0 = !plain;
     Temp acc(ctx, S * nct * acc_bs * sizeof(u64));      // [S][nct][2][l + K][N]
-    Temp r0(ctx, S * nct * lw * sizeof(u64));           // sigma(c0): [S][nct][l][N]
+    Temp r0(ctx, (fold_c0 ? 1 : S * nct * lw) * sizeof(u64));   // sigma(c0): [S][nct][l][N]
     Temp E(ctx, n_out * acc_bs * sizeof(u64)), Q0(ctx, n_out * lw * sizeof(u64)), Z(ctx, n_out * 2 * lw * sizeof(u64));
     std::vector<hisa_ct*> outs(n_out, nullptr);
     if (rc == HISA_OK && !(acc.ok() && r0.ok() && E.ok() && Q0.ok() && Z.ok())) rc = HISA_ERR_OOM;
     std::vector<int32_t> rot_steps;
     for (int t : ts.rot) rot_steps.push_back(plan.steps[t]);
-    if (rc == HISA_OK) rc = rotation_accumulators_fp(ctx, bi.base, bi.stride, nct, (int)l, rot_steps.data(), (int)S, acc.u());
-    {   // sigma(c0) for every rotated tap, as many taps per launch as the grid allows
+    if (rc == HISA_OK) rc = rotation_accumulators_fp(ctx, bi.base, bi.stride, nct, (int)l, rot_steps.data(), (int)S, acc.u(), fold_c0);
+    if (!fold_c0) {   // sigma(c0) for every rotated tap, as many taps per launch as the grid allows
         const size_t per_launch = std::max<size_t>(1, std::min<size_t>(GALOIS_TAB_MAX, 65535 / nct));
         for (size_t k0 = 0; k0 < S && rc == HISA_OK; k0 += per_launch) {
             const size_t cnt = std::min(per_launch, S - k0);
@@ -1513,13 +1517,6 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
         }
         e = shared_mac(ctx, ma, cw.dw, plain ? cw.pts->u() : nullptr, le, (int)B);
         ma.x2 = nullptr; ma.out2 = nullptr;
-        // Q0: sigma(c0) times the same weights on the l limbs
-        if (e == hipSuccess && !plain) {
-            ma.l = (int)l; ma.ct_words = lw; ma.polys = 1; ma.lq = 0; ma.gap = 0;
-            for (size_t k = 0; k < S; k++) ma.tap_base[k] = r0.u() + k * nct * lw;
-            ma.out = Q0.u();
-            e = shared_mac(ctx, ma, cw.dw, plain ? cw.pts->u() : nullptr, le, (int)B);
-        }
         // Z: the unrotated taps
         if (e == hipSuccess) {
             if (ts.zero.empty()) {
@@ -1533,7 +1530,7 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
                 e = shared_mac(ctx, ma, cw.dw_zero, plain ? cw.pts_zero->u() : nullptr, l, (int)B);
             }
         }
-        if (e == hipSuccess)   // Z0 += Q0
+        if (e == hipSuccess && plain)   // Z0 += Q0
             e = launch_addsub(ctx->d_primes, Z.u(), Q0.u(), Z.u(), OP_ADD, (int)l, 1, 1, n_out, 2 * lw, lw, 2 * lw, (int)ctx->log_n,
                               ctx->stream);
         if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));

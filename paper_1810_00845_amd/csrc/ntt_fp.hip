@@ -763,7 +763,8 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime*
 __global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs,
                                                                         int digits, int l, int K, int L, int alpha, IpSteps steps,
                                                                         int total, const u64* own_src, u64 own_bs, u64* acc,
-                                                                        u64 acc_bs, u64 n_batch, int log_n) {
+                                                                        u64 acc_bs, u64 n_batch, const u64* c0_src,
+                                                                        const u64* pmod, int log_n) {
     const u64 n = (u64)1 << log_n;
     const uint32_t j = blockIdx.x * IPF_NT + threadIdx.x;
     const int x = blockIdx.y, s = blockIdx.z;
@@ -781,6 +782,10 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const Fp
             ka[d] = fp_from_u64(key[(((u64)d * 2 + 1) * total + prime) * n + j]);
         }
     }
+    // c0_src: the first accumulator also takes P * sigma_s(c0) on the limbs of q (what ModDown turns back into
+    // sigma_s(c0): the rotated ciphertext is then the ModDown of the accumulators alone)
+    const bool fold = c0_src != nullptr && x < l;
+    const double pm = fold ? fp_from_u64(pmod[prime]) : 0.0;
     for (u64 b = 0; b < n_batch; b++) {
         double sb = 0.0, sa = 0.0;
 #pragma unroll
@@ -793,6 +798,7 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const Fp
                 sa += fp_mulmod(e, ka[d], p, pinv);
             }
         }
+        if (fold) sb = fp_norm(sb, p, pinv) + fp_mulmod(fp_from_u64(c0_src[b * own_bs + (u64)x * n + jsrc]), pm, p, pinv);
         u64* dst = acc + ((u64)s * n_batch + b) * acc_bs;
         dst[(u64)x * n + j] = fp_canonical(sb, p, pinv);
         dst[((u64)ext_limbs + x) * n + j] = fp_canonical(sa, p, pinv);
@@ -893,16 +899,17 @@ hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const u64* ext, u
 
 hipError_t launch_inner_product_steps_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
                                          int alpha, const IpSteps& steps, int n_steps, int total, const u64* own_src,
-                                         u64 own_bs, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st) {
+                                         u64 own_bs, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st,
+                                         const u64* c0_src, const u64* pmod) {
     DRY_RUN_RETURN();
     if (digits > IPF_MAXD || n_steps < 1 || n_steps > FP_MAX_STEPS) return hipErrorInvalidValue;
-    if (!fprimes || !ext || !own_src || !acc || n_batch == 0) return hipErrorInvalidValue;
+    if (!fprimes || !ext || !own_src || !acc || n_batch == 0 || (c0_src && !pmod)) return hipErrorInvalidValue;
     for (int s = 0; s < n_steps; s++)
         if (!steps.key[s] || steps.galois[s] == 0) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / IPF_NT, l + K, n_steps);
     ProfScope prof__("inner_product_steps_fp_kernel", st);
     hipLaunchKernelGGL(inner_product_steps_fp_kernel, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha,
-                       steps, total, own_src, own_bs, acc, acc_bs, n_batch, log_n);
+                       steps, total, own_src, own_bs, acc, acc_bs, n_batch, c0_src, pmod, log_n);
     return hipGetLastError();
 }
 
