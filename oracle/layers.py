@@ -162,7 +162,7 @@ class SharedModDown:
         return out
 
 
-def conv2d(o: Oracle, t: OTensor, w, stride=1, pad_same=False, mode=CONV_SCALAR, shared_moddown=False):
+def conv2d(o: Oracle, t: OTensor, w, stride=1, pad_same=False, mode=CONV_SCALAR, shared_moddown=False, fused_rescale=False):
     """Algorithm 1.  w[FH][FW][IC][OC].  Returns (output tensor, dict of the integers used)."""
     fh, fw, ic_n, oc_n = w.shape
     assert ic_n == t.channels
@@ -192,12 +192,14 @@ def conv2d(o: Oracle, t: OTensor, w, stride=1, pad_same=False, mode=CONV_SCALAR,
         ints.update(w_int=w_int, w_scale=w_scale)
         if mode == CONV_MASKED:
             ints.update(pt_coeffs=o.encode_coeffs(valid, MASK_SCALE), pt_scale=MASK_SCALE)
-    out = conv2d_fixed(o, t, ints, oc_n, fh, fw, stride, pad_same, mode, shared_moddown)
+    out = conv2d_fixed(o, t, ints, oc_n, fh, fw, stride, pad_same, mode, shared_moddown, fused_rescale)
     return out, ints
 
 
-def conv2d_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, mode, shared_moddown=False):
-    """shared_moddown: the sum over (input channel, tap) goes through SharedModDown."""
+def conv2d_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, mode, shared_moddown=False, fused_rescale=False):
+    """shared_moddown: the sum over (input channel, tap) goes through SharedModDown.  fused_rescale (with
+    shared_moddown, scalar weights without the masking multiply): that sum's division by P and the divScalar are one
+    division."""
     l = t.cts[0].limbs
     ph, pw = (fh // 2, fw // 2) if pad_same else (0, 0)
     if pad_same:
@@ -229,7 +231,11 @@ def conv2d_fixed(o: Oracle, t: OTensor, ints, oc_n, fh, fw, stride, pad_same, mo
                 else:
                     terms = [(ic, amount(fy, fx), int(ints["w_int"][fy, fx, ic, oc]), None)
                              for ic in range(t.channels) for fy in range(fh) for fx in range(fw)]
-                    acc = shared.total(terms, t.cts[0].scale * ints["w_scale"])
+                    one = fused_rescale and mode == CONV_SCALAR
+                    acc = shared.total(terms, t.cts[0].scale * ints["w_scale"], rescale=one)
+                    if one:
+                        outs.append(acc)
+                        continue
                 if mode == CONV_MASKED:
                     acc = o.mul_plain(acc, mask_pt)
                 outs.append(o.div_scalar(acc, o.max_scalar_div(acc, float("inf"))))

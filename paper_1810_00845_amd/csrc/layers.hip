@@ -1503,7 +1503,12 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
         }
     }
     const double mac_scale = in->cts[0]->scale * (plain ? cw.pt_scale : cw.w_scale);
-    if (rc == HISA_OK) rc = alloc_ct_batch(ctx, n_out, 2, l, mac_scale, outs.data());
+    // scalar weights, no masking multiply in between: the division by P and the divScalar as one division
+    // (hisa_set_fused_rescale)
+    const bool one_division = ctx->fused_rescale && g->mode == HISA_CONV_SCALAR;
+    if (rc == HISA_OK)
+        rc = alloc_ct_batch(ctx, n_out, 2, one_division ? l - 1 : l, one_division ? mac_scale / (double)ctx->mod[l - 1] : mac_scale,
+                            outs.data());
     if (rc == HISA_OK) {
         hipError_t e;
         MacArgs ma = {};
@@ -1535,7 +1540,8 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
                               ctx->stream);
         if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));
     }
-    if (rc == HISA_OK) rc = moddown_add_fp(ctx, E.u(), n_out, (int)l, Z.u(), 2 * lw, 2, 0, outs[0]->data);
+    if (rc == HISA_OK && one_division) rc = moddown_rescale_fp(ctx, E.u(), n_out, (int)l, Z.u(), 2 * lw, 2, outs[0]->data);
+    else if (rc == HISA_OK) rc = moddown_add_fp(ctx, E.u(), n_out, (int)l, Z.u(), 2 * lw, 2, 0, outs[0]->data);
     if (rc == HISA_OK && g->mode == HISA_CONV_MASKED) {
         hipError_t e = launch_mul_plain(ctx->d_primes, outs[0]->data, cw.mask->u(), outs[0]->data, (int)l, 2, n_out, 2 * lw, 2 * lw,
                                         (int)ctx->log_n, ctx->stream);
@@ -1544,7 +1550,8 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
     }
     dev_release(ctx, bi.tmp);
     free_handles(ctx, wrapped);
-    if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
+    if (rc == HISA_OK && !one_division) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
+    if (rc == HISA_OK && one_division && t_analysis) t_analysis->c.rescale += n_out;
     if (rc != HISA_OK) {
         free_handles(ctx, outs);
         return rc;

@@ -671,6 +671,20 @@ def test_shared_moddown_convolutions_bit_exact():
         exact = g.conv2d(gt, w, 3, 3, mode=mode, **kw)              # the term-by-term schedule: other bits, same values
         assert not np.array_equal(g.ct_export(exact.cts[0]), g.ct_export(gfloat.cts[0]))
         assert np.abs(g.tensor_decrypt(exact) - g.tensor_decrypt(gfloat)).max() <= 1e-6
+    # scalar weights under hisa_set_fused_rescale: the division by P and the divScalar as one division; the masked
+    # mode (a multiplication in between) keeps its two steps
+    g.set_fused_rescale(True)
+    w = synth.conv_weights(76, 3, 3, 4, 3)
+    oout, ints = layers.conv2d(o, ot, w, mode=layers.CONV_SCALAR, shared_moddown=True, fused_rescale=True, pad_same=True)
+    gout = g.conv2d_fixed(gt, ints["w_int"], ints["w_scale"], None, 1.0, 3, 3, 3, mode=layers.CONV_SCALAR, shared_moddown=True,
+                          pad_same=True)
+    same_tensor(g, o, gout, oout)
+    assert gout.cts[0].limbs == 2 and np.abs(g.tensor_decrypt(gout) - plain_net.conv2d(x, w, pad_same=True)).max() <= 1e-3
+    oout, ints = layers.conv2d(o, ot, w, mode=layers.CONV_MASKED, shared_moddown=True, pad_same=True)
+    gout = g.conv2d_fixed(gt, ints["w_int"], ints["w_scale"], ints["pt_coeffs"], ints["pt_scale"], 3, 3, 3, mode=layers.CONV_MASKED,
+                          shared_moddown=True, pad_same=True)
+    same_tensor(g, o, gout, oout)
+    g.set_fused_rescale(False)
     # CHW-tiled: 5 -> 6 channels in blocks of 4, 64 slots apart (copy behind the blocks)
     xc = synth.image(73, 5, 4, 4)[None]
     wc = synth.conv_weights(74, 3, 3, 5, 6)
