@@ -205,7 +205,8 @@ int hisa_set_merge_doublings(hisa_ctx* ctx, uint32_t max_doublings);
  * rotated folded in, times P) are divided by q_{l-1} P in one base conversion whose sources are the limb of q_{l-1} and
  * the special limbs.  One inverse and l - 1 forward transforms per polynomial instead of two rounds of them; the result
  * differs from the two-step one by the rounding of the conversion (a few units per coefficient), so ciphertext bits
- * differ.  Applies to the CHW-tiled convolutions that rotate sums; 0 (the default) keeps the two steps.  Needs what
+ * differ.  Applies to the CHW-tiled convolutions that rotate sums, the shared_moddown convolution with scalar weights and the
+ * degree-2 activation; 0 (the default) keeps the two steps.  Needs what
  * hisa_rot_left_sum_batch needs (HISA_ERR_ARG otherwise).  A setting of the context, like hisa_set_merge_doublings. */
 int hisa_set_fused_rescale(hisa_ctx* ctx, uint32_t on);
 int hisa_relinearize_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n);
