@@ -33,6 +33,9 @@ struct MacArgs {
     // in the same pass (term (t, b, ic) at x2 + t * x2_tap_words + (b * IC + ic) * x2_words), summed into
     // out2[b * OC + oc] (x2_words apart)
     const u64* x2; u64 x2_tap_words, x2_words; u64* out2;
+    // plain, optional: the w_count plaintexts in the limb-major form of pack_plain_kernel (w_count = 0: [plaintext][limb]
+    // rows of eight-byte words; w_packed bit 0: limb 0 has six-byte residues, bit 1: the limbs after it have)
+    u64 w_count; int w_packed;
 };
 
 __device__ __forceinline__ int mac_prime(const MacArgs& g, int limb) { return (g.lq && limb >= g.lq) ? limb + g.gap : limb; }
@@ -296,13 +299,20 @@ __global__ __launch_bounds__(256) void scalar_mac_mfma_kernel(const FpPrime* fpr
 #define ICP 2
 // WITH_X2: the optional second input is present (a separate instantiation, so that the common form keeps its
 // straight-line loads)
-template <bool WITH_X2, int OCP>
-__global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes, MacArgs g, int log_n) {
+// PACKED: the plaintexts are stored limb-major -- the rows that a group of outputs reads for one term lie side by
+// side -- and with six bytes per residue where the prime is below 2^48 (the row layout of pack_plain_kernel), a quarter
+// less of the bytes that bound this kernel
+// FORM of the plaintext rows this block reads: 0 as encoded, 1 limb-major with eight-byte residues, 2 limb-major with
+// six-byte residues (the form is a template argument so that the loads of a term stay one straight line)
+template <bool WITH_X2, int OCP, int FORM>
+__device__ __forceinline__ void plain_mac_fp_body(const FpPrime* fprimes, const MacArgs& g, int log_n) {
     const u64 n = (u64)1 << log_n;
     const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
-    const int limb = blockIdx.y;
+    // the groups of outputs of one limb are neighbours in launch order (and land on the same XCD: the number of
+    // blocks along x is a multiple of 8 from N = 2^11 on), so the ciphertext words they all read stay in that L2
+    const int limb = blockIdx.z;
     const int ocblocks = (g.OC + OCP - 1) / OCP;
-    const int b = blockIdx.z / ocblocks, oc0 = (blockIdx.z % ocblocks) * OCP;
+    const int b = blockIdx.y / ocblocks, oc0 = (blockIdx.y % ocblocks) * OCP;
     const mac_cdouble_ptr fp = (mac_cdouble_ptr)(unsigned long long)&fprimes[mac_prime(g, limb)].p;
     const double p = fp[0], pinv = fp[1];
     const u64 ln = (u64)g.l * n, wl = g.w_words ? g.w_words : ln;
@@ -312,9 +322,15 @@ __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes
 #pragma unroll
     for (int o = 0; o < OCP; o++) a0[o] = a1[o] = a2[o] = 0.0;
     int pending = 0;
+    // six-byte rows: per 64 residues their 64 low words, then their 64 high halfwords (384 bytes that one wave reads)
+    const u64 lo_off = (j >> 6) * 384 + (j & 63) * 4, hi_off = (j >> 6) * 384 + 256 + (j & 63) * 2;
     for (int t = 0; t < g.n_taps; t++) {
         const u64* x = g.tap_base[t] + (u64)b * g.IC * g.ct_words + (u64)limb * n + j;
         const u64* w = g.w + ((u64)t * g.IC * g.w_stride_t + (u64)oc0 * g.w_stride_oc) * wl + (u64)limb * n + j;
+        // limb-major forms: the limb's rows, in bytes
+        const u64 b0 = (g.w_packed & 1) ? 6 : 8, b1 = (g.w_packed & 2) ? 6 : 8, rb = (FORM == 2 ? 6 : 8) * n;
+        const char* wp = (const char*)g.w + (limb ? b0 + (u64)(limb - 1) * b1 : 0) * n * g.w_count +
+                         ((u64)t * g.IC * g.w_stride_t + (u64)oc0 * g.w_stride_oc) * rb;
         const u64* x2 = third ? g.x2 + (u64)t * g.x2_tap_words + (u64)b * g.IC * g.x2_words + (u64)limb * n + j : nullptr;
         for (int ic0 = 0; ic0 < g.IC; ic0 += ICP) {
             u64 xb[ICP], xa[ICP], xc[ICP], wv[ICP][OCP];
@@ -327,7 +343,10 @@ __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes
 #pragma unroll
                 for (int o = 0; o < OCP; o++) {
                     const int oo = oc0 + o < g.OC ? o : 0;
-                    wv[u][o] = w[((u64)ic * g.w_stride_t + (u64)oo * g.w_stride_oc) * wl];
+                    const char* row = wp + ((u64)ic * g.w_stride_t + (u64)oo * g.w_stride_oc) * rb;
+                    if (FORM == 2) wv[u][o] = (u64)*(const uint32_t*)(row + lo_off) | ((u64)*(const uint16_t*)(row + hi_off) << 32);
+                    else if (FORM == 1) wv[u][o] = ((const u64*)row)[j];
+                    else wv[u][o] = w[((u64)ic * g.w_stride_t + (u64)oo * g.w_stride_oc) * wl];
                 }
             }
 #pragma unroll
@@ -363,6 +382,13 @@ __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes
             if (third) g.out2[((u64)b * g.OC + oc0 + o) * g.x2_words + (u64)limb * n + j] = fp_canonical(a2[o], p, pinv);
         }
     }
+}
+
+template <bool WITH_X2, int OCP, bool PACKED = false>
+__global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes, MacArgs g, int log_n) {
+    if (!PACKED) plain_mac_fp_body<WITH_X2, OCP, 0>(fprimes, g, log_n);
+    else if (g.w_packed >> (blockIdx.z ? 1 : 0) & 1) plain_mac_fp_body<false, OCP, 2>(fprimes, g, log_n);
+    else plain_mac_fp_body<false, OCP, 1>(fprimes, g, log_n);
 }
 
 // analysis mode: a multiply-accumulate launch stands for one term per (image, output, tap, input)
@@ -422,16 +448,43 @@ static hipError_t launch_scalar_mac_mfma(const FpPrime* fprimes, const MacArgs& 
     return hipErrorInvalidValue;
 }
 
+// Plaintexts [cnt][l][N] of eight-byte residues -> the limb-major form [l][cnt] of rows of N residues: a packed row holds,
+// for every 64 residues, their 64 low 32-bit words followed by their 64 high 16-bit words (384 bytes); an unpacked one
+// is as it was (packed: bit 0 limb 0, bit 1 the rest).
+// One launch converts the plaintexts first .. first + gridDim.z - 1.
+__global__ __launch_bounds__(NT) void pack_plain_kernel(const u64* src, char* dst, int l, int packed, u64 cnt, u64 first, int log_n) {
+    const u64 n = (u64)1 << log_n;
+    const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
+    const int limb = blockIdx.y;
+    const u64 b0 = (packed & 1) ? 6 : 8, b1 = (packed & 2) ? 6 : 8, c = first + blockIdx.z;
+    const bool pk = packed >> (limb ? 1 : 0) & 1;
+    const u64 v = src[(c * l + limb) * n + j];
+    char* row = dst + (limb ? b0 + (u64)(limb - 1) * b1 : 0) * n * cnt + c * (pk ? 6 : 8) * n;
+    if (pk) {
+        *(uint32_t*)(row + (j >> 6) * 384 + (j & 63) * 4) = (uint32_t)v;
+        *(uint16_t*)(row + (j >> 6) * 384 + 256 + (j & 63) * 2) = (uint16_t)(v >> 32);
+    } else {
+        ((u64*)row)[j] = v;
+    }
+}
+
 static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
     count_mac(g, batch, true);
     DRY_RUN_RETURN();
     if (!fprimes || !g.w || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || !mac_shape_ok(g, log_n)) return hipErrorInvalidValue;
     if (g.w_words && (u64)g.l * ((u64)1 << log_n) > g.w_words) return hipErrorInvalidValue;   // plaintexts shorter than the limbs walked
     if (g.x2 && (!g.out2 || g.lq <= 0 || g.lq > g.l || g.x2_words == 0)) return hipErrorInvalidValue;
+    if (g.w_count) {   // limb-major plaintexts: of exactly the limbs walked, on the primes q_0.., no second input
+        const u64 last = ((u64)g.n_taps * g.IC - 1) * g.w_stride_t + (u64)(g.OC - 1) * g.w_stride_oc;
+        if (g.w_words || g.x2 || g.lq || (g.w_packed & ~3) || last >= g.w_count) return hipErrorInvalidValue;
+    }
     const int ocp = g.OC >= 8 ? 8 : 4;
-    dim3 grid((1u << log_n) / NT, g.l, batch * ((g.OC + ocp - 1) / ocp));
+    if ((u64)batch * ((g.OC + ocp - 1) / ocp) > 65535) return hipErrorInvalidValue;
+    dim3 grid((1u << log_n) / NT, batch * ((g.OC + ocp - 1) / ocp), g.l);
     ProfScope prof__("plain_mac_fp_kernel", st);
-    if (g.x2 && ocp == 8) hipLaunchKernelGGL((plain_mac_fp_kernel<true, 8>), grid, dim3(NT), 0, st, fprimes, g, log_n);
+    if (g.w_count && ocp == 8) hipLaunchKernelGGL((plain_mac_fp_kernel<false, 8, true>), grid, dim3(NT), 0, st, fprimes, g, log_n);
+    else if (g.w_count) hipLaunchKernelGGL((plain_mac_fp_kernel<false, 4, true>), grid, dim3(NT), 0, st, fprimes, g, log_n);
+    else if (g.x2 && ocp == 8) hipLaunchKernelGGL((plain_mac_fp_kernel<true, 8>), grid, dim3(NT), 0, st, fprimes, g, log_n);
     else if (g.x2) hipLaunchKernelGGL((plain_mac_fp_kernel<true, 4>), grid, dim3(NT), 0, st, fprimes, g, log_n);
     else if (ocp == 8) hipLaunchKernelGGL((plain_mac_fp_kernel<false, 8>), grid, dim3(NT), 0, st, fprimes, g, log_n);
     else hipLaunchKernelGGL((plain_mac_fp_kernel<false, 4>), grid, dim3(NT), 0, st, fprimes, g, log_n);
@@ -914,7 +967,8 @@ static int upload_weight_residues(hisa_ctx* ctx, const int64_t* w_int, uint32_t 
 
 // dw: SCALAR/MASKED weights (null for PLAIN); d_pts: MASKED [l][N], PLAIN [T][OC][l][N]
 static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
-                    DevWeights* dw, double w_scale, const u64* d_pts, double pt_scale, hisa_tensor* out) {
+                    DevWeights* dw, double w_scale, const u64* d_pts, double pt_scale, hisa_tensor* out, u64 pt_count = 0,
+                    int pt_packed = 0) {
     // in units of ciphertexts: IC inputs and OCm outputs per image (HW-tiling: the channels themselves)
     const uint32_t B = in->batch, ci = t_ci(in), IC = (uint32_t)t_per(in), OCm = (OC + ci - 1) / ci, l = in->cts[0]->limbs;
     const size_t nct = (size_t)B * IC, n = ctx->N;
@@ -970,7 +1024,7 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
         ma.out = outs[0]->data;
         hipError_t e;
         if (g->mode == HISA_CONV_PLAIN) {
-            ma.w = d_pts; ma.w_stride_t = OCm; ma.w_stride_oc = 1;
+            ma.w = d_pts; ma.w_stride_t = OCm; ma.w_stride_oc = 1; ma.w_count = pt_count; ma.w_packed = pt_packed;
             if (ctx->tabs.fp_ok) e = launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
             else e = launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
         } else {
@@ -1017,7 +1071,7 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
 // HISA_CHW_ROTATE_SUMS_TAPS exchanges the roles: the inputs are rotated by the d blocks, the sums (one per filter tap,
 // the unrotated tap first) by the taps; d_pts: [c_inner][IC][taps * OCm][l][N].
 static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
-                         const u64* d_pts, double pt_scale, hisa_tensor* out) {
+                         const u64* d_pts, double pt_scale, hisa_tensor* out, u64 pt_count = 0, int pt_packed = 0) {
     const uint32_t B = in->batch, ci = t_ci(in), IC = (uint32_t)t_per(in), OCm = (OC + ci - 1) / ci, l = in->cts[0]->limbs;
     const size_t nct = (size_t)B * IC, n = ctx->N;
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
@@ -1079,7 +1133,7 @@ static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_g
     if (rc == HISA_OK) {
         ma.n_taps = n_taps; ma.IC = (int)IC; ma.OC = (int)sums; ma.l = (int)l; ma.ct_words = ctw;
         ma.out = y.u();
-        ma.w = d_pts; ma.w_stride_t = sums; ma.w_stride_oc = 1;
+        ma.w = d_pts; ma.w_stride_t = sums; ma.w_stride_oc = 1; ma.w_count = pt_count; ma.w_packed = pt_packed;
         hipError_t e = launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
         if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));
     }
@@ -1117,6 +1171,8 @@ struct ConvWeights {
     DevWeights* dw_zero = nullptr;
     Temp* pts_zero = nullptr;
     Temp* mask = nullptr;
+    u64 pt_count = 0;           // PLAIN, converted by pack_plain_weights: plaintexts in the limb-major form (0: as encoded)
+    int pt_packed = 0;          // which limbs have six-byte residues (MacArgs::w_packed)
     ~ConvWeights() { delete dw; delete pts; delete dw_zero; delete pts_zero; delete mask; }
 };
 
@@ -1565,10 +1621,11 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
 
 static int conv_dispatch(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
                          const ConvWeights& cw, hisa_tensor* out) {
-    if (plan.rotate_sums) return conv_run_sums(ctx, in, g, plan, OC, cw.pts ? cw.pts->u() : nullptr, cw.pt_scale, out);
+    if (plan.rotate_sums)
+        return conv_run_sums(ctx, in, g, plan, OC, cw.pts ? cw.pts->u() : nullptr, cw.pt_scale, out, cw.pt_count, cw.pt_packed);
     if (cw.shared) return conv_run_shared(ctx, in, g, plan, OC, cw, out);
     const u64* d_pts = g->mode == HISA_CONV_MASKED ? (cw.mask ? cw.mask->u() : nullptr) : (cw.pts ? cw.pts->u() : nullptr);
-    return conv_run(ctx, in, g, plan, OC, cw.dw, cw.w_scale, d_pts, cw.pt_scale, out);
+    return conv_run(ctx, in, g, plan, OC, cw.dw, cw.w_scale, d_pts, cw.pt_scale, out, cw.pt_count, cw.pt_packed);
 }
 
 extern "C" int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* w_int, double w_scale,
@@ -1594,6 +1651,35 @@ extern "C" int hisa_conv2d(hisa_ctx* ctx, const hisa_tensor* in, const double* w
     return conv_dispatch(ctx, in, geom, plan, OC, cw, out);
 }
 
+// The plaintexts of a plan are written once and read at every application, and those reads bound the multiply-accumulate
+// launch: they are kept limb-major and, where the primes allow (below 2^48), with six bytes per residue.  (A direct
+// call reads its plaintexts once either way, so it keeps the words the encoder wrote.)
+static int pack_plain_weights(hisa_ctx* ctx, ConvWeights& cw, uint32_t l) {
+    if (!ctx->tabs.fp_ok || !cw.pts || cw.shared || cw.pt_count || l < 1) return HISA_OK;
+    const u64 lim = (u64)1 << 48, n = ctx->N, words = (u64)l * n;
+    int packed = ctx->mod[0] < lim ? 1 : 0;
+    bool rest = l > 1;
+    for (uint32_t k = 1; k < l; k++) rest = rest && ctx->mod[k] < lim;
+    if (rest) packed |= 2;
+    if (cw.pts->blk->bytes % (words * sizeof(u64))) return HISA_OK;
+    const u64 cnt = cw.pts->blk->bytes / (words * sizeof(u64));
+    const u64 bytes = (((packed & 1) ? 6 : 8) + (u64)(l - 1) * ((packed & 2) ? 6 : 8)) * n * cnt;
+    Temp* dst = new Temp(ctx, bytes);
+    if (!dst->ok()) { delete dst; return HISA_ERR_OOM; }
+    for (u64 c0 = 0; c0 < cnt; c0 += 32768) {
+        const u64 c = std::min<u64>(32768, cnt - c0);
+        hipLaunchKernelGGL(pack_plain_kernel, dim3((unsigned)(n / NT), l, (unsigned)c), dim3(NT), 0, ctx->stream,
+                           cw.pts->u(), dst->as<char>(), (int)l, packed, cnt, c0, (int)ctx->log_n);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) { delete dst; return fail(ctx, HISA_ERR_HIP, "plaintext packing: %s", hipGetErrorString(e)); }
+    }
+    delete cw.pts;     // stream-ordered: the pool may hand the block out again only to later work on this stream
+    cw.pts = dst;
+    cw.pt_count = cnt;
+    cw.pt_packed = packed;
+    return HISA_OK;
+}
+
 // A convolution whose weights were converted ahead of time for one input layout and level.
 #define HISA_MAGIC_CONVPLAN 0x43565031u
 struct hisa_conv_plan {
@@ -1613,7 +1699,8 @@ extern "C" int hisa_conv2d_prepare(hisa_ctx* ctx, const hisa_tensor* like, const
     hisa_conv_plan* p = new hisa_conv_plan{HISA_MAGIC_CONVPLAN, *geom, OC, like->channels, like->height, like->width,
                                            like->h_stride, like->w_stride, like->offset, like->clean, like->cts[0]->limbs,
                                            t_ci(like), like->c_stride, {}};
-    const int rc = conv_build(ctx, like, w, OC, geom, plan, p->cw);
+    int rc = conv_build(ctx, like, w, OC, geom, plan, p->cw);
+    if (rc == HISA_OK && geom->mode == HISA_CONV_PLAIN) rc = pack_plain_weights(ctx, p->cw, like->cts[0]->limbs);
     if (rc != HISA_OK) { delete p; return rc; }
     *plan_out = p;
     return HISA_OK;

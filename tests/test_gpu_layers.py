@@ -421,6 +421,39 @@ def test_chw_conv_bit_exact(log_n, c_stride):
     g.close()
 
 
+@pytest.mark.parametrize("q_bits", [[47, 40, 40, 40], [50, 40, 40, 40], [45, 49, 49, 49], [50, 49, 49, 49]])
+def test_plan_plaintexts_in_six_bytes_give_the_same_bits(q_bits):
+    """A plan keeps its plaintexts with six bytes per residue on the limbs whose primes are below 2^48 (all of them,
+    all but the first, the first only, none): its outputs equal those of the direct call, which multiplies by the
+    encoder's eight-byte words, bit for bit -- HW-tiled plaintext weights and the three CHW schedules, at the top level
+    and one below (a plan is made for its level) -- and both are within 1e-3 of the plaintext convolution."""
+    from oracle import layers
+    from paper_1810_00845_amd import hisa, synth
+    g = hisa.Context(12, q_bits, 2, 50, 23)
+    g.keygen()
+    x = synth.image(43, 9, 4, 4)[None]
+    w = synth.conv_weights(44, 3, 3, 9, 10)                  # 10 outputs: groups of eight and a ragged group
+    ref = plain_net.conv2d(x, w, pad_same=True)
+    hw = g.tensor_encrypt(x, 2.0 ** 40, 4, h_stride=6, offset=7)
+    chw = g.tensor_encrypt(x, 2.0 ** 40, 3, h_stride=6, offset=7, c_inner=4, c_stride=512)
+    steps = set(g.conv2d_rot_steps(hw, 3, 3, pad_same=True))
+    for sched in (hisa.CHW_ROTATE_INPUTS, hisa.CHW_ROTATE_SUMS, hisa.CHW_ROTATE_SUMS_TAPS):
+        steps |= set(g.conv2d_rot_steps(chw, 3, 3, pad_same=True, chw_schedule=sched))
+    g.gen_rot_keys(sorted(steps))
+    for t, kws in ((hw, [dict()]), (chw, [dict(chw_schedule=s) for s in (0, 1, 2)])):
+        for kw in kws:
+            direct = g.conv2d(t, w, 3, 3, pad_same=True, mode=layers.CONV_PLAIN, **kw)
+            plan = g.conv2d_prepare(t, w, 3, 3, pad_same=True, mode=layers.CONV_PLAIN, **kw)
+            for _ in range(2):                                # a plan is applied many times
+                planned = g.conv2d_apply(t, plan)
+                assert planned.meta() == direct.meta()
+                for ca, cb in zip(direct.cts, planned.cts):
+                    assert np.array_equal(g.ct_export(ca), g.ct_export(cb))
+            assert np.abs(g.tensor_decrypt(planned) - ref).max() <= 1e-3
+            g.conv_plan_free(plan)
+    g.close()
+
+
 @pytest.mark.parametrize("c_stride", [64, 512])
 def test_chw_conv_rotating_the_sums_bit_exact(c_stride):
     """The CHW-tiled convolution that reduces over the channel blocks after the multiplication, against the oracle
