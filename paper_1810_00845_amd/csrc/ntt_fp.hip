@@ -720,7 +720,9 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime*
                                                                   u64* acc, u64 acc_bs, u64 n_batch, int log_n) {
     const u64 n = (u64)1 << log_n;
     const uint32_t j = blockIdx.x * IPF_NT + threadIdx.x;
-    const int x = blockIdx.y;
+    // the limb is the slowest index of the launch: the blocks that share a limb's key rows (and sit on the same XCD,
+    // the number of blocks along x being a multiple of 8) run together and find them in that L2
+    const int x = blockIdx.z;
     const int ext_limbs = l + K;
     const int prime = x < l ? x : L + (x - l);
     const int own_digit = x < l ? x / alpha : -1;
@@ -730,7 +732,7 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime*
     const uint32_t jsrc = galois ? galois_src_fp(j, galois, log_n) : j;
     const uint32_t jext = gather_ext ? jsrc : j;
     const u64 per = (n_batch + IPF_ZSPLIT - 1) / IPF_ZSPLIT;
-    const u64 b0 = (u64)blockIdx.z * per;
+    const u64 b0 = (u64)blockIdx.y * per;
     const u64 b1 = b0 + per < n_batch ? b0 + per : n_batch;
     double kb[IPF_MAXD], ka[IPF_MAXD];
 #pragma unroll
@@ -767,7 +769,8 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const Fp
                                                                         const u64* pmod, int log_n) {
     const u64 n = (u64)1 << log_n;
     const uint32_t j = blockIdx.x * IPF_NT + threadIdx.x;
-    const int x = blockIdx.y, s = blockIdx.z;
+    // the rotations of a limb run together: they read the same extended digits (through different automorphisms)
+    const int x = blockIdx.z, s = blockIdx.y;
     const int ext_limbs = l + K;
     const int prime = x < l ? x : L + (x - l);
     const int own_digit = x < l ? x / alpha : -1;
@@ -820,8 +823,8 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_sum_fp_kernel(const FpPr
                                                                       int log_n) {
     const u64 n = (u64)1 << log_n;
     const uint32_t j = blockIdx.x * IPF_NT + threadIdx.x;
-    const int x = blockIdx.y;
-    const u64 b0 = (u64)blockIdx.z * IPS_BCH;
+    const int x = blockIdx.z;      // the groups of outputs of a limb run together: they read the same key rows
+    const u64 b0 = (u64)blockIdx.y * IPS_BCH;
     const int ext_limbs = l + K;
     const int prime = x < l ? x : L + (x - l);
     const int own_digit = x < l ? x / alpha : -1;
@@ -876,7 +879,7 @@ hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const u64* ext, u
                                        u64* acc, u64 acc_bs, u64 n_batch, int shared_input, int log_n, hipStream_t st) {
     DRY_RUN_RETURN();
     if (digits < 1 || digits > IPF_MAXD || n_steps < 1 || n_steps > FP_MAX_STEPS || l < 1 || K < 1 || alpha < 1) return hipErrorInvalidValue;
-    if (!fprimes || !ext || !own_src || !acc || n_batch == 0 || n_batch > 65535u * 4) return hipErrorInvalidValue;
+    if (!fprimes || !ext || !own_src || !acc || n_batch == 0 || n_batch > 65535u * 4 || l + K > 65535) return hipErrorInvalidValue;
     // an entry holds `digits` extended digits of l + K limbs; an accumulator two polynomials of l + K limbs; an own-digit
     // source the l limbs of the polynomial
     const u64 n = (u64)1 << log_n;
@@ -886,7 +889,7 @@ hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const u64* ext, u
     // sixteen outputs per block only where that still leaves a few thousand blocks (sixteen per compute unit)
     const u64 blocks16 = (u64)((1u << log_n) / IPF_NT) * (l + K) * ((n_batch + 15) / 16);
     const unsigned bch = (n_batch >= 32 && blocks16 >= 4096) ? 16 : 4;
-    dim3 grid((1u << log_n) / IPF_NT, l + K, (unsigned)((n_batch + bch - 1) / bch));
+    dim3 grid((1u << log_n) / IPF_NT, (unsigned)((n_batch + bch - 1) / bch), l + K);
     ProfScope prof__("inner_product_sum_fp_kernel", st);
     if (bch == 16)
         hipLaunchKernelGGL(inner_product_sum_fp_kernel<16>, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha,
@@ -906,7 +909,7 @@ hipError_t launch_inner_product_steps_fp(const FpPrime* fprimes, const u64* ext,
     if (!fprimes || !ext || !own_src || !acc || n_batch == 0 || (c0_src && !pmod)) return hipErrorInvalidValue;
     for (int s = 0; s < n_steps; s++)
         if (!steps.key[s] || steps.galois[s] == 0) return hipErrorInvalidValue;
-    dim3 grid((1u << log_n) / IPF_NT, l + K, n_steps);
+    dim3 grid((1u << log_n) / IPF_NT, n_steps, l + K);
     ProfScope prof__("inner_product_steps_fp_kernel", st);
     hipLaunchKernelGGL(inner_product_steps_fp_kernel, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha,
                        steps, total, own_src, own_bs, acc, acc_bs, n_batch, c0_src, pmod, log_n);
@@ -919,7 +922,7 @@ hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 e
     DRY_RUN_RETURN();
     if (digits > IPF_MAXD) return hipErrorInvalidValue;  // the caller falls back to the integer path
     if (!fprimes || !ext || !key || !own_src || !acc) return hipErrorInvalidValue;
-    dim3 grid((1u << log_n) / IPF_NT, l + K, IPF_ZSPLIT);
+    dim3 grid((1u << log_n) / IPF_NT, IPF_ZSPLIT, l + K);
     ProfScope prof__("inner_product_fp_kernel", st);
     hipLaunchKernelGGL(inner_product_fp_kernel, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha, key,
                        total, own_src, own_bs, galois, gather_ext, acc, acc_bs, n_batch, log_n);
