@@ -381,6 +381,14 @@ typedef struct hisa_conv_plan hisa_conv_plan;
 int hisa_conv2d_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t out_channels,
                         const hisa_conv_geom* geom, hisa_conv_plan** plan);
 int hisa_conv2d_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_plan* plan, hisa_tensor* out);
+/* Several convolutions of the same tensor (the two expansion branches of a fire module, Sec. "Evaluation" networks):
+ * outs[k] = hisa_conv2d_apply(in, plans[k]) bit for bit, but the plans that rotate their inputs (CHW_ROTATE_INPUTS by
+ * (tap, diagonal), CHW_ROTATE_SUMS by the taps, CHW_ROTATE_SUMS_TAPS by the diagonals, HW-tiled by the taps; not those
+ * with shared_moddown) take them from one set of hoisted rotations by the union of their amounts: an amount that two
+ * plans ask for is rotated once.  plans and outs are host arrays of n_plans pointers; every outs[k] is prepared by the
+ * caller like the output of hisa_conv2d_apply.  On an error no output is left allocated. */
+int hisa_conv2d_apply_multi(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_plan* const* plans, size_t n_plans,
+                            hisa_tensor* const* outs);
 int hisa_conv_plan_free(hisa_ctx* ctx, hisa_conv_plan* plan);
 /* Fully connected layer over all elements of all channels (Sec. "Homomorphic
  * matmul", the version without replicas): host w[OUT][C][H][W]; per output o:

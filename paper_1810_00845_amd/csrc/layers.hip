@@ -965,57 +965,105 @@ static int upload_weight_residues(hisa_ctx* ctx, const int64_t* w_int, uint32_t 
     return HISA_OK;
 }
 
-// dw: SCALAR/MASKED weights (null for PLAIN); d_pts: MASKED [l][N], PLAIN [T][OC][l][N]
-static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
-                    DevWeights* dw, double w_scale, const u64* d_pts, double pt_scale, hisa_tensor* out, u64 pt_count = 0,
-                    int pt_packed = 0) {
-    // in units of ciphertexts: IC inputs and OCm outputs per image (HW-tiling: the channels themselves)
-    const uint32_t B = in->batch, ci = t_ci(in), IC = (uint32_t)t_per(in), OCm = (OC + ci - 1) / ci, l = in->cts[0]->limbs;
-    const size_t nct = (size_t)B * IC, n = ctx->N;
-    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
-    const int n_taps = (int)plan.steps.size();
-    std::vector<hisa_ct*> wrapped;   // inputs with the copy of their channel blocks behind them
+// The inputs of a convolution as its multiply-accumulate reads them: the gathered batch (with the copy of the channel
+// blocks behind them where the layout needs it) and its rotations by the distinct non-zero amounts of `steps`, all from
+// one hoisted call (one decomposition of c1).  Convolutions of the same tensor that ask for the same amounts can share
+// one set (hisa_conv2d_apply_multi): a rotation computed once or twice has the same bits.
+struct RotatedInputs {
+    int32_t wrap = 0;
+    std::vector<hisa_ct*> wrapped;
+    BatchIn bi = {};
+    std::vector<int32_t> steps;                    // distinct, non-zero
+    std::vector<std::vector<hisa_ct*>> rotated;    // per entry of steps: the nct rotated ciphertexts (one allocation)
+    const u64* base_of(int32_t step) const {
+        if (step == 0) return bi.base;
+        for (size_t k = 0; k < steps.size(); k++)
+            if (steps[k] == step) return rotated[k].empty() ? nullptr : rotated[k][0]->data;
+        return nullptr;
+    }
+};
+
+static void release_inputs(hisa_ctx* ctx, RotatedInputs& r) {
+    for (auto& v : r.rotated) free_handles(ctx, v);
+    r.rotated.clear();
+    r.steps.clear();
+    dev_release(ctx, r.bi.tmp);
+    r.bi = {};
+    free_handles(ctx, r.wrapped);
+    r.wrapped.clear();
+}
+
+static int rotate_inputs(hisa_ctx* ctx, const hisa_tensor* in, int32_t wrap, const std::vector<int32_t>& steps, RotatedInputs& r) {
+    const uint32_t l = in->cts[0]->limbs;
+    const size_t nct = (size_t)in->batch * t_per(in);
+    r.wrap = wrap;
     hisa_ct* const* src = in->cts;
-    if (plan.wrap > 0) {
-        wrapped.assign(nct, nullptr);
-        TRY(hisa_rot_left_batch(ctx, (const hisa_ct* const*)in->cts, nct, norm_step(ctx, -plan.wrap), wrapped.data()));
+    if (wrap > 0) {
+        r.wrapped.assign(nct, nullptr);
+        TRY(hisa_rot_left_batch(ctx, (const hisa_ct* const*)in->cts, nct, norm_step(ctx, -wrap), r.wrapped.data()));
         BatchIn orig;
         int rcw = gather_batch(ctx, (const hisa_ct* const*)in->cts, nct, &orig);
         if (rcw == HISA_OK) {
             const u64 words = ct_words(ctx, 2, l);
-            hipError_t e = launch_addsub(ctx->d_primes, wrapped[0]->data, orig.base, wrapped[0]->data, OP_ADD, (int)l, 2, 2, nct, words,
-                                         orig.stride, words, (int)ctx->log_n, ctx->stream);
+            hipError_t e = launch_addsub(ctx->d_primes, r.wrapped[0]->data, orig.base, r.wrapped[0]->data, OP_ADD, (int)l, 2, 2, nct,
+                                         words, orig.stride, words, (int)ctx->log_n, ctx->stream);
             if (e != hipSuccess) rcw = fail(ctx, HISA_ERR_HIP, "conv wrap: %s", hipGetErrorString(e));
         }
         dev_release(ctx, orig.tmp);
-        if (rcw != HISA_OK) { free_handles(ctx, wrapped); return rcw; }
-        src = wrapped.data();
+        if (rcw != HISA_OK) { release_inputs(ctx, r); return rcw; }
+        src = r.wrapped.data();
     }
-    BatchIn bi;
     {
-        const int rcg = gather_batch(ctx, (const hisa_ct* const*)src, nct, &bi);
-        if (rcg != HISA_OK) { free_handles(ctx, wrapped); return rcg; }
+        const int rcg = gather_batch(ctx, (const hisa_ct* const*)src, nct, &r.bi);
+        if (rcg != HISA_OK) { release_inputs(ctx, r); return rcg; }
     }
-    std::vector<std::vector<hisa_ct*>> rotated(n_taps);
+    for (int32_t st : steps)
+        if (st != 0 && std::find(r.steps.begin(), r.steps.end(), st) == r.steps.end()) r.steps.push_back(st);
+    if (!r.steps.empty()) {   // one call, so that the decomposition of c1 is shared by all amounts
+        std::vector<hisa_ct*> all(r.steps.size() * nct, nullptr);
+        const int rc = hisa_rot_left_hoisted_batch(ctx, (const hisa_ct* const*)src, nct, r.steps.data(), r.steps.size(), all.data());
+        if (rc != HISA_OK) { release_inputs(ctx, r); return rc; }
+        r.rotated.resize(r.steps.size());
+        for (size_t k = 0; k < r.steps.size(); k++) r.rotated[k].assign(all.begin() + k * nct, all.begin() + (k + 1) * nct);
+    }
+    return HISA_OK;
+}
+
+// the rotated inputs of a plan's taps, from a shared set or made here
+static int tap_inputs(hisa_ctx* ctx, const hisa_tensor* in, const ConvPlan& plan, const RotatedInputs* shared, RotatedInputs& own,
+                      MacArgs& ma) {
+    const RotatedInputs* ri = shared;
+    if (!ri) {
+        TRY(rotate_inputs(ctx, in, plan.wrap, plan.steps, own));
+        ri = &own;
+    } else if (ri->wrap != plan.wrap) {
+        return fail(ctx, HISA_ERR_ARG, "shared rotations of another layout");
+    }
+    if (plan.steps.size() > MAX_TAPS) return fail(ctx, HISA_ERR_ARG, "too many taps");
+    for (size_t t = 0; t < plan.steps.size(); t++) {
+        ma.tap_base[t] = ri->base_of(plan.steps[t]);
+        if (!ma.tap_base[t]) {
+            if (!shared) release_inputs(ctx, own);
+            return fail(ctx, HISA_ERR_ARG, "a rotation of the inputs is missing");
+        }
+    }
+    return HISA_OK;
+}
+
+// dw: SCALAR/MASKED weights (null for PLAIN); d_pts: MASKED [l][N], PLAIN [T][OC][l][N]
+static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
+                    DevWeights* dw, double w_scale, const u64* d_pts, double pt_scale, hisa_tensor* out, u64 pt_count = 0,
+                    int pt_packed = 0, const RotatedInputs* shared = nullptr) {
+    // in units of ciphertexts: IC inputs and OCm outputs per image (HW-tiling: the channels themselves)
+    const uint32_t B = in->batch, ci = t_ci(in), IC = (uint32_t)t_per(in), OCm = (OC + ci - 1) / ci, l = in->cts[0]->limbs;
+    const size_t n = ctx->N;
+    if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
+    const int n_taps = (int)plan.steps.size();
     std::vector<hisa_ct*> outs((size_t)B * OCm, nullptr);
     MacArgs ma = {};
+    RotatedInputs own;
+    TRY(tap_inputs(ctx, in, plan, shared, own, ma));
     int rc = HISA_OK;
-    {   // all taps rotate the same inputs: one call, so that the decomposition of c1 is shared by the taps
-        std::vector<int32_t> nz;
-        std::vector<int> tap_of;
-        for (int t = 0; t < n_taps; t++) {
-            if (plan.steps[t] == 0) ma.tap_base[t] = bi.base;
-            else { nz.push_back(plan.steps[t]); tap_of.push_back(t); }
-        }
-        if (!nz.empty()) {
-            std::vector<hisa_ct*> all(nz.size() * nct, nullptr);
-            rc = hisa_rot_left_hoisted_batch(ctx, (const hisa_ct* const*)src, nct, nz.data(), nz.size(), all.data());
-            for (size_t k = 0; k < nz.size() && rc == HISA_OK; k++) {
-                rotated[tap_of[k]].assign(all.begin() + k * nct, all.begin() + (k + 1) * nct);
-                ma.tap_base[tap_of[k]] = rotated[tap_of[k]][0]->data;
-            }
-        }
-    }
     const double in_scale = in->cts[0]->scale;
     double mac_scale = in_scale * (g->mode == HISA_CONV_PLAIN ? pt_scale : w_scale);
     if (rc == HISA_OK) rc = alloc_ct_batch(ctx, (size_t)B * OCm, 2, l, mac_scale, outs.data());
@@ -1047,9 +1095,7 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
         }
         if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));
     }
-    for (auto& v : rotated) free_handles(ctx, v);
-    dev_release(ctx, bi.tmp);
-    free_handles(ctx, wrapped);
+    if (!shared) release_inputs(ctx, own);
     if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
     if (rc != HISA_OK) {
         for (hisa_ct* c : outs) hisa_free(ctx, c);
@@ -1071,55 +1117,20 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
 // HISA_CHW_ROTATE_SUMS_TAPS exchanges the roles: the inputs are rotated by the d blocks, the sums (one per filter tap,
 // the unrotated tap first) by the taps; d_pts: [c_inner][IC][taps * OCm][l][N].
 static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
-                         const u64* d_pts, double pt_scale, hisa_tensor* out, u64 pt_count = 0, int pt_packed = 0) {
+                         const u64* d_pts, double pt_scale, hisa_tensor* out, u64 pt_count = 0, int pt_packed = 0,
+                         const RotatedInputs* shared = nullptr) {
     const uint32_t B = in->batch, ci = t_ci(in), IC = (uint32_t)t_per(in), OCm = (OC + ci - 1) / ci, l = in->cts[0]->limbs;
-    const size_t nct = (size_t)B * IC, n = ctx->N;
+    const size_t n = ctx->N;
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "conv needs a level to rescale into");
     if (!d_pts || plan.sum_steps.size() != (plan.sums_by_taps ? plan.sum_taps.size() : (size_t)ci) - 1)
         return fail(ctx, HISA_ERR_ARG, "bad convolution plan");
     const int n_taps = (int)plan.steps.size();
     const u64 ctw = 2 * (u64)l * n;
-    std::vector<hisa_ct*> wrapped;
-    hisa_ct* const* src = in->cts;
-    if (plan.wrap > 0) {
-        wrapped.assign(nct, nullptr);
-        TRY(hisa_rot_left_batch(ctx, (const hisa_ct* const*)in->cts, nct, norm_step(ctx, -plan.wrap), wrapped.data()));
-        BatchIn orig;
-        int rcw = gather_batch(ctx, (const hisa_ct* const*)in->cts, nct, &orig);
-        if (rcw == HISA_OK) {
-            hipError_t e = launch_addsub(ctx->d_primes, wrapped[0]->data, orig.base, wrapped[0]->data, OP_ADD, (int)l, 2, 2, nct, ctw,
-                                         orig.stride, ctw, (int)ctx->log_n, ctx->stream);
-            if (e != hipSuccess) rcw = fail(ctx, HISA_ERR_HIP, "conv wrap: %s", hipGetErrorString(e));
-        }
-        dev_release(ctx, orig.tmp);
-        if (rcw != HISA_OK) { free_handles(ctx, wrapped); return rcw; }
-        src = wrapped.data();
-    }
-    BatchIn bi;
-    {
-        const int rcg = gather_batch(ctx, (const hisa_ct* const*)src, nct, &bi);
-        if (rcg != HISA_OK) { free_handles(ctx, wrapped); return rcg; }
-    }
-    std::vector<std::vector<hisa_ct*>> rotated(n_taps);
     std::vector<hisa_ct*> outs((size_t)B * OCm, nullptr);
     MacArgs ma = {};
+    RotatedInputs own;
+    TRY(tap_inputs(ctx, in, plan, shared, own, ma));
     int rc = HISA_OK;
-    {
-        std::vector<int32_t> nz;
-        std::vector<int> tap_of;
-        for (int t = 0; t < n_taps; t++) {
-            if (plan.steps[t] == 0) ma.tap_base[t] = bi.base;
-            else { nz.push_back(plan.steps[t]); tap_of.push_back(t); }
-        }
-        if (!nz.empty()) {
-            std::vector<hisa_ct*> all(nz.size() * nct, nullptr);
-            rc = hisa_rot_left_hoisted_batch(ctx, (const hisa_ct* const*)src, nct, nz.data(), nz.size(), all.data());
-            for (size_t k = 0; k < nz.size() && rc == HISA_OK; k++) {
-                rotated[tap_of[k]].assign(all.begin() + k * nct, all.begin() + (k + 1) * nct);
-                ma.tap_base[tap_of[k]] = rotated[tap_of[k]][0]->data;
-            }
-        }
-    }
     const double mac_scale = in->cts[0]->scale * pt_scale;
     const size_t terms = plan.sum_steps.size() + 1;
     const size_t sums = terms * OCm;               // per image, ordered (term, g): term = diagonal d, or sum k of the taps
@@ -1137,9 +1148,7 @@ static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_g
         hipError_t e = launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
         if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));
     }
-    for (auto& v : rotated) free_handles(ctx, v);
-    dev_release(ctx, bi.tmp);
-    free_handles(ctx, wrapped);
+    if (!shared) release_inputs(ctx, own);
     // per image: entries (d, g) are rotation-major over the OCm outputs; d = 0 is the unrotated term
     for (uint32_t b = 0; b < B && rc == HISA_OK; b++) {
         const u64* yb = y.u() + (size_t)b * sums * ctw;
@@ -1620,12 +1629,13 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
 }
 
 static int conv_dispatch(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* g, const ConvPlan& plan, uint32_t OC,
-                         const ConvWeights& cw, hisa_tensor* out) {
+                         const ConvWeights& cw, hisa_tensor* out, const RotatedInputs* shared = nullptr) {
     if (plan.rotate_sums)
-        return conv_run_sums(ctx, in, g, plan, OC, cw.pts ? cw.pts->u() : nullptr, cw.pt_scale, out, cw.pt_count, cw.pt_packed);
-    if (cw.shared) return conv_run_shared(ctx, in, g, plan, OC, cw, out);
+        return conv_run_sums(ctx, in, g, plan, OC, cw.pts ? cw.pts->u() : nullptr, cw.pt_scale, out, cw.pt_count, cw.pt_packed,
+                             shared);
+    if (cw.shared) return conv_run_shared(ctx, in, g, plan, OC, cw, out);   // rotates inside its own key switch
     const u64* d_pts = g->mode == HISA_CONV_MASKED ? (cw.mask ? cw.mask->u() : nullptr) : (cw.pts ? cw.pts->u() : nullptr);
-    return conv_run(ctx, in, g, plan, OC, cw.dw, cw.w_scale, d_pts, cw.pt_scale, out, cw.pt_count, cw.pt_packed);
+    return conv_run(ctx, in, g, plan, OC, cw.dw, cw.w_scale, d_pts, cw.pt_scale, out, cw.pt_count, cw.pt_packed, shared);
 }
 
 extern "C" int hisa_conv2d_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* w_int, double w_scale,
@@ -1713,7 +1723,7 @@ extern "C" int hisa_conv_plan_free(hisa_ctx* ctx, hisa_conv_plan* plan) {
     return HISA_OK;
 }
 
-extern "C" int hisa_conv2d_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_plan* plan, hisa_tensor* out) {
+static int check_plan_for(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_plan* plan, const hisa_tensor* out) {
     if (!ctx || !plan || plan->magic != HISA_MAGIC_CONVPLAN) return fail(ctx, HISA_ERR_ARG, "bad argument");
     TRY(check_tensor(ctx, in));
     if (!out || !out->cts) return fail(ctx, HISA_ERR_ARG, "bad output tensor");
@@ -1724,9 +1734,50 @@ extern "C" int hisa_conv2d_apply(hisa_ctx* ctx, const hisa_tensor* in, const his
     if (in->cts[0]->limbs != plan->limbs)
         return fail(ctx, HISA_ERR_LEVEL_MISMATCH, "the plan was prepared for %u limbs, the tensor has %u", plan->limbs,
                     in->cts[0]->limbs);
+    return HISA_OK;
+}
+
+extern "C" int hisa_conv2d_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_plan* plan, hisa_tensor* out) {
+    TRY(check_plan_for(ctx, in, plan, out));
     ConvPlan cp;
     TRY(conv_plan(ctx, in, &plan->geom, &cp));
     return conv_dispatch(ctx, in, &plan->geom, cp, plan->out_channels, plan->cw, out);
+}
+
+extern "C" int hisa_conv2d_apply_multi(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_plan* const* plans, size_t n_plans,
+                                       hisa_tensor* const* outs) {
+    if (!ctx || !plans || !outs || n_plans == 0) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    std::vector<ConvPlan> cps(n_plans);
+    for (size_t k = 0; k < n_plans; k++) {
+        TRY(check_plan_for(ctx, in, plans[k], outs[k]));
+        TRY(conv_plan(ctx, in, &plans[k]->geom, &cps[k]));
+    }
+    // the plans that rotate their inputs outside a key switch of their own, in the layout of the first such plan,
+    // share the rotations by the union of their amounts
+    std::vector<int32_t> steps;
+    std::vector<char> sharing(n_plans, 0);
+    int32_t wrap = -1;
+    size_t sharers = 0;
+    for (size_t k = 0; k < n_plans; k++) {
+        if (plans[k]->cw.shared && !cps[k].rotate_sums) continue;
+        if (wrap < 0) wrap = cps[k].wrap;
+        if (cps[k].wrap != wrap) continue;
+        sharing[k] = 1;
+        sharers++;
+        steps.insert(steps.end(), cps[k].steps.begin(), cps[k].steps.end());
+    }
+    RotatedInputs ri;
+    const bool share = sharers > 1;
+    if (share) TRY(rotate_inputs(ctx, in, wrap, steps, ri));
+    int rc = HISA_OK;
+    size_t done = 0;
+    for (; done < n_plans && rc == HISA_OK; done++)
+        rc = conv_dispatch(ctx, in, &plans[done]->geom, cps[done], plans[done]->out_channels, plans[done]->cw, outs[done],
+                           share && sharing[done] ? &ri : nullptr);
+    if (share) release_inputs(ctx, ri);
+    if (rc != HISA_OK)   // the outputs of the plans before the failing one are the caller's no longer
+        for (size_t k = 0; k + 1 < done; k++) hisa_tensor_free(ctx, outs[k]);
+    return rc;
 }
 
 // ---------------------------------------------------------------------------

@@ -440,6 +440,18 @@ class Context:
     def conv2d_apply(self, t, plan):
         return self._layer("hisa_conv2d_apply", t, t.batch * plan[1], plan[0])
 
+    def conv2d_apply_multi(self, t, plans):
+        """conv2d_apply of every plan on the same tensor, the rotations of the inputs shared between the plans."""
+        st, _arr = t._struct()
+        outs = [CipherTensor(self, [None] * (t.batch * p[1]), 0, 0, 0, 0, 0, 0, 0, 0, 1, 0) for p in plans]
+        structs = [o._struct() for o in outs]
+        plan_arr = (C.c_void_p * len(plans))(*[p[0] for p in plans])
+        out_arr = (C.c_void_p * len(plans))(*[C.addressof(ost) for ost, _ in structs])
+        self._ck(load().hisa_conv2d_apply_multi(self._vp, C.byref(st), plan_arr, C.c_size_t(len(plans)), out_arr))
+        for o, (ost, oarr) in zip(outs, structs):
+            o._adopt(ost, oarr)
+        return outs
+
     def conv_plan_free(self, plan):
         self._ck(load().hisa_conv_plan_free(self._vp, plan[0]))
 

@@ -189,7 +189,7 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             return out
         return hw_or_chw_convolution(key, t, w, fh, fw, **kw)
 
-    def hw_or_chw_convolution(key, t, w, fh, fw, **kw):
+    def hw_or_chw_convolution(key, t, w, fh, fw, plan_only=False, **kw):
         cleaned = None
         if t.c_inner > 1:                 # CHW-tiled: plaintext weights on a clean input
             kw["mode"] = 2
@@ -229,6 +229,8 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
         else:
             if key not in plans:
                 plans[key] = ("conv", ctx.conv2d_prepare(t, w, fh, fw, **kw))
+            if plan_only:                 # the caller applies it together with other plans of the same tensor
+                return None
             out = ctx.conv2d_apply(t, plans[key][1])
         if cleaned is not None:
             cleaned.free()
@@ -262,8 +264,14 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             s0 = convolution((idx, "squeeze"), t, ws, 1, 1)
             s1 = ctx.poly2_act(s0, a, b)
             s0.free()
-            e1 = convolution((idx, "expand1"), s1, w1 * a, 1, 1)
-            e3 = convolution((idx, "expand3"), s1, w3 * a, 3, 3, pad_same=True, mode=1)
+            if plans is not None and layout != "hw_conv" and s1.c_inner > 1 and s1.clean:
+                # CHW-tiled: both branches rotate the squeezed tensor by the channel diagonals -- once for the two
+                hw_or_chw_convolution((idx, "expand1"), s1, w1 * a, 1, 1, plan_only=True)
+                hw_or_chw_convolution((idx, "expand3"), s1, w3 * a, 3, 3, plan_only=True, pad_same=True, mode=1)
+                e1, e3 = ctx.conv2d_apply_multi(s1, [plans[(idx, "expand1")][1], plans[(idx, "expand3")][1]])
+            else:
+                e1 = convolution((idx, "expand1"), s1, w1 * a, 1, 1)
+                e3 = convolution((idx, "expand3"), s1, w3 * a, 3, 3, pad_same=True, mode=1)
             s1.free()
             nxt = _concat_channels(ctx, e1, e3)
         elif kind == "gap" and fused and 1 < t.width <= 33 and 1 < t.height <= 33:

@@ -455,6 +455,56 @@ def test_plan_plaintexts_in_six_bytes_give_the_same_bits(q_bits):
 
 
 @pytest.mark.parametrize("c_stride", [64, 512])
+def test_plans_applied_together_share_input_rotations(c_stride):
+    """Several plans applied to one tensor in one call: every output equals the plan applied alone bit for bit (and so
+    the oracle's convolution), the rotations of the inputs that two plans ask for are made once (one inner-product
+    launch over the union of the amounts instead of one per plan), an error leaves nothing behind.  A 1x1 convolution
+    rotating its inputs by the channel diagonals, a 3x3 one rotating inputs by the diagonals and sums by the taps and a
+    3x3 one rotating the inputs by the taps and the sums by the diagonals; blocks filling the slots and with their copy
+    behind them."""
+    from oracle import layers
+    from paper_1810_00845_amd import hisa, synth
+    g = hisa.Context(12, [50, 40, 40], 3, 50, 29)
+    g.keygen()
+    x = synth.image(45, 7, 4, 4)[None].repeat(2, axis=0) * np.array([1.0, -0.6])[:, None, None, None]
+    t = g.tensor_encrypt(x, 2.0 ** 40, 3, h_stride=6, offset=7, c_inner=4, c_stride=c_stride)
+    w1, w3, w3b = synth.conv_weights(46, 1, 1, 7, 5), synth.conv_weights(47, 3, 3, 7, 6), synth.conv_weights(48, 3, 3, 7, 3)
+    specs = [(w1, 1, dict(chw_schedule=hisa.CHW_ROTATE_INPUTS)),
+             (w3, 3, dict(chw_schedule=hisa.CHW_ROTATE_SUMS_TAPS, pad_same=True)),
+             (w3b, 3, dict(chw_schedule=hisa.CHW_ROTATE_SUMS, pad_same=True))]
+    steps = set()
+    for w, f, kw in specs:
+        steps |= set(g.conv2d_rot_steps(t, f, f, **kw))
+    g.gen_rot_keys(sorted(steps))
+    plans = [g.conv2d_prepare(t, w, f, f, mode=layers.CONV_PLAIN, **kw) for w, f, kw in specs]
+    g.profile_enable(True)
+    alone = [g.conv2d_apply(t, p) for p in plans]
+    g.sync()
+    launches_alone = sum(c for k, (c, _) in g.profile_read().items() if k.startswith("inner_product_steps"))
+    g.profile_enable(False); g.profile_enable(True)
+    together = g.conv2d_apply_multi(t, plans)
+    g.sync()
+    launches_together = sum(c for k, (c, _) in g.profile_read().items() if k.startswith("inner_product_steps"))
+    g.profile_enable(False)
+    assert launches_together < launches_alone
+    for (w, f, kw), a, b in zip(specs, alone, together):
+        assert a.meta() == b.meta()
+        for ca, cb in zip(a.cts, b.cts):
+            assert np.array_equal(g.ct_export(ca), g.ct_export(cb)) and ca.scale == cb.scale
+        ref = plain_net.conv2d(x, w, pad_same=kw.get("pad_same", False))
+        assert np.abs(g.tensor_decrypt(b) - ref).max() <= 1e-3
+    one = g.conv2d_apply_multi(t, plans[:1])                     # a single plan: the plain call
+    for ca, cb in zip(alone[0].cts, one[0].cts):
+        assert np.array_equal(g.ct_export(ca), g.ct_export(cb))
+    lower = g.tensor_encrypt(x, 2.0 ** 40, 2, h_stride=6, offset=7, c_inner=4, c_stride=c_stride)
+    with pytest.raises(hisa.HisaError):                           # a plan of another level among them
+        g.conv2d_apply_multi(lower, plans)
+    for p in plans:
+        g.conv_plan_free(p)
+    g.close()
+
+
+@pytest.mark.parametrize("c_stride", [64, 512])
 def test_chw_conv_rotating_the_sums_bit_exact(c_stride):
     """The CHW-tiled convolution that reduces over the channel blocks after the multiplication, against the oracle
     bit for bit: batch of two, 5 -> 6 channels in blocks of 4 (ragged last ciphertexts), SAME and VALID, stride 1 and
