@@ -384,11 +384,96 @@ __device__ __forceinline__ void plain_mac_fp_body(const FpPrime* fprimes, const 
     }
 }
 
+// The limb-major forms (1, 2) with two neighbouring coefficients per thread: sixteen-byte loads of the ciphertext words
+// and of eight-byte plaintext rows, eight + four bytes of a six-byte row (the layout of pack_plain_kernel).  Two-polynomial
+// entries on the primes q_0.. only.
+template <int OCP, int FORM>
+__device__ __forceinline__ void plain_mac_fp_body2(const FpPrime* fprimes, const MacArgs& g, int log_n) {
+    typedef unsigned long long ull2_t __attribute__((ext_vector_type(2)));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const u64 n = (u64)1 << log_n;
+    const u64 j = ((u64)blockIdx.x * NT + threadIdx.x) * 2;
+    const int limb = blockIdx.z;
+    const int ocblocks = (g.OC + OCP - 1) / OCP;
+    const int b = blockIdx.y / ocblocks, oc0 = (blockIdx.y % ocblocks) * OCP;
+    const mac_cdouble_ptr fp = (mac_cdouble_ptr)(unsigned long long)&fprimes[limb].p;
+    const double p = fp[0], pinv = fp[1];
+    const u64 ln = (u64)g.l * n;
+    double a0[OCP][2], a1[OCP][2];
+#pragma unroll
+    for (int o = 0; o < OCP; o++) a0[o][0] = a0[o][1] = a1[o][0] = a1[o][1] = 0.0;
+    int pending = 0;
+    const u64 lo_off = (j >> 7) * 768 + (j & 127) * 4, hi_off = (j >> 7) * 768 + 512 + (j & 127) * 2;
+    const u64 b0 = (g.w_packed & 1) ? 6 : 8, b1 = (g.w_packed & 2) ? 6 : 8, rb = (FORM == 2 ? 6 : 8) * n;
+    // term = (tap, input): the loads of the next term are issued before the arithmetic of the current one
+    const char* wlimb = (const char*)g.w + (limb ? b0 + (u64)(limb - 1) * b1 : 0) * n * g.w_count + (u64)oc0 * g.w_stride_oc * rb;
+    auto load = [&](int t, int ic, ull2_t& xb, ull2_t& xa, ull2_t (&wv)[OCP]) {
+        const u64* x = g.tap_base[t] + ((u64)b * g.IC + ic) * g.ct_words + (u64)limb * n + j;
+        xb = *(const ull2_t*)x;
+        xa = *(const ull2_t*)(x + ln);
+        const char* wp = wlimb + ((u64)t * g.IC + ic) * g.w_stride_t * rb;
+#pragma unroll
+        for (int o = 0; o < OCP; o++) {
+            const int oo = oc0 + o < g.OC ? o : 0;
+            const char* row = wp + (u64)oo * g.w_stride_oc * rb;
+            if (FORM == 2) {
+                const u32x2 lo = *(const u32x2*)(row + lo_off);
+                const uint32_t hi = *(const uint32_t*)(row + hi_off);
+                wv[o].x = (u64)lo.x | ((u64)(hi & 0xFFFFu) << 32);
+                wv[o].y = (u64)lo.y | ((u64)(hi >> 16) << 32);
+            } else {
+                wv[o] = *(const ull2_t*)(row + 8 * j);
+            }
+        }
+    };
+    ull2_t xb, xa, wv[OCP], nxb, nxa, nwv[OCP];
+    load(0, 0, xb, xa, wv);
+    for (int t = 0; t < g.n_taps; t++) {
+        for (int ic = 0; ic < g.IC; ic++) {
+            const bool more = ic + 1 < g.IC || t + 1 < g.n_taps;
+            if (more) load(ic + 1 < g.IC ? t : t + 1, ic + 1 < g.IC ? ic + 1 : 0, nxb, nxa, nwv);
+            const double fb[2] = {fp_from_u64(xb.x), fp_from_u64(xb.y)}, fa[2] = {fp_from_u64(xa.x), fp_from_u64(xa.y)};
+#pragma unroll
+            for (int o = 0; o < OCP; o++) {
+                const double wf[2] = {fp_from_u64(wv[o].x), fp_from_u64(wv[o].y)};
+#pragma unroll
+                for (int c = 0; c < 2; c++) {
+                    a0[o][c] += fp_mulmod(fb[c], wf[c], p, pinv);
+                    a1[o][c] += fp_mulmod(fa[c], wf[c], p, pinv);
+                }
+            }
+            if (++pending == 4) {   // canonical operands: a term can reach 0.9 p, four of them on a normalised value 4.1 p
+#pragma unroll
+                for (int o = 0; o < OCP; o++)
+#pragma unroll
+                    for (int c = 0; c < 2; c++) { a0[o][c] = fp_norm(a0[o][c], p, pinv); a1[o][c] = fp_norm(a1[o][c], p, pinv); }
+                pending = 0;
+            }
+            if (more) {
+                xb = nxb; xa = nxa;
+#pragma unroll
+                for (int o = 0; o < OCP; o++) wv[o] = nwv[o];
+            }
+        }
+    }
+#pragma unroll
+    for (int o = 0; o < OCP; o++) {
+        if (oc0 + o < g.OC) {
+            u64* dst = g.out + ((u64)b * g.OC + oc0 + o) * g.ct_words + (u64)limb * n + j;
+            ull2_t r0, r1;
+            r0.x = fp_canonical(a0[o][0], p, pinv); r0.y = fp_canonical(a0[o][1], p, pinv);
+            r1.x = fp_canonical(a1[o][0], p, pinv); r1.y = fp_canonical(a1[o][1], p, pinv);
+            *(ull2_t*)dst = r0;
+            *(ull2_t*)(dst + ln) = r1;
+        }
+    }
+}
+
 template <bool WITH_X2, int OCP, bool PACKED = false>
 __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes, MacArgs g, int log_n) {
     if (!PACKED) plain_mac_fp_body<WITH_X2, OCP, 0>(fprimes, g, log_n);
-    else if (g.w_packed >> (blockIdx.z ? 1 : 0) & 1) plain_mac_fp_body<false, OCP, 2>(fprimes, g, log_n);
-    else plain_mac_fp_body<false, OCP, 1>(fprimes, g, log_n);
+    else if (g.w_packed >> (blockIdx.z ? 1 : 0) & 1) plain_mac_fp_body2<OCP, 2>(fprimes, g, log_n);
+    else plain_mac_fp_body2<OCP, 1>(fprimes, g, log_n);
 }
 
 // analysis mode: a multiply-accumulate launch stands for one term per (image, output, tap, input)
@@ -449,7 +534,7 @@ static hipError_t launch_scalar_mac_mfma(const FpPrime* fprimes, const MacArgs& 
 }
 
 // Plaintexts [cnt][l][N] of eight-byte residues -> the limb-major form [l][cnt] of rows of N residues: a packed row holds,
-// for every 64 residues, their 64 low 32-bit words followed by their 64 high 16-bit words (384 bytes); an unpacked one
+// for every 128 residues, their 128 low 32-bit words followed by their 128 high 16-bit words (768 bytes); an unpacked one
 // is as it was (packed: bit 0 limb 0, bit 1 the rest).
 // One launch converts the plaintexts first .. first + gridDim.z - 1.
 __global__ __launch_bounds__(NT) void pack_plain_kernel(const u64* src, char* dst, int l, int packed, u64 cnt, u64 first, int log_n) {
@@ -461,8 +546,8 @@ __global__ __launch_bounds__(NT) void pack_plain_kernel(const u64* src, char* ds
     const u64 v = src[(c * l + limb) * n + j];
     char* row = dst + (limb ? b0 + (u64)(limb - 1) * b1 : 0) * n * cnt + c * (pk ? 6 : 8) * n;
     if (pk) {
-        *(uint32_t*)(row + (j >> 6) * 384 + (j & 63) * 4) = (uint32_t)v;
-        *(uint16_t*)(row + (j >> 6) * 384 + 256 + (j & 63) * 2) = (uint16_t)(v >> 32);
+        *(uint32_t*)(row + (j >> 7) * 768 + (j & 127) * 4) = (uint32_t)v;
+        *(uint16_t*)(row + (j >> 7) * 768 + 512 + (j & 127) * 2) = (uint16_t)(v >> 32);
     } else {
         ((u64*)row)[j] = v;
     }
@@ -476,14 +561,15 @@ static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, 
     if (g.x2 && (!g.out2 || g.lq <= 0 || g.lq > g.l || g.x2_words == 0)) return hipErrorInvalidValue;
     if (g.w_count) {   // limb-major plaintexts: of exactly the limbs walked, on the primes q_0.., no second input
         const u64 last = ((u64)g.n_taps * g.IC - 1) * g.w_stride_t + (u64)(g.OC - 1) * g.w_stride_oc;
-        if (g.w_words || g.x2 || g.lq || (g.w_packed & ~3) || last >= g.w_count) return hipErrorInvalidValue;
+        if (g.w_words || g.x2 || g.lq || g.polys == 1 || (g.w_packed & ~3) || last >= g.w_count || log_n < 9)
+            return hipErrorInvalidValue;
     }
-    const int ocp = g.OC >= 8 ? 8 : 4;
+    const int ocp = (g.OC >= 8 && !g.w_count) ? 8 : 4;   // two coefficients per thread: four outputs fill the registers
     if ((u64)batch * ((g.OC + ocp - 1) / ocp) > 65535) return hipErrorInvalidValue;
-    dim3 grid((1u << log_n) / NT, batch * ((g.OC + ocp - 1) / ocp), g.l);
+    // the limb-major forms take two coefficients per thread
+    dim3 grid((1u << log_n) / NT / (g.w_count ? 2 : 1), batch * ((g.OC + ocp - 1) / ocp), g.l);
     ProfScope prof__("plain_mac_fp_kernel", st);
-    if (g.w_count && ocp == 8) hipLaunchKernelGGL((plain_mac_fp_kernel<false, 8, true>), grid, dim3(NT), 0, st, fprimes, g, log_n);
-    else if (g.w_count) hipLaunchKernelGGL((plain_mac_fp_kernel<false, 4, true>), grid, dim3(NT), 0, st, fprimes, g, log_n);
+    if (g.w_count) hipLaunchKernelGGL((plain_mac_fp_kernel<false, 4, true>), grid, dim3(NT), 0, st, fprimes, g, log_n);
     else if (g.x2 && ocp == 8) hipLaunchKernelGGL((plain_mac_fp_kernel<true, 8>), grid, dim3(NT), 0, st, fprimes, g, log_n);
     else if (g.x2) hipLaunchKernelGGL((plain_mac_fp_kernel<true, 4>), grid, dim3(NT), 0, st, fprimes, g, log_n);
     else if (ocp == 8) hipLaunchKernelGGL((plain_mac_fp_kernel<false, 8>), grid, dim3(NT), 0, st, fprimes, g, log_n);
