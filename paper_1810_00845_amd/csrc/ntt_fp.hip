@@ -710,10 +710,11 @@ hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a_in, const FpTask& 
 // inner product with the switching key, fp64
 // ---------------------------------------------------------------------------
 #define IPF_NT 256
-#define IPF_ZSPLIT 4
+#define IPF_ZSPLIT 8
 #define IPF_MAXD 8
 // One thread owns one coefficient of one extended limb: the 2*digits key values stay in registers while the
-// thread walks over its share of the batch, so the key is read IPF_ZSPLIT times per batch, not once per ciphertext.
+// thread walks over its share of the batch, so the key is read IPF_ZSPLIT times per batch (from the L2 after the
+// first: see the launch order below), not once per ciphertext.
 __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits,
                                                                   int l, int K, int L, int alpha, const u64* key, int total,
                                                                   const u64* own_src, u64 own_bs, u64 galois, int gather_ext,
