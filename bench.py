@@ -73,13 +73,13 @@ def algorithmic_flops_rot_left(N, l, K, alpha, B):
 # HBM bytes = FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0 KiB (the factors a 1 GiB device-to-device copy reads back), and the
 # share of the CUs' vector-ALU issue slots in use = SQ_INSTS_VALU * 4 cycles / (4 SIMDs * SQ_BUSY_CU_CYCLES).
 MEASURED_TRAFFIC = {
-    "ntt_fp_kernel<5, 3>": (2 * 102508.4 + 360448.1) * 1024,      # mean of the three digits' launches (two paired, one not)
-    "ntt_fp_kernel<5, 4>": (2 * 644413.8 + 786432.0) * 1024,
-    "ntt_fp_kernel<5, 2>": (2 * 167774.2 + 230400.0) * 1024,
-    "inner_product_fp_kernel": (2 * 560109.2 + 720896.0) * 1024,
+    "ntt_fp_kernel<5, 3>": (2 * 102268.1 + 360448.1) * 1024,      # mean of the three digits' launches (two paired, one not)
+    "ntt_fp_kernel<5, 4>": (2 * 644340.3 + 786432.0) * 1024,
+    "ntt_fp_kernel<5, 2>": (2 * 167592.6 + 230400.0) * 1024,
+    "inner_product_fp_kernel": (2 * 562991.9 + 720896.0) * 1024,
 }
 MEASURED_VALU_BUSY = {
-    "ntt_fp_kernel<5, 3>": 0.63, "ntt_fp_kernel<5, 4>": 0.54, "ntt_fp_kernel<5, 2>": 0.58, "inner_product_fp_kernel": 0.28,
+    "ntt_fp_kernel<5, 3>": 0.64, "ntt_fp_kernel<5, 4>": 0.55, "ntt_fp_kernel<5, 2>": 0.59, "inner_product_fp_kernel": 0.30,
 }
 FP64_PEAK_TFLOPS = 78.6   # 256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz
 
