@@ -299,12 +299,7 @@ __global__ __launch_bounds__(256) void scalar_mac_mfma_kernel(const FpPrime* fpr
 #define ICP 2
 // WITH_X2: the optional second input is present (a separate instantiation, so that the common form keeps its
 // straight-line loads)
-// PACKED: the plaintexts are stored limb-major -- the rows that a group of outputs reads for one term lie side by
-// side -- and with six bytes per residue where the prime is below 2^48 (the row layout of pack_plain_kernel), a quarter
-// less of the bytes that bound this kernel
-// FORM of the plaintext rows this block reads: 0 as encoded, 1 limb-major with eight-byte residues, 2 limb-major with
-// six-byte residues (the form is a template argument so that the loads of a term stay one straight line)
-template <bool WITH_X2, int OCP, int FORM>
+template <bool WITH_X2, int OCP>
 __device__ __forceinline__ void plain_mac_fp_body(const FpPrime* fprimes, const MacArgs& g, int log_n) {
     const u64 n = (u64)1 << log_n;
     const u64 j = (u64)blockIdx.x * NT + threadIdx.x;
@@ -322,15 +317,9 @@ __device__ __forceinline__ void plain_mac_fp_body(const FpPrime* fprimes, const 
 #pragma unroll
     for (int o = 0; o < OCP; o++) a0[o] = a1[o] = a2[o] = 0.0;
     int pending = 0;
-    // six-byte rows: per 64 residues their 64 low words, then their 64 high halfwords (384 bytes that one wave reads)
-    const u64 lo_off = (j >> 6) * 384 + (j & 63) * 4, hi_off = (j >> 6) * 384 + 256 + (j & 63) * 2;
     for (int t = 0; t < g.n_taps; t++) {
         const u64* x = g.tap_base[t] + (u64)b * g.IC * g.ct_words + (u64)limb * n + j;
         const u64* w = g.w + ((u64)t * g.IC * g.w_stride_t + (u64)oc0 * g.w_stride_oc) * wl + (u64)limb * n + j;
-        // limb-major forms: the limb's rows, in bytes
-        const u64 b0 = (g.w_packed & 1) ? 6 : 8, b1 = (g.w_packed & 2) ? 6 : 8, rb = (FORM == 2 ? 6 : 8) * n;
-        const char* wp = (const char*)g.w + (limb ? b0 + (u64)(limb - 1) * b1 : 0) * n * g.w_count +
-                         ((u64)t * g.IC * g.w_stride_t + (u64)oc0 * g.w_stride_oc) * rb;
         const u64* x2 = third ? g.x2 + (u64)t * g.x2_tap_words + (u64)b * g.IC * g.x2_words + (u64)limb * n + j : nullptr;
         for (int ic0 = 0; ic0 < g.IC; ic0 += ICP) {
             u64 xb[ICP], xa[ICP], xc[ICP], wv[ICP][OCP];
@@ -343,10 +332,7 @@ __device__ __forceinline__ void plain_mac_fp_body(const FpPrime* fprimes, const 
 #pragma unroll
                 for (int o = 0; o < OCP; o++) {
                     const int oo = oc0 + o < g.OC ? o : 0;
-                    const char* row = wp + ((u64)ic * g.w_stride_t + (u64)oo * g.w_stride_oc) * rb;
-                    if (FORM == 2) wv[u][o] = (u64)*(const uint32_t*)(row + lo_off) | ((u64)*(const uint16_t*)(row + hi_off) << 32);
-                    else if (FORM == 1) wv[u][o] = ((const u64*)row)[j];
-                    else wv[u][o] = w[((u64)ic * g.w_stride_t + (u64)oo * g.w_stride_oc) * wl];
+                    wv[u][o] = w[((u64)ic * g.w_stride_t + (u64)oo * g.w_stride_oc) * wl];
                 }
             }
 #pragma unroll
@@ -384,9 +370,12 @@ __device__ __forceinline__ void plain_mac_fp_body(const FpPrime* fprimes, const 
     }
 }
 
-// The limb-major forms (1, 2) with two neighbouring coefficients per thread: sixteen-byte loads of the ciphertext words
-// and of eight-byte plaintext rows, eight + four bytes of a six-byte row (the layout of pack_plain_kernel).  Two-polynomial
-// entries on the primes q_0.. only.
+// The plaintexts of a plan: limb-major -- the rows that a group of outputs reads for one term lie side by side -- and
+// with six bytes per residue where the prime is below 2^48 (the row layout of pack_plain_kernel), a quarter less of the
+// bytes that bound this kernel.  FORM of the rows this block reads: 1 eight-byte residues, 2 six-byte residues (a
+// template argument, so that the loads of a term stay one straight line).  Two neighbouring coefficients per thread:
+// sixteen-byte loads of the ciphertext words and of eight-byte rows, eight + four bytes of a six-byte row.
+// Two-polynomial entries on the primes q_0.. only.
 template <int OCP, int FORM>
 __device__ __forceinline__ void plain_mac_fp_body2(const FpPrime* fprimes, const MacArgs& g, int log_n) {
     typedef unsigned long long ull2_t __attribute__((ext_vector_type(2)));
@@ -471,7 +460,7 @@ __device__ __forceinline__ void plain_mac_fp_body2(const FpPrime* fprimes, const
 
 template <bool WITH_X2, int OCP, bool PACKED = false>
 __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes, MacArgs g, int log_n) {
-    if (!PACKED) plain_mac_fp_body<WITH_X2, OCP, 0>(fprimes, g, log_n);
+    if (!PACKED) plain_mac_fp_body<WITH_X2, OCP>(fprimes, g, log_n);
     else if (g.w_packed >> (blockIdx.z ? 1 : 0) & 1) plain_mac_fp_body2<OCP, 2>(fprimes, g, log_n);
     else plain_mac_fp_body2<OCP, 1>(fprimes, g, log_n);
 }
