@@ -813,8 +813,8 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const Fp
 // computed from the unrotated polynomial, gathered here through sigma_s like the own-digit limbs) -- or, with
 // shared_input, entry b for every s: all terms of an output rotate the same ciphertext --
 // acc[b] = sum_s sum_j sigma_s(e_{s,b,j}) * key_s[j].  A rotation's key values stay in registers across the IPS_BCH
-// outputs of a block (4: many blocks for the few outputs of a layer; 16 from 32 outputs on, where re-reading the
-// keys per block would be a third of the traffic); partial sums are normalised per rotation (eight terms of at most
+// outputs of a block (4: many blocks for the few outputs of a layer; the blocks of a limb run together, so the key
+// rows that each of them reads come from the L2 after the first); partial sums are normalised per rotation (eight terms of at most
 // 0.875 * 2^50 stay below 2^53) and the running sums every eight rotations.
 template <int IPS_BCH>
 __global__ __launch_bounds__(IPF_NT) void inner_product_sum_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs,
@@ -887,17 +887,11 @@ hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const u64* ext, u
     if (ext_bs < (u64)digits * (l + K) * n || acc_bs < (u64)2 * (l + K) * n || own_bs < (u64)l * n) return hipErrorInvalidValue;
     for (int s = 0; s < n_steps; s++)
         if (!steps.key[s] || steps.galois[s] == 0) return hipErrorInvalidValue;
-    // sixteen outputs per block only where that still leaves a few thousand blocks (sixteen per compute unit)
-    const u64 blocks16 = (u64)((1u << log_n) / IPF_NT) * (l + K) * ((n_batch + 15) / 16);
-    const unsigned bch = (n_batch >= 32 && blocks16 >= 4096) ? 16 : 4;
+    const unsigned bch = 4;
     dim3 grid((1u << log_n) / IPF_NT, (unsigned)((n_batch + bch - 1) / bch), l + K);
     ProfScope prof__("inner_product_sum_fp_kernel", st);
-    if (bch == 16)
-        hipLaunchKernelGGL(inner_product_sum_fp_kernel<16>, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha,
-                           steps, n_steps, total, own_src, own_bs, acc, acc_bs, n_batch, shared_input, log_n);
-    else
-        hipLaunchKernelGGL(inner_product_sum_fp_kernel<4>, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha,
-                           steps, n_steps, total, own_src, own_bs, acc, acc_bs, n_batch, shared_input, log_n);
+    hipLaunchKernelGGL(inner_product_sum_fp_kernel<4>, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha,
+                       steps, n_steps, total, own_src, own_bs, acc, acc_bs, n_batch, shared_input, log_n);
     return hipGetLastError();
 }
 
