@@ -381,7 +381,8 @@ typedef struct hisa_conv_plan hisa_conv_plan;
 int hisa_conv2d_prepare(hisa_ctx* ctx, const hisa_tensor* like, const double* w, uint32_t out_channels,
                         const hisa_conv_geom* geom, hisa_conv_plan** plan);
 int hisa_conv2d_apply(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_plan* plan, hisa_tensor* out);
-/* Several convolutions of the same tensor (the two expansion branches of a fire module, Sec. "Evaluation" networks):
+/* Several convolutions of the same tensor (the two expansion branches of a fire module of the SqueezeNet-style network
+ * of Sec. "Evaluation"; the reuse of a rotated ciphertext in Algorithm 1, taken across layers):
  * outs[k] = hisa_conv2d_apply(in, plans[k]) bit for bit, but the plans that rotate their inputs (CHW_ROTATE_INPUTS by
  * (tap, diagonal), CHW_ROTATE_SUMS by the taps, CHW_ROTATE_SUMS_TAPS by the diagonals, HW-tiled by the taps; not those
  * with shared_moddown) take them from one set of hoisted rotations by the union of their amounts: an amount that two
