@@ -34,6 +34,8 @@ def test_create_rejects_bad_parameters_or_reports_no_gpu():
     assert lib.hisa_create(ctypes.byref(prm), None, ctypes.byref(h)) == -1
     assert lib.hisa_create(None, None, ctypes.byref(h)) == -1
     assert lib.hisa_free(None, None) == 0
+    assert lib.hisa_conv2d_apply_multi(None, None, None, ctypes.c_size_t(0), None) == -1
+    assert lib.hisa_conv2d_apply(None, None, None, None) == -1
     assert lib.hisa_last_error(None) == b"no context"
 
 
