@@ -146,7 +146,7 @@ int hisa_mul_plain_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_pt* p);
 int hisa_mul_scalar(hisa_ctx* ctx, const hisa_ct* a, double x, double x_scale, hisa_ct** out);
 int hisa_mul_scalar_assign(hisa_ctx* ctx, hisa_ct* a, double x, double x_scale);
 
-/* ---- rotations ("Rotate ciphertext c left/right x slots") ----
+/* ---- rotations (the rotLeft / rotRight rows of Fig. "Instructions of the HISA") ----
  * rotLeft(r): (sigma_g(c0), 0) + KeySwitch_g(sigma_g(c1)), g = 5^r mod 2N;
  * rotRight(r) = rotLeft(N/2 - r); r = 0 (mod N/2) is a copy and needs no key;
  * any other amount needs its key from hisa_gen_rot_keys, else HISA_ERR_NO_KEY. */
@@ -154,6 +154,20 @@ int hisa_rot_left(hisa_ctx* ctx, const hisa_ct* a, int32_t steps, hisa_ct** out)
 int hisa_rot_right(hisa_ctx* ctx, const hisa_ct* a, int32_t steps, hisa_ct** out);
 int hisa_rot_left_assign(hisa_ctx* ctx, hisa_ct* a, int32_t steps);
 int hisa_rot_right_assign(hisa_ctx* ctx, hisa_ct* a, int32_t steps);
+/* rotLeft for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): out = rotLeft(a, steps), bit for bit what hisa_rot_left gives, written into the
+ * EXISTING two-polynomial ciphertext `out` (same number of limbs as `a`, not overlapping it; its scale is set to
+ * a's).  The call allocates nothing on the device: its intermediates (about (4 + ceil(l/alpha)) (l + K) + l
+ * limb-polynomials of 8 N bytes) live in a static device array of HISA_NOALLOC_SCRATCH_BYTES inside the library, of
+ * which every GPU the library runs on holds its own copy until the process ends.  A rotation that needs more returns
+ * HISA_ERR_SIZE (the message names both sizes); N = 2^15 with 16 limbs and dnum 3 fits.  Needs what the fused key
+ * switch needs (2^12 <= N <= 2^15, every prime below 2^50, dnum <= 8: HISA_ERR_ARG otherwise), the amount's key
+ * (HISA_ERR_NO_KEY), per-kernel timing switched off, and the context's device current.  All calls on one GPU share
+ * that GPU's array (contexts included), which keeps the last call's contents; every part is rewritten before it is
+ * read, so nothing is cleared.  Calls that overlap in time on one GPU -- two contexts on different streams -- race on it:
+ * the caller orders them. */
+#define HISA_NOALLOC_SCRATCH_BYTES (36u << 20)
+int hisa_rot_left_noalloc(hisa_ctx* ctx, const hisa_ct* a, int32_t steps, hisa_ct* out);
 
 /* ---- Division profile, RNS reading (Sec. "HISA": the divisor is a coprime
  * modulus of the ciphertext) ----

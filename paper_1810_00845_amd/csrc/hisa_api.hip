@@ -149,6 +149,29 @@ extern "C" int hisa_profile_read(hisa_ctx* ctx, char* host_buf, size_t cap) {
 // ---------------------------------------------------------------------------
 // errors, memory
 // ---------------------------------------------------------------------------
+// Intermediates of hisa_rot_left_noalloc (conversion input, extended digits, accumulators, ModDown input of ONE
+// ciphertext).  Every GPU holds its own copy of this array for the life of the process.  `scratch` is only a
+// host-side stand-in for it: its device address on a given GPU is asked for once per device (scratch_address, at
+// hisa_create, with that device current) and that pointer is what host code hands to kernels.
+static __device__ __align__(256) unsigned char scratch[HISA_NOALLOC_SCRATCH_BYTES];
+#define HISA_MAX_DEVICES 64
+static void* g_scratch_ptr[HISA_MAX_DEVICES];
+
+// device address of `scratch` on the current device
+static int scratch_address(hisa_ctx* ctx, int* device, void** ptr) {
+    int dev = -1;
+    HIP_TRY(ctx, hipGetDevice(&dev));
+    if (dev < 0 || dev >= HISA_MAX_DEVICES) return fail(ctx, HISA_ERR_HIP, "device ordinal %d out of range", dev);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(ctx, hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(ctx, HISA_ERR_HIP, "no device address for the static scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    *device = dev;
+    *ptr = g_scratch_ptr[dev];
+    return HISA_OK;
+}
 int fail(hisa_ctx* ctx, int code, const char* fmt, ...) {
     if (ctx) {
         char buf[512];
@@ -343,6 +366,7 @@ static int modup_table(hisa_ctx* ctx, int digit, int a, ConvTable** out) {
 }
 
 static int sample_secret(hisa_ctx* ctx);
+static int fp_post_tables(hisa_ctx* ctx, int l, double** post_q, double** post_p, bool lookup_only);
 
 extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** out) {
     if (!prm || !out) return HISA_ERR_ARG;
@@ -481,6 +505,12 @@ extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** 
     }
     HIP_TRY(ctx, hipMalloc((void**)&ctx->d_secret, (size_t)ctx->total * n * sizeof(u64)));
     TRY(sample_secret(ctx));
+    TRY(scratch_address(ctx, &ctx->device, &ctx->noalloc_ws));
+    if (ctx->tabs.fp_ok && ctx->dnum <= 8) {
+        // the small per-level tables of the fused key switch, so that no later call has to build (and allocate) one
+        double *pq, *pp;
+        for (uint32_t l = 1; l <= ctx->L; l++) TRY(fp_post_tables(ctx, (int)l, &pq, &pp, false));
+    }
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     return HISA_OK;
 }
@@ -1133,9 +1163,10 @@ static int key_switch_core(hisa_ctx* ctx, const u64* d, u64 d_bs, size_t B, int 
 }
 
 // (D_j/q_i)^-1 of every limb at level l (and (P/p_m)^-1 of the special primes) as centred doubles, device resident
-static int fp_post_tables(hisa_ctx* ctx, int l, double** post_q, double** post_p) {
+static int fp_post_tables(hisa_ctx* ctx, int l, double** post_q, double** post_p, bool lookup_only) {
     const u64 KEY = 4096 + (u64)l;
     auto it = ctx->aux.find(KEY);
+    if (it == ctx->aux.end() && lookup_only) return fail(ctx, HISA_ERR_ARG, "no conversion tables for level %d", l);
     if (it == ctx->aux.end()) {
         std::vector<double> t((size_t)l + ctx->K);
         const int digits = (l + (int)ctx->alpha - 1) / (int)ctx->alpha;
@@ -1165,14 +1196,24 @@ static int fp_post_tables(hisa_ctx* ctx, int l, double** post_q, double** post_p
 // ciphertexts can share the first: the conversion works coefficient by coefficient on centred values, so it commutes
 // with the automorphism, which then becomes a gather on the extended digits inside IP.
 struct FpExt {
-    Temp y, ext;
+    Temp y, ext;       // pooled buffers, or empty when the caller brought a workspace
+    double* yp;        // [B][l][N] centred doubles
+    u64* extp;         // [B][digits][l + K][N]
     int l, digits, ext_limbs;
     u64 ext_bs;
+    static size_t y_bytes(const hisa_ctx* ctx, size_t B, int l) { return B * (size_t)l * ctx->N * sizeof(double); }
+    static size_t ext_bytes(const hisa_ctx* ctx, size_t B, int l, int K, int alpha) {
+        return B * (size_t)((l + alpha - 1) / alpha) * (size_t)(l + K) * ctx->N * sizeof(u64);
+    }
     FpExt(hisa_ctx* ctx, size_t B, int l_, int K, int alpha)
-        : y(ctx, B * (size_t)l_ * ctx->N * sizeof(double)),
-          ext(ctx, B * (size_t)((l_ + alpha - 1) / alpha) * (size_t)(l_ + K) * ctx->N * sizeof(u64)),
+        : y(ctx, y_bytes(ctx, B, l_)), ext(ctx, ext_bytes(ctx, B, l_, K, alpha)),
+          yp(y.ok() ? y.as<double>() : nullptr), extp(ext.ok() ? ext.u() : nullptr),
           l(l_), digits((l_ + alpha - 1) / alpha), ext_limbs(l_ + K), ext_bs((u64)digits * ext_limbs * ctx->N) {}
-    bool ok() const { return y.ok() && ext.ok(); }
+    // the same two buffers inside memory the caller owns: nothing is allocated
+    FpExt(hisa_ctx* ctx, int l_, int K, int alpha, double* y_ws, u64* ext_ws)
+        : y(ctx, Temp::None()), ext(ctx, Temp::None()), yp(y_ws), extp(ext_ws),
+          l(l_), digits((l_ + alpha - 1) / alpha), ext_limbs(l_ + K), ext_bs((u64)digits * ext_limbs * ctx->N) {}
+    bool ok() const { return yp && extp; }
 };
 
 static FpArgs fp_base(hisa_ctx* ctx) {
@@ -1182,21 +1223,22 @@ static FpArgs fp_base(hisa_ctx* ctx) {
     return base;
 }
 
-static int key_switch_modup_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois, size_t B, FpExt& x) {
+static int key_switch_modup_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois, size_t B, FpExt& x, bool no_alloc = false) {
     const size_t n = ctx->N;
     const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total, l = x.l;
     const int log_n = (int)ctx->log_n;
     hipStream_t st = ctx->stream;
     double *post_q, *post_p;
-    TRY(fp_post_tables(ctx, l, &post_q, &post_p));
-    const FpArgs base = fp_base(ctx);
+    TRY(fp_post_tables(ctx, l, &post_q, &post_p, no_alloc));
+    FpArgs base = fp_base(ctx);
+    if (no_alloc) { base.scratch = nullptr; base.scratch_polys = 0; base.no_pair = 1; }
     {   // A
         FpArgs a = base;
         FpTask tk = {};
         tk.period = l;
         for (int i = 0; i < l; i++) { tk.pos[i] = (int16_t)i; tk.prime[i] = (int16_t)i; }
         a.in = d; a.in_bs = d_bs; a.galois = galois; a.post = post_q;
-        a.yout = x.y.as<double>(); a.yout_bs = (u64)l * n;
+        a.yout = x.yp; a.yout_bs = (u64)l * n;
         HIP_TRY(ctx, launch_ntt_fp(FP_INV_TO_Y, log_n, a, tk, B, st));
     }
     // B.  One launch per digit, or one for all digits (single target limbs) where that takes fewer rounds of
@@ -1214,12 +1256,18 @@ static int key_switch_modup_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois
     FpArgs a = base;
     FpTask tk = {};
     int cnt = 0;
-    a.y = x.y.as<double>(); a.y_bs = (u64)l * n; a.total = total;
-    a.out = x.ext.u(); a.out_bs = x.ext_bs;
+    a.y = x.yp; a.y_bs = (u64)l * n; a.total = total;
+    a.out = x.extp; a.out_bs = x.ext_bs;
     for (int j = 0; j < x.digits; j++) {
         const int lo = j * alpha, hi = std::min(lo + alpha, l);
         ConvTable* tab;
-        TRY(modup_table(ctx, j, hi - lo, &tab));
+        if (no_alloc) {   // built with the level's tables when the context was made
+            auto it = ctx->modup_tabs.find(std::make_pair(j, hi - lo));
+            if (it == ctx->modup_tabs.end()) return fail(ctx, HISA_ERR_ARG, "no conversion table for digit %d of %d limbs", j, hi - lo);
+            tab = &it->second;
+        } else {
+            TRY(modup_table(ctx, j, hi - lo, &tab));
+        }
         const int slot = one_launch ? j : 0;
         a.dg[slot].hat = tab->d_hat_f; a.dg[slot].y_pos0 = lo; a.dg[slot].conv_a = hi - lo;
         if (!one_launch) cnt = 0;
@@ -1242,22 +1290,26 @@ static int key_switch_modup_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois
 // IP, C, D.  `galois` is applied to the own-digit limbs read from d, to the addend, and (gather_ext) to the digits.
 // C, D: acc [B][2][l + K][N] (NTT form) -> out[B][2][l][N] = ModDown(acc) (+ addend, gathered through add_galois if set)
 int moddown_add_fp(hisa_ctx* ctx, const u64* acc, size_t B, int l, const u64* add, u64 add_bs, int add_polys, u64 add_galois,
-                   u64* out) {
+                   u64* out, double* y2_ws) {
     const size_t n = ctx->N;
     const int K = (int)ctx->K, L = (int)ctx->L, total = (int)ctx->total, ext_limbs = l + K, log_n = (int)ctx->log_n;
     hipStream_t st = ctx->stream;
-    Temp y2(ctx, B * 2 * (size_t)K * n * sizeof(double));
-    if (!y2.ok()) return HISA_ERR_OOM;
+    // y2_ws: the caller's memory for the conversion input ([B][2][K][N] doubles); then nothing is allocated here
+    const bool no_alloc = y2_ws != nullptr;
+    Temp y2_t(ctx, B * 2 * (size_t)K * n * sizeof(double), !no_alloc);
+    if (!no_alloc && !y2_t.ok()) return HISA_ERR_OOM;
+    double* y2 = no_alloc ? y2_ws : y2_t.as<double>();
     double *post_q, *post_p;
-    TRY(fp_post_tables(ctx, l, &post_q, &post_p));
-    const FpArgs base = fp_base(ctx);
+    TRY(fp_post_tables(ctx, l, &post_q, &post_p, no_alloc));
+    FpArgs base = fp_base(ctx);
+    if (no_alloc) { base.scratch = nullptr; base.scratch_polys = 0; base.no_pair = 1; }
     {   // C: batch entries are (ciphertext, b|a) pairs
         FpArgs a = base;
         FpTask tk = {};
         tk.period = K;
         for (int m = 0; m < K; m++) { tk.pos[m] = (int16_t)m; tk.prime[m] = (int16_t)(L + m); }
         a.in = acc; a.in_bs = (u64)ext_limbs * n; a.in_pos_shift = l; a.post = post_p;
-        a.yout = y2.as<double>(); a.yout_bs = (u64)K * n;
+        a.yout = y2; a.yout_bs = (u64)K * n;
         HIP_TRY(ctx, launch_ntt_fp(FP_INV_TO_Y, log_n, a, tk, B * 2, st));
     }
     {   // D
@@ -1265,7 +1317,7 @@ int moddown_add_fp(hisa_ctx* ctx, const u64* acc, size_t B, int l, const u64* ad
         FpTask tk = {};
         tk.period = l;
         for (int i = 0; i < l; i++) { tk.pos[i] = (int16_t)i; tk.prime[i] = (int16_t)i; }
-        a.y = y2.as<double>(); a.y_bs = (u64)K * n; a.y_pos0 = 0; a.conv_a = K; a.total = total; a.hat = ctx->moddown_tab->d_hat_f;
+        a.y = y2; a.y_bs = (u64)K * n; a.y_pos0 = 0; a.conv_a = K; a.total = total; a.hat = ctx->moddown_tab->d_hat_f;
         a.acc = acc; a.acc_bs = (u64)ext_limbs * n; a.acc_pos_shift = 0; a.pinv_tab = ctx->d_pinv_f;
         a.add = add; a.add_bs = add_bs; a.add_ps = (u64)l * n; a.add_div = 2; a.add_polys = add_polys; a.add_galois = add_galois;
         a.out = out; a.out_bs = (u64)l * n;
@@ -1346,15 +1398,19 @@ int moddown_rescale_fp(hisa_ctx* ctx, u64* acc, size_t B, int l, const u64* add,
 }
 
 static int key_switch_finish_fp(hisa_ctx* ctx, const FpExt& x, const u64* d, u64 d_bs, u64 galois, int gather_ext, size_t B,
-                                const SwitchKey& key, const u64* add, u64 add_bs, int add_polys, u64* out) {
+                                const SwitchKey& key, const u64* add, u64 add_bs, int add_polys, u64* out,
+                                u64* acc_ws = nullptr, double* y2_ws = nullptr) {
     const size_t n = ctx->N;
     const int K = (int)ctx->K, L = (int)ctx->L, alpha = (int)ctx->alpha, total = (int)ctx->total, l = x.l;
     const int ext_limbs = x.ext_limbs, log_n = (int)ctx->log_n;
-    Temp acc(ctx, B * 2 * (size_t)ext_limbs * n * sizeof(u64));
-    if (!acc.ok()) return HISA_ERR_OOM;
-    HIP_TRY(ctx, launch_inner_product_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, key.data, total, d,
-                                         d_bs, galois, gather_ext, acc.u(), (u64)2 * ext_limbs * n, B, log_n, ctx->stream));
-    return moddown_add_fp(ctx, acc.u(), B, l, add, add_bs, add_polys, galois, out);
+    // acc_ws, y2_ws: the caller's memory for the accumulators and the ModDown input; both or neither
+    if ((acc_ws == nullptr) != (y2_ws == nullptr)) return fail(ctx, HISA_ERR_ARG, "half a workspace");
+    Temp acc_t(ctx, B * 2 * (size_t)ext_limbs * n * sizeof(u64), acc_ws == nullptr);
+    if (!acc_ws && !acc_t.ok()) return HISA_ERR_OOM;
+    u64* acc = acc_ws ? acc_ws : acc_t.u();
+    HIP_TRY(ctx, launch_inner_product_fp(ctx->tabs.fprimes, x.extp, x.ext_bs, x.digits, l, K, L, alpha, key.data, total, d,
+                                         d_bs, galois, gather_ext, acc, (u64)2 * ext_limbs * n, B, log_n, ctx->stream));
+    return moddown_add_fp(ctx, acc, B, l, add, add_bs, add_polys, galois, out, y2_ws);
 }
 
 // IP, C, D for n_steps rotations of the same B ciphertexts in one set of launches (entries rotation-major): a
@@ -1371,11 +1427,11 @@ static int key_switch_finish_steps_fp(hisa_ctx* ctx, const FpExt& x, const u64* 
     Temp y2(ctx, E * 2 * (size_t)K * n * sizeof(double));
     if (!acc.ok() || !y2.ok()) return HISA_ERR_OOM;
     double *post_q, *post_p;
-    TRY(fp_post_tables(ctx, l, &post_q, &post_p));
+    TRY(fp_post_tables(ctx, l, &post_q, &post_p, false));
     const FpArgs base = fp_base(ctx);
     IpSteps steps = {};
     for (int s = 0; s < n_steps; s++) { steps.key[s] = keys[s]->data; steps.galois[s] = (uint32_t)galois[s]; }
-    HIP_TRY(ctx, launch_inner_product_steps_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, steps, n_steps,
+    HIP_TRY(ctx, launch_inner_product_steps_fp(ctx->tabs.fprimes, x.extp, x.ext_bs, x.digits, l, K, L, alpha, steps, n_steps,
                                                total, d, d_bs, acc.u(), (u64)2 * ext_limbs * n, B, log_n, st));
     {   // C
         FpArgs a = base;
@@ -1431,7 +1487,7 @@ int rotation_accumulators_fp(hisa_ctx* ctx, const u64* cts, u64 ct_bs, size_t B,
         const int cnt = std::min(FP_MAX_STEPS, n_steps - g0);
         IpSteps st = {};
         for (int k = 0; k < cnt; k++) { st.key[k] = ctx->keys.find(gs[g0 + k])->second.data; st.galois[k] = (uint32_t)gs[g0 + k]; }
-        HIP_TRY(ctx, launch_inner_product_steps_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, st, cnt, total,
+        HIP_TRY(ctx, launch_inner_product_steps_fp(ctx->tabs.fprimes, x.extp, x.ext_bs, x.digits, l, K, L, alpha, st, cnt, total,
                                                    c1, ct_bs, acc + (u64)g0 * B * acc_bs, acc_bs, B, (int)ctx->log_n, ctx->stream,
                                                    fold_c0 ? cts : nullptr, ctx->d_pmod));
     }
@@ -1478,7 +1534,7 @@ int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const i
     if (!x.ok() || !acc.ok() || !addend.ok()) return HISA_ERR_OOM;
     const u64* c1 = rot + (size_t)l * n;
     TRY(key_switch_modup_fp(ctx, c1, ct_bs, 0, E, x));
-    HIP_TRY(ctx, launch_inner_product_sum_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, st, n_steps, total,
+    HIP_TRY(ctx, launch_inner_product_sum_fp(ctx->tabs.fprimes, x.extp, x.ext_bs, x.digits, l, K, L, alpha, st, n_steps, total,
                                              c1, ct_bs, acc.u(), (u64)2 * ext_limbs * n, Bn, shared_input ? 1 : 0, (int)ctx->log_n,
                                              ctx->stream));
     HIP_TRY(ctx, launch_automorph_sum(ctx->d_primes, rot, ct_bs, n_steps, tab, plain, plain_bs, addend.u(), (u64)2 * l * n, Bn,
@@ -1507,7 +1563,7 @@ int relinearize_rescale_fp(hisa_ctx* ctx, const u64* cts3, u64 stride, size_t n_
     if (!x.ok() || !acc.ok()) return HISA_ERR_OOM;
     const u64* d2 = cts3 + 2 * lw;
     TRY(key_switch_modup_fp(ctx, d2, stride, 0, n_cts, x));
-    HIP_TRY(ctx, launch_inner_product_fp(ctx->tabs.fprimes, x.ext.u(), x.ext_bs, x.digits, l, K, L, alpha, it->second.data, total, d2,
+    HIP_TRY(ctx, launch_inner_product_fp(ctx->tabs.fprimes, x.extp, x.ext_bs, x.digits, l, K, L, alpha, it->second.data, total, d2,
                                          stride, 0, 0, acc.u(), (u64)2 * ext_limbs * n, n_cts, (int)ctx->log_n, ctx->stream));
     return moddown_rescale_fp(ctx, acc.u(), n_cts, l, cts3, stride, 2, out);
 }
@@ -1765,6 +1821,63 @@ extern "C" int hisa_rot_right_assign(hisa_ctx* ctx, hisa_ct* a, int32_t steps) {
     hisa_ct* tmp = nullptr;
     TRY(hisa_rot_right(ctx, a, steps, &tmp));
     adopt(ctx, a, tmp);
+    return HISA_OK;
+}
+
+// rotLeft of one ciphertext into an existing one, for callers that cannot allocate: the intermediates live in the
+// library's static scratch array, the small tables were built with the context, and the conversion kernels run one
+// target limb per task (the paired form parks partial sums in a buffer of its own).  Same launches otherwise, so the
+// result is bit for bit hisa_rot_left's.
+extern "C" int hisa_rot_left_noalloc(hisa_ctx* ctx, const hisa_ct* a, int32_t steps, hisa_ct* out) {
+    if (!ctx) return HISA_ERR_ARG;
+    if (!valid_ct(a) || !valid_ct(out)) return fail(ctx, HISA_ERR_ARG, "not a ciphertext");
+    if (a->polys != 2 || out->polys != 2) return fail(ctx, HISA_ERR_SIZE, "rotation needs two-polynomial ciphertexts");
+    if (a->limbs != out->limbs) return fail(ctx, HISA_ERR_LEVEL_MISMATCH, "output has %u limbs, input %u", out->limbs, a->limbs);
+    const size_t n = ctx->N;
+    const int l = (int)a->limbs, K = (int)ctx->K, alpha = (int)ctx->alpha;
+    const size_t words = ct_words(ctx, 2, (uint32_t)l);
+    if (a->data < out->data + words && out->data < a->data + words)
+        return fail(ctx, HISA_ERR_ARG, "input and output overlap");
+    const u64 g = galois_of(ctx, steps);
+    if (t_analysis) {
+        if (g) {
+            const int32_t half = (int32_t)(ctx->N / 2);
+            t_analysis->steps.insert(((steps % half) + half) % half);
+            t_analysis->c.rot_left += 1;
+            t_analysis->c.key_switch_calls += 1;
+        }
+        out->scale = a->scale;
+        return HISA_OK;
+    }
+    if (g == 0) {
+        HIP_TRY(ctx, hipMemcpyAsync(out->data, a->data, words * sizeof(u64), hipMemcpyDeviceToDevice, ctx->stream));
+        out->scale = a->scale;
+        return HISA_OK;
+    }
+    if (!fused_key_switch_available(ctx))
+        return fail(ctx, HISA_ERR_ARG, "hisa_rot_left_noalloc needs 2^12 <= N <= 2^15, every prime below 2^50 and dnum <= 8");
+    if (g_prof_on) return fail(ctx, HISA_ERR_ARG, "per-kernel timing creates events; switch it off for hisa_rot_left_noalloc");
+    auto it = ctx->keys.find(g);
+    if (it == ctx->keys.end()) return fail(ctx, HISA_ERR_NO_KEY, "no rotation key for %d slots (galois element %llu)", steps,
+                                           (unsigned long long)g);
+    int dev = -1;
+    HIP_TRY(ctx, hipGetDevice(&dev));
+    if (dev != ctx->device || !ctx->noalloc_ws) return fail(ctx, HISA_ERR_ARG, "the context lives on device %d, current is %d", ctx->device, dev);
+    // layout of the scratch array: y | ext | acc | y2, each 256-byte aligned
+    auto up = [](size_t b) { return (b + 255) & ~(size_t)255; };
+    const size_t y_b = up(FpExt::y_bytes(ctx, 1, l)), ext_b = up(FpExt::ext_bytes(ctx, 1, l, K, alpha));
+    const size_t acc_b = up((size_t)2 * (l + K) * n * sizeof(u64)), y2_b = up((size_t)2 * K * n * sizeof(double));
+    const size_t need = y_b + ext_b + acc_b + y2_b;
+    if (need > (size_t)HISA_NOALLOC_SCRATCH_BYTES)
+        return fail(ctx, HISA_ERR_SIZE, "a rotation at N = %zu, %d limbs, %d special primes needs %zu bytes of scratch; the static array holds %zu",
+                    n, l, K, need, (size_t)HISA_NOALLOC_SCRATCH_BYTES);
+    unsigned char* ws = (unsigned char*)ctx->noalloc_ws;
+    FpExt x(ctx, l, K, alpha, (double*)ws, (u64*)(ws + y_b));
+    const size_t lw = (size_t)l * n;
+    TRY(key_switch_modup_fp(ctx, a->data + lw, words, g, 1, x, true));
+    TRY(key_switch_finish_fp(ctx, x, a->data + lw, words, g, 0, 1, it->second, a->data, words, 1, out->data,
+                             (u64*)(ws + y_b + ext_b), (double*)(ws + y_b + ext_b + acc_b)));
+    out->scale = a->scale;
     return HISA_OK;
 }
 

@@ -135,6 +135,8 @@ struct hisa_ctx {
     std::unordered_map<size_t, std::vector<void*>> pool;
     size_t pool_bytes;
     u64 enc_counter;
+    int device = -1;              // the GPU the context lives on (current when it was made)
+    void* noalloc_ws = nullptr;   // that GPU's copy of the library's static scratch array (hisa_rot_left_noalloc)
     std::string err;
 };
 
@@ -161,7 +163,10 @@ void dev_release(hisa_ctx* ctx, DevBlock* b);
 struct Temp {  // pooled scratch buffer for the duration of one call
     hisa_ctx* ctx;
     DevBlock* blk;
+    struct None {};    // no buffer: the caller brought memory of its own
     Temp(hisa_ctx* c, size_t bytes) : ctx(c), blk(dev_alloc(c, bytes)) {}
+    Temp(hisa_ctx* c, None) : ctx(c), blk(nullptr) {}
+    Temp(hisa_ctx* c, size_t bytes, bool wanted) : ctx(c), blk(wanted ? dev_alloc(c, bytes) : nullptr) {}
     ~Temp() { dev_release(ctx, blk); }
     bool ok() const { return blk != nullptr; }
     u64* u() const { return (u64*)blk->ptr; }
@@ -207,7 +212,7 @@ int moddown_rescale_fp(hisa_ctx* ctx, u64* acc, size_t B, int l, const u64* add,
 // together with the divScalar by q_{l-1}: out [n][2][l - 1][N] = ((d0, d1) + KS_relin(d2)) / q_{l-1}.
 int relinearize_rescale_fp(hisa_ctx* ctx, const u64* cts3, u64 stride, size_t n, int l, u64* out);
 int moddown_add_fp(hisa_ctx* ctx, const u64* acc, size_t B, int l, const u64* add, u64 add_bs, int add_polys, u64 add_galois,
-                   u64* out);
+                   u64* out, double* y2_ws = nullptr);
 // exact integer nearest to the double v (ties away from zero), reduced modulo q
 u64 double_to_residue(double v, u64 q);
 
@@ -278,6 +283,7 @@ struct FpArgs {
     int n_digits;
     struct Digit { const double* hat; int y_pos0, conv_a; } dg[FP_MAX_DIGITS];
     double* scratch; int scratch_polys; // one polynomial of doubles per workgroup (at most scratch_polys workgroups)
+    int no_pair;                        // one target limb per task whatever the sizes: `scratch` is then never touched
     // final combine (FP_FWD_CONV_FINAL): batch entries are (ciphertext, polynomial) pairs
     const u64* acc; u64 acc_bs; int acc_pos_shift;
     const double* pinv_tab;            // [prime] P^-1 mod q, centred

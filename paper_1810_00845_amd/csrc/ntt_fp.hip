@@ -98,10 +98,11 @@ __device__ __forceinline__ void bstoref(rsrc_t r, uint32_t lane_off, uint32_t ro
 
 // Phase timestamps of one workgroup per launch, for tuning builds only (-DNTT_FP_TIMING)
 #ifdef NTT_FP_TIMING
-__device__ long long g_fp_stamps[16 * 4096];
+// [workgroup < 256][wave < 16][stamp < 16], the last task of each workgroup stays
+__device__ long long g_fp_stamps[256 * 16 * 16];
 #define STAMP(k)                                                                                   \
     do {                                                                                           \
-        if (threadIdx.x == 0 && blockIdx.x < 4096) g_fp_stamps[blockIdx.x * 16 + (k)] = wall_clock64(); \
+        if ((threadIdx.x & 63) == 0 && blockIdx.x < 256) g_fp_stamps[(blockIdx.x * 16 + (threadIdx.x >> 6)) * 16 + (k)] = wall_clock64(); \
     } while (0)
 #else
 #define STAMP(k) do { } while (0)
@@ -261,6 +262,15 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     typedef Geo<K3> G;
     extern __shared__ uint32_t lds[];
     const int t = threadIdx.x;
+#ifdef NTT_FP_PRIO
+    {   // experiment: skew the waves of a SIMD by giving them different issue priorities
+        const int w = NTT_FP_PRIO == 1 ? (t >> 8) & 3 : (t >> 6) & 3;
+        if (w == 0) __builtin_amdgcn_s_setprio(3);
+        else if (w == 1) __builtin_amdgcn_s_setprio(2);
+        else if (w == 2) __builtin_amdgcn_s_setprio(1);
+        else __builtin_amdgcn_s_setprio(0);
+    }
+#endif
     // Persistent workgroups: each loops over its share of the tasks, so consecutive tasks on a CU run back to back
     // (no dispatch gap, the stores of one overlap the loads of the next).  Workgroups go to the eight XCDs
     // round-robin by id; each XCD gets a contiguous range of tasks, so that tasks sharing inputs (all target
@@ -643,7 +653,7 @@ static bool pair_conversions(int log_n, int conv_a, int period, u64 n_batch) {
 template <int MODE>
 static hipError_t dispatch_k3(int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
     constexpr bool conv_mode = MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL;
-    if (conv_mode && (a.n_digits > 1 || !pair_conversions(log_n, a.conv_a, tk.period, n_batch))) {
+    if (conv_mode && (a.no_pair || a.n_digits > 1 || !pair_conversions(log_n, a.conv_a, tk.period, n_batch))) {
         switch (log_n) {
             case 12: return launch_one<2, MODE, !conv_mode>(a, tk, n_batch, st);
             case 13: return launch_one<3, MODE, !conv_mode>(a, tk, n_batch, st);
@@ -690,7 +700,8 @@ hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a_in, const FpTask& 
     if (mode == FP_FWD_PLAIN && !a.in) return hipErrorInvalidValue;
     if (mode == FP_INV_TO_Y && (!a.yout || !a.post)) return hipErrorInvalidValue;
     if (mode != FP_INV_TO_Y && !a.out) return hipErrorInvalidValue;
-    if (conv && (!a.y || !a.hat || a.conv_a <= 0 || a.total <= 0 || !a.scratch || a.scratch_polys < 8)) return hipErrorInvalidValue;
+    if (conv && (!a.y || !a.hat || a.conv_a <= 0 || a.total <= 0)) return hipErrorInvalidValue;
+    if (conv && !a.no_pair && (!a.scratch || a.scratch_polys < 8)) return hipErrorInvalidValue;
     if (mode == FP_FWD_CONV_FINAL && (!a.acc || !a.pinv_tab || (a.add && a.add_div <= 0))) return hipErrorInvalidValue;
     // rotation-major entries: every entry's rotation index must fall inside galois_tab
     if (mode == FP_FWD_CONV_FINAL && a.add && (a.step_B < 0 ||

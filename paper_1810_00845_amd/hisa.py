@@ -296,6 +296,10 @@ class Context:
     def rot_left_assign(self, a, steps): self._inplace("hisa_rot_left_assign", C.c_void_p(a.h), C.c_int32(steps))
     def rot_right_assign(self, a, steps): self._inplace("hisa_rot_right_assign", C.c_void_p(a.h), C.c_int32(steps))
 
+    def rot_left_noalloc(self, a, steps, out):
+        """rotLeft into the existing ciphertext `out`; the library allocates nothing on the device."""
+        self._inplace("hisa_rot_left_noalloc", C.c_void_p(a.h), C.c_int32(steps), C.c_void_p(out.h))
+
     def max_scalar_div(self, a, ub):
         d = C.c_uint64()
         self._ck(load().hisa_max_scalar_div(self._vp, C.c_void_p(a.h), C.c_double(ub), C.byref(d)))
