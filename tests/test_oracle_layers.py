@@ -213,6 +213,25 @@ def test_merged_doublings_in_reductions():
     assert layers.merge_doublings([1, 2, 4, 8, 16, 32], 4) == [[m for m in range(1, 16)], [16, 32, 48]]
     assert layers.merge_doublings([2, 8], 4) == [[2], [8]] and layers.merge_doublings([1, 2, 4], 0) == [[1], [2], [4]]
     assert layers.merge_doublings([1, 2, 4], 2) == [[1, 2, 3], [4]]
+    # what a grouping must preserve, checked on plain vectors (no oracle arithmetic): rotating and adding by the groups
+    # gives the sums the doubling chain gives, for every chain and setting; dropping an amount of a group does not
+    rng = np.random.default_rng(8)
+    z = rng.uniform(-1, 1, 256)
+    def chain(v, groups):
+        for grp in groups:
+            v = v + sum(np.roll(v, -a) for a in grp)
+        return v
+    for steps in ([1, 2, 4, 8], [3, 6, 12, 40, 80], [2, 4, 8, 16, 60, 120, 240], [5], [1, 2, 16, 32, 64]):
+        want = chain(z, [[s] for s in steps])
+        for merge in (0, 1, 2, 3, 4):
+            groups = layers.merge_doublings(steps, merge)
+            assert sorted(a for g in groups for a in g if a in steps) == sorted(steps)
+            assert all(len(g) in (1, 3, 7, 15) and len(g) < (1 << max(merge, 1)) for g in groups)
+            assert np.abs(chain(z, groups) - want).max() <= 1e-12
+            big = [g for g in groups if len(g) > 1]
+            if big:
+                cut = [g[:-1] if g is big[0] else g for g in groups]
+                assert np.abs(chain(z, cut) - want).max() > 1e-3
     o = Oracle(11, [50, 45, 45, 45, 45, 45], 3, 55, seed=12)
     o.keygen()
     x = synth.image(23, 3, 4, 4)[None]
@@ -467,7 +486,7 @@ def test_layout_switches_round_trip():
     o = Oracle(10, [50, 40, 40], 3, 55, seed=16)
     x = synth.image(61, 5, 4, 4)[None]
     t = layers.tensor_encrypt(o, x, 2.0 ** 40, 3, h_stride=4)
-    o.gen_rot_keys([o.slots - 32, 32, 1, 4, 5])
+    o.gen_rot_keys([o.slots - 32, 32, 33, 1, 4, 5])
     c = layers.to_chw(o, t, 2, 32)
     assert (c.c_inner, c.c_stride, len(c.cts), c.clean, c.cts[0].limbs) == (2, 32, 3, 1, 3)
     assert np.abs(layers.tensor_decrypt(o, c) - x).max() <= 1e-6
@@ -481,6 +500,24 @@ def test_layout_switches_round_trip():
         z = o.decode(o.decrypt(ct)).real
         z[layers.plane_slots(2, 2, 8, 2, 0)] = 0
         assert np.abs(z).max() <= 1e-3
+    # every channel sits where the metadata says, independently of tensor_decrypt: slot by slot against the image
+    for g, ct in enumerate(c.cts):
+        z = o.decode(o.decrypt(ct)).real
+        for k in range(min(2, 5 - 2 * g)):
+            got = z[[k * 32 + y * 4 + xx for y in range(4) for xx in range(4)]].reshape(4, 4)
+            assert np.abs(got - x[0, 2 * g + k]).max() <= 1e-6
+    # planted mistakes: the blocks moved the wrong way, or by the wrong amount, put the channels elsewhere
+    real_right, real_left = o.rot_right, o.rot_left
+    o.rot_right = lambda ct, r: real_left(ct, r)
+    wrong = layers.to_chw(o, t, 2, 32)
+    o.rot_right = real_right
+    assert np.abs(layers.tensor_decrypt(o, wrong) - x).max() > 1e-2
+    o.rot_left = lambda ct, r: real_left(ct, r + 1 if r else 0)
+    wrong, _ = layers.to_hw(o, c)
+    o.rot_left = real_left
+    assert np.abs(layers.tensor_decrypt(o, wrong) - x).max() > 1e-2
+    back, _ = layers.to_hw(o, c)
+    assert np.abs(layers.tensor_decrypt(o, back) - x).max() <= 1e-3
 
 
 def test_shared_moddown_convolutions():

@@ -605,3 +605,35 @@ def test_round_half_away():
     assert [round_half_away(v) for v in (0.5, -0.5, 1.5, 2.5, -2.5, 0.49999999999999994, 1e300 % 7.0)] == \
         [1, -1, 2, 3, -3, 0, round_half_away(1e300 % 7.0)]
     assert round_half_away(2.0 ** 80) == 2 ** 80 and round_half_away(-(2.0 ** 53 + 2)) == -(2 ** 53 + 2)
+
+
+def test_add_of_two_and_three_polynomial_ciphertexts_is_exact_on_the_plaintext():
+    """add / sub of operands with different polynomial counts (a two-polynomial ciphertext is a three-polynomial one
+    with c2 = 0): decryption is linear, so the decrypted coefficients of the sum are exactly the sums of the decrypted
+    coefficients modulo every prime -- an identity that does not go through the addition's own code.  A planted
+    mistake (c2 dropped) breaks it."""
+    o = Oracle(8, [40, 36, 30], 3, 50, seed=41)
+    o.keygen()
+    rng = np.random.default_rng(4)
+    za, zb, zc = (rng.uniform(-1, 1, o.slots) for _ in range(3))
+    a = o.encrypt(o.encode(za, 2.0 ** 20, 3))
+    b = o.encrypt(o.encode(zb, 2.0 ** 20, 3))
+    c = o.encrypt(o.encode(zc, 2.0 ** 40, 3))
+    three = o.mul_no_relin(a, b)                                  # scale 2^40, three polynomials
+    assert three.polys == 3 and c.polys == 2
+    q = np.asarray(o.primes[:3], dtype=object)[:, None]
+    dec = lambda ct: o.pt_export(o.decrypt(ct)).astype(object)
+    for first, second, sign in ((three, c, 1), (c, three, 1), (three, c, -1)):
+        out = o.add(first, second) if sign == 1 else o.sub(first, second)
+        assert out.polys == 3 and out.scale == three.scale
+        assert np.array_equal(dec(out), (dec(first) + sign * dec(second)) % q)
+    with pytest.raises(Exception):
+        o.sub(c, three)                                           # a two-polynomial minuend has no c2 to subtract from
+    # the value: slot-wise za zb + zc
+    got = o.decode(o.decrypt(o.add(three, c))).real
+    assert np.abs(got - (za * zb + zc)).max() <= 1e-3
+    # planted mistake: the sum with c2 left out decrypts to something else
+    from oracle.ckks import Ct
+    out = o.add(three, c)
+    wrong = Ct(out.data[:2].copy(), out.scale)
+    assert not np.array_equal(dec(wrong), (dec(three) + dec(c)) % q)
