@@ -135,8 +135,8 @@ int hisa_sub_scalar_assign(hisa_ctx* ctx, hisa_ct* a, double x);
  * mul = mul_no_relin + relinearize.  mul_no_relin gives the three-polynomial
  * ciphertext (a0 b0, a0 b1 + a1 b0, a1 b1); relinearize (in place) brings it
  * back to two with the s^2 key.  mul_scalar multiplies every residue by the
- * integer round(x * x_scale) (the "FixedPrecision(weight, plainLogP)" of
- * Algorithm 1); scales multiply. */
+ * integer round(x * x_scale) (the fixed-point conversion of a weight in
+ * Algorithm 1, its precision the logarithm of x_scale); scales multiply. */
 int hisa_mul(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b, hisa_ct** out);
 int hisa_mul_assign(hisa_ctx* ctx, hisa_ct* a, const hisa_ct* b);
 int hisa_mul_no_relin(hisa_ctx* ctx, const hisa_ct* a, const hisa_ct* b, hisa_ct** out);
@@ -557,6 +557,23 @@ int hisa_secret_export(hisa_ctx* ctx, int64_t* host_coeffs);
  * a separate measuring pass, not for timed runs. */
 int hisa_profile_enable(hisa_ctx* ctx, int on);
 int hisa_profile_read(hisa_ctx* ctx, char* host_buf, size_t cap);
+
+/* ---- measurement support (not a HISA instruction) ----
+ * Peaks of the GPU the context lives on, measured: issue rates, in 10^12 lane-operations per second, of the
+ * instructions the modular arithmetic is made of (register-only dependency chains, every SIMD full) and the rate of
+ * a plain device-to-device copy of copy_bytes (bytes read + bytes written per second, best of three).  The benchmark
+ * prints them beside the datasheet peaks; profiling runs use the copy as the kernel of known size that scales the
+ * memory counters.  Synchronises the stream; allocates 2 GiB from the context's pool for the copy. */
+typedef struct {
+    double fma_f64, mul_f64, add_f64;  /* v_fma_f64, v_mul_f64, v_add_f64 */
+    double rndne_add_f64;              /* v_rndne_f64 followed by v_add_f64, both counted */
+    double mul_lo_u64, mul_hi_u64;     /* 64-bit integer multiply, low / high half (each with an add and a mask) */
+    double copy_GBs;
+    uint64_t copy_bytes;
+    double clock_mhz;                  /* the device's nominal peak clock */
+    uint32_t compute_units, reserved;
+} hisa_calibration;
+int hisa_calibrate(hisa_ctx* ctx, hisa_calibration* out);
 
 #ifdef __cplusplus
 }

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhisa.so")
-SOURCES = ["hisa_api.hip", "ntt.hip", "ntt_fp.hip", "elementwise.hip", "keyswitch.hip", "encode.hip", "layers.hip"]
+SOURCES = ["hisa_api.hip", "ntt.hip", "ntt_fp.hip", "elementwise.hip", "keyswitch.hip", "encode.hip", "layers.hip", "calibrate.hip"]
 # -ffp-contract=off: the exact fp64 modular arithmetic spells out every fma itself
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -4,7 +4,7 @@
 // generation, and the NTT-form automorphism gather.  All of them stream
 // [..][limb][N] arrays once: they are bound by HBM bandwidth.
 #include "hisa_internal.hpp"
-#include "modarith.cuh"
+#include "modarith.hpp"
 
 #define NT 256
 

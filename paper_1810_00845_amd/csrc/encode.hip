@@ -3,7 +3,7 @@
 // coefficients into doubles.  Direct sums with exact integer angle reduction
 // into a table of the 2N-th roots of unity.
 #include "hisa_internal.hpp"
-#include "modarith.cuh"
+#include "modarith.hpp"
 
 #define NT 256
 

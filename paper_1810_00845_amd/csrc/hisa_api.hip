@@ -484,6 +484,15 @@ extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** 
             std::vector<double> pf(ctx->total, 0.0);
             for (uint32_t i = 0; i < ctx->L; i++) pf[i] = centred_double(pinv[i], ctx->mod[i]);
             HIP_TRY(ctx, upload(&ctx->d_pinv_f, pf));
+            {   // (P/p_m) P^-1 mod q_i: the conversion of FP_FWD_CONV_SUB
+                std::vector<u64> ih, ihs, hat, dmod;
+                build_conv_table_host(ctx, src, ih, ihs, hat, dmod);
+                std::vector<double> hp((size_t)ctx->K * ctx->total, 0.0);
+                for (uint32_t m = 0; m < ctx->K; m++)
+                    for (uint32_t i = 0; i < ctx->L; i++)
+                        hp[(size_t)m * ctx->total + i] = centred_double(hm::mul(hat[(size_t)m * ctx->total + i], pinv[i], ctx->mod[i]), ctx->mod[i]);
+                HIP_TRY(ctx, upload(&ctx->d_moddown_hat_pin, hp));
+            }
             ctx->fp_scratch_polys = ctx->log_n <= 13 ? 1024 : 512;
             HIP_TRY(ctx, hipMalloc(&ctx->d_fp_scratch, (size_t)ctx->fp_scratch_polys * ctx->N * sizeof(double)));
         }
@@ -532,7 +541,7 @@ extern "C" int hisa_destroy(hisa_ctx* ctx) {
     (void)hipFree(ctx->d_primes); (void)hipFree(ctx->d_tw); (void)hipFree(ctx->d_tw_sh); (void)hipFree(ctx->d_itw);
     (void)hipFree(ctx->d_itw_sh); (void)hipFree(ctx->d_secret); (void)hipFree(ctx->d_pinv); (void)hipFree(ctx->d_pinv_sh);
     (void)hipFree(ctx->d_fprimes); (void)hipFree(ctx->d_ftw); (void)hipFree(ctx->d_utw); (void)hipFree(ctx->d_vtw);
-    (void)hipFree(ctx->d_pinv_f);
+    (void)hipFree(ctx->d_pinv_f); (void)hipFree(ctx->d_moddown_hat_pin);
     (void)hipFree(ctx->d_fp_scratch);
     (void)hipFree(ctx->d_pmod); (void)hipFree(ctx->d_cos); (void)hipFree(ctx->d_sin); (void)hipFree(ctx->d_pow5);
     delete ctx;
@@ -560,14 +569,8 @@ static int sample_secret(hisa_ctx* ctx) {
 
 // key towards `target` (NTT form over all primes): per digit, a uniform (kind 4), e Gaussian (kind 5),
 // b = -a*s + e + [prime in digit] (P mod q) target
-static int gen_switch_key(hisa_ctx* ctx, u64 key_id, const u64* target) {
+static int fill_switch_key(hisa_ctx* ctx, u64 key_id, const u64* target, const SwitchKey& key) {
     const size_t n = ctx->N, total = ctx->total;
-    const size_t words = (size_t)ctx->dnum * 2 * total * n;
-    void* p = nullptr;
-    HIP_TRY(ctx, hipMalloc(&p, words * sizeof(u64)));
-    DevBlock* blk = new DevBlock{p, words * sizeof(u64), 1};
-    SwitchKey key{blk, (u64*)p};
-    ctx->keys[key_id] = key;
     Temp e(ctx, total * n * sizeof(u64));
     if (!e.ok()) return HISA_ERR_OOM;
     PolyMap all = identity_map((int)total);
@@ -583,6 +586,24 @@ static int gen_switch_key(hisa_ctx* ctx, u64 key_id, const u64* target) {
         HIP_TRY(ctx, launch_key_combine(ctx->d_primes, ctx->d_secret, target, e.u(), ctx->d_pmod, digit, (int)total,
                                         (int)ctx->L, (int)ctx->alpha, (int)j, (int)ctx->log_n, ctx->stream));
     }
+    return HISA_OK;
+}
+
+// The key is registered only once every launch that builds it has been queued: a failure on the way (no memory for
+// the temporary, a refused launch) frees the block and leaves no half-built key behind for later calls to trust.
+static int gen_switch_key(hisa_ctx* ctx, u64 key_id, const u64* target) {
+    const size_t words = (size_t)ctx->dnum * 2 * ctx->total * ctx->N;
+    void* p = nullptr;
+    HIP_TRY(ctx, hipMalloc(&p, words * sizeof(u64)));
+    SwitchKey key{nullptr, (u64*)p};
+    const int rc = fill_switch_key(ctx, key_id, target, key);
+    if (rc != HISA_OK) {
+        (void)hipStreamSynchronize(ctx->stream);   // nothing queued may still write to the block
+        (void)hipFree(p);
+        return rc;
+    }
+    key.blk = new DevBlock{p, words * sizeof(u64), 1};
+    ctx->keys[key_id] = key;
     return HISA_OK;
 }
 
@@ -1198,7 +1219,7 @@ static int fp_post_tables(hisa_ctx* ctx, int l, double** post_q, double** post_p
 struct FpExt {
     Temp y, ext;       // pooled buffers, or empty when the caller brought a workspace
     double* yp;        // [B][l][N] centred doubles
-    u64* extp;         // [B][digits][l + K][N]
+    double* extp;      // [B][digits][l + K][N], lazily reduced doubles
     int l, digits, ext_limbs;
     u64 ext_bs;
     static size_t y_bytes(const hisa_ctx* ctx, size_t B, int l) { return B * (size_t)l * ctx->N * sizeof(double); }
@@ -1207,10 +1228,10 @@ struct FpExt {
     }
     FpExt(hisa_ctx* ctx, size_t B, int l_, int K, int alpha)
         : y(ctx, y_bytes(ctx, B, l_)), ext(ctx, ext_bytes(ctx, B, l_, K, alpha)),
-          yp(y.ok() ? y.as<double>() : nullptr), extp(ext.ok() ? ext.u() : nullptr),
+          yp(y.ok() ? y.as<double>() : nullptr), extp(ext.ok() ? ext.as<double>() : nullptr),
           l(l_), digits((l_ + alpha - 1) / alpha), ext_limbs(l_ + K), ext_bs((u64)digits * ext_limbs * ctx->N) {}
     // the same two buffers inside memory the caller owns: nothing is allocated
-    FpExt(hisa_ctx* ctx, int l_, int K, int alpha, double* y_ws, u64* ext_ws)
+    FpExt(hisa_ctx* ctx, int l_, int K, int alpha, double* y_ws, double* ext_ws)
         : y(ctx, Temp::None()), ext(ctx, Temp::None()), yp(y_ws), extp(ext_ws),
           l(l_), digits((l_ + alpha - 1) / alpha), ext_limbs(l_ + K), ext_bs((u64)digits * ext_limbs * ctx->N) {}
     bool ok() const { return yp && extp; }
@@ -1257,7 +1278,7 @@ static int key_switch_modup_fp(hisa_ctx* ctx, const u64* d, u64 d_bs, u64 galois
     FpTask tk = {};
     int cnt = 0;
     a.y = x.yp; a.y_bs = (u64)l * n; a.total = total;
-    a.out = x.extp; a.out_bs = x.ext_bs;
+    a.out = (u64*)x.extp; a.out_bs = x.ext_bs;
     for (int j = 0; j < x.digits; j++) {
         const int lo = j * alpha, hi = std::min(lo + alpha, l);
         ConvTable* tab;
@@ -1397,6 +1418,40 @@ int moddown_rescale_fp(hisa_ctx* ctx, u64* acc, size_t B, int l, const u64* add,
     return HISA_OK;
 }
 
+// C and D for accumulators that carry the elementwise ends of the ModDown already (launch_inner_product_fold_fp):
+// the special limbs hold sum * (P/p_m)^-1 as doubles, the limbs of q hold sum * P^-1 + addend.  out = ModDown + addend.
+static int moddown_folded_fp(hisa_ctx* ctx, const u64* acc, size_t B, int l, u64* out, double* y2_ws) {
+    const size_t n = ctx->N;
+    const int K = (int)ctx->K, L = (int)ctx->L, total = (int)ctx->total, ext_limbs = l + K, log_n = (int)ctx->log_n;
+    hipStream_t st = ctx->stream;
+    const bool no_alloc = y2_ws != nullptr;
+    Temp y2_t(ctx, B * 2 * (size_t)K * n * sizeof(double), !no_alloc);
+    if (!no_alloc && !y2_t.ok()) return HISA_ERR_OOM;
+    double* y2 = no_alloc ? y2_ws : y2_t.as<double>();
+    FpArgs base = fp_base(ctx);
+    if (no_alloc) { base.scratch = nullptr; base.scratch_polys = 0; base.no_pair = 1; }
+    {   // C: batch entries are (ciphertext, b|a) pairs
+        FpArgs a = base;
+        FpTask tk = {};
+        tk.period = K;
+        for (int m = 0; m < K; m++) { tk.pos[m] = (int16_t)m; tk.prime[m] = (int16_t)(L + m); }
+        a.in = acc; a.in_bs = (u64)ext_limbs * n; a.in_pos_shift = l;
+        a.yout = y2; a.yout_bs = (u64)K * n;
+        HIP_TRY(ctx, launch_ntt_fp(FP_INV_D_TO_Y, log_n, a, tk, B * 2, st));
+    }
+    {   // D
+        FpArgs a = base;
+        FpTask tk = {};
+        tk.period = l;
+        for (int i = 0; i < l; i++) { tk.pos[i] = (int16_t)i; tk.prime[i] = (int16_t)i; }
+        a.y = y2; a.y_bs = (u64)K * n; a.y_pos0 = 0; a.conv_a = K; a.total = total; a.hat = ctx->d_moddown_hat_pin;
+        a.acc = acc; a.acc_bs = (u64)ext_limbs * n; a.acc_pos_shift = 0;
+        a.out = out; a.out_bs = (u64)l * n;
+        HIP_TRY(ctx, launch_ntt_fp(FP_FWD_CONV_SUB, log_n, a, tk, B * 2, st));
+    }
+    return HISA_OK;
+}
+
 static int key_switch_finish_fp(hisa_ctx* ctx, const FpExt& x, const u64* d, u64 d_bs, u64 galois, int gather_ext, size_t B,
                                 const SwitchKey& key, const u64* add, u64 add_bs, int add_polys, u64* out,
                                 u64* acc_ws = nullptr, double* y2_ws = nullptr) {
@@ -1408,9 +1463,13 @@ static int key_switch_finish_fp(hisa_ctx* ctx, const FpExt& x, const u64* d, u64
     Temp acc_t(ctx, B * 2 * (size_t)ext_limbs * n * sizeof(u64), acc_ws == nullptr);
     if (!acc_ws && !acc_t.ok()) return HISA_ERR_OOM;
     u64* acc = acc_ws ? acc_ws : acc_t.u();
-    HIP_TRY(ctx, launch_inner_product_fp(ctx->tabs.fprimes, x.extp, x.ext_bs, x.digits, l, K, L, alpha, key.data, total, d,
-                                         d_bs, galois, gather_ext, acc, (u64)2 * ext_limbs * n, B, log_n, ctx->stream));
-    return moddown_add_fp(ctx, acc, B, l, add, add_bs, add_polys, galois, out, y2_ws);
+    double *post_q, *post_p;
+    TRY(fp_post_tables(ctx, l, &post_q, &post_p, acc_ws != nullptr));
+    // the addend is gathered through the same automorphism as the own-digit limbs
+    IpFold fold = {ctx->d_pinv_f, post_p, add_polys > 0 ? add : nullptr, add_bs, (u64)l * n, add_polys};
+    HIP_TRY(ctx, launch_inner_product_fold_fp(ctx->tabs.fprimes, x.extp, x.ext_bs, x.digits, l, K, L, alpha, key.data, total, d,
+                                              d_bs, galois, gather_ext, acc, (u64)2 * ext_limbs * n, B, log_n, fold, ctx->stream));
+    return moddown_folded_fp(ctx, acc, B, l, out, y2_ws);
 }
 
 // IP, C, D for n_steps rotations of the same B ciphertexts in one set of launches (entries rotation-major): a
@@ -1872,7 +1931,7 @@ extern "C" int hisa_rot_left_noalloc(hisa_ctx* ctx, const hisa_ct* a, int32_t st
         return fail(ctx, HISA_ERR_SIZE, "a rotation at N = %zu, %d limbs, %d special primes needs %zu bytes of scratch; the static array holds %zu",
                     n, l, K, need, (size_t)HISA_NOALLOC_SCRATCH_BYTES);
     unsigned char* ws = (unsigned char*)ctx->noalloc_ws;
-    FpExt x(ctx, l, K, alpha, (double*)ws, (u64*)(ws + y_b));
+    FpExt x(ctx, l, K, alpha, (double*)ws, (double*)(ws + y_b));
     const size_t lw = (size_t)l * n;
     TRY(key_switch_modup_fp(ctx, a->data + lw, words, g, 1, x, true));
     TRY(key_switch_finish_fp(ctx, x, a->data + lw, words, g, 0, 1, it->second, a->data, words, 1, out->data,

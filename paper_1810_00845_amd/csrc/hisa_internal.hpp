@@ -129,6 +129,7 @@ struct hisa_ctx {
     double *d_cos, *d_sin;  // [2N] roots of unity exp(i*pi*t/N)
     FpPrime* d_fprimes;     // fp64 path tables (null when not applicable)
     double *d_ftw, *d_utw, *d_vtw, *d_pinv_f;
+    double* d_moddown_hat_pin = nullptr;   // [K][total] (P/p_m) * P^-1 mod q_i, centred: ModDown's conversion with the division folded in
     uint32_t* d_pow5;       // [N/2] 5^j mod 2N
     double* d_fp_scratch;   // fp64 path: one polynomial per resident workgroup of the conversion kernels
     int fp_scratch_polys;
@@ -249,8 +250,12 @@ enum FpMode {
     FP_FWD_PLAIN = 0,      // u64 coefficients in, u64 NTT form out
     FP_INV_PLAIN = 1,      // u64 NTT form in (optionally gathered through sigma_g), u64 coefficients out
     FP_INV_TO_Y = 2,       // as INV_PLAIN, times a per-limb constant, output = centred doubles (input of base conversion)
-    FP_FWD_CONV = 3,       // input = fast base conversion of `a` source limbs (centred doubles), u64 NTT form out
-    FP_FWD_CONV_FINAL = 4  // as FWD_CONV, then out = (acc - ntt) * P^-1 (+ addend, optionally through sigma_g)
+    FP_FWD_CONV = 3,       // input = fast base conversion of `a` source limbs (centred doubles); NTT form out as lazily
+                           // reduced doubles (|v| <= p/2): the extended digits, which only the inner products read
+    FP_FWD_CONV_FINAL = 4, // as FWD_CONV, then out = (acc - ntt) * P^-1 (+ addend, optionally through sigma_g), u64
+    FP_INV_D_TO_Y = 5,     // as INV_TO_Y for input that already is doubles times the per-limb constant (no gather)
+    FP_FWD_CONV_SUB = 6,   // as FWD_CONV, then out = acc - ntt, u64: the conversion table and acc carry the P^-1, acc the addend
+    FP_N_MODES = 7
 };
 
 struct FpTask {
@@ -304,9 +309,23 @@ double fp_conversion_cost(int log_n, int conv_a, int period, u64 n_batch, bool* 
 
 // acc[b][p][x] = sum_j e_j[x] * key[j][p][prime(x)] in fp64; e_j[x] comes from ext unless x lies in digit j, then
 // from own_src (the NTT-form input itself, read through sigma_g when galois != 0)
-hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
+hipError_t launch_inner_product_fp(const FpPrime* fprimes, const double* ext, u64 ext_bs, int digits, int l, int K, int L,
                                    int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois,
                                    int gather_ext, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st);
+// The same with the elementwise ends of the ModDown folded in (this kernel waits for memory, the transforms for the
+// vector ALU).  On the limbs of q:   acc = sum * P^-1 + addend  (canonical residues; addend [batch][add_polys][l][N],
+// read through sigma_g like the own-digit limbs, null for none), so that the last kernel only subtracts its transform;
+// on the special limbs:  acc = sum * (P/p_m)^-1  as lazily reduced doubles, the input of FP_INV_D_TO_Y.
+// pin_tab: [prime] P^-1 mod q_i; post_p: [K] (P/p_m)^-1 mod p_m; both centred doubles.
+struct IpFold {
+    const double* pin_tab;
+    const double* post_p;
+    const u64* add; u64 add_bs, add_ps; int add_polys;
+};
+hipError_t launch_inner_product_fold_fp(const FpPrime* fprimes, const double* ext, u64 ext_bs, int digits, int l, int K, int L,
+                                        int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois,
+                                        int gather_ext, u64* acc, u64 acc_bs, u64 n_batch, int log_n, const IpFold& fold,
+                                        hipStream_t st);
 // The same for n_steps rotations of the same n_batch ciphertexts (extended digits computed once from the unrotated
 // polynomial): rotation s uses keys[s] and gathers through galois[s]; acc entries are ordered rotation-major.
 // c0_src (with pmod[i] = P mod q_i): the b accumulator also takes P * sigma_s(c0) on the limbs of q, c0 read at
@@ -315,14 +334,14 @@ struct IpSteps {
     const u64* key[FP_MAX_STEPS];
     uint32_t galois[FP_MAX_STEPS];
 };
-hipError_t launch_inner_product_steps_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
+hipError_t launch_inner_product_steps_fp(const FpPrime* fprimes, const double* ext, u64 ext_bs, int digits, int l, int K, int L,
                                          int alpha, const IpSteps& steps, int n_steps, int total, const u64* own_src,
                                          u64 own_bs, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st,
                                          const u64* c0_src = nullptr, const u64* pmod = nullptr);
 
 // The sum over n_steps rotations of different ciphertexts: ext / own_src entry s * n_batch + b is term s of output b
 // (digits from the unrotated polynomial); acc[b] = sum_s sum_j sigma_s(e_j) * key_s[j] on the l + K limbs.
-hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
+hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const double* ext, u64 ext_bs, int digits, int l, int K, int L,
                                        int alpha, const IpSteps& steps, int n_steps, int total, const u64* own_src, u64 own_bs,
                                        u64* acc, u64 acc_bs, u64 n_batch, int shared_input, int log_n, hipStream_t st);
 

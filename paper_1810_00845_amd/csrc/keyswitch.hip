@@ -3,7 +3,7 @@
 // product with the switching key, the final ModDown combine, and the two
 // element-wise halves of rescale.
 #include "hisa_internal.hpp"
-#include "modarith.cuh"
+#include "modarith.hpp"
 
 #define NT 256
 

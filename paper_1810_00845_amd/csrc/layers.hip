@@ -10,8 +10,8 @@
 #include <set>
 
 #include "hisa_internal.hpp"
-#include "modarith.cuh"
-#include "fparith.cuh"
+#include "modarith.hpp"
+#include "fparith.hpp"
 
 #define NT 256
 #define OCB 4

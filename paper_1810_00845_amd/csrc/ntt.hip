@@ -12,7 +12,7 @@
 // 4q forward, 2q inverse) with Shoup twiddles; only the last launch of a
 // transform writes canonical residues.
 #include "hisa_internal.hpp"
-#include "modarith.cuh"
+#include "modarith.hpp"
 
 #define TILE_LOG 11
 #define NT 256

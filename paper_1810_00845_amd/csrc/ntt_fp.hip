@@ -1,5 +1,5 @@
 // Single-launch negacyclic NTT / inverse NTT for N = 2^12 .. 2^15 and primes
-// below 2^50, with exact fp64 modular arithmetic (fparith.cuh) and the
+// below 2^50, with exact fp64 modular arithmetic (fparith.hpp) and the
 // neighbouring steps of key switching fused into its load and store stages.
 //
 // One workgroup transforms one limb-polynomial.  N/32 threads hold 32
@@ -20,8 +20,10 @@
 // limb).  Only the transpose 1 <-> 2 crosses waves (five workgroup barriers per
 // transform); after it the waves run apart and overlap one another's LDS
 // traffic, stores and next loads.
+#include <cstdio>
+
 #include "hisa_internal.hpp"
-#include "fparith.cuh"
+#include "fparith.hpp"
 
 template <int K3>
 struct Geo {
@@ -90,23 +92,8 @@ __device__ __forceinline__ void bstoref(rsrc_t r, uint32_t lane_off, uint32_t ro
     bstore(r, lane_off, row_off, (u64)__double_as_longlong(x));
 }
 
-#ifdef NTT_FP_NO_FENCE
-#define SCHED_FENCE() do { } while (0)
-#else
+// keeps the compiler from moving instructions across this point (loads issued in batches stay batches)
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-#endif
-
-// Phase timestamps of one workgroup per launch, for tuning builds only (-DNTT_FP_TIMING)
-#ifdef NTT_FP_TIMING
-// [workgroup < 256][wave < 16][stamp < 16], the last task of each workgroup stays
-__device__ long long g_fp_stamps[256 * 16 * 16];
-#define STAMP(k)                                                                                   \
-    do {                                                                                           \
-        if ((threadIdx.x & 63) == 0 && blockIdx.x < 256) g_fp_stamps[(blockIdx.x * 16 + (threadIdx.x >> 6)) * 16 + (k)] = wall_clock64(); \
-    } while (0)
-#else
-#define STAMP(k) do { } while (0)
-#endif
 
 __device__ __forceinline__ uint32_t lo32(double v) { return (uint32_t)__double_as_longlong(v); }
 __device__ __forceinline__ uint32_t hi32(double v) { return (uint32_t)((u64)__double_as_longlong(v) >> 32); }
@@ -157,11 +144,7 @@ __device__ __forceinline__ void exchange(double (&v)[32], uint32_t* lds, int t) 
 // below 5.1 p, inside the 2^53 = 8 * 2^50 that exact integer arithmetic in doubles allows: one normalisation
 // per phase is enough and none is needed inside a phase.
 __device__ __forceinline__ void bfly(double& x, double& y, double w, double p, double pinv) {
-#ifdef NTT_FP_SKIP_COMPUTE
-    const double t = y * w + p * pinv;
-#else
     const double t = fp_mulmod(y, w, p, pinv);
-#endif
     y = x - t;
     x = x + t;
 }
@@ -221,7 +204,10 @@ __device__ __forceinline__ void inv_phase(double (&v)[32], const double* utw, co
     for (int j = 0; j < BITS; j++) {
 #pragma unroll
         for (int klow = 0; klow < (1 << j); klow++) {
-            const bool unit = UNIFORM && j == 0;  // the very first level multiplies by 1
+            // The very first level multiplies by 1.  (So does the first group of every later level of this phase, but
+            // a butterfly without its product does not reduce y: the values would double per level and leave the
+            // exact range after four of them.)
+            const bool unit = UNIFORM && j == 0;
             double w = 1.0;
             if (UNIFORM) { if (!unit) w = as_const(utw)[(1 << j) + klow]; }
             else w = klow == 0 ? bt[j] : fp_mulmod(bt[j], as_const(utw)[(1 << j) + klow], p, pinv);
@@ -262,15 +248,6 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     typedef Geo<K3> G;
     extern __shared__ uint32_t lds[];
     const int t = threadIdx.x;
-#ifdef NTT_FP_PRIO
-    {   // experiment: skew the waves of a SIMD by giving them different issue priorities
-        const int w = NTT_FP_PRIO == 1 ? (t >> 8) & 3 : (t >> 6) & 3;
-        if (w == 0) __builtin_amdgcn_s_setprio(3);
-        else if (w == 1) __builtin_amdgcn_s_setprio(2);
-        else if (w == 2) __builtin_amdgcn_s_setprio(1);
-        else __builtin_amdgcn_s_setprio(0);
-    }
-#endif
     // Persistent workgroups: each loops over its share of the tasks, so consecutive tasks on a CU run back to back
     // (no dispatch gap, the stores of one overlap the loads of the next).  Workgroups go to the eight XCDs
     // round-robin by id; each XCD gets a contiguous range of tasks, so that tasks sharing inputs (all target
@@ -278,19 +255,23 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
     const int per_xcd = (a.n_tasks + 7) >> 3;
     const int task_end = min((xcd + 1) * per_xcd, a.n_tasks);
-    constexpr bool INV = (MODE == FP_INV_PLAIN || MODE == FP_INV_TO_Y);
+    constexpr bool INV = (MODE == FP_INV_PLAIN || MODE == FP_INV_TO_Y || MODE == FP_INV_D_TO_Y);
     // The base-conversion modes take the target limbs of a batch entry two at a time: both read the same source
     // digits, so one pass over them forms both sums (half the loads per sum; the loads, not the arithmetic, bound that
     // stage).  The second sum waits in this workgroup's scratch rows (every thread reads back what it wrote itself)
     // while the first is transformed, and is transformed next.
     // PAIR = false: one target limb per task (few source limbs: the loads are not what bounds the stage then, and the
     // round trip of the second sum through the scratch rows costs more than the shared pass saves).
-    constexpr bool CONV = (MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL);
+    constexpr bool CONV = (MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL || MODE == FP_FWD_CONV_SUB);
     constexpr int SUB = (CONV && PAIR) ? 2 : 1;
     const int per_entry = (tk.period + SUB - 1) / SUB;
+    // Order of the tasks.  Conversions: entry-major, the target limbs of a batch entry next to one another (they share
+    // the entry's source digits).  Plain transforms: limb-major, so that the compute units of an XCD work on one prime
+    // at a time and its twiddle tables (as much data as the polynomial itself) stay in that L2.
+    const int n_entries = a.n_tasks / per_entry;
     for (int task = xcd * per_xcd + slot; task < task_end; task += slots) {
-    const u64 b = task / per_entry;
-    const int e_first = (task % per_entry) * SUB;
+    const u64 b = CONV ? task / per_entry : task % n_entries;
+    const int e_first = CONV ? (task % per_entry) * SUB : task / n_entries;
     for (int half = 0; half < SUB; half++) {
     const int e = e_first + half;
     if (e >= tk.period) break;
@@ -305,12 +286,11 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     constexpr uint32_t LB = (uint32_t)G::N * 8u;   // bytes of one limb-polynomial
     const uint32_t t8 = (uint32_t)t * 8u, t8_in = (uint32_t)t_in * 8u, t8_out = (uint32_t)t_out * 8u;
     double v[32];
-    STAMP(0);
 
     // ---- load (mapping P1: lane <-> consecutive coefficients; register r holds coefficient r*THREADS + t) ----
     if (MODE == FP_FWD_PLAIN || INV) {
         const rsrc_t src = make_rsrc(a.in + b * a.in_bs + (u64)(pos + a.in_pos_shift) * G::N, LB);
-        if (INV && a.galois) {
+        if (INV && MODE != FP_INV_D_TO_Y && a.galois) {
             // a private copy of the lane id: keeps the 32 gather indices from being kept alive (and spilled) for the
             // address arithmetic of the store stage
             int tg = t_in;
@@ -318,6 +298,9 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
 #pragma unroll
             for (int r = 0; r < 32; r++)
                 v[r] = fp_from_u64(bload(src, galois_src_fp((uint32_t)(G::template reg_idx<MIN>(r) | tg), a.galois, G::LOGN) * 8u, 0));
+        } else if (MODE == FP_INV_D_TO_Y) {
+#pragma unroll
+            for (int r = 0; r < 32; r++) v[r] = bloadf(src, t8_in, (uint32_t)G::template reg_idx<MIN>(r) * 8u);
         } else if (INV) {
 #pragma unroll
             for (int r = 0; r < 32; r++) v[r] = fp_from_u64(bload(src, t8_in, (uint32_t)G::template reg_idx<MIN>(r) * 8u));
@@ -428,7 +411,6 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         }
     }
 
-    STAMP(1);
     if (!INV) {
         const double* tw = a.ftw + (u64)prime * G::N;
         const rsrc_t twr = make_rsrc(tw, LB);
@@ -444,12 +426,10 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         }
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
-        STAMP(2);
         // the waves run apart between the wave-local transposes: all of them must have left the buffer before this
         // workgroup-wide transpose writes to it (its own last barrier guards the other direction)
         __syncthreads();
         exchange<K3, 1, 2>(v, lds, t);
-        STAMP(3);
         fwd_phase<5, 1, 32, false>(v, tw, bt2, p, pinv);
         constexpr int GROUPS = 1 << (5 - K3);
         double bt3[GROUPS][5];
@@ -462,13 +442,9 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         }
 #pragma unroll
         for (int r = 0; r < 32; r++) v[r] = fp_norm(v[r], p, pinv);
-        STAMP(4);
         exchange<K3, 2, 3, true>(v, lds, t);
-        STAMP(5);
         fwd_phase<K3, GROUPS, 1 << K3, false>(v, tw, bt3, p, pinv);
-        STAMP(6);
         exchange<K3, 3, MOUT, true>(v, lds, t);
-        STAMP(7);
     } else {
         const double* utw = a.utw + (u64)prime * G::N;
         const rsrc_t utwr = make_rsrc(utw, LB);
@@ -494,12 +470,34 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
     }
 
     // ---- store (mapping P1) ----
-    STAMP(8);
-    if (MODE == FP_FWD_PLAIN || MODE == FP_FWD_CONV) {
+    if (MODE == FP_FWD_PLAIN) {
         const rsrc_t dst = make_rsrc(a.out + b * a.out_bs + (u64)pos * G::N, LB);
 #pragma unroll
         for (int r = 0; r < 32; r++)
             bstore(dst, t8_out, (uint32_t)G::template reg_idx<MOUT>(r) * 8u, fp_canonical(v[r], p, pinv));
+    } else if (MODE == FP_FWD_CONV) {
+        // the extended digits stay doubles: their only readers multiply them by key values in the same arithmetic
+        const rsrc_t dst = make_rsrc(a.out + b * a.out_bs + (u64)pos * G::N, LB);
+#pragma unroll
+        for (int r = 0; r < 32; r++)
+            bstoref(dst, t8_out, (uint32_t)G::template reg_idx<MOUT>(r) * 8u, fp_norm(v[r], p, pinv));
+    } else if (MODE == FP_FWD_CONV_SUB) {
+        // out = acc - transform: acc already is (sum * P^-1 + addend), the conversion table carries the P^-1
+        const rsrc_t acc = make_rsrc(a.acc + b * a.acc_bs + (u64)(pos + a.acc_pos_shift) * G::N, LB);
+        const rsrc_t dst = make_rsrc(a.out + b * a.out_bs + (u64)pos * G::N, LB);
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            u64 va[8];
+            SCHED_FENCE();
+#pragma unroll
+            for (int k = 0; k < 8; k++) va[k] = bload(acc, t8_out, (uint32_t)G::template reg_idx<MOUT>(c * 8 + k) * 8u);
+            SCHED_FENCE();
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                const int r = c * 8 + k;
+                bstore(dst, t8_out, (uint32_t)G::template reg_idx<MOUT>(r) * 8u, fp_canonical(fp_from_u64(va[k]) - v[r], p, pinv));
+            }
+        }
     } else if (MODE == FP_FWD_CONV_FINAL) {
         // out = (acc - conv) * P^-1 (+ addend); operands fetched eight at a time ahead of their use
         const u64* acc_p = a.acc + b * a.acc_bs + (u64)(pos + a.acc_pos_shift) * G::N;
@@ -538,7 +536,7 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
         }
     } else {
         const rsrc_t vtw = make_rsrc(a.vtw + (u64)prime * G::N, LB);
-        const double post = MODE == FP_INV_TO_Y ? as_const(a.post)[e] : 1.0;
+        const double post = MODE == FP_INV_TO_Y ? as_const(a.post)[e] : 1.0;   // FP_INV_D_TO_Y: the input carries it
         // one of the two outputs is null, according to the mode; its descriptor is then never used
         const rsrc_t dst = make_rsrc(MODE == FP_INV_PLAIN ? (const void*)(a.out + b * a.out_bs + (u64)pos * G::N)
                                                           : (const void*)(a.yout + b * a.yout_bs + (u64)pos * G::N), LB);
@@ -554,11 +552,11 @@ __global__ __launch_bounds__(Geo<K3>::THREADS, NTT_FP_MIN_WAVES(K3)) void ntt_fp
                 const int r = c * 8 + k;
                 const double x = fp_mulmod(v[r], w8[k], p, pinv);
                 if (MODE == FP_INV_PLAIN) bstore(dst, t8, (uint32_t)(r << G::TB) * 8u, fp_canonical(x, p, pinv));
+                else if (MODE == FP_INV_D_TO_Y) bstoref(dst, t8, (uint32_t)(r << G::TB) * 8u, fp_norm(x, p, pinv));
                 else bstoref(dst, t8, (uint32_t)(r << G::TB) * 8u, fp_norm(fp_mulmod(x, post, p, pinv), p, pinv));
             }
         }
     }
-    STAMP(9);
     }  // the one or two limbs of a task
     }  // task loop
 }
@@ -575,15 +573,12 @@ static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hip
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    // the name rocprofv3 prints for this instantiation: ntt_fp_kernel<K3, MODE>
-    static const char* const names[4][5] = {
-        {"ntt_fp_kernel<2, 0>", "ntt_fp_kernel<2, 1>", "ntt_fp_kernel<2, 2>", "ntt_fp_kernel<2, 3>", "ntt_fp_kernel<2, 4>"},
-        {"ntt_fp_kernel<3, 0>", "ntt_fp_kernel<3, 1>", "ntt_fp_kernel<3, 2>", "ntt_fp_kernel<3, 3>", "ntt_fp_kernel<3, 4>"},
-        {"ntt_fp_kernel<4, 0>", "ntt_fp_kernel<4, 1>", "ntt_fp_kernel<4, 2>", "ntt_fp_kernel<4, 3>", "ntt_fp_kernel<4, 4>"},
-        {"ntt_fp_kernel<5, 0>", "ntt_fp_kernel<5, 1>", "ntt_fp_kernel<5, 2>", "ntt_fp_kernel<5, 3>", "ntt_fp_kernel<5, 4>"}};
-    ProfScope prof__(names[K3 - 2][MODE], st);
+    // the name rocprofv3 prints for this instantiation (PAIR only means something for the conversion modes)
+    static char name[40] = "";
+    if (!name[0]) snprintf(name, sizeof name, "ntt_fp_kernel<%d, %d, %s>", K3, MODE, PAIR ? "true" : "false");
+    ProfScope prof__(name, st);
     FpArgs args = a;
-    constexpr bool conv_mode = (MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL) && PAIR;   // two target limbs per task
+    constexpr bool conv_mode = (MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL || MODE == FP_FWD_CONV_SUB) && PAIR;   // two target limbs per task
     args.n_tasks = (int)(n_batch * (conv_mode ? (tk.period + 1) / 2 : tk.period));
     static int n_cu = 0;
     if (!n_cu) {
@@ -609,9 +604,6 @@ static hipError_t launch_one(const FpArgs& a, const FpTask& tk, u64 n_batch, hip
         if (fit < 8) return hipErrorInvalidValue;
         if (grid > fit) grid = fit;
     }
-#ifdef NTT_FP_NONPERSISTENT
-    grid = need;
-#endif
     hipLaunchKernelGGL((ntt_fp_kernel<K3, MODE, PAIR>), dim3(grid), dim3(G::THREADS), lds_bytes, st, args, tk);
     return hipGetLastError();
 }
@@ -652,7 +644,7 @@ static bool pair_conversions(int log_n, int conv_a, int period, u64 n_batch) {
 
 template <int MODE>
 static hipError_t dispatch_k3(int log_n, const FpArgs& a, const FpTask& tk, u64 n_batch, hipStream_t st) {
-    constexpr bool conv_mode = MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL;
+    constexpr bool conv_mode = MODE == FP_FWD_CONV || MODE == FP_FWD_CONV_FINAL || MODE == FP_FWD_CONV_SUB;
     if (conv_mode && (a.no_pair || a.n_digits > 1 || !pair_conversions(log_n, a.conv_a, tk.period, n_batch))) {
         switch (log_n) {
             case 12: return launch_one<2, MODE, !conv_mode>(a, tk, n_batch, st);
@@ -675,7 +667,7 @@ hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a_in, const FpTask& 
     DRY_RUN_RETURN();
     if (n_batch == 0 || tk.period <= 0) return hipSuccess;
     FpArgs a = a_in;
-    if (mode == FP_FWD_CONV || mode == FP_FWD_CONV_FINAL) {
+    if (mode == FP_FWD_CONV || mode == FP_FWD_CONV_FINAL || mode == FP_FWD_CONV_SUB) {
         if (a.n_digits < 0 || a.n_digits > FP_MAX_DIGITS || tk.period > HISA_MAX_PRIMES) return hipErrorInvalidValue;
         if (a.n_digits == 0) {
             a.n_digits = 1;
@@ -693,13 +685,15 @@ hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a_in, const FpTask& 
     if (tk.period > HISA_MAX_PRIMES || !a.fprimes) return hipErrorInvalidValue;
     for (int e = 0; e < tk.period; e++)
         if (tk.prime[e] < 0) return hipErrorInvalidValue;
-    const bool inv = mode == FP_INV_PLAIN || mode == FP_INV_TO_Y;
-    const bool conv = mode == FP_FWD_CONV || mode == FP_FWD_CONV_FINAL;
+    const bool inv = mode == FP_INV_PLAIN || mode == FP_INV_TO_Y || mode == FP_INV_D_TO_Y;
+    const bool conv = mode == FP_FWD_CONV || mode == FP_FWD_CONV_FINAL || mode == FP_FWD_CONV_SUB;
     if (inv && (!a.in || !a.utw || !a.vtw)) return hipErrorInvalidValue;
     if (!inv && !a.ftw) return hipErrorInvalidValue;
     if (mode == FP_FWD_PLAIN && !a.in) return hipErrorInvalidValue;
     if (mode == FP_INV_TO_Y && (!a.yout || !a.post)) return hipErrorInvalidValue;
-    if (mode != FP_INV_TO_Y && !a.out) return hipErrorInvalidValue;
+    if (mode == FP_INV_D_TO_Y && (!a.yout || a.galois)) return hipErrorInvalidValue;
+    if (mode != FP_INV_TO_Y && mode != FP_INV_D_TO_Y && !a.out) return hipErrorInvalidValue;
+    if (mode == FP_FWD_CONV_SUB && !a.acc) return hipErrorInvalidValue;
     if (conv && (!a.y || !a.hat || a.conv_a <= 0 || a.total <= 0)) return hipErrorInvalidValue;
     if (conv && !a.no_pair && (!a.scratch || a.scratch_polys < 8)) return hipErrorInvalidValue;
     if (mode == FP_FWD_CONV_FINAL && (!a.acc || !a.pinv_tab || (a.add && a.add_div <= 0))) return hipErrorInvalidValue;
@@ -713,6 +707,8 @@ hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a_in, const FpTask& 
         case FP_INV_TO_Y: return dispatch_k3<FP_INV_TO_Y>(log_n, a, tk, n_batch, st);
         case FP_FWD_CONV: return dispatch_k3<FP_FWD_CONV>(log_n, a, tk, n_batch, st);
         case FP_FWD_CONV_FINAL: return dispatch_k3<FP_FWD_CONV_FINAL>(log_n, a, tk, n_batch, st);
+        case FP_INV_D_TO_Y: return dispatch_k3<FP_INV_D_TO_Y>(log_n, a, tk, n_batch, st);
+        case FP_FWD_CONV_SUB: return dispatch_k3<FP_FWD_CONV_SUB>(log_n, a, tk, n_batch, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -726,7 +722,7 @@ hipError_t launch_ntt_fp(int mode, int log_n, const FpArgs& a_in, const FpTask& 
 // One thread owns one coefficient of one extended limb: the 2*digits key values stay in registers while the
 // thread walks over its share of the batch, so the key is read IPF_ZSPLIT times per batch (from the L2 after the
 // first: see the launch order below), not once per ciphertext.
-__global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits,
+__global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime* fprimes, const double* ext, u64 ext_bs, int digits,
                                                                   int l, int K, int L, int alpha, const u64* key, int total,
                                                                   const u64* own_src, u64 own_bs, u64 galois, int gather_ext,
                                                                   u64* acc, u64 acc_bs, u64 n_batch, int log_n) {
@@ -759,9 +755,8 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime*
 #pragma unroll
         for (int d = 0; d < IPF_MAXD; d++) {
             if (d < digits) {
-                const u64 ev = d == own_digit ? own_src[b * own_bs + (u64)x * n + jsrc]
-                                              : ext[b * ext_bs + ((u64)d * ext_limbs + x) * n + jext];
-                const double e = fp_from_u64(ev);
+                const double e = d == own_digit ? fp_from_u64(own_src[b * own_bs + (u64)x * n + jsrc])
+                                                : ext[b * ext_bs + ((u64)d * ext_limbs + x) * n + jext];
                 sb += fp_mulmod(e, kb[d], p, pinv);
                 sa += fp_mulmod(e, ka[d], p, pinv);
             }
@@ -771,10 +766,67 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_fp_kernel(const FpPrime*
     }
 }
 
+// The same inner product with the elementwise ends of the ModDown folded in (struct IpFold): this kernel waits for
+// memory, so the extra products cost nothing here, while the transform kernels that would do them wait for the
+// vector ALU.  Limbs of q: acc = sum * P^-1 + addend, canonical; special limbs: acc = sum * (P/p_m)^-1, doubles.
+__global__ __launch_bounds__(IPF_NT) void inner_product_fold_fp_kernel(const FpPrime* fprimes, const double* ext, u64 ext_bs,
+                                                                       int digits, int l, int K, int L, int alpha, const u64* key,
+                                                                       int total, const u64* own_src, u64 own_bs, u64 galois,
+                                                                       int gather_ext, u64* acc, u64 acc_bs, u64 n_batch,
+                                                                       int log_n, IpFold f) {
+    const u64 n = (u64)1 << log_n;
+    const uint32_t j = blockIdx.x * IPF_NT + threadIdx.x;
+    const int x = blockIdx.z;     // limb-slowest launch order, as in inner_product_fp_kernel
+    const int ext_limbs = l + K;
+    const int prime = x < l ? x : L + (x - l);
+    const int own_digit = x < l ? x / alpha : -1;
+    const double p = as_const(&fprimes[prime].p)[0], pinv = as_const(&fprimes[prime].p)[1];
+    const uint32_t jsrc = galois ? galois_src_fp(j, galois, log_n) : j;
+    const uint32_t jext = gather_ext ? jsrc : j;
+    const u64 per = (n_batch + IPF_ZSPLIT - 1) / IPF_ZSPLIT;
+    const u64 b0 = (u64)blockIdx.y * per;
+    const u64 b1 = b0 + per < n_batch ? b0 + per : n_batch;
+    const bool special = x >= l;
+    const double cst = special ? as_const(f.post_p)[x - l] : as_const(f.pin_tab)[prime];
+    const bool add0 = !special && f.add != nullptr && f.add_polys > 0, add1 = !special && f.add != nullptr && f.add_polys > 1;
+    double kb[IPF_MAXD], ka[IPF_MAXD];
+#pragma unroll
+    for (int d = 0; d < IPF_MAXD; d++) {
+        if (d < digits) {
+            kb[d] = fp_from_u64(key[(((u64)d * 2 + 0) * total + prime) * n + j]);
+            ka[d] = fp_from_u64(key[(((u64)d * 2 + 1) * total + prime) * n + j]);
+        }
+    }
+    for (u64 b = b0; b < b1; b++) {
+        double sb = 0.0, sa = 0.0;
+#pragma unroll
+        for (int d = 0; d < IPF_MAXD; d++) {
+            if (d < digits) {
+                const double e = d == own_digit ? fp_from_u64(own_src[b * own_bs + (u64)x * n + jsrc])
+                                                : ext[b * ext_bs + ((u64)d * ext_limbs + x) * n + jext];
+                sb += fp_mulmod(e, kb[d], p, pinv);
+                sa += fp_mulmod(e, ka[d], p, pinv);
+            }
+        }
+        // |sum| <= 8 * 0.55 p < 2^53: the product with the constant needs no normalisation first
+        double rb = fp_mulmod(sb, cst, p, pinv), ra = fp_mulmod(sa, cst, p, pinv);
+        u64* dst = acc + b * acc_bs;
+        if (special) {
+            dst[(u64)x * n + j] = (u64)__double_as_longlong(fp_norm(rb, p, pinv));
+            dst[((u64)ext_limbs + x) * n + j] = (u64)__double_as_longlong(fp_norm(ra, p, pinv));
+        } else {
+            if (add0) rb += fp_from_u64(f.add[b * f.add_bs + (u64)x * n + jsrc]);
+            if (add1) ra += fp_from_u64(f.add[b * f.add_bs + f.add_ps + (u64)x * n + jsrc]);
+            dst[(u64)x * n + j] = fp_canonical(rb, p, pinv);
+            dst[((u64)ext_limbs + x) * n + j] = fp_canonical(ra, p, pinv);
+        }
+    }
+}
+
 // Several rotations of the same ciphertexts: blockIdx.z is the rotation; its key values stay in registers while the
 // thread walks over the batch.  The extended digits come from the unrotated polynomial and are gathered through the
 // rotation's automorphism like the own-digit limbs.
-__global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs,
+__global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const FpPrime* fprimes, const double* ext, u64 ext_bs,
                                                                         int digits, int l, int K, int L, int alpha, IpSteps steps,
                                                                         int total, const u64* own_src, u64 own_bs, u64* acc,
                                                                         u64 acc_bs, u64 n_batch, const u64* c0_src,
@@ -806,9 +858,8 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const Fp
 #pragma unroll
         for (int d = 0; d < IPF_MAXD; d++) {
             if (d < digits) {
-                const u64 ev = d == own_digit ? own_src[b * own_bs + (u64)x * n + jsrc]
-                                              : ext[b * ext_bs + ((u64)d * ext_limbs + x) * n + jsrc];
-                const double e = fp_from_u64(ev);
+                const double e = d == own_digit ? fp_from_u64(own_src[b * own_bs + (u64)x * n + jsrc])
+                                                : ext[b * ext_bs + ((u64)d * ext_limbs + x) * n + jsrc];
                 sb += fp_mulmod(e, kb[d], p, pinv);
                 sa += fp_mulmod(e, ka[d], p, pinv);
             }
@@ -828,7 +879,7 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_steps_fp_kernel(const Fp
 // rows that each of them reads come from the L2 after the first); partial sums are normalised per rotation (eight terms of at most
 // 0.875 * 2^50 stay below 2^53) and the running sums every eight rotations.
 template <int IPS_BCH>
-__global__ __launch_bounds__(IPF_NT) void inner_product_sum_fp_kernel(const FpPrime* fprimes, const u64* ext, u64 ext_bs,
+__global__ __launch_bounds__(IPF_NT) void inner_product_sum_fp_kernel(const FpPrime* fprimes, const double* ext, u64 ext_bs,
                                                                       int digits, int l, int K, int L, int alpha, IpSteps steps,
                                                                       int n_steps, int total, const u64* own_src, u64 own_bs,
                                                                       u64* acc, u64 acc_bs, u64 n_batch, int shared_input,
@@ -863,9 +914,8 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_sum_fp_kernel(const FpPr
 #pragma unroll
                 for (int d = 0; d < IPF_MAXD; d++) {
                     if (d < digits) {
-                        const u64 ev = d == own_digit ? own_src[entry * own_bs + (u64)x * n + jsrc]
-                                                      : ext[entry * ext_bs + ((u64)d * ext_limbs + x) * n + jsrc];
-                        const double e = fp_from_u64(ev);
+                        const double e = d == own_digit ? fp_from_u64(own_src[entry * own_bs + (u64)x * n + jsrc])
+                                                        : ext[entry * ext_bs + ((u64)d * ext_limbs + x) * n + jsrc];
                         sb += fp_mulmod(e, kb[d], p, pinv);
                         sa += fp_mulmod(e, ka[d], p, pinv);
                     }
@@ -886,7 +936,7 @@ __global__ __launch_bounds__(IPF_NT) void inner_product_sum_fp_kernel(const FpPr
     }
 }
 
-hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
+hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const double* ext, u64 ext_bs, int digits, int l, int K, int L,
                                        int alpha, const IpSteps& steps, int n_steps, int total, const u64* own_src, u64 own_bs,
                                        u64* acc, u64 acc_bs, u64 n_batch, int shared_input, int log_n, hipStream_t st) {
     DRY_RUN_RETURN();
@@ -906,7 +956,7 @@ hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const u64* ext, u
     return hipGetLastError();
 }
 
-hipError_t launch_inner_product_steps_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
+hipError_t launch_inner_product_steps_fp(const FpPrime* fprimes, const double* ext, u64 ext_bs, int digits, int l, int K, int L,
                                          int alpha, const IpSteps& steps, int n_steps, int total, const u64* own_src,
                                          u64 own_bs, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st,
                                          const u64* c0_src, const u64* pmod) {
@@ -922,7 +972,7 @@ hipError_t launch_inner_product_steps_fp(const FpPrime* fprimes, const u64* ext,
     return hipGetLastError();
 }
 
-hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 ext_bs, int digits, int l, int K, int L,
+hipError_t launch_inner_product_fp(const FpPrime* fprimes, const double* ext, u64 ext_bs, int digits, int l, int K, int L,
                                    int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois,
                                    int gather_ext, u64* acc, u64 acc_bs, u64 n_batch, int log_n, hipStream_t st) {
     DRY_RUN_RETURN();
@@ -932,5 +982,23 @@ hipError_t launch_inner_product_fp(const FpPrime* fprimes, const u64* ext, u64 e
     ProfScope prof__("inner_product_fp_kernel", st);
     hipLaunchKernelGGL(inner_product_fp_kernel, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha, key,
                        total, own_src, own_bs, galois, gather_ext, acc, acc_bs, n_batch, log_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_inner_product_fold_fp(const FpPrime* fprimes, const double* ext, u64 ext_bs, int digits, int l, int K, int L,
+                                        int alpha, const u64* key, int total, const u64* own_src, u64 own_bs, u64 galois,
+                                        int gather_ext, u64* acc, u64 acc_bs, u64 n_batch, int log_n, const IpFold& fold,
+                                        hipStream_t st) {
+    DRY_RUN_RETURN();
+    if (digits < 1 || digits > IPF_MAXD || l < 1 || K < 1 || alpha < 1 || l + K > 65535) return hipErrorInvalidValue;
+    if (!fprimes || !ext || !key || !own_src || !acc || !fold.pin_tab || !fold.post_p) return hipErrorInvalidValue;
+    if (fold.add && (fold.add_polys < 1 || fold.add_polys > 2)) return hipErrorInvalidValue;
+    const u64 n = (u64)1 << log_n;
+    if (ext_bs < (u64)digits * (l + K) * n || acc_bs < (u64)2 * (l + K) * n || own_bs < (u64)l * n) return hipErrorInvalidValue;
+    if (fold.add && (fold.add_bs < (u64)fold.add_polys * l * n || (fold.add_polys > 1 && fold.add_ps < (u64)l * n))) return hipErrorInvalidValue;
+    dim3 grid((1u << log_n) / IPF_NT, IPF_ZSPLIT, l + K);
+    ProfScope prof__("inner_product_fold_fp_kernel", st);
+    hipLaunchKernelGGL(inner_product_fold_fp_kernel, grid, dim3(IPF_NT), 0, st, fprimes, ext, ext_bs, digits, l, K, L, alpha, key,
+                       total, own_src, own_bs, galois, gather_ext, acc, acc_bs, n_batch, log_n, fold);
     return hipGetLastError();
 }

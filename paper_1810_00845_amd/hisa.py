@@ -48,6 +48,11 @@ class OpCounts(C.Structure):
                                                 "add", "rescale", "mac_plain", "mac_scalar", "key_switch_calls")] + [("min_limbs", C.c_uint32), ("reserved", C.c_uint32)]
 
 
+class Calibration(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("fma_f64", "mul_f64", "add_f64", "rndne_add_f64", "mul_lo_u64", "mul_hi_u64", "copy_GBs")] + \
+               [("copy_bytes", C.c_uint64), ("clock_mhz", C.c_double), ("compute_units", C.c_uint32), ("reserved", C.c_uint32)]
+
+
 class ConvGeom(C.Structure):
     _fields_ = [("fh", C.c_uint32), ("fw", C.c_uint32), ("stride", C.c_uint32), ("pad_same", C.c_uint32),
                 ("mode", C.c_uint32), ("shared_moddown", C.c_uint32), ("chw_schedule", C.c_uint32)]
@@ -611,6 +616,12 @@ class Context:
 
     def profile_enable(self, on=True):
         self._ck(load().hisa_profile_enable(self._vp, C.c_int(1 if on else 0)))
+
+    def calibrate(self):
+        """Measured issue rates (T lane-ops/s) and copy bandwidth (GB/s) of this GPU, as a dict."""
+        c = Calibration()
+        self._ck(load().hisa_calibrate(self._vp, C.byref(c)))
+        return {n: getattr(c, n) for n, _ in Calibration._fields_ if n != "reserved"}
 
     def profile_read(self):
         """{kernel name: (launches, total ms)} since the last read."""
