@@ -15,6 +15,7 @@ Prints ONE JSON line.  Besides the contract fields it carries
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -43,10 +44,15 @@ def algorithmic_bytes_rot_left(N, l, K, alpha, B):
     # kernel names as rocprofv3 prints them: ntt_fp_kernel<log2 N - 10, mode>; mode 2 = inverse transform to the
     # conversion input, 3 = base conversion + forward transform, 4 = the same + final combine
     k3 = "%d" % (N.bit_length() - 1 - 10)
-    out["ntt_fp_kernel<%s, 2>" % k3] = 2 * LP * B * (l + 2 * K)
+    # 2 = stage A (c1 to the conversion input), 5 = stage C (special limbs of the accumulators to the ModDown's
+    # conversion input), 6 = stage D (conversion + transform + subtraction from the folded accumulators)
+    out["ntt_fp_kernel<%s, 2>" % k3] = 2 * LP * B * l
+    out["ntt_fp_kernel<%s, 5>" % k3] = 2 * LP * B * 2 * K
     out["ntt_fp_kernel<%s, 3>" % k3] = LP * B * (l + conv_out)
     out["inner_product_fp_kernel"] = LP * (B * (conv_out + l + 2 * ext) + digits * 2 * ext)
+    out["inner_product_fold_fp_kernel"] = LP * (B * (conv_out + l + l + 2 * ext) + digits * 2 * ext)   # + the addend c0
     out["ntt_fp_kernel<%s, 4>" % k3] = LP * B * (2 * K + 2 * l + l + 2 * l)
+    out["ntt_fp_kernel<%s, 6>" % k3] = LP * B * (2 * K + 2 * l + 2 * l)
     return out
 
 
@@ -62,25 +68,68 @@ def algorithmic_flops_rot_left(N, l, K, alpha, B):
     ntt = 10 * (N // 2) * log_n
     k3 = "%d" % (log_n - 10)
     out = {}
-    out["ntt_fp_kernel<%s, 2>" % k3] = B * (l + 2 * K) * (ntt + 2 * 8 * N)          # + untwist and (D/q)^-1 products
+    out["ntt_fp_kernel<%s, 2>" % k3] = B * l * (ntt + 2 * 8 * N)                    # + untwist and (D/q)^-1 products
+    out["ntt_fp_kernel<%s, 5>" % k3] = B * 2 * K * (ntt + 8 * N)                    # + untwist
+    out["ntt_fp_kernel<%s, 6>" % k3] = B * 2 * l * (ntt + 9 * K * N + N)            # + acc - conv
+    out["inner_product_fold_fp_kernel"] = B * ext * N * 2 * (9 * digits + 8)
     out["ntt_fp_kernel<%s, 3>" % k3] = B * sum((ext - a) * (ntt + 9 * a * N) for a in sizes)
     out["ntt_fp_kernel<%s, 4>" % k3] = B * 2 * l * (ntt + 9 * K * N + 10 * N)       # + (acc - conv) P^-1 + addend
     out["inner_product_fp_kernel"] = B * ext * N * 2 * 9 * digits
     return out
 
 
-# Per launch on the headline configuration, from rocprofv3 --pmc runs (profiles/rot_left_n15_l16_dnum3_b64_fused_fp64.md):
-# HBM bytes = FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0 KiB (the factors a 1 GiB device-to-device copy reads back), and the
-# share of the CUs' vector-ALU issue slots in use = SQ_INSTS_VALU * 4 cycles / (4 SIMDs * SQ_BUSY_CU_CYCLES).
-MEASURED_TRAFFIC = {
-    "ntt_fp_kernel<5, 3>": (2 * 102268.1 + 360448.1) * 1024,      # mean of the three digits' launches (two paired, one not)
-    "ntt_fp_kernel<5, 4>": (2 * 644340.3 + 786432.0) * 1024,
-    "ntt_fp_kernel<5, 2>": (2 * 167592.6 + 230400.0) * 1024,
-    "inner_product_fp_kernel": (2 * 562991.9 + 720896.0) * 1024,
-}
-MEASURED_VALU_BUSY = {
-    "ntt_fp_kernel<5, 3>": 0.64, "ntt_fp_kernel<5, 4>": 0.55, "ntt_fp_kernel<5, 2>": 0.59, "inner_product_fp_kernel": 0.30,
-}
+COUNTER_FILE = os.path.join(ROOT, "profiles", "rot_left_n15_l16_dnum3_b64_counters.md")
+KERNEL_SOURCES = ("ntt_fp.hip", "fparith.hpp", "elementwise.hip")
+
+
+def kernel_source_sha():
+    """Short hash of the sources of the timed kernels: a counter summary names the hash it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_1810_00845_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def read_counters(path=COUNTER_FILE):
+    """Per-launch hardware counters of the headline configuration from the committed rocprofv3 summary (a table of
+    per-launch averages: FETCH_SIZE and WRITE_SIZE in KiB, SQ counters; the row of the library's copy kernel, which
+    moves a known 1 GiB each way, gives the factors that turn the memory counters into bytes).  Returns
+    ({kernel: {"traffic": bytes, "valu_issue_busy": share}}, source description) or ({}, reason)."""
+    if not os.path.exists(path):
+        return {}, {"file": None, "note": "no counter summary committed"}
+    rows, sha = {}, None
+    for line in open(path):
+        if line.startswith("kernel sources sha:"):
+            sha = line.split(":", 1)[1].strip()
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) == 7 and cells[0] not in ("kernel", "") and not set(cells[0]) <= set("-: "):
+            try:
+                rows[cells[0]] = [float(c) if c not in ("", "-") else None for c in cells[1:]]
+            except ValueError:
+                pass
+    copy = rows.get("copy_kernel")
+    if not copy or not copy[1] or not copy[2]:
+        return {}, {"file": os.path.relpath(path, ROOT), "note": "no copy_kernel row to scale the memory counters"}
+    gib_kib = float(1 << 20)
+    f_fetch, f_write = gib_kib / copy[1], gib_kib / copy[2]
+    out = {}
+    for name, (launches, fetch, write, valu, busy, wait_share) in rows.items():
+        d = {}
+        if fetch is not None and write is not None:
+            d["traffic"] = int((fetch * f_fetch + write * f_write) * 1024)
+        if valu is not None and busy:
+            d["valu_issue_busy"] = round(valu * 4 / (4 * busy), 3)   # 4 cycles per wave instruction, 4 SIMDs per CU
+        if wait_share is not None:
+            d["wait_share"] = wait_share
+        out[name] = d
+    src = {"file": os.path.relpath(path, ROOT), "measured_on_kernel_sources": sha, "current_kernel_sources": kernel_source_sha(),
+           "fetch_factor": round(f_fetch, 3), "write_factor": round(f_write, 3)}
+    src["stale"] = sha != src["current_kernel_sources"]
+    return out, src
+
+
 FP64_PEAK_TFLOPS = 78.6   # 256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz
 
 
@@ -198,9 +247,6 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=64, help="ciphertexts for the oracle baseline (0 = skip)")
     ap.add_argument("--no-ops", action="store_true", help="skip the per-primitive timings")
     ap.add_argument("--no-nets", action="store_true", help="skip the encrypted-network latencies")
-    ap.add_argument("--pmc-calibrate", action="store_true",
-                    help="also run device-to-device copies of 1 GiB (a plain copy of known size, to scale rocprofv3 "
-                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -244,54 +290,76 @@ def main():
     prof = ctx.profile_read()
     ctx.profile_enable(False)
     alg = algorithmic_bytes_rot_left(N, L, K, alpha, B)
-    kernels = {}
+    flops = algorithmic_flops_rot_left(N, L, K, alpha, B)
+    # the transform kernel's name carries a third template argument (two conversion targets per pass or one); the
+    # launches of a stage are summed whatever their form
+    merged = {}
     for name, (cnt, ms) in prof.items():
+        key = re.sub(r", (true|false)>$", ">", name)
+        c0, m0 = merged.get(key, (0, 0.0))
+        merged[key] = (c0 + cnt, m0 + ms)
+    kernels = {}
+    for name, (cnt, ms) in merged.items():
         per_step_ms = ms / prof_steps
         gbs = alg.get(name, 0) / (per_step_ms * 1e-3) / 1e9 if per_step_ms > 0 else 0.0
         kernels[name] = {"launches_per_step": cnt / prof_steps, "ms_per_step": round(per_step_ms, 4),
                          "avg_launch_us": round(1e3 * ms / cnt, 2), "algorithmic_GBs": round(gbs, 1)}
+        if name in flops and per_step_ms > 0:
+            kernels[name]["algorithmic_TFLOPs"] = round(flops[name] / (per_step_ms * 1e-3) / 1e12, 2)
     dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     headline = (log_n, L, dnum, B, args.bits) == (15, 16, 3, 64, 50)
-    flops = algorithmic_flops_rot_left(N, L, K, alpha, B)
-    for name, k in kernels.items():
-        if name in flops and k["ms_per_step"] > 0:
-            k["algorithmic_TFLOPs"] = round(flops[name] / (k["ms_per_step"] * 1e-3) / 1e12, 2)
+
+    # measured peaks of this GPU (hisa_calibrate: register-only instruction chains, a 1 GiB device-to-device copy)
+    cal = ctx.calibrate()
+    # An fp64 vector instruction is one lane-operation (an FMA two flops): the datasheet's 78.6 TFLOP/s is
+    # 256 CUs x 4 SIMDs x 16 lanes x 2 x 2.4 GHz; the measured counterpart is twice the measured FMA issue rate.
+    fp64_measured = 2.0 * cal["fma_f64"]
+    counters, counter_src = read_counters() if headline else ({}, {"file": None, "note": "counters exist for the headline configuration only"})
+
+    def counter_key(name):     # the counter summary keeps rocprofv3's names, without the third template argument
+        return name
+
     launches = max(kernels[dom]["launches_per_step"], 1)
     hbm_side = {"achieved_GBs": kernels[dom]["algorithmic_GBs"], "frac": round(kernels[dom]["algorithmic_GBs"] / HBM_PEAK_GBS, 4),
+                "frac_of_measured_copy": round(kernels[dom]["algorithmic_GBs"] / cal["copy_GBs"], 4) if cal["copy_GBs"] else None,
                 "algorithmic_bytes_per_launch": int(alg.get(dom, 0) / launches)}
+    cnt = counters.get(counter_key(dom), {})
     if dom in flops:
-        # the transform kernels are bound by vector-ALU issue (counters: 55-64 % of the issue slots busy, 17-20 % of the
-        # HBM peak), so the roofline is the fp64 vector peak; the HBM reading stays beside it
+        # the transform kernels are bound by the vector ALU, not by HBM (counters: 55-65 % of the issue slots busy,
+        # a fifth of the HBM peak), so the roofline is the fp64 vector peak; the HBM reading stays beside it
         tf = kernels[dom]["algorithmic_TFLOPs"]
         roofline = {"kernel": dom, "bound": "alu", "achieved": tf, "peak": FP64_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(tf / FP64_PEAK_TFLOPS, 4),
+                    "peak_measured": round(fp64_measured, 2), "frac_of_measured": round(tf / fp64_measured, 4),
                     "algorithmic_flops_per_launch": int(flops[dom] / launches),
-                    "valu_issue_busy": MEASURED_VALU_BUSY.get(dom) if headline else None, "hbm": hbm_side}
+                    "valu_issue_busy": cnt.get("valu_issue_busy"), "hbm": hbm_side}
     else:
         roofline = {"kernel": dom, "bound": "hbm", "achieved": hbm_side["achieved_GBs"], "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": hbm_side["frac"],
+                    "peak_measured": round(cal["copy_GBs"], 1), "frac_of_measured": hbm_side["frac_of_measured_copy"],
                     "algorithmic_bytes_per_launch": hbm_side["algorithmic_bytes_per_launch"]}
-    roofline["traffic"] = int(MEASURED_TRAFFIC[dom]) if headline and dom in MEASURED_TRAFFIC else None
+    roofline["traffic"] = cnt.get("traffic")
+    roofline["counters_from"] = counter_src
     roofline["avg_launch_us"] = kernels[dom]["avg_launch_us"]
     roofline["share_of_step"] = round(kernels[dom]["ms_per_step"] / sum(k["ms_per_step"] for k in kernels.values()), 3)
+    for name, k in kernels.items():      # counter readings of every kernel of the step, where the summary has them
+        c = counters.get(counter_key(name))
+        if c:
+            k["counters_per_launch"] = c
     staged, strict = staged_bytes_rot_left(N, L, K, alpha, dnum, L, B)
     per_ct_s = dt / (B * args.steps)
     rot = {"us_per_ct": round(per_ct_s * 1e6, 2),
            "staged_bytes_per_ct": int(staged), "strict_bytes_per_ct": int(strict),
            "staged_GBs": round(staged / per_ct_s / 1e9, 1), "frac_of_hbm_staged": round(staged / per_ct_s / 1e9 / HBM_PEAK_GBS, 4),
-           "frac_of_hbm_strict": round(strict / per_ct_s / 1e9 / HBM_PEAK_GBS, 4)}
+           "frac_of_hbm_strict": round(strict / per_ct_s / 1e9 / HBM_PEAK_GBS, 4),
+           "frac_of_measured_copy_staged": round(staged / per_ct_s / 1e9 / cal["copy_GBs"], 4) if cal["copy_GBs"] else None}
+    if counters:
+        per_step = sum(c.get("traffic", 0) * kernels[n]["launches_per_step"] for n, c in counters.items() if n in kernels)
+        rot["counter_bytes_per_ct"] = int(per_step / B)
 
     nets_out = None
     if not args.no_nets:
         nets_out = network_latencies()
-
-    if args.pmc_calibrate:
-        src = torch.ones(1 << 27, dtype=torch.int64, device="cuda")   # 1 GiB
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
 
     ops = {}
     if not args.no_ops:
@@ -337,6 +405,13 @@ def main():
         ops["rot_left_hoisted_x3"] = {"ms": round(t * 1e3, 4), "per_s": round(3 * B / t, 1),
                                       "note": "three rotations of each ciphertext sharing one decomposition of c1"}
 
+    # HBM traffic of the streaming primitives from the same counter summary, where it has them
+    for op, kname in (("add", "addsub_kernel"), ("mul_plain", "mul_plain_kernel"), ("mul_no_relin", "mul_no_relin_kernel")):
+        c = counters.get(kname, {})
+        if op in ops and "traffic" in c:
+            ops[op]["counter_bytes_per_launch"] = c["traffic"]
+            ops[op]["counter_GBs"] = round(c["traffic"] / (ops[op]["ms"] * 1e-3) / 1e9, 1)
+
     base = None
     if args.cpu_sample > 0:
         base = cpu_baseline(log_n, q_bits, dnum, args.bits, 1, args.cpu_sample, rot_steps)
@@ -352,7 +427,8 @@ def main():
         "config": {"workload": "primitive micro-benchmark: rotLeft over a batch of %d random ciphertexts, N=2^%d, "
                                "%d limbs of %d-bit primes, dnum %d, steps {1,7,64}" % (B, log_n, L, args.bits, dnum),
                    "log_n": log_n, "limbs": L, "dnum": dnum, "special_primes": K, "batch": B},
-        "roofline": roofline, "rot_left": rot, "kernels": kernels, "ops": ops, "networks": nets_out,
+        "roofline": roofline, "rot_left": rot, "kernels": kernels, "calibration": {k: round(v, 3) if isinstance(v, float) else v for k, v in cal.items()},
+        "ops": ops, "networks": nets_out,
         "cpu_baseline": base}))
 
 
