@@ -211,16 +211,17 @@ def network_latencies():
             nets.run_encrypted(ctx, layers, x, params["scale"], limbs, make_keys=True, **kw)
             # latency: the host queues the whole network, one wait at the end; the per-layer times come from one more
             # inference that waits after every layer
-            runs = sorted((nets.run_encrypted(ctx, layers, x, params["scale"], limbs, layer_times=False, **kw)
+            client = {}
+            runs = sorted((nets.run_encrypted(ctx, layers, x, params["scale"], limbs, layer_times=False, client_times=client, **kw)
                            for _ in range(3)), key=lambda r: r[1])
             per_layer = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, **kw)[2]
-            res[layout] = (runs[1][1], per_layer, None)
+            res[layout] = (runs[1][1], per_layer, None, dict(client))
             if layout == selected:     # one more inference with HIP events around every kernel: where the time goes
                 ctx.profile_enable(True)
                 nets.run_encrypted(ctx, layers, x, params["scale"], limbs, **kw)
                 prof = sorted(ctx.profile_read().items(), key=lambda kv: -kv[1][1])
                 ctx.profile_enable(False)
-                res[layout] = (runs[1][1], per_layer, {k: [c, round(ms, 3)] for k, (c, ms) in prof[:8]})
+                res[layout] = (runs[1][1], per_layer, {k: [c, round(ms, 3)] for k, (c, ms) in prof[:8]}, dict(client))
             nets.free_plans(ctx, plans)
             ctx.close()
         best = selected
@@ -230,6 +231,8 @@ def network_latencies():
                      "log_n": params["log_n"], "limbs": limbs, "dnum": params["dnum"],
                      "layers_ms": [[k, round(s * 1e3, 2)] for k, s in res[best][1]],
                      "kernels_launches_ms": res[best][2],
+                     # the client's side, outside the latency: encode + encrypt of the image, decrypt + decode of the result
+                     "client_ms": {k.replace("_s", ""): round(v * 1e3, 3) for k, v in res[best][3].items()},
                      "paper_context": paper, "data": "seeded random weights and image"}
     return out
 

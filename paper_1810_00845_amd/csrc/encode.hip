@@ -157,3 +157,172 @@ hipError_t launch_decode(const double* cs, const double* sn, const double* m, in
     hipLaunchKernelGGL(decode_kernel, dim3(count), dim3(NT), 0, st, cs, sn, m, count, re, im, log_n);
     return hipGetLastError();
 }
+
+// ---------------------------------------------------------------------------
+// The same two maps in O(N log N): the "special" FFT over the slot order 5^j
+// ---------------------------------------------------------------------------
+// With u_k = m_k + i m_{k+n} (n = N/2) the slot values are z_j = sum_{k<n} u_k zeta_j^k, zeta_j = exp(i pi 5^j / N).
+// Splitting k into even and odd halves the problem: zeta_j^2 are the slot roots of the ring of half the degree,
+// zeta_{j+n/2} = -zeta_j (5^(n/2) = N + 1 mod 2N), so
+//     z_j = E_j + zeta_j O_j,   z_{j+n/2} = E_j - zeta_j O_j   (j < n/2),
+// a radix-2 decimation-in-time transform from bit-reversed input whose stage of length `len` uses the twiddles
+// exp(i pi (5^j mod 4 len) / (2 len)), j < len/2, read from the table of 2N-th roots.  The matrix (zeta_j^k) is
+// unitary up to the factor n, so the inverse (encode) runs the stages backwards with conjugate twiddles.
+// Stages up to SF_C points run in LDS (one workgroup per chunk of SF_C consecutive points), longer ones one launch each.
+#define SF_C 1024
+#define SF_LOGC 10
+#define SF_T 256
+typedef double2 cplx;
+
+__device__ __forceinline__ cplx sf_twiddle(const double* cs, const double* sn, const uint32_t* pow5, uint32_t j, uint32_t len,
+                                           int log_n) {
+    const uint32_t e = (pow5[j] & (4 * len - 1)) * ((1u << log_n) / (2 * len));
+    return make_double2(cs[e], sn[e]);
+}
+__device__ __forceinline__ cplx sf_mul(cplx a, cplx b) { return make_double2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x); }
+__device__ __forceinline__ cplx sf_mulc(cplx a, cplx b) { return make_double2(a.x * b.x + a.y * b.y, a.y * b.x - a.x * b.y); }   // a * conj(b)
+
+// decode direction, stages 2 .. min(n, SF_C): work[vec][pos] from the coefficients m[vec][N]
+__global__ __launch_bounds__(SF_T) void sfft_fwd_local_kernel(const double* cs, const double* sn, const uint32_t* pow5,
+                                                              const double* m, cplx* work, int log_n) {
+    __shared__ cplx buf[SF_C];
+    const uint32_t n = 1u << (log_n - 1);
+    const uint32_t C = n < SF_C ? n : SF_C;
+    const size_t vec = blockIdx.y;
+    const uint32_t base = blockIdx.x * C;
+    const double* mv = m + (vec << log_n);
+    for (uint32_t r = threadIdx.x; r < C; r += SF_T) {
+        const uint32_t src = __brev(base + r) >> (32 - (log_n - 1));
+        buf[r] = make_double2(mv[src], mv[src + n]);
+    }
+    __syncthreads();
+    for (uint32_t len = 2; len <= C; len <<= 1) {
+        const uint32_t half = len >> 1;
+        for (uint32_t q = threadIdx.x; q < C / 2; q += SF_T) {
+            const uint32_t j = q & (half - 1), i0 = ((q - j) << 1) + j;
+            const cplx w = sf_twiddle(cs, sn, pow5, j, len, log_n);
+            const cplx u = buf[i0], v = sf_mul(buf[i0 + half], w);
+            buf[i0] = make_double2(u.x + v.x, u.y + v.y);
+            buf[i0 + half] = make_double2(u.x - v.x, u.y - v.y);
+        }
+        __syncthreads();
+    }
+    cplx* wv = work + vec * n + base;
+    for (uint32_t r = threadIdx.x; r < C; r += SF_T) wv[r] = buf[r];
+}
+
+// one stage of length len > SF_C over work[vec][n], in place; INVERSE: (a, b) -> (a + b, (a - b) conj(w))
+template <bool INVERSE>
+__global__ __launch_bounds__(SF_T) void sfft_stage_kernel(const double* cs, const double* sn, const uint32_t* pow5, cplx* work,
+                                                          uint32_t len, int log_n) {
+    const uint32_t n = 1u << (log_n - 1), half = len >> 1;
+    const uint32_t q = blockIdx.x * SF_T + threadIdx.x;
+    if (q >= n / 2) return;
+    cplx* wv = work + (size_t)blockIdx.y * n;
+    const uint32_t j = q & (half - 1), i0 = ((q - j) << 1) + j;
+    const cplx w = sf_twiddle(cs, sn, pow5, j, len, log_n);
+    const cplx a = wv[i0], b = wv[i0 + half];
+    if (INVERSE) {
+        wv[i0] = make_double2(a.x + b.x, a.y + b.y);
+        wv[i0 + half] = sf_mulc(make_double2(a.x - b.x, a.y - b.y), w);
+    } else {
+        const cplx v = sf_mul(b, w);
+        wv[i0] = make_double2(a.x + v.x, a.y + v.y);
+        wv[i0 + half] = make_double2(a.x - v.x, a.y - v.y);
+    }
+}
+
+__global__ __launch_bounds__(SF_T) void sfft_take_kernel(const cplx* work, int count, double* re, double* im, int log_n) {
+    const int j = blockIdx.x * SF_T + threadIdx.x;
+    if (j >= count) return;
+    const cplx z = work[j];
+    re[j] = z.x;
+    if (im) im[j] = z.y;
+}
+
+// encode direction, input: work[vec][slot] = the slot values (zero where there is none): dense rows re/im[vec][count] at
+// slots 0 .. count-1, or (slots != null) count values per vector at the listed slots
+__global__ __launch_bounds__(SF_T) void sfft_fill_kernel(const double* re, const double* im, const uint32_t* slots, int count,
+                                                         cplx* work, int log_n) {
+    const uint32_t n = 1u << (log_n - 1);
+    const size_t vec = blockIdx.y;
+    cplx* wv = work + vec * n;
+    if (!slots) {
+        const uint32_t j = blockIdx.x * SF_T + threadIdx.x;
+        if (j < n) wv[j] = (int)j < count ? make_double2(re[vec * count + j], im ? im[vec * count + j] : 0.0) : make_double2(0.0, 0.0);
+    } else {
+        // the rows were cleared by the launcher; every listed slot is written once
+        const int i = blockIdx.x * SF_T + threadIdx.x;
+        if (i < count) wv[slots[i]] = make_double2(re[vec * count + i], im ? im[vec * count + i] : 0.0);
+    }
+}
+
+// encode direction, stages min(n, SF_C) .. 2, then coefficients k and k + n of the bit-reversed position, rounded
+__global__ __launch_bounds__(SF_T) void sfft_inv_local_kernel(const double* cs, const double* sn, const uint32_t* pow5,
+                                                              const cplx* work, double factor, i64* coeffs, int log_n) {
+    __shared__ cplx buf[SF_C];
+    const uint32_t n = 1u << (log_n - 1);
+    const uint32_t C = n < SF_C ? n : SF_C;
+    const size_t vec = blockIdx.y;
+    const uint32_t base = blockIdx.x * C;
+    const cplx* wv = work + vec * n + base;
+    for (uint32_t r = threadIdx.x; r < C; r += SF_T) buf[r] = wv[r];
+    __syncthreads();
+    for (uint32_t len = C; len >= 2; len >>= 1) {
+        const uint32_t half = len >> 1;
+        for (uint32_t q = threadIdx.x; q < C / 2; q += SF_T) {
+            const uint32_t j = q & (half - 1), i0 = ((q - j) << 1) + j;
+            const cplx w = sf_twiddle(cs, sn, pow5, j, len, log_n);
+            const cplx a = buf[i0], b = buf[i0 + half];
+            buf[i0] = make_double2(a.x + b.x, a.y + b.y);
+            buf[i0 + half] = sf_mulc(make_double2(a.x - b.x, a.y - b.y), w);
+        }
+        __syncthreads();
+    }
+    i64* cv = coeffs + (vec << log_n);
+    for (uint32_t r = threadIdx.x; r < C; r += SF_T) {
+        const uint32_t k = __brev(base + r) >> (32 - (log_n - 1));
+        cv[k] = (i64)round(buf[r].x * factor);
+        cv[k + n] = (i64)round(buf[r].y * factor);
+    }
+}
+
+// m[N] -> re/im[count]; work: n complex numbers
+hipError_t launch_decode_fft(const double* cs, const double* sn, const uint32_t* pow5, const double* m, int count, void* work,
+                             double* re, double* im, int log_n, hipStream_t st) {
+    DRY_RUN_RETURN();
+    if (count <= 0) return hipSuccess;
+    if (!cs || !sn || !pow5 || !m || !work || !re || log_n < 2 || log_n > 17 || count > (1 << (log_n - 1))) return hipErrorInvalidValue;
+    const uint32_t n = 1u << (log_n - 1), C = n < SF_C ? n : SF_C;
+    ProfScope prof__("decode_fft", st);
+    hipLaunchKernelGGL(sfft_fwd_local_kernel, dim3(n / C, 1), dim3(SF_T), 0, st, cs, sn, pow5, m, (cplx*)work, log_n);
+    for (uint32_t len = 2 * C; len <= n && len > C; len <<= 1)
+        hipLaunchKernelGGL(sfft_stage_kernel<false>, dim3((n / 2 + SF_T - 1) / SF_T, 1), dim3(SF_T), 0, st, cs, sn, pow5, (cplx*)work, len, log_n);
+    hipLaunchKernelGGL(sfft_take_kernel, dim3((count + SF_T - 1) / SF_T), dim3(SF_T), 0, st, (const cplx*)work, count, re, im, log_n);
+    return hipGetLastError();
+}
+
+// n_pts slot vectors -> coeffs[n_pts][N] = round(factor * (inverse transform)); values re/im[n_pts][count] at slots
+// 0 .. count-1 (slots null) or at slots[count] (device); work: n_pts * n complex numbers
+hipError_t launch_encode_fft(const double* cs, const double* sn, const uint32_t* pow5, const double* re, const double* im,
+                             const uint32_t* slots, int count, int n_pts, double factor, void* work, i64* coeffs, int log_n,
+                             hipStream_t st) {
+    DRY_RUN_RETURN();
+    if (n_pts <= 0) return hipSuccess;
+    if (!cs || !sn || !pow5 || (!re && count) || !work || !coeffs || log_n < 2 || log_n > 17 || count < 0 ||
+        count > (1 << (log_n - 1)) || n_pts > 65535)
+        return hipErrorInvalidValue;
+    const uint32_t n = 1u << (log_n - 1), C = n < SF_C ? n : SF_C;
+    ProfScope prof__("encode_fft", st);
+    if (slots) {
+        hipError_t e = hipMemsetAsync(work, 0, (size_t)n_pts * n * sizeof(cplx), st);
+        if (e != hipSuccess) return e;
+        if (count) hipLaunchKernelGGL(sfft_fill_kernel, dim3((count + SF_T - 1) / SF_T, n_pts), dim3(SF_T), 0, st, re, im, slots, count, (cplx*)work, log_n);
+    } else {
+        hipLaunchKernelGGL(sfft_fill_kernel, dim3((n + SF_T - 1) / SF_T, n_pts), dim3(SF_T), 0, st, re, im, slots, count, (cplx*)work, log_n);
+    }
+    for (uint32_t len = n; len > C; len >>= 1)
+        hipLaunchKernelGGL(sfft_stage_kernel<true>, dim3((n / 2 + SF_T - 1) / SF_T, n_pts), dim3(SF_T), 0, st, cs, sn, pow5, (cplx*)work, len, log_n);
+    hipLaunchKernelGGL(sfft_inv_local_kernel, dim3(n / C, n_pts), dim3(SF_T), 0, st, cs, sn, pow5, (const cplx*)work, factor, coeffs, log_n);
+    return hipGetLastError();
+}

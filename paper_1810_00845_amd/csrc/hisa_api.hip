@@ -676,8 +676,15 @@ extern "C" int hisa_encode(hisa_ctx* ctx, const double* re, const double* im, si
     if (count) HIP_TRY(ctx, hipMemcpyAsync(d_re, re, count * sizeof(double), hipMemcpyHostToDevice, ctx->stream));
     if (im && count) HIP_TRY(ctx, hipMemcpyAsync(d_im, im, count * sizeof(double), hipMemcpyHostToDevice, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-    HIP_TRY(ctx, launch_encode(ctx->d_cos, ctx->d_sin, ctx->d_pow5, d_re, d_im, (int)count, 1, 2.0 * scale / (double)ctx->N,
-                               co.as<i64>(), (int)ctx->log_n, ctx->stream));
+    if (count > 64) {   // the O(N log N) transform over the slot order; a handful of slots is cheaper summed directly
+        Temp work(ctx, (ctx->N / 2) * 2 * sizeof(double));
+        if (!work.ok()) return HISA_ERR_OOM;
+        HIP_TRY(ctx, launch_encode_fft(ctx->d_cos, ctx->d_sin, ctx->d_pow5, d_re, d_im, nullptr, (int)count, 1,
+                                       2.0 * scale / (double)ctx->N, work.blk->ptr, co.as<i64>(), (int)ctx->log_n, ctx->stream));
+    } else {
+        HIP_TRY(ctx, launch_encode(ctx->d_cos, ctx->d_sin, ctx->d_pow5, d_re, d_im, (int)count, 1, 2.0 * scale / (double)ctx->N,
+                                   co.as<i64>(), (int)ctx->log_n, ctx->stream));
+    }
     TRY(alloc_pt(ctx, limbs, scale, out));
     HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>(), (*out)->data, (int)limbs, 1, (int)ctx->log_n, ctx->stream));
     HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, (*out)->data, 0, (int)limbs, identity_map((int)limbs), ctx->stream));
@@ -725,7 +732,14 @@ extern "C" int hisa_decode(hisa_ctx* ctx, const hisa_pt* pt, double* re, double*
                                       m.as<double>(), (int)ctx->log_n, ctx->stream));
     double* d_re = z.as<double>();
     double* d_im = d_re + count;
-    HIP_TRY(ctx, launch_decode(ctx->d_cos, ctx->d_sin, m.as<double>(), (int)count, d_re, d_im, (int)ctx->log_n, ctx->stream));
+    if (count > 16) {
+        Temp work(ctx, (n / 2) * 2 * sizeof(double));
+        if (!work.ok()) return HISA_ERR_OOM;
+        HIP_TRY(ctx, launch_decode_fft(ctx->d_cos, ctx->d_sin, ctx->d_pow5, m.as<double>(), (int)count, work.blk->ptr, d_re, d_im,
+                                       (int)ctx->log_n, ctx->stream));
+    } else {
+        HIP_TRY(ctx, launch_decode(ctx->d_cos, ctx->d_sin, m.as<double>(), (int)count, d_re, d_im, (int)ctx->log_n, ctx->stream));
+    }
     if (count) HIP_TRY(ctx, hipMemcpyAsync(re, d_re, count * sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
     if (im && count) HIP_TRY(ctx, hipMemcpyAsync(im, d_im, count * sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));

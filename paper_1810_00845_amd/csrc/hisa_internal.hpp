@@ -439,6 +439,12 @@ hipError_t launch_encode_basis(const double* cs, const uint32_t* g, const int* s
                                hipStream_t st);
 hipError_t launch_encode_combine(const double* basis, int nb, const double* v, int n_pts, double factor, i64* coeffs,
                                  int log_n, hipStream_t st);
+// the same maps through the O(N log N) transform over the slot order (encode.hip); pow5: [N/2] 5^j mod 2N
+hipError_t launch_decode_fft(const double* cs, const double* sn, const uint32_t* pow5, const double* m, int count, void* work,
+                             double* re, double* im, int log_n, hipStream_t st);
+hipError_t launch_encode_fft(const double* cs, const double* sn, const uint32_t* pow5, const double* re, const double* im,
+                             const uint32_t* slots, int count, int n_pts, double factor, void* work, i64* coeffs, int log_n,
+                             hipStream_t st);
 hipError_t launch_crt_to_double(const PrimeConst* primes, const u64* coeff_form, int limbs, const u64* garner_inv,
                                 const u64* garner_inv_sh, int L, double inv_scale, double* out, int log_n, hipStream_t st);
 hipError_t launch_decode(const double* cs, const double* sn, const double* m, int count, double* re, double* im, int log_n,

@@ -815,15 +815,31 @@ static int encode_sparse_batch(hisa_ctx* ctx, const std::vector<uint32_t>& slots
             if (k & 1) e = (e * b) & mask;
         g[i] = e;
     }
+    // Many non-zero slots (an image plane): the O(N log N) transform over the slot order, the values scattered into
+    // dense rows on the device.  Few (a mask row, a weight on a handful of positions): the direct sum over them.
+    const bool fft = nnz > 256;
+    if (fft) g.assign(slots.begin(), slots.end());
+    const size_t group = fft ? std::min<size_t>(n_pts, 256) : 0;   // plaintexts per transform launch (16 bytes per slot each)
     Temp dg(ctx, nnz * sizeof(uint32_t));
     Temp dv(ctx, n_pts * nnz * sizeof(double));
     Temp co(ctx, n_pts * n * sizeof(i64));
-    if (!dg.ok() || !dv.ok() || !co.ok()) return HISA_ERR_OOM;
+    Temp work(ctx, group * (n / 2) * 2 * sizeof(double), fft);
+    if (!dg.ok() || !dv.ok() || !co.ok() || (fft && !work.ok())) return HISA_ERR_OOM;
     HIP_TRY(ctx, hipMemcpyAsync(dg.blk->ptr, g.data(), nnz * sizeof(uint32_t), hipMemcpyHostToDevice, ctx->stream));
     HIP_TRY(ctx, hipMemcpyAsync(dv.blk->ptr, values, n_pts * nnz * sizeof(double), hipMemcpyHostToDevice, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    if (fft) {
+        for (size_t p0 = 0; p0 < n_pts; p0 += group) {
+            const int cnt = (int)std::min<size_t>(group, n_pts - p0);
+            HIP_TRY(ctx, launch_encode_fft(ctx->d_cos, ctx->d_sin, ctx->d_pow5, dv.as<double>() + p0 * nnz, nullptr, dg.as<uint32_t>(),
+                                           (int)nnz, cnt, 2.0 * scale / (double)n, work.blk->ptr, co.as<i64>() + p0 * n,
+                                           (int)ctx->log_n, ctx->stream));
+            HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>() + p0 * n, out + p0 * limbs * n, limbs, cnt,
+                                           (int)ctx->log_n, ctx->stream));
+        }
+    }
     // grid.y carries the plaintext index: stay below its limit
-    for (size_t p0 = 0; p0 < n_pts; p0 += 32768) {
+    for (size_t p0 = 0; !fft && p0 < n_pts; p0 += 32768) {
         const int cnt = (int)std::min<size_t>(32768, n_pts - p0);
         HIP_TRY(ctx, launch_encode(ctx->d_cos, ctx->d_sin, dg.as<uint32_t>(), dv.as<double>() + p0 * nnz, nullptr, (int)nnz,
                                    cnt, 2.0 * scale / (double)n, co.as<i64>() + p0 * n, (int)ctx->log_n, ctx->stream));

@@ -110,7 +110,7 @@ def chw_blocks(slots, plane_slots_needed, layers, chw_convs=True):
 
 
 def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans=None, layout="hw", shared_moddown=True,
-                  layer_times=True, rotate_sums=True, merge_doublings=4, fused_rescale=True):
+                  layer_times=True, rotate_sums=True, merge_doublings=4, fused_rescale=True, client_times=None):
     """Encrypts x, runs the layers, decrypts.  Returns (output array, seconds from encrypt-done to the last
     ciphertext ready, per-layer seconds).  With make_keys the rotation keys each layer asks for are generated
     on the way (set-up pass); otherwise they must be resident.  `plans` (a dict, filled by the set-up pass and
@@ -129,7 +129,8 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
     (hisa_set_merge_doublings; 0: the chains as they are).  fused_rescale: layers whose division by P is directly
     followed by their divScalar take both in one base conversion (hisa_set_fused_rescale).  layer_times: wait for the GPU after every layer to time it; without,
     the host queues the whole network ahead of the GPU and only the end-to-end latency is measured (per-layer entries
-    are then host queueing times)."""
+    are then host queueing times).  client_times: a dict that receives the seconds the client side took, "encrypt_s"
+    (encode + encrypt of the image) and "decrypt_s" (decrypt + decode of the result), both outside the latency."""
     assert layout in LAYOUTS
     if layout == "chw":
         border = 0      # CHW-tiled convolutions multiply by plaintexts, which carry the SAME padding: planes back to back
@@ -143,6 +144,8 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
         ci, cs = chw_blocks(ctx.N // 2, (x.shape[2] + 2 * border) * hs, layers, chw_convs=layout == "chw")
         if layout == "chw":
             tiling = dict(c_inner=ci, c_stride=cs)
+    ctx.sync()
+    t_client = time.perf_counter()
     if border:   # leave `border` rows and columns of zero slots around every plane (SAME convolutions need them)
         hs = x.shape[3] + 2 * border
         t = ctx.tensor_encrypt(x, scale, limbs, h_stride=hs, offset=border * hs + border, **tiling)
@@ -150,6 +153,8 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
         t = ctx.tensor_encrypt(x, scale, limbs, **tiling)
     ctx.sync()
     t_start = time.perf_counter()
+    if client_times is not None:
+        client_times["encrypt_s"] = t_start - t_client
     per_layer = []
     pending = 1.0     # constant factor the previous layers left to the next linear layer
     def fully_connected(idx, t, w, replicas=1):
@@ -332,7 +337,10 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
         per_layer.append((kind, time.perf_counter() - t0))
     ctx.sync()
     latency = time.perf_counter() - t_start
+    t_client = time.perf_counter()
     out = ctx.tensor_decrypt(t) * pending
+    if client_times is not None:
+        client_times["decrypt_s"] = time.perf_counter() - t_client
     t.free()
     return out, latency, per_layer
 
