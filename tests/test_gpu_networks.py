@@ -89,3 +89,38 @@ def test_network_other_layouts_match_plaintext(name, layout):
         assert np.abs(got3 - want).max() <= 1e-3
     nets.free_plans(ctx, plans)
     ctx.close()
+
+
+@pytest.mark.parametrize("seed", [6, 7])
+def test_squeezenet_style_network_on_other_seeds(seed):
+    """The SqueezeNet-style weights follow a rule of the layer shapes and activation coefficients, not of one image:
+    other seeds of weights, activations and image give the same <= 1e-3 (CHW-tiled, the layout the cost model selects)."""
+    from paper_1810_00845_amd import hisa, nets
+    params, layers, x = nets.squeezenet_cifar(seed)
+    want = plain_forward(layers, x)
+    ctx = hisa.Context(params["log_n"], params["q_bits"], params["dnum"], params["special_bits"], seed=11)
+    ctx.keygen()
+    got, _, _ = nets.run_encrypted(ctx, layers, x, params["scale"], len(params["q_bits"]), make_keys=True,
+                                   border=params["border"], layout="chw")
+    err = np.abs(got - want).max()
+    print("seed", seed, "max |output|", np.abs(want).max(), "max abs error", err, flush=True)
+    assert np.abs(want).max() > 0.02 and err <= 1e-3
+    ctx.close()
+
+
+def test_squeezenet_style_network_with_the_weights_as_worded():
+    """Weights N(0, 0.05^2) in every layer, as benchmark configuration 5 words them: the values shrink from layer to
+    layer (outputs of the order 1e-8), so the absolute bound holds by a wide margin; the error relative to the output's
+    size is printed with it."""
+    from paper_1810_00845_amd import hisa, nets
+    params, layers, x = nets.squeezenet_cifar_literal()
+    want = plain_forward(layers, x)
+    ctx = hisa.Context(params["log_n"], params["q_bits"], params["dnum"], params["special_bits"], seed=11)
+    ctx.keygen()
+    got, _, _ = nets.run_encrypted(ctx, layers, x, params["scale"], len(params["q_bits"]), make_keys=True,
+                                   border=params["border"], layout="chw")
+    err = np.abs(got - want).max()
+    print("max |output| %.3e, max abs error %.3e, relative to the output %.3f" % (np.abs(want).max(), err, err / np.abs(want).max()),
+          flush=True)
+    assert err <= 1e-3
+    ctx.close()
