@@ -247,6 +247,8 @@ int hisa_ct_random_batch(hisa_ctx* ctx, size_t n, uint32_t limbs, double scale, 
  * returns what was recorded: the operation counts (in ciphertext operations;
  * the terms of the layers' fused multiply-accumulate launches are counted apart
  * from stand-alone multiplications and their additions are not counted),
+ * for every count the sum of the limbs its operations ran on (limb_sum, in the order of the counts: what a cost
+ * that is affine in the level needs, Sec. "Data Layout Selection"),
  * the lowest limb count any ciphertext reached, and the sorted left-rotation
  * amounts that needed a key (at most cap of them into host rot_steps, the count
  * into *n; rot_steps may be null).  Handles made during the analysis stay valid
@@ -267,7 +269,10 @@ typedef struct {
                                   a small batch costs its launch latency, not its share of the throughput */
     uint32_t min_limbs;    /* 0 if no ciphertext was made */
     uint32_t reserved;
+    uint64_t limb_sum[12]; /* per count above, in that order: sum over its occurrences of the limbs they ran on */
 } hisa_op_counts;
+enum { HISA_OP_ROT_LEFT = 0, HISA_OP_ROT_SHARED, HISA_OP_ROT_SUMMED, HISA_OP_RELINEARIZE, HISA_OP_MUL, HISA_OP_MUL_PLAIN,
+       HISA_OP_MUL_SCALAR, HISA_OP_ADD, HISA_OP_RESCALE, HISA_OP_MAC_PLAIN, HISA_OP_MAC_SCALAR, HISA_OP_KEY_SWITCH_CALLS };
 int hisa_analysis_begin(hisa_ctx* ctx);
 int hisa_analysis_end(hisa_ctx* ctx, hisa_op_counts* counts, int32_t* rot_steps, size_t cap, size_t* n);
 
@@ -574,6 +579,28 @@ typedef struct {
     uint32_t compute_units, reserved;
 } hisa_calibration;
 int hisa_calibrate(hisa_ctx* ctx, hisa_calibration* out);
+
+/* The host-side check that every multiply-accumulate launch of the tensor kernels (Sec. "Runtime": convolution and
+ * matrix multiplication over CipherTensors) passes before it reaches the GPU, callable on its own: no device, no
+ * context, nothing is dereferenced.  A launch reads, per rotation amount ("tap"), batch * ic entries ct_words apart of
+ * polys * limbs limbs of 2^log_n words, and writes batch * oc such entries; an optional second input (x2_extent != 0)
+ * holds n_taps blocks x2_tap_words apart of batch * ic entries x2_words apart of lq limbs, its output batch * oc of
+ * them; plaintext weights (w_extent != 0) are read at (T * w_stride_t + o * w_stride_oc) * w_words on limbs limbs
+ * (w_words = 0: limbs * 2^log_n).  Every *_words / *_extent field counts the 8-byte words from the pointer the launch
+ * would use to the end of its allocation; tap_words holds n_taps of them (null with n_taps = 1: tap0_words).
+ * Inside the library the extents come from the context's allocator, so a launch whose shape fields do not match the
+ * buffers behind its pointers is refused with HISA_ERR_ARG instead of running.
+ * Returns HISA_OK when every access stays inside its allocation, HISA_ERR_ARG otherwise. */
+typedef struct {
+    int32_t n_taps, ic, oc, batch, log_n;
+    int32_t limbs, polys, lq, gap;     /* polys: 2 (0 is read as 2) or 1; limbs >= lq use the primes gap further on */
+    uint64_t ct_words;
+    const uint64_t* tap_words;
+    uint64_t tap0_words, out_words;
+    uint64_t x2_tap_words, x2_words, x2_extent, out2_extent;
+    uint64_t w_words, w_stride_t, w_stride_oc, w_extent;
+} hisa_mac_extents;
+int hisa_check_mac_extents(const hisa_mac_extents* a);
 
 #ifdef __cplusplus
 }

@@ -116,7 +116,7 @@ __global__ __launch_bounds__(NT) void addsub_kernel(const PrimeConst* primes, co
 
 hipError_t launch_addsub(const PrimeConst* primes, const u64* a, const u64* b, u64* out, int op, int limbs, int polys_a,
                          int polys_b, u64 n_batch, u64 a_bs, u64 b_bs, u64 o_bs, int log_n, hipStream_t st) {
-    if (t_analysis) t_analysis->c.add += n_batch;
+    if (t_analysis) TALLY(add, HISA_OP_ADD, n_batch, limbs);
     DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, limbs * polys_a, (unsigned)n_batch);
     ProfScope prof__("addsub_kernel", st);
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(NT) void add_const_kernel(const PrimeConst* primes,
 
 hipError_t launch_add_const(const PrimeConst* primes, const u64* a, u64* out, const u64* consts, int op, int limbs,
                             int polys, int log_n, hipStream_t st) {
-    if (t_analysis) t_analysis->c.add += (uint64_t)(polys + 1) / 2;
+    if (t_analysis) TALLY(add, HISA_OP_ADD, (polys + 1) / 2, limbs);
     DRY_RUN_RETURN();
     LimbConsts c = {};
     for (int i = 0; i < limbs; i++) c.v[i] = consts[i];
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(NT) void mul_plain_kernel(const PrimeConst* primes,
 
 hipError_t launch_mul_plain(const PrimeConst* primes, const u64* a, const u64* pt, u64* out, int limbs, int polys,
                             u64 n_batch, u64 a_bs, u64 o_bs, int log_n, hipStream_t st, unsigned pt_period) {
-    if (t_analysis) t_analysis->c.mul_plain += n_batch;
+    if (t_analysis) TALLY(mul_plain, HISA_OP_MUL_PLAIN, n_batch, limbs);
     DRY_RUN_RETURN();
     if (pt_period == 0 || n_batch == 0 || n_batch > 65535) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / NT, limbs * polys, (unsigned)n_batch);
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(NT) void mul_const_kernel(const PrimeConst* primes,
 
 hipError_t launch_mul_const(const PrimeConst* primes, const u64* a, u64* out, const u64* consts, int limbs, int polys,
                             int log_n, hipStream_t st) {
-    if (t_analysis) t_analysis->c.mul_scalar += (uint64_t)(polys + 1) / 2;
+    if (t_analysis) TALLY(mul_scalar, HISA_OP_MUL_SCALAR, (polys + 1) / 2, limbs);
     DRY_RUN_RETURN();
     // consts: [limbs] values followed by [limbs] Shoup companions
     LimbConsts c = {};
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(NT) void mul_no_relin_kernel(const PrimeConst* prim
 
 hipError_t launch_mul_no_relin(const PrimeConst* primes, const u64* a, const u64* b, u64* out, int limbs, u64 n_batch,
                                u64 a_bs, u64 b_bs, u64 o_bs, int log_n, hipStream_t st) {
-    if (t_analysis) t_analysis->c.mul += n_batch;
+    if (t_analysis) TALLY(mul, HISA_OP_MUL, n_batch, limbs);
     DRY_RUN_RETURN();
     dim3 grid((1u << log_n) / NT, limbs, (unsigned)n_batch);
     ProfScope prof__("mul_no_relin_kernel", st);

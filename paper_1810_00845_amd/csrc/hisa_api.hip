@@ -209,7 +209,17 @@ DevBlock* dev_alloc(hisa_ctx* ctx, size_t bytes) {
         ctx->pool_bytes += bytes;
     }
     DevBlock* b = new DevBlock{p, bytes, 1};
+    ctx->live[(uintptr_t)p] = bytes;
     return b;
+}
+
+u64 dev_words_behind(const hisa_ctx* ctx, const void* p) {
+    const uintptr_t a = (uintptr_t)p;
+    auto it = ctx->live.upper_bound(a);
+    if (it == ctx->live.begin()) return 0;
+    --it;
+    if (a >= it->first + it->second) return 0;
+    return (u64)(it->first + it->second - a) / sizeof(u64);
 }
 
 // Work on one stream: a block returned to the pool may be handed out again at
@@ -217,6 +227,7 @@ DevBlock* dev_alloc(hisa_ctx* ctx, size_t bytes) {
 void dev_release(hisa_ctx* ctx, DevBlock* b) {
     if (!b) return;
     if (--b->refs > 0) return;
+    ctx->live.erase((uintptr_t)b->ptr);
     ctx->pool[b->bytes].push_back(b->ptr);
     delete b;
 }
@@ -1592,11 +1603,11 @@ int rotate_sum_fp(hisa_ctx* ctx, const u64* rot, u64 ct_bs, int n_steps, const i
         tab.g[s] = (uint32_t)g;
     }
     if (t_analysis) {
-        t_analysis->c.rot_left += (u64)n_steps * Bn;
-        t_analysis->c.rot_summed += (u64)n_steps * Bn;
-        if (shared_input) t_analysis->c.rot_shared += (u64)(n_steps - 1) * Bn;
-        t_analysis->c.key_switch_calls += 1;
-        if (rescale) t_analysis->c.rescale += Bn;
+        TALLY(rot_left, HISA_OP_ROT_LEFT, (u64)n_steps * Bn, l);
+        TALLY(rot_summed, HISA_OP_ROT_SUMMED, (u64)n_steps * Bn, l);
+        if (shared_input) TALLY(rot_shared, HISA_OP_ROT_SHARED, (u64)(n_steps - 1) * Bn, l);
+        TALLY(key_switch_calls, HISA_OP_KEY_SWITCH_CALLS, 1, l);
+        if (rescale) TALLY(rescale, HISA_OP_RESCALE, Bn, l);
         return HISA_OK;
     }
     if (rescale && l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "no level to rescale into");
@@ -1621,9 +1632,9 @@ int relinearize_rescale_fp(hisa_ctx* ctx, const u64* cts3, u64 stride, size_t n_
     if (!fused_key_switch_available(ctx)) return fail(ctx, HISA_ERR_ARG, "no fused key-switch path for these parameters");
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "no level to rescale into");
     if (t_analysis) {
-        t_analysis->c.relinearize += n_cts;
-        t_analysis->c.rescale += n_cts;
-        t_analysis->c.key_switch_calls += 1;
+        TALLY(relinearize, HISA_OP_RELINEARIZE, n_cts, l);
+        TALLY(rescale, HISA_OP_RESCALE, n_cts, l);
+        TALLY(key_switch_calls, HISA_OP_KEY_SWITCH_CALLS, 1, l);
         return HISA_OK;
     }
     auto it = ctx->keys.find(0);
@@ -1760,8 +1771,8 @@ extern "C" int hisa_rot_left_batch(hisa_ctx* ctx, const hisa_ct* const* in, size
     if (t_analysis) {   // dry run: note the amount, hand out ciphertexts of the right level and scale
         const int32_t half = (int32_t)(ctx->N / 2);
         t_analysis->steps.insert(((steps % half) + half) % half);
-        t_analysis->c.rot_left += n;
-        t_analysis->c.key_switch_calls += 1;
+        TALLY(rot_left, HISA_OP_ROT_LEFT, n, l);
+        TALLY(key_switch_calls, HISA_OP_KEY_SWITCH_CALLS, 1, l);
         TRY(alloc_ct_batch(ctx, n, 2, (uint32_t)l, 0.0, out));
         for (size_t i = 0; i < n; i++) out[i]->scale = in[i]->scale;
         return HISA_OK;
@@ -1821,9 +1832,10 @@ extern "C" int hisa_rot_left_hoisted_batch(hisa_ctx* ctx, const hisa_ct* const* 
         if (rc == HISA_OK && switched >= 2 && ctx->tabs.fp_ok && ctx->dnum <= 8) {
             // one decomposition, then one set of launches per group of rotations (as in the branch below)
             const size_t group = std::max<size_t>(1, std::min<size_t>(FP_MAX_STEPS, 1024 / n));
-            t_analysis->c.rot_shared += (switched - 1) * n;
+            TALLY(rot_shared, HISA_OP_ROT_SHARED, (switched - 1) * n, l);
             t_analysis->c.key_switch_calls -= switched;
-            t_analysis->c.key_switch_calls += (switched + group - 1) / group;
+            t_analysis->c.limb_sum[HISA_OP_KEY_SWITCH_CALLS] -= (u64)switched * l;
+            TALLY(key_switch_calls, HISA_OP_KEY_SWITCH_CALLS, (switched + group - 1) / group, l);
         }
     } else if (switched < 2 || !(ctx->tabs.fp_ok && ctx->dnum <= 8)) {   // nothing to share, or no fused path: one by one
         for (size_t s = 0; s < n_steps && rc == HISA_OK; s++) rc = hisa_rot_left_batch(ctx, in, n, steps[s], out + s * n);
@@ -1916,8 +1928,8 @@ extern "C" int hisa_rot_left_noalloc(hisa_ctx* ctx, const hisa_ct* a, int32_t st
         if (g) {
             const int32_t half = (int32_t)(ctx->N / 2);
             t_analysis->steps.insert(((steps % half) + half) % half);
-            t_analysis->c.rot_left += 1;
-            t_analysis->c.key_switch_calls += 1;
+            TALLY(rot_left, HISA_OP_ROT_LEFT, 1, l);
+            TALLY(key_switch_calls, HISA_OP_KEY_SWITCH_CALLS, 1, l);
         }
         out->scale = a->scale;
         return HISA_OK;
@@ -1960,8 +1972,8 @@ extern "C" int hisa_relinearize_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t
     if (cts[0]->polys == 2) return HISA_OK;
     if (cts[0]->polys != 3) return fail(ctx, HISA_ERR_SIZE, "relinearize needs 2 or 3 polynomials");
     if (t_analysis) {
-        t_analysis->c.relinearize += n;
-        t_analysis->c.key_switch_calls += 1;
+        TALLY(relinearize, HISA_OP_RELINEARIZE, n, cts[0]->limbs);
+        TALLY(key_switch_calls, HISA_OP_KEY_SWITCH_CALLS, 1, cts[0]->limbs);
         std::vector<hisa_ct*> two(n);
         TRY(alloc_ct_batch(ctx, n, 2, cts[0]->limbs, 0.0, two.data()));
         for (size_t i = 0; i < n; i++) {
@@ -2075,7 +2087,7 @@ extern "C" int hisa_rescale_batch(hisa_ctx* ctx, hisa_ct* const* cts, size_t n) 
     TRY(check_batch_shape(ctx, (const hisa_ct* const*)cts, n, 0));
     const int l = (int)cts[0]->limbs, polys = (int)cts[0]->polys;
     if (l < 2) return fail(ctx, HISA_ERR_DEPTH_EXHAUSTED, "rescale of a one-limb ciphertext");
-    if (t_analysis) t_analysis->c.rescale += n;
+    if (t_analysis) TALLY(rescale, HISA_OP_RESCALE, n, l);
     const size_t nn = ctx->N, n_bp = n * polys;
     BatchIn bi;
     TRY(gather_batch(ctx, (const hisa_ct* const*)cts, n, &bi));

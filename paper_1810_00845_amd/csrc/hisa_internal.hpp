@@ -135,6 +135,7 @@ struct hisa_ctx {
     int fp_scratch_polys;
     std::unordered_map<size_t, std::vector<void*>> pool;
     size_t pool_bytes;
+    std::map<uintptr_t, size_t> live;   // blocks handed out by dev_alloc and not yet back in the pool: start -> bytes
     u64 enc_counter;
     int device = -1;              // the GPU the context lives on (current when it was made)
     void* noalloc_ws = nullptr;   // that GPU's copy of the library's static scratch array (hisa_rot_left_noalloc)
@@ -160,6 +161,8 @@ int fail(hisa_ctx* ctx, int code, const char* fmt, ...);
 
 DevBlock* dev_alloc(hisa_ctx* ctx, size_t bytes);   // from the context's pool; null (and last_error set) on failure
 void dev_release(hisa_ctx* ctx, DevBlock* b);
+// 8-byte words from p to the end of the live pool block that holds p; 0 when no live block does
+u64 dev_words_behind(const hisa_ctx* ctx, const void* p);
 
 struct Temp {  // pooled scratch buffer for the duration of one call
     hisa_ctx* ctx;
@@ -231,6 +234,12 @@ struct Analysis {
     std::set<int32_t> steps;    // left-rotation amounts that needed a key
 };
 extern thread_local Analysis* t_analysis;   // non-null while the calling thread's context is in analysis mode
+// n occurrences of an operation on ciphertexts of `limbs` limbs (call only where t_analysis is set)
+#define TALLY(field, OP, n, limbs)                                                   \
+    do {                                                                             \
+        t_analysis->c.field += (uint64_t)(n);                                        \
+        t_analysis->c.limb_sum[OP] += (uint64_t)(n) * (uint64_t)(limbs);             \
+    } while (0)
 #define DRY_RUN_RETURN() do { if (t_analysis) return hipSuccess; } while (0)
 struct ProfScope {
     hipStream_t st;

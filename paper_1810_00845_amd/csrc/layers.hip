@@ -40,14 +40,89 @@ struct MacArgs {
 
 __device__ __forceinline__ int mac_prime(const MacArgs& g, int limb) { return (g.lq && limb >= g.lq) ? limb + g.gap : limb; }
 static inline int mac_polys(const MacArgs& g) { return g.polys == 1 ? 1 : 2; }
-// host check of every multiply-accumulate launch: an entry (ct_words apart) must hold the polys * l limbs the kernel
-// walks over, and the optional second input its lq limbs
+// host check of every multiply-accumulate launch, part one: an entry (ct_words apart) must hold the polys * l limbs
+// the kernel walks over, and the optional second input its lq limbs
 static inline bool mac_shape_ok(const MacArgs& g, int log_n) {
     const u64 n = (u64)1 << log_n;
     if (g.l <= 0 || g.IC <= 0 || g.OC <= 0 || (u64)mac_polys(g) * g.l * n > g.ct_words) return false;
     if (g.lq < 0 || g.lq > g.l) return false;
     if (g.x2 && (u64)g.lq * n > g.x2_words) return false;
     return true;
+}
+
+// Part two: the words behind every pointer of a launch (from the pointer to the end of its allocation).  Host only:
+// beside the pointers of MacArgs it would not fit the kernel argument area.
+struct MacExtents {
+    u64 tap[MAX_TAPS];
+    u64 out, x2, out2;
+    u64 w;   // plain, eight-byte rows only; 0: not known (weights that live outside the context's pool)
+};
+
+// The last word each buffer is asked for, by the indexing of the kernels below: tap t reads entries 0 .. batch*IC-1
+// (ct_words apart) of polys * l limbs; out takes batch*OC such entries; the second input has n_taps blocks
+// (x2_tap_words apart) of batch*IC entries (x2_words apart) of lq limbs, out2 batch*OC of them; plaintext
+// (T, oc) starts (T * w_stride_t + oc * w_stride_oc) plaintexts in and is read on l limbs.
+static const char* mac_extents_fault(const MacArgs& g, const MacExtents& ex, int batch, int log_n) {
+    if (batch <= 0 || g.n_taps <= 0 || g.n_taps > MAX_TAPS || !mac_shape_ok(g, log_n)) return "shape";
+    const u64 n = (u64)1 << log_n;
+    const u64 entry = (u64)mac_polys(g) * g.l * n;
+    const u64 in_need = ((u64)batch * g.IC - 1) * g.ct_words + entry;
+    for (int t = 0; t < g.n_taps; t++)
+        if (in_need > ex.tap[t]) return "input past its allocation";
+    if (((u64)batch * g.OC - 1) * g.ct_words + entry > ex.out) return "output past its allocation";
+    if (g.x2) {
+        const u64 e2 = (u64)g.lq * n;
+        if ((u64)(g.n_taps - 1) * g.x2_tap_words + ((u64)batch * g.IC - 1) * g.x2_words + e2 > ex.x2)
+            return "second input past its allocation";
+        if (!g.out2 || ((u64)batch * g.OC - 1) * g.x2_words + e2 > ex.out2) return "second output past its allocation";
+    }
+    if (ex.w && !g.w_count) {
+        const u64 wl = g.w_words ? g.w_words : (u64)g.l * n;
+        const u64 last = ((u64)g.n_taps * g.IC - 1) * g.w_stride_t + (u64)(g.OC - 1) * g.w_stride_oc;
+        if (last * wl + (u64)g.l * n > ex.w) return "plaintexts past their allocation";
+    }
+    return nullptr;
+}
+
+// Every pointer of a launch is looked up among the context's live blocks: data that is not in one is an error too.
+static hipError_t mac_bounds(hisa_ctx* ctx, const MacArgs& g, int batch, bool plain) {
+    if (g.n_taps <= 0 || g.n_taps > MAX_TAPS) return hipErrorInvalidValue;
+    MacExtents ex = {};
+    for (int t = 0; t < g.n_taps; t++) ex.tap[t] = dev_words_behind(ctx, g.tap_base[t]);
+    ex.out = dev_words_behind(ctx, g.out);
+    if (g.x2) { ex.x2 = dev_words_behind(ctx, g.x2); ex.out2 = g.out2 ? dev_words_behind(ctx, g.out2) : 0; }
+    if (plain && g.w) ex.w = dev_words_behind(ctx, g.w);
+    if (const char* why = mac_extents_fault(g, ex, batch, (int)ctx->log_n)) {
+        fail(ctx, HISA_ERR_ARG, "multiply-accumulate refused: %s (l %d, lq %d, gap %d, polys %d, IC %d, OC %d, taps %d, batch %d)",
+             why, g.l, g.lq, g.gap, mac_polys(g), g.IC, g.OC, g.n_taps, batch);
+        return hipErrorInvalidDevicePointer;
+    }
+    return hipSuccess;
+}
+
+// the library's error for a launcher's: a refusal by the checks above keeps its own message
+static int mac_fail(hisa_ctx* ctx, hipError_t e, const char* what) {
+    if (e == hipErrorInvalidDevicePointer) return HISA_ERR_ARG;
+    return fail(ctx, e == hipErrorInvalidValue ? HISA_ERR_ARG : HISA_ERR_HIP, "%s multiply-accumulate: %s", what, hipGetErrorString(e));
+}
+
+extern "C" int hisa_check_mac_extents(const hisa_mac_extents* a) {
+    if (!a || a->n_taps <= 0 || a->n_taps > MAX_TAPS || a->log_n < 1 || a->log_n > 17) return HISA_ERR_ARG;
+    if (a->n_taps > 1 && !a->tap_words) return HISA_ERR_ARG;
+    MacArgs g = {};
+    MacExtents ex = {};
+    g.n_taps = a->n_taps; g.IC = a->ic; g.OC = a->oc; g.l = a->limbs; g.polys = a->polys; g.lq = a->lq; g.gap = a->gap;
+    g.ct_words = a->ct_words;
+    for (int t = 0; t < a->n_taps; t++) ex.tap[t] = a->tap_words ? a->tap_words[t] : a->tap0_words;
+    ex.out = a->out_words;
+    if (a->x2_extent || a->out2_extent) {
+        g.x2 = (const u64*)8; g.out2 = (u64*)8;   // never dereferenced: only "a second input is present"
+        g.x2_tap_words = a->x2_tap_words; g.x2_words = a->x2_words;
+        ex.x2 = a->x2_extent; ex.out2 = a->out2_extent;
+    }
+    g.w_words = a->w_words; g.w_stride_t = a->w_stride_t; g.w_stride_oc = a->w_stride_oc;
+    ex.w = a->w_extent;
+    return mac_extents_fault(g, ex, a->batch, a->log_n) ? HISA_ERR_ARG : HISA_OK;
 }
 
 // out[b][oc] = sum over T = (tap, ic) of  w[T][oc] * x[tap][b][ic]   (integer weights, one per limb)
@@ -468,12 +543,15 @@ __global__ __launch_bounds__(NT) void plain_mac_fp_kernel(const FpPrime* fprimes
 // analysis mode: a multiply-accumulate launch stands for one term per (image, output, tap, input)
 static void count_mac(const MacArgs& g, int batch, bool plain) {
     if (!t_analysis) return;
-    (plain ? t_analysis->c.mac_plain : t_analysis->c.mac_scalar) += (uint64_t)batch * g.OC * g.n_taps * g.IC;
+    const uint64_t terms = (uint64_t)batch * g.OC * g.n_taps * g.IC;
+    if (plain) TALLY(mac_plain, HISA_OP_MAC_PLAIN, terms, g.l);
+    else TALLY(mac_scalar, HISA_OP_MAC_SCALAR, terms, g.l);
 }
 
-static hipError_t launch_scalar_mac(const PrimeConst* primes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
+static hipError_t launch_scalar_mac(hisa_ctx* ctx, const PrimeConst* primes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
     count_mac(g, batch, false);
     DRY_RUN_RETURN();
+    if (hipError_t be = mac_bounds(ctx, g, batch, false)) return be;
     // the integer kernels know two-polynomial entries on the primes q_0.. only
     if (!primes || !g.w || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || g.polys == 1 || g.lq || g.x2 || g.w_words ||
         !mac_shape_ok(g, log_n))
@@ -484,10 +562,11 @@ static hipError_t launch_scalar_mac(const PrimeConst* primes, const MacArgs& g, 
     return hipGetLastError();
 }
 
-static hipError_t launch_scalar_mac_fp(const FpPrime* fprimes, const MacArgs& g, const double* wf, int batch, int log_n,
+static hipError_t launch_scalar_mac_fp(hisa_ctx* ctx, const FpPrime* fprimes, const MacArgs& g, const double* wf, int batch, int log_n,
                                        hipStream_t st) {
     count_mac(g, batch, false);
     DRY_RUN_RETURN();
+    if (hipError_t be = mac_bounds(ctx, g, batch, false)) return be;
     if (!fprimes || !wf || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || !mac_shape_ok(g, log_n)) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / NT, mac_polys(g) * g.l, batch * ((g.OC + OCF - 1) / OCF));
     ProfScope prof__("scalar_mac_fp_kernel", st);
@@ -504,10 +583,11 @@ static hipError_t launch_mfma_one(const FpPrime* fprimes, const MacArgs& g, cons
 }
 
 // da: digits the weights need (1..7); db: digits the residues need (6: every prime below 2^46, else 7)
-static hipError_t launch_scalar_mac_mfma(const FpPrime* fprimes, const MacArgs& g, const int8_t* wd, int K, int K_pad, int OC_pad,
+static hipError_t launch_scalar_mac_mfma(hisa_ctx* ctx, const FpPrime* fprimes, const MacArgs& g, const int8_t* wd, int K, int K_pad, int OC_pad,
                                          const double* c3, int da, int db, int batch, int log_n, hipStream_t st) {
     count_mac(g, batch, false);
     DRY_RUN_RETURN();
+    if (hipError_t be = mac_bounds(ctx, g, batch, false)) return be;
     if (!fprimes || !wd || !c3 || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || K != g.n_taps * g.IC || K_pad % MT_K ||
         K_pad < K || OC_pad % MT_OC || OC_pad < g.OC || log_n < 6 || da < 1 || da > MAC_DIGITS || (db != 6 && db != 7) ||
         !mac_shape_ok(g, log_n))
@@ -542,9 +622,10 @@ __global__ __launch_bounds__(NT) void pack_plain_kernel(const u64* src, char* ds
     }
 }
 
-static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
+static hipError_t launch_plain_mac_fp(hisa_ctx* ctx, const FpPrime* fprimes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
     count_mac(g, batch, true);
     DRY_RUN_RETURN();
+    if (hipError_t be = mac_bounds(ctx, g, batch, true)) return be;
     if (!fprimes || !g.w || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || !mac_shape_ok(g, log_n)) return hipErrorInvalidValue;
     if (g.w_words && (u64)g.l * ((u64)1 << log_n) > g.w_words) return hipErrorInvalidValue;   // plaintexts shorter than the limbs walked
     if (g.x2 && (!g.out2 || g.lq <= 0 || g.lq > g.l || g.x2_words == 0)) return hipErrorInvalidValue;
@@ -566,9 +647,10 @@ static hipError_t launch_plain_mac_fp(const FpPrime* fprimes, const MacArgs& g, 
     return hipGetLastError();
 }
 
-static hipError_t launch_plain_mac(const PrimeConst* primes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
+static hipError_t launch_plain_mac(hisa_ctx* ctx, const PrimeConst* primes, const MacArgs& g, int batch, int log_n, hipStream_t st) {
     count_mac(g, batch, true);
     DRY_RUN_RETURN();
+    if (hipError_t be = mac_bounds(ctx, g, batch, true)) return be;
     // the integer kernels know two-polynomial entries on the primes q_0.. only
     if (!primes || !g.w || !g.out || g.n_taps <= 0 || g.n_taps > MAX_TAPS || g.polys == 1 || g.lq || g.x2 || g.w_words ||
         !mac_shape_ok(g, log_n))
@@ -1164,27 +1246,27 @@ static int conv_run(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_geom* 
         hipError_t e;
         if (g->mode == HISA_CONV_PLAIN) {
             ma.w = d_pts; ma.w_stride_t = OCm; ma.w_stride_oc = 1; ma.w_count = pt_count; ma.w_packed = pt_packed;
-            if (ctx->tabs.fp_ok) e = launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
-            else e = launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+            if (ctx->tabs.fp_ok) e = launch_plain_mac_fp(ctx, ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+            else e = launch_plain_mac(ctx, ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
         } else {
             ma.w = dw->res.u();
             if (dw->mfma) {
                 u64 qmax = 0;
                 for (uint32_t k = 0; k < l; k++) qmax = std::max(qmax, ctx->mod[k]);
                 const int db = qmax < ((u64)1 << 46) ? 6 : 7;   // six balanced digits reach 0.498 * 2^48 (just under 2^47)
-                e = launch_scalar_mac_mfma(ctx->tabs.fprimes, ma, (const int8_t*)dw->digits.blk->ptr, (int)dw->K, (int)dw->K_pad,
+                e = launch_scalar_mac_mfma(ctx, ctx->tabs.fprimes, ma, (const int8_t*)dw->digits.blk->ptr, (int)dw->K, (int)dw->K_pad,
                                            (int)dw->OC_pad, dw->c3.as<double>(), dw->da, db, (int)B, (int)ctx->log_n, ctx->stream);
             }
             else if (dw->fp)
-                e = launch_scalar_mac_fp(ctx->tabs.fprimes, ma, dw->resf.as<double>(), (int)B, (int)ctx->log_n, ctx->stream);
-            else e = launch_scalar_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+                e = launch_scalar_mac_fp(ctx, ctx->tabs.fprimes, ma, dw->resf.as<double>(), (int)B, (int)ctx->log_n, ctx->stream);
+            else e = launch_scalar_mac(ctx, ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
             if (e == hipSuccess && g->mode == HISA_CONV_MASKED) {
                 e = launch_mul_plain(ctx->d_primes, outs[0]->data, d_pts, outs[0]->data, (int)l, 2, (u64)B * OC, ma.ct_words,
                                      ma.ct_words, (int)ctx->log_n, ctx->stream);
                 for (hisa_ct* c : outs) c->scale = mac_scale * pt_scale;
             }
         }
-        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));
+        if (e != hipSuccess) rc = mac_fail(ctx, e, "conv");
     }
     if (!shared) release_inputs(ctx, own);
     if (rc == HISA_OK) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
@@ -1236,8 +1318,8 @@ static int conv_run_sums(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv_g
         ma.n_taps = n_taps; ma.IC = (int)IC; ma.OC = (int)sums; ma.l = (int)l; ma.ct_words = ctw;
         ma.out = y.u();
         ma.w = d_pts; ma.w_stride_t = sums; ma.w_stride_oc = 1; ma.w_count = pt_count; ma.w_packed = pt_packed;
-        hipError_t e = launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
-        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));
+        hipError_t e = launch_plain_mac_fp(ctx, ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+        if (e != hipSuccess) rc = mac_fail(ctx, e, "conv");
     }
     if (!shared) release_inputs(ctx, own);
     // per image: entries (d, g) are rotation-major over the OCm outputs; d = 0 is the unrotated term
@@ -1583,16 +1665,16 @@ static int conv_build_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t*
 static hipError_t shared_mac(hisa_ctx* ctx, MacArgs ma, const DevWeights* dw, const u64* pts, uint32_t pt_limbs, int batch) {
     if (pts) {
         ma.w = pts; ma.w_stride_t = (u64)ma.OC; ma.w_stride_oc = 1; ma.w_words = (u64)pt_limbs * ctx->N;
-        return launch_plain_mac_fp(ctx->tabs.fprimes, ma, batch, (int)ctx->log_n, ctx->stream);
+        return launch_plain_mac_fp(ctx, ctx->tabs.fprimes, ma, batch, (int)ctx->log_n, ctx->stream);
     }
     if (dw->mfma) {
         u64 qmax = 0;
         for (int k = 0; k < ma.l; k++) qmax = std::max(qmax, ctx->mod[(ma.lq && k >= ma.lq) ? k + ma.gap : k]);
         const int db = qmax < ((u64)1 << 46) ? 6 : 7;
-        return launch_scalar_mac_mfma(ctx->tabs.fprimes, ma, (const int8_t*)dw->digits.blk->ptr, (int)dw->K, (int)dw->K_pad,
+        return launch_scalar_mac_mfma(ctx, ctx->tabs.fprimes, ma, (const int8_t*)dw->digits.blk->ptr, (int)dw->K, (int)dw->K_pad,
                                       (int)dw->OC_pad, dw->c3.as<double>(), dw->da, db, batch, (int)ctx->log_n, ctx->stream);
     }
-    return launch_scalar_mac_fp(ctx->tabs.fprimes, ma, dw->resf.as<double>(), batch, (int)ctx->log_n, ctx->stream);
+    return launch_scalar_mac_fp(ctx, ctx->tabs.fprimes, ma, dw->resf.as<double>(), batch, (int)ctx->log_n, ctx->stream);
 }
 
 // The convolution with ONE division by P per output ciphertext (the rotations of a convolution are only ever used
@@ -1694,7 +1776,7 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
         if (e == hipSuccess && plain)   // Z0 += Q0
             e = launch_addsub(ctx->d_primes, Z.u(), Q0.u(), Z.u(), OP_ADD, (int)l, 1, 1, n_out, 2 * lw, lw, 2 * lw, (int)ctx->log_n,
                               ctx->stream);
-        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "conv multiply-accumulate: %s", hipGetErrorString(e));
+        if (e != hipSuccess) rc = mac_fail(ctx, e, "conv");
     }
     if (rc == HISA_OK && one_division) rc = moddown_rescale_fp(ctx, E.u(), n_out, (int)l, Z.u(), 2 * lw, 2, outs[0]->data);
     else if (rc == HISA_OK) rc = moddown_add_fp(ctx, E.u(), n_out, (int)l, Z.u(), 2 * lw, 2, 0, outs[0]->data);
@@ -1707,7 +1789,7 @@ static int conv_run_shared(hisa_ctx* ctx, const hisa_tensor* in, const hisa_conv
     dev_release(ctx, bi.tmp);
     free_handles(ctx, wrapped);
     if (rc == HISA_OK && !one_division) rc = hisa_rescale_batch(ctx, outs.data(), outs.size());
-    if (rc == HISA_OK && one_division && t_analysis) t_analysis->c.rescale += n_out;
+    if (rc == HISA_OK && one_division && t_analysis) TALLY(rescale, HISA_OP_RESCALE, n_out, l);
     if (rc != HISA_OK) {
         free_handles(ctx, outs);
         return rc;
@@ -1884,9 +1966,9 @@ static int fc_chunk(hisa_ctx* ctx, const hisa_tensor* in, const BatchIn& bi, con
     ma.w = pts; ma.w_stride_t = 1; ma.w_stride_oc = C;
     ma.out = outs[0]->data;
     (void)pt_scale;
-    if (ctx->tabs.fp_ok) HIP_TRY(ctx, launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream));
-    else HIP_TRY(ctx, launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream));
-    return HISA_OK;
+    const hipError_t e = ctx->tabs.fp_ok ? launch_plain_mac_fp(ctx, ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream)
+                                         : launch_plain_mac(ctx, ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+    return e == hipSuccess ? HISA_OK : mac_fail(ctx, e, "matmul");
 }
 
 static int rotate_add_chain(hisa_ctx* ctx, std::vector<hisa_ct*>& xs, const std::vector<i64>& steps, int sign);
@@ -2350,9 +2432,9 @@ static int matmul_run(hisa_ctx* ctx, const hisa_tensor* in, const MatmulGeom& g,
         ma.ct_words = 2 * (u64)l * n;
         ma.w = pts; ma.w_stride_t = 1; ma.w_stride_oc = per;
         ma.out = outs[0]->data;
-        hipError_t e = ctx->tabs.fp_ok ? launch_plain_mac_fp(ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream)
-                                       : launch_plain_mac(ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
-        if (e != hipSuccess) rc = fail(ctx, HISA_ERR_HIP, "matmul multiply-accumulate: %s", hipGetErrorString(e));
+        hipError_t e = ctx->tabs.fp_ok ? launch_plain_mac_fp(ctx, ctx->tabs.fprimes, ma, (int)B, (int)ctx->log_n, ctx->stream)
+                                       : launch_plain_mac(ctx, ctx->d_primes, ma, (int)B, (int)ctx->log_n, ctx->stream);
+        if (e != hipSuccess) rc = mac_fail(ctx, e, "matmul");
     }
     dev_release(ctx, bi.tmp);
     free_handles(ctx, xs);

@@ -45,12 +45,31 @@ class TensorStruct(C.Structure):
 
 class OpCounts(C.Structure):
     _fields_ = [(name, C.c_uint64) for name in ("rot_left", "rot_shared", "rot_summed", "relinearize", "mul", "mul_plain", "mul_scalar",
-                                                "add", "rescale", "mac_plain", "mac_scalar", "key_switch_calls")] + [("min_limbs", C.c_uint32), ("reserved", C.c_uint32)]
+                                                "add", "rescale", "mac_plain", "mac_scalar", "key_switch_calls")] + \
+               [("min_limbs", C.c_uint32), ("reserved", C.c_uint32), ("limb_sum", C.c_uint64 * 12)]
 
 
 class Calibration(C.Structure):
     _fields_ = [(n, C.c_double) for n in ("fma_f64", "mul_f64", "add_f64", "rndne_add_f64", "mul_lo_u64", "mul_hi_u64", "copy_GBs")] + \
                [("copy_bytes", C.c_uint64), ("clock_mhz", C.c_double), ("compute_units", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class MacExtents(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_taps", "ic", "oc", "batch", "log_n", "limbs", "polys", "lq", "gap")] + \
+               [("ct_words", C.c_uint64), ("tap_words", C.POINTER(C.c_uint64))] + \
+               [(n, C.c_uint64) for n in ("tap0_words", "out_words", "x2_tap_words", "x2_words", "x2_extent", "out2_extent",
+                                          "w_words", "w_stride_t", "w_stride_oc", "w_extent")]
+
+
+def check_mac_extents(tap_words, **fields):
+    """hisa_check_mac_extents: the library's error code (0 = every access inside its allocation) for one
+    multiply-accumulate launch described by its shape fields and the words behind each pointer; host only."""
+    taps = (C.c_uint64 * len(tap_words))(*[int(t) for t in tap_words])
+    a = MacExtents(n_taps=len(tap_words), tap_words=C.cast(taps, C.POINTER(C.c_uint64)), **{k: int(v) for k, v in fields.items()})
+    fn = load().hisa_check_mac_extents
+    fn.argtypes = [C.POINTER(MacExtents)]
+    fn.restype = C.c_int
+    return fn(C.byref(a))
 
 
 class ConvGeom(C.Structure):
@@ -607,11 +626,13 @@ class Context:
         self._ck(load().hisa_analysis_begin(self._vp))
 
     def analysis_end(self):
-        """(operation counts as a dict incl. 'min_limbs', sorted left-rotation amounts that needed a key)."""
+        """(operation counts as a dict incl. 'min_limbs' and 'limb_sum' = {operation: limbs summed over its occurrences},
+        sorted left-rotation amounts that needed a key)."""
         counts, n = OpCounts(), C.c_size_t()
         buf = (C.c_int32 * 4096)()
         self._ck(load().hisa_analysis_end(self._vp, C.byref(counts), buf, C.c_size_t(4096), C.byref(n)))
-        d = {name: int(getattr(counts, name)) for name, _ in OpCounts._fields_ if name != "reserved"}
+        d = {name: int(getattr(counts, name)) for name, _ in OpCounts._fields_ if name not in ("reserved", "limb_sum")}
+        d["limb_sum"] = {name: int(counts.limb_sum[i]) for i, (name, _) in enumerate(OpCounts._fields_[:12])}
         return d, [int(buf[i]) for i in range(n.value)]
 
     def profile_enable(self, on=True):

@@ -400,9 +400,26 @@ COST_OPS = ("rot_left", "rot_shared", "rot_summed", "relinearize", "mul", "mul_p
             "mac_scalar", "key_switch_calls")
 
 
-def measure_costs(ctx, limbs, batch=64, reps=5):
-    """Seconds per ciphertext operation at `limbs` limbs, from timing each primitive on a batch of random ciphertexts
-    (Sec. "Data Layout Selection": the costs may come from micro-benchmarks).  "rot_shared" is what a rotation saves
+def measure_costs(ctx, limbs, batch=64, reps=5, low_limbs=None):
+    """The cost table of the layout selection (Sec. "Data Layout Selection": the costs may come from micro-benchmarks):
+    seconds per ciphertext operation at `limbs` limbs (see measure_costs_at), and -- a circuit spends most of its
+    operations below the level it starts at -- under "per_limb" the change of each cost per limb, from a second
+    measurement at low_limbs (default: half of limbs, at least 2; none when limbs < 4).  estimate_cost uses both."""
+    costs = measure_costs_at(ctx, limbs, batch, reps)
+    if low_limbs is None:
+        low_limbs = max(2, limbs // 2)
+    costs["limbs"] = limbs
+    if limbs >= 4 and low_limbs < limbs:
+        low = measure_costs_at(ctx, low_limbs, batch, reps)
+        # launch latency per call does not follow the level
+        costs["per_limb"] = {op: 0.0 if op == "key_switch_calls" else (costs[op] - low[op]) / (limbs - low_limbs) for op in COST_OPS}
+        costs["low"] = dict(low, limbs=low_limbs)
+    return costs
+
+
+def measure_costs_at(ctx, limbs, batch=64, reps=5):
+    """Seconds per ciphertext operation at `limbs` limbs, from timing each primitive on a batch of random ciphertexts.
+    "rot_shared" is what a rotation saves
     when it shares another one's decomposition (a negative cost); "mac_plain" and "mac_scalar" are the terms of the
     layers' fused multiply-accumulate, timed on 1x1 convolutions (which rotate nothing); "rot_summed" likewise what a
     rotation saves inside a sum of rotations that takes its division by P once."""
@@ -473,9 +490,14 @@ def measure_costs(ctx, limbs, batch=64, reps=5):
     return costs
 
 
-def estimate_cost(counts, costs):
-    """The analyser's figure for a circuit: sum over the operations of occurrences times cost."""
-    return sum(counts[op] * costs[op] for op in COST_OPS)
+def estimate_cost(counts, costs, level_aware=True):
+    """The analyser's figure for a circuit: sum over the operations of occurrences times cost.  With a cost table that
+    knows the change per limb, an occurrence at l limbs is charged cost + per_limb * (l - limbs of the table): the
+    counts carry the limbs summed over the occurrences, so the sum needs no list of the operations."""
+    flat = sum(counts[op] * costs[op] for op in COST_OPS)
+    if not level_aware or "per_limb" not in costs or "limb_sum" not in counts:
+        return flat
+    return flat + sum(costs["per_limb"][op] * (counts["limb_sum"][op] - counts[op] * costs["limbs"]) for op in COST_OPS)
 
 
 def select_layout(ctx, layers, x, scale, limbs, costs, border=0, layouts=LAYOUTS):

@@ -12,9 +12,10 @@ def recording(o):
     steps       the set of left-rotation amounts they used
     mul_plain   ciphertext x plaintext multiplications;  mul_scalar  ciphertext x integer multiplications
     mul, relinearize, rescale   as named;  add  additions and subtractions of ciphertexts
-    min_limbs   the lowest level a result reached"""
+    min_limbs   the lowest level a result reached
+    limb_sum    for rotations, mul, relinearize and rescale: the limbs of the operand, summed over the occurrences"""
     rec = {"rotations": 0, "steps": set(), "mul_plain": 0, "mul_scalar": 0, "mul": 0, "relinearize": 0, "rescale": 0, "add": 0,
-           "min_limbs": None}
+           "min_limbs": None, "limb_sum": {"rotations": 0, "mul": 0, "relinearize": 0, "rescale": 0}}
     names = ("rot_left", "mul_plain", "mul_scalar", "mul_int", "mul_no_relin", "relinearize", "div_scalar", "add", "key_switch_acc",
              "mod_down_rescale")
     real = {n: getattr(o, n) for n in names}
@@ -35,6 +36,7 @@ def recording(o):
         r = steps % o.slots
         if r:
             rec["rotations"] += 1
+            rec["limb_sum"]["rotations"] += a.limbs
             rec["steps"].add(r)
         nested[0] += 1
         try:
@@ -44,6 +46,7 @@ def recording(o):
 
     def relinearize(a):
         rec["relinearize"] += 1
+        rec["limb_sum"]["relinearize"] += a.limbs
         nested[0] += 1
         try:
             return low(real["relinearize"](a))
@@ -54,8 +57,10 @@ def recording(o):
         if not nested[0]:
             if key_id == 0:            # the s^2 key: a relinearisation whose division by P the caller takes itself
                 rec["relinearize"] += 1
+                rec["limb_sum"]["relinearize"] += d.shape[0]
             else:
                 rec["rotations"] += 1
+                rec["limb_sum"]["rotations"] += d.shape[0]
                 rec["steps"].add(step_of[key_id])
         return real["key_switch_acc"](d, key_id)
 
@@ -65,6 +70,7 @@ def recording(o):
         halves[0] += 1
         if halves[0] % 2 == 0:
             rec["rescale"] += 1
+            rec["limb_sum"]["rescale"] += l
             if rec["min_limbs"] is None or l - 1 < rec["min_limbs"]:
                 rec["min_limbs"] = l - 1
         return real["mod_down_rescale"](acc, l)
@@ -72,6 +78,8 @@ def recording(o):
     def counted(name, key):
         def f(*a, **k):
             rec[key] += 1
+            if key in rec["limb_sum"]:
+                rec["limb_sum"][key] += a[0].limbs
             return low(real[name](*a, **k))
         return f
 

@@ -136,6 +136,10 @@ def test_dry_run_counts_match_the_oracle_on_a_small_network():
     assert counts["mul_scalar"] + counts["mac_scalar"] == rec["mul_scalar"]
     assert (counts["mul"], counts["relinearize"]) == (rec["mul"], rec["relinearize"])
     assert counts["rescale"] == rec["rescale"] and counts["min_limbs"] == rec["min_limbs"]
+    # the levels the operations ran at, which the level-aware cost model reads: limbs summed over the occurrences
+    ls = counts["limb_sum"]
+    assert ls["rot_left"] == rec["limb_sum"]["rotations"] and ls["mul"] == rec["limb_sum"]["mul"]
+    assert ls["relinearize"] == rec["limb_sum"]["relinearize"] and ls["rescale"] == rec["limb_sum"]["rescale"]
     h = plain_net.fc(np.square(plain_net.conv2d(x, net[0][1], stride=2)), net[2][1])
     want = plain_net.fc(0.5 * np.square(h) + 0.25 * h, net[4][1])
     assert np.abs(layers.tensor_decrypt(o, cur) * pending - want).max() <= 1e-3
@@ -152,9 +156,15 @@ def test_layout_selection_by_cost_agrees_with_the_clock():
     costs = nets.measure_costs(ctx, limbs)
     assert costs["rot_left"] > costs["add"] > 0 and costs["rot_shared"] <= 0 and costs["key_switch_calls"] > costs["rot_left"]
     best, est = nets.select_layout(ctx, layers, x, params["scale"], limbs, costs)
-    print("unit costs (us):", {k: round(v * 1e6, 2) for k, v in costs.items()}, "estimates (ms):",
-          {k: round(v * 1e3, 2) for k, v in est.items()}, flush=True)
+    flat = {lay: nets.estimate_cost(nets.analyse(ctx, layers, x, params["scale"], limbs, 0, lay)[0], costs, level_aware=False)
+            for lay in est}
+    print("unit costs (us):", {k: round(v * 1e6, 2) for k, v in costs.items() if isinstance(v, float)},
+          "per limb (us):", {k: round(v * 1e6, 3) for k, v in costs["per_limb"].items()},
+          "estimates (ms):", {k: round(v * 1e3, 2) for k, v in est.items()},
+          "at the top level's costs throughout (ms):", {k: round(v * 1e3, 2) for k, v in flat.items()}, flush=True)
     assert best == "chw_fc" and est["chw_fc"] < est["hw"] < est["chw"]
+    # a key switch gets cheaper with every level the circuit descends: the level-aware figure is the lower one
+    assert costs["per_limb"]["rot_left"] > 0 and all(est[lay] < flat[lay] for lay in est)
     measured = {}
     for layout in nets.LAYOUTS:
         plans = {}

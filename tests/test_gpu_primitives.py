@@ -13,6 +13,7 @@ PARAMS = {
     "n10_a1": (10, [30, 30, 30], 3, 60, 11),          # single-launch NTT, alpha = 1, mixed prime sizes
     "n12_a2": (12, [50, 40, 45, 50, 36], 3, 55, 12),  # two-launch NTT, alpha = 2, ragged last digit
     "n13_d1": (13, [55, 50, 50, 50], 1, 58, 13),      # dnum = 1: alpha = 4 special primes
+    "n15_int": (15, [58, 55, 56], 3, 60, 18),         # the integer (Shoup / Barrett) kernels at the benchmark's ring degree
     # all primes below 2^50: the fp64 single-launch transforms and the fused key-switch pipeline
     "n12_fp": (12, [50, 40, 45, 50, 36], 3, 50, 14),  # alpha = 2, ragged last digit, mixed sizes
     "n13_fp": (13, [50, 50, 50, 50], 1, 50, 15),      # dnum = 1
@@ -364,3 +365,40 @@ def test_error_codes(pair):
             g.rescale(low)
         assert code(g.rescale, low) == -6                      # depth exhausted
     assert code(g.mul_no_relin, g.mul_no_relin(gct, gct), gct) == -9
+
+
+def test_largest_ring_degree_on_the_integer_kernels():
+    """N = 2^16 (the largest the library accepts; beyond the fp64 transforms' range) with primes above 2^50: the
+    strided two-launch transforms, one rotation and one multiply / relinearise / rescale, bit for bit."""
+    import torch
+    from oracle import Oracle
+    from paper_1810_00845_amd import hisa, synth
+    log_n, q_bits, dnum, sb, seed = 16, [58, 55], 2, 60, 19
+    print("[case] n16_int", flush=True)
+    g, o = hisa.Context(log_n, q_bits, dnum, sb, seed), Oracle(log_n, q_bits, dnum, sb, seed)
+    try:
+        assert g.primes == o.primes
+        for prime in range(g.L + g.K):
+            q = g.primes[prime]
+            a = synth.uniform_residues(40 + prime, (2, 1, g.N), [q])[:, 0, :]
+            a[0, :4] = [0, q - 1, 1, q // 2]
+            t = torch.from_numpy(a.view(np.int64)).cuda()
+            g.ntt_raw(t, prime)
+            got = t.cpu().numpy().view(np.uint64)
+            for r in range(2):
+                assert np.array_equal(got[r], o.ntt(a[r], prime))
+            g.ntt_raw(t, prime, inverse=True)
+            assert np.array_equal(t.cpu().numpy().view(np.uint64), a)
+        g.keygen(); o.keygen()
+        g.gen_rot_keys([3]); o.gen_rot_keys([3])
+        ga, oa, _, _ = fresh_pair(g, o, 41, g.L)
+        gb, ob, _, _ = fresh_pair(g, o, 42, g.L)
+        same(g, o, g.rot_left(ga, 3), o.rot_left(oa, 3))
+        gm, om = g.mul_no_relin(ga, gb), o.mul_no_relin(oa, ob)
+        g.relinearize(gm)
+        om = o.relinearize(om)
+        same(g, o, gm, om)
+        g.rescale(gm)
+        same(g, o, gm, o.rescale(om))
+    finally:
+        g.close()
