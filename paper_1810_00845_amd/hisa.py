@@ -625,6 +625,8 @@ class Context:
         """From here to analysis_end the calls on this context are dry runs that only record."""
         self._ck(load().hisa_analysis_begin(self._vp))
 
+    check_mac_extents = staticmethod(check_mac_extents)   # needs no context: a pure host check
+
     def analysis_end(self):
         """(operation counts as a dict incl. 'min_limbs' and 'limb_sum' = {operation: limbs summed over its occurrences},
         sorted left-rotation amounts that needed a key)."""
