@@ -247,8 +247,9 @@ int hisa_ct_random_batch(hisa_ctx* ctx, size_t n, uint32_t limbs, double scale, 
  * returns what was recorded: the operation counts (in ciphertext operations;
  * the terms of the layers' fused multiply-accumulate launches are counted apart
  * from stand-alone multiplications and their additions are not counted),
- * for every count the sum of the limbs its operations ran on (limb_sum, in the order of the counts: what a cost
- * that is affine in the level needs, Sec. "Data Layout Selection"),
+ * for every count the sum of the limbs its operations ran on and the sum of their squares (limb_sum, limb_sq_sum, in
+ * the order of the counts: what a cost that is a polynomial of degree two in the level needs, Sec. "Data Layout
+ * Selection"),
  * the lowest limb count any ciphertext reached, and the sorted left-rotation
  * amounts that needed a key (at most cap of them into host rot_steps, the count
  * into *n; rot_steps may be null).  Handles made during the analysis stay valid
@@ -270,6 +271,7 @@ typedef struct {
     uint32_t min_limbs;    /* 0 if no ciphertext was made */
     uint32_t reserved;
     uint64_t limb_sum[12]; /* per count above, in that order: sum over its occurrences of the limbs they ran on */
+    uint64_t limb_sq_sum[12]; /* and of the squares of those limbs */
 } hisa_op_counts;
 enum { HISA_OP_ROT_LEFT = 0, HISA_OP_ROT_SHARED, HISA_OP_ROT_SUMMED, HISA_OP_RELINEARIZE, HISA_OP_MUL, HISA_OP_MUL_PLAIN,
        HISA_OP_MUL_SCALAR, HISA_OP_ADD, HISA_OP_RESCALE, HISA_OP_MAC_PLAIN, HISA_OP_MAC_SCALAR, HISA_OP_KEY_SWITCH_CALLS };

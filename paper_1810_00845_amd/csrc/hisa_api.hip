@@ -1835,6 +1835,7 @@ extern "C" int hisa_rot_left_hoisted_batch(hisa_ctx* ctx, const hisa_ct* const* 
             TALLY(rot_shared, HISA_OP_ROT_SHARED, (switched - 1) * n, l);
             t_analysis->c.key_switch_calls -= switched;
             t_analysis->c.limb_sum[HISA_OP_KEY_SWITCH_CALLS] -= (u64)switched * l;
+            t_analysis->c.limb_sq_sum[HISA_OP_KEY_SWITCH_CALLS] -= (u64)switched * l * l;
             TALLY(key_switch_calls, HISA_OP_KEY_SWITCH_CALLS, (switched + group - 1) / group, l);
         }
     } else if (switched < 2 || !(ctx->tabs.fp_ok && ctx->dnum <= 8)) {   // nothing to share, or no fused path: one by one

@@ -239,6 +239,7 @@ extern thread_local Analysis* t_analysis;   // non-null while the calling thread
     do {                                                                             \
         t_analysis->c.field += (uint64_t)(n);                                        \
         t_analysis->c.limb_sum[OP] += (uint64_t)(n) * (uint64_t)(limbs);             \
+        t_analysis->c.limb_sq_sum[OP] += (uint64_t)(n) * (uint64_t)(limbs) * (uint64_t)(limbs); \
     } while (0)
 #define DRY_RUN_RETURN() do { if (t_analysis) return hipSuccess; } while (0)
 struct ProfScope {

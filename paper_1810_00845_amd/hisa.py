@@ -46,7 +46,7 @@ class TensorStruct(C.Structure):
 class OpCounts(C.Structure):
     _fields_ = [(name, C.c_uint64) for name in ("rot_left", "rot_shared", "rot_summed", "relinearize", "mul", "mul_plain", "mul_scalar",
                                                 "add", "rescale", "mac_plain", "mac_scalar", "key_switch_calls")] + \
-               [("min_limbs", C.c_uint32), ("reserved", C.c_uint32), ("limb_sum", C.c_uint64 * 12)]
+               [("min_limbs", C.c_uint32), ("reserved", C.c_uint32), ("limb_sum", C.c_uint64 * 12), ("limb_sq_sum", C.c_uint64 * 12)]
 
 
 class Calibration(C.Structure):
@@ -628,13 +628,14 @@ class Context:
     check_mac_extents = staticmethod(check_mac_extents)   # needs no context: a pure host check
 
     def analysis_end(self):
-        """(operation counts as a dict incl. 'min_limbs' and 'limb_sum' = {operation: limbs summed over its occurrences},
-        sorted left-rotation amounts that needed a key)."""
+        """(operation counts as a dict incl. 'min_limbs', 'limb_sum' = {operation: limbs summed over its occurrences} and
+        'limb_sq_sum' (their squares), sorted left-rotation amounts that needed a key)."""
         counts, n = OpCounts(), C.c_size_t()
         buf = (C.c_int32 * 4096)()
         self._ck(load().hisa_analysis_end(self._vp, C.byref(counts), buf, C.c_size_t(4096), C.byref(n)))
-        d = {name: int(getattr(counts, name)) for name, _ in OpCounts._fields_ if name not in ("reserved", "limb_sum")}
+        d = {name: int(getattr(counts, name)) for name, _ in OpCounts._fields_ if name not in ("reserved", "limb_sum", "limb_sq_sum")}
         d["limb_sum"] = {name: int(counts.limb_sum[i]) for i, (name, _) in enumerate(OpCounts._fields_[:12])}
+        d["limb_sq_sum"] = {name: int(counts.limb_sq_sum[i]) for i, (name, _) in enumerate(OpCounts._fields_[:12])}
         return d, [int(buf[i]) for i in range(n.value)]
 
     def profile_enable(self, on=True):

@@ -400,89 +400,95 @@ COST_OPS = ("rot_left", "rot_shared", "rot_summed", "relinearize", "mul", "mul_p
             "mac_scalar", "key_switch_calls")
 
 
-def measure_costs(ctx, limbs, batch=64, reps=5, low_limbs=None):
+def measure_costs(ctx, limbs, batch=64, reps=5, levels=None):
     """The cost table of the layout selection (Sec. "Data Layout Selection": the costs may come from micro-benchmarks):
     seconds per ciphertext operation at `limbs` limbs (see measure_costs_at), and -- a circuit spends most of its
-    operations below the level it starts at -- under "per_limb" the change of each cost per limb, from a second
-    measurement at low_limbs (default: half of limbs, at least 2; none when limbs < 4).  estimate_cost uses both."""
-    costs = measure_costs_at(ctx, limbs, batch, reps)
-    if low_limbs is None:
-        low_limbs = max(2, limbs // 2)
-    costs["limbs"] = limbs
-    if limbs >= 4 and low_limbs < limbs:
-        low = measure_costs_at(ctx, low_limbs, batch, reps)
-        # launch latency per call does not follow the level
-        costs["per_limb"] = {op: 0.0 if op == "key_switch_calls" else (costs[op] - low[op]) / (limbs - low_limbs) for op in COST_OPS}
-        costs["low"] = dict(low, limbs=low_limbs)
+    operations below the level it starts at, where a key switch costs a fraction of what it does at the top -- under
+    "poly" the coefficients (c0, c1, c2) of each cost as a polynomial c0 + c1 l + c2 l^2 in the level l, through
+    the measurements at `levels` (default: the top, the middle and 2 limbs; two levels give a line, one a constant).
+    Interpolation only: no circuit runs above the top or below 2 limbs.  estimate_cost uses the polynomial."""
+    if levels is None:
+        levels = sorted({limbs, (limbs + 2) // 2, min(limbs, 2)}, reverse=True)
+    at = {l: measure_costs_at(ctx, l, batch, reps) for l in levels}
+    costs = dict(at[limbs], limbs=limbs, levels=at, poly={})
+    for op in COST_OPS:
+        if op == "key_switch_calls" or len(levels) == 1:          # launch latency per call does not follow the level
+            costs["poly"][op] = (costs[op], 0.0, 0.0)
+        else:
+            fit = np.polyfit([float(l) for l in levels], [at[l][op] for l in levels], min(2, len(levels) - 1))
+            costs["poly"][op] = tuple(float(c) for c in fit[::-1]) + (0.0,) * (3 - len(fit))
     return costs
 
 
 def measure_costs_at(ctx, limbs, batch=64, reps=5):
     """Seconds per ciphertext operation at `limbs` limbs, from timing each primitive on a batch of random ciphertexts.
-    "rot_shared" is what a rotation saves
-    when it shares another one's decomposition (a negative cost); "mac_plain" and "mac_scalar" are the terms of the
-    layers' fused multiply-accumulate, timed on 1x1 convolutions (which rotate nothing); "rot_summed" likewise what a
-    rotation saves inside a sum of rotations that takes its division by P once."""
+    A key-switched call of n ciphertexts takes about t0 + n t1: t1 (from the full batch and a batch of one) is the
+    operation's cost, t0 -- what a call costs however small its batch: the launches' latency -- is "key_switch_calls".
+    "rot_shared" is what a rotation saves when it shares another one's decomposition (a negative cost), "rot_summed"
+    what it saves inside a sum of rotations that takes its division by P once; "mac_plain" and "mac_scalar" are the
+    terms of the layers' fused multiply-accumulate, timed on 1x1 convolutions (which rotate nothing)."""
     from .hisa import CipherTensor
-    import numpy as np
     cts = ctx.ct_random_batch(batch, limbs, 2.0 ** 40, 900)
     pt = ctx.encode(np.ones(8), float(ctx.primes[limbs - 1]), limbs)
     ctx.gen_rot_keys([1, 2, 3])
 
-    def timed(fn):
+    def timed(fn):                     # seconds per call
         fn()
         ctx.sync()
         t0 = time.perf_counter()
         for _ in range(reps):
             fn()
         ctx.sync()
-        return (time.perf_counter() - t0) / (reps * batch)
+        return (time.perf_counter() - t0) / reps
+
+    def split(fn):                     # fn(first n ciphertexts): (seconds per ciphertext, seconds per call) of t0 + n t1
+        full, single = timed(lambda: fn(batch)), timed(lambda: fn(1))
+        t1 = max(0.0, (full - single) / (batch - 1))
+        return t1, max(0.0, single - t1)
 
     def free(out):
         for c in out:
             free(c) if isinstance(c, list) else c.free()
 
     costs = {}
-    # a key switch of n ciphertexts takes about t0 + n t1: t1 from the full batch, t0 (what a call costs however small
-    # its batch: the launches' latency) from a batch of one
-    full = timed(lambda: free(ctx.rot_left_batch(cts, 1)))                          # seconds per ciphertext
-    single = timed(lambda: free(ctx.rot_left_batch(cts[:1], 1))) * batch           # seconds per call of one ciphertext
-    costs["rot_left"] = max(0.0, (full * batch - single) / (batch - 1))
-    costs["key_switch_calls"] = max(0.0, single - costs["rot_left"])
-    hoisted = timed(lambda: free(ctx.rot_left_hoisted_batch(cts, [1, 2, 3])))      # three rotations per ciphertext
-    costs["rot_shared"] = min(0.0, (hoisted - 3 * full) / 2)
-    costs["rot_summed"] = 0.0                 # what a rotation saves inside a sum that divides by P once
+    costs["rot_left"], costs["key_switch_calls"] = split(lambda n: free(ctx.rot_left_batch(cts[:n], 1)))
+    rot = costs["rot_left"]
+    # three rotations per ciphertext from one decomposition; never more than nine tenths of a rotation saved
+    hoisted = split(lambda n: free(ctx.rot_left_hoisted_batch(cts[:n], [1, 2, 3])))[0]
+    costs["rot_shared"] = min(0.0, max((hoisted - 3 * rot) / 2, -0.9 * rot))
+    costs["rot_summed"] = 0.0
     if ctx.log_n >= 12 and max(ctx.primes) < 2 ** 50 and ctx.dnum <= 8:
         # three terms per output, each a different ciphertext (terms that rotate the same one would share the
         # decomposition as well, which "rot_shared" already prices)
-        terms = [cts, cts[1:] + cts[:1], cts[2:] + cts[:2]]
-        summed = timed(lambda: free(ctx.rot_left_sum_batch(terms, [1, 2, 3])))
-        costs["rot_summed"] = min(0.0, (summed - 3 * full) / 2)
+        def summed(n):
+            terms = [cts[:n], (cts[1:] + cts[:1])[:n], (cts[2:] + cts[:2])[:n]]
+            free(ctx.rot_left_sum_batch(terms, [1, 2, 3]))
         # a rotation that shares both still has its inner product to pay
-        costs["rot_summed"] = max(costs["rot_summed"], -0.9 * (costs["rot_left"] + costs["rot_shared"]))
-    costs["add"] = timed(lambda: free(ctx.add_batch(cts, cts)))
-    costs["mul"] = timed(lambda: free(ctx.mul_no_relin_batch(cts, cts)))
-    costs["mul_plain"] = timed(lambda: free(ctx.mul_plain_batch(cts, pt)))
+        costs["rot_summed"] = min(0.0, max((split(summed)[0] - 3 * rot) / 2, -0.9 * (rot + costs["rot_shared"])))
+    per_ct = lambda fn: timed(fn) / batch
+    costs["add"] = per_ct(lambda: free(ctx.add_batch(cts, cts)))
+    costs["mul"] = per_ct(lambda: free(ctx.mul_no_relin_batch(cts, cts)))
+    costs["mul_plain"] = per_ct(lambda: free(ctx.mul_plain_batch(cts, pt)))
     costs["mul_scalar"] = costs["mul_plain"]          # both stream a ciphertext through one multiply per residue
 
-    def relin():
-        sq = ctx.mul_no_relin_batch(cts, cts)
+    def relin(n):
+        sq = ctx.mul_no_relin_batch(cts[:n], cts[:n])
         ctx.relinearize_batch(sq)
         free(sq)
-    costs["relinearize"] = max(0.0, timed(relin) - costs["mul"] - costs["key_switch_calls"] / batch)
+    costs["relinearize"] = max(0.0, split(relin)[0] - costs["mul"])
 
     def rescale():
         cp = ctx.add_batch(cts, cts)
         ctx.rescale_batch(cp)
         free(cp)
-    costs["rescale"] = max(0.0, timed(rescale) - costs["add"])
+    costs["rescale"] = max(0.0, per_ct(rescale) - costs["add"])
     # fused multiply-accumulate: a 1x1 convolution over `batch` channels is batch * outputs terms and one divScalar per output
     t = CipherTensor(ctx, cts, 1, batch, 1, 1, 1, 1, 0, 1)
     w = np.random.default_rng(0).normal(0.0, 0.1, (1, 1, batch, batch))
     for name, mode in (("mac_scalar", 0), ("mac_plain", 2)):
         plan = ctx.conv2d_prepare(t, w, 1, 1, mode=mode)
-        per_ct = timed(lambda: free(ctx.conv2d_apply(t, plan).cts))      # seconds / batch
-        costs[name] = max(0.0, per_ct - costs["rescale"]) / batch
+        conv = per_ct(lambda: free(ctx.conv2d_apply(t, plan).cts))      # seconds per output
+        costs[name] = max(0.0, conv - costs["rescale"]) / batch
         ctx.conv_plan_free(plan)
     t.cts = []
     pt.free()
@@ -492,12 +498,12 @@ def measure_costs_at(ctx, limbs, batch=64, reps=5):
 
 def estimate_cost(counts, costs, level_aware=True):
     """The analyser's figure for a circuit: sum over the operations of occurrences times cost.  With a cost table that
-    knows the change per limb, an occurrence at l limbs is charged cost + per_limb * (l - limbs of the table): the
-    counts carry the limbs summed over the occurrences, so the sum needs no list of the operations."""
-    flat = sum(counts[op] * costs[op] for op in COST_OPS)
-    if not level_aware or "per_limb" not in costs or "limb_sum" not in counts:
-        return flat
-    return flat + sum(costs["per_limb"][op] * (counts["limb_sum"][op] - counts[op] * costs["limbs"]) for op in COST_OPS)
+    knows each cost as c0 + c1 l + c2 l^2 in the level l, an occurrence is charged at its own level: the counts carry
+    the limbs and their squares summed over the occurrences, so the sum needs no list of the operations."""
+    if not level_aware or "poly" not in costs or "limb_sum" not in counts:
+        return sum(counts[op] * costs[op] for op in COST_OPS)
+    return sum(c[0] * counts[op] + c[1] * counts["limb_sum"][op] + c[2] * counts["limb_sq_sum"][op]
+               for op, c in ((op, costs["poly"][op]) for op in COST_OPS))
 
 
 def select_layout(ctx, layers, x, scale, limbs, costs, border=0, layouts=LAYOUTS):

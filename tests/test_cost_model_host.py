@@ -2,11 +2,12 @@
 from paper_1810_00845_amd import nets
 
 
-def table(limbs, per_limb=None):
+def table(limbs, poly=None):
     costs = {op: 0.0 for op in nets.COST_OPS}
     costs.update(rot_left=100.0, add=1.0, limbs=limbs)
-    if per_limb is not None:
-        costs["per_limb"] = dict({op: 0.0 for op in nets.COST_OPS}, **per_limb)
+    if poly is not None:
+        costs["poly"] = {op: (costs[op], 0.0, 0.0) for op in nets.COST_OPS}
+        costs["poly"].update(poly)
     return costs
 
 
@@ -14,9 +15,11 @@ def counts_of(ops):
     """ops: [(operation, limbs)], one entry per occurrence."""
     c = {op: 0 for op in nets.COST_OPS}
     c["limb_sum"] = {op: 0 for op in nets.COST_OPS}
+    c["limb_sq_sum"] = {op: 0 for op in nets.COST_OPS}
     for op, l in ops:
         c[op] += 1
         c["limb_sum"][op] += l
+        c["limb_sq_sum"][op] += l * l
     return c
 
 
@@ -26,11 +29,10 @@ def test_flat_table_is_count_times_cost():
 
 
 def test_level_aware_table_charges_each_occurrence_at_its_level():
-    # a rotation costs 100 at 8 limbs and 10 less per limb below
+    # a rotation costs 4 + 4 l + l^2: 100 at 8 limbs, 36 at 4, 16 at 2
     c = counts_of([("rot_left", 8), ("rot_left", 4), ("rot_left", 2), ("add", 8), ("add", 2)])
-    costs = table(8, {"rot_left": 10.0})
-    by_hand = 100.0 + (100.0 - 40.0) + (100.0 - 60.0) + 2.0
-    assert nets.estimate_cost(c, costs) == by_hand
+    costs = table(8, {"rot_left": (4.0, 4.0, 1.0)})
+    assert nets.estimate_cost(c, costs) == 100.0 + 36.0 + 16.0 + 2.0
     assert nets.estimate_cost(c, costs, level_aware=False) == 302.0
     # every operation at the table's own level: the two figures agree
     top = counts_of([("rot_left", 8)] * 3)

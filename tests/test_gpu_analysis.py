@@ -159,12 +159,13 @@ def test_layout_selection_by_cost_agrees_with_the_clock():
     flat = {lay: nets.estimate_cost(nets.analyse(ctx, layers, x, params["scale"], limbs, 0, lay)[0], costs, level_aware=False)
             for lay in est}
     print("unit costs (us):", {k: round(v * 1e6, 2) for k, v in costs.items() if isinstance(v, float)},
-          "per limb (us):", {k: round(v * 1e6, 3) for k, v in costs["per_limb"].items()},
+          "at the other levels (us):", {l: {k: round(v * 1e6, 2) for k, v in c.items()} for l, c in costs["levels"].items() if l != limbs},
           "estimates (ms):", {k: round(v * 1e3, 2) for k, v in est.items()},
           "at the top level's costs throughout (ms):", {k: round(v * 1e3, 2) for k, v in flat.items()}, flush=True)
     assert best == "chw_fc" and est["chw_fc"] < est["hw"] < est["chw"]
     # a key switch gets cheaper with every level the circuit descends: the level-aware figure is the lower one
-    assert costs["per_limb"]["rot_left"] > 0 and all(est[lay] < flat[lay] for lay in est)
+    low = costs["levels"][2]
+    assert low["rot_left"] < costs["rot_left"] and all(est[lay] < flat[lay] for lay in est)
     measured = {}
     for layout in nets.LAYOUTS:
         plans = {}
