@@ -48,6 +48,10 @@ def lib():
         L = _lib
         L.orc_create.restype = C.c_void_p
         L.orc_create.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.c_int, C.c_int, C.c_uint64, C.c_int]
+        L.orc_create_ex.restype = C.c_void_p
+        L.orc_create_ex.argtypes = L.orc_create.argtypes + [C.c_double, C.c_int, C.c_int]
+        L.orc_gauss_table_for.restype = C.c_int
+        L.orc_gauss_table_for.argtypes = [C.c_double, u64p]
         L.orc_destroy.argtypes = [C.c_void_p]
         L.orc_rnd.restype = C.c_uint64
         L.orc_rnd.argtypes = [C.c_uint64] * 4
@@ -151,11 +155,14 @@ class Ct:
 class Oracle:
     """One parameter set + secret key + evaluation keys."""
 
-    def __init__(self, log_n, q_bits, dnum, special_bits, seed, noise=True):
+    def __init__(self, log_n, q_bits, dnum, special_bits, seed, noise=True, sigma=3.2, secret_kind=0, hamming_weight=0):
+        """sigma: parameter of the error distribution; secret_kind 0: uniform ternary secret, 1: exactly
+        hamming_weight non-zero coefficients (see orc_create_ex)."""
         self.log_n, self.N, self.slots = log_n, 1 << log_n, 1 << (log_n - 1)
         self.L, self.dnum = len(q_bits), dnum
         qb = (C.c_int * len(q_bits))(*q_bits)
-        self._h = lib().orc_create(log_n, len(q_bits), qb, dnum, special_bits, seed, 1 if noise else 0)
+        self._h = lib().orc_create_ex(log_n, len(q_bits), qb, dnum, special_bits, seed, 1 if noise else 0,
+                                      float(sigma), int(secret_kind), int(hamming_weight))
         if not self._h:
             raise OracleError("bad parameters")
         self.K = lib().orc_num_special(self._h)

@@ -163,6 +163,30 @@ static const u64 GAUSS_CDT[19] = {
 
 void orc_gauss_table(u64 *out19) { memcpy(out19, GAUSS_CDT, sizeof GAUSS_CDT); }
 
+/* The same table for another sigma (optional parameter of the scheme's initialisation): tail cut at
+ * K = floor(6 sigma) <= ORC_MAX_CDT, out[k] = floor(2^63 * P(|X| <= k)) for k = 0..K-1, pmf proportional to
+ * exp(-x^2 / (2 sigma^2)) on |x| <= K.  sigma = 3.2 gives the table above (typed in from an 80-digit
+ * computation); any other is computed here in long double: weights w_x = expl(-x^2 / (2 sigma^2)), running sums
+ * c_0 = w_0, c_k = c_{k-1} + 2 w_k, total = c_K, entry k = floorl(2^63 * (c_k / total)) -- within a few units of
+ * 2^-63 of the exact value.  Returns K, or 0 for a sigma outside (0.2, ORC_MAX_CDT / 6]. */
+#define ORC_MAX_CDT 60
+int orc_gauss_table_for(double sigma, u64 *out) {
+    if (sigma == 3.2) { memcpy(out, GAUSS_CDT, sizeof GAUSS_CDT); return 19; }
+    if (!(sigma > 0.2) || sigma * 6.0 > (double)ORC_MAX_CDT) return 0;
+    int K = (int)floor(6.0 * sigma);
+    long double two_s2 = 2.0L * (long double)sigma * (long double)sigma;
+    long double c[ORC_MAX_CDT + 1];
+    for (int x = 0; x <= K; x++) {
+        long double w = expl(-((long double)x * (long double)x) / two_s2);
+        c[x] = x == 0 ? w : c[x - 1] + 2.0L * w;
+    }
+    for (int k = 0; k < K; k++) {
+        long double v = floorl(ldexpl(c[k] / c[K], 63));
+        out[k] = v >= 9223372036854775807.0L ? 9223372036854775807ULL : (u64)v;
+    }
+    return K;
+}
+
 /* one discrete Gaussian integer from one 64-bit word */
 i64 orc_gauss_from_word(u64 u) {
     int negative = (int)(u & 1);
@@ -189,7 +213,9 @@ typedef struct {
     int dnum;
     int alpha;      /* primes per digit = ceil(L/dnum) */
     u64 seed;
-    int noise;      /* 0: all error polynomials are zero; 1: sigma = 3.2 */
+    int noise;      /* 0: all error polynomials are zero; 1: discrete Gaussian with the table below */
+    u64 cdt[ORC_MAX_CDT];      /* floor(2^63 P(|X| <= k)) of the context's sigma */
+    int cdt_n;
     u64 mod[ORC_MAX_PRIMES];   /* q_0..q_{L-1}, p_0..p_{K-1} */
     u64 psi[ORC_MAX_PRIMES];
     u64 n_inv[ORC_MAX_PRIMES];
@@ -216,15 +242,39 @@ void orc_intt(const orc_ctx *c, int prime, u64 *a);
  * q_i in order.  The ternary secret s is drawn here (kind 1, ctr 0, idx =
  * coefficient).
  */
+static i64 gauss_from_table(const u64 *cdt, int cdt_n, u64 u) {
+    int negative = (int)(u & 1);
+    u64 v = u >> 1;
+    i64 mag = 0;
+    for (int k = 0; k < cdt_n; k++) mag += (v >= cdt[k]);
+    return negative ? -mag : mag;
+}
+
+/* secret_kind 0: every coefficient uniform in {-1, 0, 1}.  secret_kind 1: exactly h non-zero coefficients (the
+ * sparse secrets of HEAAN): a partial Fisher-Yates shuffle of the positions 0..N-1 -- step i = 0..h-1 draws the word
+ * u = rnd(seed, 1, 0, i), exchanges position i of the permutation with position i + (u >> 1) mod (N - i), and the
+ * coefficient now named by position i becomes -1 if the low bit of u is set, +1 otherwise. */
+orc_ctx *orc_create_ex(int log_n, int num_q, const int *q_bits, int dnum, int special_bits,
+                       u64 seed, int noise, double sigma, int secret_kind, int h);
+
 orc_ctx *orc_create(int log_n, int num_q, const int *q_bits, int dnum, int special_bits,
                     u64 seed, int noise) {
+    return orc_create_ex(log_n, num_q, q_bits, dnum, special_bits, seed, noise, 3.2, 0, 0);
+}
+
+orc_ctx *orc_create_ex(int log_n, int num_q, const int *q_bits, int dnum, int special_bits,
+                       u64 seed, int noise, double sigma, int secret_kind, int h) {
     if (log_n < 1 || log_n > 17 || num_q < 1 || dnum < 1 || dnum > num_q) return NULL;
+    if (secret_kind != 0 && secret_kind != 1) return NULL;
+    if (secret_kind == 1 && (h < 1 || (u64)h > ((u64)1 << log_n))) return NULL;
     int alpha = (num_q + dnum - 1) / dnum;
     if (num_q + alpha > ORC_MAX_PRIMES) return NULL;
     orc_ctx *c = calloc(1, sizeof *c);
     c->log_n = log_n; c->n = (u64)1 << log_n;
     c->L = num_q; c->K = alpha; c->dnum = dnum; c->alpha = alpha;
     c->seed = seed; c->noise = noise;
+    c->cdt_n = orc_gauss_table_for(sigma, c->cdt);
+    if (!c->cdt_n) { free(c); return NULL; }
     int total = num_q + alpha;
     for (int i = 0; i < total; i++) {
         int bits = i < num_q ? q_bits[i] : special_bits;
@@ -245,7 +295,19 @@ orc_ctx *orc_create(int log_n, int num_q, const int *q_bits, int dnum, int speci
     }
     c->s_coef = malloc(c->n * sizeof(i64));
     c->s_ntt = malloc((size_t)total * c->n * sizeof(u64));
-    for (u64 j = 0; j < c->n; j++) c->s_coef[j] = orc_ternary_from_word(orc_rnd(seed, 1, 0, j));
+    if (secret_kind == 0) {
+        for (u64 j = 0; j < c->n; j++) c->s_coef[j] = orc_ternary_from_word(orc_rnd(seed, 1, 0, j));
+    } else {
+        u64 *perm = malloc(c->n * sizeof(u64));
+        for (u64 j = 0; j < c->n; j++) { perm[j] = j; c->s_coef[j] = 0; }
+        for (u64 i = 0; i < (u64)h; i++) {
+            u64 u = orc_rnd(seed, 1, 0, i);
+            u64 j = i + (u >> 1) % (c->n - i);
+            u64 t = perm[i]; perm[i] = perm[j]; perm[j] = t;
+            c->s_coef[perm[i]] = (u & 1) ? -1 : 1;
+        }
+        free(perm);
+    }
     for (int i = 0; i < total; i++) {
         u64 *dst = c->s_ntt + (size_t)i * c->n;
         for (u64 j = 0; j < c->n; j++) dst[j] = reduce_i64(c->s_coef[j], c->mod[i]);
@@ -322,7 +384,7 @@ void orc_sample_uniform(const orc_ctx *c, u64 kind, u64 ctr, int prime, u64 *out
 /* error polynomial as signed integers (all zero when noise is off) */
 void orc_sample_error(const orc_ctx *c, u64 kind, u64 ctr, i64 *out) {
     for (u64 j = 0; j < c->n; j++)
-        out[j] = c->noise ? orc_gauss_from_word(orc_rnd(c->seed, kind, ctr, j)) : 0;
+        out[j] = c->noise ? gauss_from_table(c->cdt, c->cdt_n, orc_rnd(c->seed, kind, ctr, j)) : 0;
 }
 
 /* signed coefficient vector -> NTT form modulo prime i */

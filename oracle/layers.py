@@ -519,6 +519,27 @@ def mask_tensor_fixed(o: Oracle, t: OTensor, ints):
     return replace(t, cts=outs, clean=1)
 
 
+def add_bias(o: Oracle, t: OTensor, bias):
+    """A bias per channel after a linear layer (not part of Algorithm 1; the HISA offers addPlain for it): channel
+    c's elements get bias[c], every other slot stays as it is -- one addPlain per ciphertext of the vector that holds
+    bias[c] on the element slots of each channel of that ciphertext, encoded at the ciphertext's own scale.  Returns
+    (tensor, the encoded integers [ciphertexts per image][N])."""
+    per = cts_per_image(t)
+    sl = np.asarray(tensor_slots(t)).reshape(t.c_inner, t.height * t.width)
+    coeffs = np.zeros((per, o.N), dtype=np.int64)
+    for j in range(per):
+        z = np.zeros(o.slots)
+        for cl in range(min(t.c_inner, t.channels - j * t.c_inner)):
+            z[sl[cl]] = bias[j * t.c_inner + cl]
+        coeffs[j] = o.encode_coeffs(z, t.cts[j].scale)
+    return add_bias_fixed(o, t, coeffs), coeffs
+
+
+def add_bias_fixed(o: Oracle, t: OTensor, coeffs):
+    per = cts_per_image(t)
+    return replace(t, cts=[o.add_plain(ct, o.pt_from_coeffs(coeffs[i % per], ct.scale, ct.limbs)) for i, ct in enumerate(t.cts)])
+
+
 def chw_conv_geometry(o: Oracle, t: OTensor, fh, fw, pad_same=False):
     """CHW-tiled convolution: the c_inner channel blocks of a ciphertext are combined along diagonals, output block b
     reading input block (b + d) mod c_inner for d = 0 .. c_inner-1, so one rotation per (tap, d) brings every needed

@@ -561,3 +561,36 @@ def test_shared_moddown_convolutions():
     lazy, _ = layers.conv2d_chw(o, tc, wc, pad_same=True, shared_moddown=True)
     assert (lazy.c_inner, lazy.clean, len(lazy.cts), lazy.cts[0].limbs) == (4, 1, 2, 2)
     assert np.abs(layers.tensor_decrypt(o, lazy) - plain_net.conv2d(xc, wc, pad_same=True)).max() <= 1e-3
+
+
+@pytest.mark.parametrize("chw", [False, True])
+def test_bias_is_added_to_the_elements_of_its_channel_only(chw):
+    """addPlain of the per-channel bias vector: element slots move by exactly bias[c], every other slot by nothing
+    (a clean tensor stays clean); a bias vector in the wrong channel order fails."""
+    o = Oracle(10, [50, 40], 2, 55, seed=14)
+    x = synth.image(33, 5, 3, 3)[None]
+    bias = np.array([0.5, -1.25, 2.0, 0.0, -0.75])
+    if chw:
+        t = layers.tensor_encrypt_chw(o, x, 2.0 ** 40, 2, c_inner=2, c_stride=16, h_stride=4)
+    else:
+        t = layers.tensor_encrypt(o, x, 2.0 ** 40, 2, h_stride=4)
+    before = [o.decode(o.decrypt(ct)).real for ct in t.cts]
+    out, coeffs = layers.add_bias(o, t, bias)
+    assert coeffs.shape == (len(t.cts), o.N) and out.cts[0].scale == t.cts[0].scale and out.cts[0].limbs == 2
+    assert np.abs(layers.tensor_decrypt(o, out) - (x + bias[None, :, None, None])).max() <= 1e-6
+    elems = np.zeros((len(t.cts), o.slots), dtype=bool)
+    sl = np.asarray(layers.tensor_slots(t)).reshape(t.c_inner, -1)
+    for j in range(len(t.cts)):
+        for cl in range(min(t.c_inner, 5 - j * t.c_inner)):
+            elems[j, sl[cl]] = True
+    for j, ct in enumerate(out.cts):
+        z = o.decode(o.decrypt(ct)).real
+        assert np.abs((z - before[j])[~elems[j]]).max() <= 1e-6       # nothing outside the elements
+    wrong, _ = layers.add_bias(o, t, bias[::-1])
+    assert np.abs(layers.tensor_decrypt(o, wrong) - (x + bias[None, :, None, None])).max() > 0.1
+    # a batch of two images takes the same vectors per image
+    x2 = np.concatenate([x, 2 * x])
+    t2 = layers.tensor_encrypt_chw(o, x2, 2.0 ** 40, 2, c_inner=2, c_stride=16, h_stride=4) if chw else \
+        layers.tensor_encrypt(o, x2, 2.0 ** 40, 2, h_stride=4)
+    out2, _ = layers.add_bias(o, t2, bias)
+    assert np.abs(layers.tensor_decrypt(o, out2) - (x2 + bias[None, :, None, None])).max() <= 1e-6

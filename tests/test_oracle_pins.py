@@ -154,6 +154,86 @@ def test_gauss_and_ternary_samplers():
     assert [L.orc_ternary_from_word(w) for w in (0, 1, 2, 3, 4, 5)] == [0, 1, -1, 0, 1, -1]
 
 
+@pytest.mark.parametrize("sigma", [0.8, 1.5, 3.19, 6.0, 10.0])
+def test_gauss_table_for_other_sigmas(sigma):
+    """The computed tables against the pmf's definition at 80 digits: entries within 8 units of 2^-63 (the long double
+    computation carries 64 bits), strictly increasing, tail cut at floor(6 sigma), variance of the tabulated
+    distribution = sigma^2 up to the cut."""
+    import ctypes
+    import mpmath as mp
+    mp.mp.dps = 80
+    K = int(math.floor(6 * sigma))
+    tab = np.zeros(60, dtype=np.uint64)
+    assert lib().orc_gauss_table_for(ctypes.c_double(sigma), tab.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))) == K
+    s = mp.mpf(sigma)                      # the double's exact value, as the C code sees it
+    w = [mp.e ** (-(mp.mpf(x) ** 2) / (2 * s ** 2)) for x in range(K + 1)]
+    total = w[0] + 2 * sum(w[1:])
+    cum = mp.mpf(0)
+    for k in range(K):
+        cum += w[0] if k == 0 else 2 * w[k]
+        assert abs(int(tab[k]) - int(mp.floor(mp.mpf(2) ** 63 * cum / total))) <= 8
+        assert k == 0 or tab[k] > tab[k - 1]
+    probs = np.diff(np.concatenate([[0.0], tab[:K].astype(np.float64), [2.0 ** 63]])) / 2.0 ** 63
+    var = sum(p * k * k for k, p in enumerate(probs))
+    assert abs(math.sqrt(var) - sigma) < 2e-3 * sigma
+
+
+def test_gauss_table_rejects_bad_sigmas_and_keeps_the_literal_one():
+    import ctypes
+    tab, lit = np.zeros(60, dtype=np.uint64), np.zeros(19, dtype=np.uint64)
+    p = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))
+    for bad in (0.0, -1.0, 0.2, 10.5, float("nan")):
+        assert lib().orc_gauss_table_for(ctypes.c_double(bad), p(tab)) == 0
+    assert lib().orc_gauss_table_for(ctypes.c_double(3.2), p(tab)) == 19
+    lib().orc_gauss_table(p(lit))
+    assert np.array_equal(tab[:19], lit)
+
+
+def test_error_polynomials_follow_the_context_sigma():
+    """Encryption noise of a context made with sigma = 1.5: decrypting a fresh encryption of zero gives
+    e0 + e1 s + ... whose spread follows sigma; compared with the default context on the same seed."""
+    spread = {}
+    for sigma in (1.5, 3.2, 6.0):
+        o = Oracle(10, [40], 1, 45, seed=5, sigma=sigma)
+        ct = o.encrypt(o.pt_from_coeffs(np.zeros(o.N, dtype=np.int64), 1.0, 1))
+        spread[sigma] = np.std(np.array(o.pt_coeffs(o.decrypt(ct)), dtype=np.float64))
+    # noise of a fresh ciphertext = e0 + e1 s + v e_pk-like terms, each proportional to sigma
+    assert 0.4 < spread[1.5] / spread[3.2] < 0.55 and 1.7 < spread[6.0] / spread[3.2] < 2.05
+
+
+@pytest.mark.parametrize("log_n,h", [(4, 1), (4, 16), (10, 64), (12, 192)])
+def test_fixed_hamming_weight_secret(log_n, h):
+    o = Oracle(log_n, [40], 1, 45, seed=9, secret_kind=1, hamming_weight=h)
+    s = o.secret_coeffs()
+    assert np.count_nonzero(s) == h and set(np.unique(s)) <= {-1, 0, 1}
+    if h >= 64:      # signs and positions both look uniform
+        assert 0.3 < (s == 1).sum() / h < 0.7
+        pos = np.nonzero(s)[0]
+        assert abs(pos.mean() / o.N - 0.5) < 0.12 and (pos < o.N // 2).sum() > h // 4
+    # another seed moves the support; the uniform ternary secret of the same seed is a different one
+    assert not np.array_equal(s, Oracle(log_n, [40], 1, 45, seed=10, secret_kind=1, hamming_weight=h).secret_coeffs()) or h == 1 << log_n
+    assert np.count_nonzero(Oracle(log_n, [40], 1, 45, seed=9).secret_coeffs()) != h or log_n == 4
+    # the scheme works with it: encrypt / decrypt round trip
+    m = np.arange(o.N, dtype=np.int64) - o.N // 2
+    ct = o.encrypt(o.pt_from_coeffs(m << 20, 1.0, 1))
+    got = np.array(o.pt_coeffs(o.decrypt(ct)), dtype=np.int64)
+    assert np.abs(got - (m << 20)).max() < 1 << 12
+
+
+def test_fixed_hamming_weight_positions_are_uniform_over_seeds():
+    """Brute force on a tiny ring: over many seeds every position is hit equally often (N = 16, h = 4: 1/4 each)."""
+    hits = np.zeros(16)
+    for seed in range(600):
+        hits += Oracle(4, [30], 1, 40, seed=seed, secret_kind=1, hamming_weight=4).secret_coeffs() != 0
+    assert np.abs(hits / 600 - 0.25).max() < 0.07
+
+
+def test_bad_secret_parameters_are_rejected():
+    for kw in (dict(secret_kind=2), dict(secret_kind=1, hamming_weight=0), dict(secret_kind=1, hamming_weight=17), dict(sigma=0.0)):
+        with pytest.raises(Exception):
+            Oracle(4, [30], 1, 40, seed=1, **kw)
+
+
 # ------------------------------------------------------------------- ntt ----
 @pytest.mark.parametrize("log_n", [2, 5, 8])
 def test_ntt_is_the_defining_sum(log_n):
