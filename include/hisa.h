@@ -59,8 +59,14 @@ typedef struct hisa_pt hisa_pt;
  * (q_bits[i] bits each, = 1 mod 2N, the largest unused such prime below
  * 2^bits), dnum key-switching digits of alpha = ceil(L/dnum) primes, alpha
  * special primes of special_bits bits, and the seed of all randomness.
- * noise = 1: discrete Gaussian errors, sigma 3.2; noise = 0: all error
+ * noise = 1: discrete Gaussian errors; noise = 0: all error
  * polynomials zero (for exactness tests only).  Bits must lie in [log_n+2, 60].
+ * sigma: parameter of the error distribution, pmf proportional to
+ * exp(-x^2 / (2 sigma^2)) on |x| <= floor(6 sigma); 0 selects 3.2, otherwise
+ * 0.2 < sigma <= 10.  secret_kind = 0: every secret coefficient uniform in
+ * {-1, 0, 1}; 1: exactly hamming_weight non-zero coefficients (+-1) at
+ * uniformly drawn positions (the sparse secrets of HEAAN),
+ * 1 <= hamming_weight <= N.  Anything else is HISA_ERR_ARG.
  */
 typedef struct {
     uint32_t log_n;               /* 10 .. 16 */
@@ -70,6 +76,9 @@ typedef struct {
     uint32_t special_bits;
     uint32_t noise;
     uint64_t seed;
+    double sigma;                 /* 0: 3.2 */
+    uint32_t secret_kind;         /* 0 uniform ternary, 1 fixed Hamming weight */
+    uint32_t hamming_weight;      /* secret_kind = 1 only */
 } hisa_params;
 
 /* hip_stream: a hipStream_t (may be NULL).  The context allocates its tables,
@@ -445,6 +454,14 @@ int hisa_fc_plan_free(hisa_ctx* ctx, hisa_fc_plan* plan);
  * modulus, then divScalar: same values and scale, one level lower, clean = 1.
  * hisa_tensor_mask_fixed takes mask_coeffs[ceil(C/c_inner)][N] at mask_scale. */
 int hisa_tensor_mask(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out);
+/* A bias per channel after a linear layer (Algorithm 1 has none; Fig. "Instructions of the HISA" offers addPlain for
+ * it).  In place: every ciphertext of t gets, by one addPlain, the vector that holds bias[c] (host, t->channels
+ * values) on the element slots of each channel c it carries and zero elsewhere, encoded at the ciphertexts' own
+ * scale -- level, scale and `clean` stay as they are.  All ciphertexts of t must be at one scale
+ * (HISA_ERR_SCALE_MISMATCH); |bias[c]| * scale must stay below 2^62 (HISA_ERR_ARG: rescale first).
+ * hisa_tensor_add_bias_fixed takes the encoded integers bias_coeffs[ceil(C/c_inner)][N] instead. */
+int hisa_tensor_add_bias(hisa_ctx* ctx, hisa_tensor* t, const double* bias);
+int hisa_tensor_add_bias_fixed(hisa_ctx* ctx, hisa_tensor* t, const int64_t* bias_coeffs);
 int hisa_tensor_mask_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int64_t* mask_coeffs, double mask_scale,
                            hisa_tensor* out);
 /* Layout switches (Sec. "Data Layout Selection": the layouts that change the

@@ -20,14 +20,6 @@ __device__ __forceinline__ u64 stream_key(u64 seed, u64 kind, u64 ctr) {
 }
 __device__ __forceinline__ u64 rnd_at(u64 key, u64 idx) { return mix64(key + 0x3c6ef372fe94f82bULL * (idx + 1)); }
 
-// floor(2^63 * P(|X| <= k)) for the discrete Gaussian with sigma = 3.2 cut at |x| <= 19
-__constant__ u64 c_gauss_cdt[19] = {
-    1149872836518706973ULL, 3340023669317320718ULL, 5231742859181312982ULL, 6713673040852152709ULL,
-    7766573333558595572ULL, 8445050410543775182ULL, 8841576294031517592ULL, 9051758687454227207ULL,
-    9152802460441190481ULL, 9196859083481262423ULL, 9214281214904026344ULL, 9220529772758650828ULL,
-    9222562348483741346ULL, 9223162004373033245ULL, 9223322456656299389ULL, 9223361395058736926ULL,
-    9223369965413244325ULL, 9223371676247247624ULL, 9223371985993021523ULL};
-
 __global__ __launch_bounds__(NT) void sample_uniform_kernel(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr,
                                                             PolyMap map, u64 batch_stride, u64 ctr_step, u64* out,
                                                             int log_n) {
@@ -54,10 +46,11 @@ hipError_t launch_sample_uniform(const PrimeConst* primes, u64 seed, u64 kind, u
 
 // One small signed polynomial per batch entry (ternary secret, or Gaussian
 // error, or zero), reduced into every mapped limb.  raw (may be null) receives
-// the signed coefficients of batch entry 0.
+// the signed coefficients of batch entry 0.  cdt[k] = floor(2^63 * P(|X| <= k)), k < cdt_n, of the context's
+// error distribution: the magnitude is the number of entries the word's upper 63 bits reach, the sign its low bit.
 __global__ __launch_bounds__(NT) void sample_small_kernel(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr,
-                                                          int noise_on, int ternary, PolyMap map, u64 batch_stride,
-                                                          u64 ctr_step, u64* out, i64* raw, int log_n) {
+                                                          int noise_on, int ternary, const u64* cdt, int cdt_n, PolyMap map,
+                                                          u64 batch_stride, u64 ctr_step, u64* out, i64* raw, int log_n) {
     const u64 n = (u64)1 << log_n;
     const int b = blockIdx.y;
     const u64 key = stream_key(seed, kind, ctr + (u64)b * ctr_step);
@@ -70,7 +63,7 @@ __global__ __launch_bounds__(NT) void sample_small_kernel(const PrimeConst* prim
     } else if (noise_on) {
         u64 mag_src = w >> 1;
         i64 mag = 0;
-        for (int k = 0; k < 19; k++) mag += (mag_src >= c_gauss_cdt[k]);
+        for (int k = 0; k < cdt_n; k++) mag += (mag_src >= cdt[k]);
         v = (w & 1) ? -mag : mag;
     } else {
         v = 0;
@@ -85,13 +78,14 @@ __global__ __launch_bounds__(NT) void sample_small_kernel(const PrimeConst* prim
 }
 
 hipError_t launch_sample_small(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, int noise_on, int ternary,
-                               const PolyMap& map, int n_polys, u64 batch_stride, u64 ctr_step, u64* out, i64* raw,
-                               int log_n, hipStream_t st) {
+                               const u64* cdt, int cdt_n, const PolyMap& map, int n_polys, u64 batch_stride, u64 ctr_step,
+                               u64* out, i64* raw, int log_n, hipStream_t st) {
     DRY_RUN_RETURN();
+    if (!ternary && noise_on && (!cdt || cdt_n <= 0)) return hipErrorInvalidValue;
     dim3 grid((1u << log_n) / NT, n_polys);  // n_polys = batch entries here
     ProfScope prof__("sample_small_kernel", st);
-    hipLaunchKernelGGL(sample_small_kernel, grid, dim3(NT), 0, st, primes, seed, kind, ctr, noise_on, ternary, map,
-                       batch_stride, ctr_step, out, raw, log_n);
+    hipLaunchKernelGGL(sample_small_kernel, grid, dim3(NT), 0, st, primes, seed, kind, ctr, noise_on, ternary, cdt, cdt_n,
+                       map, batch_stride, ctr_step, out, raw, log_n);
     return hipGetLastError();
 }
 

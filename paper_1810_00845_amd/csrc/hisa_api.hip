@@ -378,6 +378,7 @@ static int modup_table(hisa_ctx* ctx, int digit, int a, ConvTable** out) {
 
 static int sample_secret(hisa_ctx* ctx);
 static int fp_post_tables(hisa_ctx* ctx, int l, double** post_q, double** post_p, bool lookup_only);
+static std::vector<u64> gauss_table(double sigma);
 
 extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** out) {
     if (!prm || !out) return HISA_ERR_ARG;
@@ -385,6 +386,9 @@ extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** 
     if (prm->log_n < 10 || prm->log_n > 16 || prm->num_q < 1 || prm->num_q > HISA_MAX_Q || prm->dnum < 1 ||
         prm->dnum > prm->num_q || prm->noise > 1)
         return HISA_ERR_ARG;
+    if (prm->secret_kind > 1 || (prm->secret_kind == 1 && (prm->hamming_weight < 1 || prm->hamming_weight > (1u << prm->log_n))))
+        return HISA_ERR_ARG;
+    if (prm->sigma != 0.0 && !(prm->sigma > 0.2 && prm->sigma <= 10.0)) return HISA_ERR_ARG;
     const uint32_t alpha = (prm->num_q + prm->dnum - 1) / prm->dnum;
     if (prm->num_q + alpha > HISA_MAX_PRIMES) return HISA_ERR_ARG;
     for (uint32_t i = 0; i < prm->num_q; i++)
@@ -523,6 +527,11 @@ extern "C" int hisa_create(const hisa_params* prm, void* hip_stream, hisa_ctx** 
         for (u64 j = 0; j < n / 2; j++) { pow5[j] = g; g = (g * 5u) & (uint32_t)(2 * n - 1); }
         HIP_TRY(ctx, upload(&ctx->d_pow5, pow5));
     }
+    {
+        const std::vector<u64> cdt = gauss_table(prm->sigma == 0.0 ? 3.2 : prm->sigma);
+        ctx->gauss_cdt_n = (int)cdt.size();
+        HIP_TRY(ctx, upload(&ctx->d_gauss_cdt, cdt));
+    }
     HIP_TRY(ctx, hipMalloc((void**)&ctx->d_secret, (size_t)ctx->total * n * sizeof(u64)));
     TRY(sample_secret(ctx));
     TRY(scratch_address(ctx, &ctx->device, &ctx->noalloc_ws));
@@ -555,6 +564,7 @@ extern "C" int hisa_destroy(hisa_ctx* ctx) {
     (void)hipFree(ctx->d_pinv_f); (void)hipFree(ctx->d_moddown_hat_pin);
     (void)hipFree(ctx->d_fp_scratch);
     (void)hipFree(ctx->d_pmod); (void)hipFree(ctx->d_cos); (void)hipFree(ctx->d_sin); (void)hipFree(ctx->d_pow5);
+    (void)hipFree(ctx->d_gauss_cdt);
     delete ctx;
     return HISA_OK;
 }
@@ -570,10 +580,70 @@ extern "C" int hisa_sync(hisa_ctx* ctx) {
 // ---------------------------------------------------------------------------
 // keys
 // ---------------------------------------------------------------------------
+// The generator of all randomness on the host (the kernels hold the device form): two rounds of a 64-bit mixer,
+// the first over seed and stream (kind, counter), the second over the index.
+static u64 host_mix(u64 x) {
+    x ^= x >> 32; x *= 0x6a09e667f3bcc909ULL;
+    x ^= x >> 29; x *= 0xbb67ae8584caa73bULL;
+    return x ^ (x >> 32);
+}
+static u64 host_rnd(u64 seed, u64 kind, u64 ctr, u64 idx) {
+    const u64 step = 0x3c6ef372fe94f82bULL;
+    return host_mix(host_mix(seed + step * (((kind << 56) | ctr) + 1)) + step * (idx + 1));
+}
+
+// Cumulative table of the error distribution: entry k = floor(2^63 * P(|X| <= k)), k < floor(6 sigma), for the pmf
+// proportional to exp(-x^2 / (2 sigma^2)) cut at |x| <= floor(6 sigma).  For sigma = 3.2 the entries are constants
+// (computed once with 80 digits); for any other sigma they are computed here in extended precision, by running sums
+// from x = 0 upwards, which places them within a few units of 2^-63 of the exact values.
+static std::vector<u64> gauss_table(double sigma) {
+    static const u64 table_3_2[19] = {
+        1149872836518706973ULL, 3340023669317320718ULL, 5231742859181312982ULL, 6713673040852152709ULL,
+        7766573333558595572ULL, 8445050410543775182ULL, 8841576294031517592ULL, 9051758687454227207ULL,
+        9152802460441190481ULL, 9196859083481262423ULL, 9214281214904026344ULL, 9220529772758650828ULL,
+        9222562348483741346ULL, 9223162004373033245ULL, 9223322456656299389ULL, 9223361395058736926ULL,
+        9223369965413244325ULL, 9223371676247247624ULL, 9223371985993021523ULL};
+    if (sigma == 3.2) return std::vector<u64>(table_3_2, table_3_2 + 19);
+    const int cut = (int)floor(6.0 * sigma);
+    const long double denom = 2.0L * (long double)sigma * (long double)sigma;
+    std::vector<long double> run((size_t)cut + 1);
+    for (int x = 0; x <= cut; x++) {
+        const long double w = expl(-((long double)x * (long double)x) / denom);
+        run[x] = x ? run[x - 1] + 2.0L * w : w;
+    }
+    std::vector<u64> t((size_t)cut);
+    for (int k = 0; k < cut; k++) {
+        const long double v = floorl(ldexpl(run[k] / run[cut], 63));
+        t[k] = v >= 9223372036854775807.0L ? 9223372036854775807ULL : (u64)v;
+    }
+    return t;
+}
+
+// The secret, NTT form over all primes.  Uniform ternary: one word per coefficient, drawn by the sampling kernel.
+// Fixed Hamming weight h: a partial shuffle of the positions 0..N-1 on the host (h dependent steps: step i draws
+// word i of the secret's stream, exchanges entry i of the permutation with entry i + (word >> 1) mod (N - i), and
+// gives the coefficient now at entry i the sign of the word's low bit), reduced and transformed on the GPU.
 static int sample_secret(hisa_ctx* ctx) {
     PolyMap all = identity_map((int)ctx->total);
-    HIP_TRY(ctx, launch_sample_small(ctx->d_primes, ctx->prm.seed, 1, 0, 0, 1, all, 1, 0, 0, ctx->d_secret, nullptr,
-                                     (int)ctx->log_n, ctx->stream));
+    if (ctx->prm.secret_kind == 1) {
+        const u64 n = ctx->N;
+        std::vector<u64> perm(n);
+        for (u64 j = 0; j < n; j++) perm[j] = j;
+        ctx->sparse_secret.assign(n, 0);
+        for (u64 i = 0; i < ctx->prm.hamming_weight; i++) {
+            const u64 u = host_rnd(ctx->prm.seed, 1, 0, i);
+            std::swap(perm[i], perm[i + (u >> 1) % (n - i)]);
+            ctx->sparse_secret[perm[i]] = (u & 1) ? -1 : 1;
+        }
+        Temp co(ctx, n * sizeof(i64));
+        if (!co.ok()) return HISA_ERR_OOM;
+        HIP_TRY(ctx, hipMemcpyAsync(co.blk->ptr, ctx->sparse_secret.data(), n * sizeof(i64), hipMemcpyHostToDevice, ctx->stream));
+        HIP_TRY(ctx, launch_reduce_i64(ctx->d_primes, co.as<i64>(), ctx->d_secret, (int)ctx->total, 1, (int)ctx->log_n, ctx->stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));   // the host vector is pageable memory
+    } else {
+        HIP_TRY(ctx, launch_sample_small(ctx->d_primes, ctx->prm.seed, 1, 0, 0, 1, nullptr, 0, all, 1, 0, 0, ctx->d_secret, nullptr,
+                                         (int)ctx->log_n, ctx->stream));
+    }
     HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, ctx->d_secret, 0, (int)ctx->total, all, ctx->stream));
     return HISA_OK;
 }
@@ -591,7 +661,8 @@ static int fill_switch_key(hisa_ctx* ctx, u64 key_id, const u64* target, const S
         HIP_TRY(ctx, launch_sample_uniform(ctx->d_primes, ctx->prm.seed, 4, ctr, all, (int)total, 0, 0, digit + total * n,
                                            (int)ctx->log_n, ctx->stream));
         HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, digit + total * n, 0, (int)total, all, ctx->stream));
-        HIP_TRY(ctx, launch_sample_small(ctx->d_primes, ctx->prm.seed, 5, ctr, (int)ctx->prm.noise, 0, all, 1, 0, 0, e.u(),
+        HIP_TRY(ctx, launch_sample_small(ctx->d_primes, ctx->prm.seed, 5, ctr, (int)ctx->prm.noise, 0, ctx->d_gauss_cdt,
+                                         ctx->gauss_cdt_n, all, 1, 0, 0, e.u(),
                                          nullptr, (int)ctx->log_n, ctx->stream));
         HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, e.u(), 0, (int)total, all, ctx->stream));
         HIP_TRY(ctx, launch_key_combine(ctx->d_primes, ctx->d_secret, target, e.u(), ctx->d_pmod, digit, (int)total,
@@ -800,7 +871,8 @@ extern "C" int hisa_encrypt_batch(hisa_ctx* ctx, const hisa_pt* const* pts, size
     HIP_TRY(ctx, launch_sample_uniform(ctx->d_primes, ctx->prm.seed, 2, ctx->enc_counter, lm, (int)(n * l), 2 * lw, 1,
                                        ct + lw, (int)ctx->log_n, ctx->stream));
     HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, ct + lw, 2 * lw, (int)(n * l), lm, ctx->stream));
-    HIP_TRY(ctx, launch_sample_small(ctx->d_primes, ctx->prm.seed, 3, ctx->enc_counter, (int)ctx->prm.noise, 0, lm, (int)n,
+    HIP_TRY(ctx, launch_sample_small(ctx->d_primes, ctx->prm.seed, 3, ctx->enc_counter, (int)ctx->prm.noise, 0, ctx->d_gauss_cdt,
+                                     ctx->gauss_cdt_n, lm, (int)n,
                                      lw, 1, e.u(), nullptr, (int)ctx->log_n, ctx->stream));
     HIP_TRY(ctx, launch_ntt(ctx->tabs, (int)ctx->log_n, e.u(), lw, (int)(n * l), lm, ctx->stream));
     const u64* pt_base = pts[0]->data;
@@ -2247,11 +2319,15 @@ extern "C" int hisa_key_export(hisa_ctx* ctx, uint64_t key_id, uint64_t* host) {
 
 extern "C" int hisa_secret_export(hisa_ctx* ctx, int64_t* host_coeffs) {
     if (!ctx || !host_coeffs) return HISA_ERR_ARG;
+    if (ctx->prm.secret_kind == 1) {
+        memcpy(host_coeffs, ctx->sparse_secret.data(), ctx->N * sizeof(i64));
+        return HISA_OK;
+    }
     Temp raw(ctx, ctx->N * sizeof(i64));
     Temp scratch(ctx, ctx->N * sizeof(u64));
     if (!raw.ok() || !scratch.ok()) return HISA_ERR_OOM;
     PolyMap one = identity_map(1);
-    HIP_TRY(ctx, launch_sample_small(ctx->d_primes, ctx->prm.seed, 1, 0, 0, 1, one, 1, 0, 0, scratch.u(), raw.as<i64>(),
+    HIP_TRY(ctx, launch_sample_small(ctx->d_primes, ctx->prm.seed, 1, 0, 0, 1, nullptr, 0, one, 1, 0, 0, scratch.u(), raw.as<i64>(),
                                      (int)ctx->log_n, ctx->stream));
     HIP_TRY(ctx, hipMemcpyAsync(host_coeffs, raw.blk->ptr, ctx->N * sizeof(i64), hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));

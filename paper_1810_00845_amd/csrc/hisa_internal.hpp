@@ -129,6 +129,9 @@ struct hisa_ctx {
     double *d_cos, *d_sin;  // [2N] roots of unity exp(i*pi*t/N)
     FpPrime* d_fprimes;     // fp64 path tables (null when not applicable)
     double *d_ftw, *d_utw, *d_vtw, *d_pinv_f;
+    u64* d_gauss_cdt = nullptr;            // [gauss_cdt_n] floor(2^63 P(|X| <= k)) of the error distribution
+    int gauss_cdt_n = 0;
+    std::vector<i64> sparse_secret;        // secret_kind = 1: the secret's coefficients, drawn on the host
     double* d_moddown_hat_pin = nullptr;   // [K][total] (P/p_m) * P^-1 mod q_i, centred: ModDown's conversion with the division folded in
     uint32_t* d_pow5;       // [N/2] 5^j mod 2N
     double* d_fp_scratch;   // fp64 path: one polynomial per resident workgroup of the conversion kernels
@@ -359,8 +362,8 @@ hipError_t launch_inner_product_sum_fp(const FpPrime* fprimes, const double* ext
 hipError_t launch_sample_uniform(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, const PolyMap& map, int n_polys,
                                  u64 batch_stride, u64 ctr_step, u64* out, int log_n, hipStream_t st);
 hipError_t launch_sample_small(const PrimeConst* primes, u64 seed, u64 kind, u64 ctr, int noise_on, int ternary,
-                               const PolyMap& map, int n_polys, u64 batch_stride, u64 ctr_step, u64* out, i64* raw,
-                               int log_n, hipStream_t st);
+                               const u64* cdt, int cdt_n, const PolyMap& map, int n_polys, u64 batch_stride, u64 ctr_step,
+                               u64* out, i64* raw, int log_n, hipStream_t st);
 
 // element-wise kernels over [batch][polys][limbs][N]
 enum ElemOp { OP_ADD = 0, OP_SUB = 1 };

@@ -2285,6 +2285,58 @@ extern "C" int hisa_tensor_mask_fixed(hisa_ctx* ctx, const hisa_tensor* in, cons
 }
 
 // ---------------------------------------------------------------------------
+// bias (not part of Algorithm 1; the HISA's addPlain after a linear layer): channel c's elements get bias[c]
+// ---------------------------------------------------------------------------
+// pts: [ciphertexts per image][l][N], NTT form, at the ciphertexts' scale; ciphertext b * per + j takes plaintext j
+static int bias_run(hisa_ctx* ctx, hisa_tensor* t, const u64* pts) {
+    const uint32_t l = t->cts[0]->limbs;
+    const size_t per = t_per(t), lw = (size_t)l * ctx->N;
+    for (size_t i = 0; i < t_ncts(t); i++) {
+        hisa_ct* c = t->cts[i];
+        HIP_TRY(ctx, launch_addsub(ctx->d_primes, c->data, pts + (i % per) * lw, c->data, OP_ADD, (int)l, (int)c->polys, 1, 1, 0,
+                                   0, 0, (int)ctx->log_n, ctx->stream));
+    }
+    return HISA_OK;
+}
+
+static int bias_check(hisa_ctx* ctx, const hisa_tensor* t) {
+    TRY(check_tensor(ctx, t));
+    for (size_t i = 1; i < t_ncts(t); i++)
+        if (t->cts[i]->scale != t->cts[0]->scale) return fail(ctx, HISA_ERR_SCALE_MISMATCH, "ciphertexts of one tensor at different scales");
+    return HISA_OK;
+}
+
+extern "C" int hisa_tensor_add_bias(hisa_ctx* ctx, hisa_tensor* t, const double* bias) {
+    TRY(bias_check(ctx, t));
+    if (!bias) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    const uint32_t ci = t_ci(t), per = (uint32_t)t_per(t), l = t->cts[0]->limbs;
+    const size_t hw = (size_t)t->height * t->width;
+    const double scale = t->cts[0]->scale;
+    std::vector<double> vals((size_t)per * ci * hw, 0.0);
+    for (uint32_t j = 0; j < per; j++)
+        for (uint32_t c = 0; c < std::min(ci, t->channels - j * ci); c++) {
+            const double b = bias[(size_t)j * ci + c];
+            // the encoder rounds to 64-bit integers: the coefficients of a constant plane stay below |b| * scale
+            if (!(fabs(b) * scale < 4.6e18)) return fail(ctx, HISA_ERR_ARG, "bias times scale does not fit 63 bits: rescale first");
+            for (size_t k = 0; k < hw; k++) vals[((size_t)j * ci + c) * hw + k] = b;
+        }
+    Temp pts(ctx, (size_t)per * l * ctx->N * sizeof(u64));
+    if (!pts.ok()) return HISA_ERR_OOM;
+    TRY(encode_sparse_batch(ctx, tensor_slots(t), vals.data(), per, scale, (int)l, pts.u()));
+    return bias_run(ctx, t, pts.u());
+}
+
+extern "C" int hisa_tensor_add_bias_fixed(hisa_ctx* ctx, hisa_tensor* t, const int64_t* bias_coeffs) {
+    TRY(bias_check(ctx, t));
+    if (!bias_coeffs) return fail(ctx, HISA_ERR_ARG, "bad argument");
+    const uint32_t l = t->cts[0]->limbs;
+    Temp pts(ctx, t_per(t) * l * ctx->N * sizeof(u64));
+    if (!pts.ok()) return HISA_ERR_OOM;
+    TRY(coeffs_to_plain_batch(ctx, bias_coeffs, t_per(t), (int)l, pts.u()));
+    return bias_run(ctx, t, pts.u());
+}
+
+// ---------------------------------------------------------------------------
 // layout switches (Sec. "Data Layout Selection": layouts that change the tiling around a layer)
 // ---------------------------------------------------------------------------
 extern "C" int hisa_tensor_layout_rot_steps(hisa_ctx* ctx, const hisa_tensor* in, uint32_t c_inner, uint32_t c_stride,

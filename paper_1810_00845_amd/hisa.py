@@ -34,7 +34,8 @@ class HisaError(RuntimeError):
 
 class Params(C.Structure):
     _fields_ = [("log_n", C.c_uint32), ("num_q", C.c_uint32), ("q_bits", C.c_uint32 * MAX_Q), ("dnum", C.c_uint32),
-                ("special_bits", C.c_uint32), ("noise", C.c_uint32), ("seed", C.c_uint64)]
+                ("special_bits", C.c_uint32), ("noise", C.c_uint32), ("seed", C.c_uint64), ("sigma", C.c_double),
+                ("secret_kind", C.c_uint32), ("hamming_weight", C.c_uint32)]
 
 
 class TensorStruct(C.Structure):
@@ -154,13 +155,17 @@ class Ciphertext(_Handle):
 class Context:
     """One parameter set on one GPU (see hisa_create)."""
 
-    def __init__(self, log_n, q_bits, dnum, special_bits, seed, noise=True, stream=None):
+    def __init__(self, log_n, q_bits, dnum, special_bits, seed, noise=True, stream=None, sigma=0.0, secret_kind=0,
+                 hamming_weight=0):
+        """sigma: parameter of the error distribution (0: 3.2); secret_kind 1: a secret with exactly hamming_weight
+        non-zero coefficients instead of the uniform ternary one."""
         lib = load()
         prm = Params()
         prm.log_n, prm.num_q, prm.dnum = log_n, len(q_bits), dnum
         for i, b in enumerate(q_bits):
             prm.q_bits[i] = b
         prm.special_bits, prm.noise, prm.seed = special_bits, 1 if noise else 0, seed
+        prm.sigma, prm.secret_kind, prm.hamming_weight = float(sigma), int(secret_kind), int(hamming_weight)
         if stream is None:
             import torch
             if not torch.cuda.is_available():
@@ -531,6 +536,21 @@ class Context:
         mc = np.ascontiguousarray(mask_coeffs, dtype=np.int64)
         assert mc.shape == (-(-t.channels // t.c_inner), self.N)
         return self._layer("hisa_tensor_mask_fixed", t, len(t.cts), mc.ctypes.data_as(C.POINTER(C.c_int64)), C.c_double(mask_scale))
+
+    def tensor_add_bias(self, t, bias):
+        """bias[c] onto the elements of channel c, in place (one addPlain per ciphertext)."""
+        b = np.ascontiguousarray(bias, dtype=np.float64)
+        assert b.shape == (t.channels,)
+        st, _arr = t._struct()
+        self._ck(load().hisa_tensor_add_bias(self._vp, C.byref(st), _dp(b)))
+        return t
+
+    def tensor_add_bias_fixed(self, t, bias_coeffs):
+        bc = np.ascontiguousarray(bias_coeffs, dtype=np.int64)
+        assert bc.shape == (-(-t.channels // t.c_inner), self.N)
+        st, _arr = t._struct()
+        self._ck(load().hisa_tensor_add_bias_fixed(self._vp, C.byref(st), bc.ctypes.data_as(C.POINTER(C.c_int64))))
+        return t
 
     def tensor_to_chw(self, t, c_inner, c_stride):
         """Clean HW-tiled tensor -> CHW-tiled (c_inner channels per ciphertext, c_stride slots apart)."""

@@ -14,6 +14,7 @@ linear layer) are multiplied into the next layer's weights here, on the host, be
     ("fire", ws, w1, w3, a, b)               SqueezeNet fire module: 1x1 squeeze, activation, 1x1 and 3x3 (SAME)
                                              expand convolutions whose outputs are concatenated along the channels
     ("gap",)                                 global average pool: one value per channel
+    ("bias", b[C])                           b[c] added to channel c, directly after a conv / fc layer
 """
 import time
 
@@ -352,10 +353,17 @@ def run_encrypted(ctx, layers, x, scale, limbs, make_keys=False, border=0, plans
             w = layer[1] * pending
             pending = 1.0
             nxt = fully_connected(idx, t, w, replicas)
+        elif kind == "bias":
+            # in place; the linear layer in front has taken up every pending factor (an activation or pool between
+            # them would leave the bias at the wrong scale)
+            assert pending == 1.0, "a bias follows a linear layer directly"
+            ctx.tensor_add_bias(t, np.asarray(layer[1], dtype=np.float64))
+            nxt = None
         else:
             raise ValueError(kind)
-        t.free()
-        t = nxt
+        if nxt is not None:
+            t.free()
+            t = nxt
         if layer_times:
             ctx.sync()
         per_layer.append((kind, time.perf_counter() - t0))

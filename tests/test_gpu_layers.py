@@ -837,3 +837,33 @@ def test_new_layer_entry_points_reject_bad_arguments():
         g.conv2d(many, np.zeros((1, 1, 64, 64)), 1, 1, mode=2, chw_schedule=hisa.CHW_ROTATE_SUMS)
     assert e.value.code == -1
     g.close()
+
+
+@pytest.mark.parametrize("chw", [False, True])
+def test_bias_bit_exact_and_accurate(chw):
+    """The per-channel bias after a linear layer: bit for bit with the oracle's addPlain on the oracle's integers
+    (HW- and CHW-tiled, two images), the library's own encoding within 1e-6 of x + bias, nothing outside the element
+    slots; a bias whose fixed-point form does not fit is refused."""
+    from oracle import layers
+    from paper_1810_00845_amd import hisa, synth
+    g, o = make_pair(10, [50, 40, 40], 2, 50, 16)
+    x = synth.image(61, 5, 3, 3)[None]
+    x = np.concatenate([x, 0.5 * x])
+    bias = np.array([0.5, -1.25, 2.0, 0.0, -0.75])
+    if chw:
+        gt, ot = chw_pair(g, o, x, 2.0 ** 40, 3, 2, 16, 902, h_stride=4)
+    else:
+        gt, ot = both_tensors(g, o, x, 2.0 ** 40, 3, h_stride=4)
+    ob, coeffs = layers.add_bias(o, ot, bias)
+    gb = g.tensor_add_bias_fixed(gt, coeffs)
+    same_tensor(g, o, gb, ob)                                   # in place: gt itself now carries the bias
+    assert np.abs(g.tensor_decrypt(gt) - (x + bias[None, :, None, None])).max() <= 1e-6
+    # the library's own encoding, on top: twice the bias now
+    g.tensor_add_bias(gt, bias)
+    assert np.abs(g.tensor_decrypt(gt) - (x + 2 * bias[None, :, None, None])).max() <= 1e-6
+    ob2, _ = layers.add_bias(o, ob, bias)
+    for gc, oc in zip(gt.cts, ob2.cts):                         # other slots: as the oracle has them (zero here)
+        assert np.abs(g.decode(g.decrypt(gc)).real - o.decode(o.decrypt(oc)).real).max() <= 1e-6
+    with pytest.raises(hisa.HisaError):
+        g.tensor_add_bias(gt, bias * 1e8)                       # 2e8 * 2^40 > 2^62
+    g.close()

@@ -26,6 +26,8 @@ def plain_forward(layers, x):
             x = np.concatenate([plain_net.conv2d(s, w1), plain_net.conv2d(s, w3, pad_same=True)], axis=1)
         elif layer[0] == "gap":
             x = x.mean(axis=(2, 3), keepdims=True)
+        elif layer[0] == "bias":
+            x = x + np.asarray(layer[1])[None, :, None, None]
         else:
             x = plain_net.fc(x, layer[1])
     return x
@@ -122,5 +124,28 @@ def test_squeezenet_style_network_with_the_weights_as_worded():
     err = np.abs(got - want).max()
     print("max |output| %.3e, max abs error %.3e, relative to the output %.3f" % (np.abs(want).max(), err, err / np.abs(want).max()),
           flush=True)
+    assert err <= 1e-3
+    ctx.close()
+
+
+@pytest.mark.parametrize("layout", ["hw", "chw_fc", "chw"])
+def test_network_with_biases_matches_plaintext(layout):
+    """LeNet-small with a bias after the convolution and after each fully connected layer (the benchmark
+    configurations name none; the layer is the HISA's addPlain), in the layouts that tile the channels differently."""
+    from paper_1810_00845_amd import hisa, nets
+    params, layers, x = nets.lenet_small()
+    rng = np.random.default_rng(77)
+    with_bias = []
+    for layer in layers:
+        with_bias.append(layer)
+        if layer[0] in ("conv", "fc"):
+            with_bias.append(("bias", rng.uniform(-0.5, 0.5, layer[1].shape[3] if layer[0] == "conv" else layer[1].shape[0])))
+    want = plain_forward(with_bias, x)
+    assert np.abs(want - plain_forward(layers, x)).max() > 0.05      # the biases matter
+    ctx = hisa.Context(params["log_n"], params["q_bits"], params["dnum"], params["special_bits"], seed=11)
+    ctx.keygen()
+    got, _, _ = nets.run_encrypted(ctx, with_bias, x, params["scale"], len(params["q_bits"]), make_keys=True, layout=layout)
+    err = np.abs(got - want).max()
+    print("lenet_small with biases,", layout, "max |value|", np.abs(want).max(), "max abs error", err, flush=True)
     assert err <= 1e-3
     ctx.close()

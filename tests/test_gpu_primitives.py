@@ -19,6 +19,9 @@ PARAMS = {
     "n13_fp": (13, [50, 50, 50, 50], 1, 50, 15),      # dnum = 1
     "n14_fp": (14, [50, 48, 45], 2, 49, 16),
     "n15_fp": (15, [50, 50, 50], 3, 50, 17),          # the benchmark's ring degree
+    # the optional initialisation parameters: another error distribution, a secret of fixed Hamming weight
+    "n12_sigma_fp": (12, [50, 40, 45], 3, 50, 20, dict(sigma=1.5)),
+    "n12_hwt": (12, [50, 40, 45], 2, 55, 21, dict(secret_kind=1, hamming_weight=64, sigma=6.0)),
 }
 
 
@@ -26,10 +29,11 @@ PARAMS = {
 def pair(request):
     from oracle import Oracle
     from paper_1810_00845_amd import hisa
-    log_n, q_bits, dnum, sb, seed = PARAMS[request.param]
+    log_n, q_bits, dnum, sb, seed = PARAMS[request.param][:5]
+    extra = PARAMS[request.param][5] if len(PARAMS[request.param]) > 5 else {}
     print("[case]", request.param, flush=True)
-    g = hisa.Context(log_n, q_bits, dnum, sb, seed)
-    o = Oracle(log_n, q_bits, dnum, sb, seed)
+    g = hisa.Context(log_n, q_bits, dnum, sb, seed, **extra)
+    o = Oracle(log_n, q_bits, dnum, sb, seed, **extra)
     g.keygen(); o.keygen()
     steps = [1, 7, g.slots - 3, 64]
     g.gen_rot_keys(steps); o.gen_rot_keys(steps)
@@ -365,6 +369,23 @@ def test_error_codes(pair):
             g.rescale(low)
         assert code(g.rescale, low) == -6                      # depth exhausted
     assert code(g.mul_no_relin, g.mul_no_relin(gct, gct), gct) == -9
+
+
+def test_bad_initialisation_parameters_are_refused():
+    from paper_1810_00845_amd import hisa
+    for kw in (dict(sigma=0.1), dict(sigma=11.0), dict(secret_kind=2), dict(secret_kind=1, hamming_weight=0),
+               dict(secret_kind=1, hamming_weight=(1 << 10) + 1)):
+        with pytest.raises(hisa.HisaError) as e:
+            hisa.Context(10, [40, 40], 2, 45, 1, **kw)
+        assert e.value.code == -1
+
+
+def test_fixed_weight_secret_has_its_weight():
+    from paper_1810_00845_amd import hisa
+    g = hisa.Context(10, [40, 40], 2, 45, 5, secret_kind=1, hamming_weight=1 << 10)
+    s = g.secret_export()
+    assert np.count_nonzero(s) == 1 << 10 and set(np.unique(s)) == {-1, 1}
+    g.close()
 
 
 def test_largest_ring_degree_on_the_integer_kernels():
