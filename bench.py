@@ -130,6 +130,65 @@ def read_counters(path=COUNTER_FILE):
     return out, src
 
 
+def summarize_counters(root):
+    """The counter summary read_counters reads, from rocprofv3's csv output under `root`: sub-folders trace
+    (--kernel-trace), fetch (--pmc FETCH_SIZE), write (--pmc WRITE_SIZE), sq (--pmc SQ_...) of the headline run with
+    --no-ops, and ops_trace / ops_fetch / ops_write of a run with the per-primitive timings (only the streaming
+    primitives' rows are taken from those).  Per kernel: launches and mean duration from the trace, per-launch means
+    of the counters.  Printed to stdout; the profiling commands themselves are listed in the committed summary."""
+    import collections
+    import csv
+    import glob
+    import re
+
+    def load(sub, pattern):
+        rows = []
+        for f in glob.glob(os.path.join(root, sub, "**", "*" + pattern), recursive=True):
+            with open(f) as fh:
+                rows += list(csv.DictReader(fh))
+        return rows
+
+    def short(name):
+        return re.sub(r", (true|false)>$", ">", name.replace("void ", "").split("(")[0])
+
+    def counters(sub):
+        agg = collections.defaultdict(lambda: collections.defaultdict(list))
+        for r in load(sub, "counter_collection.csv"):
+            agg[short(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+        return agg
+
+    def durations(sub, keep):
+        d = collections.defaultdict(list)
+        for r in load(sub, "kernel_trace.csv"):
+            if keep(short(r["Kernel_Name"])):
+                d[short(r["Kernel_Name"])].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+        return d
+
+    avg = lambda x: sum(x) / len(x) if x else None
+    cell = lambda x, fmt="%.1f": (fmt % x) if x is not None else "-"
+    ops = ("addsub_kernel", "mul_plain_kernel", "mul_no_relin_kernel")
+    dur = durations("trace", lambda n: n.startswith(("ntt_fp_kernel", "inner_product", "copy_kernel")))
+    dur.update(durations("ops_trace", lambda n: n in ops))
+    cf, cw, cs = counters("fetch"), counters("write"), counters("sq")
+    of, ow = counters("ops_fetch"), counters("ops_write")
+    for n in ops:
+        cf[n], cw[n] = of.get(n, {}), ow.get(n, {})
+    print("kernel sources sha: %s" % kernel_source_sha())
+    print()
+    print("| kernel | launches | FETCH_SIZE_KiB | WRITE_SIZE_KiB | SQ_INSTS_VALU | SQ_BUSY_CU_CYCLES | wait_share |")
+    print("|---|---|---|---|---|---|---|")
+    for n in sorted(dur):
+        wa, wc = avg(cs[n].get("SQ_WAIT_INST_ANY", [])), avg(cs[n].get("SQ_WAVE_CYCLES", []))
+        print("| %s | %d | %s | %s | %s | %s | %s |" % (
+            n, len(dur[n]), cell(avg(cf[n].get("FETCH_SIZE", []))), cell(avg(cw[n].get("WRITE_SIZE", []))),
+            cell(avg(cs[n].get("SQ_INSTS_VALU", [])), "%.0f"), cell(avg(cs[n].get("SQ_BUSY_CU_CYCLES", [])), "%.0f"),
+            cell(wa / wc if wa is not None and wc else None, "%.3f")))
+    print()
+    print("kernel durations from the trace runs (us, mean over launches):")
+    for n in sorted(dur):
+        print("  %-36s %4d launches  %10.2f" % (n, len(dur[n]), avg(dur[n]) / 1e3))
+
+
 FP64_PEAK_TFLOPS = 78.6   # 256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz
 
 
@@ -240,8 +299,8 @@ def network_latencies():
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=15)
     ap.add_argument("--log-n", type=int, default=15)
     ap.add_argument("--limbs", type=int, default=16)
     ap.add_argument("--dnum", type=int, default=3)
@@ -250,7 +309,12 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=64, help="ciphertexts for the oracle baseline (0 = skip)")
     ap.add_argument("--no-ops", action="store_true", help="skip the per-primitive timings")
     ap.add_argument("--no-nets", action="store_true", help="skip the encrypted-network latencies")
+    ap.add_argument("--summarize-counters", metavar="DIR", help="no benchmark: print the counter summary of the "
+                    "rocprofv3 csv output under DIR (the text committed under profiles/)")
     args = ap.parse_args()
+    if args.summarize_counters:
+        summarize_counters(args.summarize_counters)
+        return
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
 
