@@ -84,3 +84,54 @@ def test_rotation_sums_at_benchmark_size():
     want = SharedModDown(o, [x]).total([(0, r, 1, None) for r in steps], x.scale)
     assert np.array_equal(g.ct_export(out[i]), o.export(want))
     g.close()
+
+
+def test_other_primitives_at_benchmark_size():
+    """The remaining primitives bench.py times under `ops`, in the same batched calls at the same size (64 ciphertexts,
+    N = 2^15, 16 limbs, dnum 3): raw forward / inverse transforms of 64 x 2 x 16 limb-polynomials in one call, add,
+    mulPlain, mulNoRelin, rescale of the batch, and three rotations of every ciphertext from one decomposition;
+    sampled entries against the oracle, bit for bit."""
+    import torch
+    from oracle import Oracle
+    from paper_1810_00845_amd import hisa, synth
+    log_n, L, bits, B, seed = 15, 16, 50, 64, 1
+    g = hisa.Context(log_n, [bits] * L, 3, bits, seed)
+    o = Oracle(log_n, [bits] * L, 3, bits, seed)
+    N = g.N
+    print("[case] raw transforms", flush=True)
+    q0 = g.primes[0]
+    polys = synth.uniform_residues(10, (B * 2 * L, 1, N), [q0])[:, 0, :]
+    t = torch.from_numpy(polys.view(np.int64)).cuda()
+    g.ntt_raw(t, 0)
+    got = t.cpu().numpy().view(np.uint64)
+    for i in (0, 777, B * 2 * L - 1):
+        assert np.array_equal(got[i], o.ntt(polys[i], 0)), "transform %d differs" % i
+    g.ntt_raw(t, 0, inverse=True)
+    assert np.array_equal(t.cpu().numpy().view(np.uint64), polys)
+    del t
+    coeff = synth.uniform_residues(11, (B, 2, L, N), g.primes[:L])
+    gcts = g.ct_import_batch(coeff, 2.0 ** 50)
+    oct_ = lambda i: o.import_ct(coeff[i % B], 2.0 ** 50)
+    shifted = gcts[1:] + gcts[:1]
+    print("[case] add, mulPlain, mulNoRelin, rescale", flush=True)
+    pt_co = synth.plaintext_coeffs(12, N, 40)
+    gp, op = g.pt_from_coeffs(pt_co, 2.0 ** 50, L), o.pt_from_coeffs(pt_co, 2.0 ** 50, L)
+    gadd, gmp, gmn = g.add_batch(gcts, shifted), g.mul_plain_batch(gcts, gp), g.mul_no_relin_batch(gcts, shifted)
+    gres = g.add_batch(gcts, shifted)
+    g.rescale_batch(gres)
+    for i in (0, 29, 63):
+        a, b = oct_(i), oct_(i + 1)
+        assert np.array_equal(g.ct_export(gadd[i]), o.export(o.add(a, b)))
+        assert np.array_equal(g.ct_export(gmp[i]), o.export(o.mul_plain(a, op)))
+        assert np.array_equal(g.ct_export(gmn[i]), o.export(o.mul_no_relin(a, b)))
+        assert np.array_equal(g.ct_export(gres[i]), o.export(o.rescale(o.add(a, b))))
+    for xs in (gadd, gmp, gmn, gres):
+        for c in xs:
+            c.free()
+    print("[case] three rotations from one decomposition", flush=True)
+    steps = [1, 7, 64]
+    g.gen_rot_keys(steps); o.gen_rot_keys(steps)
+    rows = g.rot_left_hoisted_batch(gcts, steps)
+    for s, i in ((0, 3), (1, 40), (2, 63)):
+        assert np.array_equal(g.ct_export(rows[s][i]), o.export(o.rot_left(oct_(i), steps[s]))), "rotation %d of %d" % (steps[s], i)
+    g.close()
