@@ -450,6 +450,15 @@ def sum_pool2x2(o: Oracle, t: OTensor, merge=0):
                    w_stride=2 * t.w_stride, clean=0)
 
 
+def avg_pool2x2(o: Oracle, t: OTensor, merge=0):
+    """The 2x2 average: the sum pool with the scale of every output ciphertext taken four times as large -- a
+    ciphertext stands for (integer polynomial) / scale, so this is the division by 4, exact and free of any
+    ciphertext operation (no level, no noise)."""
+    from .ckks import Ct
+    s = sum_pool2x2(o, t, merge)
+    return replace(s, cts=[Ct(ct.data, 4.0 * ct.scale) for ct in s.cts])
+
+
 def divide_by_p_and_last(o: Oracle, e_b, e_a, z, l, scale):
     """(ModDown(e_b) + z_0, ModDown(e_a) + z_1) followed by the divScalar by q_{l-1}, as ONE division by q_{l-1} P: z enters
     the accumulators times P first."""

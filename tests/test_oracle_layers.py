@@ -594,3 +594,17 @@ def test_bias_is_added_to_the_elements_of_its_channel_only(chw):
         layers.tensor_encrypt(o, x2, 2.0 ** 40, 2, h_stride=4)
     out2, _ = layers.add_bias(o, t2, bias)
     assert np.abs(layers.tensor_decrypt(o, out2) - (x2 + bias[None, :, None, None])).max() <= 1e-6
+
+
+def test_average_pool_is_the_sum_pool_at_four_times_the_scale():
+    """Against the plain 2x2 mean; the ciphertext data are those of the sum pool (nothing is computed for the 1/4)."""
+    o = Oracle(10, [50, 40], 2, 55, seed=15)
+    x = synth.image(35, 2, 4, 4)[None]
+    t = layers.tensor_encrypt(o, x, 2.0 ** 40, 2)
+    o.gen_rot_keys([1, 4, 5])
+    avg, summed = layers.avg_pool2x2(o, t), layers.sum_pool2x2(o, t)
+    assert np.abs(layers.tensor_decrypt(o, avg) - plain_net.sum_pool2x2(x) / 4.0).max() <= 1e-6
+    assert np.abs(layers.tensor_decrypt(o, avg) - x.reshape(1, 2, 2, 2, 2, 2).mean(axis=(3, 5))).max() <= 1e-6
+    for a, b in zip(avg.cts, summed.cts):
+        assert np.array_equal(a.data, b.data) and a.scale == 4.0 * b.scale
+    assert (avg.height, avg.width, avg.h_stride, avg.w_stride, avg.clean) == (2, 2, 8, 2, 0)
