@@ -530,6 +530,10 @@ int hisa_matmul_plan_free(hisa_ctx* ctx, hisa_matmul_plan* plan);
  * weights): x + rot(w_stride) + rot(h_stride) + rot(h_stride + w_stride);
  * strides double, no level is used. */
 int hisa_sum_pool2x2(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out);
+/* 2x2 average pool, stride 2: hisa_sum_pool2x2 whose outputs carry four times the scale.  A ciphertext stands for
+ * (integer polynomial) / scale, so the larger scale is the division by 4: exact, no ciphertext operation, no level.
+ * Layers after it see ciphertexts at that scale (a rescale divides it by the last modulus as usual). */
+int hisa_avg_pool2x2(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out);
 /* Degree-2 activation a*x^2 + b*x computed as x^2 + (b/a)*x: one mul with
  * relinearisation, one mulScalar by b/a at scale = ciphertext scale, one add,
  * one divScalar.  The factor a belongs in the next layer's weights. */

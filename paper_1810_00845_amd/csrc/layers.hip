@@ -2639,6 +2639,12 @@ extern "C" int hisa_matmul_fixed(hisa_ctx* ctx, const hisa_tensor* in, const int
 // ---------------------------------------------------------------------------
 // pooling, activation
 // ---------------------------------------------------------------------------
+extern "C" int hisa_avg_pool2x2(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out) {
+    TRY(hisa_sum_pool2x2(ctx, in, out));
+    for (size_t i = 0; i < t_ncts(out); i++) out->cts[i]->scale *= 4.0;   // value = polynomial / scale: the mean
+    return HISA_OK;
+}
+
 extern "C" int hisa_sum_pool2x2(hisa_ctx* ctx, const hisa_tensor* in, hisa_tensor* out) {
     TRY(check_tensor(ctx, in));
     if (!out || !out->cts || in->height < 2 || in->width < 2) return fail(ctx, HISA_ERR_ARG, "bad argument");

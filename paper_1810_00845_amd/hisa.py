@@ -620,6 +620,10 @@ class Context:
     def sum_pool2x2(self, t):
         return self._layer("hisa_sum_pool2x2", t, len(t.cts))
 
+    def avg_pool2x2(self, t):
+        """The 2x2 mean: the sum pool at four times the scale (no ciphertext operation for the 1/4)."""
+        return self._layer("hisa_avg_pool2x2", t, len(t.cts))
+
     def poly2_act(self, t, a, b):
         return self._layer("hisa_poly2_act", t, len(t.cts), C.c_double(a), C.c_double(b))
 

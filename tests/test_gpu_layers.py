@@ -867,3 +867,23 @@ def test_bias_bit_exact_and_accurate(chw):
     with pytest.raises(hisa.HisaError):
         g.tensor_add_bias(gt, bias * 1e8)                       # 2e8 * 2^40 > 2^62
     g.close()
+
+
+def test_average_pool_bit_exact():
+    """hisa_avg_pool2x2 = the sum pool's ciphertexts at four times the scale, on both sides; decrypts to the 2x2 mean;
+    a convolution after it works at that scale."""
+    from oracle import layers
+    from paper_1810_00845_amd import synth
+    g, o = make_pair(10, [50, 40, 40], 2, 50, 17)
+    x = synth.image(62, 2, 4, 4)[None]
+    gt, ot = both_tensors(g, o, x, 2.0 ** 40, 3)
+    g.gen_rot_keys([1, 4, 5]); o.gen_rot_keys([1, 4, 5])
+    ga, oa = g.avg_pool2x2(gt), layers.avg_pool2x2(o, ot)
+    same_tensor(g, o, ga, oa)
+    assert ga.cts[0].scale == 4.0 * gt.cts[0].scale
+    mean = x.reshape(1, 2, 2, 2, 2, 2).mean(axis=(3, 5))
+    assert np.abs(g.tensor_decrypt(ga) - mean).max() <= 1e-6
+    w = synth.conv_weights(63, 1, 1, 2, 3)
+    gc = g.conv2d(ga, w, 1, 1)
+    assert np.abs(g.tensor_decrypt(gc) - plain_net.conv2d(mean, w)).max() <= 1e-3
+    g.close()
