@@ -267,13 +267,17 @@ def network_latencies():
             ctx.keygen()
             plans = {}
             kw = dict(border=border, plans=plans, layout=layout)
+            t_setup = time.perf_counter()
             nets.run_encrypted(ctx, layers, x, params["scale"], limbs, make_keys=True, **kw)
+            ctx.sync()
+            t_setup = time.perf_counter() - t_setup      # rotation keys and plans (weights converted and encoded) + one inference
             # latency: the host queues the whole network, one wait at the end; the per-layer times come from one more
             # inference that waits after every layer
             client = {}
             runs = sorted((nets.run_encrypted(ctx, layers, x, params["scale"], limbs, layer_times=False, client_times=client, **kw)
                            for _ in range(3)), key=lambda r: r[1])
             per_layer = nets.run_encrypted(ctx, layers, x, params["scale"], limbs, **kw)[2]
+            client["setup_s"] = t_setup
             res[layout] = (runs[1][1], per_layer, None, dict(client))
             if layout == selected:     # one more inference with HIP events around every kernel: where the time goes
                 ctx.profile_enable(True)
@@ -291,7 +295,10 @@ def network_latencies():
                      "layers_ms": [[k, round(s * 1e3, 2)] for k, s in res[best][1]],
                      "kernels_launches_ms": res[best][2],
                      # the client's side, outside the latency: encode + encrypt of the image, decrypt + decode of the result
-                     "client_ms": {k.replace("_s", ""): round(v * 1e3, 3) for k, v in res[best][3].items()},
+                     "client_ms": {k.replace("_s", ""): round(v * 1e3, 3) for k, v in res[best][3].items() if k != "setup_s"},
+                     # once per network and key set: rotation keys for the amounts the circuit uses, weights converted
+                     # and encoded into plans, and the first inference
+                     "setup_ms": round(res[best][3]["setup_s"] * 1e3, 1),
                      "paper_context": paper, "data": "seeded random weights and image"}
     return out
 
