@@ -461,18 +461,25 @@ def measure_costs_at(ctx, limbs, batch=64, reps=5):
     costs = {}
     costs["rot_left"], costs["key_switch_calls"] = split(lambda n: free(ctx.rot_left_batch(cts[:n], 1)))
     rot = costs["rot_left"]
-    # three rotations per ciphertext from one decomposition; never more than nine tenths of a rotation saved
-    hoisted = split(lambda n: free(ctx.rot_left_hoisted_batch(cts[:n], [1, 2, 3])))[0]
-    costs["rot_shared"] = min(0.0, max((hoisted - 3 * rot) / 2, -0.9 * rot))
+    # Rotations that share work are priced on groups of nine, the size of a 3x3 convolution's taps (short groups
+    # understate the sharing: their fixed costs weigh as much as the rotations).  "rot_shared": what each further
+    # rotation of a ciphertext saves when it reuses the decomposition -- nine rotations of every ciphertext in one
+    # hoisted call cost 9 rot + 8 rot_shared; never more than nine tenths of a rotation saved.
+    many = list(range(1, 10))
+    ctx.gen_rot_keys(many)
+
+    def hoisted(n):
+        for row in ctx.rot_left_hoisted_batch(cts[:n], many):
+            free(row)
+    costs["rot_shared"] = min(0.0, max((split(hoisted)[0] - 9 * rot) / 8, -0.9 * rot))
     costs["rot_summed"] = 0.0
     if ctx.log_n >= 12 and max(ctx.primes) < 2 ** 50 and ctx.dnum <= 8:
-        # three terms per output, each a different ciphertext (terms that rotate the same one would share the
-        # decomposition as well, which "rot_shared" already prices)
+        # "rot_summed": what a rotation saves inside a sum that takes its division by P once -- a sum of nine
+        # rotations of one ciphertext costs 9 rot + 8 rot_shared + 9 rot_summed; its inner product stays to be paid
         def summed(n):
-            terms = [cts[:n], (cts[1:] + cts[:1])[:n], (cts[2:] + cts[:2])[:n]]
-            free(ctx.rot_left_sum_batch(terms, [1, 2, 3]))
-        # a rotation that shares both still has its inner product to pay
-        costs["rot_summed"] = min(0.0, max((split(summed)[0] - 3 * rot) / 2, -0.9 * (rot + costs["rot_shared"])))
+            free(ctx.rot_left_sum_batch([cts[:n]] * 9, many))
+        saved = (split(summed)[0] - 9 * rot - 8 * costs["rot_shared"]) / 9
+        costs["rot_summed"] = min(0.0, max(saved, -0.9 * (rot + costs["rot_shared"])))
     per_ct = lambda fn: timed(fn) / batch
     costs["add"] = per_ct(lambda: free(ctx.add_batch(cts, cts)))
     costs["mul"] = per_ct(lambda: free(ctx.mul_no_relin_batch(cts, cts)))
