@@ -48,3 +48,22 @@ def test_binding_mirrors_the_header():
         if n in skip:
             continue
         assert hasattr(hisa.Context, n[len("hisa_"):]), n
+
+
+def test_binding_structs_have_the_layout_of_the_header(tmp_path):
+    """The ctypes structures of the binding against the C compiler's view of include/hisa.h: size of every struct that
+    crosses the boundary by pointer, and the offset of the last field of each."""
+    import subprocess
+    from paper_1810_00845_amd import hisa
+    pairs = [("hisa_params", hisa.Params, "hamming_weight"), ("hisa_op_counts", hisa.OpCounts, "limb_sq_sum"),
+             ("hisa_tensor", hisa.TensorStruct, "cts"), ("hisa_conv_geom", hisa.ConvGeom, "chw_schedule"),
+             ("hisa_calibration", hisa.Calibration, "reserved"), ("hisa_mac_extents", hisa.MacExtents, "w_extent")]
+    src = tmp_path / "layout.c"
+    body = "\n".join('    printf("%s %%zu %%zu\\n", sizeof(%s), offsetof(%s, %s));' % (c, c, c, last) for c, _, last in pairs)
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "hisa.h"\nint main(void) {\n%s\n    return 0;\n}\n' % body)
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    out = subprocess.check_output([str(exe)]).decode().split("\n")
+    seen = {line.split()[0]: (int(line.split()[1]), int(line.split()[2])) for line in out if line.strip()}
+    for cname, struct, last in pairs:
+        assert seen[cname] == (ctypes.sizeof(struct), getattr(struct, last).offset), (cname, seen[cname])
